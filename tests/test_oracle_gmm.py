@@ -1,0 +1,113 @@
+"""Pins for the MoNet / GMMConv oracle (App. A.2 "GMMConv")."""
+import numpy as np
+import pytest
+import scipy.sparse as sp
+import torch
+
+from oracle import gmm as om
+from helpers import finite_difference, random_graph
+
+
+def make_case(rng, n, m, fin, fout, K, duplicates=False):
+    indptr, indices = random_graph(rng, n, m, self_loops=True, duplicates=duplicates)
+    X = rng.standard_normal((n, fin))
+    W = rng.standard_normal((fin, K * fout)) * 0.5
+    deg = np.diff(indptr)
+    c = 1.0 / np.sqrt(np.maximum(deg, 1))
+    mu = rng.standard_normal((K, 2)) * 0.3
+    inv_sigma = 0.5 + rng.random((K, 2))
+    return indptr, indices, X, W, c, mu, inv_sigma
+
+
+def brute_force(indptr, indices, X, W, c, mu, inv_sigma):
+    n = len(indptr) - 1
+    K = mu.shape[0]
+    fout = W.shape[1] // K
+    Hk = (X @ W).reshape(n, K, fout)
+    out = np.zeros((n, fout))
+    for v in range(n):
+        for e in range(indptr[v], indptr[v + 1]):
+            u = indices[e]
+            m = np.array([c[u], c[v]])
+            for k in range(K):
+                Sinv = np.diag(inv_sigma[k] ** 2)                 # diagonal covariance inverse
+                w = np.exp(-0.5 * (m - mu[k]) @ Sinv @ (m - mu[k]))
+                out[v] += w * Hk[u, k] / K
+    return out
+
+
+def test_forward_matches_loop_brute_force():
+    rng = np.random.default_rng(1)
+    args = make_case(rng, 15, 50, 4, 3, 3, duplicates=True)
+    np.testing.assert_allclose(om.gmm_forward(*args)["out"], brute_force(*args), rtol=1e-12, atol=1e-13)
+
+
+def test_flat_kernels_reduce_to_sparse_matmul():
+    # inv_sigma = 0 -> every gaussian weight is 1 -> out = (1/K) sum_k A Hk[:, k]
+    rng = np.random.default_rng(2)
+    indptr, indices, X, W, c, mu, inv_sigma = make_case(rng, 40, 220, 5, 4, 3)
+    out = om.gmm_forward(indptr, indices, X, W, c, mu, 0 * inv_sigma)["out"]
+    A = sp.csr_matrix((np.ones(len(indices)), indices, indptr), shape=(40, 40))
+    Hk = (X @ W).reshape(40, 3, 4)
+    ref = sum(A @ Hk[:, k, :] for k in range(3)) / 3
+    np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-13)
+
+
+def test_weight_is_one_at_the_kernel_mean():
+    # regular graph: every degree equal -> all pseudo-coordinates equal; K = 1, mu = m
+    n = 12
+    edges_src = np.array([[v, (v + 1) % n, (v + 5) % n] for v in range(n)])
+    indptr = (np.arange(n + 1) * 3).astype(np.int32)
+    indices = np.sort(edges_src, axis=1).reshape(-1).astype(np.int32)
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((n, 4))
+    W = rng.standard_normal((4, 5))
+    c = np.full(n, 1 / np.sqrt(3))
+    mu = np.array([[c[0], c[0]]])
+    fwd = om.gmm_forward(indptr, indices, X, W, c, mu, np.array([[2.0, 3.0]]))
+    np.testing.assert_allclose(fwd["w"], 1.0, rtol=1e-15)
+    A = sp.csr_matrix((np.ones(len(indices)), indices, indptr), shape=(n, n))
+    np.testing.assert_allclose(fwd["out"], A @ (X @ W), rtol=1e-12, atol=1e-13)
+
+
+def _loss(args, gout):
+    return float((om.gmm_forward(*args)["out"] * gout).sum())
+
+
+def test_backward_matches_finite_differences():
+    rng = np.random.default_rng(4)
+    indptr, indices, X, W, c, mu, inv_sigma = make_case(rng, 12, 40, 3, 4, 3)
+    gout = rng.standard_normal((12, 4))
+    bwd = om.gmm_backward(indptr, indices, X, W, c, mu, inv_sigma, gout)
+    for name, theta, fun in [
+        ("gx", X, lambda t: _loss((indptr, indices, t, W, c, mu, inv_sigma), gout)),
+        ("gw_fc", W, lambda t: _loss((indptr, indices, X, t, c, mu, inv_sigma), gout)),
+        ("gmu", mu, lambda t: _loss((indptr, indices, X, W, c, t, inv_sigma), gout)),
+        ("ginv_sigma", inv_sigma, lambda t: _loss((indptr, indices, X, W, c, mu, t), gout)),
+    ]:
+        idx, g = finite_difference(fun, theta)
+        np.testing.assert_allclose(bwd[name].reshape(-1)[idx], g, rtol=2e-6, atol=2e-7, err_msg=name)
+
+
+def test_backward_matches_torch_autograd():
+    rng = np.random.default_rng(5)
+    n, K, fout = 18, 2, 3
+    indptr, indices, X, W, c, mu, inv_sigma = make_case(rng, n, 70, 4, fout, K)
+    gout = rng.standard_normal((n, fout))
+    tX, tW, tmu, tis = (torch.tensor(a, dtype=torch.float64, requires_grad=True)
+                        for a in (X, W, mu, inv_sigma))
+    Hk = (tX @ tW).reshape(n, K, fout)
+    src = torch.tensor(indices.astype(np.int64))
+    dst = torch.tensor(np.repeat(np.arange(n), np.diff(indptr)))
+    tc = torch.tensor(c)
+    m = torch.stack([tc[src], tc[dst]], dim=1)
+    q = (m[:, None, :] - tmu[None]) * tis[None]
+    w = torch.exp(-0.5 * (q * q).sum(-1))
+    msg = (w[:, :, None] * Hk[src]).sum(1) / K
+    out = torch.zeros(n, fout, dtype=torch.float64).index_add(0, dst, msg)
+    (out * torch.tensor(gout)).sum().backward()
+    bwd = om.gmm_backward(indptr, indices, X, W, c, mu, inv_sigma, gout)
+    np.testing.assert_allclose(bwd["gx"], tX.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(bwd["gw_fc"], tW.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(bwd["gmu"], tmu.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(bwd["ginv_sigma"], tis.grad.numpy(), rtol=1e-10, atol=1e-12)

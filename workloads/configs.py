@@ -1,0 +1,139 @@
+"""The named workloads: seeded graphs plus tensors shaped like the evaluation's.
+
+Inputs only (random structure, random values); no layer arithmetic lives here.
+
+  gat_c1   Cora-scale GAT forward, 64 -> 1 head x 16           (Sec. 7.2)
+  gat_c2   Pubmed-scale GAT, 500 -> 8 heads x 8, fwd+bwd       (Sec. 7.2)
+  ec_c3    EdgeConv, 32 clouds x 1024 points, k=20, 64 -> 64   (Sec. 7.2)
+  gat_c4   Reddit-scale GAT, 602 -> 4 heads x 64, fwd+bwd      (Sec. 7.2/7.3)
+  gmm_c5   MoNet, K=3 kernels, r=2 pseudo-coords, 64 -> 64     (Sec. 7.2)
+
+Smaller "mid" variants keep a workload's feature widths (hence the same kernel
+instantiation and launch shape) on a graph the CPU oracle finishes in seconds.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import graphs
+
+SEED0 = 0x9E3779B97F4A7C15
+
+__all__ = ["make", "NAMES", "glorot", "SEED0"]
+
+
+def glorot(rng, fan_in, fan_out, shape):
+    lim = np.sqrt(6.0 / (fan_in + fan_out))
+    return rng.uniform(-lim, lim, size=shape).astype(np.float32)
+
+
+def _normal(rng, shape):
+    return rng.standard_normal(size=shape, dtype=np.float32)
+
+
+def _gat(name, n, graph, fin, heads, f, seed, x_kind="normal"):
+    indptr, indices = graph
+    rng = graphs.rng_for(seed ^ 0xA5A5)
+    if x_kind == "normal":
+        x = _normal(rng, (n, fin))
+    else:  # sparse binary bag-of-words features, 5 % ones
+        x = (rng.random((n, fin), dtype=np.float32) < 0.05).astype(np.float32)
+    return dict(
+        name=name, kind="gat", n=n, nnz=int(indices.shape[0]), fin=fin, heads=heads, f=f,
+        slope=0.2, indptr=indptr, indices=indices, x=x,
+        w=glorot(rng, fin, heads * f, (fin, heads * f)),
+        a_l=glorot(rng, f, 1, (heads, f)),
+        a_r=glorot(rng, f, 1, (heads, f)),
+        gout=_normal(rng, (n, heads * f)),
+    )
+
+
+def _edgeconv(name, batch, points, k, fin, fout, seed):
+    indptr, indices, coords = graphs.knn_point_clouds(batch, points, k, seed)
+    n = batch * points
+    rng = graphs.rng_for(seed ^ 0xA5A5)
+    return dict(
+        name=name, kind="edgeconv", n=n, nnz=int(indices.shape[0]), fin=fin, fout=fout,
+        indptr=indptr, indices=indices, coords=coords,
+        x=_normal(rng, (n, fin)),
+        theta=glorot(rng, fin, fout, (fin, fout)),
+        phi=glorot(rng, fin, fout, (fin, fout)),
+        gout=_normal(rng, (n, fout)),
+    )
+
+
+def _gmm(name, n, graph, fin, fout, k, seed):
+    indptr, indices = graph
+    rng = graphs.rng_for(seed ^ 0xA5A5)
+    deg = np.diff(indptr).astype(np.float64)
+    c = (1.0 / np.sqrt(np.maximum(deg, 1.0))).astype(np.float32)
+    return dict(
+        name=name, kind="gmm", n=n, nnz=int(indices.shape[0]), fin=fin, fout=fout, k=k,
+        indptr=indptr, indices=indices,
+        x=_normal(rng, (n, fin)),
+        w_fc=glorot(rng, fin, k * fout, (fin, k * fout)),
+        c=c,
+        mu=(0.1 * rng.standard_normal(size=(k, 2))).astype(np.float32),
+        inv_sigma=np.ones((k, 2), dtype=np.float32),
+        gout=_normal(rng, (n, fout)),
+    )
+
+
+def _make_gat_c1(seed):
+    n = 2000
+    return _gat("gat_c1", n, graphs.erdos_renyi(n, 10_000, seed), 64, 1, 16, seed)
+
+
+def _make_gat_c2(seed):
+    n = 20_000
+    return _gat("gat_c2", n, graphs.chung_lu(n, 100_000, 2.1, seed), 500, 8, 8, seed,
+                x_kind="binary")
+
+
+def _make_ec_c3(seed):
+    return _edgeconv("ec_c3", 32, 1024, 20, 64, 64, seed)
+
+
+def _make_gat_c4(seed):
+    n = 232_965
+    return _gat("gat_c4", n, graphs.chung_lu(n, 114_000_000, 2.1, seed), 602, 4, 64, seed)
+
+
+def _make_gmm_c5(seed):
+    n = 100_000
+    return _gmm("gmm_c5", n, graphs.chung_lu(n, 2_000_000, 2.1, seed), 64, 64, 3, seed)
+
+
+# mid-size variants: same widths as the big workload, oracle-sized graphs
+def _make_gat_c4_mid(seed):
+    n = 6000
+    return _gat("gat_c4_mid", n, graphs.chung_lu(n, 300_000, 2.1, seed), 602, 4, 64, seed)
+
+
+def _make_ec_c3_mid(seed):
+    return _edgeconv("ec_c3_mid", 3, 500, 20, 64, 64, seed)
+
+
+def _make_gmm_c5_mid(seed):
+    n = 8000
+    return _gmm("gmm_c5_mid", n, graphs.chung_lu(n, 160_000, 2.1, seed), 64, 64, 3, seed)
+
+
+_MAKERS = {
+    "gat_c1": (1, _make_gat_c1),
+    "gat_c2": (2, _make_gat_c2),
+    "ec_c3": (3, _make_ec_c3),
+    "gat_c4": (4, _make_gat_c4),
+    "gmm_c5": (5, _make_gmm_c5),
+    "gat_c4_mid": (104, _make_gat_c4_mid),
+    "ec_c3_mid": (103, _make_ec_c3_mid),
+    "gmm_c5_mid": (105, _make_gmm_c5_mid),
+}
+NAMES = tuple(_MAKERS)
+
+
+def make(name: str, seed: int | None = None) -> dict:
+    """Build the named workload.  Default seed = SEED0 xor the workload's id."""
+    cid, fn = _MAKERS[name]
+    s = (SEED0 ^ cid) if seed is None else int(seed)
+    return fn(s)
