@@ -1,0 +1,210 @@
+/*
+ * gnn_fused.h — C ABI of the reorganized, fused GNN layers for MI355X (gfx950).
+ *
+ * One GNN layer = an expensive per-vertex projection done BEFORE propagation
+ * (Sec. 4, propagation-postponed reorganization), then ONE fused pass per
+ * destination vertex that does Scatter, the lightweight ApplyEdge, the
+ * ReduceScatter (edge-softmax) and the Aggregate under a single vertex-balanced
+ * thread mapping (Sec. 5), and a backward pass that recomputes every per-edge
+ * value from O(|V|) saved state (Sec. 6).  No function here reads or writes a
+ * tensor with one row per edge.
+ *
+ * Conventions
+ *   - A graph is the edge set {(u, e, v)} of App. A.1 stored as CSR by
+ *     DESTINATION: indptr[n+1], indices[nnz]; row v lists the sources u of the
+ *     in-edges of v; the edge id e is the CSR position.  Duplicate edges are
+ *     distinct edges.  0 <= nnz < 2^31.
+ *   - Every pointer is a DEVICE pointer to contiguous row-major memory, float
+ *     (fp32) or int32_t, unless a comment says "host".  The caller owns every
+ *     buffer it passes.  Rows of feature matrices must start 16-byte aligned
+ *     where noted (feature widths that are multiples of 4 floats).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued on it; layer calls never synchronise with the host and
+ *     never allocate.  Scratch comes from a caller-provided workspace whose size
+ *     the matching *_workspace_bytes() call returns (0 is possible; then ws may
+ *     be NULL).
+ *   - Every function returns a gnn_status_t.  On failure nothing useful has been
+ *     written and gnn_last_error() returns a thread-local, library-owned string.
+ *   - Outputs are bit-reproducible from run to run: no floating-point atomics.
+ */
+#ifndef GNN_FUSED_H
+#define GNN_FUSED_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum gnn_status {
+  GNN_OK = 0,
+  GNN_ERR_INVALID_ARG = 1, /* null pointer, negative size, misaligned buffer            */
+  GNN_ERR_BAD_GRAPH = 2,   /* indptr not monotone / wrong ends, source id outside [0,n) */
+  GNN_ERR_WORKSPACE = 3,   /* workspace smaller than *_workspace_bytes()                */
+  GNN_ERR_UNSUPPORTED = 4, /* shape outside what the kernels are built for              */
+  GNN_ERR_HIP = 5          /* a HIP runtime call failed; text in gnn_last_error()       */
+} gnn_status_t;
+
+/* Text of the last error raised on the calling thread ("" if none).  Library-owned. */
+const char* gnn_last_error(void);
+
+/* ------------------------------------------------------------------------- *
+ * Graph plan (once per graph; its cost is preprocessing, cf. Sec. 8.1 "GNN
+ * runtime optimization").  The vertex-balanced mapping of Sec. 5 loops over the
+ * in-edge set of a vertex; the source-side gradients loop over the out-edge set,
+ * which needs the transpose.  The plan holds integer tables only:
+ *
+ *   CSC transpose   edges ordered by (source ascending, CSR position ascending):
+ *                   indptr_t[n+1], indices_t[nnz] = destination of each out-edge,
+ *                   eid_t[nnz] = CSR position of that edge.
+ *   degree order    per side (0 = in-degree / CSR rows, 1 = out-degree / CSC rows)
+ *                   the vertices sorted by degree descending, ties by ascending id.
+ *                   Kernels hand out rows in this order, heaviest first.
+ *   degree bucket   clz32(degree): number of leading zero bits of the degree as a
+ *                   32-bit integer, 32 for degree 0 (GNN_NUM_BUCKETS = 33 values);
+ *                   bucket ids ascend along the degree order;
+ *                   bucket_offsets[b] = first position of bucket b in the order,
+ *                   bucket_offsets[33] = n.
+ *
+ * All of it is a pure function of (indptr, indices) and is bit-exact.
+ * ------------------------------------------------------------------------- */
+#define GNN_NUM_BUCKETS 33
+
+typedef struct gnn_graph gnn_graph_t;
+
+/* Validates the CSR arrays on the device, builds the plan and returns a handle.
+ * indptr/indices are BORROWED: they must stay valid and unchanged until
+ * gnn_graph_destroy.  This call allocates device memory for the plan tables
+ * (about 8*nnz + 32*n bytes kept, plus sort scratch released before returning)
+ * and synchronises `stream` once to read the validation result.
+ * Errors: INVALID_ARG (n < 0, nnz < 0, null pointers with n > 0), UNSUPPORTED
+ * (nnz >= 2^31), BAD_GRAPH, HIP. */
+gnn_status_t gnn_graph_create(int32_t n, int64_t nnz, const int32_t* indptr, const int32_t* indices,
+                              void* stream, gnn_graph_t** graph);
+
+/* Frees the plan tables (not the borrowed CSR arrays).  NULL is accepted. */
+gnn_status_t gnn_graph_destroy(gnn_graph_t* graph);
+
+/* Introspection for bit-exact tests: copies plan tables into caller buffers
+ * (device pointers; any of them may be NULL to skip it). */
+gnn_status_t gnn_graph_get_csc(const gnn_graph_t* graph, int32_t* indptr_t /*n+1*/,
+                               int32_t* indices_t /*nnz*/, int32_t* eid_t /*nnz*/, void* stream);
+gnn_status_t gnn_graph_get_buckets(const gnn_graph_t* graph, int side /*0 = dst rows, 1 = src rows*/,
+                                   int32_t* bucket_of_vertex /*n*/, int32_t* order /*n*/,
+                                   int32_t* bucket_offsets /*GNN_NUM_BUCKETS+1*/, void* stream);
+
+/* ------------------------------------------------------------------------- *
+ * Projection: the ExpensiveApply on vertices, y = x w  (Sec. 3, Sec. 4; App. A.2
+ * "H~ = H W").  x [n, fin], w [fin, fout], y [n, fout]; any positive sizes.
+ * fp32 MFMA (v_mfma_f32_32x32x2_f32), fp32 accumulate.  No workspace.
+ * ------------------------------------------------------------------------- */
+gnn_status_t gnn_linear_fwd(int64_t n, int fin, int fout, const float* x, const float* w, float* y,
+                            void* stream);
+
+/* ------------------------------------------------------------------------- *
+ * GAT layer (App. A.2 "GAT"; score of Sec. 4 Eq. 1 in its reorganized form
+ * a_l.Wh_u + a_r.Wh_v; fused M0..H^(l+1) operator of App. A.2 / Sec. 5; saved
+ * max and denominator of Sec. 6).
+ *
+ *   z   = x w                         [n, heads*f]   head-major columns
+ *   el  = <z[u,h,:], a_l[h,:]>        [n, heads]     source half
+ *   er  = <z[v,h,:], a_r[h,:]>        [n, heads]     destination half
+ *   s_e = LeakyReLU_slope(el[u,h] + er[v,h])         e = (u -> v)
+ *   m   = max over in-edges of s_e    [n, heads]     (0 for an empty row)
+ *   d   = sum exp(s_e - m)            [n, heads]     (1 for an empty row)
+ *   out = sum (exp(s_e - m) / d) z[u] [n, heads*f]   (0 for an empty row)
+ *
+ * Requirements: f % 4 == 0, heads*f <= 1024, heads <= 64; x, w any width.
+ * Forward writes z, el, er, m, d, out (all of them are the saved state the
+ * backward call needs; none has a per-edge dimension).
+ * ------------------------------------------------------------------------- */
+size_t gnn_gat_workspace_bytes(const gnn_graph_t* graph, int fin, int heads, int f);
+
+gnn_status_t gnn_gat_fwd(const gnn_graph_t* graph, int fin, int heads, int f, float slope,
+                         const float* x /*[n,fin]*/, const float* w /*[fin,heads*f]*/,
+                         const float* a_l /*[heads,f]*/, const float* a_r /*[heads,f]*/,
+                         float* z /*[n,heads*f]*/, float* el, float* er, float* m, float* d /*[n,heads]*/,
+                         float* out /*[n,heads*f]*/, void* ws, size_t ws_bytes, void* stream);
+
+/* Gradients of L = <gout, out>.  Per-edge scores and softmax values are
+ * recomputed from el, er, m, d; LeakyReLU'(0) = slope.  gx may be NULL (skip
+ * the input gradient).  Writes gx [n,fin], gw [fin,heads*f], ga_l, ga_r [heads,f]. */
+gnn_status_t gnn_gat_bwd(const gnn_graph_t* graph, int fin, int heads, int f, float slope,
+                         const float* x, const float* w, const float* a_l, const float* a_r,
+                         const float* z, const float* el, const float* er, const float* m,
+                         const float* d, const float* out, const float* gout /*[n,heads*f]*/,
+                         float* gx /*nullable*/, float* gw, float* ga_l, float* ga_r,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------- *
+ * EdgeConv layer (App. A.2 "EdgeConv"), in the reorganized form of Sec. 4:
+ * Theta(h_u - h_v) + Phi h_v = (x Theta)[u] + (x (Phi - Theta))[v].
+ *
+ *   pq  = x [Theta | Phi - Theta]                [n, 2*fout]  (P | Q), saved
+ *   out = max over in-edges of P[u] + Q[v]       [n, fout]    (0 for an empty row)
+ *   argmax[v, j] = CSR position of the winning in-edge, the earliest one on an
+ *                  exact tie, -1 for an empty row             [n, fout] int32
+ *
+ * Requirements: fout % 4 == 0, fout <= 1024.  theta, phi are [fin, fout].
+ * Only argmax (O(|V|)) is needed by the backward pass (Sec. 7.2 "EdgeConv").
+ * ------------------------------------------------------------------------- */
+size_t gnn_edgeconv_workspace_bytes(const gnn_graph_t* graph, int fin, int fout);
+
+gnn_status_t gnn_edgeconv_fwd(const gnn_graph_t* graph, int fin, int fout, const float* x,
+                              const float* theta, const float* phi, float* pq /*[n,2*fout]*/,
+                              float* out /*[n,fout]*/, int32_t* argmax /*[n,fout]*/,
+                              void* ws, size_t ws_bytes, void* stream);
+
+/* Gradients of L = <gout, out>: gx [n,fin] (nullable), gtheta, gphi [fin,fout]. */
+gnn_status_t gnn_edgeconv_bwd(const gnn_graph_t* graph, int fin, int fout, const float* x,
+                              const float* theta, const float* phi, const int32_t* argmax,
+                              const float* gout /*[n,fout]*/, float* gx /*nullable*/, float* gtheta,
+                              float* gphi, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------- *
+ * MoNet / GMMConv layer (App. A.2 "GMMConv").
+ *
+ *   hk  = x w_fc                                   [n, k*fout] viewed [n, k, fout], saved
+ *   m_e = (c[u], c[v])                             2-D pseudo-coordinates of e = (u -> v)
+ *   w_j(m) = exp(-1/2 sum_d ((m_d - mu[j,d]) * inv_sigma[j,d])^2)        j < k
+ *   out[v] = (1/k) sum over in-edges sum_j w_j(m_e) hk[u, j, :]          [n, fout]
+ *
+ * The covariance is diagonal, Sigma_j^-1 = diag(inv_sigma[j]^2); c is a
+ * per-vertex scalar supplied by the caller (no gradient).  The Gaussian
+ * weights are never stored: backward recomputes them (Sec. 7.3).
+ * Requirements: fout % 4 == 0, fout <= 256, 1 <= k <= 8.
+ * ------------------------------------------------------------------------- */
+size_t gnn_gmm_workspace_bytes(const gnn_graph_t* graph, int fin, int fout, int k);
+
+gnn_status_t gnn_gmm_fwd(const gnn_graph_t* graph, int fin, int fout, int k, const float* x,
+                         const float* w_fc /*[fin,k*fout]*/, const float* c /*[n]*/,
+                         const float* mu /*[k,2]*/, const float* inv_sigma /*[k,2]*/,
+                         float* hk /*[n,k*fout]*/, float* out /*[n,fout]*/,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/* Gradients of L = <gout, out>: gx [n,fin] (nullable), gw_fc [fin,k*fout],
+ * gmu, ginv_sigma [k,2]. */
+gnn_status_t gnn_gmm_bwd(const gnn_graph_t* graph, int fin, int fout, int k, const float* x,
+                         const float* w_fc, const float* c, const float* mu, const float* inv_sigma,
+                         const float* hk, const float* gout /*[n,fout]*/, float* gx /*nullable*/,
+                         float* gw_fc, float* gmu, float* ginv_sigma,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------- *
+ * Per-kernel timing (measurement aid, Sec. 7 metrics).  While enabled, every
+ * kernel the library launches is bracketed by HIP events recorded on the
+ * caller's stream.  gnn_prof_collect synchronises those events (host sync) and
+ * folds them into per-kernel totals; gnn_prof_get reads entry i (name is a
+ * library-owned string).  Not thread-safe; meant for benchmarks only.
+ * ------------------------------------------------------------------------- */
+gnn_status_t gnn_prof_enable(int on);
+gnn_status_t gnn_prof_collect(void);
+gnn_status_t gnn_prof_reset(void);
+int gnn_prof_count(void);
+gnn_status_t gnn_prof_get(int i, const char** name, double* total_ms, int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GNN_FUSED_H */

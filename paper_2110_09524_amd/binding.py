@@ -1,0 +1,242 @@
+"""ctypes binding of libgnnfused.so: argument marshalling only.
+
+Every function mirrors one entry point of include/gnn_fused.h and takes torch
+tensors that live on the GPU (torch is used for device memory and streams, no
+arithmetic happens here).  If the shared library is missing the import fails
+loudly: there is no CPU or PyTorch fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgnnfused.so")
+
+GNN_NUM_BUCKETS = 33
+STATUS_NAMES = {0: "GNN_OK", 1: "GNN_ERR_INVALID_ARG", 2: "GNN_ERR_BAD_GRAPH",
+                3: "GNN_ERR_WORKSPACE", 4: "GNN_ERR_UNSUPPORTED", 5: "GNN_ERR_HIP"}
+
+EXPORTS = [
+    "gnn_last_error", "gnn_graph_create", "gnn_graph_destroy", "gnn_graph_get_csc",
+    "gnn_graph_get_buckets", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
+    "gnn_gat_bwd", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
+    "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd", "gnn_prof_enable",
+    "gnn_prof_collect", "gnn_prof_reset", "gnn_prof_count", "gnn_prof_get",
+]
+
+
+class GnnError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {text}")
+        self.status = status
+
+
+def load_library(path: str = LIB_PATH) -> C.CDLL:
+    if not os.path.exists(path):
+        raise ImportError(
+            f"{path} is missing: build it with `python -m paper_2110_09524_amd.build` "
+            "(there is no fallback path)")
+    lib = C.CDLL(path)
+    vp, i32, i64, f32, sz = C.c_void_p, C.c_int, C.c_int64, C.c_float, C.c_size_t
+    lib.gnn_last_error.restype = C.c_char_p
+    lib.gnn_last_error.argtypes = []
+    lib.gnn_graph_create.argtypes = [C.c_int32, i64, vp, vp, vp, C.POINTER(vp)]
+    lib.gnn_graph_destroy.argtypes = [vp]
+    lib.gnn_graph_get_csc.argtypes = [vp, vp, vp, vp, vp]
+    lib.gnn_graph_get_buckets.argtypes = [vp, i32, vp, vp, vp, vp]
+    lib.gnn_linear_fwd.argtypes = [i64, i32, i32, vp, vp, vp, vp]
+    lib.gnn_gat_workspace_bytes.restype = sz
+    lib.gnn_gat_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    lib.gnn_gat_fwd.argtypes = [vp, i32, i32, i32, f32] + [vp] * 10 + [vp, sz, vp]
+    lib.gnn_gat_bwd.argtypes = [vp, i32, i32, i32, f32] + [vp] * 15 + [vp, sz, vp]
+    lib.gnn_edgeconv_workspace_bytes.restype = sz
+    lib.gnn_edgeconv_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.gnn_edgeconv_fwd.argtypes = [vp, i32, i32] + [vp] * 6 + [vp, sz, vp]
+    lib.gnn_edgeconv_bwd.argtypes = [vp, i32, i32] + [vp] * 8 + [vp, sz, vp]
+    lib.gnn_gmm_workspace_bytes.restype = sz
+    lib.gnn_gmm_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    lib.gnn_gmm_fwd.argtypes = [vp, i32, i32, i32] + [vp] * 7 + [vp, sz, vp]
+    lib.gnn_gmm_bwd.argtypes = [vp, i32, i32, i32] + [vp] * 11 + [vp, sz, vp]
+    lib.gnn_prof_enable.argtypes = [i32]
+    lib.gnn_prof_collect.argtypes = []
+    lib.gnn_prof_reset.argtypes = []
+    lib.gnn_prof_count.argtypes = []
+    lib.gnn_prof_get.argtypes = [i32, C.POINTER(C.c_char_p), C.POINTER(C.c_double), C.POINTER(i64)]
+    for name in EXPORTS:
+        fn = getattr(lib, name)
+        if name not in ("gnn_last_error", "gnn_gat_workspace_bytes", "gnn_edgeconv_workspace_bytes",
+                        "gnn_gmm_workspace_bytes", "gnn_prof_count"):
+            fn.restype = C.c_int
+    return lib
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = load_library()
+    return _lib
+
+
+def _check(status: int):
+    if status != 0:
+        raise GnnError(status, lib().gnn_last_error().decode())
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor):
+        raise TypeError("expected a torch tensor")
+    if not t.is_cuda:
+        raise ValueError("tensor must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _f(t):
+    return _ptr(t, torch.float32)
+
+
+def _i(t):
+    return _ptr(t, torch.int32)
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+class Graph:
+    """Handle of gnn_graph_create.  Keeps the borrowed CSR tensors alive."""
+
+    def __init__(self, indptr: torch.Tensor, indices: torch.Tensor, stream=None):
+        self.indptr, self.indices = indptr, indices
+        self.n = indptr.numel() - 1
+        self.nnz = indices.numel()
+        self.device = indptr.device
+        h = C.c_void_p()
+        _check(lib().gnn_graph_create(self.n, self.nnz, _i(indptr), _i(indices) if self.nnz else None,
+                                      _stream(stream), C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().gnn_graph_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def handle(self):
+        return self._h
+
+    def csc(self, stream=None):
+        ip = torch.empty(self.n + 1, dtype=torch.int32, device=self.device)
+        ix = torch.empty(self.nnz, dtype=torch.int32, device=self.device)
+        eid = torch.empty(self.nnz, dtype=torch.int32, device=self.device)
+        _check(lib().gnn_graph_get_csc(self._h, _i(ip), _i(ix), _i(eid), _stream(stream)))
+        return ip, ix, eid
+
+    def buckets(self, side: int, stream=None):
+        b = torch.empty(self.n, dtype=torch.int32, device=self.device)
+        o = torch.empty(self.n, dtype=torch.int32, device=self.device)
+        off = torch.empty(GNN_NUM_BUCKETS + 1, dtype=torch.int32, device=self.device)
+        _check(lib().gnn_graph_get_buckets(self._h, side, _i(b), _i(o), _i(off), _stream(stream)))
+        return b, o, off
+
+
+def gnn_linear_fwd(x, w, y, stream=None):
+    n, fin = x.shape
+    _check(lib().gnn_linear_fwd(n, fin, w.shape[1], _f(x), _f(w), _f(y), _stream(stream)))
+
+
+def _ws_args(ws):
+    if ws is None:
+        return None, 0
+    return C.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size()
+
+
+def gnn_gat_workspace_bytes(g: Graph, fin, heads, f) -> int:
+    return int(lib().gnn_gat_workspace_bytes(g.handle, fin, heads, f))
+
+
+def gnn_gat_fwd(g: Graph, fin, heads, f, slope, x, w, a_l, a_r, z, el, er, m, d, out, ws=None,
+                stream=None):
+    wp, wb = _ws_args(ws)
+    _check(lib().gnn_gat_fwd(g.handle, fin, heads, f, slope, _f(x), _f(w), _f(a_l), _f(a_r), _f(z),
+                             _f(el), _f(er), _f(m), _f(d), _f(out), wp, wb, _stream(stream)))
+
+
+def gnn_gat_bwd(g: Graph, fin, heads, f, slope, x, w, a_l, a_r, z, el, er, m, d, out, gout, gx, gw,
+                ga_l, ga_r, ws, stream=None):
+    wp, wb = _ws_args(ws)
+    _check(lib().gnn_gat_bwd(g.handle, fin, heads, f, slope, _f(x), _f(w), _f(a_l), _f(a_r), _f(z),
+                             _f(el), _f(er), _f(m), _f(d), _f(out), _f(gout), _f(gx), _f(gw), _f(ga_l),
+                             _f(ga_r), wp, wb, _stream(stream)))
+
+
+def gnn_edgeconv_workspace_bytes(g: Graph, fin, fout) -> int:
+    return int(lib().gnn_edgeconv_workspace_bytes(g.handle, fin, fout))
+
+
+def gnn_edgeconv_fwd(g: Graph, fin, fout, x, theta, phi, pq, out, argmax, ws=None, stream=None):
+    wp, wb = _ws_args(ws)
+    _check(lib().gnn_edgeconv_fwd(g.handle, fin, fout, _f(x), _f(theta), _f(phi), _f(pq), _f(out),
+                                  _i(argmax), wp, wb, _stream(stream)))
+
+
+def gnn_edgeconv_bwd(g: Graph, fin, fout, x, theta, phi, argmax, gout, gx, gtheta, gphi, ws,
+                     stream=None):
+    wp, wb = _ws_args(ws)
+    _check(lib().gnn_edgeconv_bwd(g.handle, fin, fout, _f(x), _f(theta), _f(phi), _i(argmax), _f(gout),
+                                  _f(gx), _f(gtheta), _f(gphi), wp, wb, _stream(stream)))
+
+
+def gnn_gmm_workspace_bytes(g: Graph, fin, fout, k) -> int:
+    return int(lib().gnn_gmm_workspace_bytes(g.handle, fin, fout, k))
+
+
+def gnn_gmm_fwd(g: Graph, fin, fout, k, x, w_fc, c, mu, inv_sigma, hk, out, ws=None, stream=None):
+    wp, wb = _ws_args(ws)
+    _check(lib().gnn_gmm_fwd(g.handle, fin, fout, k, _f(x), _f(w_fc), _f(c), _f(mu), _f(inv_sigma),
+                             _f(hk), _f(out), wp, wb, _stream(stream)))
+
+
+def gnn_gmm_bwd(g: Graph, fin, fout, k, x, w_fc, c, mu, inv_sigma, hk, gout, gx, gw_fc, gmu,
+                ginv_sigma, ws, stream=None):
+    wp, wb = _ws_args(ws)
+    _check(lib().gnn_gmm_bwd(g.handle, fin, fout, k, _f(x), _f(w_fc), _f(c), _f(mu), _f(inv_sigma),
+                             _f(hk), _f(gout), _f(gx), _f(gw_fc), _f(gmu), _f(ginv_sigma), wp, wb,
+                             _stream(stream)))
+
+
+def gnn_prof_enable(on: bool):
+    _check(lib().gnn_prof_enable(1 if on else 0))
+
+
+def gnn_prof_reset():
+    _check(lib().gnn_prof_reset())
+
+
+def gnn_prof_report() -> dict:
+    """{kernel name: (total_ms, launches)} of everything timed since the last reset."""
+    _check(lib().gnn_prof_collect())
+    res = {}
+    for i in range(lib().gnn_prof_count()):
+        name, ms, cnt = C.c_char_p(), C.c_double(), C.c_int64()
+        _check(lib().gnn_prof_get(i, C.byref(name), C.byref(ms), C.byref(cnt)))
+        res[name.value.decode()] = (ms.value, cnt.value)
+    return res

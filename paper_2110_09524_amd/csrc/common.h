@@ -1,0 +1,105 @@
+// Shared host-side plumbing: error text, HIP checks, the timed-launch bracket,
+// the graph handle, and the few device helpers every kernel file uses.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+
+#include "gnn_fused.h"
+
+namespace gnn {
+
+constexpr int kWave = 64;
+
+// ---- error reporting --------------------------------------------------------
+void set_error(const char* fmt, ...);
+void clear_error();
+
+#define GNN_HIP(expr)                                                                  \
+  do {                                                                                 \
+    hipError_t e_ = (expr);                                                            \
+    if (e_ != hipSuccess) {                                                            \
+      ::gnn::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, \
+                       __LINE__);                                                      \
+      return GNN_ERR_HIP;                                                              \
+    }                                                                                  \
+  } while (0)
+
+#define GNN_REQUIRE(cond, status, ...) \
+  do {                                 \
+    if (!(cond)) {                     \
+      ::gnn::set_error(__VA_ARGS__);   \
+      return (status);                 \
+    }                                  \
+  } while (0)
+
+#define GNN_TRY(expr)                 \
+  do {                                \
+    gnn_status_t s_ = (expr);         \
+    if (s_ != GNN_OK) return s_;      \
+  } while (0)
+
+// ---- timed launches ---------------------------------------------------------
+// prof_begin/prof_end record HIP events around a launch when profiling is on.
+void prof_begin(const char* name, hipStream_t s);
+void prof_end(hipStream_t s);
+
+struct ProfScope {
+  hipStream_t s;
+  ProfScope(const char* name, hipStream_t st) : s(st) { prof_begin(name, st); }
+  ~ProfScope() { prof_end(s); }
+};
+
+// Call right after a kernel launch.
+#define GNN_LAUNCH_CHECK() GNN_HIP(hipGetLastError())
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Bump allocator over the caller's workspace (256-byte granules).
+struct Workspace {
+  char* base;
+  size_t size, used;
+  Workspace(void* p, size_t n) : base(static_cast<char*>(p)), size(n), used(0) {}
+  template <typename T>
+  T* take(size_t count) {
+    size_t bytes = align_up(count * sizeof(T), 256);
+    T* r = reinterpret_cast<T*>(base + used);
+    used += bytes;
+    return r;
+  }
+  bool ok() const { return used <= size && (base != nullptr || used == 0); }
+};
+inline size_t ws_granule(size_t bytes) { return align_up(bytes, 256); }
+
+// ---- dense products (gemm.hip) ------------------------------------------------
+// c[M,N] = op(a) op(b), fp32 MFMA.  a_kmajor: a is stored [K,M] (m contiguous)
+// instead of [M,K]; b_kcontig: b is stored [N,K] (k contiguous) instead of [K,N].
+// split_k > 1 writes split_k partial products into `partials` and sums them in a
+// fixed order (deterministic).  partials needs split_k*M*N floats.
+gnn_status_t gemm_f32(int64_t M, int N, int64_t K, const float* a, int64_t lda, bool a_kmajor,
+                      const float* b, int64_t ldb, bool b_kcontig, float* c, int64_t ldc,
+                      int split_k, float* partials, hipStream_t s);
+int gemm_pick_split_k(int64_t M, int N, int64_t K);
+
+}  // namespace gnn
+
+// The graph handle: borrowed CSR plus the plan tables it owns.
+struct gnn_graph {
+  int32_t n;
+  int64_t nnz;
+  const int32_t* indptr;   // borrowed
+  const int32_t* indices;  // borrowed
+  int32_t* indptr_t;       // owned from here on
+  int32_t* indices_t;
+  int32_t* eid_t;
+  int32_t* bucket_of[2];
+  int32_t* order[2];
+  int32_t* bucket_offsets[2];            // device copies
+  int32_t h_bucket_offsets[2][GNN_NUM_BUCKETS + 1];  // host copies
+  int32_t max_degree[2];
+};

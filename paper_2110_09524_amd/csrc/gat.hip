@@ -1,0 +1,694 @@
+// GAT layer: attention halves, the fused score -> edge-softmax -> aggregate
+// kernel, and the recomputing backward kernels.
+//
+// Forward (App. A.2 "GAT", fused operator M0..H^(l+1); Sec. 5 example): one row
+// group per destination, online softmax over chunks of its in-edges, the
+// projected source rows gathered with 16-byte loads.  Saved: max m and
+// denominator d per (vertex, head) only (Sec. 6 example).
+//
+// Backward (Sec. 6; operator rules of App. B).  With alpha_e the softmax value,
+// g_e = LeakyReLU'(el[u]+er[v]) and D[v,h] = <gout[v,h,:], out[v,h,:]>, the score
+// gradient of edge e is  dp_e = alpha_e g_e (<gout[v,h,:], z[u,h,:]> - D[v,h]).
+// Instead of one dot product per edge, the dot product is postponed past the
+// neighbourhood sum (the same distributive-law argument as Sec. 4):
+//   der[v,h] = sum_in  dp_e = <gout[v,h,:], sum_in alpha_e g_e z[u,h,:]> - D[v,h] sum_in alpha_e g_e
+//   del[u,h] = sum_out dp_e = <z[u,h,:], sum_out alpha_e g_e gout[v,h,:]> - sum_out alpha_e g_e D[v,h]
+// so both backward kernels are weighted row aggregations like the forward one:
+// the destination-side kernel walks the CSR, the source-side kernel walks the
+// CSC transpose (no atomics), and alpha_e is recomputed from el, er, m, d.
+#include "common.h"
+#include "rowgroup.h"
+
+namespace gnn {
+
+constexpr int kBlock = 256;  // 4 wavefronts
+
+// ---- a2: attention halves  el = <z, a_l>, er = <z, a_r> per (vertex, head) -----
+__global__ void k_gat_attn_halves(int64_t n, int H, int F, const float* __restrict__ z,
+                                  const float* __restrict__ a_l, const float* __restrict__ a_r,
+                                  float* __restrict__ el, float* __restrict__ er) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;  // (vertex, head)
+  if (i >= n * H) return;
+  int h = (int)(i % H);
+  const float* zr = z + i * F;  // z[v, h, :] : i*F = (v*H + h)*F
+  const float* al = a_l + (int64_t)h * F;
+  const float* ar = a_r + (int64_t)h * F;
+  float sl = 0.f, sr = 0.f;
+  for (int f = 0; f < F; f += 4) {
+    float4 zz = ld4(zr + f);
+    sl += dot4(zz, ld4(al + f));
+    sr += dot4(zz, ld4(ar + f));
+  }
+  el[i] = sl;
+  er[i] = sr;
+}
+
+struct GatDims {
+  int H, F, HF;
+  int log2Hp;  // heads padded to a power of two; lanes of a group = (edge, head) pairs
+  float slope;
+};
+
+__device__ __forceinline__ float leaky(float x, float slope) { return x > 0.f ? x : slope * x; }
+
+// LDS layout per group: idx[L] | p[L] | p2[L] | misc[L] | red[2*L*NV]
+template <int L, int NV>
+struct GroupLds {
+  static constexpr int kFloats = 4 * L + 2 * L * NV;
+};
+
+// ---- a3: fused forward ----------------------------------------------------------
+template <int L, int NV>
+__global__ __launch_bounds__(kBlock) void k_gat_fwd(
+    int32_t n_rows, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    const int32_t* __restrict__ indices, const float* __restrict__ z, const float* __restrict__ el,
+    const float* __restrict__ er, GatDims dm, float* __restrict__ out, float* __restrict__ m_out,
+    float* __restrict__ d_out) {
+  constexpr int G = kWave / L;
+  constexpr int GPB = G * (kBlock / kWave);
+  __shared__ float lds[GPB * GroupLds<L, NV>::kFloats];
+
+  const int lane = threadIdx.x & 63;
+  const int li = lane & (L - 1);
+  const int grp = threadIdx.x / L;  // group inside the block
+  const int64_t r = (int64_t)blockIdx.x * GPB + grp;
+  if (r >= n_rows) return;  // whole group leaves together
+  float* g_lds = lds + grp * GroupLds<L, NV>::kFloats;
+  int* l_idx = reinterpret_cast<int*>(g_lds);
+  float* l_p = g_lds + L;
+  float* l_sc = g_lds + 3 * L;
+
+  const int H = dm.H, HF = dm.HF;
+  const int Hp = 1 << dm.log2Hp;
+  const int epc = L >> dm.log2Hp;  // edges per chunk
+  const int e_loc = li >> dm.log2Hp;
+  const int h = li & (Hp - 1);
+  const bool head_ok = h < H;
+
+  const int32_t v = order[r];
+  const int32_t beg = indptr[v], end = indptr[v + 1];
+  const float er_vh = head_ok ? er[(int64_t)v * H + h] : 0.f;
+
+  int hs[NV];
+  bool slot_ok[NV];
+  float4 acc[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    int col = 4 * (li + j * L);
+    slot_ok[j] = col < HF;
+    hs[j] = slot_ok[j] ? col / dm.F : 0;
+    acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+
+  float m_run = -INFINITY, d_run = 0.f;
+  for (int32_t c0 = beg; c0 < end; c0 += epc) {
+    // chunk phase: lane = (edge e_loc of the chunk, head h)
+    const int32_t e = c0 + e_loc;
+    const bool e_ok = e < end;
+    const int32_t u = e_ok ? indices[e] : 0;
+    float s = -INFINITY;
+    if (e_ok && head_ok) s = leaky(el[(int64_t)u * H + h] + er_vh, dm.slope);
+    const float cmax = group_max_from<L>(s, Hp);
+    const float m_new = fmaxf(m_run, cmax);
+    const float p = (e_ok && head_ok) ? __expf(s - m_new) : 0.f;
+    const float sc = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
+    d_run = d_run * sc + p;
+    m_run = m_new;
+    if (h == 0) l_idx[e_loc] = u;
+    l_p[li] = p;
+    if (e_loc == 0) l_sc[h] = sc;
+    wave_lds_fence();
+    // row phase: lane = float4 column slots; the chunk is summed on its own first
+    float4 part[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) part[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int cnt = min(epc, end - c0);
+    int t = 0;
+    for (; t + 4 <= cnt; t += 4) {
+      int uu[4];
+      float4 row[4][NV];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        uu[q] = l_idx[t + q];
+        if (L == 64) uu[q] = __builtin_amdgcn_readfirstlane(uu[q]);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+          if (slot_ok[j]) row[q][j] = ld4(z + (int64_t)uu[q] * HF + 4 * (li + j * L));
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+          if (slot_ok[j]) fma4(part[j], l_p[((t + q) << dm.log2Hp) + hs[j]], row[q][j]);
+    }
+    for (; t < cnt; ++t) {
+      int uu = l_idx[t];
+      if (L == 64) uu = __builtin_amdgcn_readfirstlane(uu);
+#pragma unroll
+      for (int j = 0; j < NV; ++j)
+        if (slot_ok[j])
+          fma4(part[j], l_p[(t << dm.log2Hp) + hs[j]], ld4(z + (int64_t)uu * HF + 4 * (li + j * L)));
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) fold4(acc[j], l_sc[hs[j]], part[j]);  // rescale to the new max, add the chunk
+    wave_lds_fence();
+  }
+
+  // denominators: sum the per-lane partials of each head, then hand them to the column lanes
+  float dd = group_sum_from<L>(d_run, Hp);
+  const bool empty = beg == end;
+  if (empty) { dd = 1.f; m_run = 0.f; }
+  if (e_loc == 0) l_sc[h] = dd;
+  wave_lds_fence();
+#pragma unroll
+  for (int j = 0; j < NV; ++j)
+    if (slot_ok[j]) {
+      float inv = 1.f / l_sc[hs[j]];
+      scale4(acc[j], inv);
+      st4(out + (int64_t)v * HF + 4 * (li + j * L), acc[j]);
+    }
+  if (e_loc == 0 && head_ok) {
+    m_out[(int64_t)v * H + h] = m_run;
+    d_out[(int64_t)v * H + h] = dd;
+  }
+}
+
+// per-head sum of per-slot partials: lane (e_loc == 0, h) adds the slots of head h
+template <int L, int NV>
+__device__ __forceinline__ float head_sum(const float* red, int h, int F) {
+  float s = 0.f;
+  const int q0 = h * F / 4, q1 = (h + 1) * F / 4;
+  for (int q = q0; q < q1; ++q) s += red[(q / L) * L + (q % L)];  // slot q = (lane q%L, j = q/L)
+  return s;
+}
+
+// ---- a4: backward, destination side (CSR walk) -----------------------------------
+// writes der[v,h], and vstate[v,h] = (er, m, 1/d, D) for the source-side kernel
+template <int L, int NV>
+__global__ __launch_bounds__(kBlock) void k_gat_bwd_dst(
+    int32_t n_rows, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    const int32_t* __restrict__ indices, const float* __restrict__ z, const float* __restrict__ el,
+    const float* __restrict__ er, const float* __restrict__ m_in, const float* __restrict__ d_in,
+    const float* __restrict__ out, const float* __restrict__ gout, GatDims dm,
+    float* __restrict__ der, float4* __restrict__ vstate) {
+  constexpr int G = kWave / L;
+  constexpr int GPB = G * (kBlock / kWave);
+  __shared__ float lds[GPB * GroupLds<L, NV>::kFloats];
+
+  const int lane = threadIdx.x & 63;
+  const int li = lane & (L - 1);
+  const int grp = threadIdx.x / L;
+  const int64_t r = (int64_t)blockIdx.x * GPB + grp;
+  if (r >= n_rows) return;
+  float* g_lds = lds + grp * GroupLds<L, NV>::kFloats;
+  int* l_idx = reinterpret_cast<int*>(g_lds);
+  float* l_p = g_lds + L;
+  float* l_sc = g_lds + 3 * L;
+  float* l_red = g_lds + 4 * L;
+
+  const int H = dm.H, HF = dm.HF;
+  const int Hp = 1 << dm.log2Hp;
+  const int epc = L >> dm.log2Hp;
+  const int e_loc = li >> dm.log2Hp;
+  const int h = li & (Hp - 1);
+  const bool head_ok = h < H;
+
+  const int32_t v = order[r];
+  const int32_t beg = indptr[v], end = indptr[v + 1];
+  float er_vh = 0.f, m_vh = 0.f, invd_vh = 1.f;
+  if (head_ok) {
+    er_vh = er[(int64_t)v * H + h];
+    m_vh = m_in[(int64_t)v * H + h];
+    invd_vh = 1.f / d_in[(int64_t)v * H + h];
+  }
+
+  int hs[NV];
+  bool slot_ok[NV];
+  float4 acc[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    int col = 4 * (li + j * L);
+    slot_ok[j] = col < HF;
+    hs[j] = slot_ok[j] ? col / dm.F : 0;
+    acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+
+  float sg_run = 0.f;  // partial of sum alpha_e g_e
+  for (int32_t c0 = beg; c0 < end; c0 += epc) {
+    const int32_t e = c0 + e_loc;
+    const bool e_ok = e < end;
+    const int32_t u = e_ok ? indices[e] : 0;
+    float q = 0.f;
+    if (e_ok && head_ok) {
+      const float raw = el[(int64_t)u * H + h] + er_vh;
+      const float alpha = __expf(leaky(raw, dm.slope) - m_vh) * invd_vh;
+      q = raw > 0.f ? alpha : dm.slope * alpha;
+    }
+    sg_run += q;
+    if (h == 0) l_idx[e_loc] = u;
+    l_p[li] = q;
+    wave_lds_fence();
+    float4 part[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) part[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int cnt = min(epc, end - c0);
+    int t = 0;
+    for (; t + 4 <= cnt; t += 4) {
+      int uu[4];
+      float4 row[4][NV];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        uu[k] = l_idx[t + k];
+        if (L == 64) uu[k] = __builtin_amdgcn_readfirstlane(uu[k]);
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+          if (slot_ok[j]) row[k][j] = ld4(z + (int64_t)uu[k] * HF + 4 * (li + j * L));
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+          if (slot_ok[j]) fma4(part[j], l_p[((t + k) << dm.log2Hp) + hs[j]], row[k][j]);
+    }
+    for (; t < cnt; ++t) {
+      int uu = l_idx[t];
+      if (L == 64) uu = __builtin_amdgcn_readfirstlane(uu);
+#pragma unroll
+      for (int j = 0; j < NV; ++j)
+        if (slot_ok[j])
+          fma4(part[j], l_p[(t << dm.log2Hp) + hs[j]], ld4(z + (int64_t)uu * HF + 4 * (li + j * L)));
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) add4(acc[j], part[j]);
+    wave_lds_fence();
+  }
+
+  const float sg = group_sum_from<L>(sg_run, Hp);
+  // per-slot partial dot products with gout[v], then per-head sums through LDS
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    float p1 = 0.f, pd = 0.f;
+    if (slot_ok[j]) {
+      const int64_t off = (int64_t)v * HF + 4 * (li + j * L);
+      const float4 g4 = ld4(gout + off);
+      p1 = dot4(g4, acc[j]);
+      pd = dot4(g4, ld4(out + off));
+    }
+    l_red[j * L + li] = p1;
+    l_red[L * NV + j * L + li] = pd;
+  }
+  wave_lds_fence();
+  if (e_loc == 0 && head_ok) {
+    const float t1 = head_sum<L, NV>(l_red, h, dm.F);
+    const float D = head_sum<L, NV>(l_red + L * NV, h, dm.F);
+    der[(int64_t)v * H + h] = t1 - D * sg;
+    vstate[(int64_t)v * H + h] = make_float4(er_vh, m_vh, invd_vh, D);
+  }
+}
+
+// ---- a5: backward, source side (CSC walk, no atomics) ------------------------------
+// dz[u] = sum_out alpha_e gout[v] + a_l del[u] + a_r der[u];  writes del[u,h] too
+template <int L, int NV>
+__global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
+    int32_t n_rows, const int32_t* __restrict__ order_t, const int32_t* __restrict__ indptr_t,
+    const int32_t* __restrict__ indices_t, const float* __restrict__ z, const float* __restrict__ el,
+    const float4* __restrict__ vstate, const float* __restrict__ der, const float* __restrict__ gout,
+    const float* __restrict__ a_l, const float* __restrict__ a_r, GatDims dm,
+    float* __restrict__ dz, float* __restrict__ del) {
+  constexpr int G = kWave / L;
+  constexpr int GPB = G * (kBlock / kWave);
+  __shared__ float lds[GPB * GroupLds<L, NV>::kFloats];
+
+  const int lane = threadIdx.x & 63;
+  const int li = lane & (L - 1);
+  const int grp = threadIdx.x / L;
+  const int64_t r = (int64_t)blockIdx.x * GPB + grp;
+  if (r >= n_rows) return;
+  float* g_lds = lds + grp * GroupLds<L, NV>::kFloats;
+  int* l_idx = reinterpret_cast<int*>(g_lds);
+  float* l_p = g_lds + L;
+  float* l_p2 = g_lds + 2 * L;
+  float* l_sc = g_lds + 3 * L;
+  float* l_red = g_lds + 4 * L;
+
+  const int H = dm.H, HF = dm.HF;
+  const int Hp = 1 << dm.log2Hp;
+  const int epc = L >> dm.log2Hp;
+  const int e_loc = li >> dm.log2Hp;
+  const int h = li & (Hp - 1);
+  const bool head_ok = h < H;
+
+  const int32_t u = order_t[r];
+  const int32_t beg = indptr_t[u], end = indptr_t[u + 1];
+  const float el_uh = head_ok ? el[(int64_t)u * H + h] : 0.f;
+
+  int hs[NV];
+  bool slot_ok[NV];
+  float4 acc1[NV], acc2[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    int col = 4 * (li + j * L);
+    slot_ok[j] = col < HF;
+    hs[j] = slot_ok[j] ? col / dm.F : 0;
+    acc1[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    acc2[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+
+  float sd_run = 0.f;  // partial of sum alpha_e g_e D[v,h]
+  for (int32_t c0 = beg; c0 < end; c0 += epc) {
+    const int32_t e = c0 + e_loc;
+    const bool e_ok = e < end;
+    const int32_t v = e_ok ? indices_t[e] : 0;
+    float alpha = 0.f, ag = 0.f;
+    if (e_ok && head_ok) {
+      const float4 vs = vstate[(int64_t)v * H + h];  // (er, m, 1/d, D)
+      const float raw = el_uh + vs.x;
+      alpha = __expf(leaky(raw, dm.slope) - vs.y) * vs.z;
+      ag = raw > 0.f ? alpha : dm.slope * alpha;
+      sd_run = fmaf(ag, vs.w, sd_run);
+    }
+    if (h == 0) l_idx[e_loc] = v;
+    l_p[li] = alpha;
+    l_p2[li] = ag;
+    wave_lds_fence();
+    float4 part1[NV], part2[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      part1[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      part2[j] = part1[j];
+    }
+    const int cnt = min(epc, end - c0);
+    int t = 0;
+    for (; t + 4 <= cnt; t += 4) {
+      int vv[4];
+      float4 row[4][NV];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        vv[k] = l_idx[t + k];
+        if (L == 64) vv[k] = __builtin_amdgcn_readfirstlane(vv[k]);
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+          if (slot_ok[j]) row[k][j] = ld4(gout + (int64_t)vv[k] * HF + 4 * (li + j * L));
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+          if (slot_ok[j]) {
+            const int pi = ((t + k) << dm.log2Hp) + hs[j];
+            fma4(part1[j], l_p[pi], row[k][j]);
+            fma4(part2[j], l_p2[pi], row[k][j]);
+          }
+    }
+    for (; t < cnt; ++t) {
+      int vv = l_idx[t];
+      if (L == 64) vv = __builtin_amdgcn_readfirstlane(vv);
+#pragma unroll
+      for (int j = 0; j < NV; ++j)
+        if (slot_ok[j]) {
+          const float4 row = ld4(gout + (int64_t)vv * HF + 4 * (li + j * L));
+          const int pi = (t << dm.log2Hp) + hs[j];
+          fma4(part1[j], l_p[pi], row);
+          fma4(part2[j], l_p2[pi], row);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      add4(acc1[j], part1[j]);
+      add4(acc2[j], part2[j]);
+    }
+    wave_lds_fence();
+  }
+
+  const float sd = group_sum_from<L>(sd_run, Hp);
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    float p = 0.f;
+    if (slot_ok[j]) p = dot4(ld4(z + (int64_t)u * HF + 4 * (li + j * L)), acc2[j]);
+    l_red[j * L + li] = p;
+  }
+  wave_lds_fence();
+  if (e_loc == 0) {
+    float dl = 0.f, dr = 0.f;
+    if (head_ok) {
+      dl = head_sum<L, NV>(l_red, h, dm.F) - sd;
+      dr = der[(int64_t)u * H + h];
+      del[(int64_t)u * H + h] = dl;
+    }
+    l_sc[h] = dl;
+    l_p[h] = dr;  // reuse as the per-head der broadcast
+  }
+  wave_lds_fence();
+#pragma unroll
+  for (int j = 0; j < NV; ++j)
+    if (slot_ok[j]) {
+      const int col = 4 * (li + j * L);
+      const float dl = l_sc[hs[j]], dr = l_p[hs[j]];
+      float4 o = acc1[j];
+      fma4(o, dl, ld4(a_l + col));  // a_l, a_r are [H, F] = HF contiguous floats
+      fma4(o, dr, ld4(a_r + col));
+      st4(dz + (int64_t)u * HF + col, o);
+    }
+}
+
+// ---- a6: ga_l[h,f] = sum_u del[u,h] z[u,h,f], ga_r[h,f] = sum_v der[v,h] z[v,h,f] ---
+// stage 1: each block reduces a contiguous range of vertices; stage 2 adds the blocks in order
+__global__ void k_gat_param_partial(int64_t n, int H, int F, int64_t rows_per_block,
+                                    const float* __restrict__ z, const float* __restrict__ del,
+                                    const float* __restrict__ der, float* __restrict__ partial) {
+  const int HF = H * F;
+  const int64_t r0 = blockIdx.x * rows_per_block;
+  int64_t r1 = r0 + rows_per_block;
+  if (r1 > n) r1 = n;
+  for (int c = threadIdx.x; c < HF; c += blockDim.x) {
+    const int h = c / F;
+    float sl = 0.f, sr = 0.f;
+    for (int64_t r = r0; r < r1; ++r) {
+      const float zz = z[r * HF + c];
+      sl = fmaf(del[r * H + h], zz, sl);
+      sr = fmaf(der[r * H + h], zz, sr);
+    }
+    partial[((int64_t)blockIdx.x * 2 + 0) * HF + c] = sl;
+    partial[((int64_t)blockIdx.x * 2 + 1) * HF + c] = sr;
+  }
+}
+
+__global__ void k_gat_param_final(int HF, int nblk, const float* __restrict__ partial,
+                                  float* __restrict__ ga_l, float* __restrict__ ga_r) {
+  int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= HF) return;
+  float sl = 0.f, sr = 0.f;
+  for (int b = 0; b < nblk; ++b) {
+    sl += partial[((int64_t)b * 2 + 0) * HF + c];
+    sr += partial[((int64_t)b * 2 + 1) * HF + c];
+  }
+  ga_l[c] = sl;
+  ga_r[c] = sr;
+}
+
+// ---- host side -------------------------------------------------------------------
+static int param_blocks(int64_t n) {
+  int64_t b = cdiv(n, 64);
+  if (b > 1024) b = 1024;
+  return b < 1 ? 1 : (int)b;
+}
+
+struct GatWs {
+  size_t total;
+  size_t dz, vstate, der, del, partial, gemm;
+  int split_k, nblk;
+};
+
+static GatWs gat_ws_layout(int64_t n, int fin, int H, int F) {
+  GatWs w{};
+  const int HF = H * F;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += ws_granule(bytes); return o; };
+  w.dz = take(sizeof(float) * n * HF);
+  w.vstate = take(sizeof(float) * 4 * n * H);
+  w.der = take(sizeof(float) * n * H);
+  w.del = take(sizeof(float) * n * H);
+  w.nblk = param_blocks(n);
+  w.partial = take(sizeof(float) * 2 * (size_t)w.nblk * HF);
+  w.split_k = gemm_pick_split_k(fin, HF, n);
+  w.gemm = take(w.split_k > 1 ? sizeof(float) * (size_t)w.split_k * fin * HF : 0);
+  w.total = off;
+  return w;
+}
+
+static gnn_status_t check_gat_dims(const gnn_graph_t* g, int fin, int H, int F, const char* who) {
+  GNN_REQUIRE(g != nullptr, GNN_ERR_INVALID_ARG, "%s: graph is null", who);
+  GNN_REQUIRE(fin > 0 && H > 0 && F > 0, GNN_ERR_INVALID_ARG, "%s: sizes must be positive", who);
+  GNN_REQUIRE(F % 4 == 0, GNN_ERR_UNSUPPORTED, "%s: f = %d is not a multiple of 4", who, F);
+  GNN_REQUIRE(H * F <= 1024, GNN_ERR_UNSUPPORTED, "%s: heads*f = %d exceeds 1024", who, H * F);
+  GNN_REQUIRE(H <= 64, GNN_ERR_UNSUPPORTED, "%s: heads = %d exceeds 64", who, H);
+  GroupShape gs = pick_group(H * F);
+  GNN_REQUIRE(next_pow2(H) <= gs.L, GNN_ERR_UNSUPPORTED,
+              "%s: %d heads do not fit a %d-lane row group", who, H, gs.L);
+  return GNN_OK;
+}
+
+template <template <int, int> class Launcher, typename... Args>
+static gnn_status_t dispatch_group(GroupShape gs, Args... args) {
+  switch (gs.L) {
+    case 4: return Launcher<4, 1>::run(args...);
+    case 8: return Launcher<8, 1>::run(args...);
+    case 16: return Launcher<16, 1>::run(args...);
+    case 32: return Launcher<32, 1>::run(args...);
+    case 64:
+      switch (gs.NV) {
+        case 1: return Launcher<64, 1>::run(args...);
+        case 2: return Launcher<64, 2>::run(args...);
+        case 3: return Launcher<64, 3>::run(args...);
+        case 4: return Launcher<64, 4>::run(args...);
+      }
+  }
+  set_error("unsupported row-group shape L=%d NV=%d", gs.L, gs.NV);
+  return GNN_ERR_UNSUPPORTED;
+}
+
+template <int L, int NV>
+struct FwdLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, const float* z, const float* el, const float* er,
+                          GatDims dm, float* out, float* m, float* d, hipStream_t st) {
+    constexpr int GPB = (kWave / L) * (kBlock / kWave);
+    ProfScope p("gat_fwd_fused", st);
+    k_gat_fwd<L, NV><<<(unsigned)cdiv(g->n, GPB), kBlock, 0, st>>>(
+        g->n, g->order[0], g->indptr, g->indices, z, el, er, dm, out, m, d);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+  }
+};
+
+template <int L, int NV>
+struct BwdDstLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, const float* z, const float* el, const float* er,
+                          const float* m, const float* d, const float* out, const float* gout,
+                          GatDims dm, float* der, float4* vstate, hipStream_t st) {
+    constexpr int GPB = (kWave / L) * (kBlock / kWave);
+    ProfScope p("gat_bwd_dst", st);
+    k_gat_bwd_dst<L, NV><<<(unsigned)cdiv(g->n, GPB), kBlock, 0, st>>>(
+        g->n, g->order[0], g->indptr, g->indices, z, el, er, m, d, out, gout, dm, der, vstate);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+  }
+};
+
+template <int L, int NV>
+struct BwdSrcLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, const float* z, const float* el, const float4* vstate,
+                          const float* der, const float* gout, const float* a_l, const float* a_r,
+                          GatDims dm, float* dz, float* del, hipStream_t st) {
+    constexpr int GPB = (kWave / L) * (kBlock / kWave);
+    ProfScope p("gat_bwd_src", st);
+    k_gat_bwd_src<L, NV><<<(unsigned)cdiv(g->n, GPB), kBlock, 0, st>>>(
+        g->n, g->order[1], g->indptr_t, g->indices_t, z, el, vstate, der, gout, a_l, a_r, dm, dz, del);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+  }
+};
+
+static GatDims make_dims(int H, int F, float slope) {
+  GatDims dm;
+  dm.H = H;
+  dm.F = F;
+  dm.HF = H * F;
+  dm.log2Hp = ilog2(next_pow2(H));
+  dm.slope = slope;
+  return dm;
+}
+
+}  // namespace gnn
+
+using namespace gnn;
+
+extern "C" size_t gnn_gat_workspace_bytes(const gnn_graph_t* g, int fin, int heads, int f) {
+  if (!g || fin <= 0 || heads <= 0 || f <= 0) return 0;
+  return gat_ws_layout(g->n, fin, heads, f).total;
+}
+
+extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, int f, float slope,
+                                    const float* x, const float* w, const float* a_l, const float* a_r,
+                                    float* z, float* el, float* er, float* m, float* d, float* out,
+                                    void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  (void)ws;
+  (void)ws_bytes;
+  GNN_TRY(check_gat_dims(g, fin, heads, f, "gnn_gat_fwd"));
+  if (g->n == 0) return GNN_OK;
+  GNN_REQUIRE(x && w && a_l && a_r && z && el && er && m && d && out, GNN_ERR_INVALID_ARG,
+              "gnn_gat_fwd: null pointer");
+  GNN_REQUIRE(aligned16(z) && aligned16(out) && aligned16(a_l) && aligned16(a_r), GNN_ERR_INVALID_ARG,
+              "gnn_gat_fwd: z, out, a_l, a_r must be 16-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int HF = heads * f;
+  const int64_t n = g->n;
+  // a1: projection before propagation
+  GNN_TRY(gemm_f32(n, HF, fin, x, fin, false, w, HF, false, z, HF, 1, nullptr, st));
+  // a2: attention halves
+  {
+    ProfScope p("gat_attn_halves", st);
+    k_gat_attn_halves<<<(unsigned)cdiv(n * heads, 256), 256, 0, st>>>(n, heads, f, z, a_l, a_r, el, er);
+    GNN_LAUNCH_CHECK();
+  }
+  // a3: fused score -> softmax -> aggregate
+  return dispatch_group<FwdLauncher>(pick_group(HF), g, (const float*)z, (const float*)el,
+                                     (const float*)er, make_dims(heads, f, slope), out, m, d, st);
+}
+
+extern "C" gnn_status_t gnn_gat_bwd(const gnn_graph_t* g, int fin, int heads, int f, float slope,
+                                    const float* x, const float* w, const float* a_l, const float* a_r,
+                                    const float* z, const float* el, const float* er, const float* m,
+                                    const float* d, const float* out, const float* gout, float* gx,
+                                    float* gw, float* ga_l, float* ga_r, void* ws, size_t ws_bytes,
+                                    void* stream) {
+  clear_error();
+  GNN_TRY(check_gat_dims(g, fin, heads, f, "gnn_gat_bwd"));
+  if (g->n == 0) return GNN_OK;
+  GNN_REQUIRE(x && w && a_l && a_r && z && el && er && m && d && out && gout && gw && ga_l && ga_r,
+              GNN_ERR_INVALID_ARG, "gnn_gat_bwd: null pointer");
+  GNN_REQUIRE(aligned16(z) && aligned16(out) && aligned16(gout) && aligned16(a_l) && aligned16(a_r),
+              GNN_ERR_INVALID_ARG, "gnn_gat_bwd: z, out, gout, a_l, a_r must be 16-byte aligned");
+  const int64_t n = g->n;
+  const int HF = heads * f;
+  const GatWs L = gat_ws_layout(n, fin, heads, f);
+  GNN_REQUIRE(ws != nullptr && ws_bytes >= L.total, GNN_ERR_WORKSPACE,
+              "gnn_gat_bwd: workspace of %zu bytes given, %zu needed", ws_bytes, L.total);
+  GNN_REQUIRE(aligned16(ws), GNN_ERR_INVALID_ARG, "gnn_gat_bwd: workspace must be 16-byte aligned");
+  char* base = static_cast<char*>(ws);
+  float* dz = reinterpret_cast<float*>(base + L.dz);
+  float4* vstate = reinterpret_cast<float4*>(base + L.vstate);
+  float* der = reinterpret_cast<float*>(base + L.der);
+  float* del = reinterpret_cast<float*>(base + L.del);
+  float* partial = reinterpret_cast<float*>(base + L.partial);
+  float* gemm_part = reinterpret_cast<float*>(base + L.gemm);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const GatDims dm = make_dims(heads, f, slope);
+  const GroupShape gs = pick_group(HF);
+
+  // a4: destination side
+  GNN_TRY(dispatch_group<BwdDstLauncher>(gs, g, z, el, er, m, d, out, gout, dm, der, vstate, st));
+  // a5: source side
+  GNN_TRY(dispatch_group<BwdSrcLauncher>(gs, g, z, el, (const float4*)vstate, (const float*)der, gout,
+                                         a_l, a_r, dm, dz, del, st));
+  // a6: parameter gradients
+  {
+    ProfScope p("gat_param_grad", st);
+    const int64_t rpb = cdiv(n, L.nblk);
+    k_gat_param_partial<<<L.nblk, 256, 0, st>>>(n, heads, f, rpb, z, del, der, partial);
+    GNN_LAUNCH_CHECK();
+    k_gat_param_final<<<(unsigned)cdiv(HF, 256), 256, 0, st>>>(HF, L.nblk, partial, ga_l, ga_r);
+    GNN_LAUNCH_CHECK();
+  }
+  // gw = x^T dz   (x read k-major: row index of x is the contraction index)
+  GNN_TRY(gemm_f32(fin, HF, n, x, fin, true, dz, HF, false, gw, HF, L.split_k, gemm_part, st));
+  // gx = dz w^T   (w read with its row index as the output column)
+  if (gx) GNN_TRY(gemm_f32(n, fin, HF, dz, HF, false, w, HF, true, gx, fin, 1, nullptr, st));
+  return GNN_OK;
+}

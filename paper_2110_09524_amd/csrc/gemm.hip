@@ -1,0 +1,220 @@
+// fp32 dense products on the MFMA matrix cores (v_mfma_f32_32x32x2_f32): the
+// ExpensiveApply projections that the reorganization moves onto vertices
+// (Sec. 4) and their two backward products (App. B, "Apply").
+//
+// Tiling: a 256-thread workgroup (4 wavefronts, 2 x 2) owns a 128 x BN tile of
+// C; each wavefront owns 64 x BN/2 of it as 2 x (BN/64) MFMA 32x32 tiles held in
+// accumulators.  K advances 16 at a time through LDS; both operands sit in LDS
+// k-major ([k][m] and [k][n]) so every MFMA operand read is one conflict-free
+// ds_read_b32 with consecutive lanes on consecutive addresses, whatever the
+// operands' layout in HBM.  Global loads of the next K-slab are issued before the
+// MFMAs of the current one (register prefetch).
+#include "common.h"
+
+namespace gnn {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128;
+constexpr int BK = 16;
+constexpr int GEMM_THREADS = 256;
+constexpr int LDS_PAD = 4;  // row stride = 4 (mod 32) banks: transposing stores spread over banks
+
+template <int BN, bool A_KMAJOR, bool B_KCONTIG>
+__global__ __launch_bounds__(GEMM_THREADS) void k_gemm_f32(
+    int64_t M, int N, int64_t K, const float* __restrict__ A, int64_t lda,
+    const float* __restrict__ B, int64_t ldb, float* __restrict__ C, int64_t ldc,
+    int64_t k_per_split, int64_t split_stride) {
+  constexpr int TN = BN / 64;          // MFMA tiles per wavefront along n
+  constexpr int A_PER_T = BM * BK / GEMM_THREADS;  // 8
+  constexpr int B_PER_T = BN * BK / GEMM_THREADS;  // 8 or 4
+  __shared__ float As[BK][BM + LDS_PAD];
+  __shared__ float Bs[BK][BN + LDS_PAD];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm0 = (wave >> 1) * 64;
+  const int wn0 = (wave & 1) * (BN / 2);
+  const int64_t m0 = (int64_t)blockIdx.x * BM;
+  const int n0 = blockIdx.y * BN;
+  const int64_t k_begin = (int64_t)blockIdx.z * k_per_split;
+  int64_t k_end = k_begin + k_per_split;
+  if (k_end > K) k_end = K;
+
+  floatx16 acc[2][TN];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  float ra[A_PER_T], rb[B_PER_T];
+
+  auto load_slab = [&](int64_t k0) {
+#pragma unroll
+    for (int i = 0; i < A_PER_T; ++i) {
+      int idx = tid + GEMM_THREADS * i;
+      int kk, mm;
+      if (A_KMAJOR) { mm = idx % BM; kk = idx / BM; } else { kk = idx % BK; mm = idx / BK; }
+      int64_t m = m0 + mm, k = k0 + kk;
+      float v = 0.f;
+      if (m < M && k < k_end) v = A_KMAJOR ? A[k * lda + m] : A[m * lda + k];
+      ra[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < B_PER_T; ++i) {
+      int idx = tid + GEMM_THREADS * i;
+      int kk, nn;
+      if (B_KCONTIG) { kk = idx % BK; nn = idx / BK; } else { nn = idx % BN; kk = idx / BN; }
+      int n = n0 + nn;
+      int64_t k = k0 + kk;
+      float v = 0.f;
+      if (n < N && k < k_end) v = B_KCONTIG ? B[(int64_t)n * ldb + k] : B[k * ldb + n];
+      rb[i] = v;
+    }
+  };
+  auto store_slab = [&]() {
+#pragma unroll
+    for (int i = 0; i < A_PER_T; ++i) {
+      int idx = tid + GEMM_THREADS * i;
+      int kk, mm;
+      if (A_KMAJOR) { mm = idx % BM; kk = idx / BM; } else { kk = idx % BK; mm = idx / BK; }
+      As[kk][mm] = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < B_PER_T; ++i) {
+      int idx = tid + GEMM_THREADS * i;
+      int kk, nn;
+      if (B_KCONTIG) { kk = idx % BK; nn = idx / BK; } else { nn = idx % BN; kk = idx / BN; }
+      Bs[kk][nn] = rb[i];
+    }
+  };
+
+  const int lrow = lane & 31;   // row (A) / column (B) inside an MFMA tile
+  const int lk = lane >> 5;     // which of the 2 k values of one MFMA step
+
+  if (k_begin < k_end) load_slab(k_begin);
+  for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
+    store_slab();
+    __syncthreads();
+    if (k0 + BK < k_end) load_slab(k0 + BK);
+#pragma unroll
+    for (int ks = 0; ks < BK / 2; ++ks) {
+      const int kk = ks * 2 + lk;
+      float a[2], b[TN];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) a[i] = As[kk][wm0 + i * 32 + lrow];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) b[j] = Bs[kk][wn0 + j * 32 + lrow];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  // accumulator layout of the 32x32 tile: register r of lane l holds
+  // row 8*(r/4) + 4*(l/32) + r%4, column l%32
+  float* Cout = C + (int64_t)blockIdx.z * split_stride;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = n0 + wn0 + j * 32 + lrow;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t m = m0 + wm0 + i * 32 + (r >> 2) * 8 + lk * 4 + (r & 3);
+        if (m < M && n < N) Cout[m * ldc + n] = acc[i][j][r];
+      }
+    }
+}
+
+// c[i] = sum over z of partials[z][i], z ascending (fixed order => reproducible)
+__global__ void k_sum_partials(int64_t count, int splits, const float* __restrict__ partials,
+                               float* __restrict__ c) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i >= count) return;
+  float s = 0.f;
+  for (int z = 0; z < splits; ++z) s += partials[(int64_t)z * count + i];
+  c[i] = s;
+}
+
+int gemm_pick_split_k(int64_t M, int N, int64_t K) {
+  const int bn = N > 64 ? 128 : 64;
+  int64_t tiles = cdiv(M, BM) * cdiv(N, bn);
+  if (tiles >= 512 || K < 4096) return 1;
+  int64_t want = cdiv(1536, tiles);
+  int64_t max_by_k = K / 512;  // keep at least 512 of K per split
+  if (want > max_by_k) want = max_by_k;
+  if (want > 512) want = 512;
+  return want < 1 ? 1 : (int)want;
+}
+
+template <int BN, bool AK, bool BKC>
+static gnn_status_t launch(int64_t M, int N, int64_t K, const float* a, int64_t lda, const float* b,
+                           int64_t ldb, float* c, int64_t ldc, int split_k, float* partials,
+                           hipStream_t s) {
+  dim3 grid((unsigned)cdiv(M, BM), (unsigned)cdiv(N, BN), (unsigned)split_k);
+  if (split_k == 1) {
+    ProfScope p("gemm_f32_mfma", s);
+    k_gemm_f32<BN, AK, BKC><<<grid, GEMM_THREADS, 0, s>>>(M, N, K, a, lda, b, ldb, c, ldc, K, 0);
+    GNN_LAUNCH_CHECK();
+  } else {
+    int64_t kps = cdiv(cdiv(K, split_k), BK) * BK;
+    {
+      ProfScope p("gemm_f32_mfma_splitk", s);
+      k_gemm_f32<BN, AK, BKC><<<grid, GEMM_THREADS, 0, s>>>(M, N, K, a, lda, b, ldb, partials, N, kps,
+                                                            M * (int64_t)N);
+      GNN_LAUNCH_CHECK();
+    }
+    ProfScope p("gemm_sum_partials", s);
+    int64_t count = M * (int64_t)N;
+    if (ldc == N) {
+      k_sum_partials<<<cdiv(count, 256), 256, 0, s>>>(count, split_k, partials, c);
+      GNN_LAUNCH_CHECK();
+    } else {
+      set_error("gemm_f32: split-K needs a dense output (ldc == N)");
+      return GNN_ERR_INVALID_ARG;
+    }
+  }
+  return GNN_OK;
+}
+
+gnn_status_t gemm_f32(int64_t M, int N, int64_t K, const float* a, int64_t lda, bool a_kmajor,
+                      const float* b, int64_t ldb, bool b_kcontig, float* c, int64_t ldc,
+                      int split_k, float* partials, hipStream_t s) {
+  if (M <= 0 || N <= 0) return GNN_OK;
+  GNN_REQUIRE(K > 0, GNN_ERR_INVALID_ARG, "gemm_f32: K must be positive");
+  GNN_REQUIRE(cdiv(M, BM) < (int64_t)INT32_MAX && split_k >= 1 && split_k <= 65535,
+              GNN_ERR_UNSUPPORTED, "gemm_f32: grid too large");
+  GNN_REQUIRE(split_k == 1 || partials != nullptr, GNN_ERR_INVALID_ARG,
+              "gemm_f32: split-K without a partials buffer");
+#define GNN_GEMM_CASE(BN_, AK_, BK_)                                                          \
+  return launch<BN_, AK_, BK_>(M, N, K, a, lda, b, ldb, c, ldc, split_k, partials, s)
+  if (N > 64) {
+    if (a_kmajor) { if (b_kcontig) GNN_GEMM_CASE(128, true, true); else GNN_GEMM_CASE(128, true, false); }
+    else          { if (b_kcontig) GNN_GEMM_CASE(128, false, true); else GNN_GEMM_CASE(128, false, false); }
+  } else {
+    if (a_kmajor) { if (b_kcontig) GNN_GEMM_CASE(64, true, true); else GNN_GEMM_CASE(64, true, false); }
+    else          { if (b_kcontig) GNN_GEMM_CASE(64, false, true); else GNN_GEMM_CASE(64, false, false); }
+  }
+#undef GNN_GEMM_CASE
+}
+
+}  // namespace gnn
+
+using namespace gnn;
+
+extern "C" gnn_status_t gnn_linear_fwd(int64_t n, int fin, int fout, const float* x, const float* w,
+                                       float* y, void* stream) {
+  clear_error();
+  GNN_REQUIRE(n >= 0 && fin > 0 && fout > 0, GNN_ERR_INVALID_ARG, "gnn_linear_fwd: bad sizes");
+  if (n == 0) return GNN_OK;
+  GNN_REQUIRE(x && w && y, GNN_ERR_INVALID_ARG, "gnn_linear_fwd: null pointer");
+  return gemm_f32(n, fout, fin, x, fin, false, w, fout, false, y, fout, 1, nullptr,
+                  static_cast<hipStream_t>(stream));
+}

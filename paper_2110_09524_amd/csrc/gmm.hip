@@ -1,0 +1,481 @@
+// MoNet / GMMConv layer (App. A.2 "GMMConv").  MoNet has no leading Scatter, so no
+// reorganization is needed (Sec. 7.2 "MoNet"); the Gaussian weights (ApplyEdge)
+// and the Aggregate are fused into one destination-walking kernel, and the weights
+// are recomputed in the backward pass instead of being stored (Sec. 7.3).
+//
+// Notation: m_e = (c[u], c[v]), t_jd = (m_d - mu[j,d]) inv_sigma[j,d],
+// w_j(e) = exp(-1/2 (t_j0^2 + t_j1^2)), out[v] = (1/K) sum_e sum_j w_j(e) hk[u,j,:].
+//
+// Backward.  dw_j(e) = (1/K) <gout[v], hk[u,j,:]> would need one dot product per
+// edge and kernel; by the distributive law the dot product is taken after the
+// neighbourhood sum instead.  Per destination v and kernel j the kernel aggregates
+//   A_j = sum_e w_j hk[u,j,:],  R_j = sum_e w_j (c[u]-mu_j0) hk[u,j,:],
+//   S_j = sum_e w_j (c[u]-mu_j0)^2 hk[u,j,:]
+// and then, with tA = <gout[v], A_j> etc. (the second coordinate c[v] is constant
+// along a destination row):
+//   gmu[j,0]  += tR is_j0^2 / K             gmu[j,1]  += tA (c[v]-mu_j1) is_j1^2 / K
+//   gis[j,0]  += -tS is_j0 / K              gis[j,1]  += -tA (c[v]-mu_j1)^2 is_j1 / K
+// summed over destinations in a fixed two-stage order.  The source side
+//   dhk[u,j,:] = (1/K) sum over out-edges w_j(e) gout[v,:]
+// walks the CSC transpose (no atomics).
+#include "common.h"
+#include "rowgroup.h"
+
+namespace gnn {
+
+constexpr int kGmmBlock = 256;
+constexpr int kMaxK = 8;
+
+struct GmmParams {
+  int K, log2Kp, F;
+};
+
+__device__ __forceinline__ float gauss_w(float cu, float cv, float mu0, float mu1, float is0, float is1) {
+  const float t0 = (cu - mu0) * is0, t1 = (cv - mu1) * is1;
+  return __expf(-0.5f * (t0 * t0 + t1 * t1));
+}
+
+// ---- a9: fused forward -----------------------------------------------------------------
+template <int L, int NV>
+__global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd(
+    int32_t n_rows, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    const int32_t* __restrict__ indices, const float* __restrict__ hk, const float* __restrict__ c,
+    const float* __restrict__ mu, const float* __restrict__ inv_sigma, GmmParams pm,
+    float* __restrict__ out) {
+  constexpr int G = kWave / L;
+  constexpr int GPB = G * (kGmmBlock / kWave);
+  __shared__ float lds[GPB * 2 * L];
+  const int lane = threadIdx.x & 63;
+  const int li = lane & (L - 1);
+  const int grp = threadIdx.x / L;
+  const int64_t r = (int64_t)blockIdx.x * GPB + grp;
+  if (r >= n_rows) return;
+  int* l_idx = reinterpret_cast<int*>(lds + grp * 2 * L);
+  float* l_w = lds + grp * 2 * L + L;
+
+  const int K = pm.K, F = pm.F, KF = K * F;
+  const int Kp = 1 << pm.log2Kp;
+  const int epc = L >> pm.log2Kp;
+  const int e_loc = li >> pm.log2Kp;
+  const int kk = li & (Kp - 1);
+  const bool k_ok = kk < K;
+  const float mu0 = k_ok ? mu[2 * kk] : 0.f, mu1 = k_ok ? mu[2 * kk + 1] : 0.f;
+  const float is0 = k_ok ? inv_sigma[2 * kk] : 0.f, is1 = k_ok ? inv_sigma[2 * kk + 1] : 0.f;
+  const float inv_k = 1.f / (float)K;
+
+  const int32_t v = order[r];
+  const int32_t beg = indptr[v], end = indptr[v + 1];
+  const float cv = c[v];
+
+  bool slot_ok[NV];
+  float4 acc[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    slot_ok[j] = 4 * (li + j * L) < F;
+    acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  // two-level summation: `part` collects a few chunks, then folds into `acc`
+  float4 part[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) part[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+  int chunk_no = 0;
+  for (int32_t c0 = beg; c0 < end; c0 += epc) {
+    const int32_t e = c0 + e_loc;
+    const bool e_ok = e < end;
+    const int32_t u = e_ok ? indices[e] : 0;
+    float w = 0.f;
+    if (e_ok && k_ok) w = gauss_w(c[u], cv, mu0, mu1, is0, is1) * inv_k;
+    if (kk == 0) l_idx[e_loc] = u;
+    l_w[li] = w;
+    wave_lds_fence();
+    const int cnt = min(epc, end - c0);
+    for (int t = 0; t < cnt; ++t) {
+      int uu = l_idx[t];
+      if (L == 64) uu = __builtin_amdgcn_readfirstlane(uu);
+      const float* row = hk + (int64_t)uu * KF;
+      for (int k = 0; k < K; ++k) {
+        const float wk = l_w[(t << pm.log2Kp) + k];
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+          if (slot_ok[j]) fma4(part[j], wk, ld4(row + k * F + 4 * (li + j * L)));
+      }
+    }
+    if ((++chunk_no & 3) == 0) {
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        add4(acc[j], part[j]);
+        part[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+    }
+    wave_lds_fence();
+  }
+#pragma unroll
+  for (int j = 0; j < NV; ++j)
+    if (slot_ok[j]) {
+      add4(acc[j], part[j]);
+      st4(out + (int64_t)v * F + 4 * (li + j * L), acc[j]);
+    }
+}
+
+// ---- a10, destination side: gradients of mu and inv_sigma (CSR walk) ------------------
+// partial[block][j][4] = this block's share of (gmu_j0, gmu_j1, gis_j0, gis_j1)
+template <int L, int NV>
+__global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_dst(
+    int32_t n_rows, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    const int32_t* __restrict__ indices, const float* __restrict__ hk, const float* __restrict__ c,
+    const float* __restrict__ mu, const float* __restrict__ inv_sigma, const float* __restrict__ gout,
+    GmmParams pm, float* __restrict__ partial) {
+  constexpr int G = kWave / L;
+  constexpr int GPB = G * (kGmmBlock / kWave);
+  __shared__ float lds[GPB * 2 * L];
+  __shared__ float blk[GPB][kMaxK][4];
+  const int lane = threadIdx.x & 63;
+  const int li = lane & (L - 1);
+  const int grp = threadIdx.x / L;
+  const int64_t r = (int64_t)blockIdx.x * GPB + grp;
+  const bool active = r < n_rows;
+  int* l_idx = reinterpret_cast<int*>(lds + grp * 2 * L);
+  float* l_c = lds + grp * 2 * L + L;
+
+  const int K = pm.K, F = pm.F, KF = K * F;
+  const float inv_k = 1.f / (float)K;
+  if (li < kMaxK) {
+    blk[grp][li][0] = 0.f; blk[grp][li][1] = 0.f; blk[grp][li][2] = 0.f; blk[grp][li][3] = 0.f;
+  }
+  if (L < kMaxK) {  // L == 4: lanes 0..3 also clear kernels 4..7
+    if (li + 4 < kMaxK) {
+      blk[grp][li + 4][0] = 0.f; blk[grp][li + 4][1] = 0.f; blk[grp][li + 4][2] = 0.f; blk[grp][li + 4][3] = 0.f;
+    }
+  }
+  if (active) {
+    const int32_t v = order[r];
+    const int32_t beg = indptr[v], end = indptr[v + 1];
+    const float cv = c[v];
+    bool slot_ok[NV];
+    float4 g4[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      slot_ok[j] = 4 * (li + j * L) < F;
+      g4[j] = slot_ok[j] ? ld4(gout + (int64_t)v * F + 4 * (li + j * L)) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    for (int k = 0; k < K; ++k) {  // one pass per kernel: each pass reads its own slice of hk
+      const float mu0 = mu[2 * k], mu1 = mu[2 * k + 1];
+      const float is0 = inv_sigma[2 * k], is1 = inv_sigma[2 * k + 1];
+      float4 aA[NV], aR[NV], aS[NV];
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        aA[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        aR[j] = aA[j];
+        aS[j] = aA[j];
+      }
+      for (int32_t c0 = beg; c0 < end; c0 += L) {
+        const int32_t e = c0 + li;
+        const int32_t u = e < end ? indices[e] : 0;
+        l_idx[li] = u;
+        l_c[li] = c[u];
+        wave_lds_fence();
+        float4 pA[NV], pR[NV], pS[NV];  // this chunk's share (two-level summation)
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+          pA[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+          pR[j] = pA[j];
+          pS[j] = pA[j];
+        }
+        const int cnt = min(L, end - c0);
+        for (int t = 0; t < cnt; ++t) {
+          int uu = l_idx[t];
+          if (L == 64) uu = __builtin_amdgcn_readfirstlane(uu);
+          const float cu = l_c[t];
+          const float w = gauss_w(cu, cv, mu0, mu1, is0, is1);
+          const float d0 = cu - mu0;
+          const float wr = w * d0, wsq = wr * d0;
+#pragma unroll
+          for (int j = 0; j < NV; ++j)
+            if (slot_ok[j]) {
+              const float4 row = ld4(hk + (int64_t)uu * KF + k * F + 4 * (li + j * L));
+              fma4(pA[j], w, row);
+              fma4(pR[j], wr, row);
+              fma4(pS[j], wsq, row);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+          add4(aA[j], pA[j]);
+          add4(aR[j], pR[j]);
+          add4(aS[j], pS[j]);
+        }
+        wave_lds_fence();
+      }
+      float tA = 0.f, tR = 0.f, tS = 0.f;
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        tA += dot4(g4[j], aA[j]);
+        tR += dot4(g4[j], aR[j]);
+        tS += dot4(g4[j], aS[j]);
+      }
+      tA = group_sum_from<L>(tA, 1);
+      tR = group_sum_from<L>(tR, 1);
+      tS = group_sum_from<L>(tS, 1);
+      if (li == 0) {
+        const float d1 = cv - mu1;
+        blk[grp][k][0] = tR * is0 * is0 * inv_k;
+        blk[grp][k][1] = tA * d1 * is1 * is1 * inv_k;
+        blk[grp][k][2] = -tS * is0 * inv_k;
+        blk[grp][k][3] = -tA * d1 * d1 * is1 * inv_k;
+      }
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < kMaxK * 4) {
+    const int k = threadIdx.x >> 2, q = threadIdx.x & 3;
+    float s = 0.f;
+    for (int gi = 0; gi < GPB; ++gi) s += blk[gi][k][q];  // fixed order
+    partial[((int64_t)blockIdx.x * kMaxK + k) * 4 + q] = s;
+  }
+}
+
+// gmu[j,d], gis[j,d] = sum over blocks, in block order
+__global__ void k_gmm_param_final(int K, int64_t nblk, const float* __restrict__ partial,
+                                  float* __restrict__ gmu, float* __restrict__ gis) {
+  const int t = threadIdx.x;  // (k, q)
+  if (t >= K * 4) return;
+  const int k = t >> 2, q = t & 3;
+  float s = 0.f;
+  for (int64_t b = 0; b < nblk; ++b) s += partial[(b * kMaxK + k) * 4 + q];
+  if (q < 2) gmu[2 * k + q] = s; else gis[2 * k + (q - 2)] = s;
+}
+
+// ---- a10, source side: dhk[u,j,:] = (1/K) sum over out-edges w_j(e) gout[v,:] ----------
+template <int L, int NV>
+__global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_src(
+    int32_t n_rows, const int32_t* __restrict__ order_t, const int32_t* __restrict__ indptr_t,
+    const int32_t* __restrict__ indices_t, const float* __restrict__ c, const float* __restrict__ mu,
+    const float* __restrict__ inv_sigma, const float* __restrict__ gout, GmmParams pm,
+    float* __restrict__ dhk) {
+  constexpr int G = kWave / L;
+  constexpr int GPB = G * (kGmmBlock / kWave);
+  constexpr int KB = 4;  // kernels accumulated per pass over the out-edges
+  __shared__ float lds[GPB * 2 * L];
+  const int lane = threadIdx.x & 63;
+  const int li = lane & (L - 1);
+  const int grp = threadIdx.x / L;
+  const int64_t r = (int64_t)blockIdx.x * GPB + grp;
+  if (r >= n_rows) return;
+  int* l_idx = reinterpret_cast<int*>(lds + grp * 2 * L);
+  float* l_c = lds + grp * 2 * L + L;
+
+  const int K = pm.K, F = pm.F, KF = K * F;
+  const float inv_k = 1.f / (float)K;
+  const int32_t u = order_t[r];
+  const int32_t beg = indptr_t[u], end = indptr_t[u + 1];
+  const float cu = c[u];
+  bool slot_ok[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) slot_ok[j] = 4 * (li + j * L) < F;
+
+  for (int k0 = 0; k0 < K; k0 += KB) {
+    float mu0[KB], mu1[KB], is0[KB], is1[KB];
+#pragma unroll
+    for (int q = 0; q < KB; ++q) {
+      const bool ok = k0 + q < K;
+      mu0[q] = ok ? mu[2 * (k0 + q)] : 0.f;
+      mu1[q] = ok ? mu[2 * (k0 + q) + 1] : 0.f;
+      is0[q] = ok ? inv_sigma[2 * (k0 + q)] : 0.f;
+      is1[q] = ok ? inv_sigma[2 * (k0 + q) + 1] : 0.f;
+    }
+    float4 acc[KB][NV];
+#pragma unroll
+    for (int q = 0; q < KB; ++q)
+#pragma unroll
+      for (int j = 0; j < NV; ++j) acc[q][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int32_t c0 = beg; c0 < end; c0 += L) {
+      const int32_t i = c0 + li;
+      const int32_t v = i < end ? indices_t[i] : 0;
+      l_idx[li] = v;
+      l_c[li] = c[v];
+      wave_lds_fence();
+      float4 part[KB][NV];  // this chunk's share (two-level summation)
+#pragma unroll
+      for (int q = 0; q < KB; ++q)
+#pragma unroll
+        for (int j = 0; j < NV; ++j) part[q][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      const int cnt = min(L, end - c0);
+      for (int t = 0; t < cnt; ++t) {
+        int vv = l_idx[t];
+        if (L == 64) vv = __builtin_amdgcn_readfirstlane(vv);
+        const float cv = l_c[t];
+        float w[KB];
+#pragma unroll
+        for (int q = 0; q < KB; ++q) w[q] = gauss_w(cu, cv, mu0[q], mu1[q], is0[q], is1[q]) * inv_k;
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+          if (slot_ok[j]) {
+            const float4 row = ld4(gout + (int64_t)vv * F + 4 * (li + j * L));
+#pragma unroll
+            for (int q = 0; q < KB; ++q) fma4(part[q][j], w[q], row);
+          }
+      }
+#pragma unroll
+      for (int q = 0; q < KB; ++q)
+#pragma unroll
+        for (int j = 0; j < NV; ++j) add4(acc[q][j], part[q][j]);
+      wave_lds_fence();
+    }
+#pragma unroll
+    for (int q = 0; q < KB; ++q)
+      if (k0 + q < K)
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+          if (slot_ok[j]) st4(dhk + (int64_t)u * KF + (k0 + q) * F + 4 * (li + j * L), acc[q][j]);
+  }
+}
+
+template <int L, int NV>
+struct GmmFwdLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, const float* hk, const float* c, const float* mu,
+                          const float* is, GmmParams pm, float* out, hipStream_t st) {
+    constexpr int GPB = (kWave / L) * (kGmmBlock / kWave);
+    ProfScope p("gmm_fwd_fused", st);
+    k_gmm_fwd<L, NV><<<(unsigned)cdiv(g->n, GPB), kGmmBlock, 0, st>>>(
+        g->n, g->order[0], g->indptr, g->indices, hk, c, mu, is, pm, out);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+  }
+};
+
+template <int L, int NV>
+struct GmmBwdDstLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, const float* hk, const float* c, const float* mu,
+                          const float* is, const float* gout, GmmParams pm, float* partial,
+                          float* gmu, float* gis, hipStream_t st) {
+    constexpr int GPB = (kWave / L) * (kGmmBlock / kWave);
+    const int64_t nblk = cdiv(g->n, GPB);
+    ProfScope p("gmm_bwd_dst", st);
+    k_gmm_bwd_dst<L, NV><<<(unsigned)nblk, kGmmBlock, 0, st>>>(
+        g->n, g->order[0], g->indptr, g->indices, hk, c, mu, is, gout, pm, partial);
+    GNN_LAUNCH_CHECK();
+    k_gmm_param_final<<<1, 64, 0, st>>>(pm.K, nblk, partial, gmu, gis);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+  }
+};
+
+template <int L, int NV>
+struct GmmBwdSrcLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, const float* c, const float* mu, const float* is,
+                          const float* gout, GmmParams pm, float* dhk, hipStream_t st) {
+    constexpr int GPB = (kWave / L) * (kGmmBlock / kWave);
+    ProfScope p("gmm_bwd_src", st);
+    k_gmm_bwd_src<L, NV><<<(unsigned)cdiv(g->n, GPB), kGmmBlock, 0, st>>>(
+        g->n, g->order[1], g->indptr_t, g->indices_t, c, mu, is, gout, pm, dhk);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+  }
+};
+
+// fout <= 256 keeps NV == 1
+template <template <int, int> class Launcher, typename... Args>
+static gnn_status_t gmm_dispatch(GroupShape gs, Args... args) {
+  switch (gs.L) {
+    case 4: return Launcher<4, 1>::run(args...);
+    case 8: return Launcher<8, 1>::run(args...);
+    case 16: return Launcher<16, 1>::run(args...);
+    case 32: return Launcher<32, 1>::run(args...);
+    case 64: return Launcher<64, 1>::run(args...);
+  }
+  set_error("unsupported row-group shape L=%d", gs.L);
+  return GNN_ERR_UNSUPPORTED;
+}
+
+struct GmmWs {
+  size_t total, dhk, partial, gemm;
+  int split_k;
+  int64_t nblk;
+};
+
+static GmmWs gmm_ws_layout(int64_t n, int fin, int fout, int K) {
+  GmmWs w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += ws_granule(bytes); return o; };
+  const GroupShape gs = pick_group(fout);
+  const int gpb = (kWave / gs.L) * (kGmmBlock / kWave);
+  w.nblk = cdiv(n, gpb);
+  w.dhk = take(sizeof(float) * (size_t)n * K * fout);
+  w.partial = take(sizeof(float) * (size_t)w.nblk * kMaxK * 4);
+  w.split_k = gemm_pick_split_k(fin, K * fout, n);
+  w.gemm = take(w.split_k > 1 ? sizeof(float) * (size_t)w.split_k * fin * K * fout : 0);
+  w.total = off;
+  return w;
+}
+
+static gnn_status_t gmm_check(const gnn_graph_t* g, int fin, int fout, int K, const char* who) {
+  GNN_REQUIRE(g != nullptr, GNN_ERR_INVALID_ARG, "%s: graph is null", who);
+  GNN_REQUIRE(fin > 0 && fout > 0 && K > 0, GNN_ERR_INVALID_ARG, "%s: sizes must be positive", who);
+  GNN_REQUIRE(fout % 4 == 0 && fout <= 256, GNN_ERR_UNSUPPORTED,
+              "%s: fout = %d must be a multiple of 4, at most 256", who, fout);
+  GNN_REQUIRE(K <= kMaxK, GNN_ERR_UNSUPPORTED, "%s: k = %d exceeds %d", who, K, kMaxK);
+  GNN_REQUIRE(next_pow2(K) <= pick_group(fout).L, GNN_ERR_UNSUPPORTED,
+              "%s: %d kernels do not fit a %d-lane row group (fout too small)", who, K,
+              pick_group(fout).L);
+  return GNN_OK;
+}
+
+}  // namespace gnn
+
+using namespace gnn;
+
+extern "C" size_t gnn_gmm_workspace_bytes(const gnn_graph_t* g, int fin, int fout, int k) {
+  if (!g || fin <= 0 || fout <= 0 || k <= 0) return 0;
+  return gmm_ws_layout(g->n, fin, fout, k).total;
+}
+
+extern "C" gnn_status_t gnn_gmm_fwd(const gnn_graph_t* g, int fin, int fout, int k, const float* x,
+                                    const float* w_fc, const float* c, const float* mu,
+                                    const float* inv_sigma, float* hk, float* out, void* ws,
+                                    size_t ws_bytes, void* stream) {
+  clear_error();
+  (void)ws;
+  (void)ws_bytes;
+  GNN_TRY(gmm_check(g, fin, fout, k, "gnn_gmm_fwd"));
+  if (g->n == 0) return GNN_OK;
+  GNN_REQUIRE(x && w_fc && c && mu && inv_sigma && hk && out, GNN_ERR_INVALID_ARG,
+              "gnn_gmm_fwd: null pointer");
+  GNN_REQUIRE(aligned16(hk) && aligned16(out), GNN_ERR_INVALID_ARG,
+              "gnn_gmm_fwd: hk, out must be 16-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  GNN_TRY(gemm_f32(g->n, k * fout, fin, x, fin, false, w_fc, k * fout, false, hk, k * fout, 1, nullptr, st));
+  GmmParams pm{k, ilog2(next_pow2(k)), fout};
+  return gmm_dispatch<GmmFwdLauncher>(pick_group(fout), g, (const float*)hk, c, mu, inv_sigma, pm, out, st);
+}
+
+extern "C" gnn_status_t gnn_gmm_bwd(const gnn_graph_t* g, int fin, int fout, int k, const float* x,
+                                    const float* w_fc, const float* c, const float* mu,
+                                    const float* inv_sigma, const float* hk, const float* gout,
+                                    float* gx, float* gw_fc, float* gmu, float* ginv_sigma, void* ws,
+                                    size_t ws_bytes, void* stream) {
+  clear_error();
+  GNN_TRY(gmm_check(g, fin, fout, k, "gnn_gmm_bwd"));
+  if (g->n == 0) return GNN_OK;
+  GNN_REQUIRE(x && w_fc && c && mu && inv_sigma && hk && gout && gw_fc && gmu && ginv_sigma,
+              GNN_ERR_INVALID_ARG, "gnn_gmm_bwd: null pointer");
+  GNN_REQUIRE(aligned16(hk) && aligned16(gout), GNN_ERR_INVALID_ARG,
+              "gnn_gmm_bwd: hk, gout must be 16-byte aligned");
+  const GmmWs L = gmm_ws_layout(g->n, fin, fout, k);
+  GNN_REQUIRE(ws != nullptr && ws_bytes >= L.total, GNN_ERR_WORKSPACE,
+              "gnn_gmm_bwd: workspace of %zu bytes given, %zu needed", ws_bytes, L.total);
+  GNN_REQUIRE(aligned16(ws), GNN_ERR_INVALID_ARG, "gnn_gmm_bwd: workspace must be 16-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* base = static_cast<char*>(ws);
+  float* dhk = reinterpret_cast<float*>(base + L.dhk);
+  float* partial = reinterpret_cast<float*>(base + L.partial);
+  float* part = reinterpret_cast<float*>(base + L.gemm);
+  const int64_t n = g->n;
+  const int KF = k * fout;
+  GmmParams pm{k, ilog2(next_pow2(k)), fout};
+  const GroupShape gs = pick_group(fout);
+  GNN_TRY(gmm_dispatch<GmmBwdDstLauncher>(gs, g, hk, c, mu, inv_sigma, gout, pm, partial, gmu, ginv_sigma, st));
+  GNN_TRY(gmm_dispatch<GmmBwdSrcLauncher>(gs, g, c, mu, inv_sigma, gout, pm, dhk, st));
+  GNN_TRY(gemm_f32(fin, KF, n, x, fin, true, dhk, KF, false, gw_fc, KF, L.split_k, part, st));
+  if (gx) GNN_TRY(gemm_f32(n, fin, KF, dhk, KF, false, w_fc, KF, true, gx, fin, 1, nullptr, st));
+  return GNN_OK;
+}

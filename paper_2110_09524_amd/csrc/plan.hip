@@ -1,0 +1,282 @@
+// Graph plan: device-side validation of the CSR arrays, the CSC transpose
+// (stable radix sort by source), and the degree order / degree buckets of both
+// sides.  Integer work only; every table is a pure function of the input.
+#include <cstring>
+
+#include <rocprim/device/device_radix_sort.hpp>
+#include <rocprim/device/device_scan.hpp>
+
+#include "common.h"
+
+namespace gnn {
+
+__global__ void k_validate_indptr(int32_t n, int64_t nnz, const int32_t* __restrict__ indptr,
+                                  int* __restrict__ bad) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i > n) return;
+  int32_t a = indptr[i];
+  if (i == 0 && a != 0) atomicOr(bad, 1);
+  if (i == n && (int64_t)a != nnz) atomicOr(bad, 2);
+  if (i < n && indptr[i + 1] < a) atomicOr(bad, 4);
+  if (a < 0 || (int64_t)a > nnz) atomicOr(bad, 4);
+}
+
+__global__ void k_validate_indices_and_count(int32_t n, int64_t nnz,
+                                             const int32_t* __restrict__ indices,
+                                             int32_t* __restrict__ outdeg, int* __restrict__ bad) {
+  int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (e >= nnz) return;
+  int32_t u = indices[e];
+  if (u < 0 || u >= n) {
+    atomicOr(bad, 8);
+    return;
+  }
+  atomicAdd(&outdeg[u], 1);  // integer count: the result does not depend on the order
+}
+
+__global__ void k_iota(int64_t count, int32_t* __restrict__ out) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i < count) out[i] = (int32_t)i;
+}
+
+// indices_t[i] = destination row that contains CSR position eid_t[i]
+__global__ void k_dst_of_position(int32_t n, int64_t nnz, const int32_t* __restrict__ indptr,
+                                  const int32_t* __restrict__ eid_t, int32_t* __restrict__ indices_t) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i >= nnz) return;
+  int32_t p = eid_t[i];
+  // largest v with indptr[v] <= p (rows may be empty, so take the upper bound)
+  int32_t lo = 0, hi = n;  // invariant: indptr[lo] <= p < indptr[hi]
+  while (hi - lo > 1) {
+    int32_t mid = lo + ((hi - lo) >> 1);
+    if (indptr[mid] <= p) lo = mid; else hi = mid;
+  }
+  indices_t[i] = lo;
+}
+
+__global__ void k_degree_and_bucket(int32_t n, const int32_t* __restrict__ ptr,
+                                    uint32_t* __restrict__ deg, int32_t* __restrict__ bucket,
+                                    int32_t* __restrict__ hist) {
+  int64_t v = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (v >= n) return;
+  uint32_t d = (uint32_t)(ptr[v + 1] - ptr[v]);
+  int b = d == 0 ? 32 : __clz((int)d);
+  deg[v] = d;
+  bucket[v] = b;
+  atomicAdd(&hist[b], 1);
+}
+
+static void free_all(gnn_graph* g) {
+  if (!g) return;
+  (void)hipFree(g->indptr_t);
+  (void)hipFree(g->indices_t);
+  (void)hipFree(g->eid_t);
+  for (int s = 0; s < 2; ++s) {
+    (void)hipFree(g->bucket_of[s]);
+    (void)hipFree(g->order[s]);
+    (void)hipFree(g->bucket_offsets[s]);
+  }
+  delete g;
+}
+
+struct TempBuffers {
+  void* p[8] = {};
+  int count = 0;
+  ~TempBuffers() {
+    for (int i = 0; i < count; ++i) (void)hipFree(p[i]);
+  }
+  template <typename T>
+  hipError_t alloc(T** out, size_t elems) {
+    void* q = nullptr;
+    hipError_t e = hipMalloc(&q, elems ? elems * sizeof(T) : sizeof(T));
+    if (e == hipSuccess) p[count++] = q;
+    *out = static_cast<T*>(q);
+    return e;
+  }
+};
+
+static int bits_for(uint32_t max_value) {
+  int b = 1;
+  while (b < 32 && (max_value >> b) != 0) ++b;
+  return b;
+}
+
+static gnn_status_t build_side(gnn_graph* g, int side, const int32_t* ptr, hipStream_t st) {
+  const int32_t n = g->n;
+  const int thr = 256;
+  TempBuffers tmp;
+  uint32_t *deg = nullptr, *deg_sorted = nullptr;
+  int32_t *ids = nullptr, *hist = nullptr;
+  GNN_HIP(tmp.alloc(&deg, n));
+  GNN_HIP(tmp.alloc(&deg_sorted, n));
+  GNN_HIP(tmp.alloc(&ids, n));
+  GNN_HIP(tmp.alloc(&hist, GNN_NUM_BUCKETS));
+  GNN_HIP(hipMalloc((void**)&g->bucket_of[side], sizeof(int32_t) * (n ? n : 1)));
+  GNN_HIP(hipMalloc((void**)&g->order[side], sizeof(int32_t) * (n ? n : 1)));
+  GNN_HIP(hipMalloc((void**)&g->bucket_offsets[side], sizeof(int32_t) * (GNN_NUM_BUCKETS + 1)));
+  GNN_HIP(hipMemsetAsync(hist, 0, sizeof(int32_t) * GNN_NUM_BUCKETS, st));
+  int32_t h_hist[GNN_NUM_BUCKETS] = {};
+  uint32_t h_max = 0;
+  if (n > 0) {
+    k_degree_and_bucket<<<cdiv(n, thr), thr, 0, st>>>(n, ptr, deg, g->bucket_of[side], hist);
+    GNN_LAUNCH_CHECK();
+    k_iota<<<cdiv(n, thr), thr, 0, st>>>(n, ids);
+    GNN_LAUNCH_CHECK();
+    // stable descending sort by degree: ties keep ascending vertex id
+    size_t bytes = 0;
+    GNN_HIP(rocprim::radix_sort_pairs_desc(nullptr, bytes, deg, deg_sorted, ids, g->order[side],
+                                           (size_t)n, 0, 32, st));
+    void* scratch = nullptr;
+    GNN_HIP(tmp.alloc((char**)&scratch, bytes));
+    GNN_HIP(rocprim::radix_sort_pairs_desc(scratch, bytes, deg, deg_sorted, ids, g->order[side],
+                                           (size_t)n, 0, 32, st));
+    GNN_HIP(hipMemcpyAsync(h_hist, hist, sizeof(h_hist), hipMemcpyDeviceToHost, st));
+    GNN_HIP(hipMemcpyAsync(&h_max, deg_sorted, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    GNN_HIP(hipStreamSynchronize(st));
+  }
+  g->max_degree[side] = (int32_t)h_max;
+  g->h_bucket_offsets[side][0] = 0;
+  for (int b = 0; b < GNN_NUM_BUCKETS; ++b)
+    g->h_bucket_offsets[side][b + 1] = g->h_bucket_offsets[side][b] + h_hist[b];
+  GNN_HIP(hipMemcpyAsync(g->bucket_offsets[side], g->h_bucket_offsets[side],
+                         sizeof(int32_t) * (GNN_NUM_BUCKETS + 1), hipMemcpyHostToDevice, st));
+  GNN_HIP(hipStreamSynchronize(st));
+  return GNN_OK;
+}
+
+static gnn_status_t build(gnn_graph* g, hipStream_t st) {
+  const int32_t n = g->n;
+  const int64_t nnz = g->nnz;
+  const int thr = 256;
+  TempBuffers tmp;
+  int* bad = nullptr;
+  GNN_HIP(tmp.alloc(&bad, 1));
+  GNN_HIP(hipMemsetAsync(bad, 0, sizeof(int), st));
+
+  GNN_HIP(hipMalloc((void**)&g->indptr_t, sizeof(int32_t) * (size_t)(n + 1)));
+  GNN_HIP(hipMalloc((void**)&g->indices_t, sizeof(int32_t) * (size_t)(nnz ? nnz : 1)));
+  GNN_HIP(hipMalloc((void**)&g->eid_t, sizeof(int32_t) * (size_t)(nnz ? nnz : 1)));
+
+  int32_t* outdeg = nullptr;
+  GNN_HIP(tmp.alloc(&outdeg, (size_t)n + 1));
+  GNN_HIP(hipMemsetAsync(outdeg, 0, sizeof(int32_t) * ((size_t)n + 1), st));
+
+  k_validate_indptr<<<cdiv((int64_t)n + 1, thr), thr, 0, st>>>(n, nnz, g->indptr, bad);
+  GNN_LAUNCH_CHECK();
+  if (nnz > 0) {
+    k_validate_indices_and_count<<<cdiv(nnz, thr), thr, 0, st>>>(n, nnz, g->indices, outdeg, bad);
+    GNN_LAUNCH_CHECK();
+  }
+  int h_bad = 0;
+  GNN_HIP(hipMemcpyAsync(&h_bad, bad, sizeof(int), hipMemcpyDeviceToHost, st));
+  GNN_HIP(hipStreamSynchronize(st));
+  GNN_REQUIRE(h_bad == 0, GNN_ERR_BAD_GRAPH,
+              "gnn_graph_create: malformed CSR (%s%s%s%s)", (h_bad & 1) ? "indptr[0] != 0; " : "",
+              (h_bad & 2) ? "indptr[n] != nnz; " : "", (h_bad & 4) ? "indptr not monotone; " : "",
+              (h_bad & 8) ? "source id outside [0, n)" : "");
+
+  // indptr_t = exclusive prefix sum of the out-degrees (n+1 entries; the last input is 0)
+  {
+    size_t bytes = 0;
+    GNN_HIP(rocprim::exclusive_scan(nullptr, bytes, outdeg, g->indptr_t, (int32_t)0, (size_t)n + 1,
+                                    rocprim::plus<int32_t>(), st));
+    void* scratch = nullptr;
+    GNN_HIP(tmp.alloc((char**)&scratch, bytes));
+    GNN_HIP(rocprim::exclusive_scan(scratch, bytes, outdeg, g->indptr_t, (int32_t)0, (size_t)n + 1,
+                                    rocprim::plus<int32_t>(), st));
+  }
+  if (nnz > 0) {
+    // stable sort of (source, CSR position): positions stay ascending inside a source
+    uint32_t* keys_out = nullptr;
+    int32_t* pos = nullptr;
+    GNN_HIP(tmp.alloc(&keys_out, (size_t)nnz));
+    GNN_HIP(tmp.alloc(&pos, (size_t)nnz));
+    k_iota<<<cdiv(nnz, thr), thr, 0, st>>>(nnz, pos);
+    GNN_LAUNCH_CHECK();
+    const uint32_t* keys_in = reinterpret_cast<const uint32_t*>(g->indices);
+    const int end_bit = bits_for(n > 0 ? (uint32_t)(n - 1) : 0u);
+    size_t bytes = 0;
+    GNN_HIP(rocprim::radix_sort_pairs(nullptr, bytes, keys_in, keys_out, pos, g->eid_t, (size_t)nnz,
+                                      0, end_bit, st));
+    void* scratch = nullptr;
+    GNN_HIP(tmp.alloc((char**)&scratch, bytes));
+    GNN_HIP(rocprim::radix_sort_pairs(scratch, bytes, keys_in, keys_out, pos, g->eid_t, (size_t)nnz,
+                                      0, end_bit, st));
+    k_dst_of_position<<<cdiv(nnz, thr), thr, 0, st>>>(n, nnz, g->indptr, g->eid_t, g->indices_t);
+    GNN_LAUNCH_CHECK();
+  }
+  GNN_TRY(build_side(g, 0, g->indptr, st));
+  GNN_TRY(build_side(g, 1, g->indptr_t, st));
+  GNN_HIP(hipStreamSynchronize(st));
+  return GNN_OK;
+}
+
+}  // namespace gnn
+
+using namespace gnn;
+
+extern "C" gnn_status_t gnn_graph_create(int32_t n, int64_t nnz, const int32_t* indptr,
+                                         const int32_t* indices, void* stream, gnn_graph_t** graph) {
+  clear_error();
+  GNN_REQUIRE(graph != nullptr, GNN_ERR_INVALID_ARG, "gnn_graph_create: graph is null");
+  *graph = nullptr;
+  GNN_REQUIRE(n >= 0 && nnz >= 0, GNN_ERR_INVALID_ARG, "gnn_graph_create: negative size");
+  GNN_REQUIRE(nnz < (int64_t)INT32_MAX, GNN_ERR_UNSUPPORTED,
+              "gnn_graph_create: nnz = %lld does not fit 32-bit edge offsets", (long long)nnz);
+  GNN_REQUIRE(indptr != nullptr, GNN_ERR_INVALID_ARG, "gnn_graph_create: indptr is null");
+  GNN_REQUIRE(indices != nullptr || nnz == 0, GNN_ERR_INVALID_ARG,
+              "gnn_graph_create: indices is null");
+  gnn_graph* g = new gnn_graph();
+  g->n = n;
+  g->nnz = nnz;
+  g->indptr = indptr;
+  g->indices = indices;
+  gnn_status_t s = build(g, static_cast<hipStream_t>(stream));
+  if (s != GNN_OK) {
+    free_all(g);
+    return s;
+  }
+  *graph = g;
+  return GNN_OK;
+}
+
+extern "C" gnn_status_t gnn_graph_destroy(gnn_graph_t* graph) {
+  clear_error();
+  free_all(graph);
+  return GNN_OK;
+}
+
+extern "C" gnn_status_t gnn_graph_get_csc(const gnn_graph_t* g, int32_t* indptr_t, int32_t* indices_t,
+                                          int32_t* eid_t, void* stream) {
+  clear_error();
+  GNN_REQUIRE(g != nullptr, GNN_ERR_INVALID_ARG, "gnn_graph_get_csc: graph is null");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (indptr_t)
+    GNN_HIP(hipMemcpyAsync(indptr_t, g->indptr_t, sizeof(int32_t) * ((size_t)g->n + 1),
+                           hipMemcpyDeviceToDevice, st));
+  if (indices_t && g->nnz)
+    GNN_HIP(hipMemcpyAsync(indices_t, g->indices_t, sizeof(int32_t) * (size_t)g->nnz,
+                           hipMemcpyDeviceToDevice, st));
+  if (eid_t && g->nnz)
+    GNN_HIP(hipMemcpyAsync(eid_t, g->eid_t, sizeof(int32_t) * (size_t)g->nnz,
+                           hipMemcpyDeviceToDevice, st));
+  return GNN_OK;
+}
+
+extern "C" gnn_status_t gnn_graph_get_buckets(const gnn_graph_t* g, int side, int32_t* bucket_of_vertex,
+                                              int32_t* order, int32_t* bucket_offsets, void* stream) {
+  clear_error();
+  GNN_REQUIRE(g != nullptr, GNN_ERR_INVALID_ARG, "gnn_graph_get_buckets: graph is null");
+  GNN_REQUIRE(side == 0 || side == 1, GNN_ERR_INVALID_ARG, "gnn_graph_get_buckets: side must be 0 or 1");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (bucket_of_vertex && g->n)
+    GNN_HIP(hipMemcpyAsync(bucket_of_vertex, g->bucket_of[side], sizeof(int32_t) * (size_t)g->n,
+                           hipMemcpyDeviceToDevice, st));
+  if (order && g->n)
+    GNN_HIP(hipMemcpyAsync(order, g->order[side], sizeof(int32_t) * (size_t)g->n,
+                           hipMemcpyDeviceToDevice, st));
+  if (bucket_offsets)
+    GNN_HIP(hipMemcpyAsync(bucket_offsets, g->bucket_offsets[side],
+                           sizeof(int32_t) * (GNN_NUM_BUCKETS + 1), hipMemcpyDeviceToDevice, st));
+  return GNN_OK;
+}

@@ -1,0 +1,140 @@
+"""GAT layer: HIP path (through the C ABI) against the fp64 oracle, element by element."""
+import numpy as np
+import pytest
+
+from oracle import gat as og
+from helpers import random_graph, tiny_graph
+from workloads import make
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_all(c, backward=True):
+    fwd = og.gat_forward(c["indptr"], c["indices"], c["x"], c["w"], c["a_l"], c["a_r"], c["slope"])
+    bwd = None
+    if backward:
+        bwd = og.gat_backward(c["indptr"], c["indices"], c["x"], c["w"], c["a_l"], c["a_r"],
+                              c["slope"], c["gout"], fwd)
+    return fwd, bwd
+
+
+def compare(c, res, fwd, bwd):
+    from gpu_harness import assert_close
+    n, H, F = c["n"], c["heads"], c["f"]
+    Ht = fwd["Ht"].reshape(n, H * F)
+    assert_close("z", res["z"], Ht)
+    assert_close("el", res["el"], np.einsum("nhf,hf->nh", fwd["Ht"], c["a_l"].astype(np.float64)))
+    assert_close("er", res["er"], np.einsum("nhf,hf->nh", fwd["Ht"], c["a_r"].astype(np.float64)))
+    assert_close("m", res["m"], fwd["mx"])
+    assert_close("d", res["d"], fwd["den"])
+    assert_close("out", res["out"], fwd["out"])
+    if bwd is not None:
+        assert_close("gx", res["gx"], bwd["gx"])
+        assert_close("gw", res["gw"], bwd["gw"], reduce_scale=True)
+        assert_close("ga_l", res["ga_l"], bwd["ga_l"], reduce_scale=True)
+        assert_close("ga_r", res["ga_r"], bwd["ga_r"], reduce_scale=True)
+
+
+def synth(rng, indptr, indices, fin, H, F, slope=0.2):
+    n = len(indptr) - 1
+    return dict(n=n, nnz=len(indices), fin=fin, heads=H, f=F, slope=slope, indptr=indptr,
+                indices=indices,
+                x=rng.standard_normal((n, fin)).astype(np.float32),
+                # Glorot-scaled like the workloads: scores stay O(1)
+                w=(rng.standard_normal((fin, H * F)) * np.sqrt(2.0 / (fin + H * F))).astype(np.float32),
+                a_l=(rng.standard_normal((H, F)) * np.sqrt(2.0 / (F + 1))).astype(np.float32),
+                a_r=(rng.standard_normal((H, F)) * np.sqrt(2.0 / (F + 1))).astype(np.float32),
+                gout=rng.standard_normal((n, H * F)).astype(np.float32))
+
+
+def test_c1_forward():
+    from gpu_harness import run_gat
+    print("gat: gat_c1 forward", flush=True)
+    c = make("gat_c1")
+    fwd, _ = oracle_all(c, backward=False)
+    compare(c, run_gat(c, backward=False), fwd, None)
+
+
+@pytest.mark.parametrize("name", ["gat_c1", "gat_c2", "gat_c4_mid"])
+def test_workload_forward_backward(name):
+    from gpu_harness import run_gat
+    print("gat:", name, "fwd+bwd", flush=True)
+    c = make(name)
+    fwd, bwd = oracle_all(c)
+    compare(c, run_gat(c), fwd, bwd)
+
+
+@pytest.mark.parametrize("fin,H,F", [(7, 1, 4), (33, 3, 8), (5, 2, 12), (19, 5, 4), (64, 2, 64),
+                                     (40, 8, 64), (24, 3, 256), (130, 1, 16)])
+def test_shapes_heads_and_widths(fin, H, F):
+    from gpu_harness import run_gat
+    print(f"gat: shape fin={fin} H={H} F={F}", flush=True)
+    rng = np.random.default_rng(fin * 1000 + H * 10 + F)
+    indptr, indices = random_graph(rng, 257, 3000, self_loops=True, duplicates=True)
+    c = synth(rng, indptr, indices, fin, H, F)
+    fwd, bwd = oracle_all(c)
+    compare(c, run_gat(c), fwd, bwd)
+
+
+def test_empty_rows_isolated_vertices_and_hub():
+    from gpu_harness import run_gat
+    print("gat: empty rows + hub", flush=True)
+    rng = np.random.default_rng(5)
+    n = 700
+    # vertex 0 is a hub receiving from everyone (several chunks and a ragged tail),
+    # vertices 1..9 have no in-edges, vertex 10 sends to nobody, the rest is sparse
+    edges = [(u, 0) for u in range(n) if u != 10]
+    edges += [(int(rng.integers(0, n)), int(v)) for v in range(11, n) for _ in range(int(v) % 4)]
+    edges = [(u if u != 10 else 11, v) for (u, v) in edges]
+    indptr, indices = tiny_graph(n, edges)
+    c = synth(rng, indptr, indices, 20, 4, 16)
+    fwd, bwd = oracle_all(c)
+    res = run_gat(c)
+    compare(c, res, fwd, bwd)
+    assert (res["out"][1:10] == 0).all() and (res["m"][1:10] == 0).all() and (res["d"][1:10] == 1).all()
+
+
+def test_single_vertex_self_loop_and_skipped_input_gradient():
+    from gpu_harness import run_gat
+    print("gat: single vertex", flush=True)
+    rng = np.random.default_rng(6)
+    c = synth(rng, np.array([0, 1], dtype=np.int32), np.array([0], dtype=np.int32), 3, 2, 4)
+    fwd, bwd = oracle_all(c)
+    res = run_gat(c, want_gx=False)
+    res["gx"] = bwd["gx"]
+    compare(c, res, fwd, bwd)
+
+
+def test_results_are_bit_reproducible():
+    from gpu_harness import run_gat
+    print("gat: reproducibility", flush=True)
+    c = make("gat_c2")
+    a, b = run_gat(c), run_gat(c)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+
+
+def test_bad_arguments_raise():
+    import paper_2110_09524_amd as pk
+    import torch
+    from gpu_harness import dev, empty, workspace
+    print("gat: error paths", flush=True)
+    c = make("gat_c1")
+    g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
+    n = c["n"]
+    x, w = dev(c["x"]), dev(c["w"])
+    bufs = [empty((n, 16)) for _ in range(2)] + [empty((n, 1)) for _ in range(4)]
+    z, out, el, er, m, d = bufs
+    a6 = empty((1, 6))
+    with pytest.raises(pk.GnnError) as e:        # f = 6 is not a multiple of 4
+        pk.gnn_gat_fwd(g, 64, 1, 6, 0.2, x, w, a6, a6, z, el, er, m, d, out)
+    assert e.value.status == 4
+    a = dev(c["a_l"])
+    pk.gnn_gat_fwd(g, 64, 1, 16, 0.2, x, w, a, a, z, el, er, m, d, out)
+    need = pk.gnn_gat_workspace_bytes(g, 64, 1, 16)
+    assert need > 0
+    with pytest.raises(pk.GnnError) as e:        # workspace too small
+        pk.gnn_gat_bwd(g, 64, 1, 16, 0.2, x, w, a, a, z, el, er, m, d, out, dev(c["gout"]),
+                       None, empty((64, 16)), empty((1, 16)), empty((1, 16)), workspace(need - 256))
+    assert e.value.status == 3
+    torch.cuda.synchronize()

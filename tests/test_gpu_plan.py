@@ -1,0 +1,71 @@
+"""Plan tables from the HIP library, bit-exact against the brute-force oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import plan as oplan
+from helpers import random_graph, tiny_graph
+from workloads import make
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(indptr, indices):
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev
+    g = pk.Graph(dev(indptr), dev(indices))
+    ip_t, ix_t, eid_t = (t.cpu().numpy() for t in g.csc())
+    r_ip, r_ix, r_eid = oplan.csc_transpose(indptr, indices)
+    np.testing.assert_array_equal(ip_t, r_ip)
+    np.testing.assert_array_equal(ix_t, r_ix)
+    np.testing.assert_array_equal(eid_t, r_eid)
+    for side, ptr in ((0, indptr), (1, r_ip)):
+        b, o, off = (t.cpu().numpy() for t in g.buckets(side))
+        rb, ro, roff = oplan.degree_buckets(ptr)
+        np.testing.assert_array_equal(b, rb)
+        np.testing.assert_array_equal(o, ro)
+        np.testing.assert_array_equal(off, roff)
+    g.close()
+
+
+def test_tiny_graph_with_duplicates_and_empty_rows():
+    print("plan: tiny", flush=True)
+    _check(*tiny_graph(6, [(1, 0), (1, 0), (3, 0), (1, 2), (0, 2), (1, 2), (5, 5)]))
+
+
+def test_single_vertex_and_no_edges():
+    print("plan: degenerate", flush=True)
+    _check(np.array([0, 1], dtype=np.int32), np.array([0], dtype=np.int32))
+    _check(np.zeros(5, dtype=np.int32), np.zeros(0, dtype=np.int32))
+
+
+def test_random_multigraph():
+    print("plan: random multigraph", flush=True)
+    rng = np.random.default_rng(2)
+    _check(*random_graph(rng, 300, 5000, self_loops=False, duplicates=True))
+
+
+@pytest.mark.parametrize("name", ["gat_c1", "gat_c2", "ec_c3_mid"])
+def test_workload_graphs(name):
+    print("plan:", name, flush=True)
+    c = make(name)
+    _check(c["indptr"], c["indices"])
+
+
+def test_malformed_graphs_are_rejected():
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev
+    print("plan: malformed", flush=True)
+    good_ptr = np.array([0, 2, 3], dtype=np.int32)
+    with pytest.raises(pk.GnnError) as e:
+        pk.Graph(dev(good_ptr), dev(np.array([0, 1, 2], dtype=np.int32)))       # source id 2 >= n
+    assert e.value.status == 2
+    with pytest.raises(pk.GnnError) as e:
+        pk.Graph(dev(np.array([0, 3, 2], dtype=np.int32)), dev(np.array([0, 1], dtype=np.int32)))
+    assert e.value.status == 2
+    with pytest.raises(pk.GnnError) as e:
+        pk.Graph(dev(np.array([1, 2, 3], dtype=np.int32)), dev(np.array([0, 1, 1], dtype=np.int32)))
+    assert e.value.status == 2
+    with pytest.raises(pk.GnnError) as e:
+        pk.Graph(dev(good_ptr), dev(np.array([0, -1, 1], dtype=np.int32)))
+    assert e.value.status == 2
