@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused GAT layer, forward + recomputing backward, on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gat_c4]
+
+One "step" is one pass of the whole hot path over the synthetic graph: projection
+(MFMA), attention halves, fused score/softmax/aggregate, the two recomputing
+backward edge kernels, parameter gradients and the two backward products.  The
+graph plan (CSC transpose, degree order) is built once per graph before the timed
+region and its time is reported separately.  Inputs are resident in HBM when the
+timed region starts.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+FP32_VECTOR_TFLOPS = 157.3      # MI355X published fp32 vector peak
+
+
+def unique_bytes(n, e, fin, H, F):
+    """Minimal HBM traffic of each kernel: every array it touches, once."""
+    HF = H * F
+    V = 4 * n * HF          # one [n, HF] fp32 matrix
+    S = 4 * n * H           # one [n, H] fp32 matrix
+    I = 4 * e + 8 * n       # indices + indptr + degree order
+    return {
+        "gat_fwd_fused": I + V + 2 * S + V + 2 * S,                  # z, el, er -> out, m, d
+        "gat_bwd_dst": I + 3 * V + 4 * S + S + 4 * S,                # z, out, gout, el, er, m, d -> der, vstate
+        "gat_bwd_src": I + 3 * V + S + 4 * S + S + S,                # gout, z, dz, el, vstate, der -> del
+        "gemm_f32_mfma": 4 * n * fin + 4 * fin * HF + V,             # projection
+    }
+
+
+def gather_bytes(e, H, F):
+    """Per-edge gather model (no cache reuse): index + one feature row + per-head scalars."""
+    HF = H * F
+    return {
+        "gat_fwd_fused": e * (4 + 4 * HF + 4 * H),
+        "gat_bwd_dst": e * (4 + 4 * HF + 4 * H),
+        "gat_bwd_src": e * (4 + 4 * HF + 16 * H),
+    }
+
+
+def edge_flops(e, H, F):
+    return {
+        "gat_fwd_fused": e * H * (2 * F + 12),
+        "gat_bwd_dst": e * H * (2 * F + 14),
+        "gat_bwd_src": e * H * (4 * F + 16),
+    }
+
+
+def read_traffic(workload):
+    """HBM bytes per launch of the dominant kernel, as measured with rocprofv3 --pmc
+    (FETCH_SIZE, WRITE_SIZE) and written into profiles/<workload>_hbm_traffic.txt."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
+    vals = {}
+    try:
+        for line in open(path):
+            if ":" in line and not line.startswith("#"):
+                k, v = line.split(":", 1)
+                vals[k.strip()] = v.strip()
+    except OSError:
+        return None, None
+    return vals, path
+
+
+def cpu_baseline(c, budget_rows):
+    """The numpy oracle (as it stands) timed on a bounded sample of the same workload:
+    the full projection and backward products at N vertices, and the per-edge part on
+    the in-edges of `budget_rows` seeded destination rows, scaled to all E edges."""
+    import numpy as np
+    from oracle import gat as og
+    from oracle.segments import restrict_rows
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    n, e = c["n"], c["nnz"]
+    rng = np.random.default_rng(12345)
+    rows = np.sort(rng.choice(n, size=min(budget_rows, n), replace=False))
+    ip, ix, _ = restrict_rows(c["indptr"], c["indices"], rows)
+    e_s = int(ix.shape[0])
+    t0 = time.perf_counter()
+    fwd = og.gat_forward(ip, ix, c["x"], c["w"], c["a_l"], c["a_r"], c["slope"])
+    bwd = og.gat_backward(ip, ix, c["x"], c["w"], c["a_l"], c["a_r"], c["slope"], c["gout"], fwd)
+    t_sample = time.perf_counter() - t0
+    # the three dense products inside that time do not shrink with the sample: time them alone
+    X64, W64 = c["x"].astype(np.float64), c["w"].astype(np.float64)
+    t1 = time.perf_counter()
+    Z = X64 @ W64
+    _ = X64.T @ bwd["dHt"]
+    _ = bwd["dHt"] @ W64.T
+    t_dense = time.perf_counter() - t1
+    del Z, fwd, bwd
+    t_edges = max(t_sample - t_dense, 1e-9)
+    t_full = t_dense + t_edges * (e / max(e_s, 1))
+    return {
+        "value": e / t_full, "unit": "edges/s", "cores": int(threads), "kind": "oracle",
+        "sample": (f"fp64 numpy oracle fwd+bwd on the in-edges of {len(rows)} seeded destination rows "
+                   f"({e_s} of {e} edges) with all {n} vertices' dense products; measured {t_sample:.2f} s "
+                   f"of which {t_dense:.2f} s dense; per-edge part scaled by E/E_sample"),
+        "measured_s": t_sample,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="gat_c4")
+    ap.add_argument("--cpu-rows", type=int, default=256, help="destination rows of the CPU baseline sample")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2110_09524_amd as pk
+    from workloads import make
+
+    t0 = time.perf_counter()
+    c = make(args.workload)
+    t_gen = time.perf_counter() - t0
+    assert c["kind"] == "gat"
+    n, e, fin, H, F = c["n"], c["nnz"], c["fin"], c["heads"], c["f"]
+    HF = H * F
+    print(f"[bench] {args.workload}: N={n} E={e} fin={fin} heads={H} f={F} (generated in {t_gen:.1f} s)",
+          file=sys.stderr, flush=True)
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    indptr, indices = to(c["indptr"]), to(c["indices"])
+    x, w, a_l, a_r, gout = to(c["x"]), to(c["w"]), to(c["a_l"]), to(c["a_r"]), to(c["gout"])
+    z, out = torch.empty((n, HF), device=dev), torch.empty((n, HF), device=dev)
+    el, er, m, d = (torch.empty((n, H), device=dev) for _ in range(4))
+    gx, gw = torch.empty((n, fin), device=dev), torch.empty((fin, HF), device=dev)
+    ga_l, ga_r = torch.empty((H, F), device=dev), torch.empty((H, F), device=dev)
+
+    # a plain copy of known size, so a counter run of this script can be calibrated
+    cal_src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device=dev)
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
+    t0 = time.perf_counter()
+    g = pk.Graph(indptr, indices)
+    torch.cuda.synchronize()
+    t_plan = time.perf_counter() - t0
+    ws_bytes = pk.gnn_gat_workspace_bytes(g, fin, H, F)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+
+    def step():
+        pk.gnn_gat_fwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out)
+        pk.gnn_gat_bwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, gout,
+                       gx, gw, ga_l, ga_r, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t0
+    ms_per_step = 1e3 * t_total / args.steps
+    edges_per_s = e * args.steps / t_total
+
+    # per-kernel durations: HIP events recorded by the library on the launch stream
+    pk.gnn_prof_reset()
+    pk.gnn_prof_enable(True)
+    prof_steps = max(3, min(args.steps, 10))
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
+    rep = pk.gnn_prof_report()
+    pk.gnn_prof_enable(False)
+    kern = {k: {"avg_ms": ms / cnt, "launches_per_step": cnt / prof_steps} for k, (ms, cnt) in rep.items()}
+    ub, gb, fl = unique_bytes(n, e, fin, H, F), gather_bytes(e, H, F), edge_flops(e, H, F)
+    edge_kernels = [k for k in ("gat_fwd_fused", "gat_bwd_dst", "gat_bwd_src") if k in kern]
+    dom = max(edge_kernels, key=lambda k: kern[k]["avg_ms"])
+    t_dom = kern[dom]["avg_ms"] * 1e-3
+    achieved = ub[dom] / t_dom / 1e9
+    for k in edge_kernels:
+        t = kern[k]["avg_ms"] * 1e-3
+        kern[k].update(unique_GBps=ub[k] / t / 1e9, gather_model_GBps=gb[k] / t / 1e9,
+                       fp32_TFLOPs=fl[k] / t / 1e12)
+    if "gemm_f32_mfma" in kern:
+        # two plain products per step take this name (projection and gx); same flop count each
+        t = kern["gemm_f32_mfma"]["avg_ms"] * 1e-3
+        kern["gemm_f32_mfma"]["fp32_mfma_TFLOPs"] = 2.0 * n * fin * HF / t / 1e12
+
+    traffic_vals, traffic_path = read_traffic(args.workload)
+    traffic = None
+    if traffic_vals and traffic_vals.get("kernel") == dom:
+        traffic = float(traffic_vals["hbm_bytes_per_launch"])
+    roofline = {
+        "kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+        "algorithmic_bytes_per_launch": ub[dom], "avg_launch_ms": kern[dom]["avg_ms"],
+        "bytes_model": "minimal unique bytes: every array the kernel touches counted once",
+        "gather_model_GBps": kern[dom]["gather_model_GBps"],
+        "fp32_alu_frac": kern[dom]["fp32_TFLOPs"] / FP32_VECTOR_TFLOPS,
+    }
+
+    result = {
+        "metric": "fused GAT layer fwd+bwd edges/sec", "value": edges_per_s, "unit": "edges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "vertices": n, "edges": e, "in_feat": fin, "heads": H,
+                   "hidden_per_head": F, "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded",
+                   "plan_ms_once_per_graph": 1e3 * t_plan, "workspace_bytes": ws_bytes},
+        "roofline": roofline,
+        "kernels": kern,
+    }
+    if not args.no_cpu_baseline:
+        print("[bench] timing the CPU oracle on a bounded sample ...", file=sys.stderr, flush=True)
+        result["cpu_baseline"] = cpu_baseline(c, args.cpu_rows)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -94,6 +94,29 @@ gnn_status_t gnn_graph_get_buckets(const gnn_graph_t* graph, int side /*0 = dst 
                                    int32_t* bucket_of_vertex /*n*/, int32_t* order /*n*/,
                                    int32_t* bucket_offsets /*GNN_NUM_BUCKETS+1*/, void* stream);
 
+/* Column-blocked edge lists (built when n > block_cols; else num_blocks = 1 and
+ * nothing is copied).  A gathered feature matrix that exceeds the L2 caches is
+ * walked one block of `block_cols` gathered vertices at a time, so that the rows a
+ * launch gathers stay cache-resident.  For each side (0: rows = destinations,
+ * columns = sources; 1: rows = sources, columns = destinations) the edges are
+ * stable-sorted by (column / block_cols, row):
+ *   bcol[nnz]                 column (gathered vertex) of each edge in that order
+ *   bptr[num_blocks * n + 1]  bptr[b*n + r] .. bptr[b*n + r + 1] = edges of row r
+ *                             whose column lies in block b
+ * num_blocks and block_cols are written to HOST ints; bptr, bcol are device
+ * pointers (may be NULL). */
+gnn_status_t gnn_graph_get_blocked(const gnn_graph_t* graph, int side, int32_t* num_blocks /*host*/,
+                                   int32_t* block_cols /*host*/, int32_t* bptr, int32_t* bcol,
+                                   void* stream);
+
+/* Tuning knobs, read when a graph is created or a layer is called.  Keys:
+ *   "block_cols"            gathered vertices per column block (default 16384:
+ *                           16384 rows x one 128-byte slice per XCD = 2 MB of a
+ *                           4 MB L2); 0 disables blocking
+ *   "force_simple_kernels"  1: always use the single-launch kernels
+ * Errors: INVALID_ARG for an unknown key or a value out of range. */
+gnn_status_t gnn_config_set(const char* key, int64_t value);
+
 /* ------------------------------------------------------------------------- *
  * Projection: the ExpensiveApply on vertices, y = x w  (Sec. 3, Sec. 4; App. A.2
  * "H~ = H W").  x [n, fin], w [fin, fout], y [n, fout]; any positive sizes.

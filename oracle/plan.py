@@ -49,3 +49,20 @@ def degree_buckets(indptr_side):
     for b in range(NUM_BUCKETS):
         offsets[b + 1] = offsets[b] + int((bucket == b).sum())
     return bucket, order, offsets
+
+
+def blocked_edges(ptr, cols, block_cols):
+    """Column-blocked edge list of one side: edges stable-sorted by
+    (column // block_cols, row); returns (num_blocks, bptr[num_blocks*n + 1], bcol[nnz])."""
+    n = ptr.shape[0] - 1
+    nblk = -(-n // block_cols)
+    triples = []
+    for r in range(n):
+        for pos in range(int(ptr[r]), int(ptr[r + 1])):
+            triples.append((int(cols[pos]) // block_cols, r, pos))
+    triples.sort()
+    bcol = np.array([int(cols[p]) for _, _, p in triples], dtype=np.int32).reshape(-1)
+    bptr = np.zeros(nblk * n + 1, dtype=np.int64)
+    for b, r, _ in triples:
+        bptr[b * n + r + 1] += 1
+    return nblk, np.cumsum(bptr).astype(np.int32), bcol

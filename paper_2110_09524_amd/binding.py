@@ -13,7 +13,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libgnnfused.so")
+LIB_PATH = os.environ.get("GNNFUSED_LIB") or os.path.join(_HERE, "libgnnfused.so")
 
 GNN_NUM_BUCKETS = 33
 STATUS_NAMES = {0: "GNN_OK", 1: "GNN_ERR_INVALID_ARG", 2: "GNN_ERR_BAD_GRAPH",
@@ -21,7 +21,7 @@ STATUS_NAMES = {0: "GNN_OK", 1: "GNN_ERR_INVALID_ARG", 2: "GNN_ERR_BAD_GRAPH",
 
 EXPORTS = [
     "gnn_last_error", "gnn_graph_create", "gnn_graph_destroy", "gnn_graph_get_csc",
-    "gnn_graph_get_buckets", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
+    "gnn_graph_get_buckets", "gnn_graph_get_blocked", "gnn_config_set", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
     "gnn_gat_bwd", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
     "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd", "gnn_prof_enable",
     "gnn_prof_collect", "gnn_prof_reset", "gnn_prof_count", "gnn_prof_get",
@@ -47,6 +47,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_graph_destroy.argtypes = [vp]
     lib.gnn_graph_get_csc.argtypes = [vp, vp, vp, vp, vp]
     lib.gnn_graph_get_buckets.argtypes = [vp, i32, vp, vp, vp, vp]
+    lib.gnn_graph_get_blocked.argtypes = [vp, i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), vp, vp, vp]
+    lib.gnn_config_set.argtypes = [C.c_char_p, i64]
     lib.gnn_linear_fwd.argtypes = [i64, i32, i32, vp, vp, vp, vp]
     lib.gnn_gat_workspace_bytes.restype = sz
     lib.gnn_gat_workspace_bytes.argtypes = [vp, i32, i32, i32]
@@ -150,12 +152,29 @@ class Graph:
         _check(lib().gnn_graph_get_csc(self._h, _i(ip), _i(ix), _i(eid), _stream(stream)))
         return ip, ix, eid
 
+    def blocked(self, side: int, stream=None):
+        """(num_blocks, block_cols, bptr, bcol); the tensors are None when num_blocks == 1."""
+        nb, bc = C.c_int32(), C.c_int32()
+        _check(lib().gnn_graph_get_blocked(self._h, side, C.byref(nb), C.byref(bc), None, None,
+                                           _stream(stream)))
+        if nb.value <= 1:
+            return nb.value, bc.value, None, None
+        bptr = torch.empty(nb.value * self.n + 1, dtype=torch.int32, device=self.device)
+        bcol = torch.empty(self.nnz, dtype=torch.int32, device=self.device)
+        _check(lib().gnn_graph_get_blocked(self._h, side, C.byref(nb), C.byref(bc), _i(bptr), _i(bcol),
+                                           _stream(stream)))
+        return nb.value, bc.value, bptr, bcol
+
     def buckets(self, side: int, stream=None):
         b = torch.empty(self.n, dtype=torch.int32, device=self.device)
         o = torch.empty(self.n, dtype=torch.int32, device=self.device)
         off = torch.empty(GNN_NUM_BUCKETS + 1, dtype=torch.int32, device=self.device)
         _check(lib().gnn_graph_get_buckets(self._h, side, _i(b), _i(o), _i(off), _stream(stream)))
         return b, o, off
+
+
+def gnn_config_set(key: str, value: int):
+    _check(lib().gnn_config_set(key.encode(), int(value)))
 
 
 def gnn_linear_fwd(x, w, y, stream=None):

@@ -76,6 +76,10 @@ struct Workspace {
 };
 inline size_t ws_granule(size_t bytes) { return align_up(bytes, 256); }
 
+// ---- tuning knobs (runtime.hip) -------------------------------------------------
+enum ConfigKey { kCfgBlockCols = 0, kCfgForceSimple = 1, kCfgCount };
+int64_t config_get(ConfigKey k);
+
 // ---- dense products (gemm.hip) ------------------------------------------------
 // c[M,N] = op(a) op(b), fp32 MFMA.  a_kmajor: a is stored [K,M] (m contiguous)
 // instead of [M,K]; b_kcontig: b is stored [N,K] (k contiguous) instead of [K,N].
@@ -102,4 +106,9 @@ struct gnn_graph {
   int32_t* bucket_offsets[2];            // device copies
   int32_t h_bucket_offsets[2][GNN_NUM_BUCKETS + 1];  // host copies
   int32_t max_degree[2];
+  // column-blocked edge lists (present when nblk > 1)
+  int32_t block_cols;
+  int32_t nblk;
+  int32_t* bptr[2];
+  int32_t* bcol[2];
 };

@@ -17,11 +17,16 @@
 // the destination-side kernel walks the CSR, the source-side kernel walks the
 // CSC transpose (no atomics), and alpha_e is recomputed from el, er, m, d.
 #include "common.h"
+#include "gat_common.h"
 #include "rowgroup.h"
 
 namespace gnn {
 
 constexpr int kBlock = 256;  // 4 wavefronts
+#ifndef GNN_GAT_UNROLL
+#define GNN_GAT_UNROLL 4
+#endif
+constexpr int kU = GNN_GAT_UNROLL;  // gathered rows in flight per lane
 
 // ---- a2: attention halves  el = <z, a_l>, er = <z, a_r> per (vertex, head) -----
 __global__ void k_gat_attn_halves(int64_t n, int H, int F, const float* __restrict__ z,
@@ -43,13 +48,6 @@ __global__ void k_gat_attn_halves(int64_t n, int H, int F, const float* __restri
   er[i] = sr;
 }
 
-struct GatDims {
-  int H, F, HF;
-  int log2Hp;  // heads padded to a power of two; lanes of a group = (edge, head) pairs
-  float slope;
-};
-
-__device__ __forceinline__ float leaky(float x, float slope) { return x > 0.f ? x : slope * x; }
 
 // LDS layout per group: idx[L] | p[L] | p2[L] | misc[L] | red[2*L*NV]
 template <int L, int NV>
@@ -124,21 +122,21 @@ __global__ __launch_bounds__(kBlock) void k_gat_fwd(
     for (int j = 0; j < NV; ++j) part[j] = make_float4(0.f, 0.f, 0.f, 0.f);
     const int cnt = min(epc, end - c0);
     int t = 0;
-    for (; t + 4 <= cnt; t += 4) {
-      int uu[4];
-      float4 row[4][NV];
+    for (; t + kU <= cnt; t += kU) {
+      int uu[kU];
+      float4 row[kU][NV];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
+      for (int q = 0; q < kU; ++q) {
         uu[q] = l_idx[t + q];
         if (L == 64) uu[q] = __builtin_amdgcn_readfirstlane(uu[q]);
       }
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
+      for (int q = 0; q < kU; ++q)
 #pragma unroll
         for (int j = 0; j < NV; ++j)
           if (slot_ok[j]) row[q][j] = ld4(z + (int64_t)uu[q] * HF + 4 * (li + j * L));
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
+      for (int q = 0; q < kU; ++q)
 #pragma unroll
         for (int j = 0; j < NV; ++j)
           if (slot_ok[j]) fma4(part[j], l_p[((t + q) << dm.log2Hp) + hs[j]], row[q][j]);
@@ -255,21 +253,21 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_dst(
     for (int j = 0; j < NV; ++j) part[j] = make_float4(0.f, 0.f, 0.f, 0.f);
     const int cnt = min(epc, end - c0);
     int t = 0;
-    for (; t + 4 <= cnt; t += 4) {
-      int uu[4];
-      float4 row[4][NV];
+    for (; t + kU <= cnt; t += kU) {
+      int uu[kU];
+      float4 row[kU][NV];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
+      for (int k = 0; k < kU; ++k) {
         uu[k] = l_idx[t + k];
         if (L == 64) uu[k] = __builtin_amdgcn_readfirstlane(uu[k]);
       }
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
+      for (int k = 0; k < kU; ++k)
 #pragma unroll
         for (int j = 0; j < NV; ++j)
           if (slot_ok[j]) row[k][j] = ld4(z + (int64_t)uu[k] * HF + 4 * (li + j * L));
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
+      for (int k = 0; k < kU; ++k)
 #pragma unroll
         for (int j = 0; j < NV; ++j)
           if (slot_ok[j]) fma4(part[j], l_p[((t + k) << dm.log2Hp) + hs[j]], row[k][j]);
@@ -383,21 +381,21 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
     }
     const int cnt = min(epc, end - c0);
     int t = 0;
-    for (; t + 4 <= cnt; t += 4) {
-      int vv[4];
-      float4 row[4][NV];
+    for (; t + kU <= cnt; t += kU) {
+      int vv[kU];
+      float4 row[kU][NV];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
+      for (int k = 0; k < kU; ++k) {
         vv[k] = l_idx[t + k];
         if (L == 64) vv[k] = __builtin_amdgcn_readfirstlane(vv[k]);
       }
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
+      for (int k = 0; k < kU; ++k)
 #pragma unroll
         for (int j = 0; j < NV; ++j)
           if (slot_ok[j]) row[k][j] = ld4(gout + (int64_t)vv[k] * HF + 4 * (li + j * L));
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
+      for (int k = 0; k < kU; ++k)
 #pragma unroll
         for (int j = 0; j < NV; ++j)
           if (slot_ok[j]) {
@@ -501,11 +499,12 @@ static int param_blocks(int64_t n) {
 
 struct GatWs {
   size_t total;
-  size_t dz, vstate, der, del, partial, gemm;
+  size_t dz, vstate, der, del, partial, gemm, blk_rows, blk_scal;
   int split_k, nblk;
 };
 
-static GatWs gat_ws_layout(int64_t n, int fin, int H, int F) {
+static GatWs gat_ws_layout(const gnn_graph_t* g, int fin, int H, int F) {
+  const int64_t n = g->n;
   GatWs w{};
   const int HF = H * F;
   size_t off = 0;
@@ -518,6 +517,9 @@ static GatWs gat_ws_layout(int64_t n, int fin, int H, int F) {
   w.partial = take(sizeof(float) * 2 * (size_t)w.nblk * HF);
   w.split_k = gemm_pick_split_k(fin, HF, n);
   w.gemm = take(w.split_k > 1 ? sizeof(float) * (size_t)w.split_k * fin * HF : 0);
+  const bool blocked = gat_blocked_applies(g, H, F);
+  w.blk_rows = take(blocked ? sizeof(float) * n * HF : 0);  // T, then A2
+  w.blk_scal = take(blocked ? sizeof(float) * n * H : 0);   // sg, then sd
   w.total = off;
   return w;
 }
@@ -594,15 +596,6 @@ struct BwdSrcLauncher {
   }
 };
 
-static GatDims make_dims(int H, int F, float slope) {
-  GatDims dm;
-  dm.H = H;
-  dm.F = F;
-  dm.HF = H * F;
-  dm.log2Hp = ilog2(next_pow2(H));
-  dm.slope = slope;
-  return dm;
-}
 
 }  // namespace gnn
 
@@ -610,7 +603,7 @@ using namespace gnn;
 
 extern "C" size_t gnn_gat_workspace_bytes(const gnn_graph_t* g, int fin, int heads, int f) {
   if (!g || fin <= 0 || heads <= 0 || f <= 0) return 0;
-  return gat_ws_layout(g->n, fin, heads, f).total;
+  return gat_ws_layout(g, fin, heads, f).total;
 }
 
 extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, int f, float slope,
@@ -638,6 +631,8 @@ extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, in
     GNN_LAUNCH_CHECK();
   }
   // a3: fused score -> softmax -> aggregate
+  if (gat_blocked_applies(g, heads, f))
+    return gat_blocked_fwd(g, make_dims(heads, f, slope), z, el, er, m, d, out, st);
   return dispatch_group<FwdLauncher>(pick_group(HF), g, (const float*)z, (const float*)el,
                                      (const float*)er, make_dims(heads, f, slope), out, m, d, st);
 }
@@ -657,7 +652,7 @@ extern "C" gnn_status_t gnn_gat_bwd(const gnn_graph_t* g, int fin, int heads, in
               GNN_ERR_INVALID_ARG, "gnn_gat_bwd: z, out, gout, a_l, a_r must be 16-byte aligned");
   const int64_t n = g->n;
   const int HF = heads * f;
-  const GatWs L = gat_ws_layout(n, fin, heads, f);
+  const GatWs L = gat_ws_layout(g, fin, heads, f);
   GNN_REQUIRE(ws != nullptr && ws_bytes >= L.total, GNN_ERR_WORKSPACE,
               "gnn_gat_bwd: workspace of %zu bytes given, %zu needed", ws_bytes, L.total);
   GNN_REQUIRE(aligned16(ws), GNN_ERR_INVALID_ARG, "gnn_gat_bwd: workspace must be 16-byte aligned");
@@ -672,11 +667,19 @@ extern "C" gnn_status_t gnn_gat_bwd(const gnn_graph_t* g, int fin, int heads, in
   const GatDims dm = make_dims(heads, f, slope);
   const GroupShape gs = pick_group(HF);
 
-  // a4: destination side
-  GNN_TRY(dispatch_group<BwdDstLauncher>(gs, g, z, el, er, m, d, out, gout, dm, der, vstate, st));
-  // a5: source side
-  GNN_TRY(dispatch_group<BwdSrcLauncher>(gs, g, z, el, (const float4*)vstate, (const float*)der, gout,
-                                         a_l, a_r, dm, dz, del, st));
+  if (gat_blocked_applies(g, heads, f)) {
+    float* rows_buf = reinterpret_cast<float*>(base + L.blk_rows);
+    float* scal_buf = reinterpret_cast<float*>(base + L.blk_scal);
+    GNN_TRY(gat_blocked_bwd_dst(g, dm, z, el, er, m, d, out, gout, der, vstate, rows_buf, scal_buf, st));
+    GNN_TRY(gat_blocked_bwd_src(g, dm, z, el, vstate, der, gout, a_l, a_r, dz, del, rows_buf,
+                                scal_buf, st));
+  } else {
+    // a4: destination side
+    GNN_TRY(dispatch_group<BwdDstLauncher>(gs, g, z, el, er, m, d, out, gout, dm, der, vstate, st));
+    // a5: source side
+    GNN_TRY(dispatch_group<BwdSrcLauncher>(gs, g, z, el, (const float4*)vstate, (const float*)der,
+                                           gout, a_l, a_r, dm, dz, del, st));
+  }
   // a6: parameter gradients
   {
     ProfScope p("gat_param_grad", st);

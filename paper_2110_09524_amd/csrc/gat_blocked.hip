@@ -1,0 +1,329 @@
+// Column-blocked, XCD-sliced variants of the three GAT edge kernels, for graphs whose
+// projected feature matrix does not fit the L2 caches.
+//
+// The single-launch kernels gather one full row (heads*f floats) per edge from
+// anywhere in a matrix of hundreds of MB; on MI355X each of the 8 XCDs has its own
+// 4 MB L2, so nearly every gather misses and the kernels run at the speed of the
+// fabric behind the L2s.  Here the same sums are re-associated so that what a
+// launch gathers is cache-resident:
+//   * columns are cut into 8 slices, workgroup id mod 8 picks the slice; workgroups
+//     are handed to the XCDs round-robin, so XCD k only ever touches slice k of a row;
+//   * the gathered vertices are cut into blocks of `block_cols`; launch b walks only
+//     the edges whose gathered vertex lies in block b (plan tables bptr/bcol), so one
+//     launch touches block_cols * slice_bytes per XCD (2 MB by default);
+//   * per-row partial sums live in an [n, heads*f] buffer that every launch after the
+//     first reads, adds to and writes back (launches on one stream run in order, so
+//     there is no race and the summation order is fixed).
+// The edge-softmax needs the row maximum and denominator before any block can be
+// weighted, so the forward pass first computes m and d in a light pass that gathers
+// only the per-head scalars el[u] (Sec. 6: exactly the O(|V|) state that is saved).
+// All per-edge values are still recomputed on the fly; nothing per-edge is stored.
+#include "common.h"
+#include "gat_common.h"
+#include "rowgroup.h"
+
+namespace gnn {
+
+constexpr int kBlkThreads = 256;
+constexpr int kSlices = 8;  // one column slice per XCD
+
+// ---- softmax statistics: m = max_e s_e, d = sum_e exp(s_e - m) per (vertex, head) ----
+// one wavefront per destination; lanes = (edge, head) pairs; every lane keeps a running
+// (max, sum) over its own edges, merged across lanes at the end
+__global__ __launch_bounds__(kBlkThreads) void k_gat_softmax_stats(
+    int32_t n_rows, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    const int32_t* __restrict__ indices, const float* __restrict__ el, const float* __restrict__ er,
+    GatDims dm, float* __restrict__ m_out, float* __restrict__ d_out) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * (kBlkThreads / kWave) + (threadIdx.x >> 6);
+  if (r >= n_rows) return;
+  const int H = dm.H;
+  const int Hp = 1 << dm.log2Hp;
+  const int epc = kWave >> dm.log2Hp;
+  const int e_loc = lane >> dm.log2Hp;
+  const int h = lane & (Hp - 1);
+  const bool head_ok = h < H;
+  const int32_t v = order[r];
+  const int32_t beg = indptr[v], end = indptr[v + 1];
+  const float er_vh = head_ok ? er[(int64_t)v * H + h] : 0.f;
+  float m_run = -INFINITY, d_run = 0.f;
+  for (int32_t c0 = beg; c0 < end; c0 += epc) {
+    const int32_t e = c0 + e_loc;
+    if (e < end && head_ok) {
+      const int32_t u = indices[e];
+      const float s = leaky(el[(int64_t)u * H + h] + er_vh, dm.slope);
+      const float m_new = fmaxf(m_run, s);
+      d_run = d_run * __expf(m_run - m_new) + __expf(s - m_new);  // exp(-inf) = 0 on the first edge
+      m_run = m_new;
+    }
+  }
+  // merge lanes that share a head: (m1,d1)+(m2,d2) = (M, d1 e^(m1-M) + d2 e^(m2-M))
+  for (int off = Hp; off < kWave; off <<= 1) {
+    const float m2 = __shfl_xor(m_run, off, 64);
+    const float d2 = __shfl_xor(d_run, off, 64);
+    const float M = fmaxf(m_run, m2);
+    const float a = (m_run == -INFINITY) ? 0.f : d_run * __expf(m_run - M);
+    const float b = (m2 == -INFINITY) ? 0.f : d2 * __expf(m2 - M);
+    d_run = a + b;
+    m_run = M;
+  }
+  if (e_loc == 0 && head_ok) {
+    const bool empty = beg == end;
+    m_out[(int64_t)v * H + h] = empty ? 0.f : m_run;
+    d_out[(int64_t)v * H + h] = empty ? 1.f : d_run;
+  }
+}
+
+// ---- one column block of a weighted row aggregation ---------------------------------
+// MODE 0: forward        acc[v]  += sum_e alpha_e           z[u]      (acc = out)
+// MODE 1: bwd, dst side  acc[v]  += sum_e alpha_e g_e       z[u]      (acc = T), sg += sum alpha g
+// MODE 2: bwd, src side  acc[u]  += sum_e alpha_e           gout[v]   (acc = dz)
+//                        acc2[u] += sum_e alpha_e g_e       gout[v]   (acc2 = A2), sd += sum alpha g D[v]
+// A group of SL lanes owns (row, slice); lane li owns the float4 at column slice*4*SL + 4*li.
+template <int SL, int MODE>
+__global__ __launch_bounds__(kBlkThreads) void k_gat_blk(
+    int32_t n_rows, const int32_t* __restrict__ order, const int32_t* __restrict__ bptr_b,
+    const int32_t* __restrict__ bcol, const float* __restrict__ feat /* gathered rows: z or gout */,
+    const float* __restrict__ el, const float* __restrict__ er, const float* __restrict__ m_in,
+    const float* __restrict__ d_in, const float4* __restrict__ vstate, GatDims dm, int sph,
+    int first, float* __restrict__ acc_buf, float* __restrict__ acc2_buf, float* __restrict__ scal_buf) {
+  constexpr int G = kWave / SL;
+  constexpr int GPB = G * (kBlkThreads / kWave);
+  constexpr int U = SL < 8 ? SL : 8;  // gathered rows in flight per lane
+  __shared__ float lds[GPB * 3 * SL];
+
+  const int lane = threadIdx.x & 63;
+  const int li = lane & (SL - 1);
+  const int grp = threadIdx.x / SL;
+  const int slice = blockIdx.x % kSlices;
+  const int64_t r = (int64_t)(blockIdx.x / kSlices) * GPB + grp;
+  if (r >= n_rows) return;
+  const int32_t row = order[r];
+  const int32_t beg = bptr_b[row], end = bptr_b[row + 1];
+  if (beg == end && !first) return;  // nothing to add to this row in this block
+
+  int* l_idx = reinterpret_cast<int*>(lds + grp * 3 * SL);
+  float* l_p = lds + grp * 3 * SL + SL;
+  float* l_p2 = lds + grp * 3 * SL + 2 * SL;
+
+  const int H = dm.H, HF = dm.HF;
+  const int h = slice / sph;
+  const int col = slice * 4 * SL + 4 * li;
+  const bool leader = (slice % sph) == 0;  // one slice per head keeps the per-head scalars
+  const int64_t rh = (int64_t)row * H + h;
+
+  // per-row scalars of this head
+  float r_a = 0.f, r_m = 0.f, r_invd = 1.f;
+  if (MODE == 2) {
+    r_a = el[rh];  // row is a source: its el
+  } else {
+    r_a = er[rh];  // row is a destination: its er, max, 1/denominator
+    r_m = m_in[rh];
+    r_invd = 1.f / d_in[rh];
+  }
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f), acc2 = acc;
+  float scal = 0.f;
+  if (!first) {
+    acc = ld4(acc_buf + (int64_t)row * HF + col);
+    if (MODE == 2) acc2 = ld4(acc2_buf + (int64_t)row * HF + col);
+    if (MODE != 0 && leader && li == 0) scal = scal_buf[rh];
+  }
+
+  float s_run = 0.f;
+  int32_t c_next = (beg + li < end) ? bcol[beg + li] : 0;
+  for (int32_t c0 = beg; c0 < end; c0 += SL) {
+    const int32_t c = c_next;  // gathered vertex of edge c0 + li
+    const bool e_ok = c0 + li < end;
+    if (c0 + SL + li < end) c_next = bcol[c0 + SL + li];
+    l_idx[li] = c;
+    // per-edge scalars: issue the loads now, use them after the row loads are in flight
+    float e_a = 0.f;
+    float4 vs = make_float4(0.f, 0.f, 1.f, 0.f);
+    if (e_ok) {
+      if (MODE == 2) vs = vstate[(int64_t)c * H + h];  // (er, m, 1/d, D) of the destination
+      else e_a = el[(int64_t)c * H + h];
+    }
+    wave_lds_fence();
+    const int cnt = min(SL, end - c0);
+    float4 part = make_float4(0.f, 0.f, 0.f, 0.f), part2 = part;
+#pragma unroll
+    for (int t0 = 0; t0 < SL; t0 += U) {
+      float4 rowv[U];
+#pragma unroll
+      for (int t = 0; t < U; ++t)
+        if (t0 + t < cnt) rowv[t] = ld4(feat + (int64_t)l_idx[t0 + t] * HF + col);
+      if (t0 == 0) {
+        float p = 0.f, p2 = 0.f;
+        if (e_ok) {
+          if (MODE == 2) {
+            const float raw = r_a + vs.x;
+            p = __expf(leaky(raw, dm.slope) - vs.y) * vs.z;
+            p2 = raw > 0.f ? p : dm.slope * p;
+            s_run = fmaf(p2, vs.w, s_run);
+          } else {
+            const float raw = e_a + r_a;
+            p = __expf(leaky(raw, dm.slope) - r_m) * r_invd;
+            if (MODE == 1) {
+              p = raw > 0.f ? p : dm.slope * p;
+              s_run += p;
+            }
+          }
+        }
+        l_p[li] = p;
+        if (MODE == 2) l_p2[li] = p2;
+        wave_lds_fence();
+      }
+#pragma unroll
+      for (int t = 0; t < U; ++t)
+        if (t0 + t < cnt) {
+          fma4(part, l_p[t0 + t], rowv[t]);
+          if (MODE == 2) fma4(part2, l_p2[t0 + t], rowv[t]);
+        }
+    }
+    add4(acc, part);
+    if (MODE == 2) add4(acc2, part2);
+    wave_lds_fence();
+  }
+  st4(acc_buf + (int64_t)row * HF + col, acc);
+  if (MODE == 2) st4(acc2_buf + (int64_t)row * HF + col, acc2);
+  if (MODE != 0 && leader) {
+    const float tot = group_sum_from<SL>(s_run, 1);
+    if (li == 0) scal_buf[rh] = scal + tot;
+  }
+}
+
+// der[v,h] = <gout[v,h,:], T[v,h,:]> - D[v,h] sg[v,h],  D = <gout[v,h,:], out[v,h,:]>,
+// vstate[v,h] = (er, m, 1/d, D)
+__global__ void k_gat_blk_dst_finish(int64_t n, int H, int F, const float* __restrict__ gout,
+                                     const float* __restrict__ t_buf, const float* __restrict__ out,
+                                     const float* __restrict__ sg, const float* __restrict__ er,
+                                     const float* __restrict__ m_in, const float* __restrict__ d_in,
+                                     float* __restrict__ der, float4* __restrict__ vstate) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;  // (vertex, head)
+  if (i >= n * H) return;
+  const float* g = gout + i * F;
+  const float* t = t_buf + i * F;
+  const float* o = out + i * F;
+  float t1 = 0.f, D = 0.f;
+  for (int f = 0; f < F; f += 4) {
+    const float4 g4 = ld4(g + f);
+    t1 += dot4(g4, ld4(t + f));
+    D += dot4(g4, ld4(o + f));
+  }
+  der[i] = t1 - D * sg[i];
+  vstate[i] = make_float4(er[i], m_in[i], 1.f / d_in[i], D);
+}
+
+// del[u,h] = <z[u,h,:], A2[u,h,:]> - sd[u,h];  dz[u,h,:] += a_l[h,:] del[u,h] + a_r[h,:] der[u,h]
+__global__ void k_gat_blk_src_finish(int64_t n, int H, int F, const float* __restrict__ z,
+                                     const float* __restrict__ a2, const float* __restrict__ sd,
+                                     const float* __restrict__ der, const float* __restrict__ a_l,
+                                     const float* __restrict__ a_r, float* __restrict__ dz,
+                                     float* __restrict__ del) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;  // (vertex, head)
+  if (i >= n * H) return;
+  const int h = (int)(i % H);
+  const float* zz = z + i * F;
+  const float* aa = a2 + i * F;
+  float s = 0.f;
+  for (int f = 0; f < F; f += 4) s += dot4(ld4(zz + f), ld4(aa + f));
+  const float dl = s - sd[i];
+  const float dr = der[i];
+  del[i] = dl;
+  float* o = dz + i * F;
+  const float* al = a_l + (int64_t)h * F;
+  const float* ar = a_r + (int64_t)h * F;
+  for (int f = 0; f < F; f += 4) {
+    float4 v4 = ld4(o + f);
+    fma4(v4, dl, ld4(al + f));
+    fma4(v4, dr, ld4(ar + f));
+    st4(o + f, v4);
+  }
+}
+
+// ---- host side -------------------------------------------------------------------------
+bool gat_blocked_applies(const gnn_graph_t* g, int heads, int f) {
+  if (g->nblk <= 1 || config_get(kCfgForceSimple)) return false;
+  const int HF = heads * f;
+  if (HF % (4 * kSlices) != 0) return false;
+  const int SL = HF / (4 * kSlices);
+  if (!(SL == 4 || SL == 8 || SL == 16 || SL == 32)) return false;
+  if (kSlices % heads != 0) return false;  // every slice lies inside one head
+  return true;
+}
+
+size_t gat_blocked_ws_bytes(const gnn_graph_t* g, int heads, int f) {
+  if (!gat_blocked_applies(g, heads, f)) return 0;
+  return ws_granule(sizeof(float) * (size_t)g->n * heads * f) +
+         ws_granule(sizeof(float) * (size_t)g->n * heads);
+}
+
+template <int MODE>
+static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name, GatDims dm,
+                               const float* feat, const float* el, const float* er, const float* m,
+                               const float* d, const float4* vstate, float* acc, float* acc2,
+                               float* scal, hipStream_t st) {
+  const int SL = dm.HF / (4 * kSlices);
+  const int sph = kSlices / dm.H;
+  const int gpb = (kWave / SL) * (kBlkThreads / kWave);
+  const unsigned grid = (unsigned)(cdiv(g->n, gpb) * kSlices);
+  ProfScope p(name, st);
+  for (int b = 0; b < g->nblk; ++b) {
+    const int32_t* bptr_b = g->bptr[side] + (int64_t)b * g->n;
+    const int first = b == 0;
+#define GNN_BLK_LAUNCH(SL_)                                                                     \
+  k_gat_blk<SL_, MODE><<<grid, kBlkThreads, 0, st>>>(g->n, g->order[side], bptr_b, g->bcol[side], \
+                                                     feat, el, er, m, d, vstate, dm, sph, first,  \
+                                                     acc, acc2, scal)
+    switch (SL) {
+      case 4: GNN_BLK_LAUNCH(4); break;
+      case 8: GNN_BLK_LAUNCH(8); break;
+      case 16: GNN_BLK_LAUNCH(16); break;
+      case 32: GNN_BLK_LAUNCH(32); break;
+      default: set_error("gat blocked: unsupported slice width"); return GNN_ERR_UNSUPPORTED;
+    }
+#undef GNN_BLK_LAUNCH
+    GNN_LAUNCH_CHECK();
+  }
+  return GNN_OK;
+}
+
+gnn_status_t gat_blocked_fwd(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
+                             const float* er, float* m, float* d, float* out, hipStream_t st) {
+  {
+    ProfScope p("gat_softmax_stats", st);
+    k_gat_softmax_stats<<<(unsigned)cdiv(g->n, kBlkThreads / kWave), kBlkThreads, 0, st>>>(
+        g->n, g->order[0], g->indptr, g->indices, el, er, dm, m, d);
+    GNN_LAUNCH_CHECK();
+  }
+  return run_blocks<0>(g, 0, "gat_fwd_fused", dm, z, el, er, m, d, nullptr, out, nullptr, nullptr, st);
+}
+
+gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
+                                 const float* er, const float* m, const float* d, const float* out,
+                                 const float* gout, float* der, float4* vstate, float* t_buf,
+                                 float* sg_buf, hipStream_t st) {
+  GNN_TRY(run_blocks<1>(g, 0, "gat_bwd_dst", dm, z, el, er, m, d, nullptr, t_buf, nullptr, sg_buf, st));
+  ProfScope p("gat_bwd_dst_finish", st);
+  const int64_t cnt = (int64_t)g->n * dm.H;
+  k_gat_blk_dst_finish<<<(unsigned)cdiv(cnt, 256), 256, 0, st>>>(g->n, dm.H, dm.F, gout, t_buf, out,
+                                                                 sg_buf, er, m, d, der, vstate);
+  GNN_LAUNCH_CHECK();
+  return GNN_OK;
+}
+
+gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
+                                 const float4* vstate, const float* der, const float* gout,
+                                 const float* a_l, const float* a_r, float* dz, float* del,
+                                 float* a2_buf, float* sd_buf, hipStream_t st) {
+  GNN_TRY(run_blocks<2>(g, 1, "gat_bwd_src", dm, gout, el, nullptr, nullptr, nullptr, vstate, dz,
+                        a2_buf, sd_buf, st));
+  ProfScope p("gat_bwd_src_finish", st);
+  const int64_t cnt = (int64_t)g->n * dm.H;
+  k_gat_blk_src_finish<<<(unsigned)cdiv(cnt, 256), 256, 0, st>>>(g->n, dm.H, dm.F, z, a2_buf, sd_buf,
+                                                                 der, a_l, a_r, dz, del);
+  GNN_LAUNCH_CHECK();
+  return GNN_OK;
+}
+
+}  // namespace gnn

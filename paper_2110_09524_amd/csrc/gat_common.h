@@ -1,0 +1,46 @@
+// Pieces shared by the single-launch and the column-blocked GAT kernels.
+#pragma once
+
+#include "common.h"
+#include "rowgroup.h"
+
+namespace gnn {
+
+struct GatDims {
+  int H, F, HF;
+  int log2Hp;  // heads padded to a power of two; lanes of a group = (edge, head) pairs
+  float slope;
+};
+
+inline GatDims make_dims(int H, int F, float slope) {
+  GatDims dm;
+  dm.H = H;
+  dm.F = F;
+  dm.HF = H * F;
+  dm.log2Hp = ilog2(next_pow2(H));
+  dm.slope = slope;
+  return dm;
+}
+
+__device__ __forceinline__ float leaky(float x, float slope) { return x > 0.f ? x : slope * x; }
+
+// ---- column-blocked path (gat_blocked.hip) -----------------------------------------
+// True when the blocked kernels apply: several column blocks in the plan, a row of
+// heads*f floats that splits into 8 slices (one per XCD) of 4..64 float4 each, and every
+// slice inside one head.
+bool gat_blocked_applies(const gnn_graph_t* g, int heads, int f);
+size_t gat_blocked_ws_bytes(const gnn_graph_t* g, int heads, int f);  // extra workspace (bwd)
+gnn_status_t gat_blocked_fwd(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
+                             const float* er, float* m, float* d, float* out, hipStream_t st);
+// writes der, vstate (like the single-launch destination kernel); t_buf is an [n, HF] scratch
+gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
+                                 const float* er, const float* m, const float* d, const float* out,
+                                 const float* gout, float* der, float4* vstate, float* t_buf,
+                                 float* sg_buf, hipStream_t st);
+// writes dz, del; a2_buf is an [n, HF] scratch, sd_buf an [n, H] scratch
+gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
+                                 const float4* vstate, const float* der, const float* gout,
+                                 const float* a_l, const float* a_r, float* dz, float* del,
+                                 float* a2_buf, float* sd_buf, hipStream_t st);
+
+}  // namespace gnn

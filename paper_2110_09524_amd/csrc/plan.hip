@@ -66,6 +66,23 @@ __global__ void k_degree_and_bucket(int32_t n, const int32_t* __restrict__ ptr,
   atomicAdd(&hist[b], 1);
 }
 
+// key of an edge for the column-blocked order: (block of its column) * n + its row.
+// pos -> row by binary search in the row pointers (rows may be empty).
+__global__ void k_block_keys(int32_t n, int64_t nnz, const int32_t* __restrict__ ptr,
+                             const int32_t* __restrict__ cols, int32_t block_cols,
+                             uint64_t* __restrict__ keys, int32_t* __restrict__ counts) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i >= nnz) return;
+  int32_t lo = 0, hi = n;  // invariant: ptr[lo] <= i < ptr[hi]
+  while (hi - lo > 1) {
+    int32_t mid = lo + ((hi - lo) >> 1);
+    if ((int64_t)ptr[mid] <= i) lo = mid; else hi = mid;
+  }
+  const uint64_t key = (uint64_t)(cols[i] / block_cols) * (uint64_t)n + (uint64_t)lo;
+  keys[i] = key;
+  atomicAdd(&counts[key], 1);  // integer count
+}
+
 static void free_all(gnn_graph* g) {
   if (!g) return;
   (void)hipFree(g->indptr_t);
@@ -75,6 +92,8 @@ static void free_all(gnn_graph* g) {
     (void)hipFree(g->bucket_of[s]);
     (void)hipFree(g->order[s]);
     (void)hipFree(g->bucket_offsets[s]);
+    (void)hipFree(g->bptr[s]);
+    (void)hipFree(g->bcol[s]);
   }
   delete g;
 }
@@ -144,6 +163,50 @@ static gnn_status_t build_side(gnn_graph* g, int side, const int32_t* ptr, hipSt
   return GNN_OK;
 }
 
+// Column-blocked copy of one side's edge list: edges stable-sorted by
+// (column / block_cols, row); bptr[b*n + r] .. bptr[b*n + r + 1] is the range of
+// row r inside block b.  Only built when the vertex set spans several blocks.
+static gnn_status_t build_blocked(gnn_graph* g, int side, const int32_t* ptr, const int32_t* cols,
+                                  hipStream_t st) {
+  const int32_t n = g->n;
+  const int64_t nnz = g->nnz;
+  const int thr = 256;
+  const int64_t slots = (int64_t)g->nblk * n;
+  TempBuffers tmp;
+  uint64_t *keys = nullptr, *keys_sorted = nullptr;
+  int32_t* counts = nullptr;
+  GNN_HIP(tmp.alloc(&keys, (size_t)nnz));
+  GNN_HIP(tmp.alloc(&keys_sorted, (size_t)nnz));
+  GNN_HIP(tmp.alloc(&counts, (size_t)slots + 1));
+  GNN_HIP(hipMalloc((void**)&g->bptr[side], sizeof(int32_t) * ((size_t)slots + 1)));
+  GNN_HIP(hipMalloc((void**)&g->bcol[side], sizeof(int32_t) * (size_t)nnz));
+  GNN_HIP(hipMemsetAsync(counts, 0, sizeof(int32_t) * ((size_t)slots + 1), st));
+  k_block_keys<<<cdiv(nnz, thr), thr, 0, st>>>(n, nnz, ptr, cols, g->block_cols, keys, counts);
+  GNN_LAUNCH_CHECK();
+  {
+    size_t bytes = 0;
+    GNN_HIP(rocprim::exclusive_scan(nullptr, bytes, counts, g->bptr[side], (int32_t)0,
+                                    (size_t)slots + 1, rocprim::plus<int32_t>(), st));
+    void* scratch = nullptr;
+    GNN_HIP(tmp.alloc((char**)&scratch, bytes));
+    GNN_HIP(rocprim::exclusive_scan(scratch, bytes, counts, g->bptr[side], (int32_t)0,
+                                    (size_t)slots + 1, rocprim::plus<int32_t>(), st));
+  }
+  {
+    int end_bit = 1;
+    while (end_bit < 64 && ((uint64_t)(slots - 1) >> end_bit) != 0) ++end_bit;
+    size_t bytes = 0;
+    GNN_HIP(rocprim::radix_sort_pairs(nullptr, bytes, keys, keys_sorted, cols, g->bcol[side],
+                                      (size_t)nnz, 0, end_bit, st));
+    void* scratch = nullptr;
+    GNN_HIP(tmp.alloc((char**)&scratch, bytes));
+    GNN_HIP(rocprim::radix_sort_pairs(scratch, bytes, keys, keys_sorted, cols, g->bcol[side],
+                                      (size_t)nnz, 0, end_bit, st));
+  }
+  GNN_HIP(hipStreamSynchronize(st));
+  return GNN_OK;
+}
+
 static gnn_status_t build(gnn_graph* g, hipStream_t st) {
   const int32_t n = g->n;
   const int64_t nnz = g->nnz;
@@ -207,6 +270,15 @@ static gnn_status_t build(gnn_graph* g, hipStream_t st) {
   }
   GNN_TRY(build_side(g, 0, g->indptr, st));
   GNN_TRY(build_side(g, 1, g->indptr_t, st));
+  g->block_cols = (int32_t)config_get(kCfgBlockCols);
+  g->nblk = 1;
+  // the (block, row) pointer table has nblk * n entries: keep it below 2^28
+  if (g->block_cols > 0 && n > g->block_cols && nnz > 0 &&
+      cdiv(n, g->block_cols) * (int64_t)n < ((int64_t)1 << 28)) {
+    g->nblk = (int32_t)cdiv(n, g->block_cols);
+    GNN_TRY(build_blocked(g, 0, g->indptr, g->indices, st));
+    GNN_TRY(build_blocked(g, 1, g->indptr_t, g->indices_t, st));
+  }
   GNN_HIP(hipStreamSynchronize(st));
   return GNN_OK;
 }
@@ -278,5 +350,25 @@ extern "C" gnn_status_t gnn_graph_get_buckets(const gnn_graph_t* g, int side, in
   if (bucket_offsets)
     GNN_HIP(hipMemcpyAsync(bucket_offsets, g->bucket_offsets[side],
                            sizeof(int32_t) * (GNN_NUM_BUCKETS + 1), hipMemcpyDeviceToDevice, st));
+  return GNN_OK;
+}
+
+extern "C" gnn_status_t gnn_graph_get_blocked(const gnn_graph_t* g, int side, int32_t* num_blocks,
+                                              int32_t* block_cols, int32_t* bptr, int32_t* bcol,
+                                              void* stream) {
+  clear_error();
+  GNN_REQUIRE(g != nullptr, GNN_ERR_INVALID_ARG, "gnn_graph_get_blocked: graph is null");
+  GNN_REQUIRE(side == 0 || side == 1, GNN_ERR_INVALID_ARG, "gnn_graph_get_blocked: side must be 0 or 1");
+  if (num_blocks) *num_blocks = g->nblk;
+  if (block_cols) *block_cols = g->block_cols;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (g->nblk > 1) {
+    if (bptr)
+      GNN_HIP(hipMemcpyAsync(bptr, g->bptr[side], sizeof(int32_t) * ((size_t)g->nblk * g->n + 1),
+                             hipMemcpyDeviceToDevice, st));
+    if (bcol)
+      GNN_HIP(hipMemcpyAsync(bcol, g->bcol[side], sizeof(int32_t) * (size_t)g->nnz,
+                             hipMemcpyDeviceToDevice, st));
+  }
   return GNN_OK;
 }

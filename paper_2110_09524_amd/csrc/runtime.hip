@@ -17,6 +17,13 @@ void set_error(const char* fmt, ...) {
 }
 void clear_error() { g_err[0] = 0; }
 
+// ---- tuning knobs -------------------------------------------------------------
+// block_cols: gathered vertices per column block of the blocked edge lists.  A block
+// of 128-byte row slices (one slice per XCD) should sit in one XCD's 4 MB L2:
+// 16384 * 128 B = 2 MB.  0 disables blocking.
+static int64_t g_config[kCfgCount] = {16384, 0};
+int64_t config_get(ConfigKey k) { return g_config[k]; }
+
 // ---- profiling ---------------------------------------------------------------
 struct Pending {
   const char* name;
@@ -63,6 +70,23 @@ void prof_end(hipStream_t s) {
 using namespace gnn;
 
 extern "C" const char* gnn_last_error(void) { return g_err; }
+
+extern "C" gnn_status_t gnn_config_set(const char* key, int64_t value) {
+  clear_error();
+  GNN_REQUIRE(key != nullptr, GNN_ERR_INVALID_ARG, "gnn_config_set: key is null");
+  if (std::strcmp(key, "block_cols") == 0) {
+    GNN_REQUIRE(value >= 0 && value <= (1 << 30), GNN_ERR_INVALID_ARG,
+                "gnn_config_set: block_cols out of range");
+    g_config[kCfgBlockCols] = value;
+    return GNN_OK;
+  }
+  if (std::strcmp(key, "force_simple_kernels") == 0) {
+    g_config[kCfgForceSimple] = value != 0;
+    return GNN_OK;
+  }
+  set_error("gnn_config_set: unknown key '%s'", key);
+  return GNN_ERR_INVALID_ARG;
+}
 
 extern "C" gnn_status_t gnn_prof_enable(int on) {
   g_prof_on = on != 0;

@@ -30,8 +30,14 @@ def workspace(nbytes):
     return torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
 
 
-def assert_close(name, got, ref, rtol=RTOL, atol=ATOL, reduce_scale=False):
+def assert_close(name, got, ref, rtol=RTOL, atol=ATOL, reduce_scale=False, row_scale=False):
     """Element-wise |got - ref| <= atol_eff + rtol |ref|.
+
+    row_scale=True is for the input gradient gx = dz w^T: every entry of row u is a dot
+    product with the same vector dz[u], whose fp32 rounding (inherited from the fp32
+    projection z and the scores built on it) is proportional to |dz[u]|, not to the
+    possibly cancelled entry, so the absolute term scales with the row's largest
+    entry: atol_eff[u] = atol * max(1, max_j |ref[u, j]|).
 
     reduce_scale=True is for gradients of shared parameters, each entry a sum over
     all |V| vertices (or |E| edges): fp32 rounding there is proportional to the
@@ -45,6 +51,8 @@ def assert_close(name, got, ref, rtol=RTOL, atol=ATOL, reduce_scale=False):
     a = atol
     if reduce_scale and ref.size:
         a = atol * max(1.0, float(np.sqrt(np.mean(ref * ref))))
+    if row_scale and ref.ndim == 2 and ref.size:
+        a = atol * np.maximum(1.0, np.abs(ref).max(axis=1, keepdims=True))
     err = np.abs(got - ref)
     tol = a + rtol * np.abs(ref)
     bad = err > tol

@@ -18,7 +18,7 @@ def check(c):
     n = c["n"]
     assert_close("hk", res["hk"], fwd["Hk"].reshape(n, -1))
     assert_close("out", res["out"], fwd["out"])
-    assert_close("gx", res["gx"], bwd["gx"])
+    assert_close("gx", res["gx"], bwd["gx"], row_scale=True)
     assert_close("gw_fc", res["gw_fc"], bwd["gw_fc"], reduce_scale=True)
     assert_close("gmu", res["gmu"], bwd["gmu"], reduce_scale=True)
     assert_close("ginv_sigma", res["ginv_sigma"], bwd["ginv_sigma"], reduce_scale=True)

@@ -69,3 +69,28 @@ def test_malformed_graphs_are_rejected():
     with pytest.raises(pk.GnnError) as e:
         pk.Graph(dev(good_ptr), dev(np.array([0, -1, 1], dtype=np.int32)))
     assert e.value.status == 2
+
+
+@pytest.mark.parametrize("block_cols", [16, 100])
+def test_blocked_edge_lists(block_cols):
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev
+    print("plan: blocked lists, block_cols =", block_cols, flush=True)
+    rng = np.random.default_rng(4)
+    indptr, indices = random_graph(rng, 333, 4000, self_loops=True, duplicates=True)
+    pk.gnn_config_set("block_cols", block_cols)
+    try:
+        g = pk.Graph(dev(indptr), dev(indices))
+    finally:
+        pk.gnn_config_set("block_cols", 16384)
+    ip_t, ix_t, _ = (t.cpu().numpy() for t in g.csc())
+    for side, ptr, cols in ((0, indptr, indices), (1, ip_t, ix_t)):
+        nb, bc, bptr, bcol = g.blocked(side)
+        r_nb, r_bptr, r_bcol = oplan.blocked_edges(ptr, cols, block_cols)
+        assert nb == r_nb and bc == block_cols
+        np.testing.assert_array_equal(bptr.cpu().numpy(), r_bptr)
+        np.testing.assert_array_equal(bcol.cpu().numpy(), r_bcol)
+    g.close()
+    g = pk.Graph(dev(indptr), dev(indices))          # default block size: one block, no tables
+    assert g.blocked(0)[0] == 1
+    g.close()

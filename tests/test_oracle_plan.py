@@ -81,3 +81,19 @@ def test_generators_shapes_and_degrees():
     assert deg.min() >= 1 and deg.max() > 20 * np.median(deg) / 2
     ip2, ix2 = graphs.chung_lu(3000, 30_000, 2.1, 7)
     np.testing.assert_array_equal(ix, ix2)
+
+
+def test_blocked_edge_list_is_a_partition_by_column_block():
+    rng = np.random.default_rng(8)
+    indptr, indices = random_graph(rng, 50, 400, self_loops=True, duplicates=True)
+    nblk, bptr, bcol = op.blocked_edges(indptr, indices, 16)
+    assert nblk == 4 and bptr[0] == 0 and bptr[-1] == len(indices)
+    n = 50
+    for b in range(nblk):
+        for r in (0, 7, 49):
+            seg = bcol[bptr[b * n + r]:bptr[b * n + r + 1]]
+            assert ((seg // 16) == b).all()
+            want = [c for c in indices[indptr[r]:indptr[r + 1]] if c // 16 == b]
+            assert seg.tolist() == want          # original order kept inside a (block, row) cell
+    # every edge appears exactly once
+    assert sorted(bcol.tolist()) == sorted(indices.tolist())
