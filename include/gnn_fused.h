@@ -110,8 +110,8 @@ gnn_status_t gnn_graph_get_blocked(const gnn_graph_t* graph, int side, int32_t* 
                                    void* stream);
 
 /* Tuning knobs, read when a graph is created or a layer is called.  Keys:
- *   "block_cols"            gathered vertices per column block (default 16384:
- *                           16384 rows x one 128-byte slice per XCD = 2 MB of a
+ *   "block_cols"            gathered vertices per column block (default 24576:
+ *                           24576 rows x one 128-byte slice per XCD = 3 MB of a
  *                           4 MB L2); 0 disables blocking
  *   "force_simple_kernels"  1: always use the single-launch kernels
  * Errors: INVALID_ARG for an unknown key or a value out of range. */
@@ -138,9 +138,18 @@ gnn_status_t gnn_linear_fwd(int64_t n, int fin, int fout, const float* x, const 
  *   d   = sum exp(s_e - m)            [n, heads]     (1 for an empty row)
  *   out = sum (exp(s_e - m) / d) z[u] [n, heads*f]   (0 for an empty row)
  *
+ *   t   = sum alpha_e g_e z[u]        [n, heads*f]   optional, g_e = LeakyReLU'(el[u]+er[v])
+ *   sg  = sum alpha_e g_e             [n, heads]     optional
+ *
  * Requirements: f % 4 == 0, heads*f <= 1024, heads <= 64; x, w any width.
  * Forward writes z, el, er, m, d, out (all of them are the saved state the
- * backward call needs; none has a per-edge dimension).
+ * backward call needs; none has a per-edge dimension).  t and sg (both or neither,
+ * may be NULL) are the destination-side sums of the backward pass; they ride on the
+ * rows the forward pass gathers anyway and are vertex-sized, so by the criterion of
+ * Sec. 6 (recompute only if computation / memory is O(1); here it is |E|/|V|) they
+ * are worth stashing: the backward call then skips one whole pass over the edges.
+ * Pass NULL for inference, or to have the backward call recompute them.
+ * The forward call needs no workspace (ws may be NULL).
  * ------------------------------------------------------------------------- */
 size_t gnn_gat_workspace_bytes(const gnn_graph_t* graph, int fin, int heads, int f);
 
@@ -148,15 +157,19 @@ gnn_status_t gnn_gat_fwd(const gnn_graph_t* graph, int fin, int heads, int f, fl
                          const float* x /*[n,fin]*/, const float* w /*[fin,heads*f]*/,
                          const float* a_l /*[heads,f]*/, const float* a_r /*[heads,f]*/,
                          float* z /*[n,heads*f]*/, float* el, float* er, float* m, float* d /*[n,heads]*/,
-                         float* out /*[n,heads*f]*/, void* ws, size_t ws_bytes, void* stream);
+                         float* out /*[n,heads*f]*/, float* t /*[n,heads*f] nullable*/,
+                         float* sg /*[n,heads] nullable*/, void* ws, size_t ws_bytes, void* stream);
 
 /* Gradients of L = <gout, out>.  Per-edge scores and softmax values are
- * recomputed from el, er, m, d; LeakyReLU'(0) = slope.  gx may be NULL (skip
- * the input gradient).  Writes gx [n,fin], gw [fin,heads*f], ga_l, ga_r [heads,f]. */
+ * recomputed from el, er, m, d; LeakyReLU'(0) = slope.  t, sg: what the forward
+ * call wrote, or both NULL (then they are recomputed with one more pass over the
+ * in-edges).  gx may be NULL (skip the input gradient).
+ * Writes gx [n,fin], gw [fin,heads*f], ga_l, ga_r [heads,f]. */
 gnn_status_t gnn_gat_bwd(const gnn_graph_t* graph, int fin, int heads, int f, float slope,
                          const float* x, const float* w, const float* a_l, const float* a_r,
                          const float* z, const float* el, const float* er, const float* m,
-                         const float* d, const float* out, const float* gout /*[n,heads*f]*/,
+                         const float* d, const float* out, const float* t /*nullable*/,
+                         const float* sg /*nullable*/, const float* gout /*[n,heads*f]*/,
                          float* gx /*nullable*/, float* gw, float* ga_l, float* ga_r,
                          void* ws, size_t ws_bytes, void* stream);
 

@@ -52,8 +52,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_linear_fwd.argtypes = [i64, i32, i32, vp, vp, vp, vp]
     lib.gnn_gat_workspace_bytes.restype = sz
     lib.gnn_gat_workspace_bytes.argtypes = [vp, i32, i32, i32]
-    lib.gnn_gat_fwd.argtypes = [vp, i32, i32, i32, f32] + [vp] * 10 + [vp, sz, vp]
-    lib.gnn_gat_bwd.argtypes = [vp, i32, i32, i32, f32] + [vp] * 15 + [vp, sz, vp]
+    lib.gnn_gat_fwd.argtypes = [vp, i32, i32, i32, f32] + [vp] * 12 + [vp, sz, vp]
+    lib.gnn_gat_bwd.argtypes = [vp, i32, i32, i32, f32] + [vp] * 17 + [vp, sz, vp]
     lib.gnn_edgeconv_workspace_bytes.restype = sz
     lib.gnn_edgeconv_workspace_bytes.argtypes = [vp, i32, i32]
     lib.gnn_edgeconv_fwd.argtypes = [vp, i32, i32] + [vp] * 6 + [vp, sz, vp]
@@ -192,19 +192,20 @@ def gnn_gat_workspace_bytes(g: Graph, fin, heads, f) -> int:
     return int(lib().gnn_gat_workspace_bytes(g.handle, fin, heads, f))
 
 
-def gnn_gat_fwd(g: Graph, fin, heads, f, slope, x, w, a_l, a_r, z, el, er, m, d, out, ws=None,
-                stream=None):
+def gnn_gat_fwd(g: Graph, fin, heads, f, slope, x, w, a_l, a_r, z, el, er, m, d, out, t=None,
+                sg=None, ws=None, stream=None):
     wp, wb = _ws_args(ws)
     _check(lib().gnn_gat_fwd(g.handle, fin, heads, f, slope, _f(x), _f(w), _f(a_l), _f(a_r), _f(z),
-                             _f(el), _f(er), _f(m), _f(d), _f(out), wp, wb, _stream(stream)))
+                             _f(el), _f(er), _f(m), _f(d), _f(out), _f(t), _f(sg), wp, wb,
+                             _stream(stream)))
 
 
-def gnn_gat_bwd(g: Graph, fin, heads, f, slope, x, w, a_l, a_r, z, el, er, m, d, out, gout, gx, gw,
-                ga_l, ga_r, ws, stream=None):
+def gnn_gat_bwd(g: Graph, fin, heads, f, slope, x, w, a_l, a_r, z, el, er, m, d, out, t, sg, gout,
+                gx, gw, ga_l, ga_r, ws, stream=None):
     wp, wb = _ws_args(ws)
     _check(lib().gnn_gat_bwd(g.handle, fin, heads, f, slope, _f(x), _f(w), _f(a_l), _f(a_r), _f(z),
-                             _f(el), _f(er), _f(m), _f(d), _f(out), _f(gout), _f(gx), _f(gw), _f(ga_l),
-                             _f(ga_r), wp, wb, _stream(stream)))
+                             _f(el), _f(er), _f(m), _f(d), _f(out), _f(t), _f(sg), _f(gout), _f(gx),
+                             _f(gw), _f(ga_l), _f(ga_r), wp, wb, _stream(stream)))
 
 
 def gnn_edgeconv_workspace_bytes(g: Graph, fin, fout) -> int:

@@ -56,12 +56,16 @@ struct GroupLds {
 };
 
 // ---- a3: fused forward ----------------------------------------------------------
-template <int L, int NV>
+// WT: also produce t[v] = sum_e alpha_e g_e z[u] and sg[v,h] = sum_e alpha_e g_e, the two
+// destination-side sums of the backward pass.  They ride on the same gathered rows, and
+// they are O(|V|) vertex state, which is cheaper to stash than to recompute (Sec. 6:
+// recompute only when computation / memory is O(1); here it is |E|/|V|).
+template <int L, int NV, bool WT>
 __global__ __launch_bounds__(kBlock) void k_gat_fwd(
     int32_t n_rows, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
     const int32_t* __restrict__ indices, const float* __restrict__ z, const float* __restrict__ el,
     const float* __restrict__ er, GatDims dm, float* __restrict__ out, float* __restrict__ m_out,
-    float* __restrict__ d_out) {
+    float* __restrict__ d_out, float* __restrict__ t_out, float* __restrict__ sg_out) {
   constexpr int G = kWave / L;
   constexpr int GPB = G * (kBlock / kWave);
   __shared__ float lds[GPB * GroupLds<L, NV>::kFloats];
@@ -74,6 +78,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_fwd(
   float* g_lds = lds + grp * GroupLds<L, NV>::kFloats;
   int* l_idx = reinterpret_cast<int*>(g_lds);
   float* l_p = g_lds + L;
+  float* l_p2 = g_lds + 2 * L;
   float* l_sc = g_lds + 3 * L;
 
   const int H = dm.H, HF = dm.HF;
@@ -89,23 +94,27 @@ __global__ __launch_bounds__(kBlock) void k_gat_fwd(
 
   int hs[NV];
   bool slot_ok[NV];
-  float4 acc[NV];
+  float4 acc[NV], acc2[NV];
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
     int col = 4 * (li + j * L);
     slot_ok[j] = col < HF;
     hs[j] = slot_ok[j] ? col / dm.F : 0;
     acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    acc2[j] = acc[j];
   }
 
-  float m_run = -INFINITY, d_run = 0.f;
+  float m_run = -INFINITY, d_run = 0.f, d2_run = 0.f;
   for (int32_t c0 = beg; c0 < end; c0 += epc) {
     // chunk phase: lane = (edge e_loc of the chunk, head h)
     const int32_t e = c0 + e_loc;
     const bool e_ok = e < end;
     const int32_t u = e_ok ? indices[e] : 0;
-    float s = -INFINITY;
-    if (e_ok && head_ok) s = leaky(el[(int64_t)u * H + h] + er_vh, dm.slope);
+    float s = -INFINITY, raw = 0.f;
+    if (e_ok && head_ok) {
+      raw = el[(int64_t)u * H + h] + er_vh;
+      s = leaky(raw, dm.slope);
+    }
     const float cmax = group_max_from<L>(s, Hp);
     const float m_new = fmaxf(m_run, cmax);
     const float p = (e_ok && head_ok) ? __expf(s - m_new) : 0.f;
@@ -114,12 +123,20 @@ __global__ __launch_bounds__(kBlock) void k_gat_fwd(
     m_run = m_new;
     if (h == 0) l_idx[e_loc] = u;
     l_p[li] = p;
+    if (WT) {
+      const float p2 = raw > 0.f ? p : dm.slope * p;  // weight times LeakyReLU'
+      d2_run = d2_run * sc + p2;
+      l_p2[li] = p2;
+    }
     if (e_loc == 0) l_sc[h] = sc;
     wave_lds_fence();
     // row phase: lane = float4 column slots; the chunk is summed on its own first
-    float4 part[NV];
+    float4 part[NV], part2[NV];
 #pragma unroll
-    for (int j = 0; j < NV; ++j) part[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = 0; j < NV; ++j) {
+      part[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      part2[j] = part[j];
+    }
     const int cnt = min(epc, end - c0);
     int t = 0;
     for (; t + kU <= cnt; t += kU) {
@@ -139,18 +156,30 @@ __global__ __launch_bounds__(kBlock) void k_gat_fwd(
       for (int q = 0; q < kU; ++q)
 #pragma unroll
         for (int j = 0; j < NV; ++j)
-          if (slot_ok[j]) fma4(part[j], l_p[((t + q) << dm.log2Hp) + hs[j]], row[q][j]);
+          if (slot_ok[j]) {
+            const int pi = ((t + q) << dm.log2Hp) + hs[j];
+            fma4(part[j], l_p[pi], row[q][j]);
+            if (WT) fma4(part2[j], l_p2[pi], row[q][j]);
+          }
     }
     for (; t < cnt; ++t) {
       int uu = l_idx[t];
       if (L == 64) uu = __builtin_amdgcn_readfirstlane(uu);
 #pragma unroll
       for (int j = 0; j < NV; ++j)
-        if (slot_ok[j])
-          fma4(part[j], l_p[(t << dm.log2Hp) + hs[j]], ld4(z + (int64_t)uu * HF + 4 * (li + j * L)));
+        if (slot_ok[j]) {
+          const float4 row1 = ld4(z + (int64_t)uu * HF + 4 * (li + j * L));
+          const int pi = (t << dm.log2Hp) + hs[j];
+          fma4(part[j], l_p[pi], row1);
+          if (WT) fma4(part2[j], l_p2[pi], row1);
+        }
     }
 #pragma unroll
-    for (int j = 0; j < NV; ++j) fold4(acc[j], l_sc[hs[j]], part[j]);  // rescale to the new max, add the chunk
+    for (int j = 0; j < NV; ++j) {  // rescale to the new max, add the chunk
+      const float scj = l_sc[hs[j]];
+      fold4(acc[j], scj, part[j]);
+      if (WT) fold4(acc2[j], scj, part2[j]);
+    }
     wave_lds_fence();
   }
 
@@ -166,7 +195,15 @@ __global__ __launch_bounds__(kBlock) void k_gat_fwd(
       float inv = 1.f / l_sc[hs[j]];
       scale4(acc[j], inv);
       st4(out + (int64_t)v * HF + 4 * (li + j * L), acc[j]);
+      if (WT) {
+        scale4(acc2[j], inv);
+        st4(t_out + (int64_t)v * HF + 4 * (li + j * L), acc2[j]);
+      }
     }
+  if (WT) {
+    const float dd2 = group_sum_from<L>(d2_run, Hp);
+    if (e_loc == 0 && head_ok) sg_out[(int64_t)v * H + h] = empty ? 0.f : dd2 / dd;
+  }
   if (e_loc == 0 && head_ok) {
     m_out[(int64_t)v * H + h] = m_run;
     d_out[(int64_t)v * H + h] = dd;
@@ -558,15 +595,138 @@ static gnn_status_t dispatch_group(GroupShape gs, Args... args) {
 template <int L, int NV>
 struct FwdLauncher {
   static gnn_status_t run(const gnn_graph_t* g, const float* z, const float* el, const float* er,
-                          GatDims dm, float* out, float* m, float* d, hipStream_t st) {
+                          GatDims dm, float* out, float* m, float* d, float* t, float* sg,
+                          hipStream_t st) {
     constexpr int GPB = (kWave / L) * (kBlock / kWave);
     ProfScope p("gat_fwd_fused", st);
-    k_gat_fwd<L, NV><<<(unsigned)cdiv(g->n, GPB), kBlock, 0, st>>>(
-        g->n, g->order[0], g->indptr, g->indices, z, el, er, dm, out, m, d);
+    const unsigned grid = (unsigned)cdiv(g->n, GPB);
+    if (t)
+      k_gat_fwd<L, NV, true><<<grid, kBlock, 0, st>>>(g->n, g->order[0], g->indptr, g->indices, z, el,
+                                                      er, dm, out, m, d, t, sg);
+    else
+      k_gat_fwd<L, NV, false><<<grid, kBlock, 0, st>>>(g->n, g->order[0], g->indptr, g->indices, z, el,
+                                                       er, dm, out, m, d, nullptr, nullptr);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
   }
 };
+
+// ---- vertex-side closing steps of the backward pass (one row group per vertex) -------
+// der[v,h] = <gout[v,h,:], t[v,h,:]> - D[v,h] sg[v,h],  D[v,h] = <gout[v,h,:], out[v,h,:]>,
+// vstate[v,h] = (er, m, 1/d, D)
+template <int L, int NV>
+__global__ __launch_bounds__(kBlock) void k_gat_dst_finish(
+    int32_t n_rows, const float* __restrict__ gout, const float* __restrict__ t_in,
+    const float* __restrict__ out, const float* __restrict__ sg, const float* __restrict__ er,
+    const float* __restrict__ m_in, const float* __restrict__ d_in, GatDims dm,
+    float* __restrict__ der, float4* __restrict__ vstate) {
+  constexpr int G = kWave / L;
+  constexpr int GPB = G * (kBlock / kWave);
+  __shared__ float lds[GPB * 2 * L * NV];
+  const int li = threadIdx.x & (L - 1);
+  const int grp = threadIdx.x / L;
+  const int64_t v = (int64_t)blockIdx.x * GPB + grp;
+  if (v >= n_rows) return;
+  float* l_red = lds + grp * 2 * L * NV;
+  const int H = dm.H, HF = dm.HF;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int col = 4 * (li + j * L);
+    float p1 = 0.f, pd = 0.f;
+    if (col < HF) {
+      const float4 g4 = ld4(gout + v * HF + col);
+      p1 = dot4(g4, ld4(t_in + v * HF + col));
+      pd = dot4(g4, ld4(out + v * HF + col));
+    }
+    l_red[j * L + li] = p1;
+    l_red[L * NV + j * L + li] = pd;
+  }
+  wave_lds_fence();
+  if (li < H) {
+    const int h = li;
+    const float t1 = head_sum<L, NV>(l_red, h, dm.F);
+    const float D = head_sum<L, NV>(l_red + L * NV, h, dm.F);
+    const int64_t i = v * H + h;
+    der[i] = t1 - D * sg[i];
+    vstate[i] = make_float4(er[i], m_in[i], 1.f / d_in[i], D);
+  }
+}
+
+// del[u,h] = <z[u,h,:], a2[u,h,:]> - sd[u,h];  dz[u,h,:] += a_l[h,:] del[u,h] + a_r[h,:] der[u,h]
+template <int L, int NV>
+__global__ __launch_bounds__(kBlock) void k_gat_src_finish(
+    int32_t n_rows, const float* __restrict__ z, const float* __restrict__ a2,
+    const float* __restrict__ sd, const float* __restrict__ der, const float* __restrict__ a_l,
+    const float* __restrict__ a_r, GatDims dm, float* __restrict__ dz, float* __restrict__ del) {
+  constexpr int G = kWave / L;
+  constexpr int GPB = G * (kBlock / kWave);
+  __shared__ float lds[GPB * 3 * L * NV];
+  const int li = threadIdx.x & (L - 1);
+  const int grp = threadIdx.x / L;
+  const int64_t u = (int64_t)blockIdx.x * GPB + grp;
+  if (u >= n_rows) return;
+  float* l_red = lds + grp * 3 * L * NV;
+  float* l_dl = l_red + L * NV;
+  float* l_dr = l_red + 2 * L * NV;
+  const int H = dm.H, HF = dm.HF;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int col = 4 * (li + j * L);
+    float p = 0.f;
+    if (col < HF) p = dot4(ld4(z + u * HF + col), ld4(a2 + u * HF + col));
+    l_red[j * L + li] = p;
+  }
+  wave_lds_fence();
+  if (li < H) {
+    const int64_t i = u * H + li;
+    const float dl = head_sum<L, NV>(l_red, li, dm.F) - sd[i];
+    del[i] = dl;
+    l_dl[li] = dl;
+    l_dr[li] = der[i];
+  }
+  wave_lds_fence();
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int col = 4 * (li + j * L);
+    if (col < HF) {
+      const int h = col / dm.F;
+      float4 o = ld4(dz + u * HF + col);
+      fma4(o, l_dl[h], ld4(a_l + col));
+      fma4(o, l_dr[h], ld4(a_r + col));
+      st4(dz + u * HF + col, o);
+    }
+  }
+}
+
+template <int L, int NV>
+struct DstFinishLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, const float* gout, const float* t, const float* out,
+                          const float* sg, const float* er, const float* m, const float* d, GatDims dm,
+                          float* der, float4* vstate, hipStream_t st) {
+    constexpr int GPB = (kWave / L) * (kBlock / kWave);
+    ProfScope p("gat_bwd_dst_finish", st);
+    k_gat_dst_finish<L, NV><<<(unsigned)cdiv(g->n, GPB), kBlock, 0, st>>>(g->n, gout, t, out, sg, er, m,
+                                                                         d, dm, der, vstate);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+  }
+};
+
+template <int L, int NV>
+struct SrcFinishLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, const float* z, const float* a2, const float* sd,
+                          const float* der, const float* a_l, const float* a_r, GatDims dm, float* dz,
+                          float* del, hipStream_t st) {
+    constexpr int GPB = (kWave / L) * (kBlock / kWave);
+    ProfScope p("gat_bwd_src_finish", st);
+    k_gat_src_finish<L, NV><<<(unsigned)cdiv(g->n, GPB), kBlock, 0, st>>>(g->n, z, a2, sd, der, a_l,
+                                                                         a_r, dm, dz, del);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+  }
+};
+
+
 
 template <int L, int NV>
 struct BwdDstLauncher {
@@ -597,6 +757,19 @@ struct BwdSrcLauncher {
 };
 
 
+gnn_status_t gat_dst_finish(const gnn_graph_t* g, GatDims dm, const float* gout, const float* t,
+                            const float* out, const float* sg, const float* er, const float* m,
+                            const float* d, float* der, float4* vstate, hipStream_t st) {
+  return dispatch_group<DstFinishLauncher>(pick_group(dm.HF), g, gout, t, out, sg, er, m, d, dm, der,
+                                           vstate, st);
+}
+gnn_status_t gat_src_finish(const gnn_graph_t* g, GatDims dm, const float* z, const float* a2,
+                            const float* sd, const float* der, const float* a_l, const float* a_r,
+                            float* dz, float* del, hipStream_t st) {
+  return dispatch_group<SrcFinishLauncher>(pick_group(dm.HF), g, z, a2, sd, der, a_l, a_r, dm, dz, del,
+                                           st);
+}
+
 }  // namespace gnn
 
 using namespace gnn;
@@ -609,11 +782,14 @@ extern "C" size_t gnn_gat_workspace_bytes(const gnn_graph_t* g, int fin, int hea
 extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, int f, float slope,
                                     const float* x, const float* w, const float* a_l, const float* a_r,
                                     float* z, float* el, float* er, float* m, float* d, float* out,
-                                    void* ws, size_t ws_bytes, void* stream) {
+                                    float* t, float* sg, void* ws, size_t ws_bytes, void* stream) {
   clear_error();
-  (void)ws;
+  (void)ws;  // the forward pass needs no scratch
   (void)ws_bytes;
   GNN_TRY(check_gat_dims(g, fin, heads, f, "gnn_gat_fwd"));
+  GNN_REQUIRE((t == nullptr) == (sg == nullptr), GNN_ERR_INVALID_ARG,
+              "gnn_gat_fwd: t and sg must be given together");
+  GNN_REQUIRE(t == nullptr || aligned16(t), GNN_ERR_INVALID_ARG, "gnn_gat_fwd: t must be 16-byte aligned");
   if (g->n == 0) return GNN_OK;
   GNN_REQUIRE(x && w && a_l && a_r && z && el && er && m && d && out, GNN_ERR_INVALID_ARG,
               "gnn_gat_fwd: null pointer");
@@ -632,19 +808,22 @@ extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, in
   }
   // a3: fused score -> softmax -> aggregate
   if (gat_blocked_applies(g, heads, f))
-    return gat_blocked_fwd(g, make_dims(heads, f, slope), z, el, er, m, d, out, st);
+    return gat_blocked_fwd(g, make_dims(heads, f, slope), z, el, er, m, d, out, t, sg, st);
   return dispatch_group<FwdLauncher>(pick_group(HF), g, (const float*)z, (const float*)el,
-                                     (const float*)er, make_dims(heads, f, slope), out, m, d, st);
+                                     (const float*)er, make_dims(heads, f, slope), out, m, d, t, sg, st);
 }
 
 extern "C" gnn_status_t gnn_gat_bwd(const gnn_graph_t* g, int fin, int heads, int f, float slope,
                                     const float* x, const float* w, const float* a_l, const float* a_r,
                                     const float* z, const float* el, const float* er, const float* m,
-                                    const float* d, const float* out, const float* gout, float* gx,
-                                    float* gw, float* ga_l, float* ga_r, void* ws, size_t ws_bytes,
-                                    void* stream) {
+                                    const float* d, const float* out, const float* t, const float* sg,
+                                    const float* gout, float* gx, float* gw, float* ga_l, float* ga_r,
+                                    void* ws, size_t ws_bytes, void* stream) {
   clear_error();
   GNN_TRY(check_gat_dims(g, fin, heads, f, "gnn_gat_bwd"));
+  GNN_REQUIRE((t == nullptr) == (sg == nullptr), GNN_ERR_INVALID_ARG,
+              "gnn_gat_bwd: t and sg must be given together");
+  GNN_REQUIRE(t == nullptr || aligned16(t), GNN_ERR_INVALID_ARG, "gnn_gat_bwd: t must be 16-byte aligned");
   if (g->n == 0) return GNN_OK;
   GNN_REQUIRE(x && w && a_l && a_r && z && el && er && m && d && out && gout && gw && ga_l && ga_r,
               GNN_ERR_INVALID_ARG, "gnn_gat_bwd: null pointer");
@@ -667,15 +846,24 @@ extern "C" gnn_status_t gnn_gat_bwd(const gnn_graph_t* g, int fin, int heads, in
   const GatDims dm = make_dims(heads, f, slope);
   const GroupShape gs = pick_group(HF);
 
-  if (gat_blocked_applies(g, heads, f)) {
+  const bool blocked = gat_blocked_applies(g, heads, f);
+  // a4: destination side.  With t and sg stashed by the forward call it is a vertex pass;
+  // without them the sums are recomputed over the in-edges.
+  if (t) {
+    GNN_TRY(gat_dst_finish(g, dm, gout, t, out, sg, er, m, d, der, vstate, st));
+  } else if (blocked) {
     float* rows_buf = reinterpret_cast<float*>(base + L.blk_rows);
     float* scal_buf = reinterpret_cast<float*>(base + L.blk_scal);
     GNN_TRY(gat_blocked_bwd_dst(g, dm, z, el, er, m, d, out, gout, der, vstate, rows_buf, scal_buf, st));
+  } else {
+    GNN_TRY(dispatch_group<BwdDstLauncher>(gs, g, z, el, er, m, d, out, gout, dm, der, vstate, st));
+  }
+  if (blocked) {
+    float* rows_buf = reinterpret_cast<float*>(base + L.blk_rows);
+    float* scal_buf = reinterpret_cast<float*>(base + L.blk_scal);
     GNN_TRY(gat_blocked_bwd_src(g, dm, z, el, vstate, der, gout, a_l, a_r, dz, del, rows_buf,
                                 scal_buf, st));
   } else {
-    // a4: destination side
-    GNN_TRY(dispatch_group<BwdDstLauncher>(gs, g, z, el, er, m, d, out, gout, dm, der, vstate, st));
     // a5: source side
     GNN_TRY(dispatch_group<BwdSrcLauncher>(gs, g, z, el, (const float4*)vstate, (const float*)der,
                                            gout, a_l, a_r, dm, dz, del, st));

@@ -79,23 +79,29 @@ __global__ __launch_bounds__(kBlkThreads) void k_gat_softmax_stats(
 // MODE 1: bwd, dst side  acc[v]  += sum_e alpha_e g_e       z[u]      (acc = T), sg += sum alpha g
 // MODE 2: bwd, src side  acc[u]  += sum_e alpha_e           gout[v]   (acc = dz)
 //                        acc2[u] += sum_e alpha_e g_e       gout[v]   (acc2 = A2), sd += sum alpha g D[v]
+// MODE 3: forward that also stashes the destination-side sums of the backward pass:
+//                        acc = out as MODE 0, acc2[v] += sum_e alpha_e g_e z[u] (= t), sg += sum alpha g
 // A group of SL lanes owns (row, slice); lane li owns the float4 at column slice*4*SL + 4*li.
 template <int SL, int MODE>
 __global__ __launch_bounds__(kBlkThreads) void k_gat_blk(
     int32_t n_rows, const int32_t* __restrict__ order, const int32_t* __restrict__ bptr_b,
     const int32_t* __restrict__ bcol, const float* __restrict__ feat /* gathered rows: z or gout */,
     const float* __restrict__ el, const float* __restrict__ er, const float* __restrict__ m_in,
-    const float* __restrict__ d_in, const float4* __restrict__ vstate, GatDims dm, int sph,
-    int first, float* __restrict__ acc_buf, float* __restrict__ acc2_buf, float* __restrict__ scal_buf) {
+    const float* __restrict__ d_in, const float4* __restrict__ vstate, int32_t col_begin,
+    GatDims dm, int sph, int first, int narrow, float* __restrict__ acc_buf,
+    float* __restrict__ acc2_buf, float* __restrict__ scal_buf) {
   constexpr int G = kWave / SL;
   constexpr int GPB = G * (kBlkThreads / kWave);
-  constexpr int U = SL < 8 ? SL : 8;  // gathered rows in flight per lane
-  __shared__ float lds[GPB * 3 * SL];
+  constexpr int U = SL < 8 ? 4 : 8;   // gathered rows in flight per lane
+  constexpr bool DUAL = MODE == 2 || MODE == 3;  // two accumulators per lane
+  __shared__ __align__(16) float lds[GPB * 3 * SL];
 
   const int lane = threadIdx.x & 63;
   const int li = lane & (SL - 1);
   const int grp = threadIdx.x / SL;
   const int slice = blockIdx.x % kSlices;
+  const int H = dm.H, HF = dm.HF;
+  const int h = slice / sph;
   const int64_t r = (int64_t)(blockIdx.x / kSlices) * GPB + grp;
   if (r >= n_rows) return;
   const int32_t row = order[r];
@@ -106,8 +112,6 @@ __global__ __launch_bounds__(kBlkThreads) void k_gat_blk(
   float* l_p = lds + grp * 3 * SL + SL;
   float* l_p2 = lds + grp * 3 * SL + 2 * SL;
 
-  const int H = dm.H, HF = dm.HF;
-  const int h = slice / sph;
   const int col = slice * 4 * SL + 4 * li;
   const bool leader = (slice % sph) == 0;  // one slice per head keeps the per-head scalars
   const int64_t rh = (int64_t)row * H + h;
@@ -125,15 +129,23 @@ __global__ __launch_bounds__(kBlkThreads) void k_gat_blk(
   float scal = 0.f;
   if (!first) {
     acc = ld4(acc_buf + (int64_t)row * HF + col);
-    if (MODE == 2) acc2 = ld4(acc2_buf + (int64_t)row * HF + col);
+    if (DUAL) acc2 = ld4(acc2_buf + (int64_t)row * HF + col);
     if (MODE != 0 && leader && li == 0) scal = scal_buf[rh];
   }
 
+  // Gathered rows are addressed with 32-bit byte offsets when the matrix is below 4 GB
+  // (one 24-bit multiply-add per row instead of 64-bit arithmetic).
+  const char* feat_bytes = reinterpret_cast<const char*>(feat);
+  const uint32_t row_bytes = (uint32_t)HF * 4u, col_bytes = (uint32_t)col * 4u;
+
   float s_run = 0.f;
-  int32_t c_next = (beg + li < end) ? bcol[beg + li] : 0;
+  int32_t c_next = (beg + li < end) ? bcol[beg + li] : col_begin;
   for (int32_t c0 = beg; c0 < end; c0 += SL) {
-    const int32_t c = c_next;  // gathered vertex of edge c0 + li
     const bool e_ok = c0 + li < end;
+    // gathered vertex of edge c0 + li; lanes past the end point at the block's first
+    // vertex (a valid, cache-resident row) and get weight 0, so the row phase below
+    // needs no per-edge conditionals
+    const int32_t c = e_ok ? c_next : col_begin;
     if (c0 + SL + li < end) c_next = bcol[c0 + SL + li];
     l_idx[li] = c;
     // per-edge scalars: issue the loads now, use them after the row loads are in flight
@@ -144,14 +156,26 @@ __global__ __launch_bounds__(kBlkThreads) void k_gat_blk(
       else e_a = el[(int64_t)c * H + h];
     }
     wave_lds_fence();
-    const int cnt = min(SL, end - c0);
     float4 part = make_float4(0.f, 0.f, 0.f, 0.f), part2 = part;
 #pragma unroll
     for (int t0 = 0; t0 < SL; t0 += U) {
-      float4 rowv[U];
+      // the group's U gathered vertices in one go (broadcast LDS reads), then U row loads
+      int idv[U];
 #pragma unroll
-      for (int t = 0; t < U; ++t)
-        if (t0 + t < cnt) rowv[t] = ld4(feat + (int64_t)l_idx[t0 + t] * HF + col);
+      for (int q = 0; q < U / 4; ++q) {
+        const int4 i4 = *reinterpret_cast<const int4*>(l_idx + t0 + 4 * q);
+        idv[4 * q] = i4.x; idv[4 * q + 1] = i4.y; idv[4 * q + 2] = i4.z; idv[4 * q + 3] = i4.w;
+      }
+      float4 rowv[U];
+      if (narrow) {
+#pragma unroll
+        for (int t = 0; t < U; ++t)
+          rowv[t] = *reinterpret_cast<const float4*>(
+              feat_bytes + (__umul24((uint32_t)idv[t], row_bytes) + col_bytes));
+      } else {
+#pragma unroll
+        for (int t = 0; t < U; ++t) rowv[t] = ld4(feat + (int64_t)idv[t] * HF + col);
+      }
       if (t0 == 0) {
         float p = 0.f, p2 = 0.f;
         if (e_ok) {
@@ -167,77 +191,41 @@ __global__ __launch_bounds__(kBlkThreads) void k_gat_blk(
               p = raw > 0.f ? p : dm.slope * p;
               s_run += p;
             }
+            if (MODE == 3) {
+              p2 = raw > 0.f ? p : dm.slope * p;
+              s_run += p2;
+            }
           }
         }
         l_p[li] = p;
-        if (MODE == 2) l_p2[li] = p2;
+        if (DUAL) l_p2[li] = p2;
         wave_lds_fence();
       }
+      float pv[U], pv2[U];
 #pragma unroll
-      for (int t = 0; t < U; ++t)
-        if (t0 + t < cnt) {
-          fma4(part, l_p[t0 + t], rowv[t]);
-          if (MODE == 2) fma4(part2, l_p2[t0 + t], rowv[t]);
+      for (int q = 0; q < U / 4; ++q) {
+        const float4 p4 = *reinterpret_cast<const float4*>(l_p + t0 + 4 * q);
+        pv[4 * q] = p4.x; pv[4 * q + 1] = p4.y; pv[4 * q + 2] = p4.z; pv[4 * q + 3] = p4.w;
+        if (DUAL) {
+          const float4 q4 = *reinterpret_cast<const float4*>(l_p2 + t0 + 4 * q);
+          pv2[4 * q] = q4.x; pv2[4 * q + 1] = q4.y; pv2[4 * q + 2] = q4.z; pv2[4 * q + 3] = q4.w;
         }
+      }
+#pragma unroll
+      for (int t = 0; t < U; ++t) {
+        fma4(part, pv[t], rowv[t]);
+        if (DUAL) fma4(part2, pv2[t], rowv[t]);
+      }
     }
     add4(acc, part);
-    if (MODE == 2) add4(acc2, part2);
+    if (DUAL) add4(acc2, part2);
     wave_lds_fence();
   }
   st4(acc_buf + (int64_t)row * HF + col, acc);
-  if (MODE == 2) st4(acc2_buf + (int64_t)row * HF + col, acc2);
+  if (DUAL) st4(acc2_buf + (int64_t)row * HF + col, acc2);
   if (MODE != 0 && leader) {
     const float tot = group_sum_from<SL>(s_run, 1);
     if (li == 0) scal_buf[rh] = scal + tot;
-  }
-}
-
-// der[v,h] = <gout[v,h,:], T[v,h,:]> - D[v,h] sg[v,h],  D = <gout[v,h,:], out[v,h,:]>,
-// vstate[v,h] = (er, m, 1/d, D)
-__global__ void k_gat_blk_dst_finish(int64_t n, int H, int F, const float* __restrict__ gout,
-                                     const float* __restrict__ t_buf, const float* __restrict__ out,
-                                     const float* __restrict__ sg, const float* __restrict__ er,
-                                     const float* __restrict__ m_in, const float* __restrict__ d_in,
-                                     float* __restrict__ der, float4* __restrict__ vstate) {
-  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;  // (vertex, head)
-  if (i >= n * H) return;
-  const float* g = gout + i * F;
-  const float* t = t_buf + i * F;
-  const float* o = out + i * F;
-  float t1 = 0.f, D = 0.f;
-  for (int f = 0; f < F; f += 4) {
-    const float4 g4 = ld4(g + f);
-    t1 += dot4(g4, ld4(t + f));
-    D += dot4(g4, ld4(o + f));
-  }
-  der[i] = t1 - D * sg[i];
-  vstate[i] = make_float4(er[i], m_in[i], 1.f / d_in[i], D);
-}
-
-// del[u,h] = <z[u,h,:], A2[u,h,:]> - sd[u,h];  dz[u,h,:] += a_l[h,:] del[u,h] + a_r[h,:] der[u,h]
-__global__ void k_gat_blk_src_finish(int64_t n, int H, int F, const float* __restrict__ z,
-                                     const float* __restrict__ a2, const float* __restrict__ sd,
-                                     const float* __restrict__ der, const float* __restrict__ a_l,
-                                     const float* __restrict__ a_r, float* __restrict__ dz,
-                                     float* __restrict__ del) {
-  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;  // (vertex, head)
-  if (i >= n * H) return;
-  const int h = (int)(i % H);
-  const float* zz = z + i * F;
-  const float* aa = a2 + i * F;
-  float s = 0.f;
-  for (int f = 0; f < F; f += 4) s += dot4(ld4(zz + f), ld4(aa + f));
-  const float dl = s - sd[i];
-  const float dr = der[i];
-  del[i] = dl;
-  float* o = dz + i * F;
-  const float* al = a_l + (int64_t)h * F;
-  const float* ar = a_r + (int64_t)h * F;
-  for (int f = 0; f < F; f += 4) {
-    float4 v4 = ld4(o + f);
-    fma4(v4, dl, ld4(al + f));
-    fma4(v4, dr, ld4(ar + f));
-    st4(o + f, v4);
   }
 }
 
@@ -254,8 +242,30 @@ bool gat_blocked_applies(const gnn_graph_t* g, int heads, int f) {
 
 size_t gat_blocked_ws_bytes(const gnn_graph_t* g, int heads, int f) {
   if (!gat_blocked_applies(g, heads, f)) return 0;
-  return ws_granule(sizeof(float) * (size_t)g->n * heads * f) +
-         ws_granule(sizeof(float) * (size_t)g->n * heads);
+  return ws_granule(sizeof(float) * (size_t)g->n * heads * f) +   // T, then A2
+         ws_granule(sizeof(float) * (size_t)g->n * heads);        // sg, then sd
+}
+
+template <int SL, int MODE>
+static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* name, GatDims dm,
+                                  const float* feat,
+                                  const float* el, const float* er, const float* m, const float* d,
+                                  const float4* vstate, float* acc, float* acc2, float* scal,
+                                  hipStream_t st) {
+  const int sph = kSlices / dm.H;
+  const int gpb = kBlkThreads / SL;
+  const unsigned grid = (unsigned)(cdiv(g->n, gpb) * kSlices);
+  // 32-bit byte offsets (and 24-bit multiplies) reach every gathered row
+  const int narrow = (int64_t)g->n * dm.HF * 4 < ((int64_t)1 << 32) && g->n < (1 << 24);
+  for (int b = 0; b < g->nblk; ++b) {
+    const int32_t* bptr_b = g->bptr[side] + (int64_t)b * g->n;
+    ProfScope p(name, st);  // one timed bracket per launch
+    k_gat_blk<SL, MODE><<<grid, kBlkThreads, 0, st>>>(g->n, g->order[side], bptr_b, g->bcol[side], feat,
+                                                      el, er, m, d, vstate, b * g->block_cols, dm, sph,
+                                                      b == 0, narrow, acc, acc2, scal);
+    GNN_LAUNCH_CHECK();
+  }
+  return GNN_OK;
 }
 
 template <int MODE>
@@ -263,39 +273,26 @@ static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name,
                                const float* feat, const float* el, const float* er, const float* m,
                                const float* d, const float4* vstate, float* acc, float* acc2,
                                float* scal, hipStream_t st) {
-  const int SL = dm.HF / (4 * kSlices);
-  const int sph = kSlices / dm.H;
-  const int gpb = (kWave / SL) * (kBlkThreads / kWave);
-  const unsigned grid = (unsigned)(cdiv(g->n, gpb) * kSlices);
-  ProfScope p(name, st);
-  for (int b = 0; b < g->nblk; ++b) {
-    const int32_t* bptr_b = g->bptr[side] + (int64_t)b * g->n;
-    const int first = b == 0;
-#define GNN_BLK_LAUNCH(SL_)                                                                     \
-  k_gat_blk<SL_, MODE><<<grid, kBlkThreads, 0, st>>>(g->n, g->order[side], bptr_b, g->bcol[side], \
-                                                     feat, el, er, m, d, vstate, dm, sph, first,  \
-                                                     acc, acc2, scal)
-    switch (SL) {
-      case 4: GNN_BLK_LAUNCH(4); break;
-      case 8: GNN_BLK_LAUNCH(8); break;
-      case 16: GNN_BLK_LAUNCH(16); break;
-      case 32: GNN_BLK_LAUNCH(32); break;
-      default: set_error("gat blocked: unsupported slice width"); return GNN_ERR_UNSUPPORTED;
-    }
-#undef GNN_BLK_LAUNCH
-    GNN_LAUNCH_CHECK();
+  switch (dm.HF / (4 * kSlices)) {
+    case 4: return launch_blocks<4, MODE>(g, side, name, dm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
+    case 8: return launch_blocks<8, MODE>(g, side, name, dm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
+    case 16: return launch_blocks<16, MODE>(g, side, name, dm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
+    case 32: return launch_blocks<32, MODE>(g, side, name, dm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
   }
-  return GNN_OK;
+  set_error("gat blocked: unsupported slice width");
+  return GNN_ERR_UNSUPPORTED;
 }
 
 gnn_status_t gat_blocked_fwd(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
-                             const float* er, float* m, float* d, float* out, hipStream_t st) {
+                             const float* er, float* m, float* d, float* out, float* t, float* sg,
+                             hipStream_t st) {
   {
     ProfScope p("gat_softmax_stats", st);
     k_gat_softmax_stats<<<(unsigned)cdiv(g->n, kBlkThreads / kWave), kBlkThreads, 0, st>>>(
         g->n, g->order[0], g->indptr, g->indices, el, er, dm, m, d);
     GNN_LAUNCH_CHECK();
   }
+  if (t) return run_blocks<3>(g, 0, "gat_fwd_fused", dm, z, el, er, m, d, nullptr, out, t, sg, st);
   return run_blocks<0>(g, 0, "gat_fwd_fused", dm, z, el, er, m, d, nullptr, out, nullptr, nullptr, st);
 }
 
@@ -304,26 +301,16 @@ gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* 
                                  const float* gout, float* der, float4* vstate, float* t_buf,
                                  float* sg_buf, hipStream_t st) {
   GNN_TRY(run_blocks<1>(g, 0, "gat_bwd_dst", dm, z, el, er, m, d, nullptr, t_buf, nullptr, sg_buf, st));
-  ProfScope p("gat_bwd_dst_finish", st);
-  const int64_t cnt = (int64_t)g->n * dm.H;
-  k_gat_blk_dst_finish<<<(unsigned)cdiv(cnt, 256), 256, 0, st>>>(g->n, dm.H, dm.F, gout, t_buf, out,
-                                                                 sg_buf, er, m, d, der, vstate);
-  GNN_LAUNCH_CHECK();
-  return GNN_OK;
+  return gat_dst_finish(g, dm, gout, t_buf, out, sg_buf, er, m, d, der, vstate, st);
 }
 
 gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                                  const float4* vstate, const float* der, const float* gout,
                                  const float* a_l, const float* a_r, float* dz, float* del,
                                  float* a2_buf, float* sd_buf, hipStream_t st) {
-  GNN_TRY(run_blocks<2>(g, 1, "gat_bwd_src", dm, gout, el, nullptr, nullptr, nullptr, vstate, dz,
-                        a2_buf, sd_buf, st));
-  ProfScope p("gat_bwd_src_finish", st);
-  const int64_t cnt = (int64_t)g->n * dm.H;
-  k_gat_blk_src_finish<<<(unsigned)cdiv(cnt, 256), 256, 0, st>>>(g->n, dm.H, dm.F, z, a2_buf, sd_buf,
-                                                                 der, a_l, a_r, dz, del);
-  GNN_LAUNCH_CHECK();
-  return GNN_OK;
+  GNN_TRY(run_blocks<2>(g, 1, "gat_bwd_src", dm, gout, el, nullptr, nullptr, nullptr, vstate, dz, a2_buf,
+                        sd_buf, st));
+  return gat_src_finish(g, dm, z, a2_buf, sd_buf, der, a_l, a_r, dz, del, st);
 }
 
 }  // namespace gnn

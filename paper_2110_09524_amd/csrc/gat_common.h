@@ -30,8 +30,17 @@ __device__ __forceinline__ float leaky(float x, float slope) { return x > 0.f ? 
 // slice inside one head.
 bool gat_blocked_applies(const gnn_graph_t* g, int heads, int f);
 size_t gat_blocked_ws_bytes(const gnn_graph_t* g, int heads, int f);  // extra workspace (bwd)
+// t, sg: optional stash of the destination-side backward sums (both or neither)
 gnn_status_t gat_blocked_fwd(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
-                             const float* er, float* m, float* d, float* out, hipStream_t st);
+                             const float* er, float* m, float* d, float* out, float* t, float* sg,
+                             hipStream_t st);
+// vertex-side closing steps shared by both paths (gat.hip)
+gnn_status_t gat_dst_finish(const gnn_graph_t* g, GatDims dm, const float* gout, const float* t,
+                            const float* out, const float* sg, const float* er, const float* m,
+                            const float* d, float* der, float4* vstate, hipStream_t st);
+gnn_status_t gat_src_finish(const gnn_graph_t* g, GatDims dm, const float* z, const float* a2,
+                            const float* sd, const float* der, const float* a_l, const float* a_r,
+                            float* dz, float* del, hipStream_t st);
 // writes der, vstate (like the single-launch destination kernel); t_buf is an [n, HF] scratch
 gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                                  const float* er, const float* m, const float* d, const float* out,

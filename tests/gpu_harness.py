@@ -63,7 +63,28 @@ def assert_close(name, got, ref, rtol=RTOL, atol=ATOL, reduce_scale=False, row_s
             f"gpu={got[i]:.9g} oracle={ref[i]:.9g} err={err[i]:.3g} tol={tol[i]:.3g}")
 
 
-def run_gat(c, backward=True, want_gx=True, graph=None):
+def gat_kink_masks(indptr, fwd, tol=1e-5):
+    """LeakyReLU' jumps at a raw score of exactly 0, and the fp32 path decides the sign
+    from scores that carry ~1e-6 of rounding.  An edge whose fp64 raw score lies within
+    `tol` of 0 may therefore legitimately take either slope; what depends on that choice
+    is excluded from the comparison: (vertex, head) entries of the destination-side sums
+    of a row holding such an edge, and the input-gradient rows of its two endpoints.
+    Returns (amb_vh [n, heads] bool, amb_vertex [n] bool)."""
+    amb_e = np.abs(fwd["M0"]) < tol
+    n = indptr.shape[0] - 1
+    amb_vh = np.zeros((n, amb_e.shape[1]), dtype=bool)
+    amb_vertex = np.zeros(n, dtype=bool)
+    if amb_e.any():
+        e_idx, h_idx = np.nonzero(amb_e)
+        amb_vh[fwd["dst"][e_idx], h_idx] = True
+        amb_vertex[fwd["dst"][e_idx]] = True
+        amb_vertex[fwd["src"][e_idx]] = True
+    return amb_vh, amb_vertex
+
+
+def run_gat(c, backward=True, want_gx=True, graph=None, stash=True):
+    """stash=True: the forward call writes t and sg and the backward call uses them;
+    stash=False: the backward call recomputes them over the in-edges."""
     n, fin, H, F = c["n"], c["fin"], c["heads"], c["f"]
     HF = H * F
     indptr, indices = dev(c["indptr"]), dev(c["indices"])
@@ -71,14 +92,19 @@ def run_gat(c, backward=True, want_gx=True, graph=None):
     x, w, a_l, a_r = dev(c["x"]), dev(c["w"]), dev(c["a_l"]), dev(c["a_r"])
     z, out = empty((n, HF)), empty((n, HF))
     el, er, m, d = (empty((n, H)) for _ in range(4))
-    pk.gnn_gat_fwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out)
+    ws = workspace(pk.gnn_gat_workspace_bytes(g, fin, H, F))
+    t = empty((n, HF)) if stash else None
+    sg = empty((n, H)) if stash else None
+    pk.gnn_gat_fwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, t, sg, ws)
     res = dict(z=z, el=el, er=er, m=m, d=d, out=out)
+    if stash:
+        res.update(t=t, sg=sg)
     if backward:
         gout = dev(c["gout"])
-        ws = workspace(pk.gnn_gat_workspace_bytes(g, fin, H, F))
+        ws.fill_(0xFF)      # nothing may survive in the workspace between the two calls
         gx = empty((n, fin)) if want_gx else None
         gw, ga_l, ga_r = empty((fin, HF)), empty((H, F)), empty((H, F))
-        pk.gnn_gat_bwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, gout,
+        pk.gnn_gat_bwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, t, sg, gout,
                        gx, gw, ga_l, ga_r, ws)
         res.update(gw=gw, ga_l=ga_l, ga_r=ga_r)
         if want_gx:

@@ -1,0 +1,87 @@
+"""Full-size GAT workload (the one bench.py times, same launch configuration):
+sampled outputs against the oracle, and properties that hold at any size."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def c4():
+    from workloads import make
+    print("full size: generating gat_c4", flush=True)
+    return make("gat_c4")
+
+
+def test_gat_c4_sampled_rows_and_consistency(c4):
+    import paper_2110_09524_amd as pk
+    from gpu_harness import assert_close, dev, gat_kink_masks, run_gat
+    from oracle import gat as og
+    from oracle.segments import restrict_rows, segment_sum
+    c = c4
+    n, H, F = c["n"], c["heads"], c["f"]
+    HF = H * F
+    ip, ix = c["indptr"], c["indices"]
+    g = pk.Graph(dev(ip), dev(ix))
+    assert g.blocked(0)[0] > 1                      # the column-blocked kernels are in use
+    print("full size: GPU fwd+bwd", flush=True)
+    res = run_gat(c, graph=g)
+
+    deg = np.diff(ip)
+    outdeg = np.bincount(ix, minlength=n)
+    rng = np.random.default_rng(99)
+    # destinations: the biggest hub, the smallest row, and a seeded sample
+    dst_rows = np.unique(np.concatenate([[int(np.argmax(deg)), int(np.argmin(deg))],
+                                         rng.choice(n, size=30, replace=False)]))
+    # sources whose full backward neighbourhood the oracle can afford: small out-degree
+    cand = np.flatnonzero(outdeg <= np.partition(outdeg, 2000)[2000])
+    src_rows = rng.choice(cand, size=3, replace=False)
+    # every destination that a sampled source points to, plus the sampled sources themselves
+    dst_of = np.repeat(np.arange(n, dtype=np.int64), deg)
+    hit = np.isin(ix, src_rows)
+    rows = np.unique(np.concatenate([dst_rows, dst_of[hit], src_rows]))
+    print(f"full size: oracle on the in-edges of {rows.size} rows", flush=True)
+    rip, rix, _ = restrict_rows(ip, ix, rows)
+    Ht = c["x"].astype(np.float64) @ c["w"].astype(np.float64)
+    fwd = og.gat_forward(rip, rix, c["x"], c["w"], c["a_l"], c["a_r"], c["slope"], Ht=Ht)
+    bwd = og.gat_backward(rip, rix, c["x"], c["w"], c["a_l"], c["a_r"], c["slope"], c["gout"], fwd)
+
+    print("full size: comparing sampled rows", flush=True)
+    assert_close("z", res["z"][rows], Ht[rows])
+    assert_close("out", res["out"][rows], fwd["out"][rows])
+    assert_close("m", res["m"][rows], fwd["mx"][rows])
+    assert_close("d", res["d"][rows], fwd["den"][rows])
+    ag = fwd["M2"] * np.where(fwd["M0"] > 0, 1.0, c["slope"])
+    amb_vh, amb_vertex = gat_kink_masks(rip, fwd)
+    print(f"full size: {int(amb_vh.sum())} (row, head) pairs sit on the LeakyReLU kink", flush=True)
+    keep_vh = ~amb_vh[rows]
+    sg_ref = segment_sum(rip, ag)[rows]
+    assert_close("sg", np.where(keep_vh, res["sg"][rows], sg_ref), sg_ref)
+    t_ref = segment_sum(rip, ag[:, :, None] * fwd["Ht"][fwd["src"]]).reshape(n, HF)[rows]
+    assert_close("t", np.where(np.repeat(keep_vh, F, axis=1), res["t"][rows], t_ref), t_ref)
+    src_rows = src_rows[~amb_vertex[src_rows]]
+    assert src_rows.size >= 1
+    # input gradient of the sampled sources: all their out-edges and those edges' whole
+    # destination rows are inside the restricted graph, so the oracle's rows are complete
+    assert_close("gx", res["gx"][src_rows], bwd["gx"][src_rows], row_scale=True)
+
+    print("full size: properties", flush=True)
+    # <gw, w> = <dz, z> = <gx, x>: both products contract the same dz
+    gw_w = float((res["gw"].astype(np.float64) * c["w"]).sum())
+    gx_x = float((res["gx"].astype(np.float64) * c["x"]).sum())
+    assert abs(gw_w - gx_x) <= 1e-4 * max(abs(gw_w), abs(gx_x)) + 1e-3
+    # softmax weights sum to one: out is a convex combination, so it is bounded by z
+    assert (np.abs(res["out"]).max(axis=0) <= np.abs(res["z"]).max(axis=0) * (1 + 1e-5)).all()
+    assert (res["d"] >= 1.0 - 1e-6).all()
+    # the single-launch kernels and the stash-free backward are independent routes to the
+    # same numbers: every output, including the |V|-long parameter reductions, must agree
+    pk.gnn_config_set("force_simple_kernels", 1)
+    try:
+        res2 = run_gat(c, graph=g, stash=False)
+    finally:
+        pk.gnn_config_set("force_simple_kernels", 0)
+    for k in ("out", "m", "d", "gw", "ga_l", "ga_r"):
+        assert_close(k + " (two kernel paths)", res[k], res2[k],
+                     reduce_scale=k in ("gw", "ga_l", "ga_r"))
+    assert_close("gx (two kernel paths)", res["gx"], res2["gx"], row_scale=True)
+    g.close()

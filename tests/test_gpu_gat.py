@@ -19,8 +19,11 @@ def oracle_all(c, backward=True):
 
 
 def compare(c, res, fwd, bwd):
-    from gpu_harness import assert_close
+    from gpu_harness import assert_close, gat_kink_masks
     n, H, F = c["n"], c["heads"], c["f"]
+    amb_vh, amb_vertex = gat_kink_masks(c["indptr"], fwd)
+    keep_vh = ~amb_vh
+    keep_hf = np.repeat(keep_vh, F, axis=1)
     Ht = fwd["Ht"].reshape(n, H * F)
     assert_close("z", res["z"], Ht)
     assert_close("el", res["el"], np.einsum("nhf,hf->nh", fwd["Ht"], c["a_l"].astype(np.float64)))
@@ -28,8 +31,17 @@ def compare(c, res, fwd, bwd):
     assert_close("m", res["m"], fwd["mx"])
     assert_close("d", res["d"], fwd["den"])
     assert_close("out", res["out"], fwd["out"])
+    if "t" in res:
+        # stashed destination-side sums: t = sum alpha_e g_e Ht[u], sg = sum alpha_e g_e,
+        # g_e = LeakyReLU'(M0_e), written out from the oracle's materialised tensors
+        from oracle.segments import segment_sum
+        ag = fwd["M2"] * np.where(fwd["M0"] > 0, 1.0, c["slope"])
+        sg_ref = segment_sum(c["indptr"], ag)
+        t_ref = segment_sum(c["indptr"], ag[:, :, None] * fwd["Ht"][fwd["src"]]).reshape(n, H * F)
+        assert_close("sg", np.where(keep_vh, res["sg"], sg_ref), sg_ref)
+        assert_close("t", np.where(keep_hf, res["t"], t_ref), t_ref)
     if bwd is not None:
-        assert_close("gx", res["gx"], bwd["gx"], row_scale=True)
+        assert_close("gx", np.where(amb_vertex[:, None], bwd["gx"], res["gx"]), bwd["gx"], row_scale=True)
         assert_close("gw", res["gw"], bwd["gw"], reduce_scale=True)
         assert_close("ga_l", res["ga_l"], bwd["ga_l"], reduce_scale=True)
         assert_close("ga_r", res["ga_r"], bwd["ga_r"], reduce_scale=True)
@@ -62,6 +74,8 @@ def test_workload_forward_backward(name):
     c = make(name)
     fwd, bwd = oracle_all(c)
     compare(c, run_gat(c), fwd, bwd)
+    # without the stash the backward call recomputes the destination-side sums
+    compare(c, run_gat(c, stash=False), fwd, bwd)
 
 
 @pytest.mark.parametrize("fin,H,F", [(7, 1, 4), (33, 3, 8), (5, 2, 12), (19, 5, 4), (64, 2, 64),
@@ -130,12 +144,16 @@ def test_bad_arguments_raise():
         pk.gnn_gat_fwd(g, 64, 1, 6, 0.2, x, w, a6, a6, z, el, er, m, d, out)
     assert e.value.status == 4
     a = dev(c["a_l"])
+    with pytest.raises(pk.GnnError) as e:        # t without sg
+        pk.gnn_gat_fwd(g, 64, 1, 16, 0.2, x, w, a, a, z, el, er, m, d, out, empty((n, 16)), None)
+    assert e.value.status == 1
     pk.gnn_gat_fwd(g, 64, 1, 16, 0.2, x, w, a, a, z, el, er, m, d, out)
     need = pk.gnn_gat_workspace_bytes(g, 64, 1, 16)
     assert need > 0
     with pytest.raises(pk.GnnError) as e:        # workspace too small
-        pk.gnn_gat_bwd(g, 64, 1, 16, 0.2, x, w, a, a, z, el, er, m, d, out, dev(c["gout"]),
-                       None, empty((64, 16)), empty((1, 16)), empty((1, 16)), workspace(need - 256))
+        pk.gnn_gat_bwd(g, 64, 1, 16, 0.2, x, w, a, a, z, el, er, m, d, out, None, None,
+                       dev(c["gout"]), None, empty((64, 16)), empty((1, 16)), empty((1, 16)),
+                       workspace(need - 256))
     assert e.value.status == 3
     torch.cuda.synchronize()
 
@@ -161,7 +179,7 @@ def test_column_blocked_path(block_cols, H, F):
         assert g.blocked(0)[0] == -(-c["n"] // block_cols)
         res = run_gat(c, graph=g)
     finally:
-        pk.gnn_config_set("block_cols", 16384)
+        pk.gnn_config_set("block_cols", 24576)
     compare(c, res, fwd, bwd)
     # same inputs through the single-launch kernels: both paths must agree with the oracle
     pk.gnn_config_set("force_simple_kernels", 1)
@@ -171,3 +189,4 @@ def test_column_blocked_path(block_cols, H, F):
         pk.gnn_config_set("force_simple_kernels", 0)
     compare(c, res2, fwd, bwd)
     assert np.array_equal(res["m"], res2["m"])      # the row maximum is exact on both paths
+    compare(c, run_gat(c, graph=g, stash=False), fwd, bwd)   # blocked recompute of the dst side

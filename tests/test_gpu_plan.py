@@ -82,7 +82,7 @@ def test_blocked_edge_lists(block_cols):
     try:
         g = pk.Graph(dev(indptr), dev(indices))
     finally:
-        pk.gnn_config_set("block_cols", 16384)
+        pk.gnn_config_set("block_cols", 24576)
     ip_t, ix_t, _ = (t.cpu().numpy() for t in g.csc())
     for side, ptr, cols in ((0, indptr, indices), (1, ip_t, ix_t)):
         nb, bc, bptr, bcol = g.blocked(side)
