@@ -618,7 +618,7 @@ template <int L, int NV>
 __global__ __launch_bounds__(kBlock) void k_gat_dst_finish(
     int32_t n_rows, const float* __restrict__ gout, const float* __restrict__ t_in,
     const float* __restrict__ out, const float* __restrict__ sg, const float* __restrict__ er,
-    const float* __restrict__ m_in, const float* __restrict__ d_in, GatDims dm,
+    const float* __restrict__ m_in, const float* __restrict__ d_in, GatDims dm, int head_major,
     float* __restrict__ der, float4* __restrict__ vstate) {
   constexpr int G = kWave / L;
   constexpr int GPB = G * (kBlock / kWave);
@@ -648,7 +648,9 @@ __global__ __launch_bounds__(kBlock) void k_gat_dst_finish(
     const float D = head_sum<L, NV>(l_red + L * NV, h, dm.F);
     const int64_t i = v * H + h;
     der[i] = t1 - D * sg[i];
-    vstate[i] = make_float4(er[i], m_in[i], 1.f / d_in[i], D);
+    // head-major ([H][n]) for the column-blocked source kernel, whose XCD slice reads one
+    // head only: a block of gathered vertices then spans 16 B per vertex instead of 16*H
+    vstate[head_major ? (int64_t)h * n_rows + v : i] = make_float4(er[i], m_in[i], 1.f / d_in[i], D);
   }
 }
 
@@ -702,11 +704,11 @@ template <int L, int NV>
 struct DstFinishLauncher {
   static gnn_status_t run(const gnn_graph_t* g, const float* gout, const float* t, const float* out,
                           const float* sg, const float* er, const float* m, const float* d, GatDims dm,
-                          float* der, float4* vstate, hipStream_t st) {
+                          int head_major, float* der, float4* vstate, hipStream_t st) {
     constexpr int GPB = (kWave / L) * (kBlock / kWave);
     ProfScope p("gat_bwd_dst_finish", st);
     k_gat_dst_finish<L, NV><<<(unsigned)cdiv(g->n, GPB), kBlock, 0, st>>>(g->n, gout, t, out, sg, er, m,
-                                                                         d, dm, der, vstate);
+                                                                         d, dm, head_major, der, vstate);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
   }
@@ -759,9 +761,10 @@ struct BwdSrcLauncher {
 
 gnn_status_t gat_dst_finish(const gnn_graph_t* g, GatDims dm, const float* gout, const float* t,
                             const float* out, const float* sg, const float* er, const float* m,
-                            const float* d, float* der, float4* vstate, hipStream_t st) {
-  return dispatch_group<DstFinishLauncher>(pick_group(dm.HF), g, gout, t, out, sg, er, m, d, dm, der,
-                                           vstate, st);
+                            const float* d, int head_major, float* der, float4* vstate,
+                            hipStream_t st) {
+  return dispatch_group<DstFinishLauncher>(pick_group(dm.HF), g, gout, t, out, sg, er, m, d, dm,
+                                           head_major, der, vstate, st);
 }
 gnn_status_t gat_src_finish(const gnn_graph_t* g, GatDims dm, const float* z, const float* a2,
                             const float* sd, const float* der, const float* a_l, const float* a_r,
@@ -850,7 +853,7 @@ extern "C" gnn_status_t gnn_gat_bwd(const gnn_graph_t* g, int fin, int heads, in
   // a4: destination side.  With t and sg stashed by the forward call it is a vertex pass;
   // without them the sums are recomputed over the in-edges.
   if (t) {
-    GNN_TRY(gat_dst_finish(g, dm, gout, t, out, sg, er, m, d, der, vstate, st));
+    GNN_TRY(gat_dst_finish(g, dm, gout, t, out, sg, er, m, d, blocked ? 1 : 0, der, vstate, st));
   } else if (blocked) {
     float* rows_buf = reinterpret_cast<float*>(base + L.blk_rows);
     float* scal_buf = reinterpret_cast<float*>(base + L.blk_scal);

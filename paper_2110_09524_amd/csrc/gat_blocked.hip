@@ -152,7 +152,7 @@ __global__ __launch_bounds__(kBlkThreads) void k_gat_blk(
     float e_a = 0.f;
     float4 vs = make_float4(0.f, 0.f, 1.f, 0.f);
     if (e_ok) {
-      if (MODE == 2) vs = vstate[(int64_t)c * H + h];  // (er, m, 1/d, D) of the destination
+      if (MODE == 2) vs = vstate[(int64_t)h * n_rows + c];  // head-major (er, m, 1/d, D) of the destination
       else e_a = el[(int64_t)c * H + h];
     }
     wave_lds_fence();
@@ -301,7 +301,7 @@ gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* 
                                  const float* gout, float* der, float4* vstate, float* t_buf,
                                  float* sg_buf, hipStream_t st) {
   GNN_TRY(run_blocks<1>(g, 0, "gat_bwd_dst", dm, z, el, er, m, d, nullptr, t_buf, nullptr, sg_buf, st));
-  return gat_dst_finish(g, dm, gout, t_buf, out, sg_buf, er, m, d, der, vstate, st);
+  return gat_dst_finish(g, dm, gout, t_buf, out, sg_buf, er, m, d, 1, der, vstate, st);
 }
 
 gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,

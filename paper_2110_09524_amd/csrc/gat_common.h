@@ -37,7 +37,8 @@ gnn_status_t gat_blocked_fwd(const gnn_graph_t* g, GatDims dm, const float* z, c
 // vertex-side closing steps shared by both paths (gat.hip)
 gnn_status_t gat_dst_finish(const gnn_graph_t* g, GatDims dm, const float* gout, const float* t,
                             const float* out, const float* sg, const float* er, const float* m,
-                            const float* d, float* der, float4* vstate, hipStream_t st);
+                            const float* d, int head_major, float* der, float4* vstate,
+                            hipStream_t st);
 gnn_status_t gat_src_finish(const gnn_graph_t* g, GatDims dm, const float* z, const float* a2,
                             const float* sd, const float* der, const float* a_l, const float* a_r,
                             float* dz, float* del, hipStream_t st);
