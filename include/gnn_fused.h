@@ -149,7 +149,8 @@ gnn_status_t gnn_linear_fwd(int64_t n, int fin, int fout, const float* x, const 
  * Sec. 6 (recompute only if computation / memory is O(1); here it is |E|/|V|) they
  * are worth stashing: the backward call then skips one whole pass over the edges.
  * Pass NULL for inference, or to have the backward call recompute them.
- * The forward call needs no workspace (ws may be NULL).
+ * The workspace is optional in the forward call (NULL is accepted; on graphs that
+ * take the column-blocked kernels it holds a head-major copy of el, which is faster).
  * ------------------------------------------------------------------------- */
 size_t gnn_gat_workspace_bytes(const gnn_graph_t* graph, int fin, int heads, int f);
 

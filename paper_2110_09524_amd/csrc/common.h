@@ -111,4 +111,5 @@ struct gnn_graph {
   int32_t nblk;
   int32_t* bptr[2];
   int32_t* bcol[2];
+  int32_t* bseg[2];  // (begin, end) of row order[r] in block b at [b*n + r], two ints each
 };

@@ -536,7 +536,7 @@ static int param_blocks(int64_t n) {
 
 struct GatWs {
   size_t total;
-  size_t dz, vstate, der, del, partial, gemm, blk_rows, blk_scal;
+  size_t dz, vstate, der, del, partial, gemm, blk_rows, blk_scal, blk_elt;
   int split_k, nblk;
 };
 
@@ -557,6 +557,7 @@ static GatWs gat_ws_layout(const gnn_graph_t* g, int fin, int H, int F) {
   const bool blocked = gat_blocked_applies(g, H, F);
   w.blk_rows = take(blocked ? sizeof(float) * n * HF : 0);  // T, then A2
   w.blk_scal = take(blocked ? sizeof(float) * n * H : 0);   // sg, then sd
+  w.blk_elt = take(blocked ? sizeof(float) * n * H : 0);    // head-major el
   w.total = off;
   return w;
 }
@@ -787,8 +788,6 @@ extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, in
                                     float* z, float* el, float* er, float* m, float* d, float* out,
                                     float* t, float* sg, void* ws, size_t ws_bytes, void* stream) {
   clear_error();
-  (void)ws;  // the forward pass needs no scratch
-  (void)ws_bytes;
   GNN_TRY(check_gat_dims(g, fin, heads, f, "gnn_gat_fwd"));
   GNN_REQUIRE((t == nullptr) == (sg == nullptr), GNN_ERR_INVALID_ARG,
               "gnn_gat_fwd: t and sg must be given together");
@@ -810,8 +809,14 @@ extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, in
     GNN_LAUNCH_CHECK();
   }
   // a3: fused score -> softmax -> aggregate
-  if (gat_blocked_applies(g, heads, f))
-    return gat_blocked_fwd(g, make_dims(heads, f, slope), z, el, er, m, d, out, t, sg, st);
+  if (gat_blocked_applies(g, heads, f)) {
+    // optional scratch: a head-major copy of el makes the per-edge scalar gathers denser
+    const GatWs L = gat_ws_layout(g, fin, heads, f);
+    float* el_t = nullptr;
+    if (ws != nullptr && ws_bytes >= L.total && aligned16(ws))
+      el_t = reinterpret_cast<float*>(static_cast<char*>(ws) + L.blk_elt);
+    return gat_blocked_fwd(g, make_dims(heads, f, slope), z, el, er, m, d, out, t, sg, el_t, st);
+  }
   return dispatch_group<FwdLauncher>(pick_group(HF), g, (const float*)z, (const float*)el,
                                      (const float*)er, make_dims(heads, f, slope), out, m, d, t, sg, st);
 }
@@ -857,7 +862,9 @@ extern "C" gnn_status_t gnn_gat_bwd(const gnn_graph_t* g, int fin, int heads, in
   } else if (blocked) {
     float* rows_buf = reinterpret_cast<float*>(base + L.blk_rows);
     float* scal_buf = reinterpret_cast<float*>(base + L.blk_scal);
-    GNN_TRY(gat_blocked_bwd_dst(g, dm, z, el, er, m, d, out, gout, der, vstate, rows_buf, scal_buf, st));
+    float* el_t = reinterpret_cast<float*>(base + L.blk_elt);
+    GNN_TRY(gat_blocked_bwd_dst(g, dm, z, el, er, m, d, out, gout, der, vstate, rows_buf, scal_buf, el_t,
+                                st));
   } else {
     GNN_TRY(dispatch_group<BwdDstLauncher>(gs, g, z, el, er, m, d, out, gout, dm, der, vstate, st));
   }

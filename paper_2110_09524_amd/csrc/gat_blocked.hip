@@ -82,19 +82,36 @@ __global__ __launch_bounds__(kBlkThreads) void k_gat_softmax_stats(
 // MODE 3: forward that also stashes the destination-side sums of the backward pass:
 //                        acc = out as MODE 0, acc2[v] += sum_e alpha_e g_e z[u] (= t), sg += sum alpha g
 // A group of SL lanes owns (row, slice); lane li owns the float4 at column slice*4*SL + 4*li.
+//
+// Each group walks kRowsPerGroup consecutive rows of the degree order, software-pipelined:
+// while the edges of one row are processed, the segment bounds, the first index chunk,
+// the per-row scalars and the running sums of the next row are already in flight, so the
+// chain of dependent loads at the start of a row is paid once per group, not once per row.
+constexpr int kRowsPerGroup = 4;
+
+template <int MODE>
+struct BlkRow {
+  int32_t row, beg, end, c_first;
+  float r_a, r_m, r_d, scal;
+  float4 acc, acc2;
+};
+
 template <int SL, int MODE>
 __global__ __launch_bounds__(kBlkThreads) void k_gat_blk(
-    int32_t n_rows, const int32_t* __restrict__ order, const int32_t* __restrict__ bptr_b,
+    int32_t n_rows, const int32_t* __restrict__ order, const int2* __restrict__ bseg_b,
     const int32_t* __restrict__ bcol, const float* __restrict__ feat /* gathered rows: z or gout */,
     const float* __restrict__ el, const float* __restrict__ er, const float* __restrict__ m_in,
     const float* __restrict__ d_in, const float4* __restrict__ vstate, int32_t col_begin,
-    GatDims dm, int sph, int first, int narrow, float* __restrict__ acc_buf,
-    float* __restrict__ acc2_buf, float* __restrict__ scal_buf) {
+    GatDims dm, int sph, int first, int narrow, int el_hm /* el is head-major [H][n] */,
+    float* __restrict__ acc_buf, float* __restrict__ acc2_buf, float* __restrict__ scal_buf) {
   constexpr int G = kWave / SL;
   constexpr int GPB = G * (kBlkThreads / kWave);
+  constexpr int R = kRowsPerGroup;
   constexpr int U = SL < 8 ? 4 : 8;   // gathered rows in flight per lane
   constexpr bool DUAL = MODE == 2 || MODE == 3;  // two accumulators per lane
-  __shared__ __align__(16) float lds[GPB * 3 * SL];
+  constexpr int GS = 3 * SL + 4 * R;  // LDS floats per group: idx | p | p2 | row, beg, end, pad
+  static_assert(SL >= R, "one lane per pipelined row loads its metadata");
+  __shared__ __align__(16) float lds[GPB * GS];
 
   const int lane = threadIdx.x & 63;
   const int li = lane & (SL - 1);
@@ -102,131 +119,183 @@ __global__ __launch_bounds__(kBlkThreads) void k_gat_blk(
   const int slice = blockIdx.x % kSlices;
   const int H = dm.H, HF = dm.HF;
   const int h = slice / sph;
-  const int64_t r = (int64_t)(blockIdx.x / kSlices) * GPB + grp;
-  if (r >= n_rows) return;
-  const int32_t row = order[r];
-  const int32_t beg = bptr_b[row], end = bptr_b[row + 1];
-  if (beg == end && !first) return;  // nothing to add to this row in this block
+  const int64_t r0 = ((int64_t)(blockIdx.x / kSlices) * GPB + grp) * R;
+  if (r0 >= n_rows) return;
 
-  int* l_idx = reinterpret_cast<int*>(lds + grp * 3 * SL);
-  float* l_p = lds + grp * 3 * SL + SL;
-  float* l_p2 = lds + grp * 3 * SL + 2 * SL;
+  int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
+  float* l_p = lds + grp * GS + SL;
+  float* l_p2 = lds + grp * GS + 2 * SL;
+  int* l_row = reinterpret_cast<int*>(lds + grp * GS + 3 * SL);
+  int* l_beg = l_row + R;
+  int* l_end = l_row + 2 * R;
 
   const int col = slice * 4 * SL + 4 * li;
   const bool leader = (slice % sph) == 0;  // one slice per head keeps the per-head scalars
-  const int64_t rh = (int64_t)row * H + h;
 
-  // per-row scalars of this head
-  float r_a = 0.f, r_m = 0.f, r_invd = 1.f;
-  if (MODE == 2) {
-    r_a = el[rh];  // row is a source: its el
-  } else {
-    r_a = er[rh];  // row is a destination: its er, max, 1/denominator
-    r_m = m_in[rh];
-    r_invd = 1.f / d_in[rh];
+  // segment bounds of the group's R rows inside this column block, one lane each
+  if (li < R) {
+    const int64_t r = r0 + li;
+    int32_t row = -1;
+    int2 seg = make_int2(0, 0);
+    if (r < n_rows) {
+      row = order[r];
+      seg = bseg_b[r];
+      if (!first && seg.x == seg.y) row = -1;  // nothing to add to this row in this block
+    }
+    l_row[li] = row;
+    l_beg[li] = seg.x;
+    l_end[li] = seg.y;
   }
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f), acc2 = acc;
-  float scal = 0.f;
-  if (!first) {
-    acc = ld4(acc_buf + (int64_t)row * HF + col);
-    if (DUAL) acc2 = ld4(acc2_buf + (int64_t)row * HF + col);
-    if (MODE != 0 && leader && li == 0) scal = scal_buf[rh];
-  }
+  wave_lds_fence();
+
+  // issue every load a row needs before its edge loop
+  auto fetch = [&](int k, BlkRow<MODE>& s) {
+    s.row = l_row[k];
+    s.beg = l_beg[k];
+    s.end = l_end[k];
+    s.c_first = col_begin;
+    s.r_a = 0.f; s.r_m = 0.f; s.r_d = 1.f; s.scal = 0.f;
+    s.acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    s.acc2 = s.acc;
+    if (s.row < 0) return;
+    if (s.beg + li < s.end) s.c_first = bcol[s.beg + li];
+    const int64_t rh = (int64_t)s.row * H + h;
+    if (MODE == 2) {
+      s.r_a = el[rh];  // row is a source: its el
+    } else {
+      s.r_a = er[rh];  // row is a destination: its er, max, denominator
+      s.r_m = m_in[rh];
+      s.r_d = d_in[rh];
+    }
+    if (!first) {
+      s.acc = ld4(acc_buf + (int64_t)s.row * HF + col);
+      if (DUAL) s.acc2 = ld4(acc2_buf + (int64_t)s.row * HF + col);
+      if (MODE != 0 && leader && li == 0) s.scal = scal_buf[rh];
+    }
+  };
 
   // Gathered rows are addressed with 32-bit byte offsets when the matrix is below 4 GB
   // (one 24-bit multiply-add per row instead of 64-bit arithmetic).
   const char* feat_bytes = reinterpret_cast<const char*>(feat);
   const uint32_t row_bytes = (uint32_t)HF * 4u, col_bytes = (uint32_t)col * 4u;
 
-  float s_run = 0.f;
-  int32_t c_next = (beg + li < end) ? bcol[beg + li] : col_begin;
-  for (int32_t c0 = beg; c0 < end; c0 += SL) {
-    const bool e_ok = c0 + li < end;
-    // gathered vertex of edge c0 + li; lanes past the end point at the block's first
-    // vertex (a valid, cache-resident row) and get weight 0, so the row phase below
-    // needs no per-edge conditionals
-    const int32_t c = e_ok ? c_next : col_begin;
-    if (c0 + SL + li < end) c_next = bcol[c0 + SL + li];
-    l_idx[li] = c;
-    // per-edge scalars: issue the loads now, use them after the row loads are in flight
-    float e_a = 0.f;
-    float4 vs = make_float4(0.f, 0.f, 1.f, 0.f);
-    if (e_ok) {
-      if (MODE == 2) vs = vstate[(int64_t)h * n_rows + c];  // head-major (er, m, 1/d, D) of the destination
-      else e_a = el[(int64_t)c * H + h];
-    }
-    wave_lds_fence();
-    float4 part = make_float4(0.f, 0.f, 0.f, 0.f), part2 = part;
-#pragma unroll
-    for (int t0 = 0; t0 < SL; t0 += U) {
-      // the group's U gathered vertices in one go (broadcast LDS reads), then U row loads
-      int idv[U];
-#pragma unroll
-      for (int q = 0; q < U / 4; ++q) {
-        const int4 i4 = *reinterpret_cast<const int4*>(l_idx + t0 + 4 * q);
-        idv[4 * q] = i4.x; idv[4 * q + 1] = i4.y; idv[4 * q + 2] = i4.z; idv[4 * q + 3] = i4.w;
-      }
-      float4 rowv[U];
-      if (narrow) {
-#pragma unroll
-        for (int t = 0; t < U; ++t)
-          rowv[t] = *reinterpret_cast<const float4*>(
-              feat_bytes + (__umul24((uint32_t)idv[t], row_bytes) + col_bytes));
-      } else {
-#pragma unroll
-        for (int t = 0; t < U; ++t) rowv[t] = ld4(feat + (int64_t)idv[t] * HF + col);
-      }
-      if (t0 == 0) {
-        float p = 0.f, p2 = 0.f;
+  BlkRow<MODE> cur, nxt;
+  fetch(0, cur);
+  for (int k = 0; k < R; ++k) {
+    if (k + 1 < R) fetch(k + 1, nxt);
+    if (cur.row >= 0) {
+      const int32_t end = cur.end;
+      const float r_a = cur.r_a, r_m = cur.r_m, r_invd = 1.f / cur.r_d;
+      float4 acc = cur.acc, acc2 = cur.acc2;
+      float s_run = 0.f;
+      int32_t c_next = cur.c_first;
+      for (int32_t c0 = cur.beg; c0 < end; c0 += SL) {
+        const bool e_ok = c0 + li < end;
+        // gathered vertex of edge c0 + li; lanes past the end point at the block's first
+        // vertex (a valid, cache-resident row) and get weight 0, so the row phase below
+        // needs no per-edge conditionals
+        const int32_t c = e_ok ? c_next : col_begin;
+        if (c0 + SL + li < end) c_next = bcol[c0 + SL + li];
+        l_idx[li] = c;
+        // per-edge scalars: issue the loads now, use them after the row loads are in flight
+        float e_a = 0.f;
+        float4 vs = make_float4(0.f, 0.f, 1.f, 0.f);
         if (e_ok) {
-          if (MODE == 2) {
-            const float raw = r_a + vs.x;
-            p = __expf(leaky(raw, dm.slope) - vs.y) * vs.z;
-            p2 = raw > 0.f ? p : dm.slope * p;
-            s_run = fmaf(p2, vs.w, s_run);
+          if (MODE == 2) vs = vstate[(int64_t)h * n_rows + c];  // head-major (er, m, 1/d, D) of the destination
+          else e_a = el_hm ? el[(int64_t)h * n_rows + c] : el[(int64_t)c * H + h];
+        }
+        wave_lds_fence();
+        float4 part = make_float4(0.f, 0.f, 0.f, 0.f), part2 = part;
+#pragma unroll
+        for (int t0 = 0; t0 < SL; t0 += U) {
+          // the group's U gathered vertices in one go (broadcast LDS reads), then U row loads
+          int idv[U];
+#pragma unroll
+          for (int q = 0; q < U / 4; ++q) {
+            const int4 i4 = *reinterpret_cast<const int4*>(l_idx + t0 + 4 * q);
+            idv[4 * q] = i4.x; idv[4 * q + 1] = i4.y; idv[4 * q + 2] = i4.z; idv[4 * q + 3] = i4.w;
+          }
+          float4 rowv[U];
+          if (narrow) {
+#pragma unroll
+            for (int t = 0; t < U; ++t)
+              rowv[t] = *reinterpret_cast<const float4*>(
+                  feat_bytes + (__umul24((uint32_t)idv[t], row_bytes) + col_bytes));
           } else {
-            const float raw = e_a + r_a;
-            p = __expf(leaky(raw, dm.slope) - r_m) * r_invd;
-            if (MODE == 1) {
-              p = raw > 0.f ? p : dm.slope * p;
-              s_run += p;
+#pragma unroll
+            for (int t = 0; t < U; ++t) rowv[t] = ld4(feat + (int64_t)idv[t] * HF + col);
+          }
+          if (t0 == 0) {
+            float p = 0.f, p2 = 0.f;
+            if (e_ok) {
+              if (MODE == 2) {
+                const float raw = r_a + vs.x;
+                p = __expf(leaky(raw, dm.slope) - vs.y) * vs.z;
+                p2 = raw > 0.f ? p : dm.slope * p;
+                s_run = fmaf(p2, vs.w, s_run);
+              } else {
+                const float raw = e_a + r_a;
+                p = __expf(leaky(raw, dm.slope) - r_m) * r_invd;
+                if (MODE == 1) {
+                  p = raw > 0.f ? p : dm.slope * p;
+                  s_run += p;
+                }
+                if (MODE == 3) {
+                  p2 = raw > 0.f ? p : dm.slope * p;
+                  s_run += p2;
+                }
+              }
             }
-            if (MODE == 3) {
-              p2 = raw > 0.f ? p : dm.slope * p;
-              s_run += p2;
+            l_p[li] = p;
+            if (DUAL) l_p2[li] = p2;
+            wave_lds_fence();
+          }
+          float pv[U], pv2[U];
+#pragma unroll
+          for (int q = 0; q < U / 4; ++q) {
+            const float4 p4 = *reinterpret_cast<const float4*>(l_p + t0 + 4 * q);
+            pv[4 * q] = p4.x; pv[4 * q + 1] = p4.y; pv[4 * q + 2] = p4.z; pv[4 * q + 3] = p4.w;
+            if (DUAL) {
+              const float4 q4 = *reinterpret_cast<const float4*>(l_p2 + t0 + 4 * q);
+              pv2[4 * q] = q4.x; pv2[4 * q + 1] = q4.y; pv2[4 * q + 2] = q4.z; pv2[4 * q + 3] = q4.w;
             }
           }
+#pragma unroll
+          for (int t = 0; t < U; ++t) {
+            fma4(part, pv[t], rowv[t]);
+            if (DUAL) fma4(part2, pv2[t], rowv[t]);
+          }
         }
-        l_p[li] = p;
-        if (DUAL) l_p2[li] = p2;
+        add4(acc, part);
+        if (DUAL) add4(acc2, part2);
         wave_lds_fence();
       }
-      float pv[U], pv2[U];
-#pragma unroll
-      for (int q = 0; q < U / 4; ++q) {
-        const float4 p4 = *reinterpret_cast<const float4*>(l_p + t0 + 4 * q);
-        pv[4 * q] = p4.x; pv[4 * q + 1] = p4.y; pv[4 * q + 2] = p4.z; pv[4 * q + 3] = p4.w;
-        if (DUAL) {
-          const float4 q4 = *reinterpret_cast<const float4*>(l_p2 + t0 + 4 * q);
-          pv2[4 * q] = q4.x; pv2[4 * q + 1] = q4.y; pv2[4 * q + 2] = q4.z; pv2[4 * q + 3] = q4.w;
-        }
-      }
-#pragma unroll
-      for (int t = 0; t < U; ++t) {
-        fma4(part, pv[t], rowv[t]);
-        if (DUAL) fma4(part2, pv2[t], rowv[t]);
+      st4(acc_buf + (int64_t)cur.row * HF + col, acc);
+      if (DUAL) st4(acc2_buf + (int64_t)cur.row * HF + col, acc2);
+      if (MODE != 0 && leader) {
+        const float tot = group_sum_from<SL>(s_run, 1);
+        if (li == 0) scal_buf[(int64_t)cur.row * H + h] = cur.scal + tot;
       }
     }
-    add4(acc, part);
-    if (DUAL) add4(acc2, part2);
-    wave_lds_fence();
+    cur = nxt;
   }
-  st4(acc_buf + (int64_t)row * HF + col, acc);
-  if (DUAL) st4(acc2_buf + (int64_t)row * HF + col, acc2);
-  if (MODE != 0 && leader) {
-    const float tot = group_sum_from<SL>(s_run, 1);
-    if (li == 0) scal_buf[rh] = scal + tot;
-  }
+}
+
+// elT[h][v] = el[v][h]: a column block of gathered vertices then spans 4 B per vertex in
+// the head a slice needs instead of 4*H (fewer L2 lines for the per-edge scalar gathers)
+__global__ void k_gat_head_major(int64_t n, int H, const float* __restrict__ a, float* __restrict__ aT) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;  // index into aT
+  if (i >= n * H) return;
+  const int64_t h = i / n, v = i - h * n;
+  aT[i] = a[v * H + h];
+}
+
+static gnn_status_t head_major(const gnn_graph_t* g, int H, const float* a, float* aT, hipStream_t st) {
+  ProfScope p("gat_head_major", st);
+  const int64_t cnt = (int64_t)g->n * H;
+  k_gat_head_major<<<(unsigned)cdiv(cnt, 256), 256, 0, st>>>(g->n, H, a, aT);
+  GNN_LAUNCH_CHECK();
+  return GNN_OK;
 }
 
 // ---- host side -------------------------------------------------------------------------
@@ -243,26 +312,26 @@ bool gat_blocked_applies(const gnn_graph_t* g, int heads, int f) {
 size_t gat_blocked_ws_bytes(const gnn_graph_t* g, int heads, int f) {
   if (!gat_blocked_applies(g, heads, f)) return 0;
   return ws_granule(sizeof(float) * (size_t)g->n * heads * f) +   // T, then A2
-         ws_granule(sizeof(float) * (size_t)g->n * heads);        // sg, then sd
+         2 * ws_granule(sizeof(float) * (size_t)g->n * heads);    // sg, then sd; head-major el
 }
 
 template <int SL, int MODE>
 static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* name, GatDims dm,
-                                  const float* feat,
+                                  int el_hm, const float* feat,
                                   const float* el, const float* er, const float* m, const float* d,
                                   const float4* vstate, float* acc, float* acc2, float* scal,
                                   hipStream_t st) {
   const int sph = kSlices / dm.H;
-  const int gpb = kBlkThreads / SL;
-  const unsigned grid = (unsigned)(cdiv(g->n, gpb) * kSlices);
+  const int rows_per_wg = (kBlkThreads / SL) * kRowsPerGroup;
+  const unsigned grid = (unsigned)(cdiv(g->n, rows_per_wg) * kSlices);
   // 32-bit byte offsets (and 24-bit multiplies) reach every gathered row
   const int narrow = (int64_t)g->n * dm.HF * 4 < ((int64_t)1 << 32) && g->n < (1 << 24);
   for (int b = 0; b < g->nblk; ++b) {
-    const int32_t* bptr_b = g->bptr[side] + (int64_t)b * g->n;
+    const int2* bseg_b = reinterpret_cast<const int2*>(g->bseg[side]) + (int64_t)b * g->n;
     ProfScope p(name, st);  // one timed bracket per launch
-    k_gat_blk<SL, MODE><<<grid, kBlkThreads, 0, st>>>(g->n, g->order[side], bptr_b, g->bcol[side], feat,
+    k_gat_blk<SL, MODE><<<grid, kBlkThreads, 0, st>>>(g->n, g->order[side], bseg_b, g->bcol[side], feat,
                                                       el, er, m, d, vstate, b * g->block_cols, dm, sph,
-                                                      b == 0, narrow, acc, acc2, scal);
+                                                      b == 0, narrow, el_hm, acc, acc2, scal);
     GNN_LAUNCH_CHECK();
   }
   return GNN_OK;
@@ -270,14 +339,14 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
 
 template <int MODE>
 static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name, GatDims dm,
-                               const float* feat, const float* el, const float* er, const float* m,
+                               int el_hm, const float* feat, const float* el, const float* er, const float* m,
                                const float* d, const float4* vstate, float* acc, float* acc2,
                                float* scal, hipStream_t st) {
   switch (dm.HF / (4 * kSlices)) {
-    case 4: return launch_blocks<4, MODE>(g, side, name, dm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
-    case 8: return launch_blocks<8, MODE>(g, side, name, dm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
-    case 16: return launch_blocks<16, MODE>(g, side, name, dm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
-    case 32: return launch_blocks<32, MODE>(g, side, name, dm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
+    case 4: return launch_blocks<4, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
+    case 8: return launch_blocks<8, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
+    case 16: return launch_blocks<16, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
+    case 32: return launch_blocks<32, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
   }
   set_error("gat blocked: unsupported slice width");
   return GNN_ERR_UNSUPPORTED;
@@ -285,22 +354,27 @@ static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name,
 
 gnn_status_t gat_blocked_fwd(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                              const float* er, float* m, float* d, float* out, float* t, float* sg,
-                             hipStream_t st) {
+                             float* el_t, hipStream_t st) {
+  if (el_t) GNN_TRY(head_major(g, dm.H, el, el_t, st));
+  const float* el_use = el_t ? el_t : el;
+  const int hm = el_t != nullptr;
   {
     ProfScope p("gat_softmax_stats", st);
     k_gat_softmax_stats<<<(unsigned)cdiv(g->n, kBlkThreads / kWave), kBlkThreads, 0, st>>>(
         g->n, g->order[0], g->indptr, g->indices, el, er, dm, m, d);
     GNN_LAUNCH_CHECK();
   }
-  if (t) return run_blocks<3>(g, 0, "gat_fwd_fused", dm, z, el, er, m, d, nullptr, out, t, sg, st);
-  return run_blocks<0>(g, 0, "gat_fwd_fused", dm, z, el, er, m, d, nullptr, out, nullptr, nullptr, st);
+  if (t) return run_blocks<3>(g, 0, "gat_fwd_fused", dm, hm, z, el_use, er, m, d, nullptr, out, t, sg, st);
+  return run_blocks<0>(g, 0, "gat_fwd_fused", dm, hm, z, el_use, er, m, d, nullptr, out, nullptr, nullptr, st);
 }
 
 gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                                  const float* er, const float* m, const float* d, const float* out,
                                  const float* gout, float* der, float4* vstate, float* t_buf,
-                                 float* sg_buf, hipStream_t st) {
-  GNN_TRY(run_blocks<1>(g, 0, "gat_bwd_dst", dm, z, el, er, m, d, nullptr, t_buf, nullptr, sg_buf, st));
+                                 float* sg_buf, float* el_t, hipStream_t st) {
+  if (el_t) GNN_TRY(head_major(g, dm.H, el, el_t, st));
+  GNN_TRY(run_blocks<1>(g, 0, "gat_bwd_dst", dm, el_t != nullptr, z, el_t ? el_t : el, er, m, d, nullptr,
+                        t_buf, nullptr, sg_buf, st));
   return gat_dst_finish(g, dm, gout, t_buf, out, sg_buf, er, m, d, 1, der, vstate, st);
 }
 
@@ -308,8 +382,8 @@ gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* 
                                  const float4* vstate, const float* der, const float* gout,
                                  const float* a_l, const float* a_r, float* dz, float* del,
                                  float* a2_buf, float* sd_buf, hipStream_t st) {
-  GNN_TRY(run_blocks<2>(g, 1, "gat_bwd_src", dm, gout, el, nullptr, nullptr, nullptr, vstate, dz, a2_buf,
-                        sd_buf, st));
+  GNN_TRY(run_blocks<2>(g, 1, "gat_bwd_src", dm, 0, gout, el, nullptr, nullptr, nullptr, vstate, dz,
+                        a2_buf, sd_buf, st));
   return gat_src_finish(g, dm, z, a2_buf, sd_buf, der, a_l, a_r, dz, del, st);
 }
 

@@ -33,7 +33,7 @@ size_t gat_blocked_ws_bytes(const gnn_graph_t* g, int heads, int f);  // extra w
 // t, sg: optional stash of the destination-side backward sums (both or neither)
 gnn_status_t gat_blocked_fwd(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                              const float* er, float* m, float* d, float* out, float* t, float* sg,
-                             hipStream_t st);
+                             float* el_t /* [H][n] scratch or null */, hipStream_t st);
 // vertex-side closing steps shared by both paths (gat.hip)
 gnn_status_t gat_dst_finish(const gnn_graph_t* g, GatDims dm, const float* gout, const float* t,
                             const float* out, const float* sg, const float* er, const float* m,
@@ -46,7 +46,8 @@ gnn_status_t gat_src_finish(const gnn_graph_t* g, GatDims dm, const float* z, co
 gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                                  const float* er, const float* m, const float* d, const float* out,
                                  const float* gout, float* der, float4* vstate, float* t_buf,
-                                 float* sg_buf, hipStream_t st);
+                                 float* sg_buf, float* el_t /* [H][n] scratch or null */,
+                                 hipStream_t st);
 // writes dz, del; a2_buf is an [n, HF] scratch, sd_buf an [n, H] scratch
 gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                                  const float4* vstate, const float* der, const float* gout,

@@ -83,6 +83,17 @@ __global__ void k_block_keys(int32_t n, int64_t nnz, const int32_t* __restrict__
   atomicAdd(&counts[key], 1);  // integer count
 }
 
+// bseg[b*n + r] = (bptr[b*n + row], bptr[b*n + row + 1]) with row = order[r]: the blocked
+// kernels hand out rows in degree order and read their bounds with one coalesced load
+__global__ void k_block_segments(int32_t n, int32_t nblk, const int32_t* __restrict__ bptr,
+                                 const int32_t* __restrict__ order, int2* __restrict__ bseg) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i >= (int64_t)n * nblk) return;
+  const int64_t b = i / n, r = i - b * n;
+  const int64_t j = b * n + order[r];
+  bseg[i] = make_int2(bptr[j], bptr[j + 1]);
+}
+
 static void free_all(gnn_graph* g) {
   if (!g) return;
   (void)hipFree(g->indptr_t);
@@ -94,6 +105,7 @@ static void free_all(gnn_graph* g) {
     (void)hipFree(g->bucket_offsets[s]);
     (void)hipFree(g->bptr[s]);
     (void)hipFree(g->bcol[s]);
+    (void)hipFree(g->bseg[s]);
   }
   delete g;
 }
@@ -203,6 +215,10 @@ static gnn_status_t build_blocked(gnn_graph* g, int side, const int32_t* ptr, co
     GNN_HIP(rocprim::radix_sort_pairs(scratch, bytes, keys, keys_sorted, cols, g->bcol[side],
                                       (size_t)nnz, 0, end_bit, st));
   }
+  GNN_HIP(hipMalloc((void**)&g->bseg[side], sizeof(int32_t) * 2 * (size_t)slots));
+  k_block_segments<<<cdiv(slots, thr), thr, 0, st>>>(n, g->nblk, g->bptr[side], g->order[side],
+                                                     reinterpret_cast<int2*>(g->bseg[side]));
+  GNN_LAUNCH_CHECK();
   GNN_HIP(hipStreamSynchronize(st));
   return GNN_OK;
 }
