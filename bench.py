@@ -1,14 +1,16 @@
 #!/usr/bin/env python3
-"""Benchmark of the fused GAT layer, forward + recomputing backward, on one MI355X.
+"""Benchmark of the fused GNN layers, forward + backward, on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gat_c4]
 
-One "step" is one pass of the whole hot path over the synthetic graph: projection
-(MFMA), attention halves, fused score/softmax/aggregate, the two recomputing
-backward edge kernels, parameter gradients and the two backward products.  The
-graph plan (CSC transpose, degree order) is built once per graph before the timed
-region and its time is reported separately.  Inputs are resident in HBM when the
-timed region starts.  Prints ONE JSON line.
+Default workload: the Reddit-scale GAT layer (`gat_c4`), the largest GAT configuration,
+on which the headline metric is quoted.  `ec_c3` (EdgeConv) and `gmm_c5` (MoNet) run
+the same way.  One "step" is one pass of the whole hot path over the synthetic graph:
+projection (MFMA), the fused edge kernels of the forward pass, the backward edge
+kernels, parameter gradients and the backward products.  The graph plan (CSC
+transpose, degree order, blocked edge lists) is built once per graph before the timed
+region and its time is reported separately.  Inputs are resident in HBM when the timed
+region starts.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -25,41 +27,55 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 FP32_VECTOR_TFLOPS = 157.3      # MI355X published fp32 vector peak
 
 
-def unique_bytes(n, e, fin, H, F):
-    """Minimal HBM traffic of each kernel: every array it touches, once."""
+# ---- byte / flop models (stated in the design doc section 6) -------------------------------
+def gat_models(n, e, fin, H, F):
     HF = H * F
-    V = 4 * n * HF          # one [n, HF] fp32 matrix
-    S = 4 * n * H           # one [n, H] fp32 matrix
-    I = 4 * e + 8 * n       # indices + indptr + degree order
-    return {
-        "gat_fwd_fused": I + V + 4 * S + 2 * V + S,                  # z, el, er, m, d -> out, t, sg
-        "gat_bwd_dst": I + 3 * V + 4 * S + S + 4 * S,                # z, out, gout, el, er, m, d -> der, vstate
-        "gat_bwd_src": I + 3 * V + S + 4 * S + S + S,                # gout, z, dz, el, vstate, der -> del
-        "gemm_f32_mfma": 4 * n * fin + 4 * fin * HF + V,             # projection
+    V, S = 4 * n * HF, 4 * n * H        # one [n, HF] / one [n, H] fp32 matrix
+    I = 4 * e + 8 * n                   # indices + indptr + degree order
+    unique = {
+        "gat_fwd_fused": I + V + 4 * S + 2 * V + S,    # z, el, er, m, d -> out, t, sg
+        "gat_bwd_dst": I + 3 * V + 4 * S + S + 4 * S,  # z, out, gout, el, er, m, d -> der, table
+        "gat_bwd_src": I + 3 * V + S + 4 * S + S + S,  # gout, z, dz, el, table, der -> del
     }
-
-
-def gather_bytes(e, H, F):
-    """Per-edge gather model (no cache reuse): index + one feature row + per-head scalars."""
-    HF = H * F
-    return {
+    gather = {
         "gat_fwd_fused": e * (4 + 4 * HF + 4 * H),
         "gat_bwd_dst": e * (4 + 4 * HF + 4 * H),
         "gat_bwd_src": e * (4 + 4 * HF + 16 * H),
     }
-
-
-def edge_flops(e, H, F):
-    return {
-        "gat_fwd_fused": e * H * (2 * F + 12),
+    flops = {
+        "gat_fwd_fused": e * H * (4 * F + 14),
         "gat_bwd_dst": e * H * (2 * F + 14),
         "gat_bwd_src": e * H * (4 * F + 16),
     }
+    return unique, gather, flops
+
+
+def edgeconv_models(n, e, fin, F):
+    V = 4 * n * F
+    unique = {"edgeconv_fwd_fused": 4 * e + 8 * n + 2 * V + 2 * V,          # pq -> out, argmax
+              "edgeconv_bwd_src": 8 * e + 8 * n + 2 * V + 2 * V}            # argmax, gout -> dpq
+    gather = {"edgeconv_fwd_fused": e * (4 + 4 * F), "edgeconv_bwd_src": e * (8 + 8 * F)}
+    flops = {"edgeconv_fwd_fused": e * F, "edgeconv_bwd_src": e * F}
+    return unique, gather, flops
+
+
+def gmm_models(n, e, fin, F, K):
+    V = 4 * n * F
+    I = 4 * e + 8 * n
+    unique = {"gmm_fwd_fused": I + K * V + 4 * n + V,
+              "gmm_bwd_dst": I + K * V + 4 * n + V,
+              "gmm_bwd_src": I + V + 4 * n + K * V}
+    gather = {"gmm_fwd_fused": e * (8 + 4 * K * F), "gmm_bwd_dst": e * (8 + 4 * K * F),
+              "gmm_bwd_src": e * (8 + 4 * F)}
+    flops = {"gmm_fwd_fused": e * K * (2 * F + 12), "gmm_bwd_dst": e * K * (6 * F + 14),
+             "gmm_bwd_src": e * K * (2 * F + 12)}
+    return unique, gather, flops
 
 
 def read_traffic(workload):
-    """HBM bytes per launch of the dominant kernel, as measured with rocprofv3 --pmc
-    (FETCH_SIZE, WRITE_SIZE) and written into profiles/<workload>_hbm_traffic.txt."""
+    """HBM-side bytes per launch of the dominant kernel, measured with rocprofv3 --pmc
+    (FETCH_SIZE, WRITE_SIZE, each calibrated on a device copy of known size) and kept in
+    profiles/<workload>_hbm_traffic.txt."""
     path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
     vals = {}
     try:
@@ -68,22 +84,25 @@ def read_traffic(workload):
                 k, v = line.split(":", 1)
                 vals[k.strip()] = v.strip()
     except OSError:
-        return None, None
-    return vals, path
+        return None
+    return vals
 
 
-def cpu_baseline(c, budget_rows):
+def oracle_threads():
+    try:
+        from threadpoolctl import threadpool_info
+        return max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        return os.cpu_count() or 1
+
+
+def cpu_baseline_gat(c, budget_rows):
     """The numpy oracle (as it stands) timed on a bounded sample of the same workload:
-    the full projection and backward products at N vertices, and the per-edge part on
-    the in-edges of `budget_rows` seeded destination rows, scaled to all E edges."""
+    the dense products at all N vertices, and the per-edge part on the in-edges of
+    `budget_rows` seeded destination rows, scaled to all E edges."""
     import numpy as np
     from oracle import gat as og
     from oracle.segments import restrict_rows
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        threads = os.cpu_count() or 1
     n, e = c["n"], c["nnz"]
     rng = np.random.default_rng(12345)
     rows = np.sort(rng.choice(n, size=min(budget_rows, n), replace=False))
@@ -96,20 +115,39 @@ def cpu_baseline(c, budget_rows):
     # the three dense products inside that time do not shrink with the sample: time them alone
     X64, W64 = c["x"].astype(np.float64), c["w"].astype(np.float64)
     t1 = time.perf_counter()
-    Z = X64 @ W64
+    _ = X64 @ W64
     _ = X64.T @ bwd["dHt"]
     _ = bwd["dHt"] @ W64.T
     t_dense = time.perf_counter() - t1
-    del Z, fwd, bwd
+    del fwd, bwd
     t_edges = max(t_sample - t_dense, 1e-9)
     t_full = t_dense + t_edges * (e / max(e_s, 1))
     return {
-        "value": e / t_full, "unit": "edges/s", "cores": int(threads), "kind": "oracle",
+        "value": e / t_full, "unit": "edges/s", "cores": int(oracle_threads()), "kind": "oracle",
         "sample": (f"fp64 numpy oracle fwd+bwd on the in-edges of {len(rows)} seeded destination rows "
                    f"({e_s} of {e} edges) with all {n} vertices' dense products; measured {t_sample:.2f} s "
                    f"of which {t_dense:.2f} s dense; per-edge part scaled by E/E_sample"),
         "measured_s": t_sample,
     }
+
+
+def cpu_baseline_full(c):
+    """EdgeConv / GMM workloads are small enough for the oracle to run whole."""
+    e = c["nnz"]
+    t0 = time.perf_counter()
+    if c["kind"] == "edgeconv":
+        from oracle import edgeconv as oe
+        fwd = oe.edgeconv_forward(c["indptr"], c["indices"], c["x"], c["theta"], c["phi"])
+        oe.edgeconv_backward(c["indptr"], c["indices"], c["x"], c["theta"], c["phi"], c["gout"], fwd)
+    else:
+        from oracle import gmm as om
+        args = (c["indptr"], c["indices"], c["x"], c["w_fc"], c["c"], c["mu"], c["inv_sigma"])
+        fwd = om.gmm_forward(*args)
+        om.gmm_backward(*args, c["gout"], fwd)
+    dt = time.perf_counter() - t0
+    return {"value": e / dt, "unit": "edges/s", "cores": int(oracle_threads()), "kind": "oracle",
+            "sample": f"fp64 numpy oracle fwd+bwd on the whole workload ({e} edges), {dt:.2f} s",
+            "measured_s": dt}
 
 
 def main():
@@ -118,7 +156,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gat_c4")
-    ap.add_argument("--cpu-rows", type=int, default=2048, help="destination rows of the CPU baseline sample")
+    ap.add_argument("--cpu-rows", type=int, default=2048, help="destination rows of the CPU baseline sample (GAT)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -134,22 +172,15 @@ def main():
     t0 = time.perf_counter()
     c = make(args.workload)
     t_gen = time.perf_counter() - t0
-    assert c["kind"] == "gat"
-    n, e, fin, H, F = c["n"], c["nnz"], c["fin"], c["heads"], c["f"]
-    HF = H * F
-    print(f"[bench] {args.workload}: N={n} E={e} fin={fin} heads={H} f={F} (generated in {t_gen:.1f} s)",
+    kind, n, e, fin = c["kind"], c["n"], c["nnz"], c["fin"]
+    print(f"[bench] {args.workload}: kind={kind} N={n} E={e} (generated in {t_gen:.1f} s)",
           file=sys.stderr, flush=True)
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    new = lambda *shape, dtype=torch.float32: torch.empty(shape, dtype=dtype, device=dev)
     indptr, indices = to(c["indptr"]), to(c["indices"])
-    x, w, a_l, a_r, gout = to(c["x"]), to(c["w"]), to(c["a_l"]), to(c["a_r"]), to(c["gout"])
-    z, out = torch.empty((n, HF), device=dev), torch.empty((n, HF), device=dev)
-    el, er, m, d = (torch.empty((n, H), device=dev) for _ in range(4))
-    t, sg = torch.empty((n, HF), device=dev), torch.empty((n, H), device=dev)  # stashed dst-side sums
-    gx, gw = torch.empty((n, fin), device=dev), torch.empty((fin, HF), device=dev)
-    ga_l, ga_r = torch.empty((H, F), device=dev), torch.empty((H, F), device=dev)
 
     # a plain copy of known size, so a counter run of this script can be calibrated
     cal_src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device=dev)
@@ -162,13 +193,60 @@ def main():
     g = pk.Graph(indptr, indices)
     torch.cuda.synchronize()
     t_plan = time.perf_counter() - t0
-    ws_bytes = pk.gnn_gat_workspace_bytes(g, fin, H, F)
-    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
 
-    def step():
-        pk.gnn_gat_fwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, t, sg, ws)
-        pk.gnn_gat_bwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, t, sg, gout,
-                       gx, gw, ga_l, ga_r, ws)
+    x, gout = to(c["x"]), to(c["gout"])
+    if kind == "gat":
+        H, F = c["heads"], c["f"]
+        HF = H * F
+        w, a_l, a_r = to(c["w"]), to(c["a_l"]), to(c["a_r"])
+        z, out, t = new(n, HF), new(n, HF), new(n, HF)      # t, sg: stashed dst-side sums
+        el, er, m, d, sg = (new(n, H) for _ in range(5))
+        gx, gw, ga_l, ga_r = new(n, fin), new(fin, HF), new(H, F), new(H, F)
+        ws_bytes = pk.gnn_gat_workspace_bytes(g, fin, H, F)
+        ws = new(max(ws_bytes, 16), dtype=torch.uint8)
+
+        def step():
+            pk.gnn_gat_fwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, t, sg, ws)
+            pk.gnn_gat_bwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, t, sg, gout,
+                           gx, gw, ga_l, ga_r, ws)
+        unique, gather, flops = gat_models(n, e, fin, H, F)
+        metric = "fused GAT layer fwd+bwd edges/sec"
+        cfg = {"in_feat": fin, "heads": H, "hidden_per_head": F,
+               "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded"}
+        gemm_flops = 2.0 * n * fin * HF
+    elif kind == "edgeconv":
+        F = c["fout"]
+        theta, phi = to(c["theta"]), to(c["phi"])
+        pq, out, argmax = new(n, 2 * F), new(n, F), new(n, F, dtype=torch.int32)
+        gx, gtheta, gphi = new(n, fin), new(fin, F), new(fin, F)
+        ws_bytes = pk.gnn_edgeconv_workspace_bytes(g, fin, F)
+        ws = new(max(ws_bytes, 16), dtype=torch.uint8)
+
+        def step():
+            pk.gnn_edgeconv_fwd(g, fin, F, x, theta, phi, pq, out, argmax, ws)
+            pk.gnn_edgeconv_bwd(g, fin, F, x, theta, phi, argmax, gout, gx, gtheta, gphi, ws)
+        unique, gather, flops = edgeconv_models(n, e, fin, F)
+        metric = "fused EdgeConv layer fwd+bwd edges/sec"
+        cfg = {"in_feat": fin, "out_feat": F, "graph": "32 clouds x 1024 points, kNN k=20 incl. self, seeded"}
+        gemm_flops = 2.0 * n * fin * 2 * F
+    elif kind == "gmm":
+        F, K = c["fout"], c["k"]
+        w_fc, cc, mu, inv_sigma = to(c["w_fc"]), to(c["c"]), to(c["mu"]), to(c["inv_sigma"])
+        hk, out = new(n, K * F), new(n, F)
+        gx, gw_fc, gmu, gis = new(n, fin), new(fin, K * F), new(K, 2), new(K, 2)
+        ws_bytes = pk.gnn_gmm_workspace_bytes(g, fin, F, K)
+        ws = new(max(ws_bytes, 16), dtype=torch.uint8)
+
+        def step():
+            pk.gnn_gmm_fwd(g, fin, F, K, x, w_fc, cc, mu, inv_sigma, hk, out)
+            pk.gnn_gmm_bwd(g, fin, F, K, x, w_fc, cc, mu, inv_sigma, hk, gout, gx, gw_fc, gmu, gis, ws)
+        unique, gather, flops = gmm_models(n, e, fin, F, K)
+        metric = "fused MoNet/GMM layer fwd+bwd edges/sec"
+        cfg = {"in_feat": fin, "out_feat": F, "kernels": K,
+               "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded"}
+        gemm_flops = 2.0 * n * fin * K * F
+    else:
+        raise SystemExit(f"unknown workload kind {kind}")
 
     for _ in range(args.warmup):
         step()
@@ -192,51 +270,42 @@ def main():
     pk.gnn_prof_enable(False)
     kern = {k: {"avg_launch_ms": ms / cnt, "launches_per_step": cnt / prof_steps,
                 "ms_per_step": ms / prof_steps} for k, (ms, cnt) in rep.items()}
-    ub, gb, fl = unique_bytes(n, e, fin, H, F), gather_bytes(e, H, F), edge_flops(e, H, F)
-    edge_kernels = [k for k in ("gat_fwd_fused", "gat_bwd_dst", "gat_bwd_src") if k in kern]
+    edge_kernels = [k for k in unique if k in kern]
     dom = max(edge_kernels, key=lambda k: kern[k]["ms_per_step"])
     # a large graph is walked in several column-block launches of the same kernel: the
     # algorithmic bytes of the operation are split evenly over them
     lps = kern[dom]["launches_per_step"]
-    t_dom = kern[dom]["avg_launch_ms"] * 1e-3
-    achieved = ub[dom] / lps / t_dom / 1e9
+    achieved = unique[dom] / lps / (kern[dom]["avg_launch_ms"] * 1e-3) / 1e9
     for k in edge_kernels:
-        t = kern[k]["ms_per_step"] * 1e-3
-        kern[k].update(unique_GBps=ub[k] / t / 1e9, gather_model_GBps=gb[k] / t / 1e9,
-                       fp32_TFLOPs=fl[k] / t / 1e12)
+        t_k = kern[k]["ms_per_step"] * 1e-3
+        kern[k].update(unique_GBps=unique[k] / t_k / 1e9, gather_model_GBps=gather[k] / t_k / 1e9,
+                       fp32_TFLOPs=flops[k] / t_k / 1e12)
     if "gemm_f32_mfma" in kern:
-        # two plain products per step take this name (projection and gx); same flop count each
-        t = kern["gemm_f32_mfma"]["avg_launch_ms"] * 1e-3
-        kern["gemm_f32_mfma"]["fp32_mfma_TFLOPs"] = 2.0 * n * fin * HF / t / 1e12
+        # the projection and the input-gradient product take this name; same flop count each
+        kern["gemm_f32_mfma"]["fp32_mfma_TFLOPs"] = gemm_flops / (kern["gemm_f32_mfma"]["avg_launch_ms"] * 1e-3) / 1e12
 
-    traffic_vals, traffic_path = read_traffic(args.workload)
-    traffic = None
-    if traffic_vals and traffic_vals.get("kernel") == dom:
-        traffic = float(traffic_vals["hbm_bytes_per_launch"])
+    tv = read_traffic(args.workload)
+    traffic = float(tv["hbm_bytes_per_launch"]) if tv and tv.get("kernel") == dom else None
     roofline = {
         "kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-        "algorithmic_bytes_per_launch": ub[dom] / lps, "avg_launch_ms": kern[dom]["avg_launch_ms"],
+        "algorithmic_bytes_per_launch": unique[dom] / lps, "avg_launch_ms": kern[dom]["avg_launch_ms"],
         "launches_per_step": lps,
         "bytes_model": "minimal unique bytes: every array the kernel touches counted once",
         "gather_model_GBps": kern[dom]["gather_model_GBps"],
         "fp32_alu_frac": kern[dom]["fp32_TFLOPs"] / FP32_VECTOR_TFLOPS,
     }
-
+    cfg.update(workload=args.workload, vertices=n, edges=e, plan_ms_once_per_graph=1e3 * t_plan,
+               workspace_bytes=ws_bytes)
     result = {
-        "metric": "fused GAT layer fwd+bwd edges/sec", "value": edges_per_s, "unit": "edges/s",
+        "metric": metric, "value": edges_per_s, "unit": "edges/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
-        "data": "synthetic",
-        "config": {"workload": args.workload, "vertices": n, "edges": e, "in_feat": fin, "heads": H,
-                   "hidden_per_head": F, "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded",
-                   "plan_ms_once_per_graph": 1e3 * t_plan, "workspace_bytes": ws_bytes},
-        "roofline": roofline,
-        "kernels": kern,
+        "data": "synthetic", "config": cfg, "roofline": roofline, "kernels": kern,
     }
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample ...", file=sys.stderr, flush=True)
-        result["cpu_baseline"] = cpu_baseline(c, args.cpu_rows)
+        result["cpu_baseline"] = cpu_baseline_gat(c, args.cpu_rows) if kind == "gat" else cpu_baseline_full(c)
     print(json.dumps(result))
 
 

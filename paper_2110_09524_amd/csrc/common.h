@@ -89,6 +89,16 @@ gnn_status_t gemm_f32(int64_t M, int N, int64_t K, const float* a, int64_t lda, 
                       const float* b, int64_t ldb, bool b_kcontig, float* c, int64_t ldc,
                       int split_k, float* partials, hipStream_t s);
 int gemm_pick_split_k(int64_t M, int N, int64_t K);
+// out[i] = sum over z < parts of partials[z*count + i], in a fixed order (reproducible)
+gnn_status_t sum_partials(int64_t count, int parts, const float* partials, float* out, hipStream_t s);
+constexpr int kSumChunk = 64;
+int sum_partials_scratch_rows(int parts);
+// two levels for very many parts; scratch holds sum_partials_scratch_rows(parts) * count floats
+gnn_status_t sum_partials_two_level(int64_t count, int parts, const float* partials, float* scratch,
+                                    float* out, hipStream_t s);
+// same with a distance of `stride` floats between consecutive parts
+gnn_status_t sum_partials_strided(int64_t count, int parts, const float* partials, int64_t stride,
+                                  float* out, hipStream_t s);
 
 }  // namespace gnn
 

@@ -62,19 +62,23 @@ struct GroupLds {
 // recompute only when computation / memory is O(1); here it is |E|/|V|).
 template <int L, int NV, bool WT>
 __global__ __launch_bounds__(kBlock) void k_gat_fwd(
-    int32_t n_rows, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    RowRange rr, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
     const int32_t* __restrict__ indices, const float* __restrict__ z, const float* __restrict__ el,
     const float* __restrict__ er, GatDims dm, float* __restrict__ out, float* __restrict__ m_out,
     float* __restrict__ d_out, float* __restrict__ t_out, float* __restrict__ sg_out) {
   constexpr int G = kWave / L;
   constexpr int GPB = G * (kBlock / kWave);
+  constexpr int NC = (WT ? 8 : 4) * NV + 2;  // floats per lane folded across cooperating groups
   __shared__ float lds[GPB * GroupLds<L, NV>::kFloats];
+  __shared__ float coop_buf[GPB * L * NC];
+  __shared__ float coop_m[GPB * L];
 
   const int lane = threadIdx.x & 63;
   const int li = lane & (L - 1);
   const int grp = threadIdx.x / L;  // group inside the block
-  const int64_t r = (int64_t)blockIdx.x * GPB + grp;
-  if (r >= n_rows) return;  // whole group leaves together
+  int64_t r;
+  int gi, ngrp;
+  if (!pick_row<GPB>(rr, grp, r, gi, ngrp)) return;  // whole group (coop: whole workgroup) leaves together
   float* g_lds = lds + grp * GroupLds<L, NV>::kFloats;
   int* l_idx = reinterpret_cast<int*>(g_lds);
   float* l_p = g_lds + L;
@@ -105,7 +109,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_fwd(
   }
 
   float m_run = -INFINITY, d_run = 0.f, d2_run = 0.f;
-  for (int32_t c0 = beg; c0 < end; c0 += epc) {
+  for (int32_t c0 = beg + gi * epc; c0 < end; c0 += ngrp * epc) {
     // chunk phase: lane = (edge e_loc of the chunk, head h)
     const int32_t e = c0 + e_loc;
     const bool e_ok = e < end;
@@ -183,6 +187,40 @@ __global__ __launch_bounds__(kBlock) void k_gat_fwd(
     wave_lds_fence();
   }
 
+  if (rr.coop) {
+    // groups ran their own online softmax: bring them to the common maximum, then add
+    if (e_loc == 0) coop_m[grp * Hp + h] = m_run;
+    __syncthreads();
+    float m_all = -INFINITY;
+    for (int g2 = 0; g2 < GPB; ++g2) m_all = fmaxf(m_all, coop_m[g2 * Hp + h]);
+    const float sc_own = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_all);
+    float v[NC];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      float mj_all = -INFINITY;
+      for (int g2 = 0; g2 < GPB; ++g2) mj_all = fmaxf(mj_all, coop_m[g2 * Hp + hs[j]]);
+      const float mj = coop_m[grp * Hp + hs[j]];
+      const float scj = (mj == -INFINITY) ? 0.f : __expf(mj - mj_all);
+      scale4(acc[j], scj);
+      pack4(v + 4 * j, acc[j]);
+      if (WT) {
+        scale4(acc2[j], scj);
+        pack4(v + 4 * NV + 4 * j, acc2[j]);
+      }
+    }
+    v[NC - 2] = d_run * sc_own;
+    v[NC - 1] = d2_run * sc_own;
+    coop_sum<L, NC, GPB>(coop_buf, v, grp, li);
+    if (grp != 0) return;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      acc[j] = unpack4(v + 4 * j);
+      if (WT) acc2[j] = unpack4(v + 4 * NV + 4 * j);
+    }
+    d_run = v[NC - 2];
+    d2_run = v[NC - 1];
+    m_run = m_all;
+  }
   // denominators: sum the per-lane partials of each head, then hand them to the column lanes
   float dd = group_sum_from<L>(d_run, Hp);
   const bool empty = beg == end;
@@ -223,20 +261,23 @@ __device__ __forceinline__ float head_sum(const float* red, int h, int F) {
 // writes der[v,h], and vstate[v,h] = (er, m, 1/d, D) for the source-side kernel
 template <int L, int NV>
 __global__ __launch_bounds__(kBlock) void k_gat_bwd_dst(
-    int32_t n_rows, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    RowRange rr, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
     const int32_t* __restrict__ indices, const float* __restrict__ z, const float* __restrict__ el,
     const float* __restrict__ er, const float* __restrict__ m_in, const float* __restrict__ d_in,
     const float* __restrict__ out, const float* __restrict__ gout, GatDims dm,
     float* __restrict__ der, float4* __restrict__ vstate) {
   constexpr int G = kWave / L;
   constexpr int GPB = G * (kBlock / kWave);
+  constexpr int NC = 4 * NV + 1;
   __shared__ float lds[GPB * GroupLds<L, NV>::kFloats];
+  __shared__ float coop_buf[GPB * L * NC];
 
   const int lane = threadIdx.x & 63;
   const int li = lane & (L - 1);
   const int grp = threadIdx.x / L;
-  const int64_t r = (int64_t)blockIdx.x * GPB + grp;
-  if (r >= n_rows) return;
+  int64_t r;
+  int gi, ngrp;
+  if (!pick_row<GPB>(rr, grp, r, gi, ngrp)) return;
   float* g_lds = lds + grp * GroupLds<L, NV>::kFloats;
   int* l_idx = reinterpret_cast<int*>(g_lds);
   float* l_p = g_lds + L;
@@ -271,7 +312,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_dst(
   }
 
   float sg_run = 0.f;  // partial of sum alpha_e g_e
-  for (int32_t c0 = beg; c0 < end; c0 += epc) {
+  for (int32_t c0 = beg + gi * epc; c0 < end; c0 += ngrp * epc) {
     const int32_t e = c0 + e_loc;
     const bool e_ok = e < end;
     const int32_t u = e_ok ? indices[e] : 0;
@@ -322,6 +363,17 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_dst(
     wave_lds_fence();
   }
 
+  if (rr.coop) {
+    float v[NC];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) pack4(v + 4 * j, acc[j]);
+    v[NC - 1] = sg_run;
+    coop_sum<L, NC, GPB>(coop_buf, v, grp, li);
+    if (grp != 0) return;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) acc[j] = unpack4(v + 4 * j);
+    sg_run = v[NC - 1];
+  }
   const float sg = group_sum_from<L>(sg_run, Hp);
   // per-slot partial dot products with gout[v], then per-head sums through LDS
 #pragma unroll
@@ -349,20 +401,23 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_dst(
 // dz[u] = sum_out alpha_e gout[v] + a_l del[u] + a_r der[u];  writes del[u,h] too
 template <int L, int NV>
 __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
-    int32_t n_rows, const int32_t* __restrict__ order_t, const int32_t* __restrict__ indptr_t,
+    RowRange rr, const int32_t* __restrict__ order_t, const int32_t* __restrict__ indptr_t,
     const int32_t* __restrict__ indices_t, const float* __restrict__ z, const float* __restrict__ el,
     const float4* __restrict__ vstate, const float* __restrict__ der, const float* __restrict__ gout,
     const float* __restrict__ a_l, const float* __restrict__ a_r, GatDims dm,
     float* __restrict__ dz, float* __restrict__ del) {
   constexpr int G = kWave / L;
   constexpr int GPB = G * (kBlock / kWave);
+  constexpr int NC = 8 * NV + 1;
   __shared__ float lds[GPB * GroupLds<L, NV>::kFloats];
+  __shared__ float coop_buf[GPB * L * NC];
 
   const int lane = threadIdx.x & 63;
   const int li = lane & (L - 1);
   const int grp = threadIdx.x / L;
-  const int64_t r = (int64_t)blockIdx.x * GPB + grp;
-  if (r >= n_rows) return;
+  int64_t r;
+  int gi, ngrp;
+  if (!pick_row<GPB>(rr, grp, r, gi, ngrp)) return;
   float* g_lds = lds + grp * GroupLds<L, NV>::kFloats;
   int* l_idx = reinterpret_cast<int*>(g_lds);
   float* l_p = g_lds + L;
@@ -394,7 +449,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
   }
 
   float sd_run = 0.f;  // partial of sum alpha_e g_e D[v,h]
-  for (int32_t c0 = beg; c0 < end; c0 += epc) {
+  for (int32_t c0 = beg + gi * epc; c0 < end; c0 += ngrp * epc) {
     const int32_t e = c0 + e_loc;
     const bool e_ok = e < end;
     const int32_t v = e_ok ? indices_t[e] : 0;
@@ -461,6 +516,23 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
     wave_lds_fence();
   }
 
+  if (rr.coop) {
+    float v[NC];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      pack4(v + 4 * j, acc1[j]);
+      pack4(v + 4 * NV + 4 * j, acc2[j]);
+    }
+    v[NC - 1] = sd_run;
+    coop_sum<L, NC, GPB>(coop_buf, v, grp, li);
+    if (grp != 0) return;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      acc1[j] = unpack4(v + 4 * j);
+      acc2[j] = unpack4(v + 4 * NV + 4 * j);
+    }
+    sd_run = v[NC - 1];
+  }
   const float sd = group_sum_from<L>(sd_run, Hp);
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
@@ -512,19 +584,6 @@ __global__ void k_gat_param_partial(int64_t n, int H, int F, int64_t rows_per_bl
     partial[((int64_t)blockIdx.x * 2 + 0) * HF + c] = sl;
     partial[((int64_t)blockIdx.x * 2 + 1) * HF + c] = sr;
   }
-}
-
-__global__ void k_gat_param_final(int HF, int nblk, const float* __restrict__ partial,
-                                  float* __restrict__ ga_l, float* __restrict__ ga_r) {
-  int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= HF) return;
-  float sl = 0.f, sr = 0.f;
-  for (int b = 0; b < nblk; ++b) {
-    sl += partial[((int64_t)b * 2 + 0) * HF + c];
-    sr += partial[((int64_t)b * 2 + 1) * HF + c];
-  }
-  ga_l[c] = sl;
-  ga_r[c] = sr;
 }
 
 // ---- host side -------------------------------------------------------------------
@@ -600,14 +659,19 @@ struct FwdLauncher {
                           hipStream_t st) {
     constexpr int GPB = (kWave / L) * (kBlock / kWave);
     ProfScope p("gat_fwd_fused", st);
-    const unsigned grid = (unsigned)cdiv(g->n, GPB);
-    if (t)
-      k_gat_fwd<L, NV, true><<<grid, kBlock, 0, st>>>(g->n, g->order[0], g->indptr, g->indices, z, el,
-                                                      er, dm, out, m, d, t, sg);
-    else
-      k_gat_fwd<L, NV, false><<<grid, kBlock, 0, st>>>(g->n, g->order[0], g->indptr, g->indices, z, el,
-                                                       er, dm, out, m, d, nullptr, nullptr);
-    GNN_LAUNCH_CHECK();
+    const RowSplit sp = split_rows(g, 0, L >> dm.log2Hp, GPB);
+    for (int pass = 0; pass < 2; ++pass) {
+      const RowRange rr = pass == 0 ? sp.hub : sp.rest;
+      const unsigned grid = pass == 0 ? sp.hub_grid : sp.rest_grid;
+      if (grid == 0) continue;
+      if (t)
+        k_gat_fwd<L, NV, true><<<grid, kBlock, 0, st>>>(rr, g->order[0], g->indptr, g->indices, z, el, er,
+                                                        dm, out, m, d, t, sg);
+      else
+        k_gat_fwd<L, NV, false><<<grid, kBlock, 0, st>>>(rr, g->order[0], g->indptr, g->indices, z, el,
+                                                         er, dm, out, m, d, nullptr, nullptr);
+      GNN_LAUNCH_CHECK();
+    }
     return GNN_OK;
   }
 };
@@ -738,9 +802,15 @@ struct BwdDstLauncher {
                           GatDims dm, float* der, float4* vstate, hipStream_t st) {
     constexpr int GPB = (kWave / L) * (kBlock / kWave);
     ProfScope p("gat_bwd_dst", st);
-    k_gat_bwd_dst<L, NV><<<(unsigned)cdiv(g->n, GPB), kBlock, 0, st>>>(
-        g->n, g->order[0], g->indptr, g->indices, z, el, er, m, d, out, gout, dm, der, vstate);
-    GNN_LAUNCH_CHECK();
+    const RowSplit sp = split_rows(g, 0, L >> dm.log2Hp, GPB);
+    for (int pass = 0; pass < 2; ++pass) {
+      const RowRange rr = pass == 0 ? sp.hub : sp.rest;
+      const unsigned grid = pass == 0 ? sp.hub_grid : sp.rest_grid;
+      if (grid == 0) continue;
+      k_gat_bwd_dst<L, NV><<<grid, kBlock, 0, st>>>(rr, g->order[0], g->indptr, g->indices, z, el, er, m, d,
+                                                    out, gout, dm, der, vstate);
+      GNN_LAUNCH_CHECK();
+    }
     return GNN_OK;
   }
 };
@@ -752,13 +822,18 @@ struct BwdSrcLauncher {
                           GatDims dm, float* dz, float* del, hipStream_t st) {
     constexpr int GPB = (kWave / L) * (kBlock / kWave);
     ProfScope p("gat_bwd_src", st);
-    k_gat_bwd_src<L, NV><<<(unsigned)cdiv(g->n, GPB), kBlock, 0, st>>>(
-        g->n, g->order[1], g->indptr_t, g->indices_t, z, el, vstate, der, gout, a_l, a_r, dm, dz, del);
-    GNN_LAUNCH_CHECK();
+    const RowSplit sp = split_rows(g, 1, L >> dm.log2Hp, GPB);
+    for (int pass = 0; pass < 2; ++pass) {
+      const RowRange rr = pass == 0 ? sp.hub : sp.rest;
+      const unsigned grid = pass == 0 ? sp.hub_grid : sp.rest_grid;
+      if (grid == 0) continue;
+      k_gat_bwd_src<L, NV><<<grid, kBlock, 0, st>>>(rr, g->order[1], g->indptr_t, g->indices_t, z, el,
+                                                    vstate, der, gout, a_l, a_r, dm, dz, del);
+      GNN_LAUNCH_CHECK();
+    }
     return GNN_OK;
   }
 };
-
 
 gnn_status_t gat_dst_finish(const gnn_graph_t* g, GatDims dm, const float* gout, const float* t,
                             const float* out, const float* sg, const float* er, const float* m,
@@ -884,8 +959,9 @@ extern "C" gnn_status_t gnn_gat_bwd(const gnn_graph_t* g, int fin, int heads, in
     const int64_t rpb = cdiv(n, L.nblk);
     k_gat_param_partial<<<L.nblk, 256, 0, st>>>(n, heads, f, rpb, z, del, der, partial);
     GNN_LAUNCH_CHECK();
-    k_gat_param_final<<<(unsigned)cdiv(HF, 256), 256, 0, st>>>(HF, L.nblk, partial, ga_l, ga_r);
-    GNN_LAUNCH_CHECK();
+    // partial is [nblk][2][HF]: sum the l and the r halves separately, block order fixed
+    GNN_TRY(sum_partials_strided(HF, L.nblk, partial, 2 * (int64_t)HF, ga_l, st));
+    GNN_TRY(sum_partials_strided(HF, L.nblk, partial + HF, 2 * (int64_t)HF, ga_r, st));
   }
   // gw = x^T dz   (x read k-major: row index of x is the contraction index)
   GNN_TRY(gemm_f32(fin, HF, n, x, fin, true, dz, HF, false, gw, HF, L.split_k, gemm_part, st));

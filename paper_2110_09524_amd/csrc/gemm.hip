@@ -134,13 +134,71 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_f32(
 }
 
 // c[i] = sum over z of partials[z][i], z ascending (fixed order => reproducible)
-__global__ void k_sum_partials(int64_t count, int splits, const float* __restrict__ partials,
-                               float* __restrict__ c) {
+__global__ void k_sum_partials(int64_t count, int splits, int64_t stride,
+                               const float* __restrict__ partials, float* __restrict__ c) {
   int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
   if (i >= count) return;
   float s = 0.f;
-  for (int z = 0; z < splits; ++z) s += partials[(int64_t)z * count + i];
+  for (int z = 0; z < splits; ++z) s += partials[(int64_t)z * stride + i];
   c[i] = s;
+}
+
+// Same sum for short outputs and many parts: 8 threads share one output element, each
+// adds every 8th part of its range in ascending order, then the 8 subtotals are added in
+// order through LDS.  blockIdx.y selects a range of `chunk` consecutive parts and writes
+// its subtotal to row blockIdx.y of the output (a second call then adds the rows).
+// The grouping is fixed, so the result is reproducible.
+__global__ __launch_bounds__(256) void k_sum_partials_wide(int64_t count, int parts, int64_t stride,
+                                                           const float* __restrict__ partials,
+                                                           int chunk, float* __restrict__ c) {
+  __shared__ float sub[8][32];
+  const int col = threadIdx.x & 31, lane8 = threadIdx.x >> 5;
+  const int64_t i = (int64_t)blockIdx.x * 32 + col;
+  const int z0 = blockIdx.y * chunk;
+  const int z1 = z0 + chunk < parts ? z0 + chunk : parts;
+  float s = 0.f;
+  if (i < count)
+    for (int z = z0 + lane8; z < z1; z += 8) s += partials[(int64_t)z * stride + i];
+  sub[lane8][col] = s;
+  __syncthreads();
+  if (lane8 == 0 && i < count) {
+    float tot = 0.f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) tot += sub[q][col];
+    c[(int64_t)blockIdx.y * count + i] = tot;
+  }
+}
+
+gnn_status_t sum_partials_strided(int64_t count, int parts, const float* partials, int64_t stride,
+                                  float* out, hipStream_t s) {
+  if (count <= 0) return GNN_OK;
+  if (count >= 32768 || parts < 16) {
+    k_sum_partials<<<(unsigned)cdiv(count, 256), 256, 0, s>>>(count, parts, stride, partials, out);
+  } else {
+    k_sum_partials_wide<<<dim3((unsigned)cdiv(count, 32), 1), 256, 0, s>>>(count, parts, stride, partials,
+                                                                           parts, out);
+  }
+  GNN_LAUNCH_CHECK();
+  return GNN_OK;
+}
+
+gnn_status_t sum_partials(int64_t count, int parts, const float* partials, float* out, hipStream_t s) {
+  return sum_partials_strided(count, parts, partials, count, out, s);
+}
+
+// Two levels for very many parts: ranges of kSumChunk parts into `scratch`
+// (sum_partials_scratch_rows(parts) rows of `count` floats), then those rows into `out`.
+int sum_partials_scratch_rows(int parts) { return (int)cdiv(parts, kSumChunk); }
+
+gnn_status_t sum_partials_two_level(int64_t count, int parts, const float* partials, float* scratch,
+                                    float* out, hipStream_t s) {
+  if (count <= 0) return GNN_OK;
+  const int rows = sum_partials_scratch_rows(parts);
+  if (rows <= 1) return sum_partials(count, parts, partials, out, s);
+  k_sum_partials_wide<<<dim3((unsigned)cdiv(count, 32), (unsigned)rows), 256, 0, s>>>(
+      count, parts, count, partials, kSumChunk, scratch);
+  GNN_LAUNCH_CHECK();
+  return sum_partials(count, rows, scratch, out, s);
 }
 
 int gemm_pick_split_k(int64_t M, int N, int64_t K) {
@@ -174,8 +232,7 @@ static gnn_status_t launch(int64_t M, int N, int64_t K, const float* a, int64_t 
     ProfScope p("gemm_sum_partials", s);
     int64_t count = M * (int64_t)N;
     if (ldc == N) {
-      k_sum_partials<<<cdiv(count, 256), 256, 0, s>>>(count, split_k, partials, c);
-      GNN_LAUNCH_CHECK();
+      GNN_TRY(sum_partials(count, split_k, partials, c, s));
     } else {
       set_error("gemm_f32: split-K needs a dense output (ldc == N)");
       return GNN_ERR_INVALID_ARG;

@@ -38,18 +38,21 @@ __device__ __forceinline__ float gauss_w(float cu, float cv, float mu0, float mu
 // ---- a9: fused forward -----------------------------------------------------------------
 template <int L, int NV>
 __global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd(
-    int32_t n_rows, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    RowRange rr, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
     const int32_t* __restrict__ indices, const float* __restrict__ hk, const float* __restrict__ c,
     const float* __restrict__ mu, const float* __restrict__ inv_sigma, GmmParams pm,
     float* __restrict__ out) {
   constexpr int G = kWave / L;
   constexpr int GPB = G * (kGmmBlock / kWave);
+  constexpr int NC = 4 * NV;
   __shared__ float lds[GPB * 2 * L];
+  __shared__ float coop_buf[GPB * L * NC];
   const int lane = threadIdx.x & 63;
   const int li = lane & (L - 1);
   const int grp = threadIdx.x / L;
-  const int64_t r = (int64_t)blockIdx.x * GPB + grp;
-  if (r >= n_rows) return;
+  int64_t r;
+  int gi, ngrp;
+  if (!pick_row<GPB>(rr, grp, r, gi, ngrp)) return;
   int* l_idx = reinterpret_cast<int*>(lds + grp * 2 * L);
   float* l_w = lds + grp * 2 * L + L;
 
@@ -79,7 +82,7 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd(
 #pragma unroll
   for (int j = 0; j < NV; ++j) part[j] = make_float4(0.f, 0.f, 0.f, 0.f);
   int chunk_no = 0;
-  for (int32_t c0 = beg; c0 < end; c0 += epc) {
+  for (int32_t c0 = beg + gi * epc; c0 < end; c0 += ngrp * epc) {
     const int32_t e = c0 + e_loc;
     const bool e_ok = e < end;
     const int32_t u = e_ok ? indices[e] : 0;
@@ -110,30 +113,40 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd(
     wave_lds_fence();
   }
 #pragma unroll
+  for (int j = 0; j < NV; ++j) add4(acc[j], part[j]);
+  if (rr.coop) {
+    float vv[NC];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) pack4(vv + 4 * j, acc[j]);
+    coop_sum<L, NC, GPB>(coop_buf, vv, grp, li);
+    if (grp != 0) return;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) acc[j] = unpack4(vv + 4 * j);
+  }
+#pragma unroll
   for (int j = 0; j < NV; ++j)
-    if (slot_ok[j]) {
-      add4(acc[j], part[j]);
-      st4(out + (int64_t)v * F + 4 * (li + j * L), acc[j]);
-    }
+    if (slot_ok[j]) st4(out + (int64_t)v * F + 4 * (li + j * L), acc[j]);
 }
 
 // ---- a10, destination side: gradients of mu and inv_sigma (CSR walk) ------------------
 // partial[block][j][4] = this block's share of (gmu_j0, gmu_j1, gis_j0, gis_j1)
 template <int L, int NV>
 __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_dst(
-    int32_t n_rows, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    RowRange rr, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
     const int32_t* __restrict__ indices, const float* __restrict__ hk, const float* __restrict__ c,
     const float* __restrict__ mu, const float* __restrict__ inv_sigma, const float* __restrict__ gout,
-    GmmParams pm, float* __restrict__ partial) {
+    GmmParams pm, int64_t block_base, float* __restrict__ partial) {
   constexpr int G = kWave / L;
   constexpr int GPB = G * (kGmmBlock / kWave);
   __shared__ float lds[GPB * 2 * L];
   __shared__ float blk[GPB][kMaxK][4];
+  __shared__ float coop_buf[GPB * L * 3];
   const int lane = threadIdx.x & 63;
   const int li = lane & (L - 1);
   const int grp = threadIdx.x / L;
-  const int64_t r = (int64_t)blockIdx.x * GPB + grp;
-  const bool active = r < n_rows;
+  int64_t r;
+  int gi, ngrp;
+  const bool active = pick_row<GPB>(rr, grp, r, gi, ngrp);  // coop: the same for the whole workgroup
   int* l_idx = reinterpret_cast<int*>(lds + grp * 2 * L);
   float* l_c = lds + grp * 2 * L + L;
 
@@ -168,7 +181,7 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_dst(
         aR[j] = aA[j];
         aS[j] = aA[j];
       }
-      for (int32_t c0 = beg; c0 < end; c0 += L) {
+      for (int32_t c0 = beg + gi * L; c0 < end; c0 += ngrp * L) {
         const int32_t e = c0 + li;
         const int32_t u = e < end ? indices[e] : 0;
         l_idx[li] = u;
@@ -216,7 +229,12 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_dst(
       tA = group_sum_from<L>(tA, 1);
       tR = group_sum_from<L>(tR, 1);
       tS = group_sum_from<L>(tS, 1);
-      if (li == 0) {
+      if (rr.coop) {
+        float vv[3] = {tA, tR, tS};
+        coop_sum<L, 3, GPB>(coop_buf, vv, grp, li);
+        tA = vv[0]; tR = vv[1]; tS = vv[2];
+      }
+      if (li == 0 && (!rr.coop || grp == 0)) {
         const float d1 = cv - mu1;
         blk[grp][k][0] = tR * is0 * is0 * inv_k;
         blk[grp][k][1] = tA * d1 * is1 * is1 * inv_k;
@@ -230,37 +248,38 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_dst(
     const int k = threadIdx.x >> 2, q = threadIdx.x & 3;
     float s = 0.f;
     for (int gi = 0; gi < GPB; ++gi) s += blk[gi][k][q];  // fixed order
-    partial[((int64_t)blockIdx.x * kMaxK + k) * 4 + q] = s;
+    partial[((block_base + blockIdx.x) * kMaxK + k) * 4 + q] = s;
   }
 }
 
-// gmu[j,d], gis[j,d] = sum over blocks, in block order
-__global__ void k_gmm_param_final(int K, int64_t nblk, const float* __restrict__ partial,
-                                  float* __restrict__ gmu, float* __restrict__ gis) {
+// totals[j][4] -> gmu[j, 0..1], gis[j, 0..1]
+__global__ void k_gmm_param_split(int K, const float* __restrict__ totals, float* __restrict__ gmu,
+                                  float* __restrict__ gis) {
   const int t = threadIdx.x;  // (k, q)
   if (t >= K * 4) return;
   const int k = t >> 2, q = t & 3;
-  float s = 0.f;
-  for (int64_t b = 0; b < nblk; ++b) s += partial[(b * kMaxK + k) * 4 + q];
-  if (q < 2) gmu[2 * k + q] = s; else gis[2 * k + (q - 2)] = s;
+  if (q < 2) gmu[2 * k + q] = totals[t]; else gis[2 * k + (q - 2)] = totals[t];
 }
 
 // ---- a10, source side: dhk[u,j,:] = (1/K) sum over out-edges w_j(e) gout[v,:] ----------
 template <int L, int NV>
 __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_src(
-    int32_t n_rows, const int32_t* __restrict__ order_t, const int32_t* __restrict__ indptr_t,
+    RowRange rr, const int32_t* __restrict__ order_t, const int32_t* __restrict__ indptr_t,
     const int32_t* __restrict__ indices_t, const float* __restrict__ c, const float* __restrict__ mu,
     const float* __restrict__ inv_sigma, const float* __restrict__ gout, GmmParams pm,
     float* __restrict__ dhk) {
   constexpr int G = kWave / L;
   constexpr int GPB = G * (kGmmBlock / kWave);
   constexpr int KB = 4;  // kernels accumulated per pass over the out-edges
+  constexpr int NC = 4 * KB * NV;
   __shared__ float lds[GPB * 2 * L];
+  __shared__ float coop_buf[GPB * L * NC];
   const int lane = threadIdx.x & 63;
   const int li = lane & (L - 1);
   const int grp = threadIdx.x / L;
-  const int64_t r = (int64_t)blockIdx.x * GPB + grp;
-  if (r >= n_rows) return;
+  int64_t r;
+  int gi, ngrp;
+  if (!pick_row<GPB>(rr, grp, r, gi, ngrp)) return;
   int* l_idx = reinterpret_cast<int*>(lds + grp * 2 * L);
   float* l_c = lds + grp * 2 * L + L;
 
@@ -288,7 +307,7 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_src(
     for (int q = 0; q < KB; ++q)
 #pragma unroll
       for (int j = 0; j < NV; ++j) acc[q][j] = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int32_t c0 = beg; c0 < end; c0 += L) {
+    for (int32_t c0 = beg + gi * L; c0 < end; c0 += ngrp * L) {
       const int32_t i = c0 + li;
       const int32_t v = i < end ? indices_t[i] : 0;
       l_idx[li] = v;
@@ -321,6 +340,19 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_src(
         for (int j = 0; j < NV; ++j) add4(acc[q][j], part[q][j]);
       wave_lds_fence();
     }
+    if (rr.coop) {
+      float vv[NC];
+#pragma unroll
+      for (int q = 0; q < KB; ++q)
+#pragma unroll
+        for (int j = 0; j < NV; ++j) pack4(vv + 4 * (q * NV + j), acc[q][j]);
+      coop_sum<L, NC, GPB>(coop_buf, vv, grp, li);
+#pragma unroll
+      for (int q = 0; q < KB; ++q)
+#pragma unroll
+        for (int j = 0; j < NV; ++j) acc[q][j] = unpack4(vv + 4 * (q * NV + j));
+    }
+    if (!rr.coop || grp == 0)
 #pragma unroll
     for (int q = 0; q < KB; ++q)
       if (k0 + q < K)
@@ -336,12 +368,26 @@ struct GmmFwdLauncher {
                           const float* is, GmmParams pm, float* out, hipStream_t st) {
     constexpr int GPB = (kWave / L) * (kGmmBlock / kWave);
     ProfScope p("gmm_fwd_fused", st);
-    k_gmm_fwd<L, NV><<<(unsigned)cdiv(g->n, GPB), kGmmBlock, 0, st>>>(
-        g->n, g->order[0], g->indptr, g->indices, hk, c, mu, is, pm, out);
-    GNN_LAUNCH_CHECK();
+    const RowSplit sp = split_rows(g, 0, L >> pm.log2Kp, GPB);
+    for (int pass = 0; pass < 2; ++pass) {
+      const RowRange rr = pass == 0 ? sp.hub : sp.rest;
+      const unsigned grid = pass == 0 ? sp.hub_grid : sp.rest_grid;
+      if (grid == 0) continue;
+      k_gmm_fwd<L, NV><<<grid, kGmmBlock, 0, st>>>(rr, g->order[0], g->indptr, g->indices, hk, c, mu, is, pm,
+                                                   out);
+      GNN_LAUNCH_CHECK();
+    }
     return GNN_OK;
   }
 };
+
+// number of workgroups (= partial slots) the destination-side kernel uses
+template <int L>
+static int64_t gmm_dst_blocks(const gnn_graph_t* g) {
+  constexpr int GPB = (kWave / L) * (kGmmBlock / kWave);
+  const RowSplit sp = split_rows(g, 0, L, GPB);
+  return (int64_t)sp.hub_grid + sp.rest_grid;
+}
 
 template <int L, int NV>
 struct GmmBwdDstLauncher {
@@ -349,12 +395,22 @@ struct GmmBwdDstLauncher {
                           const float* is, const float* gout, GmmParams pm, float* partial,
                           float* gmu, float* gis, hipStream_t st) {
     constexpr int GPB = (kWave / L) * (kGmmBlock / kWave);
-    const int64_t nblk = cdiv(g->n, GPB);
     ProfScope p("gmm_bwd_dst", st);
-    k_gmm_bwd_dst<L, NV><<<(unsigned)nblk, kGmmBlock, 0, st>>>(
-        g->n, g->order[0], g->indptr, g->indices, hk, c, mu, is, gout, pm, partial);
-    GNN_LAUNCH_CHECK();
-    k_gmm_param_final<<<1, 64, 0, st>>>(pm.K, nblk, partial, gmu, gis);
+    const RowSplit sp = split_rows(g, 0, L, GPB);
+    int64_t base = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+      const RowRange rr = pass == 0 ? sp.hub : sp.rest;
+      const unsigned grid = pass == 0 ? sp.hub_grid : sp.rest_grid;
+      if (grid == 0) continue;
+      k_gmm_bwd_dst<L, NV><<<grid, kGmmBlock, 0, st>>>(rr, g->order[0], g->indptr, g->indices, hk, c, mu, is,
+                                                       gout, pm, base, partial);
+      GNN_LAUNCH_CHECK();
+      base += grid;
+    }
+    // after the base block slots: one slot for the totals, then the second-level scratch
+    float* totals = partial + base * kMaxK * 4;
+    GNN_TRY(sum_partials_two_level(kMaxK * 4, (int)base, partial, totals + kMaxK * 4, totals, st));
+    k_gmm_param_split<<<1, 64, 0, st>>>(pm.K, totals, gmu, gis);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
   }
@@ -366,9 +422,15 @@ struct GmmBwdSrcLauncher {
                           const float* gout, GmmParams pm, float* dhk, hipStream_t st) {
     constexpr int GPB = (kWave / L) * (kGmmBlock / kWave);
     ProfScope p("gmm_bwd_src", st);
-    k_gmm_bwd_src<L, NV><<<(unsigned)cdiv(g->n, GPB), kGmmBlock, 0, st>>>(
-        g->n, g->order[1], g->indptr_t, g->indices_t, c, mu, is, gout, pm, dhk);
-    GNN_LAUNCH_CHECK();
+    const RowSplit sp = split_rows(g, 1, L, GPB);
+    for (int pass = 0; pass < 2; ++pass) {
+      const RowRange rr = pass == 0 ? sp.hub : sp.rest;
+      const unsigned grid = pass == 0 ? sp.hub_grid : sp.rest_grid;
+      if (grid == 0) continue;
+      k_gmm_bwd_src<L, NV><<<grid, kGmmBlock, 0, st>>>(rr, g->order[1], g->indptr_t, g->indices_t, c, mu, is,
+                                                       gout, pm, dhk);
+      GNN_LAUNCH_CHECK();
+    }
     return GNN_OK;
   }
 };
@@ -393,15 +455,22 @@ struct GmmWs {
   int64_t nblk;
 };
 
-static GmmWs gmm_ws_layout(int64_t n, int fin, int fout, int K) {
+static GmmWs gmm_ws_layout(const gnn_graph_t* g, int fin, int fout, int K) {
+  const int64_t n = g->n;
   GmmWs w{};
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += ws_granule(bytes); return o; };
   const GroupShape gs = pick_group(fout);
-  const int gpb = (kWave / gs.L) * (kGmmBlock / kWave);
-  w.nblk = cdiv(n, gpb);
+  switch (gs.L) {
+    case 4: w.nblk = gmm_dst_blocks<4>(g); break;
+    case 8: w.nblk = gmm_dst_blocks<8>(g); break;
+    case 16: w.nblk = gmm_dst_blocks<16>(g); break;
+    case 32: w.nblk = gmm_dst_blocks<32>(g); break;
+    default: w.nblk = gmm_dst_blocks<64>(g); break;
+  }
   w.dhk = take(sizeof(float) * (size_t)n * K * fout);
-  w.partial = take(sizeof(float) * (size_t)w.nblk * kMaxK * 4);
+  // block slots + one slot for the totals + second-level scratch
+  w.partial = take(sizeof(float) * (size_t)(w.nblk + 1 + sum_partials_scratch_rows((int)w.nblk)) * kMaxK * 4);
   w.split_k = gemm_pick_split_k(fin, K * fout, n);
   w.gemm = take(w.split_k > 1 ? sizeof(float) * (size_t)w.split_k * fin * K * fout : 0);
   w.total = off;
@@ -426,7 +495,7 @@ using namespace gnn;
 
 extern "C" size_t gnn_gmm_workspace_bytes(const gnn_graph_t* g, int fin, int fout, int k) {
   if (!g || fin <= 0 || fout <= 0 || k <= 0) return 0;
-  return gmm_ws_layout(g->n, fin, fout, k).total;
+  return gmm_ws_layout(g, fin, fout, k).total;
 }
 
 extern "C" gnn_status_t gnn_gmm_fwd(const gnn_graph_t* g, int fin, int fout, int k, const float* x,
@@ -460,7 +529,7 @@ extern "C" gnn_status_t gnn_gmm_bwd(const gnn_graph_t* g, int fin, int fout, int
               GNN_ERR_INVALID_ARG, "gnn_gmm_bwd: null pointer");
   GNN_REQUIRE(aligned16(hk) && aligned16(gout), GNN_ERR_INVALID_ARG,
               "gnn_gmm_bwd: hk, gout must be 16-byte aligned");
-  const GmmWs L = gmm_ws_layout(g->n, fin, fout, k);
+  const GmmWs L = gmm_ws_layout(g, fin, fout, k);
   GNN_REQUIRE(ws != nullptr && ws_bytes >= L.total, GNN_ERR_WORKSPACE,
               "gnn_gmm_bwd: workspace of %zu bytes given, %zu needed", ws_bytes, L.total);
   GNN_REQUIRE(aligned16(ws), GNN_ERR_INVALID_ARG, "gnn_gmm_bwd: workspace must be 16-byte aligned");

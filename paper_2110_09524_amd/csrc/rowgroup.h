@@ -66,6 +66,57 @@ __device__ __forceinline__ void scale4(float4& a, float s) {
   a.x *= s; a.y *= s; a.z *= s; a.w *= s;
 }
 
+// ---- which row a group works on ---------------------------------------------------
+// Normal launches give every group its own row.  Rows whose degree is many chunks
+// long would make one group loop for a long time while the rest of the chip is idle
+// (power-law hubs), so the heaviest rows (a prefix of the degree order) are launched
+// "cooperatively": all groups of a workgroup share one row, take its chunks round-robin,
+// and fold their partial sums through LDS in group order (deterministic).
+struct RowRange {
+  int32_t begin, end;  // positions in the degree order
+  int coop;            // 1: one row per workgroup
+};
+
+template <int GPB>
+__device__ __forceinline__ bool pick_row(const RowRange& rr, int grp, int64_t& r, int& gi, int& ngrp) {
+  if (rr.coop) {
+    r = (int64_t)rr.begin + blockIdx.x;
+    gi = grp;
+    ngrp = GPB;
+  } else {
+    r = (int64_t)rr.begin + (int64_t)blockIdx.x * GPB + grp;
+    gi = 0;
+    ngrp = 1;
+  }
+  return r < rr.end;
+}
+
+// Adds the N per-lane values of groups 1..GPB-1 onto group 0's, in group order.  Every
+// thread of the workgroup must call it; afterwards only group 0 holds the totals.
+// buf: GPB * L * N floats of LDS.
+template <int L, int N, int GPB>
+__device__ __forceinline__ void coop_sum(float* buf, float (&v)[N], int grp, int li) {
+  if (grp != 0) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) buf[(grp * N + i) * L + li] = v[i];
+  }
+  __syncthreads();
+  if (grp == 0) {
+    for (int g = 1; g < GPB; ++g) {
+#pragma unroll
+      for (int i = 0; i < N; ++i) v[i] += buf[(g * N + i) * L + li];
+    }
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ void pack4(float* dst, const float4& a) {
+  dst[0] = a.x; dst[1] = a.y; dst[2] = a.z; dst[3] = a.w;
+}
+__device__ __forceinline__ float4 unpack4(const float* src) {
+  return make_float4(src[0], src[1], src[2], src[3]);
+}
+
 // Host-side choice of the group shape for a row of `width` floats (width % 4 == 0).
 struct GroupShape {
   int L;   // lanes per group
@@ -87,6 +138,26 @@ inline int ilog2(int p) {
   int l = 0;
   while ((1 << l) < p) ++l;
   return l;
+}
+
+// Split of one side's degree order into a cooperative prefix (rows at least
+// kCoopChunks chunks long) and the rest, with the grids of the two launches.
+constexpr int kCoopChunks = 16;
+struct RowSplit {
+  RowRange hub, rest;
+  unsigned hub_grid, rest_grid;
+};
+inline RowSplit split_rows(const gnn_graph* g, int side, int chunk_edges, int gpb) {
+  const int thr = next_pow2(kCoopChunks * chunk_edges);  // degree threshold, a power of two
+  const int k = ilog2(thr);
+  // degree >= 2^k  <=>  clz32(degree) <= 31 - k: a prefix of the degree order
+  int32_t n_hub = k >= 31 ? 0 : g->h_bucket_offsets[side][32 - k];
+  RowSplit s;
+  s.hub = RowRange{0, n_hub, 1};
+  s.rest = RowRange{n_hub, g->n, 0};
+  s.hub_grid = (unsigned)n_hub;
+  s.rest_grid = (unsigned)((g->n - n_hub + gpb - 1) / gpb);
+  return s;
 }
 
 }  // namespace gnn
