@@ -158,6 +158,8 @@ def main():
     ap.add_argument("--workload", default="gat_c4")
     ap.add_argument("--cpu-rows", type=int, default=2048, help="destination rows of the CPU baseline sample (GAT)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--compare-unfused", action="store_true",
+                    help="also time the one-operator-per-kernel comparator (GAT with heads*f = 256)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -303,6 +305,12 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic", "config": cfg, "roofline": roofline, "kernels": kern,
     }
+    if args.compare_unfused and kind == "gat":
+        from unfused_baseline.compare import compare_gat
+        dz_fused = ws.view(torch.float32)[: n * HF].view(n, HF)     # first workspace region holds dz
+        result["unfused_comparison"] = compare_gat(
+            c, g, indptr, indices, z, el, er, gout, a_l, a_r, out, dz_fused,
+            {k: v["ms_per_step"] for k, v in kern.items()})
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample ...", file=sys.stderr, flush=True)
         result["cpu_baseline"] = cpu_baseline_gat(c, args.cpu_rows) if kind == "gat" else cpu_baseline_full(c)

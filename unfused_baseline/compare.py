@@ -1,0 +1,96 @@
+"""Times the one-operator-per-kernel comparator against the fused edge kernels on the same
+device tensors and reports time, stash and peak-intermediate-memory ratios."""
+import ctypes as C
+
+import numpy as np
+import torch
+
+from . import load
+
+
+def _p(t):
+    return C.c_void_p(t.data_ptr())
+
+
+class UnfusedGat:
+    def __init__(self, c, g, indptr, indices):
+        self.lib = load()
+        self.n, self.nnz, self.H, self.F = c["n"], c["nnz"], c["heads"], c["f"]
+        dev = indptr.device
+        self.indptr, self.indices = indptr, indices
+        deg = (indptr[1:] - indptr[:-1]).to(torch.int64)
+        self.dst = torch.repeat_interleave(torch.arange(self.n, device=dev, dtype=torch.int32), deg)
+        self.indptr_t, self.indices_t, self.eid_t = g.csc()
+        EH, NH, NHF = self.nnz * self.H, self.n * self.H, self.n * self.H * self.F
+        f = lambda k: torch.empty(k, dtype=torch.float32, device=dev)
+        # per-edge tensors: M0, M2 are stashed for backward; M1, EX, dM2, tmp, dM0 are transient
+        self.M0, self.M1, self.EX, self.M2 = f(EH), f(EH), f(EH), f(EH)
+        self.dM2, self.tmp, self.dM0 = f(EH), f(EH), f(EH)
+        self.mx, self.den, self.t, self.der, self.del_ = f(NH), f(NH), f(NH), f(NH), f(NH)
+        self.out, self.dz = f(NHF), f(NHF)
+        self.slope = float(c["slope"])
+
+    def fwd(self, z, el, er):
+        st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        rc = self.lib.unfused_gat_graph_fwd(self.n, self.nnz, self.H, self.F, self.slope, _p(self.indptr),
+                                            _p(self.indices), _p(self.dst), _p(z), _p(el), _p(er), _p(self.M0),
+                                            _p(self.M1), _p(self.mx), _p(self.EX), _p(self.den), _p(self.M2),
+                                            _p(self.out), st)
+        if rc:
+            raise RuntimeError(f"unfused_gat_graph_fwd failed: {rc}")
+
+    def bwd(self, z, gout, a_l, a_r):
+        st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        rc = self.lib.unfused_gat_graph_bwd(self.n, self.nnz, self.H, self.F, self.slope, _p(self.indptr),
+                                            _p(self.indices), _p(self.dst), _p(self.indptr_t),
+                                            _p(self.indices_t), _p(self.eid_t), _p(z), _p(gout), _p(a_l),
+                                            _p(a_r), _p(self.M0), _p(self.M2), _p(self.dM2), _p(self.tmp),
+                                            _p(self.t), _p(self.dM0), _p(self.der), _p(self.del_), _p(self.dz), st)
+        if rc:
+            raise RuntimeError(f"unfused_gat_graph_bwd failed: {rc}")
+
+    def stash_bytes(self):
+        return 2 * 4 * self.nnz * self.H                  # M0, M2
+
+    def peak_intermediate_bytes(self):
+        return 4 * 4 * self.nnz * self.H                  # M0, M2 stashed + two transient per-edge tensors
+
+
+def timed(fn, reps=3):
+    fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def compare_gat(c, g, indptr, indices, z, el, er, gout, a_l, a_r, out_fused, dz_fused, fused_kernels):
+    """fused_kernels: {name: ms_per_step} of the library's kernels (from its HIP-event brackets)."""
+    u = UnfusedGat(c, g, indptr, indices)
+    t_fwd = timed(lambda: u.fwd(z, el, er))
+    t_bwd = timed(lambda: u.bwd(z, gout, a_l, a_r))
+    n, H, F, e = u.n, u.H, u.F, u.nnz
+    err_out = float((u.out.view(n, -1) - out_fused).abs().max())
+    err_dz = float((u.dz.view(n, -1) - dz_fused).abs().max())
+    graph_names = ("gat_softmax_stats", "gat_fwd_fused", "gat_bwd_dst", "gat_bwd_dst_finish", "gat_bwd_src",
+                   "gat_bwd_src_finish", "gat_head_major")
+    fused_ms = sum(v for k, v in fused_kernels.items() if k in graph_names)
+    fused_stash = 4 * n * H * F + 3 * 4 * n * H          # t + sg, m, d
+    V, E = n, e
+    return {
+        "scope": "graph-related operators only (projection, attention halves, parameter gradients are common)",
+        "unfused_graph_ms": {"fwd": t_fwd, "bwd": t_bwd, "total": t_fwd + t_bwd},
+        "fused_graph_ms": fused_ms,
+        "time_ratio_unfused_over_fused": (t_fwd + t_bwd) / fused_ms,
+        "stash_bytes": {"unfused_per_edge_tensors": u.stash_bytes(), "fused_vertex_tensors": fused_stash,
+                        "ratio": u.stash_bytes() / fused_stash},
+        "peak_intermediate_bytes": {"unfused": u.peak_intermediate_bytes(),
+                                    "fused": fused_stash, "ratio": u.peak_intermediate_bytes() / fused_stash},
+        "paper_io_closed_form_elements": {           # Sec. 5 example, forward graph operators
+            "unfused": V * H * F + 7 * E * H + 3 * E * H * F, "fused": V * H * F + 5 * E * H + 2 * E * H * F},
+        "max_abs_diff_vs_fused": {"out": err_out, "dz": err_dz},
+    }
