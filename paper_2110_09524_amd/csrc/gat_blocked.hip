@@ -168,8 +168,8 @@ __global__ __launch_bounds__(kBlkThreads) void k_gat_blk(
       s.r_d = d_in[rh];
     }
     if (!first) {
-      s.acc = ld4(acc_buf + (int64_t)s.row * HF + col);
-      if (DUAL) s.acc2 = ld4(acc2_buf + (int64_t)s.row * HF + col);
+      s.acc = ld4_stream(acc_buf + (int64_t)s.row * HF + col);
+      if (DUAL) s.acc2 = ld4_stream(acc2_buf + (int64_t)s.row * HF + col);
       if (MODE != 0 && leader && li == 0) s.scal = scal_buf[rh];
     }
   };
@@ -270,8 +270,8 @@ __global__ __launch_bounds__(kBlkThreads) void k_gat_blk(
         if (DUAL) add4(acc2, part2);
         wave_lds_fence();
       }
-      st4(acc_buf + (int64_t)cur.row * HF + col, acc);
-      if (DUAL) st4(acc2_buf + (int64_t)cur.row * HF + col, acc2);
+      st4_stream(acc_buf + (int64_t)cur.row * HF + col, acc);
+      if (DUAL) st4_stream(acc2_buf + (int64_t)cur.row * HF + col, acc2);
       if (MODE != 0 && leader) {
         const float tot = group_sum_from<SL>(s_run, 1);
         if (li == 0) scal_buf[(int64_t)cur.row * H + h] = cur.scal + tot;

@@ -41,6 +41,17 @@ __device__ __forceinline__ float group_sum_from(float v, int lo_stride) {
 
 __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
 __device__ __forceinline__ void st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+// streaming variants: data that is touched once per launch is marked non-temporal so that it
+// does not displace the cache-resident gathered rows
+typedef float nt_f4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 ld4_stream(const float* p) {
+  const nt_f4 v = __builtin_nontemporal_load(reinterpret_cast<const nt_f4*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st4_stream(float* p, float4 v) {
+  nt_f4 w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, reinterpret_cast<nt_f4*>(p));
+}
 __device__ __forceinline__ void fma4(float4& acc, float s, const float4& v) {
   acc.x = fmaf(s, v.x, acc.x);
   acc.y = fmaf(s, v.y, acc.y);
