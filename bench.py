@@ -296,14 +296,25 @@ def main():
         "bytes_model": "minimal unique bytes: every array the kernel touches counted once",
         "gather_model_GBps": kern[dom]["gather_model_GBps"],
         "fp32_alu_frac": kern[dom]["fp32_TFLOPs"] / FP32_VECTOR_TFLOPS,
+        # the larger of the two floors of this kernel (unique bytes at HBM speed, flops at the
+        # fp32 vector peak) over its measured time
+        "frac_combined": max(unique[dom] / (HBM_PEAK_GBPS * 1e9), flops[dom] / (FP32_VECTOR_TFLOPS * 1e12))
+                         / (kern[dom]["ms_per_step"] * 1e-3),
     }
+    # whole-layer floor: edge kernels at max(unique bytes / HBM, flops / fp32 vector peak), the
+    # three dense products at the fp32 MFMA peak
+    floor_s = sum(max(unique[k] / (HBM_PEAK_GBPS * 1e9), flops[k] / (FP32_VECTOR_TFLOPS * 1e12)) for k in unique)
+    floor_s += 3 * gemm_flops / (FP32_VECTOR_TFLOPS * 1e12)
+    layer_floor = {"floor_ms": floor_s * 1e3, "frac": floor_s * 1e3 / ms_per_step,
+                   "edge_kernels_ms_per_step": sum(kern[k]["ms_per_step"] for k in edge_kernels),
+                   "edge_kernels_edges_per_s": e / (1e-3 * sum(kern[k]["ms_per_step"] for k in edge_kernels))}
     cfg.update(workload=args.workload, vertices=n, edges=e, plan_ms_once_per_graph=1e3 * t_plan,
                workspace_bytes=ws_bytes)
     result = {
         "metric": metric, "value": edges_per_s, "unit": "edges/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
-        "data": "synthetic", "config": cfg, "roofline": roofline, "kernels": kern,
+        "data": "synthetic", "config": cfg, "roofline": roofline, "layer_floor": layer_floor, "kernels": kern,
     }
     if args.compare_unfused and kind == "gat":
         from unfused_baseline.compare import compare_gat
