@@ -303,7 +303,7 @@ def main():
     }
     # whole-layer floor: edge kernels at max(unique bytes / HBM, flops / fp32 vector peak), the
     # three dense products at the fp32 MFMA peak
-    floor_s = sum(max(unique[k] / (HBM_PEAK_GBPS * 1e9), flops[k] / (FP32_VECTOR_TFLOPS * 1e12)) for k in unique)
+    floor_s = sum(max(unique[k] / (HBM_PEAK_GBPS * 1e9), flops[k] / (FP32_VECTOR_TFLOPS * 1e12)) for k in edge_kernels)
     floor_s += 3 * gemm_flops / (FP32_VECTOR_TFLOPS * 1e12)
     layer_floor = {"floor_ms": floor_s * 1e3, "frac": floor_s * 1e3 / ms_per_step,
                    "edge_kernels_ms_per_step": sum(kern[k]["ms_per_step"] for k in edge_kernels),

@@ -35,6 +35,15 @@ __device__ __forceinline__ float gauss_w(float cu, float cv, float mu0, float mu
   return __expf(-0.5f * (t0 * t0 + t1 * t1));
 }
 
+constexpr int kGmmKB = 4;  // kernels handled per pass over a row's edges
+constexpr int kGmmU = 2;   // edges whose rows are in flight together in the row phase
+
+// Both destination-walking kernels work on chunks of L edges in two phases.  Chunk phase:
+// lane li owns edge c0 + li, gathers c[u] and evaluates the Gaussian weights of up to kGmmKB
+// kernels (one exp per edge and kernel, not one per lane); edges past the end of the row
+// become vertex 0 with weight 0, so the row phase needs no per-edge conditionals.  Row phase:
+// lanes own columns; kGmmU edges x kGmmKB kernel rows are loaded before they are used.
+
 // ---- a9: fused forward -----------------------------------------------------------------
 template <int L, int NV>
 __global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd(
@@ -44,8 +53,10 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd(
     float* __restrict__ out) {
   constexpr int G = kWave / L;
   constexpr int GPB = G * (kGmmBlock / kWave);
+  constexpr int KB = kGmmKB, U = kGmmU;
   constexpr int NC = 4 * NV;
-  __shared__ float lds[GPB * 2 * L];
+  constexpr int GS = (1 + KB) * L;  // LDS floats per group: idx | w[KB][L]
+  __shared__ __align__(16) float lds[GPB * GS];
   __shared__ float coop_buf[GPB * L * NC];
   const int lane = threadIdx.x & 63;
   const int li = lane & (L - 1);
@@ -53,67 +64,82 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd(
   int64_t r;
   int gi, ngrp;
   if (!pick_row<GPB>(rr, grp, r, gi, ngrp)) return;
-  int* l_idx = reinterpret_cast<int*>(lds + grp * 2 * L);
-  float* l_w = lds + grp * 2 * L + L;
+  int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
+  float* l_w = lds + grp * GS + L;
 
   const int K = pm.K, F = pm.F, KF = K * F;
-  const int Kp = 1 << pm.log2Kp;
-  const int epc = L >> pm.log2Kp;
-  const int e_loc = li >> pm.log2Kp;
-  const int kk = li & (Kp - 1);
-  const bool k_ok = kk < K;
-  const float mu0 = k_ok ? mu[2 * kk] : 0.f, mu1 = k_ok ? mu[2 * kk + 1] : 0.f;
-  const float is0 = k_ok ? inv_sigma[2 * kk] : 0.f, is1 = k_ok ? inv_sigma[2 * kk + 1] : 0.f;
   const float inv_k = 1.f / (float)K;
-
   const int32_t v = order[r];
   const int32_t beg = indptr[v], end = indptr[v + 1];
   const float cv = c[v];
 
   bool slot_ok[NV];
-  float4 acc[NV];
+  float4 acc[NV], part[NV];  // two-level summation: `part` collects a few chunks, then folds into `acc`
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
     slot_ok[j] = 4 * (li + j * L) < F;
     acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    part[j] = acc[j];
   }
-  // two-level summation: `part` collects a few chunks, then folds into `acc`
-  float4 part[NV];
+  for (int k0 = 0; k0 < K; k0 += KB) {
+    float mu0[KB], mu1[KB], is0[KB], is1[KB];
 #pragma unroll
-  for (int j = 0; j < NV; ++j) part[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-  int chunk_no = 0;
-  for (int32_t c0 = beg + gi * epc; c0 < end; c0 += ngrp * epc) {
-    const int32_t e = c0 + e_loc;
-    const bool e_ok = e < end;
-    const int32_t u = e_ok ? indices[e] : 0;
-    float w = 0.f;
-    if (e_ok && k_ok) w = gauss_w(c[u], cv, mu0, mu1, is0, is1) * inv_k;
-    if (kk == 0) l_idx[e_loc] = u;
-    l_w[li] = w;
-    wave_lds_fence();
-    const int cnt = min(epc, end - c0);
-    for (int t = 0; t < cnt; ++t) {
-      int uu = l_idx[t];
-      if (L == 64) uu = __builtin_amdgcn_readfirstlane(uu);
-      const float* row = hk + (int64_t)uu * KF;
-      for (int k = 0; k < K; ++k) {
-        const float wk = l_w[(t << pm.log2Kp) + k];
-#pragma unroll
-        for (int j = 0; j < NV; ++j)
-          if (slot_ok[j]) fma4(part[j], wk, ld4(row + k * F + 4 * (li + j * L)));
-      }
+    for (int q = 0; q < KB; ++q) {
+      const bool ok = k0 + q < K;
+      mu0[q] = ok ? mu[2 * (k0 + q)] : 0.f;
+      mu1[q] = ok ? mu[2 * (k0 + q) + 1] : 0.f;
+      is0[q] = ok ? inv_sigma[2 * (k0 + q)] : 0.f;
+      is1[q] = ok ? inv_sigma[2 * (k0 + q) + 1] : 0.f;
     }
-    if ((++chunk_no & 3) == 0) {
+    int chunk_no = 0;
+    for (int32_t c0 = beg + gi * L; c0 < end; c0 += ngrp * L) {
+      const bool e_ok = c0 + li < end;
+      const int32_t u = e_ok ? indices[c0 + li] : 0;
+      const float cu = c[u];
+      l_idx[li] = u;
 #pragma unroll
-      for (int j = 0; j < NV; ++j) {
-        add4(acc[j], part[j]);
-        part[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int q = 0; q < KB; ++q)
+        l_w[q * L + li] = (e_ok && k0 + q < K) ? gauss_w(cu, cv, mu0[q], mu1[q], is0[q], is1[q]) * inv_k : 0.f;
+      wave_lds_fence();
+      const int cnt = min(L, end - c0);
+      for (int t0 = 0; t0 < cnt; t0 += U) {
+        int uu[U];
+#pragma unroll
+        for (int t = 0; t < U; ++t) {
+          uu[t] = l_idx[t0 + t];
+          if (L == 64) uu[t] = __builtin_amdgcn_readfirstlane(uu[t]);
+        }
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+          if (!slot_ok[j]) continue;
+          float4 rowv[U][KB];
+#pragma unroll
+          for (int t = 0; t < U; ++t)
+#pragma unroll
+            for (int q = 0; q < KB; ++q)
+              if (k0 + q < K) rowv[t][q] = ld4(hk + (int64_t)uu[t] * KF + (k0 + q) * F + 4 * (li + j * L));
+#pragma unroll
+          for (int t = 0; t < U; ++t)
+#pragma unroll
+            for (int q = 0; q < KB; ++q)
+              if (k0 + q < K) fma4(part[j], l_w[q * L + t0 + t], rowv[t][q]);
+        }
       }
+      if ((++chunk_no & 3) == 0) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+          add4(acc[j], part[j]);
+          part[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+      }
+      wave_lds_fence();
     }
-    wave_lds_fence();
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      add4(acc[j], part[j]);
+      part[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
   }
-#pragma unroll
-  for (int j = 0; j < NV; ++j) add4(acc[j], part[j]);
   if (rr.coop) {
     float vv[NC];
 #pragma unroll
@@ -138,7 +164,9 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_dst(
     GmmParams pm, int64_t block_base, float* __restrict__ partial) {
   constexpr int G = kWave / L;
   constexpr int GPB = G * (kGmmBlock / kWave);
-  __shared__ float lds[GPB * 2 * L];
+  constexpr int KB = kGmmKB, U = kGmmU;
+  constexpr int GS = (1 + 3 * KB) * L;  // LDS floats per group: idx | w[KB][L] | wr[KB][L] | ws[KB][L]
+  __shared__ __align__(16) float lds[GPB * GS];
   __shared__ float blk[GPB][kMaxK][4];
   __shared__ float coop_buf[GPB * L * 3];
   const int lane = threadIdx.x & 63;
@@ -147,8 +175,10 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_dst(
   int64_t r;
   int gi, ngrp;
   const bool active = pick_row<GPB>(rr, grp, r, gi, ngrp);  // coop: the same for the whole workgroup
-  int* l_idx = reinterpret_cast<int*>(lds + grp * 2 * L);
-  float* l_c = lds + grp * 2 * L + L;
+  int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
+  float* l_w = lds + grp * GS + L;
+  float* l_wr = l_w + KB * L;
+  float* l_ws = l_wr + KB * L;
 
   const int K = pm.K, F = pm.F, KF = K * F;
   const float inv_k = 1.f / (float)K;
@@ -171,75 +201,96 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_dst(
       slot_ok[j] = 4 * (li + j * L) < F;
       g4[j] = slot_ok[j] ? ld4(gout + (int64_t)v * F + 4 * (li + j * L)) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    for (int k = 0; k < K; ++k) {  // one pass per kernel: each pass reads its own slice of hk
-      const float mu0 = mu[2 * k], mu1 = mu[2 * k + 1];
-      const float is0 = inv_sigma[2 * k], is1 = inv_sigma[2 * k + 1];
-      float4 aA[NV], aR[NV], aS[NV];
+    for (int k0 = 0; k0 < K; k0 += KB) {
+      float mu0[KB], mu1[KB], is0[KB], is1[KB];
 #pragma unroll
-      for (int j = 0; j < NV; ++j) {
-        aA[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-        aR[j] = aA[j];
-        aS[j] = aA[j];
+      for (int q = 0; q < KB; ++q) {
+        const bool ok = k0 + q < K;
+        mu0[q] = ok ? mu[2 * (k0 + q)] : 0.f;
+        mu1[q] = ok ? mu[2 * (k0 + q) + 1] : 0.f;
+        is0[q] = ok ? inv_sigma[2 * (k0 + q)] : 0.f;
+        is1[q] = ok ? inv_sigma[2 * (k0 + q) + 1] : 0.f;
       }
+      // a row that is not shared by the workgroup has fewer than kCoopChunks chunks, a shared
+      // one is cut into GPB interleaved parts: either way one running sum sees few terms
+      float4 aA[KB][NV], aR[KB][NV], aS[KB][NV];
+#pragma unroll
+      for (int q = 0; q < KB; ++q)
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+          aA[q][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+          aR[q][j] = aA[q][j];
+          aS[q][j] = aA[q][j];
+        }
       for (int32_t c0 = beg + gi * L; c0 < end; c0 += ngrp * L) {
-        const int32_t e = c0 + li;
-        const int32_t u = e < end ? indices[e] : 0;
+        const bool e_ok = c0 + li < end;
+        const int32_t u = e_ok ? indices[c0 + li] : 0;
+        const float cu = c[u];
         l_idx[li] = u;
-        l_c[li] = c[u];
-        wave_lds_fence();
-        float4 pA[NV], pR[NV], pS[NV];  // this chunk's share (two-level summation)
 #pragma unroll
-        for (int j = 0; j < NV; ++j) {
-          pA[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-          pR[j] = pA[j];
-          pS[j] = pA[j];
+        for (int q = 0; q < KB; ++q) {
+          const float w = (e_ok && k0 + q < K) ? gauss_w(cu, cv, mu0[q], mu1[q], is0[q], is1[q]) : 0.f;
+          const float d0 = cu - mu0[q];
+          l_w[q * L + li] = w;
+          l_wr[q * L + li] = w * d0;
+          l_ws[q * L + li] = w * d0 * d0;
         }
+        wave_lds_fence();
         const int cnt = min(L, end - c0);
-        for (int t = 0; t < cnt; ++t) {
-          int uu = l_idx[t];
-          if (L == 64) uu = __builtin_amdgcn_readfirstlane(uu);
-          const float cu = l_c[t];
-          const float w = gauss_w(cu, cv, mu0, mu1, is0, is1);
-          const float d0 = cu - mu0;
-          const float wr = w * d0, wsq = wr * d0;
+        for (int t0 = 0; t0 < cnt; t0 += U) {
+          int uu[U];
 #pragma unroll
-          for (int j = 0; j < NV; ++j)
-            if (slot_ok[j]) {
-              const float4 row = ld4(hk + (int64_t)uu * KF + k * F + 4 * (li + j * L));
-              fma4(pA[j], w, row);
-              fma4(pR[j], wr, row);
-              fma4(pS[j], wsq, row);
-            }
-        }
+          for (int t = 0; t < U; ++t) {
+            uu[t] = l_idx[t0 + t];
+            if (L == 64) uu[t] = __builtin_amdgcn_readfirstlane(uu[t]);
+          }
 #pragma unroll
-        for (int j = 0; j < NV; ++j) {
-          add4(aA[j], pA[j]);
-          add4(aR[j], pR[j]);
-          add4(aS[j], pS[j]);
+          for (int j = 0; j < NV; ++j) {
+            if (!slot_ok[j]) continue;
+            float4 rowv[U][KB];
+#pragma unroll
+            for (int t = 0; t < U; ++t)
+#pragma unroll
+              for (int q = 0; q < KB; ++q)
+                if (k0 + q < K) rowv[t][q] = ld4(hk + (int64_t)uu[t] * KF + (k0 + q) * F + 4 * (li + j * L));
+#pragma unroll
+            for (int t = 0; t < U; ++t)
+#pragma unroll
+              for (int q = 0; q < KB; ++q)
+                if (k0 + q < K) {
+                  fma4(aA[q][j], l_w[q * L + t0 + t], rowv[t][q]);
+                  fma4(aR[q][j], l_wr[q * L + t0 + t], rowv[t][q]);
+                  fma4(aS[q][j], l_ws[q * L + t0 + t], rowv[t][q]);
+                }
+          }
         }
         wave_lds_fence();
       }
-      float tA = 0.f, tR = 0.f, tS = 0.f;
 #pragma unroll
-      for (int j = 0; j < NV; ++j) {
-        tA += dot4(g4[j], aA[j]);
-        tR += dot4(g4[j], aR[j]);
-        tS += dot4(g4[j], aS[j]);
-      }
-      tA = group_sum_from<L>(tA, 1);
-      tR = group_sum_from<L>(tR, 1);
-      tS = group_sum_from<L>(tS, 1);
-      if (rr.coop) {
-        float vv[3] = {tA, tR, tS};
-        coop_sum<L, 3, GPB>(coop_buf, vv, grp, li);
-        tA = vv[0]; tR = vv[1]; tS = vv[2];
-      }
-      if (li == 0 && (!rr.coop || grp == 0)) {
-        const float d1 = cv - mu1;
-        blk[grp][k][0] = tR * is0 * is0 * inv_k;
-        blk[grp][k][1] = tA * d1 * is1 * is1 * inv_k;
-        blk[grp][k][2] = -tS * is0 * inv_k;
-        blk[grp][k][3] = -tA * d1 * d1 * is1 * inv_k;
+      for (int q = 0; q < KB; ++q) {
+        if (k0 + q >= K) continue;
+        float tA = 0.f, tR = 0.f, tS = 0.f;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+          tA += dot4(g4[j], aA[q][j]);
+          tR += dot4(g4[j], aR[q][j]);
+          tS += dot4(g4[j], aS[q][j]);
+        }
+        tA = group_sum_from<L>(tA, 1);
+        tR = group_sum_from<L>(tR, 1);
+        tS = group_sum_from<L>(tS, 1);
+        if (rr.coop) {
+          float vv[3] = {tA, tR, tS};
+          coop_sum<L, 3, GPB>(coop_buf, vv, grp, li);
+          tA = vv[0]; tR = vv[1]; tS = vv[2];
+        }
+        if (li == 0 && (!rr.coop || grp == 0)) {
+          const float d1 = cv - mu1[q];
+          blk[grp][k0 + q][0] = tR * is0[q] * is0[q] * inv_k;
+          blk[grp][k0 + q][1] = tA * d1 * is1[q] * is1[q] * inv_k;
+          blk[grp][k0 + q][2] = -tS * is0[q] * inv_k;
+          blk[grp][k0 + q][3] = -tA * d1 * d1 * is1[q] * inv_k;
+        }
       }
     }
   }
@@ -270,9 +321,11 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_src(
     float* __restrict__ dhk) {
   constexpr int G = kWave / L;
   constexpr int GPB = G * (kGmmBlock / kWave);
-  constexpr int KB = 4;  // kernels accumulated per pass over the out-edges
+  constexpr int KB = kGmmKB;  // kernels accumulated per pass over the out-edges
+  constexpr int U = 4;        // gathered rows in flight per lane
   constexpr int NC = 4 * KB * NV;
-  __shared__ float lds[GPB * 2 * L];
+  constexpr int GS = (1 + KB) * L;  // LDS floats per group: idx | w[KB][L]
+  __shared__ __align__(16) float lds[GPB * GS];
   __shared__ float coop_buf[GPB * L * NC];
   const int lane = threadIdx.x & 63;
   const int li = lane & (L - 1);
@@ -280,8 +333,8 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_src(
   int64_t r;
   int gi, ngrp;
   if (!pick_row<GPB>(rr, grp, r, gi, ngrp)) return;
-  int* l_idx = reinterpret_cast<int*>(lds + grp * 2 * L);
-  float* l_c = lds + grp * 2 * L + L;
+  int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
+  float* l_w = lds + grp * GS + L;
 
   const int K = pm.K, F = pm.F, KF = K * F;
   const float inv_k = 1.f / (float)K;
@@ -308,10 +361,14 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_src(
 #pragma unroll
       for (int j = 0; j < NV; ++j) acc[q][j] = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int32_t c0 = beg + gi * L; c0 < end; c0 += ngrp * L) {
-      const int32_t i = c0 + li;
-      const int32_t v = i < end ? indices_t[i] : 0;
+      // chunk phase: lane li owns out-edge c0 + li; edges past the end become vertex 0, weight 0
+      const bool e_ok = c0 + li < end;
+      const int32_t v = e_ok ? indices_t[c0 + li] : 0;
+      const float cv = c[v];
       l_idx[li] = v;
-      l_c[li] = c[v];
+#pragma unroll
+      for (int q = 0; q < KB; ++q)
+        l_w[q * L + li] = (e_ok && k0 + q < K) ? gauss_w(cu, cv, mu0[q], mu1[q], is0[q], is1[q]) * inv_k : 0.f;
       wave_lds_fence();
       float4 part[KB][NV];  // this chunk's share (two-level summation)
 #pragma unroll
@@ -319,20 +376,24 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_src(
 #pragma unroll
         for (int j = 0; j < NV; ++j) part[q][j] = make_float4(0.f, 0.f, 0.f, 0.f);
       const int cnt = min(L, end - c0);
-      for (int t = 0; t < cnt; ++t) {
-        int vv = l_idx[t];
-        if (L == 64) vv = __builtin_amdgcn_readfirstlane(vv);
-        const float cv = l_c[t];
-        float w[KB];
+      for (int t0 = 0; t0 < cnt; t0 += U) {
+        int vv[U];
 #pragma unroll
-        for (int q = 0; q < KB; ++q) w[q] = gauss_w(cu, cv, mu0[q], mu1[q], is0[q], is1[q]) * inv_k;
+        for (int t = 0; t < U; ++t) {
+          vv[t] = l_idx[t0 + t];
+          if (L == 64) vv[t] = __builtin_amdgcn_readfirstlane(vv[t]);
+        }
 #pragma unroll
-        for (int j = 0; j < NV; ++j)
-          if (slot_ok[j]) {
-            const float4 row = ld4(gout + (int64_t)vv * F + 4 * (li + j * L));
+        for (int j = 0; j < NV; ++j) {
+          if (!slot_ok[j]) continue;
+          float4 rowv[U];
 #pragma unroll
-            for (int q = 0; q < KB; ++q) fma4(part[q][j], w[q], row);
-          }
+          for (int t = 0; t < U; ++t) rowv[t] = ld4(gout + (int64_t)vv[t] * F + 4 * (li + j * L));
+#pragma unroll
+          for (int t = 0; t < U; ++t)
+#pragma unroll
+            for (int q = 0; q < KB; ++q) fma4(part[q][j], l_w[q * L + t0 + t], rowv[t]);
+        }
       }
 #pragma unroll
       for (int q = 0; q < KB; ++q)
@@ -368,7 +429,7 @@ struct GmmFwdLauncher {
                           const float* is, GmmParams pm, float* out, hipStream_t st) {
     constexpr int GPB = (kWave / L) * (kGmmBlock / kWave);
     ProfScope p("gmm_fwd_fused", st);
-    const RowSplit sp = split_rows(g, 0, L >> pm.log2Kp, GPB);
+    const RowSplit sp = split_rows(g, 0, L, GPB);
     for (int pass = 0; pass < 2; ++pass) {
       const RowRange rr = pass == 0 ? sp.hub : sp.rest;
       const unsigned grid = pass == 0 ? sp.hub_grid : sp.rest_grid;
