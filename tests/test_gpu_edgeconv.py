@@ -70,6 +70,17 @@ def test_shapes(fin, fout):
     check(synth(rng, indptr, indices, fin, fout))
 
 
+def test_graph_without_edges():
+    from gpu_harness import run_edgeconv
+    print("edgeconv: no edges", flush=True)
+    rng = np.random.default_rng(63)
+    n = 29
+    c = synth(rng, np.zeros(n + 1, dtype=np.int32), np.zeros(0, dtype=np.int32), 6, 8)
+    res = run_edgeconv(c, backward=False)
+    assert (res["argmax"] == -1).all() and (res["out"] == 0).all()
+    check(c)
+
+
 def test_duplicate_edges_empty_rows_and_hub():
     from gpu_harness import run_edgeconv
     print("edgeconv: duplicates + empty rows + hub", flush=True)

@@ -13,6 +13,33 @@ def c4():
     return make("gat_c4")
 
 
+def test_gat_c4_plan_is_the_stable_transpose(c4):
+    """At this size the oracle's sort of Python tuples is out of reach; the CSC transpose is
+    instead pinned by the properties that define it uniquely: eid_t is a permutation of the
+    CSR positions, grouped by source in ascending source order, ascending inside a source
+    (stability), and indices_t / indptr_t follow from it."""
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev
+    ip, ix = c4["indptr"], c4["indices"]
+    n, nnz = ip.shape[0] - 1, ix.shape[0]
+    print("full size: plan", flush=True)
+    g = pk.Graph(dev(ip), dev(ix))
+    indptr_t, indices_t, eid_t = (a.cpu().numpy() for a in g.csc())
+    g.close()
+    assert indptr_t[0] == 0 and indptr_t[-1] == nnz
+    assert np.array_equal(np.diff(indptr_t), np.bincount(ix, minlength=n))
+    seen = np.zeros(nnz, dtype=bool)
+    seen[eid_t] = True
+    assert seen.all()                                              # a permutation
+    src_of_slot = np.repeat(np.arange(n, dtype=np.int32), np.diff(indptr_t))
+    assert np.array_equal(ix[eid_t], src_of_slot)                  # grouped by source, sources ascending
+    inner = np.ones(nnz, dtype=bool)
+    inner[indptr_t[:-1][np.diff(indptr_t) > 0]] = False            # first slot of every non-empty row
+    assert (np.diff(eid_t.astype(np.int64))[inner[1:]] > 0).all()  # CSR order kept inside a source
+    dst_of = np.repeat(np.arange(n, dtype=np.int32), np.diff(ip))
+    assert np.array_equal(indices_t, dst_of[eid_t])
+
+
 def test_gat_c4_sampled_rows_and_consistency(c4):
     import paper_2110_09524_amd as pk
     from gpu_harness import assert_close, dev, gat_kink_masks, run_gat

@@ -119,6 +119,20 @@ def test_single_vertex_self_loop_and_skipped_input_gradient():
     compare(c, res, fwd, bwd)
 
 
+def test_graph_without_edges():
+    from gpu_harness import run_gat
+    print("gat: no edges", flush=True)
+    rng = np.random.default_rng(61)
+    n = 37
+    c = synth(rng, np.zeros(n + 1, dtype=np.int32), np.zeros(0, dtype=np.int32), 5, 2, 8)
+    fwd, bwd = oracle_all(c)
+    res = run_gat(c)
+    compare(c, res, fwd, bwd)
+    assert (res["out"] == 0).all() and (res["m"] == 0).all() and (res["d"] == 1).all()
+    for k in ("gx", "gw", "ga_l", "ga_r"):
+        assert (res[k] == 0).all(), k
+
+
 def test_results_are_bit_reproducible():
     from gpu_harness import run_gat
     print("gat: reproducibility", flush=True)

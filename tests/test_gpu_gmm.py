@@ -51,6 +51,13 @@ def test_shapes(fin, fout, K):
     check(synth(rng, indptr, indices, fin, fout, K))
 
 
+def test_graph_without_edges():
+    print("gmm: no edges", flush=True)
+    rng = np.random.default_rng(62)
+    n = 41
+    check(synth(rng, np.zeros(n + 1, dtype=np.int32), np.zeros(0, dtype=np.int32), 6, 16, 3))
+
+
 def test_empty_rows_and_hub():
     print("gmm: empty rows + hub", flush=True)
     rng = np.random.default_rng(3)
