@@ -158,6 +158,8 @@ def main():
     ap.add_argument("--workload", default="gat_c4")
     ap.add_argument("--cpu-rows", type=int, default=2048, help="destination rows of the CPU baseline sample (GAT)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="record one step into a HIP graph and time its replays (launch-bound small workloads)")
     ap.add_argument("--compare-unfused", action="store_true",
                     help="also time the one-operator-per-kernel comparator (GAT with heads*f = 256)")
     args = ap.parse_args()
@@ -250,12 +252,25 @@ def main():
     else:
         raise SystemExit(f"unknown workload kind {kind}")
 
+    run = step
+    if args.hip_graph:
+        # the entry points only enqueue kernels on the given stream, so a step can be recorded
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        hip_graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(hip_graph, stream=side):
+            step()
+        run = hip_graph.replay
     for _ in range(args.warmup):
-        step()
+        run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run()
     torch.cuda.synchronize()
     t_total = time.perf_counter() - t0
     ms_per_step = 1e3 * t_total / args.steps
@@ -308,7 +323,8 @@ def main():
     layer_floor = {"floor_ms": floor_s * 1e3, "frac": floor_s * 1e3 / ms_per_step,
                    "edge_kernels_ms_per_step": sum(kern[k]["ms_per_step"] for k in edge_kernels),
                    "edge_kernels_edges_per_s": e / (1e-3 * sum(kern[k]["ms_per_step"] for k in edge_kernels))}
-    cfg.update(workload=args.workload, vertices=n, edges=e, plan_ms_once_per_graph=1e3 * t_plan,
+    cfg.update(workload=args.workload, vertices=n, edges=e, hip_graph=bool(args.hip_graph),
+               plan_ms_once_per_graph=1e3 * t_plan,
                workspace_bytes=ws_bytes)
     result = {
         "metric": metric, "value": edges_per_s, "unit": "edges/s",

@@ -204,9 +204,9 @@ gnn_status_t sum_partials_two_level(int64_t count, int parts, const float* parti
 int gemm_pick_split_k(int64_t M, int N, int64_t K) {
   const int bn = N > 64 ? 128 : 64;
   int64_t tiles = cdiv(M, BM) * cdiv(N, bn);
-  if (tiles >= 512 || K < 4096) return 1;
+  if (tiles >= 512 || K < 256) return 1;
   int64_t want = cdiv(1536, tiles);
-  int64_t max_by_k = K / 512;  // keep at least 512 of K per split
+  int64_t max_by_k = K / 128;  // keep at least 128 of K (8 slabs) per split
   if (want > max_by_k) want = max_by_k;
   if (want > 512) want = 512;
   return want < 1 ? 1 : (int)want;
