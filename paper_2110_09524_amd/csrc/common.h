@@ -43,14 +43,19 @@ void clear_error();
   } while (0)
 
 // ---- timed launches ---------------------------------------------------------
-// prof_begin/prof_end record HIP events around a launch when profiling is on.
-void prof_begin(const char* name, hipStream_t s);
-void prof_end(hipStream_t s);
+// prof_begin/prof_end record HIP events around a launch when profiling is on.  The
+// bookkeeping is process-wide and guarded by a mutex; prof_begin returns the slot of the
+// bracket (-1 when profiling is off or no event could be created).
+int64_t prof_begin(const char* name, hipStream_t s);
+void prof_end(int64_t slot, hipStream_t s);
 
 struct ProfScope {
   hipStream_t s;
-  ProfScope(const char* name, hipStream_t st) : s(st) { prof_begin(name, st); }
-  ~ProfScope() { prof_end(s); }
+  int64_t slot;
+  ProfScope(const char* name, hipStream_t st) : s(st), slot(prof_begin(name, st)) {}
+  ~ProfScope() { prof_end(slot, s); }
+  ProfScope(const ProfScope&) = delete;
+  ProfScope& operator=(const ProfScope&) = delete;
 };
 
 // Call right after a kernel launch.

@@ -1,7 +1,9 @@
 // Error text and the per-kernel timing bracket.
 #include "common.h"
 
+#include <atomic>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -23,24 +25,27 @@ void clear_error() { g_err[0] = 0; }
 // 24576 * 128 B = 3 MB (the measured optimum at the Reddit-scale workload; fewer,
 // larger blocks save accumulator read-modify-writes, more would spill the L2).
 // 0 disables blocking.
-static int64_t g_config[kCfgCount] = {24576, 0};
-int64_t config_get(ConfigKey k) { return g_config[k]; }
+static std::atomic<int64_t> g_config[kCfgCount] = {{24576}, {0}};
+int64_t config_get(ConfigKey k) { return g_config[k].load(std::memory_order_relaxed); }
 
 // ---- profiling ---------------------------------------------------------------
 struct Pending {
   const char* name;
   hipEvent_t a, b;
+  bool closed = false;
 };
 struct Total {
   const char* name;
   double ms;
   int64_t launches;
 };
-static bool g_prof_on = false;
+static std::atomic<bool> g_prof_on{false};
+static std::mutex g_prof_mu;  // guards everything below
 static std::vector<Pending> g_pending;
 static std::vector<Total> g_totals;
 static std::vector<hipEvent_t> g_free_events;
-static Pending g_open;
+static int64_t g_generation = 0;  // bumped whenever g_pending is emptied: stale slots are ignored
+constexpr int64_t kSlotBits = 32;
 
 static hipEvent_t get_event() {
   if (!g_free_events.empty()) {
@@ -49,22 +54,34 @@ static hipEvent_t get_event() {
     return e;
   }
   hipEvent_t e = nullptr;
-  (void)hipEventCreate(&e);
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
   return e;
 }
 
-void prof_begin(const char* name, hipStream_t s) {
-  if (!g_prof_on) return;
-  g_open.name = name;
-  g_open.a = get_event();
-  g_open.b = get_event();
-  (void)hipEventRecord(g_open.a, s);
+int64_t prof_begin(const char* name, hipStream_t s) {
+  if (!g_prof_on.load(std::memory_order_relaxed)) return -1;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  Pending p{name, get_event(), get_event()};
+  if (!p.a || !p.b) {
+    if (p.a) g_free_events.push_back(p.a);
+    if (p.b) g_free_events.push_back(p.b);
+    return -1;
+  }
+  (void)hipEventRecord(p.a, s);
+  g_pending.push_back(p);
+  return (g_generation << kSlotBits) | static_cast<int64_t>(g_pending.size() - 1);
 }
 
-void prof_end(hipStream_t s) {
-  if (!g_prof_on) return;
-  (void)hipEventRecord(g_open.b, s);
-  g_pending.push_back(g_open);
+void prof_end(int64_t token, hipStream_t s) {
+  if (token < 0) return;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  // gnn_prof_collect may have run in between (it drops unfinished brackets)
+  if ((token >> kSlotBits) != g_generation) return;
+  const size_t slot = static_cast<size_t>(token & ((int64_t(1) << kSlotBits) - 1));
+  if (slot < g_pending.size() && !g_pending[slot].closed) {
+    (void)hipEventRecord(g_pending[slot].b, s);
+    g_pending[slot].closed = true;
+  }
 }
 
 }  // namespace gnn
@@ -79,11 +96,11 @@ extern "C" gnn_status_t gnn_config_set(const char* key, int64_t value) {
   if (std::strcmp(key, "block_cols") == 0) {
     GNN_REQUIRE(value >= 0 && value <= (1 << 30), GNN_ERR_INVALID_ARG,
                 "gnn_config_set: block_cols out of range");
-    g_config[kCfgBlockCols] = value;
+    g_config[kCfgBlockCols].store(value);
     return GNN_OK;
   }
   if (std::strcmp(key, "force_simple_kernels") == 0) {
-    g_config[kCfgForceSimple] = value != 0;
+    g_config[kCfgForceSimple].store(value != 0);
     return GNN_OK;
   }
   set_error("gnn_config_set: unknown key '%s'", key);
@@ -91,12 +108,17 @@ extern "C" gnn_status_t gnn_config_set(const char* key, int64_t value) {
 }
 
 extern "C" gnn_status_t gnn_prof_enable(int on) {
-  g_prof_on = on != 0;
+  g_prof_on.store(on != 0);
   return GNN_OK;
 }
 
-extern "C" gnn_status_t gnn_prof_collect(void) {
+static gnn_status_t collect_locked() {
   for (Pending& p : g_pending) {
+    if (!p.closed) {  // a bracket still open on another thread: drop it
+      g_free_events.push_back(p.a);
+      g_free_events.push_back(p.b);
+      continue;
+    }
     GNN_HIP(hipEventSynchronize(p.b));
     float ms = 0.f;
     GNN_HIP(hipEventElapsedTime(&ms, p.a, p.b));
@@ -116,18 +138,29 @@ extern "C" gnn_status_t gnn_prof_collect(void) {
     g_free_events.push_back(p.b);
   }
   g_pending.clear();
+  ++g_generation;
   return GNN_OK;
 }
 
+extern "C" gnn_status_t gnn_prof_collect(void) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  return collect_locked();
+}
+
 extern "C" gnn_status_t gnn_prof_reset(void) {
-  GNN_TRY(gnn_prof_collect());
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  GNN_TRY(collect_locked());
   g_totals.clear();
   return GNN_OK;
 }
 
-extern "C" int gnn_prof_count(void) { return static_cast<int>(g_totals.size()); }
+extern "C" int gnn_prof_count(void) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  return static_cast<int>(g_totals.size());
+}
 
 extern "C" gnn_status_t gnn_prof_get(int i, const char** name, double* total_ms, int64_t* launches) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
   GNN_REQUIRE(i >= 0 && i < static_cast<int>(g_totals.size()), GNN_ERR_INVALID_ARG,
               "gnn_prof_get: index %d out of range", i);
   if (name) *name = g_totals[i].name;
