@@ -51,10 +51,11 @@ __global__ __launch_bounds__(kEcBlock) void k_edgeconv_fwd(
   const int lane = threadIdx.x & 63;
   const int li = lane & (L - 1);
   const int grp = threadIdx.x / L;
-  const int64_t r = (int64_t)blockIdx.x * GPB + grp;
+  // order == nullptr: vertex order in XCD-contiguous ranges (near-uniform degrees)
+  const int64_t r = order ? (int64_t)blockIdx.x * GPB + grp : xcd_contiguous_row(blockIdx.x, gridDim.x, GPB, grp);
   if (r >= n_rows) return;
   int* l_idx = lds + grp * L;
-  const int32_t v = order[r];
+  const int32_t v = order ? order[r] : (int32_t)r;
   const int32_t beg = indptr[v], end = indptr[v + 1];
   const int ld = 2 * F;
 
@@ -140,11 +141,11 @@ __global__ __launch_bounds__(kEcBlock) void k_edgeconv_bwd_src(
   const int lane = threadIdx.x & 63;
   const int li = lane & (L - 1);
   const int grp = threadIdx.x / L;
-  const int64_t r = (int64_t)blockIdx.x * GPB + grp;
+  const int64_t r = order_t ? (int64_t)blockIdx.x * GPB + grp : xcd_contiguous_row(blockIdx.x, gridDim.x, GPB, grp);
   if (r >= n_rows) return;
   int* l_v = lds + grp * 2 * L;
   int* l_e = l_v + L;
-  const int32_t u = order_t[r];
+  const int32_t u = order_t ? order_t[r] : (int32_t)r;
   const int32_t beg = indptr_t[u], end = indptr_t[u + 1];
 
   bool slot_ok[NV];
@@ -159,21 +160,37 @@ __global__ __launch_bounds__(kEcBlock) void k_edgeconv_bwd_src(
     l_v[li] = i < end ? indices_t[i] : 0;
     l_e[li] = i < end ? eid_t[i] : -2;
     wave_lds_fence();
+    // slots past the end of the row hold vertex 0 and edge id -2, which no arg-max equals:
+    // the loop runs in steps of U with all 2U row loads issued before they are used
+    constexpr int U = 4;
     const int cnt = min(L, end - c0);
-    for (int t = 0; t < cnt; ++t) {
-      int v = l_v[t], e = l_e[t];
-      if (L == 64) { v = __builtin_amdgcn_readfirstlane(v); e = __builtin_amdgcn_readfirstlane(e); }
+    for (int t0 = 0; t0 < cnt; t0 += U) {
+      int vv[U], ee[U];
 #pragma unroll
-      for (int j = 0; j < NV; ++j)
-        if (slot_ok[j]) {
-          const int64_t off = (int64_t)v * F + 4 * (li + j * L);
-          const int4 a = *reinterpret_cast<const int4*>(argmax + off);
-          const float4 g = ld4(gout + off);
-          acc[j].x += a.x == e ? g.x : 0.f;
-          acc[j].y += a.y == e ? g.y : 0.f;
-          acc[j].z += a.z == e ? g.z : 0.f;
-          acc[j].w += a.w == e ? g.w : 0.f;
+      for (int t = 0; t < U; ++t) {
+        vv[t] = l_v[t0 + t];
+        ee[t] = l_e[t0 + t];
+        if (L == 64) { vv[t] = __builtin_amdgcn_readfirstlane(vv[t]); ee[t] = __builtin_amdgcn_readfirstlane(ee[t]); }
+      }
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        if (!slot_ok[j]) continue;
+        int4 a[U];
+        float4 gg[U];
+#pragma unroll
+        for (int t = 0; t < U; ++t) {
+          const int64_t off = (int64_t)vv[t] * F + 4 * (li + j * L);
+          a[t] = *reinterpret_cast<const int4*>(argmax + off);
+          gg[t] = ld4(gout + off);
         }
+#pragma unroll
+        for (int t = 0; t < U; ++t) {
+          acc[j].x += a[t].x == ee[t] ? gg[t].x : 0.f;
+          acc[j].y += a[t].y == ee[t] ? gg[t].y : 0.f;
+          acc[j].z += a[t].z == ee[t] ? gg[t].z : 0.f;
+          acc[j].w += a[t].w == ee[t] ? gg[t].w : 0.f;
+        }
+      }
     }
     wave_lds_fence();
   }
@@ -190,14 +207,24 @@ __global__ __launch_bounds__(kEcBlock) void k_edgeconv_bwd_src(
     }
 }
 
+// Degree order (heaviest rows first) balances skewed graphs; when the largest degree is within
+// a small factor of the mean it buys nothing and vertex order keeps neighbourhoods together.
+static bool near_uniform_degrees(const gnn_graph_t* g, int side) {
+  if (config_get(kCfgForceSimple)) return false;
+  const int64_t mean = g->n > 0 ? (g->nnz + g->n - 1) / g->n : 0;
+  return (int64_t)g->max_degree[side] <= 4 * (mean > 1 ? mean : 1);
+}
+
 template <int L, int NV>
 struct EcFwdLauncher {
   static gnn_status_t run(const gnn_graph_t* g, const float* pq, int F, float* out, int32_t* argmax,
                           hipStream_t st) {
     constexpr int GPB = (kWave / L) * (kEcBlock / kWave);
     ProfScope p("edgeconv_fwd_fused", st);
-    k_edgeconv_fwd<L, NV><<<(unsigned)cdiv(g->n, GPB), kEcBlock, 0, st>>>(
-        g->n, g->order[0], g->indptr, g->indices, pq, F, out, argmax);
+    const bool by_id = near_uniform_degrees(g, 0);
+    const unsigned grid = by_id ? xcd_contiguous_grid(g->n, GPB) : (unsigned)cdiv(g->n, GPB);
+    k_edgeconv_fwd<L, NV><<<grid, kEcBlock, 0, st>>>(g->n, by_id ? nullptr : g->order[0], g->indptr,
+                                                     g->indices, pq, F, out, argmax);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
   }
@@ -209,8 +236,10 @@ struct EcBwdLauncher {
                           float* dpq, hipStream_t st) {
     constexpr int GPB = (kWave / L) * (kEcBlock / kWave);
     ProfScope p("edgeconv_bwd_src", st);
-    k_edgeconv_bwd_src<L, NV><<<(unsigned)cdiv(g->n, GPB), kEcBlock, 0, st>>>(
-        g->n, g->order[1], g->indptr_t, g->indices_t, g->eid_t, argmax, gout, F, dpq);
+    const bool by_id = near_uniform_degrees(g, 1);
+    const unsigned grid = by_id ? xcd_contiguous_grid(g->n, GPB) : (unsigned)cdiv(g->n, GPB);
+    k_edgeconv_bwd_src<L, NV><<<grid, kEcBlock, 0, st>>>(g->n, by_id ? nullptr : g->order[1], g->indptr_t,
+                                                         g->indices_t, g->eid_t, argmax, gout, F, dpq);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
   }

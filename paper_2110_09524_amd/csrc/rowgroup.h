@@ -83,6 +83,20 @@ __device__ __forceinline__ void scale4(float4& a, float s) {
 // (power-law hubs), so the heaviest rows (a prefix of the degree order) are launched
 // "cooperatively": all groups of a workgroup share one row, take its chunks round-robin,
 // and fold their partial sums through LDS in group order (deterministic).
+// Row handed to a group when rows are taken in vertex order instead of degree order (graphs
+// with near-uniform degrees, e.g. kNN batches, where neighbours have nearby ids): workgroups
+// go to the 8 XCDs round-robin, so workgroup w serves XCD w % 8; giving XCD k the k-th
+// contiguous eighth of the row blocks keeps each XCD's gathers inside 1/8 of the matrix,
+// which its own L2 can hold.  The grid must be a multiple of 8 workgroups.
+__device__ __forceinline__ int64_t xcd_contiguous_row(unsigned wg, unsigned nwg, int gpb, int grp) {
+  const unsigned per_xcd = nwg / 8;
+  return ((int64_t)(wg % 8) * per_xcd + wg / 8) * gpb + grp;
+}
+inline unsigned xcd_contiguous_grid(int64_t rows, int gpb) {
+  const int64_t blocks = (rows + gpb - 1) / gpb;
+  return (unsigned)((blocks + 7) / 8 * 8);
+}
+
 struct RowRange {
   int32_t begin, end;  // positions in the degree order
   int coop;            // 1: one row per workgroup
