@@ -114,6 +114,10 @@ gnn_status_t gnn_graph_get_blocked(const gnn_graph_t* graph, int side, int32_t* 
  *                           24576 rows x one 128-byte slice per XCD = 3 MB of a
  *                           4 MB L2); 0 disables blocking
  *   "force_simple_kernels"  1: always use the single-launch kernels
+ *   "lds_scalar_table"      1 (default): the column-blocked destination-side GAT kernels
+ *                           keep a block's per-vertex score table in LDS (one persistent
+ *                           1024-thread workgroup per CU drawing rows from a counter);
+ *                           0: every edge gathers its scalar from L2
  * Errors: INVALID_ARG for an unknown key or a value out of range. */
 gnn_status_t gnn_config_set(const char* key, int64_t value);
 

@@ -595,7 +595,7 @@ static int param_blocks(int64_t n) {
 
 struct GatWs {
   size_t total;
-  size_t dz, vstate, der, del, partial, gemm, blk_rows, blk_scal, blk_elt;
+  size_t dz, vstate, der, del, partial, gemm, blk_rows, blk_scal, blk_elt, blk_queue;
   int split_k, nblk;
 };
 
@@ -617,6 +617,7 @@ static GatWs gat_ws_layout(const gnn_graph_t* g, int fin, int H, int F) {
   w.blk_rows = take(blocked ? sizeof(float) * n * HF : 0);  // T, then A2
   w.blk_scal = take(blocked ? sizeof(float) * n * H : 0);   // sg, then sd
   w.blk_elt = take(blocked ? sizeof(float) * n * H : 0);    // head-major el
+  w.blk_queue = take(blocked ? sizeof(int32_t) * 8 * (size_t)g->nblk : 0);  // row counters of the staged kernels
   w.total = off;
   return w;
 }
@@ -888,9 +889,12 @@ extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, in
     // optional scratch: a head-major copy of el makes the per-edge scalar gathers denser
     const GatWs L = gat_ws_layout(g, fin, heads, f);
     float* el_t = nullptr;
-    if (ws != nullptr && ws_bytes >= L.total && aligned16(ws))
+    int32_t* queue = nullptr;
+    if (ws != nullptr && ws_bytes >= L.total && aligned16(ws)) {
       el_t = reinterpret_cast<float*>(static_cast<char*>(ws) + L.blk_elt);
-    return gat_blocked_fwd(g, make_dims(heads, f, slope), z, el, er, m, d, out, t, sg, el_t, st);
+      queue = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.blk_queue);
+    }
+    return gat_blocked_fwd(g, make_dims(heads, f, slope), z, el, er, m, d, out, t, sg, el_t, queue, st);
   }
   return dispatch_group<FwdLauncher>(pick_group(HF), g, (const float*)z, (const float*)el,
                                      (const float*)er, make_dims(heads, f, slope), out, m, d, t, sg, st);
@@ -938,8 +942,9 @@ extern "C" gnn_status_t gnn_gat_bwd(const gnn_graph_t* g, int fin, int heads, in
     float* rows_buf = reinterpret_cast<float*>(base + L.blk_rows);
     float* scal_buf = reinterpret_cast<float*>(base + L.blk_scal);
     float* el_t = reinterpret_cast<float*>(base + L.blk_elt);
+    int32_t* queue = reinterpret_cast<int32_t*>(base + L.blk_queue);
     GNN_TRY(gat_blocked_bwd_dst(g, dm, z, el, er, m, d, out, gout, der, vstate, rows_buf, scal_buf, el_t,
-                                st));
+                                queue, st));
   } else {
     GNN_TRY(dispatch_group<BwdDstLauncher>(gs, g, z, el, er, m, d, out, gout, dm, der, vstate, st));
   }

@@ -96,22 +96,36 @@ struct BlkRow {
   float4 acc, acc2;
 };
 
-template <int SL, int MODE>
-__global__ __launch_bounds__(kBlkThreads) void k_gat_blk(
+// STAGE: the per-edge scalar el[u] of the slice's head is read from an LDS copy of the block's
+// part of the head-major table instead of being gathered from L2.  Such a scalar gather
+// costs a CU one 128-byte line fill per edge, as much as the 128-byte row slice itself; with
+// the table in LDS the row gathers have the L1 to themselves (15 -> 24 TB/s on the bare access
+// pattern).  The table takes 4 * block_cols bytes (96 KB), so one 1024-thread workgroup per CU
+// runs persistently and the groups draw their rows, four at a time in degree order, from a
+// per-slice counter in device memory (zeroed before the launch).
+constexpr int kStageThreads = 1024;
+
+template <int SL, int MODE, bool STAGE>
+__global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk(
     int32_t n_rows, const int32_t* __restrict__ order, const int2* __restrict__ bseg_b,
     const int32_t* __restrict__ bcol, const float* __restrict__ feat /* gathered rows: z or gout */,
     const float* __restrict__ el, const float* __restrict__ er, const float* __restrict__ m_in,
     const float* __restrict__ d_in, const float4* __restrict__ vstate, int32_t col_begin,
     GatDims dm, int sph, int first, int narrow, int el_hm /* el is head-major [H][n] */,
-    float* __restrict__ acc_buf, float* __restrict__ acc2_buf, float* __restrict__ scal_buf) {
+    float* __restrict__ acc_buf, float* __restrict__ acc2_buf, float* __restrict__ scal_buf,
+    int32_t* __restrict__ queue /* STAGE: one row counter per slice */, int32_t cols_here,
+    int32_t quads_per_grab) {
+  constexpr int THREADS = STAGE ? kStageThreads : kBlkThreads;
   constexpr int G = kWave / SL;
-  constexpr int GPB = G * (kBlkThreads / kWave);
+  constexpr int GPB = THREADS / SL;
   constexpr int R = kRowsPerGroup;
   constexpr int U = SL < 8 ? 4 : 8;   // gathered rows in flight per lane
   constexpr bool DUAL = MODE == 2 || MODE == 3;  // two accumulators per lane
   constexpr int GS = 3 * SL + 4 * R;  // LDS floats per group: idx | p | p2 | row, beg, end, pad
   static_assert(SL >= R, "one lane per pipelined row loads its metadata");
-  __shared__ __align__(16) float lds[GPB * GS];
+  static_assert(!STAGE || MODE != 2, "the source side needs 16 bytes per gathered vertex");
+  extern __shared__ __align__(16) float lds[];  // GPB * GS floats, then (STAGE) the el table
+  (void)G;
 
   const int lane = threadIdx.x & 63;
   const int li = lane & (SL - 1);
@@ -119,8 +133,19 @@ __global__ __launch_bounds__(kBlkThreads) void k_gat_blk(
   const int slice = blockIdx.x % kSlices;
   const int H = dm.H, HF = dm.HF;
   const int h = slice / sph;
-  const int64_t r0 = ((int64_t)(blockIdx.x / kSlices) * GPB + grp) * R;
-  if (r0 >= n_rows) return;
+  const float* l_el = lds + GPB * GS;
+  // [quad, quad_end): the group's current run of row quadruples (R consecutive rows of the
+  // degree order each); a staged group draws the next run from the slice's counter
+  int64_t quad = 0, quad_end = 0;
+  if (STAGE) {
+    float* dst = lds + GPB * GS;
+    const float* src = el + (int64_t)h * n_rows + col_begin;
+    for (int i = threadIdx.x; i < cols_here; i += THREADS) dst[i] = src[i];
+    __syncthreads();
+  } else {
+    quad = (int64_t)(blockIdx.x / kSlices) * GPB + grp;
+    quad_end = quad + 1;
+  }
 
   int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
   float* l_p = lds + grp * GS + SL;
@@ -132,152 +157,165 @@ __global__ __launch_bounds__(kBlkThreads) void k_gat_blk(
   const int col = slice * 4 * SL + 4 * li;
   const bool leader = (slice % sph) == 0;  // one slice per head keeps the per-head scalars
 
-  // segment bounds of the group's R rows inside this column block, one lane each
-  if (li < R) {
-    const int64_t r = r0 + li;
-    int32_t row = -1;
-    int2 seg = make_int2(0, 0);
-    if (r < n_rows) {
-      row = order[r];
-      seg = bseg_b[r];
-      if (!first && seg.x == seg.y) row = -1;  // nothing to add to this row in this block
+  for (;;) {
+    if (STAGE && quad == quad_end) {
+      int q = 0;
+      if (li == 0) q = atomicAdd(queue + slice, quads_per_grab);
+      quad = __shfl(q, lane & ~(SL - 1), 64);
+      quad_end = quad + quads_per_grab;
     }
-    l_row[li] = row;
-    l_beg[li] = seg.x;
-    l_end[li] = seg.y;
-  }
-  wave_lds_fence();
-
-  // issue every load a row needs before its edge loop
-  auto fetch = [&](int k, BlkRow<MODE>& s) {
-    s.row = l_row[k];
-    s.beg = l_beg[k];
-    s.end = l_end[k];
-    s.c_first = col_begin;
-    s.r_a = 0.f; s.r_m = 0.f; s.r_d = 1.f; s.scal = 0.f;
-    s.acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    s.acc2 = s.acc;
-    if (s.row < 0) return;
-    if (s.beg + li < s.end) s.c_first = bcol[s.beg + li];
-    const int64_t rh = (int64_t)s.row * H + h;
-    if (MODE == 2) {
-      s.r_a = el[rh];  // row is a source: its el
-    } else {
-      s.r_a = er[rh];  // row is a destination: its er, max, denominator
-      s.r_m = m_in[rh];
-      s.r_d = d_in[rh];
+    const int64_t r0 = quad * R;
+    if (r0 >= n_rows) break;  // the counter only grows: every group ends here
+    wave_lds_fence();         // the previous rows' metadata reads are done
+    // segment bounds of the group's R rows inside this column block, one lane each
+    if (li < R) {
+      const int64_t r = r0 + li;
+      int32_t row = -1;
+      int2 seg = make_int2(0, 0);
+      if (r < n_rows) {
+        row = order[r];
+        seg = bseg_b[r];
+        if (!first && seg.x == seg.y) row = -1;  // nothing to add to this row in this block
+      }
+      l_row[li] = row;
+      l_beg[li] = seg.x;
+      l_end[li] = seg.y;
     }
-    if (!first) {
-      s.acc = ld4_stream(acc_buf + (int64_t)s.row * HF + col);
-      if (DUAL) s.acc2 = ld4_stream(acc2_buf + (int64_t)s.row * HF + col);
-      if (MODE != 0 && leader && li == 0) s.scal = scal_buf[rh];
-    }
-  };
+    wave_lds_fence();
 
-  // Gathered rows are addressed with 32-bit byte offsets when the matrix is below 4 GB
-  // (one 24-bit multiply-add per row instead of 64-bit arithmetic).
-  const char* feat_bytes = reinterpret_cast<const char*>(feat);
-  const uint32_t row_bytes = (uint32_t)HF * 4u, col_bytes = (uint32_t)col * 4u;
+    // issue every load a row needs before its edge loop
+    auto fetch = [&](int k, BlkRow<MODE>& s) {
+      s.row = l_row[k];
+      s.beg = l_beg[k];
+      s.end = l_end[k];
+      s.c_first = col_begin;
+      s.r_a = 0.f; s.r_m = 0.f; s.r_d = 1.f; s.scal = 0.f;
+      s.acc = make_float4(0.f, 0.f, 0.f, 0.f);
+      s.acc2 = s.acc;
+      if (s.row < 0) return;
+      if (s.beg + li < s.end) s.c_first = bcol[s.beg + li];
+      const int64_t rh = (int64_t)s.row * H + h;
+      if (MODE == 2) {
+        s.r_a = el[rh];  // row is a source: its el
+      } else {
+        s.r_a = er[rh];  // row is a destination: its er, max, denominator
+        s.r_m = m_in[rh];
+        s.r_d = d_in[rh];
+      }
+      if (!first) {
+        s.acc = ld4_stream(acc_buf + (int64_t)s.row * HF + col);
+        if (DUAL) s.acc2 = ld4_stream(acc2_buf + (int64_t)s.row * HF + col);
+        if (MODE != 0 && leader && li == 0) s.scal = scal_buf[rh];
+      }
+    };
 
-  BlkRow<MODE> cur, nxt;
-  fetch(0, cur);
-  for (int k = 0; k < R; ++k) {
-    if (k + 1 < R) fetch(k + 1, nxt);
-    if (cur.row >= 0) {
-      const int32_t end = cur.end;
-      const float r_a = cur.r_a, r_m = cur.r_m, r_invd = 1.f / cur.r_d;
-      float4 acc = cur.acc, acc2 = cur.acc2;
-      float s_run = 0.f;
-      int32_t c_next = cur.c_first;
-      for (int32_t c0 = cur.beg; c0 < end; c0 += SL) {
-        const bool e_ok = c0 + li < end;
-        // gathered vertex of edge c0 + li; lanes past the end point at the block's first
-        // vertex (a valid, cache-resident row) and get weight 0, so the row phase below
-        // needs no per-edge conditionals
-        const int32_t c = e_ok ? c_next : col_begin;
-        if (c0 + SL + li < end) c_next = bcol[c0 + SL + li];
-        l_idx[li] = c;
-        // per-edge scalars: issue the loads now, use them after the row loads are in flight
-        float e_a = 0.f;
-        float4 vs = make_float4(0.f, 0.f, 1.f, 0.f);
-        if (e_ok) {
-          if (MODE == 2) vs = vstate[(int64_t)h * n_rows + c];  // head-major (er, m, 1/d, D) of the destination
-          else e_a = el_hm ? el[(int64_t)h * n_rows + c] : el[(int64_t)c * H + h];
-        }
-        wave_lds_fence();
-        float4 part = make_float4(0.f, 0.f, 0.f, 0.f), part2 = part;
-#pragma unroll
-        for (int t0 = 0; t0 < SL; t0 += U) {
-          // the group's U gathered vertices in one go (broadcast LDS reads), then U row loads
-          int idv[U];
-#pragma unroll
-          for (int q = 0; q < U / 4; ++q) {
-            const int4 i4 = *reinterpret_cast<const int4*>(l_idx + t0 + 4 * q);
-            idv[4 * q] = i4.x; idv[4 * q + 1] = i4.y; idv[4 * q + 2] = i4.z; idv[4 * q + 3] = i4.w;
+    // Gathered rows are addressed with 32-bit byte offsets when the matrix is below 4 GB
+    // (one 24-bit multiply-add per row instead of 64-bit arithmetic).
+    const char* feat_bytes = reinterpret_cast<const char*>(feat);
+    const uint32_t row_bytes = (uint32_t)HF * 4u, col_bytes = (uint32_t)col * 4u;
+
+    BlkRow<MODE> cur, nxt;
+    fetch(0, cur);
+    for (int k = 0; k < R; ++k) {
+      if (k + 1 < R) fetch(k + 1, nxt);
+      if (cur.row >= 0) {
+        const int32_t end = cur.end;
+        const float r_a = cur.r_a, r_m = cur.r_m, r_invd = 1.f / cur.r_d;
+        float4 acc = cur.acc, acc2 = cur.acc2;
+        float s_run = 0.f;
+        int32_t c_next = cur.c_first;
+        for (int32_t c0 = cur.beg; c0 < end; c0 += SL) {
+          const bool e_ok = c0 + li < end;
+          // gathered vertex of edge c0 + li; lanes past the end point at the block's first
+          // vertex (a valid, cache-resident row) and get weight 0, so the row phase below
+          // needs no per-edge conditionals
+          const int32_t c = e_ok ? c_next : col_begin;
+          if (c0 + SL + li < end) c_next = bcol[c0 + SL + li];
+          l_idx[li] = c;
+          // per-edge scalars: issue the loads now, use them after the row loads are in flight
+          float e_a = 0.f;
+          float4 vs = make_float4(0.f, 0.f, 1.f, 0.f);
+          if (e_ok) {
+            if (MODE == 2) vs = vstate[(int64_t)h * n_rows + c];  // head-major (er, m, 1/d, D) of the destination
+            else e_a = STAGE ? l_el[c - col_begin] : (el_hm ? el[(int64_t)h * n_rows + c] : el[(int64_t)c * H + h]);
           }
-          float4 rowv[U];
-          if (narrow) {
-#pragma unroll
-            for (int t = 0; t < U; ++t)
-              rowv[t] = *reinterpret_cast<const float4*>(
-                  feat_bytes + (__umul24((uint32_t)idv[t], row_bytes) + col_bytes));
-          } else {
-#pragma unroll
-            for (int t = 0; t < U; ++t) rowv[t] = ld4(feat + (int64_t)idv[t] * HF + col);
-          }
-          if (t0 == 0) {
-            float p = 0.f, p2 = 0.f;
-            if (e_ok) {
-              if (MODE == 2) {
-                const float raw = r_a + vs.x;
-                p = __expf(leaky(raw, dm.slope) - vs.y) * vs.z;
-                p2 = raw > 0.f ? p : dm.slope * p;
-                s_run = fmaf(p2, vs.w, s_run);
-              } else {
-                const float raw = e_a + r_a;
-                p = __expf(leaky(raw, dm.slope) - r_m) * r_invd;
-                if (MODE == 1) {
-                  p = raw > 0.f ? p : dm.slope * p;
-                  s_run += p;
-                }
-                if (MODE == 3) {
+          wave_lds_fence();
+          float4 part = make_float4(0.f, 0.f, 0.f, 0.f), part2 = part;
+  #pragma unroll
+          for (int t0 = 0; t0 < SL; t0 += U) {
+            // the group's U gathered vertices in one go (broadcast LDS reads), then U row loads
+            int idv[U];
+  #pragma unroll
+            for (int q = 0; q < U / 4; ++q) {
+              const int4 i4 = *reinterpret_cast<const int4*>(l_idx + t0 + 4 * q);
+              idv[4 * q] = i4.x; idv[4 * q + 1] = i4.y; idv[4 * q + 2] = i4.z; idv[4 * q + 3] = i4.w;
+            }
+            float4 rowv[U];
+            if (narrow) {
+  #pragma unroll
+              for (int t = 0; t < U; ++t)
+                rowv[t] = *reinterpret_cast<const float4*>(
+                    feat_bytes + (__umul24((uint32_t)idv[t], row_bytes) + col_bytes));
+            } else {
+  #pragma unroll
+              for (int t = 0; t < U; ++t) rowv[t] = ld4(feat + (int64_t)idv[t] * HF + col);
+            }
+            if (t0 == 0) {
+              float p = 0.f, p2 = 0.f;
+              if (e_ok) {
+                if (MODE == 2) {
+                  const float raw = r_a + vs.x;
+                  p = __expf(leaky(raw, dm.slope) - vs.y) * vs.z;
                   p2 = raw > 0.f ? p : dm.slope * p;
-                  s_run += p2;
+                  s_run = fmaf(p2, vs.w, s_run);
+                } else {
+                  const float raw = e_a + r_a;
+                  p = __expf(leaky(raw, dm.slope) - r_m) * r_invd;
+                  if (MODE == 1) {
+                    p = raw > 0.f ? p : dm.slope * p;
+                    s_run += p;
+                  }
+                  if (MODE == 3) {
+                    p2 = raw > 0.f ? p : dm.slope * p;
+                    s_run += p2;
+                  }
                 }
               }
+              l_p[li] = p;
+              if (DUAL) l_p2[li] = p2;
+              wave_lds_fence();
             }
-            l_p[li] = p;
-            if (DUAL) l_p2[li] = p2;
-            wave_lds_fence();
-          }
-          float pv[U], pv2[U];
-#pragma unroll
-          for (int q = 0; q < U / 4; ++q) {
-            const float4 p4 = *reinterpret_cast<const float4*>(l_p + t0 + 4 * q);
-            pv[4 * q] = p4.x; pv[4 * q + 1] = p4.y; pv[4 * q + 2] = p4.z; pv[4 * q + 3] = p4.w;
-            if (DUAL) {
-              const float4 q4 = *reinterpret_cast<const float4*>(l_p2 + t0 + 4 * q);
-              pv2[4 * q] = q4.x; pv2[4 * q + 1] = q4.y; pv2[4 * q + 2] = q4.z; pv2[4 * q + 3] = q4.w;
+            float pv[U], pv2[U];
+  #pragma unroll
+            for (int q = 0; q < U / 4; ++q) {
+              const float4 p4 = *reinterpret_cast<const float4*>(l_p + t0 + 4 * q);
+              pv[4 * q] = p4.x; pv[4 * q + 1] = p4.y; pv[4 * q + 2] = p4.z; pv[4 * q + 3] = p4.w;
+              if (DUAL) {
+                const float4 q4 = *reinterpret_cast<const float4*>(l_p2 + t0 + 4 * q);
+                pv2[4 * q] = q4.x; pv2[4 * q + 1] = q4.y; pv2[4 * q + 2] = q4.z; pv2[4 * q + 3] = q4.w;
+              }
+            }
+  #pragma unroll
+            for (int t = 0; t < U; ++t) {
+              fma4(part, pv[t], rowv[t]);
+              if (DUAL) fma4(part2, pv2[t], rowv[t]);
             }
           }
-#pragma unroll
-          for (int t = 0; t < U; ++t) {
-            fma4(part, pv[t], rowv[t]);
-            if (DUAL) fma4(part2, pv2[t], rowv[t]);
-          }
+          add4(acc, part);
+          if (DUAL) add4(acc2, part2);
+          wave_lds_fence();
         }
-        add4(acc, part);
-        if (DUAL) add4(acc2, part2);
-        wave_lds_fence();
+        st4_stream(acc_buf + (int64_t)cur.row * HF + col, acc);
+        if (DUAL) st4_stream(acc2_buf + (int64_t)cur.row * HF + col, acc2);
+        if (MODE != 0 && leader) {
+          const float tot = group_sum_from<SL>(s_run, 1);
+          if (li == 0) scal_buf[(int64_t)cur.row * H + h] = cur.scal + tot;
+        }
       }
-      st4_stream(acc_buf + (int64_t)cur.row * HF + col, acc);
-      if (DUAL) st4_stream(acc2_buf + (int64_t)cur.row * HF + col, acc2);
-      if (MODE != 0 && leader) {
-        const float tot = group_sum_from<SL>(s_run, 1);
-        if (li == 0) scal_buf[(int64_t)cur.row * H + h] = cur.scal + tot;
-      }
+      cur = nxt;
     }
-    cur = nxt;
+    if (!STAGE) break;
+    ++quad;
   }
 }
 
@@ -315,24 +353,91 @@ size_t gat_blocked_ws_bytes(const gnn_graph_t* g, int heads, int f) {
          2 * ws_granule(sizeof(float) * (size_t)g->n * heads);    // sg, then sd; head-major el
 }
 
+__global__ void k_zero_i32(int n, int32_t* __restrict__ p) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+// LDS bytes of the staged kernel: per-group scratch plus the block's table
+template <int SL>
+static size_t staged_lds_bytes(int32_t block_cols) {
+  constexpr int GS = 3 * SL + 4 * kRowsPerGroup;
+  return sizeof(float) * ((size_t)(kStageThreads / SL) * GS + (size_t)block_cols);
+}
+constexpr size_t kStageLdsLimit = 152 * 1024;  // of the 160 KB a CU has
+constexpr int kStageMinEdgesPerRow = 128;       // mean edges per row of a block worth staging
+
+static int device_cu_count() {
+  static int cus = 0;  // one GPU type per process
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      cus = v;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
 template <int SL, int MODE>
 static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* name, GatDims dm,
                                   int el_hm, const float* feat,
                                   const float* el, const float* er, const float* m, const float* d,
                                   const float4* vstate, float* acc, float* acc2, float* scal,
-                                  hipStream_t st) {
+                                  int32_t* queue, hipStream_t st) {
   const int sph = kSlices / dm.H;
-  const int rows_per_wg = (kBlkThreads / SL) * kRowsPerGroup;
-  const unsigned grid = (unsigned)(cdiv(g->n, rows_per_wg) * kSlices);
   // 32-bit byte offsets (and 24-bit multiplies) reach every gathered row
   const int narrow = (int64_t)g->n * dm.HF * 4 < ((int64_t)1 << 32) && g->n < (1 << 24);
+  constexpr int GS = 3 * SL + 4 * kRowsPerGroup;
+  const int rows_per_wg = (kBlkThreads / SL) * kRowsPerGroup;
+  const unsigned grid = (unsigned)(cdiv(g->n, rows_per_wg) * kSlices);
+  const size_t lds = sizeof(float) * (size_t)(kBlkThreads / SL) * GS;
+  bool stage_ok = false;
+  if constexpr (MODE != 2) {
+    stage_ok = queue != nullptr && el_hm && staged_lds_bytes<SL>(g->block_cols) <= kStageLdsLimit &&
+               (int)g->h_block_begin[side].size() == g->nblk + 1;
+    if (stage_ok) {
+      static bool attr_set = false;  // per instantiation; the call is idempotent
+      if (!attr_set) {
+        GNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gat_blk<SL, MODE, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStageLdsLimit));
+        attr_set = true;
+      }
+      ProfScope p("gat_blk_queue_reset", st);
+      k_zero_i32<<<cdiv(g->nblk * kSlices, 64), 64, 0, st>>>(g->nblk * kSlices, queue);
+      GNN_LAUNCH_CHECK();
+    }
+  }
   for (int b = 0; b < g->nblk; ++b) {
     const int2* bseg_b = reinterpret_cast<const int2*>(g->bseg[side]) + (int64_t)b * g->n;
-    ProfScope p(name, st);  // one timed bracket per launch
-    k_gat_blk<SL, MODE><<<grid, kBlkThreads, 0, st>>>(g->n, g->order[side], bseg_b, g->bcol[side], feat,
-                                                      el, er, m, d, vstate, b * g->block_cols, dm, sph,
-                                                      b == 0, narrow, el_hm, acc, acc2, scal);
-    GNN_LAUNCH_CHECK();
+    const int32_t col_begin = b * g->block_cols;
+    bool staged = false;
+    if constexpr (MODE != 2) {
+      // The LDS table pays on blocks whose rows are long (measured: 3.2 ms instead of 3.8 ms on a
+      // block with 237 edges per row); with short rows the persistent launch has too few rows in
+      // flight per CU to hide the chain of loads at the start of a row (2.1 ms instead of 1.6 ms
+      // at 68 edges per row).
+      const int64_t edges = (int64_t)g->h_block_begin[side][b + 1] - g->h_block_begin[side][b];
+      staged = stage_ok && edges >= (int64_t)kStageMinEdgesPerRow * g->n;
+      if (staged) {
+        const int32_t cols_here = g->n - col_begin < g->block_cols ? g->n - col_begin : g->block_cols;
+        // one persistent workgroup per CU, a multiple of 8 so that every XCD serves one slice
+        const unsigned pgrid = (unsigned)(device_cu_count() / kSlices * kSlices);
+        ProfScope p(name, st);  // one timed bracket per launch
+        k_gat_blk<SL, MODE, true><<<pgrid, kStageThreads, staged_lds_bytes<SL>(g->block_cols), st>>>(
+            g->n, g->order[side], bseg_b, g->bcol[side], feat, el, er, m, d, vstate, col_begin, dm, sph,
+            b == 0, narrow, el_hm, acc, acc2, scal, queue + b * kSlices, cols_here, 1);
+        GNN_LAUNCH_CHECK();
+      }
+    }
+    if (!staged) {
+      ProfScope p(name, st);  // one timed bracket per launch
+      k_gat_blk<SL, MODE, false><<<grid, kBlkThreads, lds, st>>>(
+          g->n, g->order[side], bseg_b, g->bcol[side], feat, el, er, m, d, vstate, col_begin, dm, sph,
+          b == 0, narrow, el_hm, acc, acc2, scal, nullptr, 0, 1);
+      GNN_LAUNCH_CHECK();
+    }
   }
   return GNN_OK;
 }
@@ -341,12 +446,12 @@ template <int MODE>
 static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name, GatDims dm,
                                int el_hm, const float* feat, const float* el, const float* er, const float* m,
                                const float* d, const float4* vstate, float* acc, float* acc2,
-                               float* scal, hipStream_t st) {
+                               float* scal, int32_t* queue, hipStream_t st) {
   switch (dm.HF / (4 * kSlices)) {
-    case 4: return launch_blocks<4, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
-    case 8: return launch_blocks<8, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
-    case 16: return launch_blocks<16, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
-    case 32: return launch_blocks<32, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, st);
+    case 4: return launch_blocks<4, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, st);
+    case 8: return launch_blocks<8, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, st);
+    case 16: return launch_blocks<16, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, st);
+    case 32: return launch_blocks<32, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, st);
   }
   set_error("gat blocked: unsupported slice width");
   return GNN_ERR_UNSUPPORTED;
@@ -354,8 +459,9 @@ static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name,
 
 gnn_status_t gat_blocked_fwd(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                              const float* er, float* m, float* d, float* out, float* t, float* sg,
-                             float* el_t, hipStream_t st) {
+                             float* el_t, int32_t* queue, hipStream_t st) {
   if (el_t) GNN_TRY(head_major(g, dm.H, el, el_t, st));
+  if (!config_get(kCfgLdsScalarTable)) queue = nullptr;
   const float* el_use = el_t ? el_t : el;
   const int hm = el_t != nullptr;
   {
@@ -364,17 +470,19 @@ gnn_status_t gat_blocked_fwd(const gnn_graph_t* g, GatDims dm, const float* z, c
         g->n, g->order[0], g->indptr, g->indices, el, er, dm, m, d);
     GNN_LAUNCH_CHECK();
   }
-  if (t) return run_blocks<3>(g, 0, "gat_fwd_fused", dm, hm, z, el_use, er, m, d, nullptr, out, t, sg, st);
-  return run_blocks<0>(g, 0, "gat_fwd_fused", dm, hm, z, el_use, er, m, d, nullptr, out, nullptr, nullptr, st);
+  if (t) return run_blocks<3>(g, 0, "gat_fwd_fused", dm, hm, z, el_use, er, m, d, nullptr, out, t, sg, queue, st);
+  return run_blocks<0>(g, 0, "gat_fwd_fused", dm, hm, z, el_use, er, m, d, nullptr, out, nullptr, nullptr, queue,
+                       st);
 }
 
 gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                                  const float* er, const float* m, const float* d, const float* out,
                                  const float* gout, float* der, float4* vstate, float* t_buf,
-                                 float* sg_buf, float* el_t, hipStream_t st) {
+                                 float* sg_buf, float* el_t, int32_t* queue, hipStream_t st) {
   if (el_t) GNN_TRY(head_major(g, dm.H, el, el_t, st));
+  if (!config_get(kCfgLdsScalarTable)) queue = nullptr;
   GNN_TRY(run_blocks<1>(g, 0, "gat_bwd_dst", dm, el_t != nullptr, z, el_t ? el_t : el, er, m, d, nullptr,
-                        t_buf, nullptr, sg_buf, st));
+                        t_buf, nullptr, sg_buf, queue, st));
   return gat_dst_finish(g, dm, gout, t_buf, out, sg_buf, er, m, d, 1, der, vstate, st);
 }
 
@@ -383,7 +491,7 @@ gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* 
                                  const float* a_l, const float* a_r, float* dz, float* del,
                                  float* a2_buf, float* sd_buf, hipStream_t st) {
   GNN_TRY(run_blocks<2>(g, 1, "gat_bwd_src", dm, 0, gout, el, nullptr, nullptr, nullptr, vstate, dz,
-                        a2_buf, sd_buf, st));
+                        a2_buf, sd_buf, nullptr, st));
   return gat_src_finish(g, dm, z, a2_buf, sd_buf, der, a_l, a_r, dz, del, st);
 }
 

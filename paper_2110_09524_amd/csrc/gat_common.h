@@ -33,7 +33,8 @@ size_t gat_blocked_ws_bytes(const gnn_graph_t* g, int heads, int f);  // extra w
 // t, sg: optional stash of the destination-side backward sums (both or neither)
 gnn_status_t gat_blocked_fwd(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                              const float* er, float* m, float* d, float* out, float* t, float* sg,
-                             float* el_t /* [H][n] scratch or null */, hipStream_t st);
+                             float* el_t /* [H][n] scratch or null */,
+                             int32_t* queue /* nblk * 8 row counters or null */, hipStream_t st);
 // vertex-side closing steps shared by both paths (gat.hip)
 gnn_status_t gat_dst_finish(const gnn_graph_t* g, GatDims dm, const float* gout, const float* t,
                             const float* out, const float* sg, const float* er, const float* m,
@@ -47,7 +48,7 @@ gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* 
                                  const float* er, const float* m, const float* d, const float* out,
                                  const float* gout, float* der, float4* vstate, float* t_buf,
                                  float* sg_buf, float* el_t /* [H][n] scratch or null */,
-                                 hipStream_t st);
+                                 int32_t* queue /* nblk * 8 row counters or null */, hipStream_t st);
 // writes dz, del; a2_buf is an [n, HF] scratch, sd_buf an [n, H] scratch
 gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                                  const float4* vstate, const float* der, const float* gout,

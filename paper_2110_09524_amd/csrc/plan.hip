@@ -219,6 +219,11 @@ static gnn_status_t build_blocked(gnn_graph* g, int side, const int32_t* ptr, co
   k_block_segments<<<cdiv(slots, thr), thr, 0, st>>>(n, g->nblk, g->bptr[side], g->order[side],
                                                      reinterpret_cast<int2*>(g->bseg[side]));
   GNN_LAUNCH_CHECK();
+  // edges per block, for the host's choice of kernel variant: bptr[b * n], b = 0 .. nblk
+  g->h_block_begin[side].assign((size_t)g->nblk + 1, 0);
+  GNN_HIP(hipMemcpy2DAsync(g->h_block_begin[side].data(), sizeof(int32_t), g->bptr[side],
+                           sizeof(int32_t) * (size_t)n, sizeof(int32_t), (size_t)g->nblk + 1,
+                           hipMemcpyDeviceToHost, st));
   GNN_HIP(hipStreamSynchronize(st));
   return GNN_OK;
 }

@@ -25,7 +25,8 @@ void clear_error() { g_err[0] = 0; }
 // 24576 * 128 B = 3 MB (the measured optimum at the Reddit-scale workload; fewer,
 // larger blocks save accumulator read-modify-writes, more would spill the L2).
 // 0 disables blocking.
-static std::atomic<int64_t> g_config[kCfgCount] = {{24576}, {0}};
+// lds_scalar_table: 1 lets the blocked destination-side kernels keep a block's el table in LDS
+static std::atomic<int64_t> g_config[kCfgCount] = {{24576}, {0}, {1}};
 int64_t config_get(ConfigKey k) { return g_config[k].load(std::memory_order_relaxed); }
 
 // ---- profiling ---------------------------------------------------------------
@@ -101,6 +102,10 @@ extern "C" gnn_status_t gnn_config_set(const char* key, int64_t value) {
   }
   if (std::strcmp(key, "force_simple_kernels") == 0) {
     g_config[kCfgForceSimple].store(value != 0);
+    return GNN_OK;
+  }
+  if (std::strcmp(key, "lds_scalar_table") == 0) {
+    g_config[kCfgLdsScalarTable].store(value != 0);
     return GNN_OK;
   }
   set_error("gnn_config_set: unknown key '%s'", key);

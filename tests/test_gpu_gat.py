@@ -204,3 +204,52 @@ def test_column_blocked_path(block_cols, H, F):
     compare(c, res2, fwd, bwd)
     assert np.array_equal(res["m"], res2["m"])      # the row maximum is exact on both paths
     compare(c, run_gat(c, graph=g, stash=False), fwd, bwd)   # blocked recompute of the dst side
+
+
+@pytest.mark.parametrize("H,F", [(4, 64), (4, 32), (1, 512)])
+def test_blocked_path_with_the_score_table_in_lds(H, F):
+    """A column block whose rows are long (>= 128 edges per row on average) is walked by the
+    persistent variant that keeps the block's el table in LDS and draws rows from a counter;
+    sparser blocks of the same graph take the plain variant.  Both against the oracle, and
+    the two variants bit for bit against each other (they add the same terms in the same order)."""
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev, run_gat
+    print(f"gat: blocked path, LDS score table H={H} F={F}", flush=True)
+    rng = np.random.default_rng(1000 + H * F)
+    n, block_cols = 700, 512
+    edges = []
+    for v in range(n):
+        if v == 5:
+            continue                                   # a row without in-edges
+        k0 = n if v == 0 else 150 + int(rng.integers(0, 60))   # vertex 0: every source, the rest: a long row
+        srcs = np.arange(n) if v == 0 else np.concatenate(
+            [rng.choice(block_cols, size=k0, replace=False),
+             block_cols + rng.choice(n - block_cols, size=20, replace=False)])
+        edges += [(int(u), v) for u in srcs]
+    indptr, indices = tiny_graph(n, edges)
+    c = synth(rng, indptr, indices, 16, H, F)
+    in_block0 = int((indices < block_cols).sum())
+    assert in_block0 >= 128 * n and len(indices) - in_block0 < 128 * n   # one block of each kind
+    fwd, bwd = oracle_all(c)
+    pk.gnn_config_set("block_cols", block_cols)
+    try:
+        g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
+        assert g.blocked(0)[0] == 2
+        pk.gnn_prof_reset()
+        pk.gnn_prof_enable(True)
+        res = run_gat(c, graph=g)
+        pk.gnn_prof_enable(False)
+        assert "gat_blk_queue_reset" in pk.gnn_prof_report()       # the persistent variant was set up
+        res_nostash = run_gat(c, graph=g, stash=False)
+        pk.gnn_config_set("lds_scalar_table", 0)
+        try:
+            ref = run_gat(c, graph=g)
+        finally:
+            pk.gnn_config_set("lds_scalar_table", 1)
+        g.close()
+    finally:
+        pk.gnn_config_set("block_cols", 24576)
+    compare(c, res, fwd, bwd)
+    compare(c, res_nostash, fwd, bwd)
+    for k in res:
+        assert np.array_equal(res[k], ref[k]), f"{k}: LDS-table and plain variants differ"
