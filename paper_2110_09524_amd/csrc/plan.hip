@@ -94,6 +94,13 @@ __global__ void k_block_segments(int32_t n, int32_t nblk, const int32_t* __restr
   bseg[i] = make_int2(bptr[j], bptr[j + 1]);
 }
 
+// dst[i] = src[i * stride]
+__global__ void k_gather_strided(int count, const int32_t* __restrict__ src, int64_t stride,
+                                 int32_t* __restrict__ dst) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) dst[i] = src[(int64_t)i * stride];
+}
+
 static void free_all(gnn_graph* g) {
   if (!g) return;
   (void)hipFree(g->indptr_t);
@@ -119,6 +126,8 @@ struct TempBuffers {
   template <typename T>
   hipError_t alloc(T** out, size_t elems) {
     void* q = nullptr;
+    *out = nullptr;
+    if (count == 8) return hipErrorOutOfMemory;  // more temporaries than slots: a bug, not a device state
     hipError_t e = hipMalloc(&q, elems ? elems * sizeof(T) : sizeof(T));
     if (e == hipSuccess) p[count++] = q;
     *out = static_cast<T*>(q);
@@ -221,9 +230,12 @@ static gnn_status_t build_blocked(gnn_graph* g, int side, const int32_t* ptr, co
   GNN_LAUNCH_CHECK();
   // edges per block, for the host's choice of kernel variant: bptr[b * n], b = 0 .. nblk
   g->h_block_begin[side].assign((size_t)g->nblk + 1, 0);
-  GNN_HIP(hipMemcpy2DAsync(g->h_block_begin[side].data(), sizeof(int32_t), g->bptr[side],
-                           sizeof(int32_t) * (size_t)n, sizeof(int32_t), (size_t)g->nblk + 1,
-                           hipMemcpyDeviceToHost, st));
+  int32_t* starts = nullptr;
+  GNN_HIP(tmp.alloc(&starts, (size_t)g->nblk + 1));
+  k_gather_strided<<<cdiv((int64_t)g->nblk + 1, thr), thr, 0, st>>>(g->nblk + 1, g->bptr[side], n, starts);
+  GNN_LAUNCH_CHECK();
+  GNN_HIP(hipMemcpyAsync(g->h_block_begin[side].data(), starts, sizeof(int32_t) * ((size_t)g->nblk + 1),
+                         hipMemcpyDeviceToHost, st));
   GNN_HIP(hipStreamSynchronize(st));
   return GNN_OK;
 }
