@@ -52,28 +52,49 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_f32(
 
   float ra[A_PER_T], rb[B_PER_T];
 
+  // Element i of this thread sits at a fixed (row, k) of the slab.  Its address is a uniform
+  // base pointer, advanced once per slab, plus a 32-bit offset computed once; rows past M and
+  // columns past N are clamped to the last valid one (their products land in rows / columns
+  // of C that are never stored), so only the last, partial K-slab needs predicated loads.
+  uint32_t offa[A_PER_T], offb[B_PER_T];
+  int ka[A_PER_T], kb[B_PER_T];
+#pragma unroll
+  for (int i = 0; i < A_PER_T; ++i) {
+    const int idx = tid + GEMM_THREADS * i;
+    int kk, mm;
+    if (A_KMAJOR) { mm = idx % BM; kk = idx / BM; } else { kk = idx % BK; mm = idx / BK; }
+    const int64_t mrow = (m0 + mm < M ? m0 + mm : M - 1) - m0;
+    offa[i] = (uint32_t)(A_KMAJOR ? kk * lda + mrow : mrow * lda + kk);
+    ka[i] = kk;
+  }
+#pragma unroll
+  for (int i = 0; i < B_PER_T; ++i) {
+    const int idx = tid + GEMM_THREADS * i;
+    int kk, nn;
+    if (B_KCONTIG) { kk = idx % BK; nn = idx / BK; } else { nn = idx % BN; kk = idx / BN; }
+    const int64_t ncol = (n0 + nn < N ? n0 + nn : N - 1) - n0;
+    offb[i] = (uint32_t)(B_KCONTIG ? ncol * ldb + kk : kk * ldb + ncol);
+    kb[i] = kk;
+  }
+  const float* abase = A + (A_KMAJOR ? k_begin * lda + m0 : m0 * lda + k_begin);
+  const float* bbase = B + (B_KCONTIG ? (int64_t)n0 * ldb + k_begin : k_begin * ldb + n0);
+  const int64_t astep = A_KMAJOR ? BK * lda : BK, bstep = B_KCONTIG ? BK : BK * ldb;
+
   auto load_slab = [&](int64_t k0) {
+    const int64_t rem = k_end - k0;
+    if (rem >= BK) {
 #pragma unroll
-    for (int i = 0; i < A_PER_T; ++i) {
-      int idx = tid + GEMM_THREADS * i;
-      int kk, mm;
-      if (A_KMAJOR) { mm = idx % BM; kk = idx / BM; } else { kk = idx % BK; mm = idx / BK; }
-      int64_t m = m0 + mm, k = k0 + kk;
-      float v = 0.f;
-      if (m < M && k < k_end) v = A_KMAJOR ? A[k * lda + m] : A[m * lda + k];
-      ra[i] = v;
-    }
+      for (int i = 0; i < A_PER_T; ++i) ra[i] = abase[offa[i]];
 #pragma unroll
-    for (int i = 0; i < B_PER_T; ++i) {
-      int idx = tid + GEMM_THREADS * i;
-      int kk, nn;
-      if (B_KCONTIG) { kk = idx % BK; nn = idx / BK; } else { nn = idx % BN; kk = idx / BN; }
-      int n = n0 + nn;
-      int64_t k = k0 + kk;
-      float v = 0.f;
-      if (n < N && k < k_end) v = B_KCONTIG ? B[(int64_t)n * ldb + k] : B[k * ldb + n];
-      rb[i] = v;
+      for (int i = 0; i < B_PER_T; ++i) rb[i] = bbase[offb[i]];
+    } else {
+#pragma unroll
+      for (int i = 0; i < A_PER_T; ++i) ra[i] = ka[i] < rem ? abase[offa[i]] : 0.f;
+#pragma unroll
+      for (int i = 0; i < B_PER_T; ++i) rb[i] = kb[i] < rem ? bbase[offb[i]] : 0.f;
     }
+    abase += astep;
+    bbase += bstep;
   };
   auto store_slab = [&]() {
 #pragma unroll
@@ -246,6 +267,8 @@ gnn_status_t gemm_f32(int64_t M, int N, int64_t K, const float* a, int64_t lda, 
                       int split_k, float* partials, hipStream_t s) {
   if (M <= 0 || N <= 0) return GNN_OK;
   GNN_REQUIRE(K > 0, GNN_ERR_INVALID_ARG, "gemm_f32: K must be positive");
+  GNN_REQUIRE(lda > 0 && ldb > 0 && lda < (1 << 24) && ldb < (1 << 24), GNN_ERR_UNSUPPORTED,
+              "gemm_f32: leading dimensions must be below 2^24 (32-bit tile offsets)");
   GNN_REQUIRE(cdiv(M, BM) < (int64_t)INT32_MAX && split_k >= 1 && split_k <= 65535,
               GNN_ERR_UNSUPPORTED, "gemm_f32: grid too large");
   GNN_REQUIRE(split_k == 1 || partials != nullptr, GNN_ERR_INVALID_ARG,
