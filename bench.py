@@ -161,7 +161,8 @@ def main():
     ap.add_argument("--hip-graph", action="store_true",
                     help="record one step into a HIP graph and time its replays (launch-bound small workloads)")
     ap.add_argument("--compare-unfused", action="store_true",
-                    help="also time the one-operator-per-kernel comparator (GAT with heads*f = 256)")
+                    help="also time the one-operator-per-kernel comparator (GAT with heads*f = 256: forward and "
+                         "backward graph operators; EdgeConv and GMM: forward)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -338,6 +339,18 @@ def main():
         result["unfused_comparison"] = compare_gat(
             c, g, indptr, indices, z, el, er, gout, a_l, a_r, out, dz_fused,
             {k: v["ms_per_step"] for k, v in kern.items()})
+    if args.compare_unfused and kind == "edgeconv":
+        from unfused_baseline.compare import compare_edgeconv
+        result["unfused_comparison"] = compare_edgeconv(
+            c, indptr, indices, x, theta, phi,
+            lambda: pk.gnn_edgeconv_fwd(g, fin, F, x, theta, phi, pq, out, argmax, ws), out)
+    if args.compare_unfused and kind == "gmm":
+        from unfused_baseline.compare import compare_gmm
+        cmp = compare_gmm(c, indptr, indices, cc, mu, inv_sigma, hk,
+                          lambda: pk.gnn_gmm_fwd(g, fin, F, K, x, w_fc, cc, mu, inv_sigma, hk, out), out)
+        cmp["fused_graph_fwd_ms"] = kern["gmm_fwd_fused"]["ms_per_step"]
+        cmp["time_ratio_unfused_over_fused"] = cmp["unfused_graph_fwd_ms"] / cmp["fused_graph_fwd_ms"]
+        result["unfused_comparison"] = cmp
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample ...", file=sys.stderr, flush=True)
         result["cpu_baseline"] = cpu_baseline_gat(c, args.cpu_rows) if kind == "gat" else cpu_baseline_full(c)

@@ -33,3 +33,39 @@ def test_comparator_matches_the_oracle():
     assert_close("out", u.out.view(n, -1).cpu().numpy(), fwd["out"])
     assert_close("alpha", u.M2.view(-1, H).cpu().numpy(), fwd["M2"])
     assert_close("dz", u.dz.view(n, -1).cpu().numpy(), bwd["dHt"], row_scale=True)
+
+
+def test_edgeconv_comparator_matches_the_oracle():
+    import torch
+    from gpu_harness import assert_close, dev
+    from oracle import edgeconv as oe
+    from unfused_baseline.compare import UnfusedEdgeConv
+    from workloads import make
+    print("unfused comparator: ec_c3_mid", flush=True)
+    c = make("ec_c3_mid")
+    fwd = oe.edgeconv_forward(c["indptr"], c["indices"], c["x"], c["theta"], c["phi"])
+    u = UnfusedEdgeConv(c, dev(c["indptr"]), dev(c["indices"]))
+    u.fwd(dev(c["x"]), dev(c["theta"]), dev(c["phi"]))
+    torch.cuda.synchronize()
+    assert_close("out", u.out.cpu().numpy(), fwd["out"])
+    # the winner the comparator stored reaches the maximum (near-ties may pick another edge)
+    am = u.argmax.cpu().numpy().astype(np.int64)
+    E2 = u.E2.cpu().numpy()
+    cols = np.broadcast_to(np.arange(c["fout"]), am.shape)
+    assert_close("value at argmax", E2[am, cols], fwd["out"])
+
+
+def test_gmm_comparator_matches_the_oracle():
+    import torch
+    from gpu_harness import assert_close, dev
+    from oracle import gmm as om
+    from unfused_baseline.compare import UnfusedGmm
+    from workloads import make
+    print("unfused comparator: gmm_c5_mid", flush=True)
+    c = make("gmm_c5_mid")
+    fwd = om.gmm_forward(c["indptr"], c["indices"], c["x"], c["w_fc"], c["c"], c["mu"], c["inv_sigma"])
+    hk = (c["x"].astype(np.float64) @ c["w_fc"].astype(np.float64)).astype(np.float32)
+    u = UnfusedGmm(c, dev(c["indptr"]), dev(c["indices"]))
+    u.fwd(dev(c["c"]), dev(c["mu"]), dev(c["inv_sigma"]), dev(hk))
+    torch.cuda.synchronize()
+    assert_close("out", u.out.cpu().numpy(), fwd["out"])

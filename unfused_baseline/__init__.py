@@ -6,12 +6,13 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "libgnnunfused.so")
+SOURCES = ["unfused_gat.hip", "unfused_edgeconv_gmm.hip"]
 
 
 def build(verbose=True):
     cmd = ["/opt/rocm/bin/hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
-           os.path.join(HERE, "unfused_gat.hip"), "-o", LIB]
+           *[os.path.join(HERE, f) for f in SOURCES], "-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -30,6 +31,12 @@ def load():
     vp, i32, i64, f32 = C.c_void_p, C.c_int, C.c_int64, C.c_float
     lib.unfused_gat_graph_fwd.argtypes = [C.c_int32, i64, i32, i32, f32] + [vp] * 13 + [vp]
     lib.unfused_gat_graph_bwd.argtypes = [C.c_int32, i64, i32, i32, f32] + [vp] * 19 + [vp]
+    lib.unfused_ec_u_sub_v.argtypes = [i64, i32] + [vp] * 4 + [vp]
+    lib.unfused_ec_add_max.argtypes = [C.c_int32, i64, i32] + [vp] * 7 + [vp]
+    lib.unfused_gmm_graph_fwd.argtypes = [C.c_int32, i64, i32, i32] + [vp] * 10 + [vp]
+    lib.unfused_marker.argtypes = [i32, vp]
+    for f in (lib.unfused_ec_u_sub_v, lib.unfused_ec_add_max, lib.unfused_gmm_graph_fwd, lib.unfused_marker):
+        f.restype = C.c_int
     lib.unfused_gat_graph_fwd.restype = C.c_int
     lib.unfused_gat_graph_bwd.restype = C.c_int
     return lib

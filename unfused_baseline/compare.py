@@ -56,6 +56,74 @@ class UnfusedGat:
         return 4 * 4 * self.nnz * self.H                  # M0, M2 stashed + two transient per-edge tensors
 
 
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dst_of_edges(indptr, n):
+    deg = (indptr[1:] - indptr[:-1]).to(torch.int64)
+    return torch.repeat_interleave(torch.arange(n, device=indptr.device, dtype=torch.int32), deg)
+
+
+class UnfusedEdgeConv:
+    """Forward pass in the original dataflow: u_sub_v, Theta on edges, Phi on vertices,
+    e_add_v, reduce_max; E0, E1, E2 live in HBM."""
+
+    def __init__(self, c, indptr, indices):
+        self.lib = load()
+        self.n, self.nnz, self.fin, self.fout = c["n"], c["nnz"], c["fin"], c["fout"]
+        dev = indptr.device
+        self.indptr, self.indices = indptr, indices
+        self.dst = _dst_of_edges(indptr, self.n)
+        f = lambda *shape: torch.empty(shape, dtype=torch.float32, device=dev)
+        self.E0, self.E1, self.E2 = f(self.nnz, self.fin), f(self.nnz, self.fout), f(self.nnz, self.fout)
+        self.N1, self.out = f(self.n, self.fout), f(self.n, self.fout)
+        self.argmax = torch.empty((self.n, self.fout), dtype=torch.int32, device=dev)
+
+    def fwd(self, x, theta, phi):
+        import paper_2110_09524_amd as pk
+        rc = self.lib.unfused_ec_u_sub_v(self.nnz, self.fin, _p(self.indices), _p(self.dst), _p(x), _p(self.E0),
+                                         _stream())
+        if rc:
+            raise RuntimeError(f"unfused_ec_u_sub_v failed: {rc}")
+        pk.gnn_linear_fwd(self.E0, theta, self.E1)   # Theta on every edge
+        pk.gnn_linear_fwd(x, phi, self.N1)           # Phi on vertices
+        rc = self.lib.unfused_ec_add_max(self.n, self.nnz, self.fout, _p(self.indptr), _p(self.dst), _p(self.E1),
+                                         _p(self.N1), _p(self.E2), _p(self.out), _p(self.argmax), _stream())
+        if rc:
+            raise RuntimeError(f"unfused_ec_add_max failed: {rc}")
+
+    def intermediate_bytes(self):
+        return 4 * self.nnz * (self.fin + 2 * self.fout) + 4 * self.n * self.fout   # E0, E1, E2, N1
+
+
+class UnfusedGmm:
+    """Forward graph operators with the pseudo-coordinates and Gaussian weights in HBM."""
+
+    def __init__(self, c, indptr, indices):
+        self.lib = load()
+        self.n, self.nnz, self.F, self.K = c["n"], c["nnz"], c["fout"], c["k"]
+        dev = indptr.device
+        self.indptr, self.indices = indptr, indices
+        self.dst = _dst_of_edges(indptr, self.n)
+        f = lambda *shape: torch.empty(shape, dtype=torch.float32, device=dev)
+        self.P, self.W, self.out = f(self.nnz, 2), f(self.nnz, self.K), f(self.n, self.F)
+
+    def fwd(self, cc, mu, inv_sigma, hk):
+        rc = self.lib.unfused_gmm_graph_fwd(self.n, self.nnz, self.K, self.F, _p(self.indptr), _p(self.indices),
+                                            _p(self.dst), _p(cc), _p(mu), _p(inv_sigma), _p(hk), _p(self.P),
+                                            _p(self.W), _p(self.out), _stream())
+        if rc:
+            raise RuntimeError(f"unfused_gmm_graph_fwd failed: {rc}")
+
+    def intermediate_bytes(self):
+        return 4 * self.nnz * (2 + self.K)
+
+
+def marker(i):
+    load().unfused_marker(i, _stream())
+
+
 def timed(fn, reps=3):
     fn()
     torch.cuda.synchronize()
@@ -93,4 +161,44 @@ def compare_gat(c, g, indptr, indices, z, el, er, gout, a_l, a_r, out_fused, dz_
         "paper_io_closed_form_elements": {           # Sec. 5 example, forward graph operators
             "unfused": V * H * F + 7 * E * H + 3 * E * H * F, "fused": V * H * F + 5 * E * H + 2 * E * H * F},
         "max_abs_diff_vs_fused": {"out": err_out, "dz": err_dz},
+    }
+
+
+def compare_edgeconv(c, indptr, indices, x, theta, phi, fused_fwd, out_fused, reps=20):
+    """Whole forward layer both ways (the reorganization moves the linear layers, so they are
+    inside the comparison): fused_fwd() runs the library's forward call."""
+    u = UnfusedEdgeConv(c, indptr, indices)
+    marker(0)
+    t_unf = timed(lambda: u.fwd(x, theta, phi), reps)
+    marker(1)
+    t_fus = timed(fused_fwd, reps)
+    marker(2)
+    n, fout = u.n, u.fout
+    fused_bytes = 4 * n * 2 * fout + 4 * n * fout + 4 * n * fout       # pq, out, argmax
+    return {
+        "scope": "whole forward layer (linear layers included: the reorganization moves them)",
+        "unfused_fwd_ms": t_unf, "fused_fwd_ms": t_fus, "time_ratio_unfused_over_fused": t_unf / t_fus,
+        "intermediate_bytes": {"unfused_per_edge_tensors": u.intermediate_bytes(), "fused_vertex_tensors": fused_bytes,
+                               "ratio": u.intermediate_bytes() / fused_bytes},
+        "linear_flops": {"unfused": 2.0 * (u.nnz + n) * u.fin * fout, "fused": 2.0 * n * u.fin * 2 * fout},
+        "max_abs_diff_vs_fused": {"out": float((u.out - out_fused).abs().max())},
+        "dispatches_per_section": reps + 1,
+    }
+
+
+def compare_gmm(c, indptr, indices, cc, mu, inv_sigma, hk, fused_fwd, out_fused, reps=20):
+    """Forward graph operators; the projection hk = x w_fc is the same in both arms and is part of
+    fused_fwd() only because the library's forward call includes it (its time is reported apart)."""
+    u = UnfusedGmm(c, indptr, indices)
+    marker(0)
+    t_unf = timed(lambda: u.fwd(cc, mu, inv_sigma, hk), reps)
+    marker(1)
+    t_fus = timed(fused_fwd, reps)
+    marker(2)
+    return {
+        "scope": "forward graph operators (fused_fwd_ms also contains the projection, see kernels)",
+        "unfused_graph_fwd_ms": t_unf, "fused_fwd_ms_with_projection": t_fus,
+        "intermediate_bytes": {"unfused_per_edge_tensors": u.intermediate_bytes(), "fused": 0},
+        "max_abs_diff_vs_fused": {"out": float((u.out - out_fused).abs().max())},
+        "dispatches_per_section": reps + 1,
     }
