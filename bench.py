@@ -27,7 +27,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 FP32_VECTOR_TFLOPS = 157.3      # MI355X published fp32 vector peak
 
 
-# ---- byte / flop models (stated in the design doc section 6) -------------------------------
+# ---- byte / flop models: every array a kernel touches counted once (unique), per-edge bytes with
+# no cache reuse (gather), fp32 flops ------------------------------------------------------------
 def gat_models(n, e, fin, H, F):
     HF = H * F
     V, S = 4 * n * HF, 4 * n * H        # one [n, HF] / one [n, H] fp32 matrix
