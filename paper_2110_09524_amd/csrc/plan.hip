@@ -67,20 +67,19 @@ __global__ void k_degree_and_bucket(int32_t n, const int32_t* __restrict__ ptr,
 }
 
 // key of an edge for the column-blocked order: (block of its column) * n + its row.
-// pos -> row by binary search in the row pointers (rows may be empty).
+// One wavefront per row, lanes strided over the row's edges (coalesced, no search).
 __global__ void k_block_keys(int32_t n, int64_t nnz, const int32_t* __restrict__ ptr,
                              const int32_t* __restrict__ cols, int32_t block_cols,
                              uint64_t* __restrict__ keys, int32_t* __restrict__ counts) {
-  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (i >= nnz) return;
-  int32_t lo = 0, hi = n;  // invariant: ptr[lo] <= i < ptr[hi]
-  while (hi - lo > 1) {
-    int32_t mid = lo + ((hi - lo) >> 1);
-    if ((int64_t)ptr[mid] <= i) lo = mid; else hi = mid;
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) >> 6;
+  if (row >= n) return;
+  const int32_t beg = ptr[row], end = ptr[row + 1];
+  for (int32_t i = beg + lane; i < end; i += 64) {
+    const uint64_t key = (uint64_t)(cols[i] / block_cols) * (uint64_t)n + (uint64_t)row;
+    keys[i] = key;
+    atomicAdd(&counts[key], 1);  // integer count
   }
-  const uint64_t key = (uint64_t)(cols[i] / block_cols) * (uint64_t)n + (uint64_t)lo;
-  keys[i] = key;
-  atomicAdd(&counts[key], 1);  // integer count
 }
 
 // bseg[b*n + r] = (bptr[b*n + row], bptr[b*n + row + 1]) with row = order[r]: the blocked
@@ -202,7 +201,7 @@ static gnn_status_t build_blocked(gnn_graph* g, int side, const int32_t* ptr, co
   GNN_HIP(hipMalloc((void**)&g->bptr[side], sizeof(int32_t) * ((size_t)slots + 1)));
   GNN_HIP(hipMalloc((void**)&g->bcol[side], sizeof(int32_t) * (size_t)nnz));
   GNN_HIP(hipMemsetAsync(counts, 0, sizeof(int32_t) * ((size_t)slots + 1), st));
-  k_block_keys<<<cdiv(nnz, thr), thr, 0, st>>>(n, nnz, ptr, cols, g->block_cols, keys, counts);
+  k_block_keys<<<cdiv((int64_t)n * 64, thr), thr, 0, st>>>(n, nnz, ptr, cols, g->block_cols, keys, counts);
   GNN_LAUNCH_CHECK();
   {
     size_t bytes = 0;
