@@ -194,14 +194,7 @@ def test_column_blocked_path(block_cols, H, F):
         res = run_gat(c, graph=g)
     finally:
         pk.gnn_config_set("block_cols", 24576)
-    grads = {k: res.pop(k) for k in ("gx", "gw", "ga_l", "ga_r")}
-    compare(c, res, fwd, None)
-    assert np.isfinite(res["out"]).all() and (res["d"] >= 1.0 - 1e-6).all()
-    _, amb_vertex = gat_kink_masks(c["indptr"], fwd)
-    assert_close("gx", np.where(amb_vertex[:, None], bwd["gx"], grads["gx"]), bwd["gx"], rtol=10 * RTOL,
-                 atol=10 * ATOL, row_scale=True)
-    for k in ("gw", "ga_l", "ga_r"):
-        assert_close(k, grads[k], bwd[k], rtol=10 * RTOL, atol=10 * ATOL, reduce_scale=True)
+    compare(c, res, fwd, bwd)
     # same inputs through the single-launch kernels: both paths must agree with the oracle
     pk.gnn_config_set("force_simple_kernels", 1)
     try:
@@ -256,14 +249,7 @@ def test_blocked_path_with_the_score_table_in_lds(H, F):
         g.close()
     finally:
         pk.gnn_config_set("block_cols", 24576)
-    grads = {k: res.pop(k) for k in ("gx", "gw", "ga_l", "ga_r")}
-    compare(c, res, fwd, None)
-    assert np.isfinite(res["out"]).all() and (res["d"] >= 1.0 - 1e-6).all()
-    _, amb_vertex = gat_kink_masks(c["indptr"], fwd)
-    assert_close("gx", np.where(amb_vertex[:, None], bwd["gx"], grads["gx"]), bwd["gx"], rtol=10 * RTOL,
-                 atol=10 * ATOL, row_scale=True)
-    for k in ("gw", "ga_l", "ga_r"):
-        assert_close(k, grads[k], bwd[k], rtol=10 * RTOL, atol=10 * ATOL, reduce_scale=True)
+    compare(c, res, fwd, bwd)
     compare(c, res_nostash, fwd, bwd)
     for k in res:
         assert np.array_equal(res[k], ref[k]), f"{k}: LDS-table and plain variants differ"
