@@ -4,8 +4,8 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gat_c4]
 
 Default workload: the Reddit-scale GAT layer (`gat_c4`), the largest GAT configuration,
-on which the headline metric is quoted.  `ec_c3` (EdgeConv) and `gmm_c5` (MoNet) run
-the same way.  One "step" is one pass of the whole hot path over the synthetic graph:
+on which the headline metric is quoted.  `ec_c3` (EdgeConv), `gmm_c5` (MoNet) and `gcn_c4`
+(GCN on the same graph) run the same way.  One "step" is one pass of the whole hot path over the synthetic graph:
 projection (MFMA), the fused edge kernels of the forward pass, the backward edge
 kernels, parameter gradients and the backward products.  The graph plan (CSC
 transpose, degree order, blocked edge lists) is built once per graph before the timed
@@ -73,6 +73,15 @@ def gmm_models(n, e, fin, F, K):
     return unique, gather, flops
 
 
+def gcn_models(n, e, fin, F):
+    V = 4 * n * F
+    I = 4 * e + 8 * n
+    unique = {"gcn_fwd_fused": I + V + 4 * n + V, "gcn_bwd_src": I + V + 4 * n + V}
+    gather = {"gcn_fwd_fused": e * (4 + 4 * F), "gcn_bwd_src": e * (4 + 4 * F)}
+    flops = {"gcn_fwd_fused": e * F, "gcn_bwd_src": e * F}
+    return unique, gather, flops
+
+
 def read_traffic(workload):
     """HBM-side bytes per launch of the dominant kernel, measured with rocprofv3 --pmc
     (FETCH_SIZE, WRITE_SIZE, each calibrated on a device copy of known size) and kept in
@@ -123,6 +132,37 @@ def cpu_baseline_gat(c, budget_rows):
     del fwd, bwd
     t_edges = max(t_sample - t_dense, 1e-9)
     t_full = t_dense + t_edges * (e / max(e_s, 1))
+    return {
+        "value": e / t_full, "unit": "edges/s", "cores": int(oracle_threads()), "kind": "oracle",
+        "sample": (f"fp64 numpy oracle fwd+bwd on the in-edges of {len(rows)} seeded destination rows "
+                   f"({e_s} of {e} edges) with all {n} vertices' dense products; measured {t_sample:.2f} s "
+                   f"of which {t_dense:.2f} s dense; per-edge part scaled by E/E_sample"),
+        "measured_s": t_sample,
+    }
+
+
+def cpu_baseline_gcn(c, budget_rows):
+    """As cpu_baseline_gat: dense products at all vertices, per-edge part on sampled rows."""
+    import numpy as np
+    from oracle import gcn as og
+    from oracle.segments import restrict_rows
+    n, e = c["n"], c["nnz"]
+    rng = np.random.default_rng(12345)
+    rows = np.sort(rng.choice(n, size=min(budget_rows, n), replace=False))
+    ip, ix, _ = restrict_rows(c["indptr"], c["indices"], rows)
+    e_s = int(ix.shape[0])
+    t0 = time.perf_counter()
+    fwd = og.gcn_forward(ip, ix, c["x"], c["w"], c["c_src"], c["c_dst"])
+    bwd = og.gcn_backward(ip, ix, c["x"], c["w"], c["c_src"], c["c_dst"], c["gout"], fwd)
+    t_sample = time.perf_counter() - t0
+    X64, W64 = c["x"].astype(np.float64), c["w"].astype(np.float64)
+    t1 = time.perf_counter()
+    _ = X64 @ W64
+    _ = X64.T @ bwd["dZ"]
+    _ = bwd["dZ"] @ W64.T
+    t_dense = time.perf_counter() - t1
+    del fwd, bwd
+    t_full = t_dense + max(t_sample - t_dense, 1e-9) * (e / max(e_s, 1))
     return {
         "value": e / t_full, "unit": "edges/s", "cores": int(oracle_threads()), "kind": "oracle",
         "sample": (f"fp64 numpy oracle fwd+bwd on the in-edges of {len(rows)} seeded destination rows "
@@ -251,6 +291,22 @@ def main():
         cfg = {"in_feat": fin, "out_feat": F, "kernels": K,
                "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded"}
         gemm_flops = 2.0 * n * fin * K * F
+    elif kind == "gcn":
+        F = c["fout"]
+        w, c_src, c_dst = to(c["w"]), to(c["c_src"]), to(c["c_dst"])
+        zs, out = new(n, F), new(n, F)
+        gx, gw = new(n, fin), new(fin, F)
+        ws_bytes = pk.gnn_gcn_workspace_bytes(g, fin, F)
+        ws = new(max(ws_bytes, 16), dtype=torch.uint8)
+
+        def step():
+            pk.gnn_gcn_fwd(g, fin, F, x, w, c_src, c_dst, zs, out)
+            pk.gnn_gcn_bwd(g, fin, F, x, w, c_src, c_dst, gout, gx, gw, ws)
+        unique, gather, flops = gcn_models(n, e, fin, F)
+        metric = "fused GCN layer fwd+bwd edges/sec"
+        cfg = {"in_feat": fin, "out_feat": F, "edge_weight": "1/sqrt(outdeg(u) indeg(v))",
+               "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded"}
+        gemm_flops = 2.0 * n * fin * F
     else:
         raise SystemExit(f"unknown workload kind {kind}")
 
@@ -354,7 +410,12 @@ def main():
         result["unfused_comparison"] = cmp
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample ...", file=sys.stderr, flush=True)
-        result["cpu_baseline"] = cpu_baseline_gat(c, args.cpu_rows) if kind == "gat" else cpu_baseline_full(c)
+        if kind == "gat":
+            result["cpu_baseline"] = cpu_baseline_gat(c, args.cpu_rows)
+        elif kind == "gcn":
+            result["cpu_baseline"] = cpu_baseline_gcn(c, args.cpu_rows)
+        else:
+            result["cpu_baseline"] = cpu_baseline_full(c)
     print(json.dumps(result))
 
 

@@ -233,11 +233,35 @@ gnn_status_t gnn_gmm_bwd(const gnn_graph_t* graph, int fin, int fout, int k, con
                          void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------- *
+ * GCN layer with separable static edge weights (App. A.2 "GCN", no bias, identity
+ * activation):
+ *   out[v] = sum over in-edges (u -> v) of  c_src[u] c_dst[v] (x w)[u]
+ * c_src, c_dst [n] are per-vertex factors of the gradient-free edge weight (both
+ * 1/sqrt(degree) for the symmetric normalisation; (1, 1/degree) for the mean).
+ * Both factors are applied on vertices (Sec. 4), so the fused pass is an unweighted
+ * gather-sum.  zs [n,fout] receives c_src * (x w) (an output; the backward call does
+ * not need it).  fout % 4 == 0, fout <= 1024; zs, out, gout 16-byte aligned.
+ * gnn_gcn_bwd: gradients of L = <gout, out> w.r.t. x (gx [n,fin], nullable) and
+ * w (gw [fin,fout]); workspace of gnn_gcn_workspace_bytes (vertex-sized).
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP as for the other layers.
+ * ------------------------------------------------------------------------- */
+size_t gnn_gcn_workspace_bytes(const gnn_graph_t* graph, int fin, int fout);
+
+gnn_status_t gnn_gcn_fwd(const gnn_graph_t* graph, int fin, int fout, const float* x /*[n,fin]*/,
+                         const float* w /*[fin,fout]*/, const float* c_src /*[n]*/,
+                         const float* c_dst /*[n]*/, float* zs /*[n,fout]*/, float* out /*[n,fout]*/,
+                         void* stream);
+
+gnn_status_t gnn_gcn_bwd(const gnn_graph_t* graph, int fin, int fout, const float* x, const float* w,
+                         const float* c_src, const float* c_dst, const float* gout /*[n,fout]*/,
+                         float* gx /*nullable*/, float* gw, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------- *
  * Per-kernel timing (measurement aid, Sec. 7 metrics).  While enabled, every
  * kernel the library launches is bracketed by HIP events recorded on the
  * caller's stream.  gnn_prof_collect synchronises those events (host sync) and
  * folds them into per-kernel totals; gnn_prof_get reads entry i (name is a
- * library-owned string).  Not thread-safe; meant for benchmarks only.
+ * library-owned string).  The bookkeeping is process-wide (one mutex); meant for benchmarks.
  * ------------------------------------------------------------------------- */
 gnn_status_t gnn_prof_enable(int on);
 gnn_status_t gnn_prof_collect(void);

@@ -23,7 +23,8 @@ EXPORTS = [
     "gnn_last_error", "gnn_graph_create", "gnn_graph_destroy", "gnn_graph_get_csc",
     "gnn_graph_get_buckets", "gnn_graph_get_blocked", "gnn_config_set", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
     "gnn_gat_bwd", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
-    "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd", "gnn_prof_enable",
+    "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd",
+    "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_prof_enable",
     "gnn_prof_collect", "gnn_prof_reset", "gnn_prof_count", "gnn_prof_get",
 ]
 
@@ -62,6 +63,10 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_gmm_workspace_bytes.argtypes = [vp, i32, i32, i32]
     lib.gnn_gmm_fwd.argtypes = [vp, i32, i32, i32] + [vp] * 7 + [vp, sz, vp]
     lib.gnn_gmm_bwd.argtypes = [vp, i32, i32, i32] + [vp] * 11 + [vp, sz, vp]
+    lib.gnn_gcn_workspace_bytes.restype = sz
+    lib.gnn_gcn_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.gnn_gcn_fwd.argtypes = [vp, i32, i32] + [vp] * 6 + [vp]
+    lib.gnn_gcn_bwd.argtypes = [vp, i32, i32] + [vp] * 7 + [vp, sz, vp]
     lib.gnn_prof_enable.argtypes = [i32]
     lib.gnn_prof_collect.argtypes = []
     lib.gnn_prof_reset.argtypes = []
@@ -70,7 +75,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     for name in EXPORTS:
         fn = getattr(lib, name)
         if name not in ("gnn_last_error", "gnn_gat_workspace_bytes", "gnn_edgeconv_workspace_bytes",
-                        "gnn_gmm_workspace_bytes", "gnn_prof_count"):
+                        "gnn_gmm_workspace_bytes", "gnn_gcn_workspace_bytes", "gnn_prof_count"):
             fn.restype = C.c_int
     return lib
 
@@ -223,6 +228,21 @@ def gnn_edgeconv_bwd(g: Graph, fin, fout, x, theta, phi, argmax, gout, gx, gthet
     wp, wb = _ws_args(ws)
     _check(lib().gnn_edgeconv_bwd(g.handle, fin, fout, _f(x), _f(theta), _f(phi), _i(argmax), _f(gout),
                                   _f(gx), _f(gtheta), _f(gphi), wp, wb, _stream(stream)))
+
+
+def gnn_gcn_workspace_bytes(g: Graph, fin, fout) -> int:
+    return int(lib().gnn_gcn_workspace_bytes(g.handle, fin, fout))
+
+
+def gnn_gcn_fwd(g: Graph, fin, fout, x, w, c_src, c_dst, zs, out, stream=None):
+    _check(lib().gnn_gcn_fwd(g.handle, fin, fout, _f(x), _f(w), _f(c_src), _f(c_dst), _f(zs), _f(out),
+                             _stream(stream)))
+
+
+def gnn_gcn_bwd(g: Graph, fin, fout, x, w, c_src, c_dst, gout, gx, gw, ws, stream=None):
+    wp, wb = _ws_args(ws)
+    _check(lib().gnn_gcn_bwd(g.handle, fin, fout, _f(x), _f(w), _f(c_src), _f(c_dst), _f(gout), _f(gx),
+                             _f(gw), wp, wb, _stream(stream)))
 
 
 def gnn_gmm_workspace_bytes(g: Graph, fin, fout, k) -> int:

@@ -150,3 +150,24 @@ def run_gmm(c, backward=True):
         res.update(gx=gx, gw_fc=gw_fc, gmu=gmu, ginv_sigma=gis)
     torch.cuda.synchronize()
     return {k: v.cpu().numpy() for k, v in res.items()}
+
+
+def run_gcn(c, backward=True, want_gx=True, graph=None):
+    n, fin, fout = c["n"], c["fin"], c["fout"]
+    indptr, indices = dev(c["indptr"]), dev(c["indices"])
+    g = graph or pk.Graph(indptr, indices)
+    x, w, c_src, c_dst = dev(c["x"]), dev(c["w"]), dev(c["c_src"]), dev(c["c_dst"])
+    zs, out = empty((n, fout)), empty((n, fout))
+    pk.gnn_gcn_fwd(g, fin, fout, x, w, c_src, c_dst, zs, out)
+    res = dict(zs=zs, out=out)
+    if backward:
+        ws = workspace(pk.gnn_gcn_workspace_bytes(g, fin, fout))
+        ws.fill_(0xFF)
+        gx = empty((n, fin)) if want_gx else None
+        gw = empty((fin, fout))
+        pk.gnn_gcn_bwd(g, fin, fout, x, w, c_src, c_dst, dev(c["gout"]), gx, gw, ws)
+        res["gw"] = gw
+        if want_gx:
+            res["gx"] = gx
+    torch.cuda.synchronize()
+    return {k: v.cpu().numpy() for k, v in res.items()}

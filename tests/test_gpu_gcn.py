@@ -1,0 +1,104 @@
+"""GCN layer: HIP path (through the C ABI) against the fp64 oracle, element by element."""
+import numpy as np
+import pytest
+
+from helpers import random_graph, tiny_graph
+from oracle import gcn as og
+from workloads import make
+
+pytestmark = pytest.mark.gpu
+
+
+def synth(rng, indptr, indices, fin, fout):
+    n = len(indptr) - 1
+    return dict(n=n, nnz=len(indices), fin=fin, fout=fout, indptr=indptr, indices=indices,
+                x=rng.standard_normal((n, fin)).astype(np.float32),
+                w=(rng.standard_normal((fin, fout)) * np.sqrt(2.0 / (fin + fout))).astype(np.float32),
+                c_src=rng.uniform(0.2, 1.5, n).astype(np.float32),
+                c_dst=rng.uniform(0.2, 1.5, n).astype(np.float32),
+                gout=rng.standard_normal((n, fout)).astype(np.float32))
+
+
+def check(c, **kw):
+    from gpu_harness import assert_close, run_gcn
+    fwd = og.gcn_forward(c["indptr"], c["indices"], c["x"], c["w"], c["c_src"], c["c_dst"])
+    bwd = og.gcn_backward(c["indptr"], c["indices"], c["x"], c["w"], c["c_src"], c["c_dst"], c["gout"], fwd)
+    res = run_gcn(c, **kw)
+    assert_close("zs", res["zs"], c["c_src"].astype(np.float64)[:, None] * fwd["Z"])
+    assert_close("out", res["out"], fwd["out"])
+    assert_close("gw", res["gw"], bwd["gw"], reduce_scale=True)
+    if "gx" in res:
+        assert_close("gx", res["gx"], bwd["gx"], row_scale=True)
+    return res
+
+
+def test_mid_workload():
+    print("gcn: gcn_mid", flush=True)
+    check(make("gcn_mid"))
+
+
+@pytest.mark.parametrize("fin,fout", [(3, 4), (9, 20), (64, 64), (17, 128), (8, 512), (5, 1024)])
+def test_shapes(fin, fout):
+    print(f"gcn: shapes fin={fin} fout={fout}", flush=True)
+    rng = np.random.default_rng(fin * 100 + fout)
+    indptr, indices = random_graph(rng, 300, 3000, self_loops=True, duplicates=True)
+    check(synth(rng, indptr, indices, fin, fout))
+
+
+def test_empty_rows_hub_and_skipped_input_gradient():
+    print("gcn: empty rows + hub", flush=True)
+    rng = np.random.default_rng(8)
+    n = 600
+    edges = [(u, 0) for u in range(n)]                      # vertex 0 hears from everyone
+    edges += [(0, v) for v in range(1, n, 3)]               # and speaks to many
+    edges += [(int(rng.integers(0, n)), int(v)) for v in range(20, n) for _ in range(int(v) % 3)]
+    indptr, indices = tiny_graph(n, edges)
+    c = synth(rng, indptr, indices, 12, 32)
+    res = check(c)
+    empty_rows = np.flatnonzero(np.diff(indptr) == 0)
+    assert empty_rows.size > 0 and (res["out"][empty_rows] == 0).all()
+    check(c, want_gx=False)
+
+
+def test_graph_without_edges():
+    print("gcn: no edges", flush=True)
+    rng = np.random.default_rng(9)
+    n = 33
+    res = check(synth(rng, np.zeros(n + 1, dtype=np.int32), np.zeros(0, dtype=np.int32), 6, 16))
+    assert (res["out"] == 0).all() and (res["gw"] == 0).all() and (res["gx"] == 0).all()
+
+
+@pytest.mark.parametrize("block_cols,fout", [(256, 256), (500, 128), (300, 512), (128, 1024)])
+def test_column_blocked_path(block_cols, fout):
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev
+    print(f"gcn: blocked path block_cols={block_cols} fout={fout}", flush=True)
+    rng = np.random.default_rng(block_cols + fout)
+    indptr, indices = random_graph(rng, 1500, 30000, self_loops=False, duplicates=True)
+    c = synth(rng, indptr, indices, 24, fout)
+    pk.gnn_config_set("block_cols", block_cols)
+    try:
+        g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
+        assert g.blocked(0)[0] == -(-c["n"] // block_cols)
+        check(c, graph=g)
+        g.close()
+    finally:
+        pk.gnn_config_set("block_cols", 24576)
+
+
+def test_bad_arguments_raise():
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev, empty, workspace
+    rng = np.random.default_rng(10)
+    indptr, indices = random_graph(rng, 50, 200)
+    c = synth(rng, indptr, indices, 8, 16)
+    g = pk.Graph(dev(indptr), dev(indices))
+    x, w, cs, cd = dev(c["x"]), dev(c["w"]), dev(c["c_src"]), dev(c["c_dst"])
+    with pytest.raises(pk.GnnError) as e:          # fout not a multiple of 4
+        pk.gnn_gcn_fwd(g, 8, 18, x, w, cs, cd, empty((50, 18)), empty((50, 18)))
+    assert e.value.status == 4
+    with pytest.raises(pk.GnnError) as e:          # workspace too small
+        pk.gnn_gcn_bwd(g, 8, 16, x, w, cs, cd, dev(c["gout"]), None, empty((8, 16)),
+                       workspace(pk.gnn_gcn_workspace_bytes(g, 8, 16) - 256))
+    assert e.value.status == 3
+    g.close()

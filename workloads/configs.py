@@ -7,6 +7,7 @@ Inputs only (random structure, random values); no layer arithmetic lives here.
   ec_c3    EdgeConv, 32 clouds x 1024 points, k=20, 64 -> 64   (Sec. 7.2)
   gat_c4   Reddit-scale GAT, 602 -> 4 heads x 64, fwd+bwd      (Sec. 7.2/7.3)
   gmm_c5   MoNet, K=3 kernels, r=2 pseudo-coords, 64 -> 64     (Sec. 7.2)
+  gcn_c4   GCN with symmetric normalisation on the gat_c4 graph, 602 -> 256 (App. A.2)
 
 Smaller "mid" variants keep a workload's feature widths (hence the same kernel
 instantiation and launch shape) on a graph the CPU oracle finishes in seconds.
@@ -79,6 +80,24 @@ def _gmm(name, n, graph, fin, fout, k, seed):
     )
 
 
+def _gcn(name, n, graph, fin, fout, seed):
+    indptr, indices = graph
+    rng = graphs.rng_for(seed ^ 0xA5A5)
+    indeg = np.diff(indptr).astype(np.float64)
+    outdeg = np.bincount(indices, minlength=n).astype(np.float64)
+    return dict(
+        name=name, kind="gcn", n=n, nnz=int(indices.shape[0]), fin=fin, fout=fout,
+        indptr=indptr, indices=indices,
+        x=_normal(rng, (n, fin)),
+        w=glorot(rng, fin, fout, (fin, fout)),
+        # symmetric normalisation of a directed graph: 1/sqrt(out-degree of the source) and
+        # 1/sqrt(in-degree of the destination)
+        c_src=(1.0 / np.sqrt(np.maximum(outdeg, 1.0))).astype(np.float32),
+        c_dst=(1.0 / np.sqrt(np.maximum(indeg, 1.0))).astype(np.float32),
+        gout=_normal(rng, (n, fout)),
+    )
+
+
 def _make_gat_c1(seed):
     n = 2000
     return _gat("gat_c1", n, graphs.erdos_renyi(n, 10_000, seed), 64, 1, 16, seed)
@@ -102,6 +121,17 @@ def _make_gat_c4(seed):
 def _make_gmm_c5(seed):
     n = 100_000
     return _gmm("gmm_c5", n, graphs.chung_lu(n, 2_000_000, 2.1, seed), 64, 64, 3, seed)
+
+
+def _make_gcn_c4(seed):
+    n = 232_965
+    # the same graph as gat_c4 (its id seeds the generator)
+    return _gcn("gcn_c4", n, graphs.chung_lu(n, 114_000_000, 2.1, SEED0 ^ 4), 602, 256, seed)
+
+
+def _make_gcn_mid(seed):
+    n = 6000
+    return _gcn("gcn_mid", n, graphs.chung_lu(n, 300_000, 2.1, seed), 602, 256, seed)
 
 
 # mid-size variants: same widths as the big workload, oracle-sized graphs
@@ -128,6 +158,8 @@ _MAKERS = {
     "gat_c4_mid": (104, _make_gat_c4_mid),
     "ec_c3_mid": (103, _make_ec_c3_mid),
     "gmm_c5_mid": (105, _make_gmm_c5_mid),
+    "gcn_c4": (6, _make_gcn_c4),
+    "gcn_mid": (106, _make_gcn_mid),
 }
 NAMES = tuple(_MAKERS)
 
