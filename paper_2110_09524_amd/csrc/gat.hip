@@ -565,24 +565,41 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
 }
 
 // ---- a6: ga_l[h,f] = sum_u del[u,h] z[u,h,f], ga_r[h,f] = sum_v der[v,h] z[v,h,f] ---
-// stage 1: each block reduces a contiguous range of vertices; stage 2 adds the blocks in order
-__global__ void k_gat_param_partial(int64_t n, int H, int F, int64_t rows_per_block,
-                                    const float* __restrict__ z, const float* __restrict__ del,
-                                    const float* __restrict__ der, float* __restrict__ partial) {
+// stage 1: each block reduces a contiguous range of vertices; stage 2 adds the blocks in order.
+// Inside a block, HF/4 lanes own the float4 columns of a row and the 256 / (HF/4) row groups
+// take the block's rows round-robin; their sums are added in group order (fixed => reproducible).
+constexpr int kParamThreads = 256;
+__global__ __launch_bounds__(kParamThreads) void k_gat_param_partial(
+    int64_t n, int H, int F, int64_t rows_per_block, const float* __restrict__ z,
+    const float* __restrict__ del, const float* __restrict__ der, float* __restrict__ partial) {
+  __shared__ float4 red[2][kParamThreads];
   const int HF = H * F;
+  const int lanes = HF / 4;                      // float4 columns of a row (<= 256)
+  const int groups = kParamThreads / lanes;      // row groups in this block (>= 1)
+  const int li = threadIdx.x % lanes, grp = threadIdx.x / lanes;
   const int64_t r0 = blockIdx.x * rows_per_block;
   int64_t r1 = r0 + rows_per_block;
   if (r1 > n) r1 = n;
-  for (int c = threadIdx.x; c < HF; c += blockDim.x) {
-    const int h = c / F;
-    float sl = 0.f, sr = 0.f;
-    for (int64_t r = r0; r < r1; ++r) {
-      const float zz = z[r * HF + c];
-      sl = fmaf(del[r * H + h], zz, sl);
-      sr = fmaf(der[r * H + h], zz, sr);
+  float4 sl = make_float4(0.f, 0.f, 0.f, 0.f), sr = sl;
+  if (grp < groups) {
+    const int h = (4 * li) / F;
+    for (int64_t r = r0 + grp; r < r1; r += groups) {
+      const float4 zz = ld4(z + r * HF + 4 * li);
+      fma4(sl, del[r * H + h], zz);
+      fma4(sr, der[r * H + h], zz);
     }
-    partial[((int64_t)blockIdx.x * 2 + 0) * HF + c] = sl;
-    partial[((int64_t)blockIdx.x * 2 + 1) * HF + c] = sr;
+  }
+  red[0][threadIdx.x] = sl;
+  red[1][threadIdx.x] = sr;
+  __syncthreads();
+  if (threadIdx.x < lanes) {
+    float4 tl = red[0][li], tr = red[1][li];
+    for (int g = 1; g < groups; ++g) {
+      add4(tl, red[0][g * lanes + li]);
+      add4(tr, red[1][g * lanes + li]);
+    }
+    st4(partial + ((int64_t)blockIdx.x * 2 + 0) * HF + 4 * li, tl);
+    st4(partial + ((int64_t)blockIdx.x * 2 + 1) * HF + 4 * li, tr);
   }
 }
 
@@ -962,7 +979,7 @@ extern "C" gnn_status_t gnn_gat_bwd(const gnn_graph_t* g, int fin, int heads, in
   {
     ProfScope p("gat_param_grad", st);
     const int64_t rpb = cdiv(n, L.nblk);
-    k_gat_param_partial<<<L.nblk, 256, 0, st>>>(n, heads, f, rpb, z, del, der, partial);
+    k_gat_param_partial<<<L.nblk, kParamThreads, 0, st>>>(n, heads, f, rpb, z, del, der, partial);
     GNN_LAUNCH_CHECK();
     // partial is [nblk][2][HF]: sum the l and the r halves separately, block order fixed
     GNN_TRY(sum_partials_strided(HF, L.nblk, partial, 2 * (int64_t)HF, ga_l, st));
