@@ -112,3 +112,57 @@ def test_gat_c4_sampled_rows_and_consistency(c4):
                      reduce_scale=k in ("gw", "ga_l", "ga_r"))
     assert_close("gx (two kernel paths)", res["gx"], res2["gx"], row_scale=True)
     g.close()
+
+
+def test_gcn_on_the_c4_graph_sampled_rows_and_consistency(c4):
+    """The GCN layer on the same graph and feature widths (602 -> 256), in the launch
+    configuration bench.py times for gcn_c4: sampled rows against the oracle, and
+    properties that hold at any size."""
+    import paper_2110_09524_amd as pk
+    from gpu_harness import assert_close, dev, run_gcn
+    from oracle import gcn as og
+    from oracle.segments import restrict_rows
+    c = dict(c4)
+    n = c["n"]
+    ip, ix = c["indptr"], c["indices"]
+    indeg = np.diff(ip).astype(np.float64)
+    outdeg = np.bincount(ix, minlength=n).astype(np.float64)
+    c.update(kind="gcn", fout=c["heads"] * c["f"],
+             c_src=(1.0 / np.sqrt(np.maximum(outdeg, 1.0))).astype(np.float32),
+             c_dst=(1.0 / np.sqrt(np.maximum(indeg, 1.0))).astype(np.float32))
+    g = pk.Graph(dev(ip), dev(ix))
+    assert g.blocked(0)[0] > 1
+    print("full size gcn: GPU fwd+bwd", flush=True)
+    res = run_gcn(c, graph=g)
+
+    rng = np.random.default_rng(7)
+    rows = np.unique(np.concatenate([[int(np.argmax(indeg)), int(np.argmin(indeg))],
+                                     rng.choice(n, size=40, replace=False)]))
+    print(f"full size gcn: oracle on the in-edges of {rows.size} rows", flush=True)
+    rip, rix, _ = restrict_rows(ip, ix, rows)
+    fwd = og.gcn_forward(rip, rix, c["x"], c["w"], c["c_src"], c["c_dst"])
+    assert_close("zs", res["zs"][rows], (c["c_src"].astype(np.float64)[:, None] * fwd["Z"])[rows])
+    assert_close("out", res["out"][rows], fwd["out"][rows])
+    # backward on sampled sources: their out-edges reach into many rows, so compare through the
+    # transposed graph restricted to those sources: dZ[u] = c_src[u] sum_v c_dst[v] gout[v]
+    srcs = rng.choice(np.flatnonzero(outdeg <= np.partition(outdeg, 2000)[2000]), size=5, replace=False)
+    dst_of = np.repeat(np.arange(n, dtype=np.int64), np.diff(ip))
+    W64 = c["w"].astype(np.float64)
+    for u in srcs:
+        vs = dst_of[ix == u]
+        dz_u = c["c_src"][u].astype(np.float64) * (c["c_dst"][vs].astype(np.float64)[:, None]
+                                                   * c["gout"][vs].astype(np.float64)).sum(axis=0)
+        assert_close(f"gx[{u}]", res["gx"][u][None, :], (dz_u @ W64.T)[None, :], row_scale=True)
+    print("full size gcn: properties", flush=True)
+    gw_w = float((res["gw"].astype(np.float64) * c["w"]).sum())
+    gx_x = float((res["gx"].astype(np.float64) * c["x"]).sum())
+    assert abs(gw_w - gx_x) <= 1e-4 * max(abs(gw_w), abs(gx_x)) + 1e-3
+    pk.gnn_config_set("force_simple_kernels", 1)
+    try:
+        res2 = run_gcn(c, graph=g)
+    finally:
+        pk.gnn_config_set("force_simple_kernels", 0)
+    assert_close("out (two kernel paths)", res["out"], res2["out"])
+    assert_close("gw (two kernel paths)", res["gw"], res2["gw"], reduce_scale=True)
+    assert_close("gx (two kernel paths)", res["gx"], res2["gx"], row_scale=True)
+    g.close()
