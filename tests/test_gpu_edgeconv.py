@@ -57,6 +57,11 @@ def test_c3_mid():
     check(make("ec_c3_mid"))
 
 
+def test_k40_mid():
+    print("edgeconv: ec_k40_mid", flush=True)
+    check(make("ec_k40_mid"))
+
+
 def test_c3_full():
     print("edgeconv: ec_c3", flush=True)
     check(make("ec_c3"))

@@ -7,6 +7,7 @@ Inputs only (random structure, random values); no layer arithmetic lives here.
   ec_c3    EdgeConv, 32 clouds x 1024 points, k=20, 64 -> 64   (Sec. 7.2)
   gat_c4   Reddit-scale GAT, 602 -> 4 heads x 64, fwd+bwd      (Sec. 7.2/7.3)
   gmm_c5   MoNet, K=3 kernels, r=2 pseudo-coords, 64 -> 64     (Sec. 7.2)
+  ec_k40   EdgeConv ablation setting: 64 clouds x 1024 points, k=40, 64 -> 64  (Sec. 7.3)
   gcn_c4   GCN with symmetric normalisation on the gat_c4 graph, 602 -> 256 (App. A.2)
 
 Smaller "mid" variants keep a workload's feature widths (hence the same kernel
@@ -123,6 +124,14 @@ def _make_gmm_c5(seed):
     return _gmm("gmm_c5", n, graphs.chung_lu(n, 2_000_000, 2.1, seed), 64, 64, 3, seed)
 
 
+def _make_ec_k40(seed):
+    return _edgeconv("ec_k40", 64, 1024, 40, 64, 64, seed)
+
+
+def _make_ec_k40_mid(seed):
+    return _edgeconv("ec_k40_mid", 3, 400, 40, 64, 128, seed)
+
+
 def _make_gcn_c4(seed):
     n = 232_965
     # the same graph as gat_c4 (its id seeds the generator)
@@ -158,6 +167,8 @@ _MAKERS = {
     "gat_c4_mid": (104, _make_gat_c4_mid),
     "ec_c3_mid": (103, _make_ec_c3_mid),
     "gmm_c5_mid": (105, _make_gmm_c5_mid),
+    "ec_k40": (7, _make_ec_k40),
+    "ec_k40_mid": (107, _make_ec_k40_mid),
     "gcn_c4": (6, _make_gcn_c4),
     "gcn_mid": (106, _make_gcn_mid),
 }
