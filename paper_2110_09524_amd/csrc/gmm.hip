@@ -544,9 +544,6 @@ static gnn_status_t gmm_check(const gnn_graph_t* g, int fin, int fout, int K, co
   GNN_REQUIRE(fout % 4 == 0 && fout <= 256, GNN_ERR_UNSUPPORTED,
               "%s: fout = %d must be a multiple of 4, at most 256", who, fout);
   GNN_REQUIRE(K <= kMaxK, GNN_ERR_UNSUPPORTED, "%s: k = %d exceeds %d", who, K, kMaxK);
-  GNN_REQUIRE(next_pow2(K) <= pick_group(fout).L, GNN_ERR_UNSUPPORTED,
-              "%s: %d kernels do not fit a %d-lane row group (fout too small)", who, K,
-              pick_group(fout).L);
   return GNN_OK;
 }
 

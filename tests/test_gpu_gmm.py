@@ -42,7 +42,7 @@ def test_workloads(name):
     check(make(name))
 
 
-@pytest.mark.parametrize("fin,fout,K", [(5, 16, 1), (9, 16, 4), (64, 64, 3), (12, 32, 8), (7, 256, 5),
+@pytest.mark.parametrize("fin,fout,K", [(6, 4, 8), (3, 16, 5), (5, 16, 1), (9, 16, 4), (64, 64, 3), (12, 32, 8), (7, 256, 5),
                                         (20, 24, 2)])
 def test_shapes(fin, fout, K):
     print(f"gmm: shape {fin}->{fout} K={K}", flush=True)
