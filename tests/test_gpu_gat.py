@@ -287,3 +287,42 @@ def test_large_score_range_is_stable(blocked):
                  atol=10 * ATOL, row_scale=True)
     for k in ("gw", "ga_l", "ga_r"):
         assert_close(k, grads[k], bwd[k], rtol=10 * RTOL, atol=10 * ATOL, reduce_scale=True)
+
+
+@pytest.mark.parametrize("fin,H,F", [(8, 64, 16), (8, 1, 1024), (1024, 2, 8), (4, 64, 4)])
+def test_largest_supported_shapes(fin, H, F):
+    """heads*f = 1024 (the widest row the kernels take), 64 heads, a wide input."""
+    from gpu_harness import run_gat
+    print(f"gat: largest shapes fin={fin} H={H} F={F}", flush=True)
+    rng = np.random.default_rng(fin + 7 * H + 13 * F)
+    indptr, indices = random_graph(rng, 200, 1500, self_loops=True, duplicates=True)
+    c = synth(rng, indptr, indices, fin, H, F)
+    fwd, bwd = oracle_all(c)
+    compare(c, run_gat(c), fwd, bwd)
+
+
+def test_many_vertices_few_edges_on_the_blocked_path():
+    """More vertices than one column block holds, almost all (row, block) segments empty,
+    rows without any edge in the first block, whole rows without edges."""
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev, run_gat
+    print("gat: 70000 vertices, sparse", flush=True)
+    rng = np.random.default_rng(4242)
+    n = 70_000
+    src = rng.integers(0, n, size=150_000)
+    dst = rng.integers(0, n // 2, size=150_000)            # the upper half has no in-edges
+    order = np.lexsort((src, dst))
+    src, dst = src[order], dst[order]
+    indptr = np.zeros(n + 1, dtype=np.int32)
+    np.add.at(indptr, dst + 1, 1)
+    indptr = np.cumsum(indptr).astype(np.int32)
+    indices = src.astype(np.int32)
+    c = synth(rng, indptr, indices, 6, 4, 32)
+    fwd, bwd = oracle_all(c)
+    g = pk.Graph(dev(indptr), dev(indices))
+    assert g.blocked(0)[0] == 3
+    res = run_gat(c, graph=g)
+    compare(c, res, fwd, bwd)
+    assert (res["out"][n // 2:] == 0).all()
+    compare(c, run_gat(c, graph=g, stash=False), fwd, bwd)
+    g.close()

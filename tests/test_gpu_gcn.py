@@ -102,3 +102,24 @@ def test_bad_arguments_raise():
                        workspace(pk.gnn_gcn_workspace_bytes(g, 8, 16) - 256))
     assert e.value.status == 3
     g.close()
+
+
+def test_many_vertices_few_edges_on_the_blocked_path():
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev
+    print("gcn: 70000 vertices, sparse", flush=True)
+    rng = np.random.default_rng(4243)
+    n = 70_000
+    src = rng.integers(0, n, size=150_000)
+    dst = rng.integers(0, n // 2, size=150_000)
+    order = np.lexsort((src, dst))
+    src, dst = src[order], dst[order]
+    indptr = np.zeros(n + 1, dtype=np.int32)
+    np.add.at(indptr, dst + 1, 1)
+    indptr = np.cumsum(indptr).astype(np.int32)
+    c = synth(rng, indptr, src.astype(np.int32), 6, 128)
+    g = pk.Graph(dev(indptr), dev(c["indices"]))
+    assert g.blocked(0)[0] == 3
+    res = check(c, graph=g)
+    assert (res["out"][n // 2:] == 0).all()
+    g.close()
