@@ -121,3 +121,27 @@ def test_backward_matches_torch_autograd():
     np.testing.assert_allclose(bwd["gx"], tX.grad.numpy(), rtol=1e-10, atol=1e-12)
     np.testing.assert_allclose(bwd["gtheta"], tT.grad.numpy(), rtol=1e-10, atol=1e-12)
     np.testing.assert_allclose(bwd["gphi"], tP.grad.numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_translating_all_points_moves_the_output_by_the_phi_image_only():
+    """Theta sees differences of features, so a common shift t of every vertex only enters
+    through Phi: out(x + t) = out(x) + t Phi, with the same winners."""
+    rng = np.random.default_rng(41)
+    indptr, indices, X, Theta, Phi = make_case(rng, 30, 150, 5, 6)
+    t = rng.standard_normal(5)
+    f0 = oe.edgeconv_forward(indptr, indices, X, Theta, Phi)
+    f1 = oe.edgeconv_forward(indptr, indices, X + t[None, :], Theta, Phi)
+    has_edges = np.diff(indptr) > 0
+    np.testing.assert_allclose(f1["out"][has_edges], (f0["out"] + (t @ Phi)[None, :])[has_edges], rtol=1e-10, atol=1e-10)
+    assert np.array_equal(f1["argmax"], f0["argmax"])
+
+
+def test_backward_is_linear_in_the_upstream_gradient():
+    rng = np.random.default_rng(42)
+    indptr, indices, X, Theta, Phi = make_case(rng, 25, 100, 4, 5)
+    g1, g2 = rng.standard_normal((25, 5)), rng.standard_normal((25, 5))
+    fwd = oe.edgeconv_forward(indptr, indices, X, Theta, Phi)
+    b = lambda g: oe.edgeconv_backward(indptr, indices, X, Theta, Phi, g, fwd)
+    b1, b2, b12 = b(g1), b(g2), b(0.5 * g1 + 4.0 * g2)
+    for k in ("gx", "gtheta", "gphi"):
+        np.testing.assert_allclose(b12[k], 0.5 * b1[k] + 4.0 * b2[k], rtol=1e-10, atol=1e-10)

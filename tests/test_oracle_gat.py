@@ -212,3 +212,59 @@ def test_slope_one_kills_the_destination_half_gradient():
     s = np.zeros((20, 2))
     np.add.at(s, og.edge_dst(indptr), bwd["dM1"])
     np.testing.assert_allclose(s, 0.0, atol=1e-12)
+
+
+def test_heads_are_independent_and_laid_out_head_major():
+    """Permuting the heads (column blocks of W, rows of a_l and a_r) permutes the output's
+    column blocks and nothing else (App. A.2: heads are concatenated)."""
+    rng = np.random.default_rng(31)
+    indptr, indices = random_graph(rng, 25, 90, self_loops=True, duplicates=True)
+    H, F, fin = 3, 4, 5
+    X = rng.standard_normal((25, fin))
+    W = rng.standard_normal((fin, H * F))
+    a_l, a_r = rng.standard_normal((H, F)), rng.standard_normal((H, F))
+    gout = rng.standard_normal((25, H * F))
+    perm = np.array([2, 0, 1])
+    cols = (perm[:, None] * F + np.arange(F)[None, :]).reshape(-1)
+    f0 = og.gat_forward(indptr, indices, X, W, a_l, a_r, 0.2)
+    f1 = og.gat_forward(indptr, indices, X, W[:, cols], a_l[perm], a_r[perm], 0.2)
+    np.testing.assert_allclose(f1["out"], f0["out"][:, cols], rtol=1e-12, atol=1e-12)
+    b0 = og.gat_backward(indptr, indices, X, W, a_l, a_r, 0.2, gout, f0)
+    b1 = og.gat_backward(indptr, indices, X, W[:, cols], a_l[perm], a_r[perm], 0.2, gout[:, cols], f1)
+    np.testing.assert_allclose(b1["gx"], b0["gx"], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(b1["gw"], b0["gw"][:, cols], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(b1["ga_l"], b0["ga_l"][perm], rtol=1e-10, atol=1e-12)
+
+
+def test_backward_is_linear_in_the_upstream_gradient_and_local():
+    """Every gradient is a linear map of gout; a destination with zero upstream gradient and
+    no out-edges contributes nothing."""
+    rng = np.random.default_rng(32)
+    indptr, indices = random_graph(rng, 30, 120, self_loops=True, duplicates=False)
+    H, F, fin = 2, 4, 6
+    X, W = rng.standard_normal((30, fin)), rng.standard_normal((fin, H * F))
+    a_l, a_r = rng.standard_normal((H, F)), rng.standard_normal((H, F))
+    g1, g2 = rng.standard_normal((30, H * F)), rng.standard_normal((30, H * F))
+    fwd = og.gat_forward(indptr, indices, X, W, a_l, a_r, 0.2)
+    b = lambda g: og.gat_backward(indptr, indices, X, W, a_l, a_r, 0.2, g, fwd)
+    b1, b2, b12 = b(g1), b(g2), b(2.0 * g1 - 3.0 * g2)
+    for k in ("gx", "gw", "ga_l", "ga_r"):
+        np.testing.assert_allclose(b12[k], 2.0 * b1[k] - 3.0 * b2[k], rtol=1e-10, atol=1e-10)
+    z = b(np.zeros_like(g1))
+    for k in ("gx", "gw", "ga_l", "ga_r"):
+        assert np.abs(z[k]).max() == 0.0
+
+
+def test_a_uniform_shift_of_the_scores_changes_nothing():
+    """Softmax is shift-invariant: adding a constant feature direction that raises every
+    destination score by the same amount leaves the attention weights alone."""
+    rng = np.random.default_rng(33)
+    indptr, indices = random_graph(rng, 20, 80, self_loops=True, duplicates=False)
+    F, fin = 4, 3
+    X, W = rng.standard_normal((20, fin)), rng.standard_normal((fin, F))
+    a_l, a_r = rng.standard_normal((1, F)), rng.standard_normal((1, F))
+    f0 = og.gat_forward(indptr, indices, X, W, a_l, a_r, 1.0)            # slope 1: scores are linear
+    # with slope 1 the destination half is constant along a row and cancels in the softmax
+    f1 = og.gat_forward(indptr, indices, X, W, a_l, 5.0 * a_r, 1.0)
+    np.testing.assert_allclose(f1["out"], f0["out"], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(f1["M2"], f0["M2"], rtol=1e-10, atol=1e-12)

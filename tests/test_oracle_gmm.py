@@ -111,3 +111,40 @@ def test_backward_matches_torch_autograd():
     np.testing.assert_allclose(bwd["gw_fc"], tW.grad.numpy(), rtol=1e-10, atol=1e-12)
     np.testing.assert_allclose(bwd["gmu"], tmu.grad.numpy(), rtol=1e-10, atol=1e-12)
     np.testing.assert_allclose(bwd["ginv_sigma"], tis.grad.numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_kernels_are_exchangeable():
+    """Permuting the K kernels (rows of mu / inv_sigma, column blocks of W_fc) leaves the
+    output alone and permutes their gradients (App. A.2: a plain sum over k)."""
+    rng = np.random.default_rng(51)
+    K, fout = 3, 4
+    indptr, indices, X, W, c, mu, inv_sigma = make_case(rng, 30, 140, 5, fout, K)
+    gout = rng.standard_normal((30, fout))
+    perm = np.array([1, 2, 0])
+    cols = (perm[:, None] * fout + np.arange(fout)[None, :]).reshape(-1)
+    f0 = om.gmm_forward(indptr, indices, X, W, c, mu, inv_sigma)
+    f1 = om.gmm_forward(indptr, indices, X, W[:, cols], c, mu[perm], inv_sigma[perm])
+    np.testing.assert_allclose(f1["out"], f0["out"], rtol=1e-12, atol=1e-12)
+    b0 = om.gmm_backward(indptr, indices, X, W, c, mu, inv_sigma, gout, f0)
+    b1 = om.gmm_backward(indptr, indices, X, W[:, cols], c, mu[perm], inv_sigma[perm], gout, f1)
+    np.testing.assert_allclose(b1["gmu"], b0["gmu"][perm], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(b1["ginv_sigma"], b0["ginv_sigma"][perm], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(b1["gw_fc"], b0["gw_fc"][:, cols], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(b1["gx"], b0["gx"], rtol=1e-10, atol=1e-12)
+
+
+def test_far_away_kernels_contribute_nothing_and_scale_is_one_over_k():
+    """A kernel whose mean is far from every pseudo-coordinate has weight exp(-large) = 0;
+    with K identical kernels the 1/K factor makes the layer equal to the single-kernel one."""
+    rng = np.random.default_rng(52)
+    fout = 4
+    indptr, indices, X, W1, c, mu1, is1 = make_case(rng, 25, 100, 5, fout, 1)
+    f1 = om.gmm_forward(indptr, indices, X, W1, c, mu1, is1)
+    # three copies of the same kernel
+    f3 = om.gmm_forward(indptr, indices, X, np.tile(W1, (1, 3)), c, np.tile(mu1, (3, 1)), np.tile(is1, (3, 1)))
+    np.testing.assert_allclose(f3["out"], f1["out"], rtol=1e-12, atol=1e-12)
+    # one real kernel plus one far away: half of the single-kernel output
+    mu2 = np.vstack([mu1, [[1e3, 1e3]]])
+    f2 = om.gmm_forward(indptr, indices, X, np.hstack([W1, rng.standard_normal(W1.shape)]), c, mu2,
+                        np.vstack([is1, [[1.0, 1.0]]]))
+    np.testing.assert_allclose(f2["out"], 0.5 * f1["out"], rtol=1e-12, atol=1e-12)
