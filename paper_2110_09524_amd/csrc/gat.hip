@@ -62,7 +62,7 @@ struct GroupLds {
 // recompute only when computation / memory is O(1); here it is |E|/|V|).
 template <int L, int NV, bool WT>
 __global__ __launch_bounds__(kBlock) void k_gat_fwd(
-    RowRange rr, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
     const int32_t* __restrict__ indices, const float* __restrict__ z, const float* __restrict__ el,
     const float* __restrict__ er, GatDims dm, float* __restrict__ out, float* __restrict__ m_out,
     float* __restrict__ d_out, float* __restrict__ t_out, float* __restrict__ sg_out) {
@@ -78,7 +78,8 @@ __global__ __launch_bounds__(kBlock) void k_gat_fwd(
   const int grp = threadIdx.x / L;  // group inside the block
   int64_t r;
   int gi, ngrp;
-  if (!pick_row<GPB>(rr, grp, r, gi, ngrp)) return;  // whole group (coop: whole workgroup) leaves together
+  RowRange rr;
+  if (!pick_row<GPB>(rl, grp, rr, r, gi, ngrp)) return;  // whole group (coop: whole workgroup) leaves together
   float* g_lds = lds + grp * GroupLds<L, NV>::kFloats;
   int* l_idx = reinterpret_cast<int*>(g_lds);
   float* l_p = g_lds + L;
@@ -261,7 +262,7 @@ __device__ __forceinline__ float head_sum(const float* red, int h, int F) {
 // writes der[v,h], and vstate[v,h] = (er, m, 1/d, D) for the source-side kernel
 template <int L, int NV>
 __global__ __launch_bounds__(kBlock) void k_gat_bwd_dst(
-    RowRange rr, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
     const int32_t* __restrict__ indices, const float* __restrict__ z, const float* __restrict__ el,
     const float* __restrict__ er, const float* __restrict__ m_in, const float* __restrict__ d_in,
     const float* __restrict__ out, const float* __restrict__ gout, GatDims dm,
@@ -277,7 +278,8 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_dst(
   const int grp = threadIdx.x / L;
   int64_t r;
   int gi, ngrp;
-  if (!pick_row<GPB>(rr, grp, r, gi, ngrp)) return;
+  RowRange rr;
+  if (!pick_row<GPB>(rl, grp, rr, r, gi, ngrp)) return;
   float* g_lds = lds + grp * GroupLds<L, NV>::kFloats;
   int* l_idx = reinterpret_cast<int*>(g_lds);
   float* l_p = g_lds + L;
@@ -401,7 +403,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_dst(
 // dz[u] = sum_out alpha_e gout[v] + a_l del[u] + a_r der[u];  writes del[u,h] too
 template <int L, int NV>
 __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
-    RowRange rr, const int32_t* __restrict__ order_t, const int32_t* __restrict__ indptr_t,
+    RowLaunch rl, const int32_t* __restrict__ order_t, const int32_t* __restrict__ indptr_t,
     const int32_t* __restrict__ indices_t, const float* __restrict__ z, const float* __restrict__ el,
     const float4* __restrict__ vstate, const float* __restrict__ der, const float* __restrict__ gout,
     const float* __restrict__ a_l, const float* __restrict__ a_r, GatDims dm,
@@ -417,7 +419,8 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
   const int grp = threadIdx.x / L;
   int64_t r;
   int gi, ngrp;
-  if (!pick_row<GPB>(rr, grp, r, gi, ngrp)) return;
+  RowRange rr;
+  if (!pick_row<GPB>(rl, grp, rr, r, gi, ngrp)) return;
   float* g_lds = lds + grp * GroupLds<L, NV>::kFloats;
   int* l_idx = reinterpret_cast<int*>(g_lds);
   float* l_p = g_lds + L;
@@ -678,15 +681,15 @@ struct FwdLauncher {
     constexpr int GPB = (kWave / L) * (kBlock / kWave);
     ProfScope p("gat_fwd_fused", st);
     const RowSplit sp = split_rows(g, 0, L >> dm.log2Hp, GPB);
-    for (int pass = 0; pass < 2; ++pass) {
-      const RowRange rr = pass == 0 ? sp.hub : sp.rest;
-      const unsigned grid = pass == 0 ? sp.hub_grid : sp.rest_grid;
-      if (grid == 0) continue;
+    // hub rows (one workgroup each) and the rest in one launch
+    const unsigned grid = sp.hub_grid + sp.rest_grid;
+    const RowLaunch rl{sp.hub.end, g->n};
+    if (grid != 0) {
       if (t)
-        k_gat_fwd<L, NV, true><<<grid, kBlock, 0, st>>>(rr, g->order[0], g->indptr, g->indices, z, el, er,
+        k_gat_fwd<L, NV, true><<<grid, kBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, z, el, er,
                                                         dm, out, m, d, t, sg);
       else
-        k_gat_fwd<L, NV, false><<<grid, kBlock, 0, st>>>(rr, g->order[0], g->indptr, g->indices, z, el,
+        k_gat_fwd<L, NV, false><<<grid, kBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, z, el,
                                                          er, dm, out, m, d, nullptr, nullptr);
       GNN_LAUNCH_CHECK();
     }
@@ -821,11 +824,11 @@ struct BwdDstLauncher {
     constexpr int GPB = (kWave / L) * (kBlock / kWave);
     ProfScope p("gat_bwd_dst", st);
     const RowSplit sp = split_rows(g, 0, L >> dm.log2Hp, GPB);
-    for (int pass = 0; pass < 2; ++pass) {
-      const RowRange rr = pass == 0 ? sp.hub : sp.rest;
-      const unsigned grid = pass == 0 ? sp.hub_grid : sp.rest_grid;
-      if (grid == 0) continue;
-      k_gat_bwd_dst<L, NV><<<grid, kBlock, 0, st>>>(rr, g->order[0], g->indptr, g->indices, z, el, er, m, d,
+    // hub rows (one workgroup each) and the rest in one launch
+    const unsigned grid = sp.hub_grid + sp.rest_grid;
+    const RowLaunch rl{sp.hub.end, g->n};
+    if (grid != 0) {
+      k_gat_bwd_dst<L, NV><<<grid, kBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, z, el, er, m, d,
                                                     out, gout, dm, der, vstate);
       GNN_LAUNCH_CHECK();
     }
@@ -841,11 +844,11 @@ struct BwdSrcLauncher {
     constexpr int GPB = (kWave / L) * (kBlock / kWave);
     ProfScope p("gat_bwd_src", st);
     const RowSplit sp = split_rows(g, 1, L >> dm.log2Hp, GPB);
-    for (int pass = 0; pass < 2; ++pass) {
-      const RowRange rr = pass == 0 ? sp.hub : sp.rest;
-      const unsigned grid = pass == 0 ? sp.hub_grid : sp.rest_grid;
-      if (grid == 0) continue;
-      k_gat_bwd_src<L, NV><<<grid, kBlock, 0, st>>>(rr, g->order[1], g->indptr_t, g->indices_t, z, el,
+    // hub rows (one workgroup each) and the rest in one launch
+    const unsigned grid = sp.hub_grid + sp.rest_grid;
+    const RowLaunch rl{sp.hub.end, g->n};
+    if (grid != 0) {
+      k_gat_bwd_src<L, NV><<<grid, kBlock, 0, st>>>(rl, g->order[1], g->indptr_t, g->indices_t, z, el,
                                                     vstate, der, gout, a_l, a_r, dm, dz, del);
       GNN_LAUNCH_CHECK();
     }

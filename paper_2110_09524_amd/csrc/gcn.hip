@@ -34,7 +34,7 @@ __global__ void k_scale_rows(int64_t quads, int q_per_row, const float* __restri
 // ---- single launch: out[row,:] = scale[row] * sum over the row's gathered vertices of feat ----
 template <int L, int NV>
 __global__ __launch_bounds__(kGcnBlock) void k_rowsum(
-    RowRange rr, const int32_t* __restrict__ order, const int32_t* __restrict__ ptr,
+    RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ ptr,
     const int32_t* __restrict__ cols, const float* __restrict__ feat, int F,
     const float* __restrict__ scale, float* __restrict__ out) {
   constexpr int G = kWave / L;
@@ -48,7 +48,8 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum(
   const int grp = threadIdx.x / L;
   int64_t r;
   int gi, ngrp;
-  if (!pick_row<GPB>(rr, grp, r, gi, ngrp)) return;
+  RowRange rr;
+  if (!pick_row<GPB>(rl, grp, rr, r, gi, ngrp)) return;
   int* l_idx = lds + grp * L;
   const int32_t v = order[r];
   const int32_t beg = ptr[v], end = ptr[v + 1];
@@ -229,11 +230,11 @@ struct RowsumLauncher {
     const RowSplit sp = split_rows(g, side, L, GPB);
     const int32_t* ptr = side == 0 ? g->indptr : g->indptr_t;
     const int32_t* cols = side == 0 ? g->indices : g->indices_t;
-    for (int pass = 0; pass < 2; ++pass) {
-      const RowRange rr = pass == 0 ? sp.hub : sp.rest;
-      const unsigned grid = pass == 0 ? sp.hub_grid : sp.rest_grid;
-      if (grid == 0) continue;
-      k_rowsum<L, NV><<<grid, kGcnBlock, 0, st>>>(rr, g->order[side], ptr, cols, feat, F, scale, out);
+    // hub rows (one workgroup each) and the rest in one launch
+    const unsigned grid = sp.hub_grid + sp.rest_grid;
+    const RowLaunch rl{sp.hub.end, g->n};
+    if (grid != 0) {
+      k_rowsum<L, NV><<<grid, kGcnBlock, 0, st>>>(rl, g->order[side], ptr, cols, feat, F, scale, out);
       GNN_LAUNCH_CHECK();
     }
     return GNN_OK;

@@ -47,7 +47,7 @@ constexpr int kGmmU = 2;   // edges whose rows are in flight together in the row
 // ---- a9: fused forward -----------------------------------------------------------------
 template <int L, int NV>
 __global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd(
-    RowRange rr, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
     const int32_t* __restrict__ indices, const float* __restrict__ hk, const float* __restrict__ c,
     const float* __restrict__ mu, const float* __restrict__ inv_sigma, GmmParams pm,
     float* __restrict__ out) {
@@ -63,7 +63,8 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd(
   const int grp = threadIdx.x / L;
   int64_t r;
   int gi, ngrp;
-  if (!pick_row<GPB>(rr, grp, r, gi, ngrp)) return;
+  RowRange rr;
+  if (!pick_row<GPB>(rl, grp, rr, r, gi, ngrp)) return;
   int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
   float* l_w = lds + grp * GS + L;
 
@@ -91,6 +92,7 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd(
       is0[q] = ok ? inv_sigma[2 * (k0 + q)] : 0.f;
       is1[q] = ok ? inv_sigma[2 * (k0 + q) + 1] : 0.f;
     }
+    constexpr int kFold = L >= 32 ? 1 : 32 / L;  // `part` is folded into `acc` every ~32 edges
     int chunk_no = 0;
     for (int32_t c0 = beg + gi * L; c0 < end; c0 += ngrp * L) {
       const bool e_ok = c0 + li < end;
@@ -125,7 +127,7 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd(
               if (k0 + q < K) fma4(part[j], l_w[q * L + t0 + t], rowv[t][q]);
         }
       }
-      if ((++chunk_no & 3) == 0) {
+      if ((++chunk_no % kFold) == 0) {
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
           add4(acc[j], part[j]);
@@ -158,7 +160,7 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd(
 // partial[block][j][4] = this block's share of (gmu_j0, gmu_j1, gis_j0, gis_j1)
 template <int L, int NV>
 __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_dst(
-    RowRange rr, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
     const int32_t* __restrict__ indices, const float* __restrict__ hk, const float* __restrict__ c,
     const float* __restrict__ mu, const float* __restrict__ inv_sigma, const float* __restrict__ gout,
     GmmParams pm, int64_t block_base, float* __restrict__ partial) {
@@ -174,7 +176,8 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_dst(
   const int grp = threadIdx.x / L;
   int64_t r;
   int gi, ngrp;
-  const bool active = pick_row<GPB>(rr, grp, r, gi, ngrp);  // coop: the same for the whole workgroup
+  RowRange rr;
+  const bool active = pick_row<GPB>(rl, grp, rr, r, gi, ngrp);  // coop: the same for the whole workgroup
   int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
   float* l_w = lds + grp * GS + L;
   float* l_wr = l_w + KB * L;
@@ -315,7 +318,7 @@ __global__ void k_gmm_param_split(int K, const float* __restrict__ totals, float
 // ---- a10, source side: dhk[u,j,:] = (1/K) sum over out-edges w_j(e) gout[v,:] ----------
 template <int L, int NV>
 __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_src(
-    RowRange rr, const int32_t* __restrict__ order_t, const int32_t* __restrict__ indptr_t,
+    RowLaunch rl, const int32_t* __restrict__ order_t, const int32_t* __restrict__ indptr_t,
     const int32_t* __restrict__ indices_t, const float* __restrict__ c, const float* __restrict__ mu,
     const float* __restrict__ inv_sigma, const float* __restrict__ gout, GmmParams pm,
     float* __restrict__ dhk) {
@@ -332,7 +335,8 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_src(
   const int grp = threadIdx.x / L;
   int64_t r;
   int gi, ngrp;
-  if (!pick_row<GPB>(rr, grp, r, gi, ngrp)) return;
+  RowRange rr;
+  if (!pick_row<GPB>(rl, grp, rr, r, gi, ngrp)) return;
   int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
   float* l_w = lds + grp * GS + L;
 
@@ -430,11 +434,11 @@ struct GmmFwdLauncher {
     constexpr int GPB = (kWave / L) * (kGmmBlock / kWave);
     ProfScope p("gmm_fwd_fused", st);
     const RowSplit sp = split_rows(g, 0, L, GPB);
-    for (int pass = 0; pass < 2; ++pass) {
-      const RowRange rr = pass == 0 ? sp.hub : sp.rest;
-      const unsigned grid = pass == 0 ? sp.hub_grid : sp.rest_grid;
-      if (grid == 0) continue;
-      k_gmm_fwd<L, NV><<<grid, kGmmBlock, 0, st>>>(rr, g->order[0], g->indptr, g->indices, hk, c, mu, is, pm,
+    // hub rows (one workgroup each) and the rest in one launch
+    const unsigned grid = sp.hub_grid + sp.rest_grid;
+    const RowLaunch rl{sp.hub.end, g->n};
+    if (grid != 0) {
+      k_gmm_fwd<L, NV><<<grid, kGmmBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, hk, c, mu, is, pm,
                                                    out);
       GNN_LAUNCH_CHECK();
     }
@@ -459,11 +463,11 @@ struct GmmBwdDstLauncher {
     ProfScope p("gmm_bwd_dst", st);
     const RowSplit sp = split_rows(g, 0, L, GPB);
     int64_t base = 0;
-    for (int pass = 0; pass < 2; ++pass) {
-      const RowRange rr = pass == 0 ? sp.hub : sp.rest;
-      const unsigned grid = pass == 0 ? sp.hub_grid : sp.rest_grid;
-      if (grid == 0) continue;
-      k_gmm_bwd_dst<L, NV><<<grid, kGmmBlock, 0, st>>>(rr, g->order[0], g->indptr, g->indices, hk, c, mu, is,
+    // hub rows (one workgroup each) and the rest in one launch
+    const unsigned grid = sp.hub_grid + sp.rest_grid;
+    const RowLaunch rl{sp.hub.end, g->n};
+    if (grid != 0) {
+      k_gmm_bwd_dst<L, NV><<<grid, kGmmBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, hk, c, mu, is,
                                                        gout, pm, base, partial);
       GNN_LAUNCH_CHECK();
       base += grid;
@@ -484,11 +488,11 @@ struct GmmBwdSrcLauncher {
     constexpr int GPB = (kWave / L) * (kGmmBlock / kWave);
     ProfScope p("gmm_bwd_src", st);
     const RowSplit sp = split_rows(g, 1, L, GPB);
-    for (int pass = 0; pass < 2; ++pass) {
-      const RowRange rr = pass == 0 ? sp.hub : sp.rest;
-      const unsigned grid = pass == 0 ? sp.hub_grid : sp.rest_grid;
-      if (grid == 0) continue;
-      k_gmm_bwd_src<L, NV><<<grid, kGmmBlock, 0, st>>>(rr, g->order[1], g->indptr_t, g->indices_t, c, mu, is,
+    // hub rows (one workgroup each) and the rest in one launch
+    const unsigned grid = sp.hub_grid + sp.rest_grid;
+    const RowLaunch rl{sp.hub.end, g->n};
+    if (grid != 0) {
+      k_gmm_bwd_src<L, NV><<<grid, kGmmBlock, 0, st>>>(rl, g->order[1], g->indptr_t, g->indices_t, c, mu, is,
                                                        gout, pm, dhk);
       GNN_LAUNCH_CHECK();
     }

@@ -116,6 +116,28 @@ __device__ __forceinline__ bool pick_row(const RowRange& rr, int grp, int64_t& r
   return r < rr.end;
 }
 
+// One launch serves both kinds of rows: its first n_hub workgroups take one hub row each
+// (cooperatively), the others GPB rows of the rest each; the kind is uniform in a workgroup.
+struct RowLaunch {
+  int32_t n_hub, n_rows;
+};
+template <int GPB>
+__device__ __forceinline__ bool pick_row(const RowLaunch& rl, int grp, RowRange& rr, int64_t& r, int& gi,
+                                         int& ngrp) {
+  if (blockIdx.x < (unsigned)rl.n_hub) {
+    rr = RowRange{0, rl.n_hub, 1};
+    r = blockIdx.x;
+    gi = grp;
+    ngrp = GPB;
+  } else {
+    rr = RowRange{rl.n_hub, rl.n_rows, 0};
+    r = (int64_t)rl.n_hub + (int64_t)(blockIdx.x - (unsigned)rl.n_hub) * GPB + grp;
+    gi = 0;
+    ngrp = 1;
+  }
+  return r < rr.end;
+}
+
 // Adds the N per-lane values of groups 1..GPB-1 onto group 0's, in group order.  Every
 // thread of the workgroup must call it; afterwards only group 0 holds the totals.
 // buf: GPB * L * N floats of LDS.
