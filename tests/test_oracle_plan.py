@@ -60,6 +60,38 @@ def test_closed_form_operation_counts():
     assert 1.45 < ratio < 1.55
 
 
+def test_closed_forms_equal_the_printed_ones():
+    """tests/golden/closed_forms.txt holds the polynomials as the paper prints them; the cost
+    model's functions must evaluate to the same numbers."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "closed_forms.txt")
+    forms = {}
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        name, _cite, terms = [t.strip() for t in line.split(";")]
+        forms[name] = [t.strip().split("*") for t in terms.split("+")]
+    assert set(forms) == {"gat_score_ops_original", "gat_score_ops_reorganized", "gat_graph_io_unfused",
+                          "gat_graph_io_fused"}
+
+    def evaluate(terms, env):
+        total = 0
+        for t in terms:
+            prod = int(t[0])
+            for sym in t[1:]:
+                prod *= env[sym]
+            total += prod
+        return total
+
+    for V, E, h, f in ((7, 31, 1, 1), (200, 900, 3, 8), (232965, 114_000_000, 4, 64)):
+        env = dict(V=V, E=E, h=h, f=f)
+        assert cm.gat_score_ops_original(V, E, f) == evaluate(forms["gat_score_ops_original"], env)
+        assert cm.gat_score_ops_reorganized(V, E, f) == evaluate(forms["gat_score_ops_reorganized"], env)
+        assert cm.gat_graph_io_unfused(V, E, h, f) == evaluate(forms["gat_graph_io_unfused"], env)
+        assert cm.gat_graph_io_fused(V, E, h, f) == evaluate(forms["gat_graph_io_fused"], env)
+
+
 def test_generators_shapes_and_degrees():
     ip, ix = graphs.erdos_renyi(2000, 10_000, 1)
     assert ip[-1] == 12_000 and ix.shape == (12_000,)
