@@ -111,6 +111,14 @@ def test_gat_c4_sampled_rows_and_consistency(c4):
         assert_close(k + " (two kernel paths)", res[k], res2[k],
                      reduce_scale=k in ("gw", "ga_l", "ga_r"))
     assert_close("gx (two kernel paths)", res["gx"], res2["gx"], row_scale=True)
+    # the hub block's LDS-table variant adds the same terms in the same order as the plain one
+    pk.gnn_config_set("lds_scalar_table", 0)
+    try:
+        res3 = run_gat(c, graph=g, backward=False)
+    finally:
+        pk.gnn_config_set("lds_scalar_table", 1)
+    for k in ("out", "t", "sg", "m", "d"):
+        assert np.array_equal(res[k], res3[k]), f"{k}: LDS-table and plain variants differ at full size"
     g.close()
 
 
