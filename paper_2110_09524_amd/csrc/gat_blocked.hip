@@ -18,6 +18,8 @@
 // weighted, so the forward pass first computes m and d in a light pass that gathers
 // only the per-head scalars el[u] (Sec. 6: exactly the O(|V|) state that is saved).
 // All per-edge values are still recomputed on the fly; nothing per-edge is stored.
+#include <atomic>
+
 #include "common.h"
 #include "gat_common.h"
 #include "rowgroup.h"
@@ -367,16 +369,15 @@ static size_t staged_lds_bytes(int32_t block_cols) {
 constexpr size_t kStageLdsLimit = 152 * 1024;  // of the 160 KB a CU has
 constexpr int kStageMinEdgesPerRow = 128;       // mean edges per row of a block worth staging
 
+static int query_cu_count() {
+  int dev = 0, v = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+    return v;
+  return 256;
+}
 static int device_cu_count() {
-  static int cus = 0;  // one GPU type per process
-  if (cus == 0) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-      cus = v;
-    else
-      cus = 256;
-  }
+  static const int cus = query_cu_count();  // one GPU type per process; initialised once, thread-safe
   return cus;
 }
 
@@ -398,11 +399,13 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
     stage_ok = queue != nullptr && el_hm && staged_lds_bytes<SL>(g->block_cols) <= kStageLdsLimit &&
                (int)g->h_block_begin[side].size() == g->nblk + 1;
     if (stage_ok) {
-      static bool attr_set = false;  // per instantiation; the call is idempotent
-      if (!attr_set) {
+      // more than 64 KB of dynamic LDS needs the attribute; once per instantiation (the call is
+      // idempotent, so a race between two first callers is harmless)
+      static std::atomic<bool> attr_set{false};
+      if (!attr_set.load(std::memory_order_acquire)) {
         GNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gat_blk<SL, MODE, true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStageLdsLimit));
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
       }
       ProfScope p("gat_blk_queue_reset", st);
       k_zero_i32<<<cdiv(g->nblk * kSlices, 64), 64, 0, st>>>(g->nblk * kSlices, queue);

@@ -27,7 +27,7 @@ constexpr int kGmmBlock = 256;
 constexpr int kMaxK = 8;
 
 struct GmmParams {
-  int K, log2Kp, F;
+  int K, F;
 };
 
 __device__ __forceinline__ float gauss_w(float cu, float cv, float mu0, float mu1, float is0, float is1) {
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_dst(
     RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
     const int32_t* __restrict__ indices, const float* __restrict__ hk, const float* __restrict__ c,
     const float* __restrict__ mu, const float* __restrict__ inv_sigma, const float* __restrict__ gout,
-    GmmParams pm, int64_t block_base, float* __restrict__ partial) {
+    GmmParams pm, float* __restrict__ partial) {
   constexpr int G = kWave / L;
   constexpr int GPB = G * (kGmmBlock / kWave);
   constexpr int KB = kGmmKB, U = kGmmU;
@@ -302,7 +302,7 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_dst(
     const int k = threadIdx.x >> 2, q = threadIdx.x & 3;
     float s = 0.f;
     for (int gi = 0; gi < GPB; ++gi) s += blk[gi][k][q];  // fixed order
-    partial[((block_base + blockIdx.x) * kMaxK + k) * 4 + q] = s;
+    partial[((int64_t)blockIdx.x * kMaxK + k) * 4 + q] = s;
   }
 }
 
@@ -462,19 +462,17 @@ struct GmmBwdDstLauncher {
     constexpr int GPB = (kWave / L) * (kGmmBlock / kWave);
     ProfScope p("gmm_bwd_dst", st);
     const RowSplit sp = split_rows(g, 0, L, GPB);
-    int64_t base = 0;
-    // hub rows (one workgroup each) and the rest in one launch
+    // hub rows (one workgroup each) and the rest in one launch; one partial slot per workgroup
     const unsigned grid = sp.hub_grid + sp.rest_grid;
     const RowLaunch rl{sp.hub.end, g->n};
     if (grid != 0) {
       k_gmm_bwd_dst<L, NV><<<grid, kGmmBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, hk, c, mu, is,
-                                                       gout, pm, base, partial);
+                                                       gout, pm, partial);
       GNN_LAUNCH_CHECK();
-      base += grid;
     }
-    // after the base block slots: one slot for the totals, then the second-level scratch
-    float* totals = partial + base * kMaxK * 4;
-    GNN_TRY(sum_partials_two_level(kMaxK * 4, (int)base, partial, totals + kMaxK * 4, totals, st));
+    // after the block slots: one slot for the totals, then the second-level scratch
+    float* totals = partial + (int64_t)grid * kMaxK * 4;
+    GNN_TRY(sum_partials_two_level(kMaxK * 4, (int)grid, partial, totals + kMaxK * 4, totals, st));
     k_gmm_param_split<<<1, 64, 0, st>>>(pm.K, totals, gmu, gis);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
@@ -575,7 +573,7 @@ extern "C" gnn_status_t gnn_gmm_fwd(const gnn_graph_t* g, int fin, int fout, int
               "gnn_gmm_fwd: hk, out must be 16-byte aligned");
   hipStream_t st = static_cast<hipStream_t>(stream);
   GNN_TRY(gemm_f32(g->n, k * fout, fin, x, fin, false, w_fc, k * fout, false, hk, k * fout, 1, nullptr, st));
-  GmmParams pm{k, ilog2(next_pow2(k)), fout};
+  GmmParams pm{k, fout};
   return gmm_dispatch<GmmFwdLauncher>(pick_group(fout), g, (const float*)hk, c, mu, inv_sigma, pm, out, st);
 }
 
@@ -602,7 +600,7 @@ extern "C" gnn_status_t gnn_gmm_bwd(const gnn_graph_t* g, int fin, int fout, int
   float* part = reinterpret_cast<float*>(base + L.gemm);
   const int64_t n = g->n;
   const int KF = k * fout;
-  GmmParams pm{k, ilog2(next_pow2(k)), fout};
+  GmmParams pm{k, fout};
   const GroupShape gs = pick_group(fout);
   GNN_TRY(gmm_dispatch<GmmBwdDstLauncher>(gs, g, hk, c, mu, inv_sigma, gout, pm, partial, gmu, ginv_sigma, st));
   GNN_TRY(gmm_dispatch<GmmBwdSrcLauncher>(gs, g, c, mu, inv_sigma, gout, pm, dhk, st));
