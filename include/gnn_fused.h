@@ -153,8 +153,9 @@ gnn_status_t gnn_linear_fwd(int64_t n, int fin, int fout, const float* x, const 
  * Sec. 6 (recompute only if computation / memory is O(1); here it is |E|/|V|) they
  * are worth stashing: the backward call then skips one whole pass over the edges.
  * Pass NULL for inference, or to have the backward call recompute them.
- * The workspace is optional in the forward call (NULL is accepted; on graphs that
- * take the column-blocked kernels it holds a head-major copy of el, which is faster).
+ * The workspace is optional in the forward call (NULL is accepted; the column-blocked
+ * kernels keep a head-major copy of el and their running softmax statistics there, so
+ * without it large graphs fall back to the slower single-launch kernels).
  * ------------------------------------------------------------------------- */
 size_t gnn_gat_workspace_bytes(const gnn_graph_t* graph, int fin, int heads, int f);
 

@@ -905,16 +905,16 @@ extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, in
     GNN_LAUNCH_CHECK();
   }
   // a3: fused score -> softmax -> aggregate
-  if (gat_blocked_applies(g, heads, f)) {
-    // optional scratch: a head-major copy of el makes the per-edge scalar gathers denser
-    const GatWs L = gat_ws_layout(g, fin, heads, f);
-    float* el_t = nullptr;
-    int32_t* queue = nullptr;
-    if (ws != nullptr && ws_bytes >= L.total && aligned16(ws)) {
-      el_t = reinterpret_cast<float*>(static_cast<char*>(ws) + L.blk_elt);
-      queue = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.blk_queue);
-    }
-    return gat_blocked_fwd(g, make_dims(heads, f, slope), z, el, er, m, d, out, t, sg, el_t, queue, st);
+  // The column-blocked kernels need scratch (a head-major copy of el, row counters, and the
+  // running softmax statistics, which borrow the dz area the backward call uses later: 128 of
+  // its >= 512 bytes per vertex); without a workspace the single-launch kernels run.
+  const GatWs L = gat_ws_layout(g, fin, heads, f);
+  if (gat_blocked_applies(g, heads, f) && ws != nullptr && ws_bytes >= L.total && aligned16(ws)) {
+    char* base = static_cast<char*>(ws);
+    return gat_blocked_fwd(g, make_dims(heads, f, slope), z, el, er, m, d, out, t, sg,
+                           reinterpret_cast<float*>(base + L.blk_elt),
+                           reinterpret_cast<int32_t*>(base + L.blk_queue),
+                           reinterpret_cast<float4*>(base + L.dz), st);
   }
   return dispatch_group<FwdLauncher>(pick_group(HF), g, (const float*)z, (const float*)el,
                                      (const float*)er, make_dims(heads, f, slope), out, m, d, t, sg, st);

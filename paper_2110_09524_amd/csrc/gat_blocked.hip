@@ -14,9 +14,9 @@
 //   * per-row partial sums live in an [n, heads*f] buffer that every launch after the
 //     first reads, adds to and writes back (launches on one stream run in order, so
 //     there is no race and the summation order is fixed).
-// The edge-softmax needs the row maximum and denominator before any block can be
-// weighted, so the forward pass first computes m and d in a light pass that gathers
-// only the per-head scalars el[u] (Sec. 6: exactly the O(|V|) state that is saved).
+// The edge-softmax of the forward pass runs online across the launches: every (row, slice)
+// carries its running maximum and sums from block to block and the last block normalises,
+// which also yields m and d (Sec. 6: exactly the O(|V|) state that is saved).
 // All per-edge values are still recomputed on the fly; nothing per-edge is stored.
 #include <atomic>
 
@@ -28,53 +28,6 @@ namespace gnn {
 
 constexpr int kBlkThreads = 256;
 constexpr int kSlices = 8;  // one column slice per XCD
-
-// ---- softmax statistics: m = max_e s_e, d = sum_e exp(s_e - m) per (vertex, head) ----
-// one wavefront per destination; lanes = (edge, head) pairs; every lane keeps a running
-// (max, sum) over its own edges, merged across lanes at the end
-__global__ __launch_bounds__(kBlkThreads) void k_gat_softmax_stats(
-    int32_t n_rows, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
-    const int32_t* __restrict__ indices, const float* __restrict__ el, const float* __restrict__ er,
-    GatDims dm, float* __restrict__ m_out, float* __restrict__ d_out) {
-  const int lane = threadIdx.x & 63;
-  const int64_t r = (int64_t)blockIdx.x * (kBlkThreads / kWave) + (threadIdx.x >> 6);
-  if (r >= n_rows) return;
-  const int H = dm.H;
-  const int Hp = 1 << dm.log2Hp;
-  const int epc = kWave >> dm.log2Hp;
-  const int e_loc = lane >> dm.log2Hp;
-  const int h = lane & (Hp - 1);
-  const bool head_ok = h < H;
-  const int32_t v = order[r];
-  const int32_t beg = indptr[v], end = indptr[v + 1];
-  const float er_vh = head_ok ? er[(int64_t)v * H + h] : 0.f;
-  float m_run = -INFINITY, d_run = 0.f;
-  for (int32_t c0 = beg; c0 < end; c0 += epc) {
-    const int32_t e = c0 + e_loc;
-    if (e < end && head_ok) {
-      const int32_t u = indices[e];
-      const float s = leaky(el[(int64_t)u * H + h] + er_vh, dm.slope);
-      const float m_new = fmaxf(m_run, s);
-      d_run = d_run * __expf(m_run - m_new) + __expf(s - m_new);  // exp(-inf) = 0 on the first edge
-      m_run = m_new;
-    }
-  }
-  // merge lanes that share a head: (m1,d1)+(m2,d2) = (M, d1 e^(m1-M) + d2 e^(m2-M))
-  for (int off = Hp; off < kWave; off <<= 1) {
-    const float m2 = __shfl_xor(m_run, off, 64);
-    const float d2 = __shfl_xor(d_run, off, 64);
-    const float M = fmaxf(m_run, m2);
-    const float a = (m_run == -INFINITY) ? 0.f : d_run * __expf(m_run - M);
-    const float b = (m2 == -INFINITY) ? 0.f : d2 * __expf(m2 - M);
-    d_run = a + b;
-    m_run = M;
-  }
-  if (e_loc == 0 && head_ok) {
-    const bool empty = beg == end;
-    m_out[(int64_t)v * H + h] = empty ? 0.f : m_run;
-    d_out[(int64_t)v * H + h] = empty ? 1.f : d_run;
-  }
-}
 
 // ---- one column block of a weighted row aggregation ---------------------------------
 // MODE 0: forward        acc[v]  += sum_e alpha_e           z[u]      (acc = out)
@@ -116,13 +69,20 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
     GatDims dm, int sph, int first, int narrow, int el_hm /* el is head-major [H][n] */,
     float* __restrict__ acc_buf, float* __restrict__ acc2_buf, float* __restrict__ scal_buf,
     int32_t* __restrict__ queue /* STAGE: one row counter per slice */, int32_t cols_here,
-    int32_t quads_per_grab) {
+    int32_t quads_per_grab, int last /* forward modes: this is the last block */,
+    float4* __restrict__ state /* forward modes: running (max, sum, sum2) per (row, slice) */,
+    float* __restrict__ m_out, float* __restrict__ d_out) {
   constexpr int THREADS = STAGE ? kStageThreads : kBlkThreads;
   constexpr int G = kWave / SL;
   constexpr int GPB = THREADS / SL;
   constexpr int R = kRowsPerGroup;
   constexpr int U = SL < 8 ? 4 : 8;   // gathered rows in flight per lane
   constexpr bool DUAL = MODE == 2 || MODE == 3;  // two accumulators per lane
+  // The forward modes run the edge-softmax online across the block launches: every (row, slice)
+  // carries its running maximum and sums from launch to launch, the running sums are rescaled
+  // when the maximum grows, and the last block divides by the denominator.  No separate pass
+  // over the edges is needed for the softmax statistics.
+  constexpr bool ONLINE = MODE == 0 || MODE == 3;
   constexpr int GS = 3 * SL + 4 * R;  // LDS floats per group: idx | p | p2 | row, beg, end, pad
   static_assert(SL >= R, "one lane per pipelined row loads its metadata");
   static_assert(!STAGE || MODE != 2, "the source side needs 16 bytes per gathered vertex");
@@ -177,7 +137,7 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
       if (r < n_rows) {
         row = order[r];
         seg = bseg_b[r];
-        if (!first && seg.x == seg.y) row = -1;  // nothing to add to this row in this block
+        if (!first && seg.x == seg.y && !(ONLINE && last)) row = -1;  // nothing to add to this row in this block
       }
       l_row[li] = row;
       l_beg[li] = seg.x;
@@ -199,6 +159,14 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
       const int64_t rh = (int64_t)s.row * H + h;
       if (MODE == 2) {
         s.r_a = el[rh];  // row is a source: its el
+      } else if (ONLINE) {
+        s.r_a = er[rh];  // row is a destination; running max, denominator, second sum so far
+        s.r_m = -INFINITY;
+        s.r_d = 0.f;
+        if (!first) {
+          const float4 stt = state[(int64_t)s.row * kSlices + slice];
+          s.r_m = stt.x; s.r_d = stt.y; s.scal = stt.z;
+        }
       } else {
         s.r_a = er[rh];  // row is a destination: its er, max, denominator
         s.r_m = m_in[rh];
@@ -207,7 +175,7 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
       if (!first) {
         s.acc = ld4_stream(acc_buf + (int64_t)s.row * HF + col);
         if (DUAL) s.acc2 = ld4_stream(acc2_buf + (int64_t)s.row * HF + col);
-        if (MODE != 0 && leader && li == 0) s.scal = scal_buf[rh];
+        if (!ONLINE && MODE != 0 && leader && li == 0) s.scal = scal_buf[rh];
       }
     };
 
@@ -222,9 +190,13 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
       if (k + 1 < R) fetch(k + 1, nxt);
       if (cur.row >= 0) {
         const int32_t end = cur.end;
-        const float r_a = cur.r_a, r_m = cur.r_m, r_invd = 1.f / cur.r_d;
+        const float r_a = cur.r_a, r_m = cur.r_m, r_invd = ONLINE ? 0.f : 1.f / cur.r_d;
         float4 acc = cur.acc, acc2 = cur.acc2;
         float s_run = 0.f;
+        // online state: the running maximum is uniform in the group, the sums are per lane
+        // (lane 0 carries what earlier blocks left) and are added across lanes at the end
+        float m_run = cur.r_m;
+        float d_lane = li == 0 ? cur.r_d : 0.f, s2_lane = li == 0 ? cur.scal : 0.f;
         int32_t c_next = cur.c_first;
         for (int32_t c0 = cur.beg; c0 < end; c0 += SL) {
           const bool e_ok = c0 + li < end;
@@ -243,23 +215,24 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
           }
           wave_lds_fence();
           float4 part = make_float4(0.f, 0.f, 0.f, 0.f), part2 = part;
-  #pragma unroll
+          float sc = 1.f;  // ONLINE: factor that brings the running sums to this chunk's maximum
+#pragma unroll
           for (int t0 = 0; t0 < SL; t0 += U) {
             // the group's U gathered vertices in one go (broadcast LDS reads), then U row loads
             int idv[U];
-  #pragma unroll
+#pragma unroll
             for (int q = 0; q < U / 4; ++q) {
               const int4 i4 = *reinterpret_cast<const int4*>(l_idx + t0 + 4 * q);
               idv[4 * q] = i4.x; idv[4 * q + 1] = i4.y; idv[4 * q + 2] = i4.z; idv[4 * q + 3] = i4.w;
             }
             float4 rowv[U];
             if (narrow) {
-  #pragma unroll
+#pragma unroll
               for (int t = 0; t < U; ++t)
                 rowv[t] = *reinterpret_cast<const float4*>(
                     feat_bytes + (__umul24((uint32_t)idv[t], row_bytes) + col_bytes));
             } else {
-  #pragma unroll
+#pragma unroll
               for (int t = 0; t < U; ++t) rowv[t] = ld4(feat + (int64_t)idv[t] * HF + col);
             }
             if (t0 == 0) {
@@ -270,25 +243,30 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
                   p = __expf(leaky(raw, dm.slope) - vs.y) * vs.z;
                   p2 = raw > 0.f ? p : dm.slope * p;
                   s_run = fmaf(p2, vs.w, s_run);
-                } else {
+                } else if (!ONLINE) {
                   const float raw = e_a + r_a;
                   p = __expf(leaky(raw, dm.slope) - r_m) * r_invd;
-                  if (MODE == 1) {
-                    p = raw > 0.f ? p : dm.slope * p;
-                    s_run += p;
-                  }
-                  if (MODE == 3) {
-                    p2 = raw > 0.f ? p : dm.slope * p;
-                    s_run += p2;
-                  }
+                  p = raw > 0.f ? p : dm.slope * p;  // MODE 1
+                  s_run += p;
                 }
+              }
+              if (ONLINE) {
+                const float raw = e_a + r_a;
+                const float sc_e = e_ok ? leaky(raw, dm.slope) : -INFINITY;
+                const float m_new = fmaxf(m_run, group_max_from<SL>(sc_e, 1));  // finite: lane 0 of a chunk is valid
+                sc = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
+                p = e_ok ? __expf(sc_e - m_new) : 0.f;
+                p2 = raw > 0.f ? p : dm.slope * p;
+                d_lane = fmaf(d_lane, sc, p);
+                s2_lane = fmaf(s2_lane, sc, p2);
+                m_run = m_new;
               }
               l_p[li] = p;
               if (DUAL) l_p2[li] = p2;
               wave_lds_fence();
             }
             float pv[U], pv2[U];
-  #pragma unroll
+#pragma unroll
             for (int q = 0; q < U / 4; ++q) {
               const float4 p4 = *reinterpret_cast<const float4*>(l_p + t0 + 4 * q);
               pv[4 * q] = p4.x; pv[4 * q + 1] = p4.y; pv[4 * q + 2] = p4.z; pv[4 * q + 3] = p4.w;
@@ -297,19 +275,42 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
                 pv2[4 * q] = q4.x; pv2[4 * q + 1] = q4.y; pv2[4 * q + 2] = q4.z; pv2[4 * q + 3] = q4.w;
               }
             }
-  #pragma unroll
+#pragma unroll
             for (int t = 0; t < U; ++t) {
               fma4(part, pv[t], rowv[t]);
               if (DUAL) fma4(part2, pv2[t], rowv[t]);
             }
           }
-          add4(acc, part);
-          if (DUAL) add4(acc2, part2);
+          if (ONLINE) {
+            fold4(acc, sc, part);
+            if (DUAL) fold4(acc2, sc, part2);
+          } else {
+            add4(acc, part);
+            if (DUAL) add4(acc2, part2);
+          }
           wave_lds_fence();
+        }
+        if (ONLINE) {
+          const float d_tot = group_sum_from<SL>(d_lane, 1);
+          const float s2_tot = MODE == 3 ? group_sum_from<SL>(s2_lane, 1) : 0.f;
+          if (last) {
+            // the row is complete: normalise (a row without in-edges keeps out = 0, m = 0, d = 1)
+            const float inv = d_tot > 0.f ? 1.f / d_tot : 0.f;
+            acc = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+            if (DUAL) acc2 = make_float4(acc2.x * inv, acc2.y * inv, acc2.z * inv, acc2.w * inv);
+            if (leader && li == 0) {
+              const int64_t rh = (int64_t)cur.row * H + h;
+              m_out[rh] = d_tot > 0.f ? m_run : 0.f;
+              d_out[rh] = d_tot > 0.f ? d_tot : 1.f;
+              if (MODE == 3) scal_buf[rh] = s2_tot * inv;
+            }
+          } else if (li == 0) {
+            state[(int64_t)cur.row * kSlices + slice] = make_float4(m_run, d_tot, s2_tot, 0.f);
+          }
         }
         st4_stream(acc_buf + (int64_t)cur.row * HF + col, acc);
         if (DUAL) st4_stream(acc2_buf + (int64_t)cur.row * HF + col, acc2);
-        if (MODE != 0 && leader) {
+        if (!ONLINE && MODE != 0 && leader) {
           const float tot = group_sum_from<SL>(s_run, 1);
           if (li == 0) scal_buf[(int64_t)cur.row * H + h] = cur.scal + tot;
         }
@@ -386,7 +387,7 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
                                   int el_hm, const float* feat,
                                   const float* el, const float* er, const float* m, const float* d,
                                   const float4* vstate, float* acc, float* acc2, float* scal,
-                                  int32_t* queue, hipStream_t st) {
+                                  int32_t* queue, float4* state, float* m_out, float* d_out, hipStream_t st) {
   const int sph = kSlices / dm.H;
   // 32-bit byte offsets (and 24-bit multiplies) reach every gathered row
   const int narrow = (int64_t)g->n * dm.HF * 4 < ((int64_t)1 << 32) && g->n < (1 << 24);
@@ -430,7 +431,8 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
         ProfScope p(name, st);  // one timed bracket per launch
         k_gat_blk<SL, MODE, true><<<pgrid, kStageThreads, staged_lds_bytes<SL>(g->block_cols), st>>>(
             g->n, g->order[side], bseg_b, g->bcol[side], feat, el, er, m, d, vstate, col_begin, dm, sph,
-            b == 0, narrow, el_hm, acc, acc2, scal, queue + b * kSlices, cols_here, 1);
+            b == 0, narrow, el_hm, acc, acc2, scal, queue + b * kSlices, cols_here, 1, b == g->nblk - 1, state,
+            m_out, d_out);
         GNN_LAUNCH_CHECK();
       }
     }
@@ -438,7 +440,7 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
       ProfScope p(name, st);  // one timed bracket per launch
       k_gat_blk<SL, MODE, false><<<grid, kBlkThreads, lds, st>>>(
           g->n, g->order[side], bseg_b, g->bcol[side], feat, el, er, m, d, vstate, col_begin, dm, sph,
-          b == 0, narrow, el_hm, acc, acc2, scal, nullptr, 0, 1);
+          b == 0, narrow, el_hm, acc, acc2, scal, nullptr, 0, 1, b == g->nblk - 1, state, m_out, d_out);
       GNN_LAUNCH_CHECK();
     }
   }
@@ -449,12 +451,13 @@ template <int MODE>
 static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name, GatDims dm,
                                int el_hm, const float* feat, const float* el, const float* er, const float* m,
                                const float* d, const float4* vstate, float* acc, float* acc2,
-                               float* scal, int32_t* queue, hipStream_t st) {
+                               float* scal, int32_t* queue, float4* state, float* m_out, float* d_out,
+                               hipStream_t st) {
   switch (dm.HF / (4 * kSlices)) {
-    case 4: return launch_blocks<4, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, st);
-    case 8: return launch_blocks<8, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, st);
-    case 16: return launch_blocks<16, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, st);
-    case 32: return launch_blocks<32, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, st);
+    case 4: return launch_blocks<4, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
+    case 8: return launch_blocks<8, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
+    case 16: return launch_blocks<16, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
+    case 32: return launch_blocks<32, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
   }
   set_error("gat blocked: unsupported slice width");
   return GNN_ERR_UNSUPPORTED;
@@ -462,20 +465,16 @@ static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name,
 
 gnn_status_t gat_blocked_fwd(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                              const float* er, float* m, float* d, float* out, float* t, float* sg,
-                             float* el_t, int32_t* queue, hipStream_t st) {
+                             float* el_t, int32_t* queue, float4* state, hipStream_t st) {
   if (el_t) GNN_TRY(head_major(g, dm.H, el, el_t, st));
   if (!config_get(kCfgLdsScalarTable)) queue = nullptr;
   const float* el_use = el_t ? el_t : el;
   const int hm = el_t != nullptr;
-  {
-    ProfScope p("gat_softmax_stats", st);
-    k_gat_softmax_stats<<<(unsigned)cdiv(g->n, kBlkThreads / kWave), kBlkThreads, 0, st>>>(
-        g->n, g->order[0], g->indptr, g->indices, el, er, dm, m, d);
-    GNN_LAUNCH_CHECK();
-  }
-  if (t) return run_blocks<3>(g, 0, "gat_fwd_fused", dm, hm, z, el_use, er, m, d, nullptr, out, t, sg, queue, st);
-  return run_blocks<0>(g, 0, "gat_fwd_fused", dm, hm, z, el_use, er, m, d, nullptr, out, nullptr, nullptr, queue,
-                       st);
+  if (t)
+    return run_blocks<3>(g, 0, "gat_fwd_fused", dm, hm, z, el_use, er, nullptr, nullptr, nullptr, out, t, sg,
+                         queue, state, m, d, st);
+  return run_blocks<0>(g, 0, "gat_fwd_fused", dm, hm, z, el_use, er, nullptr, nullptr, nullptr, out, nullptr,
+                       nullptr, queue, state, m, d, st);
 }
 
 gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
@@ -485,7 +484,7 @@ gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* 
   if (el_t) GNN_TRY(head_major(g, dm.H, el, el_t, st));
   if (!config_get(kCfgLdsScalarTable)) queue = nullptr;
   GNN_TRY(run_blocks<1>(g, 0, "gat_bwd_dst", dm, el_t != nullptr, z, el_t ? el_t : el, er, m, d, nullptr,
-                        t_buf, nullptr, sg_buf, queue, st));
+                        t_buf, nullptr, sg_buf, queue, nullptr, nullptr, nullptr, st));
   return gat_dst_finish(g, dm, gout, t_buf, out, sg_buf, er, m, d, 1, der, vstate, st);
 }
 
@@ -494,7 +493,7 @@ gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* 
                                  const float* a_l, const float* a_r, float* dz, float* del,
                                  float* a2_buf, float* sd_buf, hipStream_t st) {
   GNN_TRY(run_blocks<2>(g, 1, "gat_bwd_src", dm, 0, gout, el, nullptr, nullptr, nullptr, vstate, dz,
-                        a2_buf, sd_buf, nullptr, st));
+                        a2_buf, sd_buf, nullptr, nullptr, nullptr, nullptr, st));
   return gat_src_finish(g, dm, z, a2_buf, sd_buf, der, a_l, a_r, dz, del, st);
 }
 

@@ -30,11 +30,13 @@ __device__ __forceinline__ float leaky(float x, float slope) { return x > 0.f ? 
 // slice inside one head.
 bool gat_blocked_applies(const gnn_graph_t* g, int heads, int f);
 size_t gat_blocked_ws_bytes(const gnn_graph_t* g, int heads, int f);  // extra workspace (bwd)
-// t, sg: optional stash of the destination-side backward sums (both or neither)
+// t, sg: optional stash of the destination-side backward sums (both or neither);
+// state: n * 8 float4 of scratch for the running softmax statistics (required)
 gnn_status_t gat_blocked_fwd(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                              const float* er, float* m, float* d, float* out, float* t, float* sg,
                              float* el_t /* [H][n] scratch or null */,
-                             int32_t* queue /* nblk * 8 row counters or null */, hipStream_t st);
+                             int32_t* queue /* nblk * 8 row counters or null */, float4* state,
+                             hipStream_t st);
 // vertex-side closing steps shared by both paths (gat.hip)
 gnn_status_t gat_dst_finish(const gnn_graph_t* g, GatDims dm, const float* gout, const float* t,
                             const float* out, const float* sg, const float* er, const float* m,
