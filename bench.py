@@ -201,6 +201,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--hip-graph", action="store_true",
                     help="record one step into a HIP graph and time its replays (launch-bound small workloads)")
+    ap.add_argument("--gcn-mapping", choices=("vertex", "edge", "tuned"), default="vertex",
+                    help="GCN workloads: thread mapping of the aggregation; 'tuned' times both on the graph "
+                         "first (gnn_gcn_tune) and uses the faster one per side")
     ap.add_argument("--compare-unfused", action="store_true",
                     help="also time the one-operator-per-kernel comparator (GAT with heads*f = 256: forward and "
                          "backward graph operators; EdgeConv and GMM: forward)")
@@ -305,7 +308,12 @@ def main():
         unique, gather, flops = gcn_models(n, e, fin, F)
         metric = "fused GCN layer fwd+bwd edges/sec"
         cfg = {"in_feat": fin, "out_feat": F, "edge_weight": "1/sqrt(outdeg(u) indeg(v))",
-               "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded"}
+               "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded", "mapping": args.gcn_mapping}
+        pk.gnn_config_set("gcn_mapping", {"vertex": 0, "edge": 1, "tuned": 2}[args.gcn_mapping])
+        if args.gcn_mapping == "tuned":
+            t = pk.gnn_gcn_tune(g, F, ws)
+            cfg["tune_ms"] = {"in_vertex": round(t[0], 4), "in_edge": round(t[1], 4),
+                              "out_vertex": round(t[2], 4), "out_edge": round(t[3], 4)}
         gemm_flops = 2.0 * n * fin * F
     else:
         raise SystemExit(f"unknown workload kind {kind}")

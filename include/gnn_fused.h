@@ -118,6 +118,9 @@ gnn_status_t gnn_graph_get_blocked(const gnn_graph_t* graph, int side, int32_t* 
  *                           keep a block's per-vertex score table in LDS (one persistent
  *                           1024-thread workgroup per CU drawing rows from a counter);
  *                           0: every edge gathers its scalar from L2
+ *   "gcn_mapping"           thread mapping of the GCN aggregation: 0 vertex-balanced,
+ *                           1 edge-balanced, 2 (default) what gnn_gcn_tune measured as
+ *                           faster on the graph (vertex-balanced if it never ran)
  * Errors: INVALID_ARG for an unknown key or a value out of range. */
 gnn_status_t gnn_config_set(const char* key, int64_t value);
 
@@ -256,6 +259,23 @@ gnn_status_t gnn_gcn_fwd(const gnn_graph_t* graph, int fin, int fout, const floa
 gnn_status_t gnn_gcn_bwd(const gnn_graph_t* graph, int fin, int fout, const float* x, const float* w,
                          const float* c_src, const float* c_dst, const float* gout /*[n,fout]*/,
                          float* gx /*nullable*/, float* gw, void* ws, size_t ws_bytes, void* stream);
+
+/* Profile-driven choice of the thread mapping (Sec. 5: the fused Gather runs either
+ * vertex-balanced, one thread group per row, or edge-balanced, one group per fixed run of
+ * edges with atomic adds where a row spans several runs; the faster one is picked by
+ * profiling).  Times both mappings of the aggregation at width fout on this graph, for the
+ * in-edge side (forward) and the out-edge side (backward), and records the faster one per
+ * side in the graph handle; gnn_gcn_fwd / gnn_gcn_bwd use it while the configuration key
+ * "gcn_mapping" is 2 (the default; 0 forces vertex-balanced, 1 edge-balanced).  The
+ * edge-balanced mapping sums the pieces of a row longer than 64 edges in arrival order:
+ * results agree to rounding but are not bit-reproducible from run to run.
+ * ws: device scratch of gnn_gcn_workspace_bytes(graph, 1, fout) bytes (contents destroyed).
+ * ms_out (host, nullable) receives 4 floats: milliseconds per aggregation for
+ * {in-edge side vertex-balanced, edge-balanced, out-edge side vertex-balanced, edge-balanced}.
+ * Unlike the layer calls this one waits for the stream (a set-up call, like
+ * gnn_graph_create).  Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
+gnn_status_t gnn_gcn_tune(gnn_graph_t* graph, int fout, void* ws, size_t ws_bytes, void* stream,
+                          float* ms_out /*host [4], nullable*/);
 
 /* ------------------------------------------------------------------------- *
  * Per-kernel timing (measurement aid, Sec. 7 metrics).  While enabled, every

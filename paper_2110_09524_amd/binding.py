@@ -24,7 +24,7 @@ EXPORTS = [
     "gnn_graph_get_buckets", "gnn_graph_get_blocked", "gnn_config_set", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
     "gnn_gat_bwd", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
     "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd",
-    "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_prof_enable",
+    "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_gcn_tune", "gnn_prof_enable",
     "gnn_prof_collect", "gnn_prof_reset", "gnn_prof_count", "gnn_prof_get",
 ]
 
@@ -67,6 +67,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_gcn_workspace_bytes.argtypes = [vp, i32, i32]
     lib.gnn_gcn_fwd.argtypes = [vp, i32, i32] + [vp] * 6 + [vp]
     lib.gnn_gcn_bwd.argtypes = [vp, i32, i32] + [vp] * 7 + [vp, sz, vp]
+    lib.gnn_gcn_tune.argtypes = [vp, i32, vp, sz, vp, C.POINTER(C.c_float)]
     lib.gnn_prof_enable.argtypes = [i32]
     lib.gnn_prof_collect.argtypes = []
     lib.gnn_prof_reset.argtypes = []
@@ -243,6 +244,14 @@ def gnn_gcn_bwd(g: Graph, fin, fout, x, w, c_src, c_dst, gout, gx, gw, ws, strea
     wp, wb = _ws_args(ws)
     _check(lib().gnn_gcn_bwd(g.handle, fin, fout, _f(x), _f(w), _f(c_src), _f(c_dst), _f(gout), _f(gx),
                              _f(gw), wp, wb, _stream(stream)))
+
+
+def gnn_gcn_tune(g: Graph, fout, ws, stream=None):
+    """Returns the four measured times (ms): in-edge side vertex-/edge-balanced, out-edge side likewise."""
+    wp, wb = _ws_args(ws)
+    ms = (C.c_float * 4)()
+    _check(lib().gnn_gcn_tune(g.handle, fout, wp, wb, _stream(stream), ms))
+    return [float(v) for v in ms]
 
 
 def gnn_gmm_workspace_bytes(g: Graph, fin, fout, k) -> int:

@@ -12,6 +12,12 @@
 // Large graphs use the same column-blocked, XCD-sliced traversal as the GAT kernels: 8
 // column slices (workgroup id mod 8, one per XCD), blocks of `block_cols` gathered vertices,
 // one launch per block, running sums read-add-written between launches.
+//
+// Two thread mappings of the single-launch sum (Sec. 5, the vertex-balanced and the
+// edge-balanced mapping of a fused Gather): k_rowsum gives a group one row, k_rowsum_eb gives
+// a group a fixed run of consecutive edges and joins the pieces of a row that spans several
+// runs with atomic adds.  gnn_gcn_tune times both on a graph and the layer calls then use the
+// faster one per side (the profile-driven choice of the mapping).
 #include "common.h"
 #include "rowgroup.h"
 
@@ -103,6 +109,102 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum(
   for (int j = 0; j < NV; ++j)
     if (slot_ok[j])
       st4(out + (int64_t)v * F + 4 * (li + j * L), make_float4(s * acc[j].x, s * acc[j].y, s * acc[j].z, s * acc[j].w));
+}
+
+// ---- edge-balanced mapping of the same sum ------------------------------------------------
+// A group owns kEbEdges consecutive positions of the edge array, whatever rows they belong to
+// (every group does the same amount of gathering, however skewed the degrees are).  It finds
+// the row of its first edge by bisection of ptr, then walks row by row.  A row that lies
+// entirely inside the run is stored; a row that continues into other runs is added atomically
+// onto an output that a fill kernel zeroed before (rows without edges stay zero).  Two pieces
+// add up the same in either order; rows of more than two pieces (degree > kEbEdges) depend on
+// the arrival order in the last bits.
+constexpr int kEbEdges = 64;
+
+__global__ void k_zero_f4(int64_t quads, float* __restrict__ p) {
+  const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i < quads) st4(p + 4 * i, make_float4(0.f, 0.f, 0.f, 0.f));
+}
+
+template <int L, int NV>
+__global__ __launch_bounds__(kGcnBlock) void k_rowsum_eb(
+    int32_t n, int32_t nnz, const int32_t* __restrict__ ptr, const int32_t* __restrict__ cols,
+    const float* __restrict__ feat, int F, const float* __restrict__ scale, float* __restrict__ out) {
+  constexpr int GPB = kGcnBlock / L;
+  constexpr int U = 4;
+  constexpr int GS = kEbEdges + U;  // the run's gathered vertices, then U entries of padding
+  __shared__ int lds[GPB * GS];
+  const int lane = threadIdx.x & 63;
+  const int li = lane & (L - 1);
+  const int grp = threadIdx.x / L;
+  const int64_t run = (int64_t)blockIdx.x * GPB + grp;
+  if (run * kEbEdges >= nnz) return;
+  const int32_t e0 = (int32_t)(run * kEbEdges);
+  const int32_t e1 = min(e0 + kEbEdges, nnz);
+  int* l_idx = lds + grp * GS;
+  for (int i = li; i < GS; i += L) l_idx[i] = e0 + i < e1 ? cols[e0 + i] : 0;  // padding gathers row 0, weight 0
+
+  // row of the first edge: ptr[lo] <= e0 < ptr[hi] throughout (ptr[0] = 0, ptr[n] = nnz)
+  int32_t lo = 0, hi = n;
+  while (hi - lo > 1) {
+    const int32_t mid = (lo + hi) >> 1;
+    if (ptr[mid] <= e0) lo = mid; else hi = mid;
+  }
+  int32_t v = lo, row_beg = ptr[v], row_end = ptr[v + 1];
+  wave_lds_fence();
+
+  bool slot_ok[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) slot_ok[j] = 4 * (li + j * L) < F;
+
+  int32_t e = e0;
+  while (e < e1) {
+    const int32_t seg_end = min(row_end, e1);
+    float4 acc[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int32_t t0 = e; t0 < seg_end; t0 += U) {
+      int uu[U];
+#pragma unroll
+      for (int t = 0; t < U; ++t) {
+        uu[t] = l_idx[t0 - e0 + t];
+        if (L == 64) uu[t] = __builtin_amdgcn_readfirstlane(uu[t]);
+      }
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        if (!slot_ok[j]) continue;
+        float4 rowv[U];
+#pragma unroll
+        for (int t = 0; t < U; ++t) rowv[t] = ld4(feat + (int64_t)uu[t] * F + 4 * (li + j * L));
+#pragma unroll
+        for (int t = 0; t < U; ++t) fma4(acc[j], t0 + t < seg_end ? 1.f : 0.f, rowv[t]);
+      }
+    }
+    const float s = scale[v];
+    const bool whole = row_beg >= e0 && row_end <= e1;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      if (!slot_ok[j]) continue;
+      float* o = out + (int64_t)v * F + 4 * (li + j * L);
+      const float4 r = make_float4(s * acc[j].x, s * acc[j].y, s * acc[j].z, s * acc[j].w);
+      if (whole) {
+        st4(o, r);
+      } else {
+        unsafeAtomicAdd(o, r.x);
+        unsafeAtomicAdd(o + 1, r.y);
+        unsafeAtomicAdd(o + 2, r.z);
+        unsafeAtomicAdd(o + 3, r.w);
+      }
+    }
+    e = seg_end;
+    if (e < e1) {  // the next row that has edges (it starts at e)
+      do {
+        ++v;
+        row_beg = row_end;
+        row_end = ptr[v + 1];
+      } while (row_end == row_beg);
+    }
+  }
 }
 
 // ---- one column block of the same sum (running sums in acc_buf) -----------------------
@@ -241,9 +343,58 @@ struct RowsumLauncher {
   }
 };
 
-// out[row,:] = scale[row] * sum of feat over the row's neighbours on `side` (0: in-edges, 1: out-edges)
-static gnn_status_t gcn_aggregate(const gnn_graph_t* g, int side, const char* name, const float* feat, int F,
-                                  const float* scale, float* out, hipStream_t st) {
+template <int L, int NV>
+struct RowsumEbLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, int side, const char* name, const float* feat, int F,
+                          const float* scale, float* out, hipStream_t st) {
+    constexpr int GPB = kGcnBlock / L;
+    ProfScope p(name, st);
+    const int64_t quads = (int64_t)g->n * (F / 4);
+    k_zero_f4<<<(unsigned)cdiv(quads, 256), 256, 0, st>>>(quads, out);
+    GNN_LAUNCH_CHECK();
+    const int64_t runs = cdiv(g->nnz, kEbEdges);
+    if (runs != 0) {
+      k_rowsum_eb<L, NV><<<(unsigned)cdiv(runs, GPB), kGcnBlock, 0, st>>>(
+          g->n, (int32_t)g->nnz, side == 0 ? g->indptr : g->indptr_t, side == 0 ? g->indices : g->indices_t,
+          feat, F, scale, out);
+      GNN_LAUNCH_CHECK();
+    }
+    return GNN_OK;
+  }
+};
+
+template <template <int, int> class Launcher>
+static gnn_status_t dispatch_rowsum(const gnn_graph_t* g, int side, const char* name, const float* feat, int F,
+                                    const float* scale, float* out, hipStream_t st) {
+  const GroupShape gs = pick_group(F);
+  switch (gs.L) {
+    case 4: return Launcher<4, 1>::run(g, side, name, feat, F, scale, out, st);
+    case 8: return Launcher<8, 1>::run(g, side, name, feat, F, scale, out, st);
+    case 16: return Launcher<16, 1>::run(g, side, name, feat, F, scale, out, st);
+    case 32: return Launcher<32, 1>::run(g, side, name, feat, F, scale, out, st);
+    case 64:
+      switch (gs.NV) {
+        case 1: return Launcher<64, 1>::run(g, side, name, feat, F, scale, out, st);
+        case 2: return Launcher<64, 2>::run(g, side, name, feat, F, scale, out, st);
+        case 3: return Launcher<64, 3>::run(g, side, name, feat, F, scale, out, st);
+        case 4: return Launcher<64, 4>::run(g, side, name, feat, F, scale, out, st);
+      }
+  }
+  set_error("unsupported row-group shape L=%d NV=%d", gs.L, gs.NV);
+  return GNN_ERR_UNSUPPORTED;
+}
+
+// mapping: 0 vertex-balanced, 1 edge-balanced, 2 what gnn_gcn_tune found faster on this graph
+// (vertex-balanced on a graph that was never tuned)
+static bool use_edge_balanced(const gnn_graph_t* g, int side) {
+  const int64_t mode = config_get(kCfgGcnMapping);
+  if (mode == 1) return true;
+  return mode == 2 && g->gcn_edge_balanced[side] == 1;
+}
+
+// vertex-balanced: column-blocked launches on large graphs, else one launch
+static gnn_status_t gcn_aggregate_vertex(const gnn_graph_t* g, int side, const char* name, const float* feat,
+                                         int F, const float* scale, float* out, hipStream_t st) {
   if (gcn_blocked_applies(g, F)) {
     switch (F / (4 * kGcnSlices)) {
       case 4: GNN_TRY(launch_rowsum_blocks<4>(g, side, name, feat, F, out, st)); break;
@@ -257,22 +408,14 @@ static gnn_status_t gcn_aggregate(const gnn_graph_t* g, int side, const char* na
     GNN_LAUNCH_CHECK();
     return GNN_OK;
   }
-  const GroupShape gs = pick_group(F);
-  switch (gs.L) {
-    case 4: return RowsumLauncher<4, 1>::run(g, side, name, feat, F, scale, out, st);
-    case 8: return RowsumLauncher<8, 1>::run(g, side, name, feat, F, scale, out, st);
-    case 16: return RowsumLauncher<16, 1>::run(g, side, name, feat, F, scale, out, st);
-    case 32: return RowsumLauncher<32, 1>::run(g, side, name, feat, F, scale, out, st);
-    case 64:
-      switch (gs.NV) {
-        case 1: return RowsumLauncher<64, 1>::run(g, side, name, feat, F, scale, out, st);
-        case 2: return RowsumLauncher<64, 2>::run(g, side, name, feat, F, scale, out, st);
-        case 3: return RowsumLauncher<64, 3>::run(g, side, name, feat, F, scale, out, st);
-        case 4: return RowsumLauncher<64, 4>::run(g, side, name, feat, F, scale, out, st);
-      }
-  }
-  set_error("unsupported row-group shape L=%d NV=%d", gs.L, gs.NV);
-  return GNN_ERR_UNSUPPORTED;
+  return dispatch_rowsum<RowsumLauncher>(g, side, name, feat, F, scale, out, st);
+}
+
+// out[row,:] = scale[row] * sum of feat over the row's neighbours on `side` (0: in-edges, 1: out-edges)
+static gnn_status_t gcn_aggregate(const gnn_graph_t* g, int side, const char* name, const float* feat, int F,
+                                  const float* scale, float* out, hipStream_t st) {
+  if (use_edge_balanced(g, side)) return dispatch_rowsum<RowsumEbLauncher>(g, side, name, feat, F, scale, out, st);
+  return gcn_aggregate_vertex(g, side, name, feat, F, scale, out, st);
 }
 
 struct GcnWs {
@@ -356,5 +499,65 @@ extern "C" gnn_status_t gnn_gcn_bwd(const gnn_graph_t* g, int fin, int fout, con
   GNN_TRY(gcn_aggregate(g, 1, "gcn_bwd_src", gs, fout, c_src, dz, st));
   GNN_TRY(gemm_f32(fin, fout, g->n, x, fin, true, dz, fout, false, gw, fout, L.split_k, part, st));
   if (gx) GNN_TRY(gemm_f32(g->n, fin, fout, dz, fout, false, w, fout, true, gx, fin, 1, nullptr, st));
+  return GNN_OK;
+}
+
+__global__ void k_fill_f32(int64_t count, float value, float* __restrict__ p) {
+  const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i < count) p[i] = value;
+}
+
+extern "C" gnn_status_t gnn_gcn_tune(gnn_graph_t* g, int fout, void* ws, size_t ws_bytes, void* stream,
+                                     float* ms_out) {
+  clear_error();
+  GNN_TRY(gcn_check(g, 1, fout, "gnn_gcn_tune"));
+  const GcnWs L = gcn_ws_layout(g->n, 1, fout);
+  GNN_REQUIRE(ws != nullptr && ws_bytes >= L.total, GNN_ERR_WORKSPACE,
+              "gnn_gcn_tune: workspace of %zu bytes given, %zu needed", ws_bytes, L.total);
+  GNN_REQUIRE(aligned16(ws), GNN_ERR_INVALID_ARG, "gnn_gcn_tune: workspace must be 16-byte aligned");
+  float ms[4] = {0.f, 0.f, 0.f, 0.f};
+  if (g->n != 0 && g->nnz != 0) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(ws);
+    float* feat = reinterpret_cast<float*>(base + L.gs);  // all ones; its first n entries double as the scale
+    float* out = reinterpret_cast<float*>(base + L.dz);
+    const int64_t count = (int64_t)g->n * fout;
+    k_fill_f32<<<(unsigned)cdiv(count, 256), 256, 0, st>>>(count, 1.f, feat);
+    GNN_LAUNCH_CHECK();
+    hipEvent_t a = nullptr, b = nullptr;
+    GNN_HIP(hipEventCreate(&a));
+    if (hipEventCreate(&b) != hipSuccess) {
+      (void)hipEventDestroy(a);
+      set_error("gnn_gcn_tune: hipEventCreate failed");
+      return GNN_ERR_HIP;
+    }
+    constexpr int kReps = 3;
+    gnn_status_t status = GNN_OK;
+    for (int side = 0; side < 2 && status == GNN_OK; ++side) {
+      for (int eb = 0; eb < 2 && status == GNN_OK; ++eb) {
+        auto once = [&]() {
+          return eb ? dispatch_rowsum<RowsumEbLauncher>(g, side, "gcn_tune", feat, fout, feat, out, st)
+                    : gcn_aggregate_vertex(g, side, "gcn_tune", feat, fout, feat, out, st);
+        };
+        status = once();  // warm-up
+        if (status == GNN_OK && hipEventRecord(a, st) != hipSuccess) status = GNN_ERR_HIP;
+        for (int r = 0; r < kReps && status == GNN_OK; ++r) status = once();
+        if (status == GNN_OK && (hipEventRecord(b, st) != hipSuccess || hipEventSynchronize(b) != hipSuccess))
+          status = GNN_ERR_HIP;
+        float t = 0.f;
+        if (status == GNN_OK && hipEventElapsedTime(&t, a, b) != hipSuccess) status = GNN_ERR_HIP;
+        ms[2 * side + eb] = t / kReps;
+      }
+    }
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    if (status != GNN_OK) {
+      if (status == GNN_ERR_HIP && gnn_last_error()[0] == 0) set_error("gnn_gcn_tune: a HIP event call failed");
+      return status;
+    }
+    for (int side = 0; side < 2; ++side) g->gcn_edge_balanced[side] = ms[2 * side + 1] < ms[2 * side] ? 1 : 0;
+  }
+  if (ms_out)
+    for (int i = 0; i < 4; ++i) ms_out[i] = ms[i];
   return GNN_OK;
 }

@@ -26,7 +26,9 @@ void clear_error() { g_err[0] = 0; }
 // larger blocks save accumulator read-modify-writes, more would spill the L2).
 // 0 disables blocking.
 // lds_scalar_table: 1 lets the blocked destination-side kernels keep a block's el table in LDS
-static std::atomic<int64_t> g_config[kCfgCount] = {{24576}, {0}, {1}};
+// gcn_mapping: thread mapping of the GCN aggregation, 0 vertex-balanced, 1 edge-balanced,
+// 2 (default) per graph what gnn_gcn_tune measured, vertex-balanced where it never ran
+static std::atomic<int64_t> g_config[kCfgCount] = {{24576}, {0}, {1}, {2}};
 int64_t config_get(ConfigKey k) { return g_config[k].load(std::memory_order_relaxed); }
 
 // ---- profiling ---------------------------------------------------------------
@@ -106,6 +108,11 @@ extern "C" gnn_status_t gnn_config_set(const char* key, int64_t value) {
   }
   if (std::strcmp(key, "lds_scalar_table") == 0) {
     g_config[kCfgLdsScalarTable].store(value != 0);
+    return GNN_OK;
+  }
+  if (std::strcmp(key, "gcn_mapping") == 0) {
+    GNN_REQUIRE(value >= 0 && value <= 2, GNN_ERR_INVALID_ARG, "gnn_config_set: gcn_mapping must be 0, 1 or 2");
+    g_config[kCfgGcnMapping].store(value);
     return GNN_OK;
   }
   set_error("gnn_config_set: unknown key '%s'", key);

@@ -123,3 +123,68 @@ def test_many_vertices_few_edges_on_the_blocked_path():
     res = check(c, graph=g)
     assert (res["out"][n // 2:] == 0).all()
     g.close()
+
+
+# ---- edge-balanced mapping (Sec. 5) and the profile-driven choice -------------------------
+@pytest.fixture
+def edge_balanced():
+    import paper_2110_09524_amd as pk
+    pk.gnn_config_set("gcn_mapping", 1)
+    yield
+    pk.gnn_config_set("gcn_mapping", 2)
+
+
+def test_edge_balanced_mid_workload(edge_balanced):
+    print("gcn: edge-balanced gcn_mid", flush=True)
+    check(make("gcn_mid"))
+
+
+@pytest.mark.parametrize("fin,fout", [(3, 4), (9, 20), (64, 64), (17, 128), (8, 512), (5, 1024)])
+def test_edge_balanced_shapes(edge_balanced, fin, fout):
+    print(f"gcn: edge-balanced shapes fin={fin} fout={fout}", flush=True)
+    rng = np.random.default_rng(fin * 100 + fout + 1)
+    indptr, indices = random_graph(rng, 300, 3000, self_loops=True, duplicates=True)
+    check(synth(rng, indptr, indices, fin, fout))
+
+
+def test_edge_balanced_empty_rows_hub_and_ragged_tail(edge_balanced):
+    """Rows without edges between rows with edges, a row of 600 edges that spans ten runs, rows that
+    start or end exactly on a run boundary, and an edge count that is not a multiple of the run."""
+    print("gcn: edge-balanced empty rows + hub", flush=True)
+    rng = np.random.default_rng(18)
+    n = 600
+    edges = [(u, 0) for u in range(n)]
+    edges += [(int(rng.integers(0, n)), 5) for _ in range(64 - (n % 64))]      # row 5 ends on a boundary
+    edges += [(int(rng.integers(0, n)), 9) for _ in range(64)]                   # row 9 is exactly one run
+    edges += [(0, v) for v in range(12, n, 3)]
+    edges += [(int(rng.integers(0, n)), int(v)) for v in range(20, n) for _ in range(int(v) % 3)]
+    indptr, indices = tiny_graph(n, edges)
+    assert len(indices) % 64 != 0
+    c = synth(rng, indptr, indices, 12, 32)
+    res = check(c)
+    empty_rows = np.flatnonzero(np.diff(indptr) == 0)
+    assert empty_rows.size > 0 and (res["out"][empty_rows] == 0).all()
+
+
+def test_edge_balanced_graph_without_edges(edge_balanced):
+    rng = np.random.default_rng(19)
+    n = 33
+    res = check(synth(rng, np.zeros(n + 1, dtype=np.int32), np.zeros(0, dtype=np.int32), 6, 16))
+    assert (res["out"] == 0).all() and (res["gw"] == 0).all()
+
+
+def test_tune_records_a_choice_and_results_stay_right():
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev, workspace
+    print("gcn: tune", flush=True)
+    c = make("gcn_mid")
+    g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
+    ms = pk.gnn_gcn_tune(g, c["fout"], workspace(pk.gnn_gcn_workspace_bytes(g, 1, c["fout"])))
+    assert len(ms) == 4 and all(t > 0 for t in ms)
+    check(c, graph=g)        # whichever mapping was recorded per side
+    with pytest.raises(pk.GnnError) as e:
+        pk.gnn_gcn_tune(g, c["fout"], workspace(256))
+    assert e.value.status == 3
+    with pytest.raises(pk.GnnError):
+        pk.gnn_config_set("gcn_mapping", 3)
+    g.close()

@@ -138,6 +138,12 @@ def _make_gcn_c4(seed):
     return _gcn("gcn_c4", n, graphs.chung_lu(n, 114_000_000, 2.1, SEED0 ^ 4), 602, 256, seed)
 
 
+def _make_gcn_c5(seed):
+    # GCN on the gmm_c5 graph (100 000 vertices, average degree 21): several rows per run of edges
+    n = 100_000
+    return _gcn("gcn_c5", n, graphs.chung_lu(n, 2_000_000, 2.1, SEED0 ^ 5), 64, 64, seed)
+
+
 def _make_gcn_mid(seed):
     n = 6000
     return _gcn("gcn_mid", n, graphs.chung_lu(n, 300_000, 2.1, seed), 602, 256, seed)
@@ -171,6 +177,7 @@ _MAKERS = {
     "ec_k40_mid": (107, _make_ec_k40_mid),
     "gcn_c4": (6, _make_gcn_c4),
     "gcn_mid": (106, _make_gcn_mid),
+    "gcn_c5": (8, _make_gcn_c5),
 }
 NAMES = tuple(_MAKERS)
 
