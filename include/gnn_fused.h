@@ -278,6 +278,55 @@ gnn_status_t gnn_gcn_tune(gnn_graph_t* graph, int fout, void* ws, size_t ws_byte
                           float* ms_out /*host [4], nullable*/);
 
 /* ------------------------------------------------------------------------- *
+ * Lightweight vertex operators and the loss of a node-classification step (Sec. 3:
+ * element-wise Apply- operators on vertices; Sec. 7.2: the end-to-end runs train
+ * two-layer node classifiers).  All matrices are [n, f] fp32, rows 16-byte aligned
+ * (f % 4 == 0, f <= 1024).
+ *
+ * gnn_bias_act_fwd:  out = act(in + bias); bias [f] may be NULL; in == out allowed.
+ *   act: GNN_ACT_IDENTITY, GNN_ACT_RELU, GNN_ACT_ELU (alpha 1), GNN_ACT_LEAKY (slope >= 0).
+ * gnn_bias_act_bwd:  gin = gout * act'(.) taken from the forward OUTPUT y (ReLU'(0) = 0,
+ *   LeakyReLU'(0) = slope, ELU' = y + 1 for y <= 0), gbias [f] = column sums of gin
+ *   (NULL to skip; needs the workspace of gnn_bias_act_workspace_bytes, summed in a fixed
+ *   order).  gin == gout allowed; y may be NULL for the identity.
+ * gnn_softmax_xent:  loss (device scalar) = mean over the labelled vertices of
+ *   log sum_c exp(z[v,c]) - z[v, label[v]];  glogits [n,c] = (softmax(z[v]) - onehot) /
+ *   n_labelled, zero rows for unlabelled vertices.  A label outside [0, c) marks a vertex
+ *   as unlabelled; n_labelled is the caller's count of the others (0: loss 0).
+ *   Any c <= 4096, no alignment needed.
+ * gnn_sgd_update:    param -= lr * grad over `count` floats.
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP as for the layers.
+ * ------------------------------------------------------------------------- */
+enum { GNN_ACT_IDENTITY = 0, GNN_ACT_RELU = 1, GNN_ACT_ELU = 2, GNN_ACT_LEAKY = 3 };
+
+gnn_status_t gnn_bias_act_fwd(int64_t n, int f, int act, float slope, const float* in /*[n,f]*/,
+                              const float* bias /*[f] nullable*/, float* out /*[n,f]*/, void* stream);
+size_t gnn_bias_act_workspace_bytes(int64_t n, int f);
+gnn_status_t gnn_bias_act_bwd(int64_t n, int f, int act, float slope, const float* y /*[n,f]*/,
+                              const float* gout /*[n,f]*/, float* gin /*[n,f]*/,
+                              float* gbias /*[f] nullable*/, void* ws, size_t ws_bytes, void* stream);
+size_t gnn_softmax_xent_workspace_bytes(int64_t n);
+gnn_status_t gnn_softmax_xent(int64_t n, int c, int64_t n_labelled, const float* logits /*[n,c]*/,
+                              const int32_t* labels /*[n]*/, float* loss /*device, 1 float*/,
+                              float* glogits /*[n,c]*/, void* ws, size_t ws_bytes, void* stream);
+gnn_status_t gnn_sgd_update(int64_t count, float lr, const float* grad, float* param, void* stream);
+
+/* ------------------------------------------------------------------------- *
+ * k-nearest-neighbour graph of a batch of point clouds (the EdgeConv model builds its
+ * graph from the points, Sec. 7.2: k = 20 / 40 inside each cloud).  coords is
+ * [clouds*points, dim] fp32; vertex id = cloud * points + i.  For every point: the k
+ * points of its own cloud with the smallest squared Euclidean distance, itself included,
+ * ties towards the lower index.  The squared distance is accumulated in float32,
+ * coordinate by coordinate in index order, each operation rounded on its own, so the
+ * choice is reproducible bit for bit.  Output: CSR by destination, indptr [n+1]
+ * (= i*k), indices [n*k] (sources ascending in a row), ready for gnn_graph_create.
+ * Limits: k <= 64, k <= points <= 2048, n*k < 2^31.  Coordinates must not be NaN.
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP.
+ * ------------------------------------------------------------------------- */
+gnn_status_t gnn_knn_graph(int clouds, int points, int dim, int k, const float* coords,
+                           int32_t* indptr /*[n+1]*/, int32_t* indices /*[n*k]*/, void* stream);
+
+/* ------------------------------------------------------------------------- *
  * Per-kernel timing (measurement aid, Sec. 7 metrics).  While enabled, every
  * kernel the library launches is bracketed by HIP events recorded on the
  * caller's stream.  gnn_prof_collect synchronises those events (host sync) and

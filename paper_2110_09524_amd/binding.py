@@ -24,7 +24,9 @@ EXPORTS = [
     "gnn_graph_get_buckets", "gnn_graph_get_blocked", "gnn_config_set", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
     "gnn_gat_bwd", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
     "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd",
-    "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_gcn_tune", "gnn_prof_enable",
+    "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_gcn_tune",
+    "gnn_bias_act_fwd", "gnn_bias_act_workspace_bytes", "gnn_bias_act_bwd", "gnn_softmax_xent_workspace_bytes",
+    "gnn_softmax_xent", "gnn_sgd_update", "gnn_knn_graph", "gnn_prof_enable",
     "gnn_prof_collect", "gnn_prof_reset", "gnn_prof_count", "gnn_prof_get",
 ]
 
@@ -68,6 +70,15 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_gcn_fwd.argtypes = [vp, i32, i32] + [vp] * 6 + [vp]
     lib.gnn_gcn_bwd.argtypes = [vp, i32, i32] + [vp] * 7 + [vp, sz, vp]
     lib.gnn_gcn_tune.argtypes = [vp, i32, vp, sz, vp, C.POINTER(C.c_float)]
+    lib.gnn_bias_act_fwd.argtypes = [i64, i32, i32, f32, vp, vp, vp, vp]
+    lib.gnn_bias_act_workspace_bytes.restype = sz
+    lib.gnn_bias_act_workspace_bytes.argtypes = [i64, i32]
+    lib.gnn_bias_act_bwd.argtypes = [i64, i32, i32, f32, vp, vp, vp, vp, vp, sz, vp]
+    lib.gnn_softmax_xent_workspace_bytes.restype = sz
+    lib.gnn_softmax_xent_workspace_bytes.argtypes = [i64]
+    lib.gnn_softmax_xent.argtypes = [i64, i32, i64, vp, vp, vp, vp, vp, sz, vp]
+    lib.gnn_sgd_update.argtypes = [i64, f32, vp, vp, vp]
+    lib.gnn_knn_graph.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp]
     lib.gnn_prof_enable.argtypes = [i32]
     lib.gnn_prof_collect.argtypes = []
     lib.gnn_prof_reset.argtypes = []
@@ -76,7 +87,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     for name in EXPORTS:
         fn = getattr(lib, name)
         if name not in ("gnn_last_error", "gnn_gat_workspace_bytes", "gnn_edgeconv_workspace_bytes",
-                        "gnn_gmm_workspace_bytes", "gnn_gcn_workspace_bytes", "gnn_prof_count"):
+                        "gnn_gmm_workspace_bytes", "gnn_gcn_workspace_bytes", "gnn_prof_count",
+                        "gnn_bias_act_workspace_bytes", "gnn_softmax_xent_workspace_bytes"):
             fn.restype = C.c_int
     return lib
 
@@ -252,6 +264,42 @@ def gnn_gcn_tune(g: Graph, fout, ws, stream=None):
     ms = (C.c_float * 4)()
     _check(lib().gnn_gcn_tune(g.handle, fout, wp, wb, _stream(stream), ms))
     return [float(v) for v in ms]
+
+
+ACTS = {"identity": 0, "relu": 1, "elu": 2, "leaky": 3}
+
+
+def gnn_bias_act_fwd(n, f, act, slope, x, bias, out, stream=None):
+    _check(lib().gnn_bias_act_fwd(n, f, ACTS[act], slope, _f(x), _f(bias), _f(out), _stream(stream)))
+
+
+def gnn_bias_act_workspace_bytes(n, f) -> int:
+    return int(lib().gnn_bias_act_workspace_bytes(n, f))
+
+
+def gnn_bias_act_bwd(n, f, act, slope, y, gout, gin, gbias, ws=None, stream=None):
+    wp, wb = _ws_args(ws)
+    _check(lib().gnn_bias_act_bwd(n, f, ACTS[act], slope, _f(y), _f(gout), _f(gin), _f(gbias), wp, wb,
+                                  _stream(stream)))
+
+
+def gnn_softmax_xent_workspace_bytes(n) -> int:
+    return int(lib().gnn_softmax_xent_workspace_bytes(n))
+
+
+def gnn_softmax_xent(n, c, n_labelled, logits, labels, loss, glogits, ws, stream=None):
+    wp, wb = _ws_args(ws)
+    _check(lib().gnn_softmax_xent(n, c, n_labelled, _f(logits), _i(labels), _f(loss), _f(glogits), wp, wb,
+                                  _stream(stream)))
+
+
+def gnn_sgd_update(lr, grad, param, stream=None):
+    assert grad.numel() == param.numel()
+    _check(lib().gnn_sgd_update(param.numel(), lr, _f(grad), _f(param), _stream(stream)))
+
+
+def gnn_knn_graph(clouds, points, dim, k, coords, indptr, indices, stream=None):
+    _check(lib().gnn_knn_graph(clouds, points, dim, k, _f(coords), _i(indptr), _i(indices), _stream(stream)))
 
 
 def gnn_gmm_workspace_bytes(g: Graph, fin, fout, k) -> int:

@@ -50,6 +50,29 @@ def _gat(name, n, graph, fin, heads, f, seed, x_kind="normal"):
     )
 
 
+def _gat2(name, n, graph, fin, heads1, f1, classes, seed, x_kind="normal", labelled=0.5):
+    """Two-layer node classifier: fin -> heads1 x f1 (ELU) -> classes (one head), seeded labels on a
+    fraction of the vertices (the others carry -1)."""
+    indptr, indices = graph
+    rng = graphs.rng_for(seed ^ 0xA5A5)
+    if x_kind == "normal":
+        x = _normal(rng, (n, fin))
+    else:
+        x = (rng.random((n, fin), dtype=np.float32) < 0.05).astype(np.float32)
+    hf = heads1 * f1
+    labels = rng.integers(0, classes, n).astype(np.int32)
+    labels[rng.random(n) >= labelled] = -1
+    return dict(
+        name=name, kind="gat2", n=n, nnz=int(indices.shape[0]), fin=fin, heads1=heads1, f1=f1,
+        classes=classes, slope=0.2, indptr=indptr, indices=indices, x=x, labels=labels,
+        params=dict(
+            w1=glorot(rng, fin, hf, (fin, hf)), al1=glorot(rng, f1, 1, (heads1, f1)),
+            ar1=glorot(rng, f1, 1, (heads1, f1)), b1=(0.1 * _normal(rng, (hf,))).astype(np.float32),
+            w2=glorot(rng, hf, classes, (hf, classes)), al2=glorot(rng, classes, 1, (1, classes)),
+            ar2=glorot(rng, classes, 1, (1, classes)), b2=(0.1 * _normal(rng, (classes,))).astype(np.float32)),
+    )
+
+
 def _edgeconv(name, batch, points, k, fin, fout, seed):
     indptr, indices, coords = graphs.knn_point_clouds(batch, points, k, seed)
     n = batch * points
@@ -144,6 +167,25 @@ def _make_gcn_c5(seed):
     return _gcn("gcn_c5", n, graphs.chung_lu(n, 2_000_000, 2.1, SEED0 ^ 5), 64, 64, seed)
 
 
+def _make_gat2_mid(seed):
+    n = 3000
+    return _gat2("gat2_mid", n, graphs.chung_lu(n, 60_000, 2.1, seed), 96, 2, 32, 8, seed)
+
+
+def _make_gat2_c2(seed):
+    # the end-to-end GAT setting of Sec. 7.2 (two layers, 128 hidden, one head) on the gat_c2 graph
+    n = 20_000
+    return _gat2("gat2_c2", n, graphs.chung_lu(n, 100_000, 2.1, SEED0 ^ 2), 500, 1, 128, 4, seed,
+                 x_kind="binary", labelled=0.3)
+
+
+def _make_gat2_c4(seed):
+    # the same on the gat_c4 graph; 44 output columns stand in for Reddit's 41 classes (f % 4 == 0)
+    n = 232_965
+    return _gat2("gat2_c4", n, graphs.chung_lu(n, 114_000_000, 2.1, SEED0 ^ 4), 602, 1, 128, 44, seed,
+                 labelled=0.66)
+
+
 def _make_gcn_mid(seed):
     n = 6000
     return _gcn("gcn_mid", n, graphs.chung_lu(n, 300_000, 2.1, seed), 602, 256, seed)
@@ -178,6 +220,9 @@ _MAKERS = {
     "gcn_c4": (6, _make_gcn_c4),
     "gcn_mid": (106, _make_gcn_mid),
     "gcn_c5": (8, _make_gcn_c5),
+    "gat2_mid": (109, _make_gat2_mid),
+    "gat2_c2": (9, _make_gat2_c2),
+    "gat2_c4": (10, _make_gat2_c4),
 }
 NAMES = tuple(_MAKERS)
 
