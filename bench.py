@@ -172,6 +172,33 @@ def cpu_baseline_gcn(c, budget_rows):
     }
 
 
+def cpu_baseline_gat2(c, sample_vertices=8192):
+    """Two-layer step: the oracle runs whole on the subgraph induced by a seeded vertex sample."""
+    import numpy as np
+    from oracle import two_layer as ot
+    n = c["n"]
+    rng = np.random.default_rng(12345)
+    keep = np.sort(rng.choice(n, size=min(sample_vertices, n), replace=False))
+    new_id = np.full(n, -1, dtype=np.int64)
+    new_id[keep] = np.arange(len(keep))
+    dst = np.repeat(np.arange(n), np.diff(c["indptr"]))
+    src = c["indices"].astype(np.int64)
+    ok = (new_id[dst] >= 0) & (new_id[src] >= 0)
+    d2, s2 = new_id[dst[ok]], new_id[src[ok]]          # still sorted by destination
+    ip = np.zeros(len(keep) + 1, dtype=np.int32)
+    np.add.at(ip, d2 + 1, 1)
+    ip = np.cumsum(ip).astype(np.int32)
+    ix = s2.astype(np.int32)
+    t0 = time.perf_counter()
+    fwd = ot.gat2_forward(ip, ix, c["x"][keep], c["params"], c["labels"][keep], c["slope"])
+    ot.gat2_backward(ip, ix, c["x"][keep], c["params"], c["labels"][keep], c["slope"], fwd)
+    dt = time.perf_counter() - t0
+    return {"value": len(ix) / dt, "unit": "edges/s", "cores": int(oracle_threads()), "kind": "oracle",
+            "sample": (f"fp64 numpy oracle, whole two-layer forward + backward on the subgraph induced by "
+                       f"{len(keep)} seeded vertices ({len(ix)} edges), {dt:.2f} s"),
+            "measured_s": dt}
+
+
 def cpu_baseline_full(c):
     """EdgeConv / GMM workloads are small enough for the oracle to run whole."""
     e = c["nnz"]
@@ -243,8 +270,33 @@ def main():
     torch.cuda.synchronize()
     t_plan = time.perf_counter() - t0
 
-    x, gout = to(c["x"]), to(c["gout"])
-    if kind == "gat":
+    x = to(c["x"])
+    gout = to(c["gout"]) if "gout" in c else None
+    gemm_total_flops = None
+    if kind == "gat2":
+        from paper_2110_09524_amd.steps import Gat2Step
+        H, F, C2 = c["heads1"], c["f1"], c["classes"]
+        HF = H * F
+        params = {k: to(v) for k, v in c["params"].items()}
+        model = Gat2Step(g, fin, H, F, C2, c["slope"], params, to(c["labels"]), int((c["labels"] >= 0).sum()))
+        ws_bytes = model.ws.numel()
+        lr = 1e-3
+
+        def step():
+            model.step(x, lr)
+        u1, g1, f1_ = gat_models(n, e, fin, H, F)
+        u2, g2, f2_ = gat_models(n, e, HF, 1, C2)
+        unique = {k: u1[k] + u2[k] for k in u1}
+        gather = {k: g1[k] + g2[k] for k in g1}
+        flops = {k: f1_[k] + f2_[k] for k in f1_}
+        metric = "two-layer GAT training step (fwd + bwd + SGD) edges/sec"
+        cfg = {"layers": 2, "in_feat": fin, "hidden": f"{H}x{F}", "classes": C2, "activation": "bias + ELU",
+               "loss": "softmax cross-entropy on seeded labels", "optimizer": "SGD",
+               "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded"}
+        # products named gemm_f32_mfma: layer-1 projection, layer-2 projection, layer-2 input gradient
+        gemm_flops = (2.0 * n * fin * HF + 2 * 2.0 * n * HF * C2) / 3
+        gemm_total_flops = 2 * 2.0 * n * fin * HF + 3 * 2.0 * n * HF * C2
+    elif kind == "gat":
         H, F = c["heads"], c["f"]
         HF = H * F
         w, a_l, a_r = to(c["w"]), to(c["a_l"]), to(c["a_r"])
@@ -276,7 +328,22 @@ def main():
             pk.gnn_edgeconv_bwd(g, fin, F, x, theta, phi, argmax, gout, gx, gtheta, gphi, ws)
         unique, gather, flops = edgeconv_models(n, e, fin, F)
         metric = "fused EdgeConv layer fwd+bwd edges/sec"
-        cfg = {"in_feat": fin, "out_feat": F, "graph": "32 clouds x 1024 points, kNN k=20 incl. self, seeded"}
+        k_nn, points = e // n, 1024
+        cfg = {"in_feat": fin, "out_feat": F,
+               "graph": f"{n // points} clouds x {points} points, kNN k={k_nn} incl. self, seeded"}
+        # building the same kind of graph on the GPU from the coordinates (not part of `value`:
+        # the layer is timed on a resident graph, as for the other workloads)
+        coords = to(c["coords"])
+        knn_ptr = new(n + 1, dtype=torch.int32)
+        knn_idx = new(e, dtype=torch.int32)
+        for rep in range(4):
+            if rep == 1:
+                torch.cuda.synchronize()
+                t_k0 = time.perf_counter()
+            pk.gnn_knn_graph(n // points, points, coords.shape[1], k_nn, coords, knn_ptr, knn_idx)
+        torch.cuda.synchronize()
+        cfg["knn_graph_build_ms"] = 1e3 * (time.perf_counter() - t_k0) / 3
+        del coords, knn_ptr, knn_idx
         gemm_flops = 2.0 * n * fin * 2 * F
     elif kind == "gmm":
         F, K = c["fout"], c["k"]
@@ -385,7 +452,7 @@ def main():
     # whole-layer floor: edge kernels at max(unique bytes / HBM, flops / fp32 vector peak), the
     # three dense products at the fp32 MFMA peak
     floor_s = sum(max(unique[k] / (HBM_PEAK_GBPS * 1e9), flops[k] / (FP32_VECTOR_TFLOPS * 1e12)) for k in edge_kernels)
-    floor_s += 3 * gemm_flops / (FP32_VECTOR_TFLOPS * 1e12)
+    floor_s += (3 * gemm_flops if gemm_total_flops is None else gemm_total_flops) / (FP32_VECTOR_TFLOPS * 1e12)
     layer_floor = {"floor_ms": floor_s * 1e3, "frac": floor_s * 1e3 / ms_per_step,
                    "edge_kernels_ms_per_step": sum(kern[k]["ms_per_step"] for k in edge_kernels),
                    "edge_kernels_edges_per_s": e / (1e-3 * sum(kern[k]["ms_per_step"] for k in edge_kernels))}
@@ -420,6 +487,8 @@ def main():
         print("[bench] timing the CPU oracle on a bounded sample ...", file=sys.stderr, flush=True)
         if kind == "gat":
             result["cpu_baseline"] = cpu_baseline_gat(c, args.cpu_rows)
+        elif kind == "gat2":
+            result["cpu_baseline"] = cpu_baseline_gat2(c)
         elif kind == "gcn":
             result["cpu_baseline"] = cpu_baseline_gcn(c, args.cpu_rows)
         else:

@@ -27,7 +27,30 @@
 namespace gnn {
 
 constexpr int kBlkThreads = 256;
-constexpr int kSlices = 8;  // one column slice per XCD
+constexpr int kSlices = 8;  // column slices of a wide row: one per XCD
+
+// How a row of HF floats is cut: `ns` slices of SL float4 each.  Wide rows (>= 1 KB) give every
+// XCD its own slice.  Narrower rows keep slices of a full 128-byte line (SL = 8) and have fewer
+// of them (ns = 4, 2, 1): workgroup id mod ns picks the slice, so XCD k and XCD k + ns work on the
+// same columns (for different rows) and each L2 still holds one slice of the column block.  A
+// gather of a half line would cost the L1 the same fill as a full one.
+struct Slicing {
+  int SL, ns;
+};
+static bool pick_slicing(int heads, int HF, Slicing& sl) {
+  if (HF % 32 != 0) return false;
+  const int q = HF / 32;  // 128-byte lines per row
+  if (q >= kSlices) {
+    sl = Slicing{q, kSlices};
+    return (q == 8 || q == 16 || q == 32) && kSlices % heads == 0;
+  }
+  if ((q == 4 || q == 2 || q == 1) && q % heads == 0) {
+    sl = Slicing{8, q};
+    return true;
+  }
+  sl = Slicing{q, kSlices};  // 64-byte slices, every slice inside one head
+  return q == 4 && kSlices % heads == 0;
+}
 
 // ---- one column block of a weighted row aggregation ---------------------------------
 // MODE 0: forward        acc[v]  += sum_e alpha_e           z[u]      (acc = out)
@@ -69,7 +92,8 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
     GatDims dm, int sph, int first, int narrow, int el_hm /* el is head-major [H][n] */,
     float* __restrict__ acc_buf, float* __restrict__ acc2_buf, float* __restrict__ scal_buf,
     int32_t* __restrict__ queue /* STAGE: one row counter per slice */, int32_t cols_here,
-    int32_t quads_per_grab, int last /* forward modes: this is the last block */,
+    int32_t quads_per_grab, int ns /* column slices: 8, 4, 2 or 1 */,
+    int last /* forward modes: this is the last block */,
     float4* __restrict__ state /* forward modes: running (max, sum, sum2) per (row, slice) */,
     float* __restrict__ m_out, float* __restrict__ d_out) {
   constexpr int THREADS = STAGE ? kStageThreads : kBlkThreads;
@@ -92,7 +116,7 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
   const int lane = threadIdx.x & 63;
   const int li = lane & (SL - 1);
   const int grp = threadIdx.x / SL;
-  const int slice = blockIdx.x % kSlices;
+  const int slice = blockIdx.x % ns;
   const int H = dm.H, HF = dm.HF;
   const int h = slice / sph;
   const float* l_el = lds + GPB * GS;
@@ -105,7 +129,7 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
     for (int i = threadIdx.x; i < cols_here; i += THREADS) dst[i] = src[i];
     __syncthreads();
   } else {
-    quad = (int64_t)(blockIdx.x / kSlices) * GPB + grp;
+    quad = (int64_t)(blockIdx.x / ns) * GPB + grp;
     quad_end = quad + 1;
   }
 
@@ -343,11 +367,8 @@ static gnn_status_t head_major(const gnn_graph_t* g, int H, const float* a, floa
 bool gat_blocked_applies(const gnn_graph_t* g, int heads, int f) {
   if (g->nblk <= 1 || config_get(kCfgForceSimple)) return false;
   const int HF = heads * f;
-  if (HF % (4 * kSlices) != 0) return false;
-  const int SL = HF / (4 * kSlices);
-  if (!(SL == 4 || SL == 8 || SL == 16 || SL == 32)) return false;
-  if (kSlices % heads != 0) return false;  // every slice lies inside one head
-  return true;
+  Slicing sl;
+  return pick_slicing(heads, HF, sl);
 }
 
 size_t gat_blocked_ws_bytes(const gnn_graph_t* g, int heads, int f) {
@@ -388,12 +409,13 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
                                   const float* el, const float* er, const float* m, const float* d,
                                   const float4* vstate, float* acc, float* acc2, float* scal,
                                   int32_t* queue, float4* state, float* m_out, float* d_out, hipStream_t st) {
-  const int sph = kSlices / dm.H;
+  const int ns = dm.HF / (4 * SL);
+  const int sph = ns / dm.H;
   // 32-bit byte offsets (and 24-bit multiplies) reach every gathered row
   const int narrow = (int64_t)g->n * dm.HF * 4 < ((int64_t)1 << 32) && g->n < (1 << 24);
   constexpr int GS = 3 * SL + 4 * kRowsPerGroup;
   const int rows_per_wg = (kBlkThreads / SL) * kRowsPerGroup;
-  const unsigned grid = (unsigned)(cdiv(g->n, rows_per_wg) * kSlices);
+  const unsigned grid = (unsigned)(cdiv(g->n, rows_per_wg) * ns);
   const size_t lds = sizeof(float) * (size_t)(kBlkThreads / SL) * GS;
   bool stage_ok = false;
   if constexpr (MODE != 2) {
@@ -431,7 +453,7 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
         ProfScope p(name, st);  // one timed bracket per launch
         k_gat_blk<SL, MODE, true><<<pgrid, kStageThreads, staged_lds_bytes<SL>(g->block_cols), st>>>(
             g->n, g->order[side], bseg_b, g->bcol[side], feat, el, er, m, d, vstate, col_begin, dm, sph,
-            b == 0, narrow, el_hm, acc, acc2, scal, queue + b * kSlices, cols_here, 1, b == g->nblk - 1, state,
+            b == 0, narrow, el_hm, acc, acc2, scal, queue + b * kSlices, cols_here, 1, ns, b == g->nblk - 1, state,
             m_out, d_out);
         GNN_LAUNCH_CHECK();
       }
@@ -440,7 +462,7 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
       ProfScope p(name, st);  // one timed bracket per launch
       k_gat_blk<SL, MODE, false><<<grid, kBlkThreads, lds, st>>>(
           g->n, g->order[side], bseg_b, g->bcol[side], feat, el, er, m, d, vstate, col_begin, dm, sph,
-          b == 0, narrow, el_hm, acc, acc2, scal, nullptr, 0, 1, b == g->nblk - 1, state, m_out, d_out);
+          b == 0, narrow, el_hm, acc, acc2, scal, nullptr, 0, 1, ns, b == g->nblk - 1, state, m_out, d_out);
       GNN_LAUNCH_CHECK();
     }
   }
@@ -453,7 +475,9 @@ static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name,
                                const float* d, const float4* vstate, float* acc, float* acc2,
                                float* scal, int32_t* queue, float4* state, float* m_out, float* d_out,
                                hipStream_t st) {
-  switch (dm.HF / (4 * kSlices)) {
+  Slicing sl;
+  if (!pick_slicing(dm.H, dm.HF, sl)) sl.SL = 0;
+  switch (sl.SL) {
     case 4: return launch_blocks<4, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
     case 8: return launch_blocks<8, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
     case 16: return launch_blocks<16, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
