@@ -212,7 +212,7 @@ template <int SL>
 __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
     int32_t n_rows, const int32_t* __restrict__ order, const int2* __restrict__ bseg_b,
     const int32_t* __restrict__ bcol, const float* __restrict__ feat, int32_t col_begin, int F,
-    int first, float* __restrict__ acc_buf) {
+    int first, int ns /* column slices: 8, 4, 2 or 1 */, float* __restrict__ acc_buf) {
   constexpr int GPB = kGcnBlock / SL;
   constexpr int R = kGcnRows;
   constexpr int U = SL < 8 ? 4 : 8;
@@ -222,8 +222,8 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
   const int lane = threadIdx.x & 63;
   const int li = lane & (SL - 1);
   const int grp = threadIdx.x / SL;
-  const int slice = blockIdx.x % kGcnSlices;
-  const int64_t r0 = ((int64_t)(blockIdx.x / kGcnSlices) * GPB + grp) * R;
+  const int slice = blockIdx.x % ns;
+  const int64_t r0 = ((int64_t)(blockIdx.x / ns) * GPB + grp) * R;
   if (r0 >= n_rows) return;
   int* l_idx = lds + grp * GS;
   int* l_row = l_idx + SL;
@@ -301,23 +301,39 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
   }
 }
 
+// A row of F floats is cut into `ns` slices of SL float4: one slice per XCD for rows of 1 KB and
+// more; narrower rows keep slices of a full 128-byte line and have fewer of them (workgroup id
+// mod ns picks the slice, so XCD k and XCD k + ns share columns and split the rows).
+static bool gcn_slicing(int F, int& SL, int& ns) {
+  if (F % 32 != 0) return false;
+  const int q = F / 32;
+  if (q >= kGcnSlices) {
+    SL = q;
+    ns = kGcnSlices;
+    return q == 8 || q == 16 || q == 32;
+  }
+  SL = 8;
+  ns = q;
+  return q == 4 || q == 2 || q == 1;
+}
+
 static bool gcn_blocked_applies(const gnn_graph_t* g, int F) {
   if (g->nblk <= 1 || config_get(kCfgForceSimple)) return false;
-  if (F % (4 * kGcnSlices) != 0) return false;
-  const int SL = F / (4 * kGcnSlices);
-  return SL == 4 || SL == 8 || SL == 16 || SL == 32;
+  int SL, ns;
+  return gcn_slicing(F, SL, ns);
 }
 
 template <int SL>
 static gnn_status_t launch_rowsum_blocks(const gnn_graph_t* g, int side, const char* name, const float* feat,
                                          int F, float* acc, hipStream_t st) {
   const int rows_per_wg = (kGcnBlock / SL) * kGcnRows;
-  const unsigned grid = (unsigned)(cdiv(g->n, rows_per_wg) * kGcnSlices);
+  const int ns = F / (4 * SL);
+  const unsigned grid = (unsigned)(cdiv(g->n, rows_per_wg) * ns);
   for (int b = 0; b < g->nblk; ++b) {
     const int2* bseg_b = reinterpret_cast<const int2*>(g->bseg[side]) + (int64_t)b * g->n;
     ProfScope p(name, st);  // one timed bracket per launch
     k_rowsum_blk<SL><<<grid, kGcnBlock, 0, st>>>(g->n, g->order[side], bseg_b, g->bcol[side], feat,
-                                                b * g->block_cols, F, b == 0, acc);
+                                                b * g->block_cols, F, b == 0, ns, acc);
     GNN_LAUNCH_CHECK();
   }
   return GNN_OK;
@@ -396,8 +412,9 @@ static bool use_edge_balanced(const gnn_graph_t* g, int side) {
 static gnn_status_t gcn_aggregate_vertex(const gnn_graph_t* g, int side, const char* name, const float* feat,
                                          int F, const float* scale, float* out, hipStream_t st) {
   if (gcn_blocked_applies(g, F)) {
-    switch (F / (4 * kGcnSlices)) {
-      case 4: GNN_TRY(launch_rowsum_blocks<4>(g, side, name, feat, F, out, st)); break;
+    int SL = 0, ns = 0;
+    gcn_slicing(F, SL, ns);
+    switch (SL) {
       case 8: GNN_TRY(launch_rowsum_blocks<8>(g, side, name, feat, F, out, st)); break;
       case 16: GNN_TRY(launch_rowsum_blocks<16>(g, side, name, feat, F, out, st)); break;
       default: GNN_TRY(launch_rowsum_blocks<32>(g, side, name, feat, F, out, st)); break;
