@@ -320,7 +320,7 @@ gnn_status_t gnn_sgd_update(int64_t count, float lr, const float* grad, float* p
  * coordinate by coordinate in index order, each operation rounded on its own, so the
  * choice is reproducible bit for bit.  Output: CSR by destination, indptr [n+1]
  * (= i*k), indices [n*k] (sources ascending in a row), ready for gnn_graph_create.
- * Limits: k <= 64, k <= points <= 2048, n*k < 2^31.  Coordinates must not be NaN.
+ * Limits: k <= points <= 2048, n*k < 2^31.  Coordinates must not be NaN.
  * Errors: INVALID_ARG, UNSUPPORTED, HIP.
  * ------------------------------------------------------------------------- */
 gnn_status_t gnn_knn_graph(int clouds, int points, int dim, int k, const float* coords,

@@ -9,71 +9,80 @@
 // squared distance is accumulated in float32, coordinate by coordinate in index order, every
 // subtraction, product and sum rounded on its own (no fused multiply-add).
 //
-// One wavefront per query point.  Every candidate becomes a 64-bit key (distance bits in the
-// high word - non-negative floats order like unsigned integers - and the candidate's index in
-// the low word), kept in LDS; lane l owns the candidates l, l+64, ...  The k smallest keys are
-// drawn one by one: a butterfly minimum over the lanes' current minima, then the owning lane
-// strikes the winner out and rescans its own list.  A rank sort over the k winners puts
-// them in ascending index order.
+// One wavefront per query point, no LDS and no cross-lane data movement: lane l keeps the
+// distance bits of candidates l, l+64, ... in registers (non-negative floats order like
+// unsigned integers).  The k-th smallest distance T is found by bisection on the 32-bit
+// pattern; each probe counts the candidates at or below it with one wave-wide vote and a
+// scalar population count per register slot.  Everything below T is chosen, and of the
+// candidates exactly at T the lowest indices fill up to k.  Positions in the output row come
+// from the same votes (candidates before me that are chosen), which leaves the row in
+// ascending index order because index = lane + 64 * slot.
 #include "common.h"
 
 namespace gnn {
 
 constexpr int kKnnThreads = 256;
 constexpr int kKnnQueries = kKnnThreads / kWave;
-constexpr int kKnnMaxPoints = 2048;  // 4 wavefronts x 2048 keys x 8 B = 64 KB of LDS
-constexpr unsigned long long kKeyGone = ~0ull;
+constexpr int kKnnMaxPoints = 2048;  // 32 register slots per lane
+constexpr uint32_t kKeyNone = 0xFFFFFFFFu;  // above every distance pattern
 
+template <int NSLOT>
 __global__ __launch_bounds__(kKnnThreads) void k_knn(int64_t n, int points, int dim, int k,
                                                      const float* __restrict__ coords,
                                                      int32_t* __restrict__ indices) {
-  extern __shared__ unsigned long long knn_keys[];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int64_t q = (int64_t)blockIdx.x * kKnnQueries + w;
-  if (q >= n) return;  // whole wavefront; nothing below synchronises across wavefronts
+  if (q >= n) return;  // whole wavefront
   const int64_t base = q / points * points;
-  unsigned long long* my = knn_keys + (size_t)w * points;
   const float* a = coords + q * dim;
 
-  unsigned long long best = kKeyGone;
-  for (int j = lane; j < points; j += kWave) {
-    const float* b = coords + (base + j) * dim;
-    float acc = 0.f;
-    for (int d = 0; d < dim; ++d) {
-      const float diff = __fsub_rn(a[d], b[d]);
-      const float sq = __fmul_rn(diff, diff);
-      acc = d == 0 ? sq : __fadd_rn(acc, sq);
+  uint32_t key[NSLOT];
+#pragma unroll
+  for (int t = 0; t < NSLOT; ++t) {
+    const int j = lane + kWave * t;
+    uint32_t bits = kKeyNone;
+    if (j < points) {
+      const float* b = coords + (base + j) * dim;
+      float acc = 0.f;
+      for (int d = 0; d < dim; ++d) {
+        const float diff = __fsub_rn(a[d], b[d]);
+        const float sq = __fmul_rn(diff, diff);
+        acc = d == 0 ? sq : __fadd_rn(acc, sq);
+      }
+      bits = __float_as_uint(acc);
     }
-    const unsigned long long key = ((unsigned long long)__float_as_uint(acc) << 32) | (unsigned)j;
-    my[j] = key;
-    best = key < best ? key : best;
+    key[t] = bits;
   }
 
-  int mine = 0;  // lane r keeps the r-th winner
-  for (int r = 0; r < k; ++r) {
-    unsigned long long win = best;
-    for (int off = 1; off < kWave; off <<= 1) {
-      const unsigned long long o = __shfl_xor(win, off, 64);
-      win = o < win ? o : win;
-    }
-    const int j = (int)(unsigned)(win & 0xffffffffull);
-    if (lane == r) mine = j;
-    if (lane == (j & 63)) {  // the owner strikes it out and looks for its next minimum
-      my[j] = kKeyGone;
-      best = kKeyGone;
-      for (int t = lane; t < points; t += kWave) {
-        const unsigned long long key = my[t];
-        best = key < best ? key : best;
-      }
-    }
+  // T = the smallest pattern with at least k candidates at or below it; the count is uniform
+  // over the wavefront, so this loop is scalar control flow
+  uint32_t lo = 0u, hi = kKeyNone - 1u;  // all `points` >= k candidates are <= hi
+  while (lo < hi) {
+    const uint32_t mid = lo + ((hi - lo) >> 1);
+    int cnt = 0;
+#pragma unroll
+    for (int t = 0; t < NSLOT; ++t) cnt += __popcll(__ballot(key[t] <= mid));
+    if (cnt >= k) hi = mid; else lo = mid + 1u;
   }
-  // ascending index order: the rank of a winner is the number of smaller winners
-  int rank = 0;
-  for (int r = 0; r < k; ++r) {
-    const int other = __shfl(mine, r, 64);
-    rank += other < mine ? 1 : 0;
+  const uint32_t T = lo;
+  int below = 0;
+#pragma unroll
+  for (int t = 0; t < NSLOT; ++t) below += __popcll(__ballot(key[t] < T));
+  const int ties_wanted = k - below;  // >= 1: candidates exactly at T, lowest indices first
+
+  const unsigned long long before_me = (1ull << lane) - 1ull;
+  int ties_seen = 0, chosen_seen = 0;
+#pragma unroll
+  for (int t = 0; t < NSLOT; ++t) {
+    const bool tie = key[t] == T;
+    const unsigned long long tie_vote = __ballot(tie);
+    const int tie_rank = ties_seen + __popcll(tie_vote & before_me);
+    const bool chosen = key[t] < T || (tie && tie_rank < ties_wanted);
+    const unsigned long long vote = __ballot(chosen);
+    if (chosen) indices[q * k + chosen_seen + __popcll(vote & before_me)] = (int32_t)(base + lane + kWave * t);
+    ties_seen += __popcll(tie_vote);
+    chosen_seen += __popcll(vote);
   }
-  if (lane < k) indices[q * k + rank] = (int32_t)(base + mine);
 }
 
 __global__ void k_knn_indptr(int64_t n, int k, int32_t* __restrict__ indptr) {
@@ -90,8 +99,7 @@ extern "C" gnn_status_t gnn_knn_graph(int clouds, int points, int dim, int k, co
   clear_error();
   GNN_REQUIRE(clouds >= 0 && points > 0 && dim > 0 && k > 0, GNN_ERR_INVALID_ARG,
               "gnn_knn_graph: sizes must be positive");
-  GNN_REQUIRE(k <= points && k <= kWave, GNN_ERR_UNSUPPORTED,
-              "gnn_knn_graph: k = %d must not exceed the cloud size or 64", k);
+  GNN_REQUIRE(k <= points, GNN_ERR_UNSUPPORTED, "gnn_knn_graph: k = %d exceeds the cloud size %d", k, points);
   GNN_REQUIRE(points <= kKnnMaxPoints, GNN_ERR_UNSUPPORTED, "gnn_knn_graph: %d points per cloud exceed %d",
               points, kKnnMaxPoints);
   const int64_t n = (int64_t)clouds * points;
@@ -103,8 +111,17 @@ extern "C" gnn_status_t gnn_knn_graph(int clouds, int points, int dim, int k, co
   GNN_LAUNCH_CHECK();
   if (n == 0) return GNN_OK;
   GNN_REQUIRE(coords && indices, GNN_ERR_INVALID_ARG, "gnn_knn_graph: null pointer");
-  const size_t lds = sizeof(unsigned long long) * (size_t)kKnnQueries * points;
-  k_knn<<<(unsigned)cdiv(n, kKnnQueries), kKnnThreads, lds, st>>>(n, points, dim, k, coords, indices);
+  const unsigned grid = (unsigned)cdiv(n, kKnnQueries);
+#define GNN_KNN_CASE(NSLOT_)                                                                    \
+  k_knn<NSLOT_><<<grid, kKnnThreads, 0, st>>>(n, points, dim, k, coords, indices)
+  const int slots = (int)cdiv(points, kWave);  // register slots a lane needs
+  if (slots <= 1) GNN_KNN_CASE(1);
+  else if (slots <= 2) GNN_KNN_CASE(2);
+  else if (slots <= 4) GNN_KNN_CASE(4);
+  else if (slots <= 8) GNN_KNN_CASE(8);
+  else if (slots <= 16) GNN_KNN_CASE(16);
+  else GNN_KNN_CASE(32);
+#undef GNN_KNN_CASE
   GNN_LAUNCH_CHECK();
   return GNN_OK;
 }

@@ -21,7 +21,8 @@ def build(coords, clouds, points, k):
 
 @pytest.mark.parametrize("clouds,points,dim,k", [(1, 1, 3, 1), (3, 50, 3, 7), (2, 64, 3, 64), (5, 333, 3, 20),
                                                  (4, 1024, 3, 20), (2, 1024, 3, 40), (2, 200, 8, 9),
-                                                 (1, 2048, 3, 33), (3, 130, 1, 5)])
+                                                 (1, 2048, 3, 33), (3, 130, 1, 5), (2, 200, 3, 150), (1, 65, 2, 65),
+                                                 (70, 100, 3, 10)])
 def test_matches_the_oracle_exactly(clouds, points, dim, k):
     print(f"knn: clouds={clouds} points={points} dim={dim} k={k}", flush=True)
     rng = np.random.default_rng(clouds * 1000 + points + k)
