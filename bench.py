@@ -228,9 +228,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--hip-graph", action="store_true",
                     help="record one step into a HIP graph and time its replays (launch-bound small workloads)")
-    ap.add_argument("--gcn-mapping", choices=("vertex", "edge", "tuned"), default="vertex",
-                    help="GCN workloads: thread mapping of the aggregation; 'tuned' times both on the graph "
-                         "first (gnn_gcn_tune) and uses the faster one per side")
+    ap.add_argument("--gcn-mapping", "--mapping", dest="gcn_mapping", choices=("vertex", "edge", "tuned"),
+                    default="vertex",
+                    help="GCN and GMM workloads: thread mapping of the aggregation; 'tuned' times both on the "
+                         "graph first (gnn_gcn_tune / gnn_gmm_tune) and uses the faster one")
     ap.add_argument("--compare-unfused", action="store_true",
                     help="also time the one-operator-per-kernel comparator (GAT with heads*f = 256: forward and "
                          "backward graph operators; EdgeConv and GMM: forward)")
@@ -357,9 +358,17 @@ def main():
             pk.gnn_gmm_fwd(g, fin, F, K, x, w_fc, cc, mu, inv_sigma, hk, out)
             pk.gnn_gmm_bwd(g, fin, F, K, x, w_fc, cc, mu, inv_sigma, hk, gout, gx, gw_fc, gmu, gis, ws)
         unique, gather, flops = gmm_models(n, e, fin, F, K)
+        pk.gnn_config_set("gmm_mapping", {"vertex": 0, "edge": 1, "tuned": 2}[args.gcn_mapping])
+        gmm_tune_ms = None
+        if args.gcn_mapping == "tuned":
+            pk.gnn_gmm_fwd(g, fin, F, K, x, w_fc, cc, mu, inv_sigma, hk, out)
+            t = pk.gnn_gmm_tune(g, F, K, hk, cc, mu, inv_sigma, out)
+            gmm_tune_ms = {"fwd_vertex": round(t[0], 4), "fwd_edge": round(t[1], 4)}
         metric = "fused MoNet/GMM layer fwd+bwd edges/sec"
         cfg = {"in_feat": fin, "out_feat": F, "kernels": K,
-               "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded"}
+               "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded", "mapping": args.gcn_mapping}
+        if gmm_tune_ms:
+            cfg["tune_ms"] = gmm_tune_ms
         gemm_flops = 2.0 * n * fin * K * F
     elif kind == "gcn":
         F = c["fout"]

@@ -121,6 +121,8 @@ gnn_status_t gnn_graph_get_blocked(const gnn_graph_t* graph, int side, int32_t* 
  *   "gcn_mapping"           thread mapping of the GCN aggregation: 0 vertex-balanced,
  *                           1 edge-balanced, 2 (default) what gnn_gcn_tune measured as
  *                           faster on the graph (vertex-balanced if it never ran)
+ *   "gmm_mapping"           the same for the forward aggregation of the GMM layer
+ *                           (gnn_gmm_tune; the edge-balanced mapping takes at most 4 kernels)
  * Errors: INVALID_ARG for an unknown key or a value out of range. */
 gnn_status_t gnn_config_set(const char* key, int64_t value);
 
@@ -235,6 +237,19 @@ gnn_status_t gnn_gmm_bwd(const gnn_graph_t* graph, int fin, int fout, int k, con
                          const float* hk, const float* gout /*[n,fout]*/, float* gx /*nullable*/,
                          float* gw_fc, float* gmu, float* ginv_sigma,
                          void* ws, size_t ws_bytes, void* stream);
+
+/* Profile-driven choice of the thread mapping of the forward aggregation (Sec. 5), as
+ * gnn_gcn_tune: runs the fused Gaussian-weight + aggregate pass on the given tensors (the
+ * ones of a forward call: hk already projected) in the vertex-balanced and in the
+ * edge-balanced mapping (groups own runs of 32 edges, atomic adds between runs, at most 4
+ * kernels), and records the faster one in the graph handle; gnn_gmm_fwd uses it while the
+ * configuration key "gmm_mapping" is 2 (default; 0 / 1 force one).  out holds the layer's
+ * result afterwards.  ms_out (host, nullable): 2 floats, milliseconds per pass
+ * {vertex-balanced, edge-balanced} (zeros when k > 4 or the graph has no edges: nothing to
+ * choose).  Waits for the stream.  Errors: INVALID_ARG, UNSUPPORTED, HIP. */
+gnn_status_t gnn_gmm_tune(gnn_graph_t* graph, int fout, int k, const float* hk /*[n,k*fout]*/,
+                          const float* c, const float* mu, const float* inv_sigma, float* out /*[n,fout]*/,
+                          void* stream, float* ms_out /*host [2], nullable*/);
 
 /* ------------------------------------------------------------------------- *
  * GCN layer with separable static edge weights (App. A.2 "GCN", no bias, identity

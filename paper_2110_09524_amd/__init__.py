@@ -6,7 +6,7 @@ from .binding import (  # noqa: F401
     gnn_config_set, gnn_linear_fwd,
     gnn_gat_workspace_bytes, gnn_gat_fwd, gnn_gat_bwd,
     gnn_edgeconv_workspace_bytes, gnn_edgeconv_fwd, gnn_edgeconv_bwd,
-    gnn_gmm_workspace_bytes, gnn_gmm_fwd, gnn_gmm_bwd,
+    gnn_gmm_workspace_bytes, gnn_gmm_fwd, gnn_gmm_bwd, gnn_gmm_tune,
     gnn_gcn_workspace_bytes, gnn_gcn_fwd, gnn_gcn_bwd, gnn_gcn_tune,
     gnn_bias_act_fwd, gnn_bias_act_workspace_bytes, gnn_bias_act_bwd,
     gnn_softmax_xent_workspace_bytes, gnn_softmax_xent, gnn_sgd_update, gnn_knn_graph,

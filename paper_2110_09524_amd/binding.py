@@ -23,7 +23,7 @@ EXPORTS = [
     "gnn_last_error", "gnn_graph_create", "gnn_graph_destroy", "gnn_graph_get_csc",
     "gnn_graph_get_buckets", "gnn_graph_get_blocked", "gnn_config_set", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
     "gnn_gat_bwd", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
-    "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd",
+    "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd", "gnn_gmm_tune",
     "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_gcn_tune",
     "gnn_bias_act_fwd", "gnn_bias_act_workspace_bytes", "gnn_bias_act_bwd", "gnn_softmax_xent_workspace_bytes",
     "gnn_softmax_xent", "gnn_sgd_update", "gnn_knn_graph", "gnn_prof_enable",
@@ -65,6 +65,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_gmm_workspace_bytes.argtypes = [vp, i32, i32, i32]
     lib.gnn_gmm_fwd.argtypes = [vp, i32, i32, i32] + [vp] * 7 + [vp, sz, vp]
     lib.gnn_gmm_bwd.argtypes = [vp, i32, i32, i32] + [vp] * 11 + [vp, sz, vp]
+    lib.gnn_gmm_tune.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, C.POINTER(C.c_float)]
     lib.gnn_gcn_workspace_bytes.restype = sz
     lib.gnn_gcn_workspace_bytes.argtypes = [vp, i32, i32]
     lib.gnn_gcn_fwd.argtypes = [vp, i32, i32] + [vp] * 6 + [vp]
@@ -263,6 +264,13 @@ def gnn_gcn_tune(g: Graph, fout, ws, stream=None):
     wp, wb = _ws_args(ws)
     ms = (C.c_float * 4)()
     _check(lib().gnn_gcn_tune(g.handle, fout, wp, wb, _stream(stream), ms))
+    return [float(v) for v in ms]
+
+
+def gnn_gmm_tune(g: Graph, fout, k, hk, c, mu, inv_sigma, out, stream=None):
+    """Returns the two measured times (ms): vertex-balanced, edge-balanced forward aggregation."""
+    ms = (C.c_float * 2)()
+    _check(lib().gnn_gmm_tune(g.handle, fout, k, _f(hk), _f(c), _f(mu), _f(inv_sigma), _f(out), _stream(stream), ms))
     return [float(v) for v in ms]
 
 

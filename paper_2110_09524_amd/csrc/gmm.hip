@@ -156,6 +156,134 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd(
     if (slot_ok[j]) st4(out + (int64_t)v * F + 4 * (li + j * L), acc[j]);
 }
 
+// ---- a9, edge-balanced mapping (Sec. 5) ---------------------------------------------------
+// A group owns kGmmEbEdges consecutive positions of the edge array instead of a row: it finds
+// the row of its first edge by bisection of indptr and walks row by row inside its run.  For
+// each row piece the lanes first evaluate the Gaussian weights (lanes = edges), then aggregate
+// (lanes = columns).  A row that lies inside the run is stored, a row that continues into other
+// runs is added atomically onto an output zeroed before (rows of more than two pieces depend
+// on arrival order in the last bits).  At most kGmmKB kernels.
+constexpr int kGmmEbEdges = 32;
+
+__global__ void k_gmm_zero_f4(int64_t quads, float* __restrict__ p) {
+  const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i < quads) st4(p + 4 * i, make_float4(0.f, 0.f, 0.f, 0.f));
+}
+
+template <int L, int NV>
+__global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd_eb(
+    int32_t n, int32_t nnz, const int32_t* __restrict__ indptr, const int32_t* __restrict__ indices,
+    const float* __restrict__ hk, const float* __restrict__ c, const float* __restrict__ mu,
+    const float* __restrict__ inv_sigma, GmmParams pm, float* __restrict__ out) {
+  constexpr int GPB = kGmmBlock / L;
+  constexpr int KB = kGmmKB, U = kGmmU, RUN = kGmmEbEdges;
+  constexpr int GS = (1 + KB) * (RUN + U);  // idx | w[KB], each with U entries of padding
+  __shared__ __align__(16) float lds[GPB * GS];
+  const int lane = threadIdx.x & 63;
+  const int li = lane & (L - 1);
+  const int grp = threadIdx.x / L;
+  const int64_t run = (int64_t)blockIdx.x * GPB + grp;
+  if (run * RUN >= nnz) return;
+  const int32_t e0 = (int32_t)(run * RUN);
+  const int32_t e1 = min(e0 + RUN, nnz);
+  int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
+  float* l_w = lds + grp * GS + (RUN + U);
+  const int K = pm.K, F = pm.F, KF = K * F;
+  const float inv_k = 1.f / (float)K;
+
+  for (int i = li; i < RUN + U; i += L) {
+    l_idx[i] = e0 + i < e1 ? indices[e0 + i] : 0;  // padding gathers row 0 with weight 0
+#pragma unroll
+    for (int q = 0; q < KB; ++q) l_w[q * (RUN + U) + i] = 0.f;
+  }
+  float mu0[KB], mu1[KB], is0[KB], is1[KB];
+#pragma unroll
+  for (int q = 0; q < KB; ++q) {
+    const bool ok = q < K;
+    mu0[q] = ok ? mu[2 * q] : 0.f;
+    mu1[q] = ok ? mu[2 * q + 1] : 0.f;
+    is0[q] = ok ? inv_sigma[2 * q] : 0.f;
+    is1[q] = ok ? inv_sigma[2 * q + 1] : 0.f;
+  }
+  // row of the first edge: indptr[lo] <= e0 < indptr[hi] throughout
+  int32_t lo = 0, hi = n;
+  while (hi - lo > 1) {
+    const int32_t mid = (lo + hi) >> 1;
+    if (indptr[mid] <= e0) lo = mid; else hi = mid;
+  }
+  int32_t v = lo, row_beg = indptr[v], row_end = indptr[v + 1];
+  wave_lds_fence();
+
+  bool slot_ok[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) slot_ok[j] = 4 * (li + j * L) < F;
+
+  int32_t e = e0;
+  while (e < e1) {
+    const int32_t seg_end = min(row_end, e1);
+    const float cv = c[v];
+    // chunk phase: the weights of this row piece (edges outside it keep weight 0 from the start
+    // or get it back below)
+    for (int32_t t = e + li; t < seg_end; t += L) {
+      const float cu = c[l_idx[t - e0]];
+#pragma unroll
+      for (int q = 0; q < KB; ++q)
+        if (q < K) l_w[q * (RUN + U) + (t - e0)] = gauss_w(cu, cv, mu0[q], mu1[q], is0[q], is1[q]) * inv_k;
+    }
+    wave_lds_fence();
+    float4 acc[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int32_t t0 = e; t0 < seg_end; t0 += U) {
+      int uu[U];
+      float ok[U];
+#pragma unroll
+      for (int t = 0; t < U; ++t) {
+        uu[t] = l_idx[t0 - e0 + t];
+        if (L == 64) uu[t] = __builtin_amdgcn_readfirstlane(uu[t]);
+        ok[t] = t0 + t < seg_end ? 1.f : 0.f;  // entries past the piece belong to the next row
+      }
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        if (!slot_ok[j]) continue;
+        float4 rowv[U][KB];
+#pragma unroll
+        for (int t = 0; t < U; ++t)
+#pragma unroll
+          for (int q = 0; q < KB; ++q)
+            if (q < K) rowv[t][q] = ld4(hk + (int64_t)uu[t] * KF + q * F + 4 * (li + j * L));
+#pragma unroll
+        for (int t = 0; t < U; ++t)
+#pragma unroll
+          for (int q = 0; q < KB; ++q)
+            if (q < K) fma4(acc[j], ok[t] * l_w[q * (RUN + U) + (t0 - e0 + t)], rowv[t][q]);
+      }
+    }
+    const bool whole = row_beg >= e0 && row_end <= e1;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      if (!slot_ok[j]) continue;
+      float* o = out + (int64_t)v * F + 4 * (li + j * L);
+      if (whole) {
+        st4(o, acc[j]);
+      } else {
+        unsafeAtomicAdd(o, acc[j].x);
+        unsafeAtomicAdd(o + 1, acc[j].y);
+        unsafeAtomicAdd(o + 2, acc[j].z);
+        unsafeAtomicAdd(o + 3, acc[j].w);
+      }
+    }
+    e = seg_end;
+    if (e < e1) {  // the next row that has edges starts at e
+      do {
+        ++v;
+        row_beg = row_end;
+        row_end = indptr[v + 1];
+      } while (row_end == row_beg);
+    }
+  }
+}
+
 // ---- a10, destination side: gradients of mu and inv_sigma (CSR walk) ------------------
 // partial[block][j][4] = this block's share of (gmu_j0, gmu_j1, gis_j0, gis_j1)
 template <int L, int NV>
@@ -446,6 +574,25 @@ struct GmmFwdLauncher {
   }
 };
 
+template <int L, int NV>
+struct GmmFwdEbLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, const float* hk, const float* c, const float* mu,
+                          const float* is, GmmParams pm, float* out, hipStream_t st) {
+    constexpr int GPB = kGmmBlock / L;
+    ProfScope p("gmm_fwd_fused", st);
+    const int64_t quads = (int64_t)g->n * (pm.F / 4);
+    k_gmm_zero_f4<<<(unsigned)cdiv(quads, 256), 256, 0, st>>>(quads, out);
+    GNN_LAUNCH_CHECK();
+    const int64_t runs = cdiv(g->nnz, kGmmEbEdges);
+    if (runs != 0) {
+      k_gmm_fwd_eb<L, NV><<<(unsigned)cdiv(runs, GPB), kGmmBlock, 0, st>>>(
+          g->n, (int32_t)g->nnz, g->indptr, g->indices, hk, c, mu, is, pm, out);
+      GNN_LAUNCH_CHECK();
+    }
+    return GNN_OK;
+  }
+};
+
 // number of workgroups (= partial slots) the destination-side kernel uses
 template <int L>
 static int64_t gmm_dst_blocks(const gnn_graph_t* g) {
@@ -512,6 +659,21 @@ static gnn_status_t gmm_dispatch(GroupShape gs, Args... args) {
   return GNN_ERR_UNSUPPORTED;
 }
 
+// mapping of the forward aggregation: 0 vertex-balanced, 1 edge-balanced (at most kGmmKB kernels),
+// 2 what gnn_gmm_tune found faster on this graph (vertex-balanced on a graph never tuned)
+static bool gmm_use_edge_balanced(const gnn_graph_t* g, int K) {
+  if (K > kGmmKB) return false;
+  const int64_t mode = config_get(kCfgGmmMapping);
+  if (mode == 1) return true;
+  return mode == 2 && g->gmm_edge_balanced == 1;
+}
+
+static gnn_status_t gmm_aggregate(const gnn_graph_t* g, bool edge_balanced, const float* hk, const float* c,
+                                  const float* mu, const float* is, GmmParams pm, float* out, hipStream_t st) {
+  if (edge_balanced) return gmm_dispatch<GmmFwdEbLauncher>(pick_group(pm.F), g, hk, c, mu, is, pm, out, st);
+  return gmm_dispatch<GmmFwdLauncher>(pick_group(pm.F), g, hk, c, mu, is, pm, out, st);
+}
+
 struct GmmWs {
   size_t total, dhk, partial, gemm;
   int split_k;
@@ -574,7 +736,54 @@ extern "C" gnn_status_t gnn_gmm_fwd(const gnn_graph_t* g, int fin, int fout, int
   hipStream_t st = static_cast<hipStream_t>(stream);
   GNN_TRY(gemm_f32(g->n, k * fout, fin, x, fin, false, w_fc, k * fout, false, hk, k * fout, 1, nullptr, st));
   GmmParams pm{k, fout};
-  return gmm_dispatch<GmmFwdLauncher>(pick_group(fout), g, (const float*)hk, c, mu, inv_sigma, pm, out, st);
+  return gmm_aggregate(g, gmm_use_edge_balanced(g, k), hk, c, mu, inv_sigma, pm, out, st);
+}
+
+extern "C" gnn_status_t gnn_gmm_tune(gnn_graph_t* g, int fout, int k, const float* hk, const float* c,
+                                     const float* mu, const float* inv_sigma, float* out, void* stream,
+                                     float* ms_out) {
+  clear_error();
+  GNN_TRY(gmm_check(g, 1, fout, k, "gnn_gmm_tune"));
+  float ms[2] = {0.f, 0.f};
+  if (g->n != 0 && g->nnz != 0 && k <= kGmmKB) {
+    GNN_REQUIRE(hk && c && mu && inv_sigma && out, GNN_ERR_INVALID_ARG, "gnn_gmm_tune: null pointer");
+    GNN_REQUIRE(aligned16(hk) && aligned16(out), GNN_ERR_INVALID_ARG,
+                "gnn_gmm_tune: hk, out must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipEvent_t a = nullptr, b = nullptr;
+    GNN_HIP(hipEventCreate(&a));
+    if (hipEventCreate(&b) != hipSuccess) {
+      (void)hipEventDestroy(a);
+      set_error("gnn_gmm_tune: hipEventCreate failed");
+      return GNN_ERR_HIP;
+    }
+    constexpr int kReps = 3;
+    GmmParams pm{k, fout};
+    gnn_status_t status = GNN_OK;
+    for (int eb = 0; eb < 2 && status == GNN_OK; ++eb) {
+      status = gmm_aggregate(g, eb != 0, hk, c, mu, inv_sigma, pm, out, st);  // warm-up
+      if (status == GNN_OK && hipEventRecord(a, st) != hipSuccess) status = GNN_ERR_HIP;
+      for (int r = 0; r < kReps && status == GNN_OK; ++r)
+        status = gmm_aggregate(g, eb != 0, hk, c, mu, inv_sigma, pm, out, st);
+      if (status == GNN_OK && (hipEventRecord(b, st) != hipSuccess || hipEventSynchronize(b) != hipSuccess))
+        status = GNN_ERR_HIP;
+      float t = 0.f;
+      if (status == GNN_OK && hipEventElapsedTime(&t, a, b) != hipSuccess) status = GNN_ERR_HIP;
+      ms[eb] = t / kReps;
+    }
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    if (status != GNN_OK) {
+      if (status == GNN_ERR_HIP && gnn_last_error()[0] == 0) set_error("gnn_gmm_tune: a HIP event call failed");
+      return status;
+    }
+    g->gmm_edge_balanced = ms[1] < ms[0] ? 1 : 0;
+  }
+  if (ms_out) {
+    ms_out[0] = ms[0];
+    ms_out[1] = ms[1];
+  }
+  return GNN_OK;
 }
 
 extern "C" gnn_status_t gnn_gmm_bwd(const gnn_graph_t* g, int fin, int fout, int k, const float* x,

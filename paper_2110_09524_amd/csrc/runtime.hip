@@ -28,7 +28,8 @@ void clear_error() { g_err[0] = 0; }
 // lds_scalar_table: 1 lets the blocked destination-side kernels keep a block's el table in LDS
 // gcn_mapping: thread mapping of the GCN aggregation, 0 vertex-balanced, 1 edge-balanced,
 // 2 (default) per graph what gnn_gcn_tune measured, vertex-balanced where it never ran
-static std::atomic<int64_t> g_config[kCfgCount] = {{24576}, {0}, {1}, {2}};
+// gmm_mapping: the same for the forward aggregation of the GMM layer (gnn_gmm_tune)
+static std::atomic<int64_t> g_config[kCfgCount] = {{24576}, {0}, {1}, {2}, {2}};
 int64_t config_get(ConfigKey k) { return g_config[k].load(std::memory_order_relaxed); }
 
 // ---- profiling ---------------------------------------------------------------
@@ -113,6 +114,11 @@ extern "C" gnn_status_t gnn_config_set(const char* key, int64_t value) {
   if (std::strcmp(key, "gcn_mapping") == 0) {
     GNN_REQUIRE(value >= 0 && value <= 2, GNN_ERR_INVALID_ARG, "gnn_config_set: gcn_mapping must be 0, 1 or 2");
     g_config[kCfgGcnMapping].store(value);
+    return GNN_OK;
+  }
+  if (std::strcmp(key, "gmm_mapping") == 0) {
+    GNN_REQUIRE(value >= 0 && value <= 2, GNN_ERR_INVALID_ARG, "gnn_config_set: gmm_mapping must be 0, 1 or 2");
+    g_config[kCfgGmmMapping].store(value);
     return GNN_OK;
   }
   set_error("gnn_config_set: unknown key '%s'", key);

@@ -66,3 +66,63 @@ def test_empty_rows_and_hub():
     edges += [(int(rng.integers(0, n)), int(v)) for v in range(10, n) for _ in range(2)]
     indptr, indices = tiny_graph(n, edges)
     check(synth(rng, indptr, indices, 10, 32, 3))
+
+
+# ---- edge-balanced forward mapping (Sec. 5) and the profile-driven choice ------------------
+@pytest.fixture
+def edge_balanced():
+    import paper_2110_09524_amd as pk
+    pk.gnn_config_set("gmm_mapping", 1)
+    yield
+    pk.gnn_config_set("gmm_mapping", 2)
+
+
+@pytest.mark.parametrize("name", ["gmm_c5_mid", "gmm_c5"])
+def test_edge_balanced_workloads(edge_balanced, name):
+    print("gmm: edge-balanced", name, flush=True)
+    check(make(name))
+
+
+@pytest.mark.parametrize("fin,fout,K", [(5, 16, 1), (9, 16, 4), (64, 64, 3), (6, 4, 2), (7, 256, 3), (20, 24, 2),
+                                        (12, 32, 8)])   # K = 8 > 4: stays vertex-balanced
+def test_edge_balanced_shapes(edge_balanced, fin, fout, K):
+    print(f"gmm: edge-balanced shape {fin}->{fout} K={K}", flush=True)
+    rng = np.random.default_rng(fin + fout + K + 1)
+    indptr, indices = random_graph(rng, 263, 2601, self_loops=True, duplicates=True)
+    check(synth(rng, indptr, indices, fin, fout, K))
+
+
+def test_edge_balanced_empty_rows_and_a_row_spanning_many_runs(edge_balanced):
+    print("gmm: edge-balanced hub + empty rows", flush=True)
+    rng = np.random.default_rng(77)
+    n = 400
+    edges = [(u, 3) for u in range(n)]                       # row 3 spans 13 runs of 32
+    edges += [(int(rng.integers(0, n)), 7) for _ in range(32 - (n % 32))]   # row 7 ends on a run boundary
+    edges += [(int(rng.integers(0, n)), int(v)) for v in range(30, n) for _ in range(int(v) % 4)]
+    indptr, indices = tiny_graph(n, edges)
+    assert (np.diff(indptr) == 0).any() and len(indices) % 32 != 0
+    check(synth(rng, indptr, indices, 10, 32, 3))
+    check(synth(rng, np.zeros(n + 1, dtype=np.int32), np.zeros(0, dtype=np.int32), 6, 16, 3))
+
+
+def test_tune_records_a_choice_and_results_stay_right():
+    import torch
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev, empty
+    print("gmm: tune", flush=True)
+    c = make("gmm_c5_mid")
+    n, fin, fout, K = c["n"], c["fin"], c["fout"], c["k"]
+    g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
+    x, w_fc, cc, mu, isg = dev(c["x"]), dev(c["w_fc"]), dev(c["c"]), dev(c["mu"]), dev(c["inv_sigma"])
+    hk, out = empty((n, K * fout)), empty((n, fout))
+    pk.gnn_gmm_fwd(g, fin, fout, K, x, w_fc, cc, mu, isg, hk, out)
+    ms = pk.gnn_gmm_tune(g, fout, K, hk, cc, mu, isg, out)
+    assert len(ms) == 2 and all(t > 0 for t in ms)
+    ref = om.gmm_forward(c["indptr"], c["indices"], c["x"], c["w_fc"], c["c"], c["mu"], c["inv_sigma"])["out"]
+    np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-4, atol=1e-5)     # the tuner leaves the result
+    pk.gnn_gmm_fwd(g, fin, fout, K, x, w_fc, cc, mu, isg, hk, out)                # the recorded mapping
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-4, atol=1e-5)
+    with pytest.raises(pk.GnnError):
+        pk.gnn_config_set("gmm_mapping", 5)
+    g.close()
