@@ -232,6 +232,12 @@ def main():
                     default="vertex",
                     help="GCN and GMM workloads: thread mapping of the aggregation; 'tuned' times both on the "
                          "graph first (gnn_gcn_tune / gnn_gmm_tune) and uses the faster one")
+    ap.add_argument("--arm", choices=("vertex_stash", "recompute", "edge_stash"), default="vertex_stash",
+                    help="GAT workloads, the recomputation study: vertex_stash (default: forward stashes the "
+                         "vertex-sized sums t, sg), recompute (nothing but m, d is kept; one more edge pass in "
+                         "backward), edge_stash (per-edge softmax values stored after forward and read back)")
+    ap.add_argument("--single-launch", action="store_true",
+                    help="use the single-launch kernels also where the column-blocked ones apply")
     ap.add_argument("--compare-unfused", action="store_true",
                     help="also time the one-operator-per-kernel comparator (GAT with heads*f = 256: forward and "
                          "backward graph operators; EdgeConv and GMM: forward)")
@@ -266,6 +272,8 @@ def main():
     torch.cuda.synchronize()
     del cal_src, cal_dst
 
+    if args.single_launch:
+        pk.gnn_config_set("force_simple_kernels", 1)
     t0 = time.perf_counter()
     g = pk.Graph(indptr, indices)
     torch.cuda.synchronize()
@@ -307,13 +315,25 @@ def main():
         ws_bytes = pk.gnn_gat_workspace_bytes(g, fin, H, F)
         ws = new(max(ws_bytes, 16), dtype=torch.uint8)
 
+        if args.arm == "recompute":
+            t, sg = None, None
+        alpha_t = new(e, H) if args.arm == "edge_stash" else None
+
         def step():
             pk.gnn_gat_fwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, t, sg, ws)
-            pk.gnn_gat_bwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, t, sg, gout,
-                           gx, gw, ga_l, ga_r, ws)
+            if alpha_t is None:
+                pk.gnn_gat_bwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, t, sg, gout,
+                               gx, gw, ga_l, ga_r, ws)
+            else:
+                pk.gnn_gat_stash_alpha(g, H, c["slope"], el, er, m, d, alpha_t)
+                pk.gnn_gat_bwd_stashed(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, t, sg,
+                                       alpha_t, gout, gx, gw, ga_l, ga_r, ws)
         unique, gather, flops = gat_models(n, e, fin, H, F)
         metric = "fused GAT layer fwd+bwd edges/sec"
-        cfg = {"in_feat": fin, "heads": H, "hidden_per_head": F,
+        saved = 4 * (3 * n * HF + 4 * n * H) + (4 * (n * HF + n * H) if t is not None else 0) \
+            + (4 * e * H if alpha_t is not None else 0)
+        cfg = {"in_feat": fin, "heads": H, "hidden_per_head": F, "arm": args.arm,
+               "single_launch_kernels": bool(args.single_launch), "saved_for_backward_bytes": saved,
                "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded"}
         gemm_flops = 2.0 * n * fin * HF
     elif kind == "edgeconv":

@@ -184,6 +184,27 @@ gnn_status_t gnn_gat_bwd(const gnn_graph_t* graph, int fin, int heads, int f, fl
                          float* gx /*nullable*/, float* gw, float* ga_l, float* ga_r,
                          void* ws, size_t ws_bytes, void* stream);
 
+/* The "fusion with stashing" arm of the recomputation study (Sec. 7.3): the fused kernels, but
+ * the per-edge softmax values are stored after the forward pass and read back in the
+ * backward pass instead of being recomputed.  Kept for that comparison; it needs O(|E|)
+ * memory, which the default path avoids.
+ * gnn_gat_stash_alpha: alpha_t [nnz, heads] in the order of the plan's CSC transpose
+ *   (position p = p-th edge in (source, CSR position) order), value = softmax weight of the
+ *   edge with the sign of its raw score (negative: LeakyReLU' = slope).  Call after
+ *   gnn_gat_fwd (needs el, er, m, d).
+ * gnn_gat_bwd_stashed: as gnn_gat_bwd, with the source side reading alpha_t; it always uses
+ *   the single-launch kernels (the stash is laid out for them). */
+gnn_status_t gnn_gat_stash_alpha(const gnn_graph_t* graph, int heads, float slope, const float* el,
+                                 const float* er, const float* m, const float* d,
+                                 float* alpha_t /*[nnz,heads]*/, void* stream);
+gnn_status_t gnn_gat_bwd_stashed(const gnn_graph_t* graph, int fin, int heads, int f, float slope,
+                                 const float* x, const float* w, const float* a_l, const float* a_r,
+                                 const float* z, const float* el, const float* er, const float* m,
+                                 const float* d, const float* out, const float* t /*nullable*/,
+                                 const float* sg /*nullable*/, const float* alpha_t /*[nnz,heads]*/,
+                                 const float* gout, float* gx /*nullable*/, float* gw, float* ga_l,
+                                 float* ga_r, void* ws, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------------------------- *
  * EdgeConv layer (App. A.2 "EdgeConv"), in the reorganized form of Sec. 4:
  * Theta(h_u - h_v) + Phi h_v = (x Theta)[u] + (x (Phi - Theta))[v].

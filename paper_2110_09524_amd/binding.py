@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "GNN_OK", 1: "GNN_ERR_INVALID_ARG", 2: "GNN_ERR_BAD_GRAPH",
 EXPORTS = [
     "gnn_last_error", "gnn_graph_create", "gnn_graph_destroy", "gnn_graph_get_csc",
     "gnn_graph_get_buckets", "gnn_graph_get_blocked", "gnn_config_set", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
-    "gnn_gat_bwd", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
+    "gnn_gat_bwd", "gnn_gat_stash_alpha", "gnn_gat_bwd_stashed", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
     "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd", "gnn_gmm_tune",
     "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_gcn_tune",
     "gnn_bias_act_fwd", "gnn_bias_act_workspace_bytes", "gnn_bias_act_bwd", "gnn_softmax_xent_workspace_bytes",
@@ -57,6 +57,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_gat_workspace_bytes.argtypes = [vp, i32, i32, i32]
     lib.gnn_gat_fwd.argtypes = [vp, i32, i32, i32, f32] + [vp] * 12 + [vp, sz, vp]
     lib.gnn_gat_bwd.argtypes = [vp, i32, i32, i32, f32] + [vp] * 17 + [vp, sz, vp]
+    lib.gnn_gat_stash_alpha.argtypes = [vp, i32, f32] + [vp] * 5 + [vp]
+    lib.gnn_gat_bwd_stashed.argtypes = [vp, i32, i32, i32, f32] + [vp] * 18 + [vp, sz, vp]
     lib.gnn_edgeconv_workspace_bytes.restype = sz
     lib.gnn_edgeconv_workspace_bytes.argtypes = [vp, i32, i32]
     lib.gnn_edgeconv_fwd.argtypes = [vp, i32, i32] + [vp] * 6 + [vp, sz, vp]
@@ -225,6 +227,19 @@ def gnn_gat_bwd(g: Graph, fin, heads, f, slope, x, w, a_l, a_r, z, el, er, m, d,
     _check(lib().gnn_gat_bwd(g.handle, fin, heads, f, slope, _f(x), _f(w), _f(a_l), _f(a_r), _f(z),
                              _f(el), _f(er), _f(m), _f(d), _f(out), _f(t), _f(sg), _f(gout), _f(gx),
                              _f(gw), _f(ga_l), _f(ga_r), wp, wb, _stream(stream)))
+
+
+def gnn_gat_stash_alpha(g: Graph, heads, slope, el, er, m, d, alpha_t, stream=None):
+    _check(lib().gnn_gat_stash_alpha(g.handle, heads, slope, _f(el), _f(er), _f(m), _f(d), _f(alpha_t),
+                                     _stream(stream)))
+
+
+def gnn_gat_bwd_stashed(g: Graph, fin, heads, f, slope, x, w, a_l, a_r, z, el, er, m, d, out, t, sg, alpha_t,
+                        gout, gx, gw, ga_l, ga_r, ws, stream=None):
+    wp, wb = _ws_args(ws)
+    _check(lib().gnn_gat_bwd_stashed(g.handle, fin, heads, f, slope, _f(x), _f(w), _f(a_l), _f(a_r), _f(z),
+                                     _f(el), _f(er), _f(m), _f(d), _f(out), _f(t), _f(sg), _f(alpha_t),
+                                     _f(gout), _f(gx), _f(gw), _f(ga_l), _f(ga_r), wp, wb, _stream(stream)))
 
 
 def gnn_edgeconv_workspace_bytes(g: Graph, fin, fout) -> int:

@@ -407,7 +407,8 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
     const int32_t* __restrict__ indices_t, const float* __restrict__ z, const float* __restrict__ el,
     const float4* __restrict__ vstate, const float* __restrict__ der, const float* __restrict__ gout,
     const float* __restrict__ a_l, const float* __restrict__ a_r, GatDims dm,
-    float* __restrict__ dz, float* __restrict__ del) {
+    float* __restrict__ dz, float* __restrict__ del,
+    const float* __restrict__ alpha_t /* nullable: stashed softmax values, CSC order, signed */) {
   constexpr int G = kWave / L;
   constexpr int GPB = G * (kBlock / kWave);
   constexpr int NC = 8 * NV + 1;
@@ -459,9 +460,15 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
     float alpha = 0.f, ag = 0.f;
     if (e_ok && head_ok) {
       const float4 vs = vstate[(int64_t)v * H + h];  // (er, m, 1/d, D)
-      const float raw = el_uh + vs.x;
-      alpha = __expf(leaky(raw, dm.slope) - vs.y) * vs.z;
-      ag = raw > 0.f ? alpha : dm.slope * alpha;
+      if (alpha_t) {  // the "fusion with stashing" arm: nothing per-edge is recomputed
+        const float a = alpha_t[(int64_t)e * H + h];
+        alpha = fabsf(a);
+        ag = signbit(a) ? dm.slope * alpha : alpha;
+      } else {
+        const float raw = el_uh + vs.x;
+        alpha = __expf(leaky(raw, dm.slope) - vs.y) * vs.z;
+        ag = raw > 0.f ? alpha : dm.slope * alpha;
+      }
       sd_run = fmaf(ag, vs.w, sd_run);
     }
     if (h == 0) l_idx[e_loc] = v;
@@ -840,7 +847,7 @@ template <int L, int NV>
 struct BwdSrcLauncher {
   static gnn_status_t run(const gnn_graph_t* g, const float* z, const float* el, const float4* vstate,
                           const float* der, const float* gout, const float* a_l, const float* a_r,
-                          GatDims dm, float* dz, float* del, hipStream_t st) {
+                          GatDims dm, float* dz, float* del, const float* alpha_t, hipStream_t st) {
     constexpr int GPB = (kWave / L) * (kBlock / kWave);
     ProfScope p("gat_bwd_src", st);
     const RowSplit sp = split_rows(g, 1, L >> dm.log2Hp, GPB);
@@ -849,7 +856,7 @@ struct BwdSrcLauncher {
     const RowLaunch rl{sp.hub.end, g->n};
     if (grid != 0) {
       k_gat_bwd_src<L, NV><<<grid, kBlock, 0, st>>>(rl, g->order[1], g->indptr_t, g->indices_t, z, el,
-                                                    vstate, der, gout, a_l, a_r, dm, dz, del);
+                                                    vstate, der, gout, a_l, a_r, dm, dz, del, alpha_t);
       GNN_LAUNCH_CHECK();
     }
     return GNN_OK;
@@ -869,6 +876,35 @@ gnn_status_t gat_src_finish(const gnn_graph_t* g, GatDims dm, const float* z, co
   return dispatch_group<SrcFinishLauncher>(pick_group(dm.HF), g, z, a2, sd, der, a_l, a_r, dm, dz, del,
                                            st);
 }
+
+
+// ---- the per-edge stash of the "fusion with stashing" arm (Sec. 7.3, recomputation study) ----
+// alpha_t[p, h] for CSC position p: the softmax value of that edge, carrying the sign of the
+// raw score (the only other per-edge fact the backward pass needs: LeakyReLU' is 1 or slope).
+// One thread per (position, head); the edge's source comes from the plan's position -> CSR
+// edge id table.
+__global__ void k_gat_stash_alpha(int64_t count, int H, float slope, const int32_t* __restrict__ indices,
+                                  const int32_t* __restrict__ indices_t, const int32_t* __restrict__ eid_t,
+                                  const float* __restrict__ el, const float* __restrict__ er,
+                                  const float* __restrict__ m, const float* __restrict__ d,
+                                  float* __restrict__ alpha_t) {
+  const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i >= count) return;
+  const int64_t p = i / H;
+  const int h = (int)(i - p * H);
+  const int32_t v = indices_t[p];
+  const int32_t u = indices[eid_t[p]];
+  const float raw = el[(int64_t)u * H + h] + er[(int64_t)v * H + h];
+  const float a = __expf(leaky(raw, slope) - m[(int64_t)v * H + h]) / d[(int64_t)v * H + h];
+  alpha_t[i] = raw > 0.f ? a : -a;
+}
+
+static gnn_status_t gat_bwd_impl(const char* who, const gnn_graph_t* g, int fin, int heads, int f, float slope,
+                                 const float* x, const float* w, const float* a_l, const float* a_r,
+                                 const float* z, const float* el, const float* er, const float* m,
+                                 const float* d, const float* out, const float* t, const float* sg,
+                                 const float* alpha_t, const float* gout, float* gx, float* gw, float* ga_l,
+                                 float* ga_r, void* ws, size_t ws_bytes, void* stream);
 
 }  // namespace gnn
 
@@ -926,22 +962,66 @@ extern "C" gnn_status_t gnn_gat_bwd(const gnn_graph_t* g, int fin, int heads, in
                                     const float* d, const float* out, const float* t, const float* sg,
                                     const float* gout, float* gx, float* gw, float* ga_l, float* ga_r,
                                     void* ws, size_t ws_bytes, void* stream) {
+  return gat_bwd_impl("gnn_gat_bwd", g, fin, heads, f, slope, x, w, a_l, a_r, z, el, er, m, d, out, t, sg,
+                      nullptr, gout, gx, gw, ga_l, ga_r, ws, ws_bytes, stream);
+}
+
+extern "C" gnn_status_t gnn_gat_stash_alpha(const gnn_graph_t* g, int heads, float slope, const float* el,
+                                            const float* er, const float* m, const float* d, float* alpha_t,
+                                            void* stream) {
   clear_error();
-  GNN_TRY(check_gat_dims(g, fin, heads, f, "gnn_gat_bwd"));
+  GNN_REQUIRE(g != nullptr, GNN_ERR_INVALID_ARG, "gnn_gat_stash_alpha: graph is null");
+  GNN_REQUIRE(heads > 0 && heads <= 64, GNN_ERR_INVALID_ARG, "gnn_gat_stash_alpha: heads out of range");
+  if (g->nnz == 0) return GNN_OK;
+  GNN_REQUIRE(el && er && m && d && alpha_t, GNN_ERR_INVALID_ARG, "gnn_gat_stash_alpha: null pointer");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  ProfScope p("gat_stash_alpha", st);
+  const int64_t count = g->nnz * heads;
+  k_gat_stash_alpha<<<(unsigned)cdiv(count, 256), 256, 0, st>>>(count, heads, slope, g->indices, g->indices_t,
+                                                               g->eid_t, el, er, m, d, alpha_t);
+  GNN_LAUNCH_CHECK();
+  return GNN_OK;
+}
+
+extern "C" gnn_status_t gnn_gat_bwd_stashed(const gnn_graph_t* g, int fin, int heads, int f, float slope,
+                                            const float* x, const float* w, const float* a_l,
+                                            const float* a_r, const float* z, const float* el,
+                                            const float* er, const float* m, const float* d, const float* out,
+                                            const float* t, const float* sg, const float* alpha_t,
+                                            const float* gout, float* gx, float* gw, float* ga_l, float* ga_r,
+                                            void* ws, size_t ws_bytes, void* stream) {
+  if (g != nullptr && g->nnz != 0 && alpha_t == nullptr) {
+    clear_error();
+    set_error("gnn_gat_bwd_stashed: alpha_t is null");
+    return GNN_ERR_INVALID_ARG;
+  }
+  return gat_bwd_impl("gnn_gat_bwd_stashed", g, fin, heads, f, slope, x, w, a_l, a_r, z, el, er, m, d, out, t, sg,
+                      alpha_t, gout, gx, gw, ga_l, ga_r, ws, ws_bytes, stream);
+}
+
+namespace gnn {
+static gnn_status_t gat_bwd_impl(const char* who, const gnn_graph_t* g, int fin, int heads, int f, float slope,
+                                 const float* x, const float* w, const float* a_l, const float* a_r,
+                                 const float* z, const float* el, const float* er, const float* m,
+                                 const float* d, const float* out, const float* t, const float* sg,
+                                 const float* alpha_t, const float* gout, float* gx, float* gw, float* ga_l,
+                                 float* ga_r, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  GNN_TRY(check_gat_dims(g, fin, heads, f, who));
   GNN_REQUIRE((t == nullptr) == (sg == nullptr), GNN_ERR_INVALID_ARG,
-              "gnn_gat_bwd: t and sg must be given together");
-  GNN_REQUIRE(t == nullptr || aligned16(t), GNN_ERR_INVALID_ARG, "gnn_gat_bwd: t must be 16-byte aligned");
+              "%s: t and sg must be given together", who);
+  GNN_REQUIRE(t == nullptr || aligned16(t), GNN_ERR_INVALID_ARG, "%s: t must be 16-byte aligned", who);
   if (g->n == 0) return GNN_OK;
   GNN_REQUIRE(x && w && a_l && a_r && z && el && er && m && d && out && gout && gw && ga_l && ga_r,
-              GNN_ERR_INVALID_ARG, "gnn_gat_bwd: null pointer");
+              GNN_ERR_INVALID_ARG, "%s: null pointer", who);
   GNN_REQUIRE(aligned16(z) && aligned16(out) && aligned16(gout) && aligned16(a_l) && aligned16(a_r),
-              GNN_ERR_INVALID_ARG, "gnn_gat_bwd: z, out, gout, a_l, a_r must be 16-byte aligned");
+              GNN_ERR_INVALID_ARG, "%s: z, out, gout, a_l, a_r must be 16-byte aligned", who);
   const int64_t n = g->n;
   const int HF = heads * f;
   const GatWs L = gat_ws_layout(g, fin, heads, f);
   GNN_REQUIRE(ws != nullptr && ws_bytes >= L.total, GNN_ERR_WORKSPACE,
-              "gnn_gat_bwd: workspace of %zu bytes given, %zu needed", ws_bytes, L.total);
-  GNN_REQUIRE(aligned16(ws), GNN_ERR_INVALID_ARG, "gnn_gat_bwd: workspace must be 16-byte aligned");
+              "%s: workspace of %zu bytes given, %zu needed", who, ws_bytes, L.total);
+  GNN_REQUIRE(aligned16(ws), GNN_ERR_INVALID_ARG, "%s: workspace must be 16-byte aligned", who);
   char* base = static_cast<char*>(ws);
   float* dz = reinterpret_cast<float*>(base + L.dz);
   float4* vstate = reinterpret_cast<float4*>(base + L.vstate);
@@ -953,7 +1033,8 @@ extern "C" gnn_status_t gnn_gat_bwd(const gnn_graph_t* g, int fin, int heads, in
   const GatDims dm = make_dims(heads, f, slope);
   const GroupShape gs = pick_group(HF);
 
-  const bool blocked = gat_blocked_applies(g, heads, f);
+  // the per-edge stash is laid out for the single-launch source-side kernel
+  const bool blocked = alpha_t == nullptr && gat_blocked_applies(g, heads, f);
   // a4: destination side.  With t and sg stashed by the forward call it is a vertex pass;
   // without them the sums are recomputed over the in-edges.
   if (t) {
@@ -976,7 +1057,7 @@ extern "C" gnn_status_t gnn_gat_bwd(const gnn_graph_t* g, int fin, int heads, in
   } else {
     // a5: source side
     GNN_TRY(dispatch_group<BwdSrcLauncher>(gs, g, z, el, (const float4*)vstate, (const float*)der,
-                                           gout, a_l, a_r, dm, dz, del, st));
+                                           gout, a_l, a_r, dm, dz, del, alpha_t, st));
   }
   // a6: parameter gradients
   {
@@ -994,3 +1075,4 @@ extern "C" gnn_status_t gnn_gat_bwd(const gnn_graph_t* g, int fin, int heads, in
   if (gx) GNN_TRY(gemm_f32(n, fin, HF, dz, HF, false, w, HF, true, gx, fin, 1, nullptr, st));
   return GNN_OK;
 }
+}  // namespace gnn

@@ -82,9 +82,11 @@ def gat_kink_masks(indptr, fwd, tol=1e-5):
     return amb_vh, amb_vertex
 
 
-def run_gat(c, backward=True, want_gx=True, graph=None, stash=True):
+def run_gat(c, backward=True, want_gx=True, graph=None, stash=True, alpha_stash=False):
     """stash=True: the forward call writes t and sg and the backward call uses them;
-    stash=False: the backward call recomputes them over the in-edges."""
+    stash=False: the backward call recomputes them over the in-edges.
+    alpha_stash=True: the per-edge softmax values are stored after the forward call and the
+    backward call reads them back (gnn_gat_stash_alpha + gnn_gat_bwd_stashed)."""
     n, fin, H, F = c["n"], c["fin"], c["heads"], c["f"]
     HF = H * F
     indptr, indices = dev(c["indptr"]), dev(c["indices"])
@@ -99,13 +101,22 @@ def run_gat(c, backward=True, want_gx=True, graph=None, stash=True):
     res = dict(z=z, el=el, er=er, m=m, d=d, out=out)
     if stash:
         res.update(t=t, sg=sg)
+    alpha_t = None
+    if alpha_stash:
+        alpha_t = empty((max(len(c["indices"]), 1), H))
+        pk.gnn_gat_stash_alpha(g, H, c["slope"], el, er, m, d, alpha_t)
+        res["alpha_t"] = alpha_t
     if backward:
         gout = dev(c["gout"])
         ws.fill_(0xFF)      # nothing may survive in the workspace between the two calls
         gx = empty((n, fin)) if want_gx else None
         gw, ga_l, ga_r = empty((fin, HF)), empty((H, F)), empty((H, F))
-        pk.gnn_gat_bwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, t, sg, gout,
-                       gx, gw, ga_l, ga_r, ws)
+        if alpha_stash:
+            pk.gnn_gat_bwd_stashed(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, t, sg,
+                                   alpha_t, gout, gx, gw, ga_l, ga_r, ws)
+        else:
+            pk.gnn_gat_bwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, t, sg, gout,
+                           gx, gw, ga_l, ga_r, ws)
         res.update(gw=gw, ga_l=ga_l, ga_r=ga_r)
         if want_gx:
             res["gx"] = gx

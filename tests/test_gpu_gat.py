@@ -329,3 +329,46 @@ def test_many_vertices_few_edges_on_the_blocked_path():
     assert (res["out"][n // 2:] == 0).all()
     compare(c, run_gat(c, graph=g, stash=False), fwd, bwd)
     g.close()
+
+
+@pytest.mark.parametrize("stash", [True, False])
+@pytest.mark.parametrize("name", ["gat_c2", "gat_c4_mid"])
+def test_fusion_with_stashing_arm(name, stash):
+    """The per-edge softmax values stored after the forward pass (CSC order, signed by the raw
+    score) equal the oracle's materialised M2, and the backward pass that reads them back gives
+    the oracle's gradients."""
+    from gpu_harness import assert_close, run_gat
+    print(f"gat: fusion with stashing {name} vertex-stash={stash}", flush=True)
+    c = make(name)
+    fwd, bwd = oracle_all(c)
+    res = run_gat(c, stash=stash, alpha_stash=True)
+    # CSC order: edges by (source, CSR position)
+    order = np.lexsort((np.arange(c["nnz"]), c["indices"]))
+    ref = (fwd["M2"] * np.where(fwd["M0"] > 0, 1.0, -1.0))[order]
+    got = res.pop("alpha_t")[:c["nnz"]]
+    near_kink = np.abs(fwd["M0"][order]) < 1e-5
+    assert_close("alpha_t", np.where(near_kink, ref, got), ref)
+    compare(c, res, fwd, bwd)
+
+
+def test_fusion_with_stashing_arm_on_a_column_blocked_graph_and_bad_arguments():
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev, empty, run_gat
+    rng = np.random.default_rng(321)
+    indptr, indices = random_graph(rng, 1500, 30000, self_loops=False, duplicates=True)
+    c = synth(rng, indptr, indices, 24, 4, 64)
+    fwd, bwd = oracle_all(c)
+    pk.gnn_config_set("block_cols", 256)
+    try:
+        g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
+        res = run_gat(c, graph=g, alpha_stash=True)      # forward blocked, stashed backward single-launch
+    finally:
+        pk.gnn_config_set("block_cols", 24576)
+    res.pop("alpha_t")
+    compare(c, res, fwd, bwd)
+    a = empty((4, 4))
+    with pytest.raises(pk.GnnError) as e:
+        pk.gnn_gat_bwd_stashed(g, 24, 4, 64, 0.2, a, a, a, a, a, a, a, a, a, a, None, None, None, a, None, a, a, a,
+                               None)
+    assert e.value.status == 1
+    g.close()
