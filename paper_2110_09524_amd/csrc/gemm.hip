@@ -159,9 +159,16 @@ __global__ void k_sum_partials(int64_t count, int splits, int64_t stride,
                                const float* __restrict__ partials, float* __restrict__ c) {
   int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
   if (i >= count) return;
-  float s = 0.f;
-  for (int z = 0; z < splits; ++z) s += partials[(int64_t)z * stride + i];
-  c[i] = s;
+  // four interleaved running sums keep four loads in flight; their order is fixed
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int z = 0;
+  for (; z + 4 <= splits; z += 4) {
+    const float* p = partials + (int64_t)z * stride + i;
+    const float v0 = p[0], v1 = p[stride], v2 = p[2 * stride], v3 = p[3 * stride];
+    s0 += v0; s1 += v1; s2 += v2; s3 += v3;
+  }
+  for (; z < splits; ++z) s0 += partials[(int64_t)z * stride + i];
+  c[i] = (s0 + s1) + (s2 + s3);
 }
 
 // Same sum for short outputs and many parts: 8 threads share one output element, each

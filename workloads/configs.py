@@ -151,6 +151,15 @@ def _make_ec_k40(seed):
     return _edgeconv("ec_k40", 64, 1024, 40, 64, 64, seed)
 
 
+def _make_ec_l3(seed):
+    # third and fourth layer widths of the four-layer EdgeConv model (Sec. 7.2: {64, 64, 128, 256})
+    return _edgeconv("ec_l3", 64, 1024, 40, 64, 128, seed)
+
+
+def _make_ec_l4(seed):
+    return _edgeconv("ec_l4", 64, 1024, 40, 128, 256, seed)
+
+
 def _make_ec_k40_mid(seed):
     return _edgeconv("ec_k40_mid", 3, 400, 40, 64, 128, seed)
 
@@ -217,6 +226,8 @@ _MAKERS = {
     "gmm_c5_mid": (105, _make_gmm_c5_mid),
     "ec_k40": (7, _make_ec_k40),
     "ec_k40_mid": (107, _make_ec_k40_mid),
+    "ec_l3": (11, _make_ec_l3),
+    "ec_l4": (12, _make_ec_l4),
     "gcn_c4": (6, _make_gcn_c4),
     "gcn_mid": (106, _make_gcn_mid),
     "gcn_c5": (8, _make_gcn_c5),
