@@ -199,6 +199,24 @@ def cpu_baseline_gat2(c, sample_vertices=8192):
             "measured_s": dt}
 
 
+def cpu_baseline_ec2(c, sample_clouds=2):
+    """Two-layer EdgeConv step incl. the neighbour search: the oracle on the first clouds of the batch."""
+    from oracle import knn as ok
+    from oracle import two_layer as ot
+    m = min(sample_clouds, c["clouds"]) * c["points"]
+    t0 = time.perf_counter()
+    ip, ix = ok.knn_graph(c["coords"][:m], m // c["points"], c["points"], c["k"])
+    fwd = ot.two_layer_forward("edgeconv", ip, ix, c["x"][:m], c["p1"], c["b1"], c["p2"], c["b2"], {},
+                               c["labels"][:m], "leaky", 0.2)
+    ot.two_layer_backward("edgeconv", ip, ix, c["x"][:m], c["p1"], c["b1"], c["p2"], c["b2"], {}, c["labels"][:m],
+                          "leaky", 0.2, fwd)
+    dt = time.perf_counter() - t0
+    return {"value": len(ix) / dt, "unit": "edges/s", "cores": int(oracle_threads()), "kind": "oracle",
+            "sample": (f"numpy oracle, neighbour search (float32 distances) + fp64 two-layer forward + backward on "
+                       f"the first {m // c['points']} clouds ({len(ix)} edges), {dt:.2f} s"),
+            "measured_s": dt}
+
+
 def cpu_baseline_full(c):
     """EdgeConv / GMM workloads are small enough for the oracle to run whole."""
     e = c["nnz"]
@@ -282,7 +300,38 @@ def main():
     x = to(c["x"])
     gout = to(c["gout"]) if "gout" in c else None
     gemm_total_flops = None
-    if kind == "gat2":
+    if kind == "ec2":
+        from paper_2110_09524_amd import steps as S
+        clouds, points, k_nn, hid, C2 = c["clouds"], c["points"], c["k"], c["hid"], c["classes"]
+        coords = x
+        knn_ptr, knn_idx = new(n + 1, dtype=torch.int32), new(e, dtype=torch.int32)
+        P1, P2 = {k: to(v) for k, v in c["p1"].items()}, {k: to(v) for k, v in c["p2"].items()}
+        l1, l2 = S.EdgeConvLayer(g, fin, hid, P1), S.EdgeConvLayer(g, hid, C2, P2)
+        model = S.TwoLayerStep(l1, l2, to(c["b1"]), to(c["b2"]), to(c["labels"]), n, act="leaky", act_slope=0.2)
+        ws_bytes = model.ws.numel()
+        held = {"g": g}
+
+        def step():
+            # the graph is rebuilt from the coordinates in every step: neighbour search, then the plan
+            pk.gnn_knn_graph(clouds, points, fin, k_nn, coords, knn_ptr, knn_idx)
+            g_new = pk.Graph(knn_ptr, knn_idx)
+            l1.g = l2.g = g_new
+            model.step(x, 1e-3)
+            if held["g"] is not g:
+                held["g"].close()
+            held["g"] = g_new
+        u1, g1, f1_ = edgeconv_models(n, e, fin, hid)
+        u2, g2, f2_ = edgeconv_models(n, e, hid, C2)
+        unique = {k: u1[k] + u2[k] for k in u1}
+        gather = {k: g1[k] + g2[k] for k in g1}
+        flops = {k: f1_[k] + f2_[k] for k in f1_}
+        metric = "two-layer EdgeConv training step incl. kNN graph construction (fwd + bwd + SGD) edges/sec"
+        cfg = {"layers": 2, "in_feat": fin, "hidden": hid, "classes": C2, "activation": "bias + LeakyReLU(0.2)",
+               "graph": f"{clouds} clouds x {points} points, kNN k={k_nn} incl. self, rebuilt on the GPU every step",
+               "loss": "softmax cross-entropy per point", "optimizer": "SGD"}
+        gemm_flops = (2.0 * n * fin * 2 * hid + 2.0 * n * hid * 2 * C2) / 2
+        gemm_total_flops = 3 * (2.0 * n * fin * 2 * hid + 2.0 * n * hid * 2 * C2)
+    elif kind == "gat2":
         from paper_2110_09524_amd.steps import Gat2Step
         H, F, C2 = c["heads1"], c["f1"], c["classes"]
         HF = H * F
@@ -518,6 +567,8 @@ def main():
             result["cpu_baseline"] = cpu_baseline_gat(c, args.cpu_rows)
         elif kind == "gat2":
             result["cpu_baseline"] = cpu_baseline_gat2(c)
+        elif kind == "ec2":
+            result["cpu_baseline"] = cpu_baseline_ec2(c)
         elif kind == "gcn":
             result["cpu_baseline"] = cpu_baseline_gcn(c, args.cpu_rows)
         else:

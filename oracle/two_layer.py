@@ -36,3 +36,66 @@ def gat2_backward(indptr, indices, x, p, labels, slope, fwd=None):
     return dict(gw1=b1["gw"], gal1=b1["ga_l"], gar1=b1["ga_r"], gb1=gb1,
                 gw2=b2["gw"], gal2=b2["ga_l"], gar2=b2["ga_r"], gb2=gb2,
                 gh1=gh1, gh2=gh2, ga1=b2["gx"])
+
+
+# ---- the same chain for the other layer types --------------------------------------------
+# A layer is described by (kind, parameter dict, constants dict):
+#   "gat":      params w, al, ar;  consts slope
+#   "edgeconv": params theta, phi
+#   "gmm":      params w_fc, mu, inv_sigma;  consts c (per-vertex pseudo-coordinate)
+#   "gcn":      params w;  consts c_src, c_dst
+def layer_forward(kind, indptr, indices, x, p, k):
+    if kind == "gat":
+        return og.gat_forward(indptr, indices, x, p["w"], p["al"], p["ar"], k["slope"])
+    if kind == "edgeconv":
+        from . import edgeconv as oe
+        return oe.edgeconv_forward(indptr, indices, x, p["theta"], p["phi"])
+    if kind == "gmm":
+        from . import gmm as om
+        return om.gmm_forward(indptr, indices, x, p["w_fc"], k["c"], p["mu"], p["inv_sigma"])
+    if kind == "gcn":
+        from . import gcn as oc
+        return oc.gcn_forward(indptr, indices, x, p["w"], k["c_src"], k["c_dst"])
+    raise ValueError(kind)
+
+
+def layer_backward(kind, indptr, indices, x, p, k, gout, fwd):
+    """Returns (gx, dict of parameter gradients keyed like p)."""
+    if kind == "gat":
+        b = og.gat_backward(indptr, indices, x, p["w"], p["al"], p["ar"], k["slope"], gout, fwd)
+        return b["gx"], dict(w=b["gw"], al=b["ga_l"], ar=b["ga_r"])
+    if kind == "edgeconv":
+        from . import edgeconv as oe
+        b = oe.edgeconv_backward(indptr, indices, x, p["theta"], p["phi"], gout, fwd)
+        return b["gx"], dict(theta=b["gtheta"], phi=b["gphi"])
+    if kind == "gmm":
+        from . import gmm as om
+        b = om.gmm_backward(indptr, indices, x, p["w_fc"], k["c"], p["mu"], p["inv_sigma"], gout, fwd)
+        return b["gx"], dict(w_fc=b["gw_fc"], mu=b["gmu"], inv_sigma=b["ginv_sigma"])
+    if kind == "gcn":
+        from . import gcn as oc
+        b = oc.gcn_backward(indptr, indices, x, p["w"], k["c_src"], k["c_dst"], gout, fwd)
+        return b["gx"], dict(w=b["gw"])
+    raise ValueError(kind)
+
+
+def two_layer_forward(kind, indptr, indices, x, p1, b1, p2, b2, consts, labels, act="elu", act_slope=0.0):
+    """layer -> act(. + b1) -> layer -> (. + b2) -> mean cross-entropy over labelled vertices."""
+    f1 = layer_forward(kind, indptr, indices, x, p1, consts)
+    a1 = av.bias_act_forward(f1["out"], b1, act, act_slope)
+    f2 = layer_forward(kind, indptr, indices, a1, p2, consts)
+    z = av.bias_act_forward(f2["out"], b2, "identity")
+    loss, gz = av.softmax_xent(z, labels)
+    return dict(f1=f1, a1=a1, f2=f2, z=z, loss=loss, gz=gz)
+
+
+def two_layer_backward(kind, indptr, indices, x, p1, b1, p2, b2, consts, labels, act="elu", act_slope=0.0,
+                       fwd=None):
+    """Returns (g1, gb1, g2, gb2): parameter gradient dicts of the two layers and the bias gradients."""
+    if fwd is None:
+        fwd = two_layer_forward(kind, indptr, indices, x, p1, b1, p2, b2, consts, labels, act, act_slope)
+    gh2, gb2 = av.bias_act_backward(fwd["f2"]["out"], b2, "identity", fwd["gz"])
+    ga1, g2 = layer_backward(kind, indptr, indices, fwd["a1"], p2, consts, gh2, fwd["f2"])
+    gh1, gb1 = av.bias_act_backward(fwd["f1"]["out"], b1, act, ga1, act_slope)
+    _, g1 = layer_backward(kind, indptr, indices, x, p1, consts, gh1, fwd["f1"])
+    return g1, gb1, g2, gb2

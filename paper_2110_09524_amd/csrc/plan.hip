@@ -2,6 +2,8 @@
 // (stable radix sort by source), and the degree order / degree buckets of both
 // sides.  Integer work only; every table is a pure function of the input.
 #include <cstring>
+#include <mutex>
+#include <unordered_map>
 
 #include <rocprim/device/device_radix_sort.hpp>
 #include <rocprim/device/device_scan.hpp>
@@ -54,16 +56,36 @@ __global__ void k_dst_of_position(int32_t n, int64_t nnz, const int32_t* __restr
   indices_t[i] = lo;
 }
 
-__global__ void k_degree_and_bucket(int32_t n, const int32_t* __restrict__ ptr,
-                                    uint32_t* __restrict__ deg, int32_t* __restrict__ bucket,
-                                    int32_t* __restrict__ hist) {
-  int64_t v = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (v >= n) return;
-  uint32_t d = (uint32_t)(ptr[v + 1] - ptr[v]);
-  int b = d == 0 ? 32 : __clz((int)d);
-  deg[v] = d;
-  bucket[v] = b;
-  atomicAdd(&hist[b], 1);
+// The histogram is counted per workgroup in LDS first, one vote per distinct bucket of a
+// wavefront: graphs whose vertices all have the same degree (k-nearest-neighbour graphs) would
+// otherwise send every vertex's atomic to one address.
+__global__ __launch_bounds__(256) void k_degree_and_bucket(int32_t n, const int32_t* __restrict__ ptr,
+                                                           uint32_t* __restrict__ deg,
+                                                           int32_t* __restrict__ bucket,
+                                                           int32_t* __restrict__ hist) {
+  __shared__ int l_hist[GNN_NUM_BUCKETS];
+  if (threadIdx.x < GNN_NUM_BUCKETS) l_hist[threadIdx.x] = 0;
+  __syncthreads();
+  const int64_t v = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  const bool ok = v < n;
+  int b = -1;
+  if (ok) {
+    const uint32_t d = (uint32_t)(ptr[v + 1] - ptr[v]);
+    b = d == 0 ? 32 : __clz((int)d);
+    deg[v] = d;
+    bucket[v] = b;
+  }
+  const int lane = threadIdx.x & 63;
+  unsigned long long todo = __ballot(ok);
+  while (todo) {  // uniform over the wavefront
+    const int first = __ffsll((long long)todo) - 1;
+    const int bb = __shfl(b, first, 64);
+    const unsigned long long same = __ballot(ok && b == bb);
+    if (lane == first) atomicAdd(&l_hist[bb], __popcll(same));
+    todo &= ~same;
+  }
+  __syncthreads();
+  if (threadIdx.x < GNN_NUM_BUCKETS && l_hist[threadIdx.x] != 0) atomicAdd(&hist[threadIdx.x], l_hist[threadIdx.x]);
 }
 
 // key of an edge for the column-blocked order: (block of its column) * n + its row.
@@ -100,34 +122,94 @@ __global__ void k_gather_strided(int count, const int32_t* __restrict__ src, int
   if (i < count) dst[i] = src[(int64_t)i * stride];
 }
 
+// ---- device memory for plan tables and temporaries ---------------------------------------
+// Graphs that are rebuilt all the time (a k-nearest-neighbour graph per training step) would
+// otherwise spend more time in hipMalloc / hipFree than in the plan kernels.  Blocks of up to
+// 64 MB are rounded up to a power of two and, when released, kept on a free list (at most
+// 512 MB in total) for the next plan of a similar size; larger blocks go straight to the
+// driver.  A block is only released once nothing on the device can still touch it (the
+// callers below synchronise first), so handing it out again needs no further care.
+constexpr size_t kPoolMaxBlock = (size_t)64 << 20;
+constexpr size_t kPoolMaxCached = (size_t)512 << 20;
+static std::mutex g_pool_mu;  // guards the three objects below
+static std::unordered_multimap<size_t, void*> g_pool_free;  // capacity -> idle block
+static std::unordered_map<void*, size_t> g_pool_capacity;   // every pooled block, idle or in use
+static size_t g_pool_cached = 0;
+
+static hipError_t pool_alloc(void** out, size_t bytes) {
+  *out = nullptr;
+  if (bytes == 0) bytes = 1;
+  if (bytes > kPoolMaxBlock) return hipMalloc(out, bytes);
+  size_t cap = 256;
+  while (cap < bytes) cap <<= 1;
+  {
+    std::lock_guard<std::mutex> lk(g_pool_mu);
+    auto it = g_pool_free.find(cap);
+    if (it != g_pool_free.end()) {
+      *out = it->second;
+      g_pool_free.erase(it);
+      g_pool_cached -= cap;
+      return hipSuccess;
+    }
+  }
+  hipError_t e = hipMalloc(out, cap);
+  if (e == hipSuccess) {
+    std::lock_guard<std::mutex> lk(g_pool_mu);
+    g_pool_capacity[*out] = cap;
+  }
+  return e;
+}
+
+// the block must be idle on the device
+static void pool_free(void* p) {
+  if (!p) return;
+  {
+    std::lock_guard<std::mutex> lk(g_pool_mu);
+    auto it = g_pool_capacity.find(p);
+    if (it != g_pool_capacity.end()) {
+      if (g_pool_cached + it->second <= kPoolMaxCached) {
+        g_pool_free.emplace(it->second, p);
+        g_pool_cached += it->second;
+        return;
+      }
+      g_pool_capacity.erase(it);
+    }
+  }
+  (void)hipFree(p);
+}
+
 static void free_all(gnn_graph* g) {
   if (!g) return;
-  (void)hipFree(g->indptr_t);
-  (void)hipFree(g->indices_t);
-  (void)hipFree(g->eid_t);
+  (void)hipDeviceSynchronize();  // kernels that read the tables have finished (hipFree used to wait, too)
+  pool_free(g->indptr_t);
+  pool_free(g->indices_t);
+  pool_free(g->eid_t);
   for (int s = 0; s < 2; ++s) {
-    (void)hipFree(g->bucket_of[s]);
-    (void)hipFree(g->order[s]);
-    (void)hipFree(g->bucket_offsets[s]);
-    (void)hipFree(g->bptr[s]);
-    (void)hipFree(g->bcol[s]);
-    (void)hipFree(g->bseg[s]);
+    pool_free(g->bucket_of[s]);
+    pool_free(g->order[s]);
+    pool_free(g->bucket_offsets[s]);
+    pool_free(g->bptr[s]);
+    pool_free(g->bcol[s]);
+    pool_free(g->bseg[s]);
   }
   delete g;
 }
 
 struct TempBuffers {
-  void* p[8] = {};
+  void* p[24] = {};
   int count = 0;
+  hipStream_t st;
+  explicit TempBuffers(hipStream_t stream) : st(stream) {}
   ~TempBuffers() {
-    for (int i = 0; i < count; ++i) (void)hipFree(p[i]);
+    if (count) (void)hipStreamSynchronize(st);  // also on error paths: nothing may still be writing
+    for (int i = 0; i < count; ++i) pool_free(p[i]);
   }
   template <typename T>
   hipError_t alloc(T** out, size_t elems) {
     void* q = nullptr;
     *out = nullptr;
-    if (count == 8) return hipErrorOutOfMemory;  // more temporaries than slots: a bug, not a device state
-    hipError_t e = hipMalloc(&q, elems ? elems * sizeof(T) : sizeof(T));
+    if (count == 24) return hipErrorOutOfMemory;  // more temporaries than slots: a bug, not a device state
+    hipError_t e = pool_alloc(&q, elems ? elems * sizeof(T) : sizeof(T));
     if (e == hipSuccess) p[count++] = q;
     *out = static_cast<T*>(q);
     return e;
@@ -140,25 +222,57 @@ static int bits_for(uint32_t max_value) {
   return b;
 }
 
-static gnn_status_t build_side(gnn_graph* g, int side, const int32_t* ptr, hipStream_t st) {
+// Small results the host needs (error flags, bucket histograms, largest degrees) are copied into
+// pinned memory, so that the copies are asynchronous and one wait at the end of the build
+// serves all of them.  One staging block per host thread, allocated on first use and kept.
+struct PlanStage {
+  int32_t hist[2][GNN_NUM_BUCKETS];
+  uint32_t max_degree[2];
+  int bad;
+};
+static PlanStage* plan_stage() {
+  static thread_local PlanStage* stage = nullptr;
+  if (!stage) {
+    void* p = nullptr;
+    if (hipHostMalloc(&p, sizeof(PlanStage), hipHostMallocDefault) != hipSuccess) return nullptr;
+    stage = static_cast<PlanStage*>(p);
+  }
+  return stage;
+}
+
+__global__ void k_bucket_offsets(const int32_t* __restrict__ hist, int32_t* __restrict__ offsets) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    int32_t run = 0;
+    offsets[0] = 0;
+    for (int b = 0; b < GNN_NUM_BUCKETS; ++b) {
+      run += hist[b];
+      offsets[b + 1] = run;
+    }
+  }
+}
+
+// enqueues the degree order and buckets of one side; finish_side completes it after the wait
+static gnn_status_t build_side(gnn_graph* g, int side, const int32_t* ptr, TempBuffers& tmp,
+                               PlanStage* stage, hipStream_t st) {
   const int32_t n = g->n;
   const int thr = 256;
-  TempBuffers tmp;
   uint32_t *deg = nullptr, *deg_sorted = nullptr;
   int32_t *ids = nullptr, *hist = nullptr;
   GNN_HIP(tmp.alloc(&deg, n));
   GNN_HIP(tmp.alloc(&deg_sorted, n));
   GNN_HIP(tmp.alloc(&ids, n));
   GNN_HIP(tmp.alloc(&hist, GNN_NUM_BUCKETS));
-  GNN_HIP(hipMalloc((void**)&g->bucket_of[side], sizeof(int32_t) * (n ? n : 1)));
-  GNN_HIP(hipMalloc((void**)&g->order[side], sizeof(int32_t) * (n ? n : 1)));
-  GNN_HIP(hipMalloc((void**)&g->bucket_offsets[side], sizeof(int32_t) * (GNN_NUM_BUCKETS + 1)));
+  GNN_HIP(pool_alloc((void**)&g->bucket_of[side], sizeof(int32_t) * (n ? n : 1)));
+  GNN_HIP(pool_alloc((void**)&g->order[side], sizeof(int32_t) * (n ? n : 1)));
+  GNN_HIP(pool_alloc((void**)&g->bucket_offsets[side], sizeof(int32_t) * (GNN_NUM_BUCKETS + 1)));
   GNN_HIP(hipMemsetAsync(hist, 0, sizeof(int32_t) * GNN_NUM_BUCKETS, st));
-  int32_t h_hist[GNN_NUM_BUCKETS] = {};
-  uint32_t h_max = 0;
   if (n > 0) {
     k_degree_and_bucket<<<cdiv(n, thr), thr, 0, st>>>(n, ptr, deg, g->bucket_of[side], hist);
     GNN_LAUNCH_CHECK();
+  }
+  k_bucket_offsets<<<1, 64, 0, st>>>(hist, g->bucket_offsets[side]);
+  GNN_LAUNCH_CHECK();
+  if (n > 0) {
     k_iota<<<cdiv(n, thr), thr, 0, st>>>(n, ids);
     GNN_LAUNCH_CHECK();
     // stable descending sort by degree: ties keep ascending vertex id
@@ -169,18 +283,18 @@ static gnn_status_t build_side(gnn_graph* g, int side, const int32_t* ptr, hipSt
     GNN_HIP(tmp.alloc((char**)&scratch, bytes));
     GNN_HIP(rocprim::radix_sort_pairs_desc(scratch, bytes, deg, deg_sorted, ids, g->order[side],
                                            (size_t)n, 0, 32, st));
-    GNN_HIP(hipMemcpyAsync(h_hist, hist, sizeof(h_hist), hipMemcpyDeviceToHost, st));
-    GNN_HIP(hipMemcpyAsync(&h_max, deg_sorted, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-    GNN_HIP(hipStreamSynchronize(st));
+    GNN_HIP(hipMemcpyAsync(stage->hist[side], hist, sizeof(stage->hist[side]), hipMemcpyDeviceToHost, st));
+    GNN_HIP(hipMemcpyAsync(&stage->max_degree[side], deg_sorted, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
   }
-  g->max_degree[side] = (int32_t)h_max;
+  return GNN_OK;
+}
+
+// after the stream has been waited for: the host copies of the bucket table
+static void finish_side(gnn_graph* g, int side, const PlanStage* stage) {
+  g->max_degree[side] = (int32_t)stage->max_degree[side];
   g->h_bucket_offsets[side][0] = 0;
   for (int b = 0; b < GNN_NUM_BUCKETS; ++b)
-    g->h_bucket_offsets[side][b + 1] = g->h_bucket_offsets[side][b] + h_hist[b];
-  GNN_HIP(hipMemcpyAsync(g->bucket_offsets[side], g->h_bucket_offsets[side],
-                         sizeof(int32_t) * (GNN_NUM_BUCKETS + 1), hipMemcpyHostToDevice, st));
-  GNN_HIP(hipStreamSynchronize(st));
-  return GNN_OK;
+    g->h_bucket_offsets[side][b + 1] = g->h_bucket_offsets[side][b] + stage->hist[side][b];
 }
 
 // Column-blocked copy of one side's edge list: edges stable-sorted by
@@ -192,14 +306,14 @@ static gnn_status_t build_blocked(gnn_graph* g, int side, const int32_t* ptr, co
   const int64_t nnz = g->nnz;
   const int thr = 256;
   const int64_t slots = (int64_t)g->nblk * n;
-  TempBuffers tmp;
+  TempBuffers tmp(st);
   uint64_t *keys = nullptr, *keys_sorted = nullptr;
   int32_t* counts = nullptr;
   GNN_HIP(tmp.alloc(&keys, (size_t)nnz));
   GNN_HIP(tmp.alloc(&keys_sorted, (size_t)nnz));
   GNN_HIP(tmp.alloc(&counts, (size_t)slots + 1));
-  GNN_HIP(hipMalloc((void**)&g->bptr[side], sizeof(int32_t) * ((size_t)slots + 1)));
-  GNN_HIP(hipMalloc((void**)&g->bcol[side], sizeof(int32_t) * (size_t)nnz));
+  GNN_HIP(pool_alloc((void**)&g->bptr[side], sizeof(int32_t) * ((size_t)slots + 1)));
+  GNN_HIP(pool_alloc((void**)&g->bcol[side], sizeof(int32_t) * (size_t)nnz));
   GNN_HIP(hipMemsetAsync(counts, 0, sizeof(int32_t) * ((size_t)slots + 1), st));
   k_block_keys<<<cdiv((int64_t)n * 64, thr), thr, 0, st>>>(n, nnz, ptr, cols, g->block_cols, keys, counts);
   GNN_LAUNCH_CHECK();
@@ -223,7 +337,7 @@ static gnn_status_t build_blocked(gnn_graph* g, int side, const int32_t* ptr, co
     GNN_HIP(rocprim::radix_sort_pairs(scratch, bytes, keys, keys_sorted, cols, g->bcol[side],
                                       (size_t)nnz, 0, end_bit, st));
   }
-  GNN_HIP(hipMalloc((void**)&g->bseg[side], sizeof(int32_t) * 2 * (size_t)slots));
+  GNN_HIP(pool_alloc((void**)&g->bseg[side], sizeof(int32_t) * 2 * (size_t)slots));
   k_block_segments<<<cdiv(slots, thr), thr, 0, st>>>(n, g->nblk, g->bptr[side], g->order[side],
                                                      reinterpret_cast<int2*>(g->bseg[side]));
   GNN_LAUNCH_CHECK();
@@ -243,14 +357,17 @@ static gnn_status_t build(gnn_graph* g, hipStream_t st) {
   const int32_t n = g->n;
   const int64_t nnz = g->nnz;
   const int thr = 256;
-  TempBuffers tmp;
+  TempBuffers tmp(st);
+  PlanStage* stage = plan_stage();
+  GNN_REQUIRE(stage != nullptr, GNN_ERR_HIP, "gnn_graph_create: no pinned staging memory");
+  std::memset(stage, 0, sizeof(PlanStage));
   int* bad = nullptr;
   GNN_HIP(tmp.alloc(&bad, 1));
   GNN_HIP(hipMemsetAsync(bad, 0, sizeof(int), st));
 
-  GNN_HIP(hipMalloc((void**)&g->indptr_t, sizeof(int32_t) * (size_t)(n + 1)));
-  GNN_HIP(hipMalloc((void**)&g->indices_t, sizeof(int32_t) * (size_t)(nnz ? nnz : 1)));
-  GNN_HIP(hipMalloc((void**)&g->eid_t, sizeof(int32_t) * (size_t)(nnz ? nnz : 1)));
+  GNN_HIP(pool_alloc((void**)&g->indptr_t, sizeof(int32_t) * (size_t)(n + 1)));
+  GNN_HIP(pool_alloc((void**)&g->indices_t, sizeof(int32_t) * (size_t)(nnz ? nnz : 1)));
+  GNN_HIP(pool_alloc((void**)&g->eid_t, sizeof(int32_t) * (size_t)(nnz ? nnz : 1)));
 
   int32_t* outdeg = nullptr;
   GNN_HIP(tmp.alloc(&outdeg, (size_t)n + 1));
@@ -262,9 +379,10 @@ static gnn_status_t build(gnn_graph* g, hipStream_t st) {
     k_validate_indices_and_count<<<cdiv(nnz, thr), thr, 0, st>>>(n, nnz, g->indices, outdeg, bad);
     GNN_LAUNCH_CHECK();
   }
-  int h_bad = 0;
-  GNN_HIP(hipMemcpyAsync(&h_bad, bad, sizeof(int), hipMemcpyDeviceToHost, st));
+  // the kernels below index with the source ids, so this one has to be waited for
+  GNN_HIP(hipMemcpyAsync(&stage->bad, bad, sizeof(int), hipMemcpyDeviceToHost, st));
   GNN_HIP(hipStreamSynchronize(st));
+  const int h_bad = stage->bad;
   GNN_REQUIRE(h_bad == 0, GNN_ERR_BAD_GRAPH,
               "gnn_graph_create: malformed CSR (%s%s%s%s)", (h_bad & 1) ? "indptr[0] != 0; " : "",
               (h_bad & 2) ? "indptr[n] != nnz; " : "", (h_bad & 4) ? "indptr not monotone; " : "",
@@ -300,8 +418,8 @@ static gnn_status_t build(gnn_graph* g, hipStream_t st) {
     k_dst_of_position<<<cdiv(nnz, thr), thr, 0, st>>>(n, nnz, g->indptr, g->eid_t, g->indices_t);
     GNN_LAUNCH_CHECK();
   }
-  GNN_TRY(build_side(g, 0, g->indptr, st));
-  GNN_TRY(build_side(g, 1, g->indptr_t, st));
+  GNN_TRY(build_side(g, 0, g->indptr, tmp, stage, st));
+  GNN_TRY(build_side(g, 1, g->indptr_t, tmp, stage, st));
   g->block_cols = (int32_t)config_get(kCfgBlockCols);
   g->nblk = 1;
   // the (block, row) pointer table has nblk * n entries: keep it below 2^28
@@ -312,6 +430,8 @@ static gnn_status_t build(gnn_graph* g, hipStream_t st) {
     GNN_TRY(build_blocked(g, 1, g->indptr_t, g->indices_t, st));
   }
   GNN_HIP(hipStreamSynchronize(st));
+  finish_side(g, 0, stage);
+  finish_side(g, 1, stage);
   return GNN_OK;
 }
 

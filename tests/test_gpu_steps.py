@@ -132,3 +132,93 @@ def test_two_layer_gat_step_matches_the_composed_oracle():
         assert_close("g" + k, res["g" + k], bwd["g" + k], reduce_scale=True)
         want = c["params"][k].astype(np.float64) - 0.1 * bwd["g" + k]
         np.testing.assert_allclose(res["new_" + k], want, rtol=1e-4, atol=1e-5, err_msg="sgd " + k)
+
+
+def _two_layer_case(kind, seed):
+    """A seeded two-layer node classifier of the given layer type on a graph the oracle handles."""
+    from helpers import random_graph
+    from oracle import knn as ok
+    rng = np.random.default_rng(seed)
+    consts, extra = {}, {}
+    if kind == "edgeconv":
+        clouds, points, k = 3, 400, 12
+        coords = rng.random((clouds * points, 3), dtype=np.float32)
+        indptr, indices = ok.knn_graph(coords, clouds, points, k)
+        n, fin, hid, c = clouds * points, 3, 32, 8
+        x = coords                                  # the first layer works on the coordinates
+        extra = dict(coords=coords, clouds=clouds, points=points, k=k)
+    else:
+        n, fin, hid, c = 1500, 24, 32, 8
+        indptr, indices = random_graph(rng, n, 20000, self_loops=True, duplicates=False)
+        x = rng.standard_normal((n, fin)).astype(np.float32)
+    deg = np.maximum(np.diff(indptr), 1)
+    f32 = lambda a: np.asarray(a, dtype=np.float32)
+
+    def params(fi, fo):
+        s = np.sqrt(2.0 / (fi + fo))
+        if kind == "edgeconv":
+            return dict(theta=f32(rng.standard_normal((fi, fo)) * s), phi=f32(rng.standard_normal((fi, fo)) * s))
+        if kind == "gmm":
+            return dict(w_fc=f32(rng.standard_normal((fi, 3 * fo)) * s), mu=f32(rng.standard_normal((3, 2)) * 0.3),
+                        inv_sigma=f32(0.5 + rng.random((3, 2))))
+        return dict(w=f32(rng.standard_normal((fi, fo)) * s))
+    if kind == "gmm":
+        consts["c"] = f32(1.0 / np.sqrt(deg))
+    if kind == "gcn":
+        consts["c_src"] = f32(1.0 / np.sqrt(np.maximum(np.bincount(indices, minlength=n), 1)))
+        consts["c_dst"] = f32(1.0 / np.sqrt(deg))
+    labels = rng.integers(0, c, n).astype(np.int32)
+    labels[rng.random(n) < 0.4] = -1
+    return dict(kind=kind, n=n, fin=fin, hid=hid, c=c, indptr=indptr, indices=indices, x=x, consts=consts,
+                p1=params(fin, hid), p2=params(hid, c), b1=f32(0.1 * rng.standard_normal(hid)),
+                b2=f32(0.1 * rng.standard_normal(c)), labels=labels, **extra)
+
+
+@pytest.mark.parametrize("kind", ["edgeconv", "gmm", "gcn"])
+def test_two_layer_step_of_every_layer_type(kind):
+    """EdgeConv: the graph itself is built on the GPU from the coordinates (gnn_knn_graph)."""
+    import torch
+    import paper_2110_09524_amd as pk
+    from paper_2110_09524_amd import steps
+    from gpu_harness import assert_close, dev
+    print(f"two-layer step: {kind}", flush=True)
+    t = _two_layer_case(kind, 2024)
+    n, fin, hid, c = t["n"], t["fin"], t["hid"], t["c"]
+    act, slope = ("leaky", 0.2) if kind == "edgeconv" else ("relu", 0.0)
+    fwd = ot.two_layer_forward(kind, t["indptr"], t["indices"], t["x"], t["p1"], t["b1"], t["p2"], t["b2"],
+                               t["consts"], t["labels"], act, slope)
+    g1, gb1, g2, gb2 = ot.two_layer_backward(kind, t["indptr"], t["indices"], t["x"], t["p1"], t["b1"], t["p2"],
+                                             t["b2"], t["consts"], t["labels"], act, slope, fwd)
+    if kind == "edgeconv":
+        from oracle import edgeconv as oe
+        for f, name in ((fwd["f1"], "layer 1"), (fwd["f2"], "layer 2")):     # the comparison needs a clear winner
+            assert not oe.near_tie_mask(t["indptr"], f, 1e-6).any(), f"seed gives a near-tie in {name}"
+        ip = torch.empty(n + 1, dtype=torch.int32, device="cuda:0")
+        ix = torch.empty(n * t["k"], dtype=torch.int32, device="cuda:0")
+        pk.gnn_knn_graph(t["clouds"], t["points"], 3, t["k"], dev(t["coords"]), ip, ix)
+        assert (ix.cpu().numpy() == t["indices"]).all()
+        g = pk.Graph(ip, ix)
+    else:
+        g = pk.Graph(dev(t["indptr"]), dev(t["indices"]))
+    P1, P2 = {k: dev(v) for k, v in t["p1"].items()}, {k: dev(v) for k, v in t["p2"].items()}
+    if kind == "edgeconv":
+        l1, l2 = steps.EdgeConvLayer(g, fin, hid, P1), steps.EdgeConvLayer(g, hid, c, P2)
+    elif kind == "gmm":
+        cc = dev(t["consts"]["c"])
+        l1, l2 = steps.GmmLayer(g, fin, hid, 3, P1, cc), steps.GmmLayer(g, hid, c, 3, P2, cc)
+    else:
+        cs, cd = dev(t["consts"]["c_src"]), dev(t["consts"]["c_dst"])
+        l1, l2 = steps.GcnLayer(g, fin, hid, P1, cs, cd), steps.GcnLayer(g, hid, c, P2, cs, cd)
+    step = steps.TwoLayerStep(l1, l2, dev(t["b1"]), dev(t["b2"]), dev(t["labels"]), int((t["labels"] >= 0).sum()),
+                              act=act, act_slope=slope)
+    step.step(dev(t["x"]))
+    torch.cuda.synchronize()
+    assert_close("a1", step.a1.cpu().numpy(), fwd["a1"])
+    assert_close("logits", step.logits.cpu().numpy(), fwd["z"])
+    assert abs(float(step.loss.cpu()[0]) - fwd["loss"]) <= 1e-5 + 1e-4 * abs(fwd["loss"])
+    for name in t["p1"]:
+        assert_close(f"layer 1 g{name}", l1.grads[name].cpu().numpy(), g1[name], reduce_scale=True)
+        assert_close(f"layer 2 g{name}", l2.grads[name].cpu().numpy(), g2[name], reduce_scale=True)
+    assert_close("gb1", step.gb1.cpu().numpy(), gb1, reduce_scale=True)
+    assert_close("gb2", step.gb2.cpu().numpy(), gb2, reduce_scale=True)
+    g.close()

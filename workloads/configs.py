@@ -195,6 +195,23 @@ def _make_gat2_c4(seed):
                  labelled=0.66)
 
 
+def _make_ec2_c3(seed):
+    """Two EdgeConv layers on point clouds, graph built from the coordinates in every step
+    (the end-to-end EdgeConv setting of Sec. 7.2, cut to two layers): 3 -> 64 -> 40 classes per point."""
+    batch, points, k, hid, classes = 32, 1024, 20, 64, 40
+    indptr, indices, coords = graphs.knn_point_clouds(batch, points, k, SEED0 ^ 3)
+    n = batch * points
+    rng = graphs.rng_for(seed ^ 0xA5A5)
+    labels = rng.integers(0, classes, n).astype(np.int32)
+    return dict(
+        name="ec2_c3", kind="ec2", n=n, nnz=int(indices.shape[0]), fin=3, hid=hid, classes=classes,
+        clouds=batch, points=points, k=k, indptr=indptr, indices=indices, coords=coords, x=coords, labels=labels,
+        p1=dict(theta=glorot(rng, 3, hid, (3, hid)), phi=glorot(rng, 3, hid, (3, hid))),
+        p2=dict(theta=glorot(rng, hid, classes, (hid, classes)), phi=glorot(rng, hid, classes, (hid, classes))),
+        b1=(0.1 * _normal(rng, (hid,))).astype(np.float32), b2=(0.1 * _normal(rng, (classes,))).astype(np.float32),
+    )
+
+
 def _make_gcn_mid(seed):
     n = 6000
     return _gcn("gcn_mid", n, graphs.chung_lu(n, 300_000, 2.1, seed), 602, 256, seed)
@@ -234,6 +251,7 @@ _MAKERS = {
     "gat2_mid": (109, _make_gat2_mid),
     "gat2_c2": (9, _make_gat2_c2),
     "gat2_c4": (10, _make_gat2_c4),
+    "ec2_c3": (13, _make_ec2_c3),
 }
 NAMES = tuple(_MAKERS)
 
