@@ -105,6 +105,9 @@ gnn_status_t sum_partials_two_level(int64_t count, int parts, const float* parti
 // same with a distance of `stride` floats between consecutive parts
 gnn_status_t sum_partials_strided(int64_t count, int parts, const float* partials, int64_t stride,
                                   float* out, hipStream_t s);
+// partials is [parts][2][count]: first halves into out0, second halves into out1, one launch
+gnn_status_t sum_partials_pair(int64_t count, int parts, const float* partials, float* out0, float* out1,
+                               hipStream_t s);
 
 }  // namespace gnn
 

@@ -622,8 +622,8 @@ static int param_blocks(int64_t n) {
 
 struct GatWs {
   size_t total;
-  size_t dz, vstate, der, del, partial, gemm, blk_rows, blk_scal, blk_elt, blk_queue;
-  int split_k, nblk;
+  size_t dz, vstate, der, del, partial, gemm, blk_rows, blk_scal, blk_elt, blk_queue, fwd_gemm;
+  int split_k, nblk, fwd_split_k;
 };
 
 static GatWs gat_ws_layout(const gnn_graph_t* g, int fin, int H, int F) {
@@ -645,6 +645,9 @@ static GatWs gat_ws_layout(const gnn_graph_t* g, int fin, int H, int F) {
   w.blk_scal = take(blocked ? sizeof(float) * n * H : 0);   // sg, then sd
   w.blk_elt = take(blocked ? sizeof(float) * n * H : 0);    // head-major el
   w.blk_queue = take(blocked ? sizeof(int32_t) * 8 * (size_t)g->nblk : 0);  // row counters of the staged kernels
+  // a narrow projection of a mid-sized graph has too few output tiles to fill the chip: split K
+  w.fwd_split_k = gemm_pick_split_k(n, HF, fin);
+  w.fwd_gemm = take(w.fwd_split_k > 1 ? sizeof(float) * (size_t)w.fwd_split_k * n * HF : 0);
   w.total = off;
   return w;
 }
@@ -932,8 +935,15 @@ extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, in
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int HF = heads * f;
   const int64_t n = g->n;
-  // a1: projection before propagation
-  GNN_TRY(gemm_f32(n, HF, fin, x, fin, false, w, HF, false, z, HF, 1, nullptr, st));
+  // a1: projection before propagation (split over K when the workspace offers room for the parts)
+  const GatWs L = gat_ws_layout(g, fin, heads, f);
+  const bool have_ws = ws != nullptr && ws_bytes >= L.total && aligned16(ws);
+  if (have_ws && L.fwd_split_k > 1) {
+    GNN_TRY(gemm_f32(n, HF, fin, x, fin, false, w, HF, false, z, HF, L.fwd_split_k,
+                     reinterpret_cast<float*>(static_cast<char*>(ws) + L.fwd_gemm), st));
+  } else {
+    GNN_TRY(gemm_f32(n, HF, fin, x, fin, false, w, HF, false, z, HF, 1, nullptr, st));
+  }
   // a2: attention halves
   {
     ProfScope p("gat_attn_halves", st);
@@ -944,8 +954,7 @@ extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, in
   // The column-blocked kernels need scratch (a head-major copy of el, row counters, and the
   // running softmax statistics, which borrow the dz area the backward call uses later: 128 of
   // its >= 512 bytes per vertex); without a workspace the single-launch kernels run.
-  const GatWs L = gat_ws_layout(g, fin, heads, f);
-  if (gat_blocked_applies(g, heads, f) && ws != nullptr && ws_bytes >= L.total && aligned16(ws)) {
+  if (gat_blocked_applies(g, heads, f) && have_ws) {
     char* base = static_cast<char*>(ws);
     return gat_blocked_fwd(g, make_dims(heads, f, slope), z, el, er, m, d, out, t, sg,
                            reinterpret_cast<float*>(base + L.blk_elt),
@@ -1065,9 +1074,8 @@ static gnn_status_t gat_bwd_impl(const char* who, const gnn_graph_t* g, int fin,
     const int64_t rpb = cdiv(n, L.nblk);
     k_gat_param_partial<<<L.nblk, kParamThreads, 0, st>>>(n, heads, f, rpb, z, del, der, partial);
     GNN_LAUNCH_CHECK();
-    // partial is [nblk][2][HF]: sum the l and the r halves separately, block order fixed
-    GNN_TRY(sum_partials_strided(HF, L.nblk, partial, 2 * (int64_t)HF, ga_l, st));
-    GNN_TRY(sum_partials_strided(HF, L.nblk, partial + HF, 2 * (int64_t)HF, ga_r, st));
+    // partial is [nblk][2][HF]: the l and the r halves summed by one launch, block order fixed
+    GNN_TRY(sum_partials_pair(HF, L.nblk, partial, ga_l, ga_r, st));
   }
   // gw = x^T dz   (x read k-major: row index of x is the contraction index)
   GNN_TRY(gemm_f32(fin, HF, n, x, fin, true, dz, HF, false, gw, HF, L.split_k, gemm_part, st));

@@ -155,8 +155,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_f32(
 }
 
 // c[i] = sum over z of partials[z][i], z ascending (fixed order => reproducible)
+// c2 != null: elements from index `cut` on go to c2[i - cut] (two results from one launch)
+__device__ __forceinline__ void store_split(float* c, float* c2, int64_t cut, int64_t i, float v) {
+  if (c2 != nullptr && i >= cut) c2[i - cut] = v;
+  else c[i] = v;
+}
+
 __global__ void k_sum_partials(int64_t count, int splits, int64_t stride,
-                               const float* __restrict__ partials, float* __restrict__ c) {
+                               const float* __restrict__ partials, float* __restrict__ c,
+                               float* __restrict__ c2, int64_t cut) {
   int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
   if (i >= count) return;
   // four interleaved running sums keep four loads in flight; their order is fixed
@@ -168,7 +175,7 @@ __global__ void k_sum_partials(int64_t count, int splits, int64_t stride,
     s0 += v0; s1 += v1; s2 += v2; s3 += v3;
   }
   for (; z < splits; ++z) s0 += partials[(int64_t)z * stride + i];
-  c[i] = (s0 + s1) + (s2 + s3);
+  store_split(c, c2, cut, i, (s0 + s1) + (s2 + s3));
 }
 
 // Same sum for short outputs and many parts: 8 threads share one output element, each
@@ -178,7 +185,8 @@ __global__ void k_sum_partials(int64_t count, int splits, int64_t stride,
 // The grouping is fixed, so the result is reproducible.
 __global__ __launch_bounds__(256) void k_sum_partials_wide(int64_t count, int parts, int64_t stride,
                                                            const float* __restrict__ partials,
-                                                           int chunk, float* __restrict__ c) {
+                                                           int chunk, float* __restrict__ c,
+                                                           float* __restrict__ c2, int64_t cut) {
   __shared__ float sub[8][32];
   const int col = threadIdx.x & 31, lane8 = threadIdx.x >> 5;
   const int64_t i = (int64_t)blockIdx.x * 32 + col;
@@ -193,21 +201,32 @@ __global__ __launch_bounds__(256) void k_sum_partials_wide(int64_t count, int pa
     float tot = 0.f;
 #pragma unroll
     for (int q = 0; q < 8; ++q) tot += sub[q][col];
-    c[(int64_t)blockIdx.y * count + i] = tot;
+    store_split(c, c2, cut, (int64_t)blockIdx.y * count + i, tot);
   }
+}
+
+static gnn_status_t sum_partials_launch(int64_t count, int parts, const float* partials, int64_t stride,
+                                        float* out, float* out2, int64_t cut, hipStream_t s) {
+  if (count <= 0) return GNN_OK;
+  if (count >= 32768 || parts < 16) {
+    k_sum_partials<<<(unsigned)cdiv(count, 256), 256, 0, s>>>(count, parts, stride, partials, out, out2, cut);
+  } else {
+    k_sum_partials_wide<<<dim3((unsigned)cdiv(count, 32), 1), 256, 0, s>>>(count, parts, stride, partials,
+                                                                           parts, out, out2, cut);
+  }
+  GNN_LAUNCH_CHECK();
+  return GNN_OK;
 }
 
 gnn_status_t sum_partials_strided(int64_t count, int parts, const float* partials, int64_t stride,
                                   float* out, hipStream_t s) {
-  if (count <= 0) return GNN_OK;
-  if (count >= 32768 || parts < 16) {
-    k_sum_partials<<<(unsigned)cdiv(count, 256), 256, 0, s>>>(count, parts, stride, partials, out);
-  } else {
-    k_sum_partials_wide<<<dim3((unsigned)cdiv(count, 32), 1), 256, 0, s>>>(count, parts, stride, partials,
-                                                                           parts, out);
-  }
-  GNN_LAUNCH_CHECK();
-  return GNN_OK;
+  return sum_partials_launch(count, parts, partials, stride, out, nullptr, 0, s);
+}
+
+// partials is [parts][2][count]: the first halves are summed into out0, the second into out1
+gnn_status_t sum_partials_pair(int64_t count, int parts, const float* partials, float* out0, float* out1,
+                               hipStream_t s) {
+  return sum_partials_launch(2 * count, parts, partials, 2 * count, out0, out1, count, s);
 }
 
 gnn_status_t sum_partials(int64_t count, int parts, const float* partials, float* out, hipStream_t s) {
@@ -224,7 +243,7 @@ gnn_status_t sum_partials_two_level(int64_t count, int parts, const float* parti
   const int rows = sum_partials_scratch_rows(parts);
   if (rows <= 1) return sum_partials(count, parts, partials, out, s);
   k_sum_partials_wide<<<dim3((unsigned)cdiv(count, 32), (unsigned)rows), 256, 0, s>>>(
-      count, parts, count, partials, kSumChunk, scratch);
+      count, parts, count, partials, kSumChunk, scratch, nullptr, 0);
   GNN_LAUNCH_CHECK();
   return sum_partials(count, rows, scratch, out, s);
 }
