@@ -113,6 +113,9 @@ gnn_status_t gnn_graph_get_blocked(const gnn_graph_t* graph, int side, int32_t* 
  *   "block_cols"            gathered vertices per column block (default 24576:
  *                           24576 rows x one 128-byte slice per XCD = 3 MB of a
  *                           4 MB L2); 0 disables blocking
+ *   "blocked_min_edges"     mean number of edges per (row, column block) from which the
+ *                           column-blocked kernels are used (default 16; sparser graphs take
+ *                           the single-launch kernels even when they span several blocks)
  *   "force_simple_kernels"  1: always use the single-launch kernels
  *   "lds_scalar_table"      1 (default): the column-blocked destination-side GAT kernels
  *                           keep a block's per-vertex score table in LDS (one persistent

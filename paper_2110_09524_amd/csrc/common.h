@@ -83,7 +83,8 @@ struct Workspace {
 inline size_t ws_granule(size_t bytes) { return align_up(bytes, 256); }
 
 // ---- tuning knobs (runtime.hip) -------------------------------------------------
-enum ConfigKey { kCfgBlockCols = 0, kCfgForceSimple = 1, kCfgLdsScalarTable = 2, kCfgGcnMapping = 3, kCfgGmmMapping = 4, kCfgCount };
+enum ConfigKey { kCfgBlockCols = 0, kCfgForceSimple = 1, kCfgLdsScalarTable = 2, kCfgGcnMapping = 3, kCfgGmmMapping = 4, kCfgBlockedMinEdges = 5,
+                 kCfgCount };
 int64_t config_get(ConfigKey k);
 
 // ---- dense products (gemm.hip) ------------------------------------------------
@@ -132,6 +133,11 @@ struct gnn_graph {
   int32_t* bcol[2];
   int32_t* bseg[2];  // (begin, end) of row order[r] in block b at [b*n + r], two ints each
   std::vector<int32_t> h_block_begin[2];  // host: first edge of block b (nblk + 1 entries)
+  // The column-blocked kernels visit every row once per block; that pays only when a row has
+  // enough edges inside a block (configuration key "blocked_min_edges", mean over rows and blocks).
+  bool blocked_pays() const {
+    return nblk > 1 && nnz >= gnn::config_get(gnn::kCfgBlockedMinEdges) * (int64_t)n * nblk;
+  }
   int8_t gcn_edge_balanced[2];  // per side: -1 not tuned, 0 / 1 what gnn_gcn_tune found faster
   int8_t gmm_edge_balanced;     // forward aggregation: -1 not tuned, 0 / 1 what gnn_gmm_tune found faster
 };

@@ -60,35 +60,44 @@ struct GroupLds {
 // destination-side sums of the backward pass.  They ride on the same gathered rows, and
 // they are O(|V|) vertex state, which is cheaper to stash than to recompute (Sec. 6:
 // recompute only when computation / memory is O(1); here it is |E|/|V|).
-template <int L, int NV, bool WT>
+template <int L, int NV, bool WT, int ES>
 __global__ __launch_bounds__(kBlock) void k_gat_fwd(
     RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
     const int32_t* __restrict__ indices, const float* __restrict__ z, const float* __restrict__ el,
     const float* __restrict__ er, GatDims dm, float* __restrict__ out, float* __restrict__ m_out,
     float* __restrict__ d_out, float* __restrict__ t_out, float* __restrict__ sg_out) {
-  constexpr int G = kWave / L;
+  // A row group has GL = L * ES lanes: L column lanes (float4 slots), replicated ES times.  The
+  // chunk phase spreads all GL lanes over (edge, head) pairs; in the row phase replica s takes
+  // the chunk's edges s, s + ES, ... and the replicas' sums are added at the end of the row.
+  // Narrow rows with many heads (8 heads x 8 columns: L = 16) would otherwise see two edges
+  // per chunk and walk a row in many short, latency-bound steps.
+  constexpr int GL = L * ES;
+  constexpr int G = kWave / GL;
   constexpr int GPB = G * (kBlock / kWave);
   constexpr int NC = (WT ? 8 : 4) * NV + 2;  // floats per lane folded across cooperating groups
-  __shared__ float lds[GPB * GroupLds<L, NV>::kFloats];
-  __shared__ float coop_buf[GPB * L * NC];
-  __shared__ float coop_m[GPB * L];
+  static_assert(GL <= kWave && (ES == 1 || NV == 1), "replicas only for rows of at most 64 float4 slots");
+  __shared__ float lds[GPB * GroupLds<GL, NV>::kFloats];
+  __shared__ float coop_buf[GPB * GL * NC];
+  __shared__ float coop_m[GPB * GL];
 
   const int lane = threadIdx.x & 63;
-  const int li = lane & (L - 1);
-  const int grp = threadIdx.x / L;  // group inside the block
+  const int li = lane & (GL - 1);
+  const int grp = threadIdx.x / GL;  // group inside the block
+  const int cl = li & (L - 1);       // column lane
+  const int rep = li / L;            // replica: which of the chunk's edges this lane adds up
   int64_t r;
   int gi, ngrp;
   RowRange rr;
   if (!pick_row<GPB>(rl, grp, rr, r, gi, ngrp)) return;  // whole group (coop: whole workgroup) leaves together
-  float* g_lds = lds + grp * GroupLds<L, NV>::kFloats;
+  float* g_lds = lds + grp * GroupLds<GL, NV>::kFloats;
   int* l_idx = reinterpret_cast<int*>(g_lds);
-  float* l_p = g_lds + L;
-  float* l_p2 = g_lds + 2 * L;
-  float* l_sc = g_lds + 3 * L;
+  float* l_p = g_lds + GL;
+  float* l_p2 = g_lds + 2 * GL;
+  float* l_sc = g_lds + 3 * GL;
 
   const int H = dm.H, HF = dm.HF;
   const int Hp = 1 << dm.log2Hp;
-  const int epc = L >> dm.log2Hp;  // edges per chunk
+  const int epc = GL >> dm.log2Hp;  // edges per chunk
   const int e_loc = li >> dm.log2Hp;
   const int h = li & (Hp - 1);
   const bool head_ok = h < H;
@@ -102,7 +111,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_fwd(
   float4 acc[NV], acc2[NV];
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
-    int col = 4 * (li + j * L);
+    int col = 4 * (cl + j * L);
     slot_ok[j] = col < HF;
     hs[j] = slot_ok[j] ? col / dm.F : 0;
     acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -120,7 +129,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_fwd(
       raw = el[(int64_t)u * H + h] + er_vh;
       s = leaky(raw, dm.slope);
     }
-    const float cmax = group_max_from<L>(s, Hp);
+    const float cmax = group_max_from<GL>(s, Hp);
     const float m_new = fmaxf(m_run, cmax);
     const float p = (e_ok && head_ok) ? __expf(s - m_new) : 0.f;
     const float sc = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
@@ -143,37 +152,37 @@ __global__ __launch_bounds__(kBlock) void k_gat_fwd(
       part2[j] = part[j];
     }
     const int cnt = min(epc, end - c0);
-    int t = 0;
-    for (; t + kU <= cnt; t += kU) {
+    int t = rep;
+    for (; t + (kU - 1) * ES < cnt; t += kU * ES) {
       int uu[kU];
       float4 row[kU][NV];
 #pragma unroll
       for (int q = 0; q < kU; ++q) {
-        uu[q] = l_idx[t + q];
+        uu[q] = l_idx[t + q * ES];
         if (L == 64) uu[q] = __builtin_amdgcn_readfirstlane(uu[q]);
       }
 #pragma unroll
       for (int q = 0; q < kU; ++q)
 #pragma unroll
         for (int j = 0; j < NV; ++j)
-          if (slot_ok[j]) row[q][j] = ld4(z + (int64_t)uu[q] * HF + 4 * (li + j * L));
+          if (slot_ok[j]) row[q][j] = ld4(z + (int64_t)uu[q] * HF + 4 * (cl + j * L));
 #pragma unroll
       for (int q = 0; q < kU; ++q)
 #pragma unroll
         for (int j = 0; j < NV; ++j)
           if (slot_ok[j]) {
-            const int pi = ((t + q) << dm.log2Hp) + hs[j];
+            const int pi = ((t + q * ES) << dm.log2Hp) + hs[j];
             fma4(part[j], l_p[pi], row[q][j]);
             if (WT) fma4(part2[j], l_p2[pi], row[q][j]);
           }
     }
-    for (; t < cnt; ++t) {
+    for (; t < cnt; t += ES) {
       int uu = l_idx[t];
       if (L == 64) uu = __builtin_amdgcn_readfirstlane(uu);
 #pragma unroll
       for (int j = 0; j < NV; ++j)
         if (slot_ok[j]) {
-          const float4 row1 = ld4(z + (int64_t)uu * HF + 4 * (li + j * L));
+          const float4 row1 = ld4(z + (int64_t)uu * HF + 4 * (cl + j * L));
           const int pi = (t << dm.log2Hp) + hs[j];
           fma4(part[j], l_p[pi], row1);
           if (WT) fma4(part2[j], l_p2[pi], row1);
@@ -211,7 +220,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_fwd(
     }
     v[NC - 2] = d_run * sc_own;
     v[NC - 1] = d2_run * sc_own;
-    coop_sum<L, NC, GPB>(coop_buf, v, grp, li);
+    coop_sum<GL, NC, GPB>(coop_buf, v, grp, li);
     if (grp != 0) return;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
@@ -222,25 +231,42 @@ __global__ __launch_bounds__(kBlock) void k_gat_fwd(
     d2_run = v[NC - 1];
     m_run = m_all;
   }
+  if (ES > 1) {  // add the replicas' sums; afterwards every replica holds the row's totals
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      for (int off = L; off < GL; off <<= 1) {
+        acc[j].x += __shfl_xor(acc[j].x, off, 64);
+        acc[j].y += __shfl_xor(acc[j].y, off, 64);
+        acc[j].z += __shfl_xor(acc[j].z, off, 64);
+        acc[j].w += __shfl_xor(acc[j].w, off, 64);
+        if (WT) {
+          acc2[j].x += __shfl_xor(acc2[j].x, off, 64);
+          acc2[j].y += __shfl_xor(acc2[j].y, off, 64);
+          acc2[j].z += __shfl_xor(acc2[j].z, off, 64);
+          acc2[j].w += __shfl_xor(acc2[j].w, off, 64);
+        }
+      }
+    }
+  }
   // denominators: sum the per-lane partials of each head, then hand them to the column lanes
-  float dd = group_sum_from<L>(d_run, Hp);
+  float dd = group_sum_from<GL>(d_run, Hp);
   const bool empty = beg == end;
   if (empty) { dd = 1.f; m_run = 0.f; }
   if (e_loc == 0) l_sc[h] = dd;
   wave_lds_fence();
 #pragma unroll
   for (int j = 0; j < NV; ++j)
-    if (slot_ok[j]) {
+    if (slot_ok[j] && rep == 0) {
       float inv = 1.f / l_sc[hs[j]];
       scale4(acc[j], inv);
-      st4(out + (int64_t)v * HF + 4 * (li + j * L), acc[j]);
+      st4(out + (int64_t)v * HF + 4 * (cl + j * L), acc[j]);
       if (WT) {
         scale4(acc2[j], inv);
-        st4(t_out + (int64_t)v * HF + 4 * (li + j * L), acc2[j]);
+        st4(t_out + (int64_t)v * HF + 4 * (cl + j * L), acc2[j]);
       }
     }
   if (WT) {
-    const float dd2 = group_sum_from<L>(d2_run, Hp);
+    const float dd2 = group_sum_from<GL>(d2_run, Hp);
     if (e_loc == 0 && head_ok) sg_out[(int64_t)v * H + h] = empty ? 0.f : dd2 / dd;
   }
   if (e_loc == 0 && head_ok) {
@@ -401,7 +427,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_dst(
 
 // ---- a5: backward, source side (CSC walk, no atomics) ------------------------------
 // dz[u] = sum_out alpha_e gout[v] + a_l del[u] + a_r der[u];  writes del[u,h] too
-template <int L, int NV>
+template <int L, int NV, int ES>
 __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
     RowLaunch rl, const int32_t* __restrict__ order_t, const int32_t* __restrict__ indptr_t,
     const int32_t* __restrict__ indices_t, const float* __restrict__ z, const float* __restrict__ el,
@@ -409,29 +435,34 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
     const float* __restrict__ a_l, const float* __restrict__ a_r, GatDims dm,
     float* __restrict__ dz, float* __restrict__ del,
     const float* __restrict__ alpha_t /* nullable: stashed softmax values, CSC order, signed */) {
-  constexpr int G = kWave / L;
+  // GL = L * ES lanes per row: L column lanes replicated ES times, as in k_gat_fwd
+  constexpr int GL = L * ES;
+  constexpr int G = kWave / GL;
   constexpr int GPB = G * (kBlock / kWave);
   constexpr int NC = 8 * NV + 1;
-  __shared__ float lds[GPB * GroupLds<L, NV>::kFloats];
-  __shared__ float coop_buf[GPB * L * NC];
+  static_assert(GL <= kWave && (ES == 1 || NV == 1), "replicas only for rows of at most 64 float4 slots");
+  __shared__ float lds[GPB * GroupLds<GL, NV>::kFloats];
+  __shared__ float coop_buf[GPB * GL * NC];
 
   const int lane = threadIdx.x & 63;
-  const int li = lane & (L - 1);
-  const int grp = threadIdx.x / L;
+  const int li = lane & (GL - 1);
+  const int grp = threadIdx.x / GL;
+  const int cl = li & (L - 1);
+  const int rep = li / L;
   int64_t r;
   int gi, ngrp;
   RowRange rr;
   if (!pick_row<GPB>(rl, grp, rr, r, gi, ngrp)) return;
-  float* g_lds = lds + grp * GroupLds<L, NV>::kFloats;
+  float* g_lds = lds + grp * GroupLds<GL, NV>::kFloats;
   int* l_idx = reinterpret_cast<int*>(g_lds);
-  float* l_p = g_lds + L;
-  float* l_p2 = g_lds + 2 * L;
-  float* l_sc = g_lds + 3 * L;
-  float* l_red = g_lds + 4 * L;
+  float* l_p = g_lds + GL;
+  float* l_p2 = g_lds + 2 * GL;
+  float* l_sc = g_lds + 3 * GL;
+  float* l_red = g_lds + 4 * GL;
 
   const int H = dm.H, HF = dm.HF;
   const int Hp = 1 << dm.log2Hp;
-  const int epc = L >> dm.log2Hp;
+  const int epc = GL >> dm.log2Hp;
   const int e_loc = li >> dm.log2Hp;
   const int h = li & (Hp - 1);
   const bool head_ok = h < H;
@@ -445,7 +476,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
   float4 acc1[NV], acc2[NV];
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
-    int col = 4 * (li + j * L);
+    int col = 4 * (cl + j * L);
     slot_ok[j] = col < HF;
     hs[j] = slot_ok[j] ? col / dm.F : 0;
     acc1[j] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -482,37 +513,37 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
       part2[j] = part1[j];
     }
     const int cnt = min(epc, end - c0);
-    int t = 0;
-    for (; t + kU <= cnt; t += kU) {
+    int t = rep;
+    for (; t + (kU - 1) * ES < cnt; t += kU * ES) {
       int vv[kU];
       float4 row[kU][NV];
 #pragma unroll
       for (int k = 0; k < kU; ++k) {
-        vv[k] = l_idx[t + k];
+        vv[k] = l_idx[t + k * ES];
         if (L == 64) vv[k] = __builtin_amdgcn_readfirstlane(vv[k]);
       }
 #pragma unroll
       for (int k = 0; k < kU; ++k)
 #pragma unroll
         for (int j = 0; j < NV; ++j)
-          if (slot_ok[j]) row[k][j] = ld4(gout + (int64_t)vv[k] * HF + 4 * (li + j * L));
+          if (slot_ok[j]) row[k][j] = ld4(gout + (int64_t)vv[k] * HF + 4 * (cl + j * L));
 #pragma unroll
       for (int k = 0; k < kU; ++k)
 #pragma unroll
         for (int j = 0; j < NV; ++j)
           if (slot_ok[j]) {
-            const int pi = ((t + k) << dm.log2Hp) + hs[j];
+            const int pi = ((t + k * ES) << dm.log2Hp) + hs[j];
             fma4(part1[j], l_p[pi], row[k][j]);
             fma4(part2[j], l_p2[pi], row[k][j]);
           }
     }
-    for (; t < cnt; ++t) {
+    for (; t < cnt; t += ES) {
       int vv = l_idx[t];
       if (L == 64) vv = __builtin_amdgcn_readfirstlane(vv);
 #pragma unroll
       for (int j = 0; j < NV; ++j)
         if (slot_ok[j]) {
-          const float4 row = ld4(gout + (int64_t)vv * HF + 4 * (li + j * L));
+          const float4 row = ld4(gout + (int64_t)vv * HF + 4 * (cl + j * L));
           const int pi = (t << dm.log2Hp) + hs[j];
           fma4(part1[j], l_p[pi], row);
           fma4(part2[j], l_p2[pi], row);
@@ -534,7 +565,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
       pack4(v + 4 * NV + 4 * j, acc2[j]);
     }
     v[NC - 1] = sd_run;
-    coop_sum<L, NC, GPB>(coop_buf, v, grp, li);
+    coop_sum<GL, NC, GPB>(coop_buf, v, grp, li);
     if (grp != 0) return;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
@@ -543,12 +574,27 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
     }
     sd_run = v[NC - 1];
   }
-  const float sd = group_sum_from<L>(sd_run, Hp);
+  if (ES > 1) {  // add the replicas' sums; afterwards every replica holds the row's totals
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      for (int off = L; off < GL; off <<= 1) {
+        acc1[j].x += __shfl_xor(acc1[j].x, off, 64);
+        acc1[j].y += __shfl_xor(acc1[j].y, off, 64);
+        acc1[j].z += __shfl_xor(acc1[j].z, off, 64);
+        acc1[j].w += __shfl_xor(acc1[j].w, off, 64);
+        acc2[j].x += __shfl_xor(acc2[j].x, off, 64);
+        acc2[j].y += __shfl_xor(acc2[j].y, off, 64);
+        acc2[j].z += __shfl_xor(acc2[j].z, off, 64);
+        acc2[j].w += __shfl_xor(acc2[j].w, off, 64);
+      }
+    }
+  }
+  const float sd = group_sum_from<GL>(sd_run, Hp);
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
     float p = 0.f;
-    if (slot_ok[j]) p = dot4(ld4(z + (int64_t)u * HF + 4 * (li + j * L)), acc2[j]);
-    l_red[j * L + li] = p;
+    if (slot_ok[j]) p = dot4(ld4(z + (int64_t)u * HF + 4 * (cl + j * L)), acc2[j]);
+    if (rep == 0) l_red[j * L + cl] = p;   // per-slot partials of <z[u], A2[u]>, read by head_sum
   }
   wave_lds_fence();
   if (e_loc == 0) {
@@ -564,8 +610,8 @@ __global__ __launch_bounds__(kBlock) void k_gat_bwd_src(
   wave_lds_fence();
 #pragma unroll
   for (int j = 0; j < NV; ++j)
-    if (slot_ok[j]) {
-      const int col = 4 * (li + j * L);
+    if (slot_ok[j] && rep == 0) {
+      const int col = 4 * (cl + j * L);
       const float dl = l_sc[hs[j]], dr = l_p[hs[j]];
       float4 o = acc1[j];
       fma4(o, dl, ld4(a_l + col));  // a_l, a_r are [H, F] = HF contiguous floats
@@ -683,27 +729,50 @@ static gnn_status_t dispatch_group(GroupShape gs, Args... args) {
   return GNN_ERR_UNSUPPORTED;
 }
 
+// Replicas of the column lanes per row group (see k_gat_fwd): doubled while the group still fits
+// a wavefront and a chunk would hold fewer than 8 edges; at most 4.
+template <int L, int NV>
+static int pick_replicas(const GatDims& dm) {
+  int es = 1;
+  if (NV == 1)
+    while (es < 4 && L * es * 2 <= kWave && ((L * es) >> dm.log2Hp) < 8) es *= 2;
+  return es;
+}
+
 template <int L, int NV>
 struct FwdLauncher {
+  template <int ES>
+  static gnn_status_t launch(const gnn_graph_t* g, const float* z, const float* el, const float* er,
+                             GatDims dm, float* out, float* m, float* d, float* t, float* sg,
+                             hipStream_t st) {
+    if constexpr (L * ES <= kWave && (ES == 1 || NV == 1)) {
+      constexpr int GL = L * ES;
+      constexpr int GPB = (kWave / GL) * (kBlock / kWave);
+      const RowSplit sp = split_rows(g, 0, GL >> dm.log2Hp, GPB);
+      // hub rows (one workgroup each) and the rest in one launch
+      const unsigned grid = sp.hub_grid + sp.rest_grid;
+      const RowLaunch rl{sp.hub.end, g->n};
+      if (grid != 0) {
+        if (t)
+          k_gat_fwd<L, NV, true, ES><<<grid, kBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, z, el,
+                                                              er, dm, out, m, d, t, sg);
+        else
+          k_gat_fwd<L, NV, false, ES><<<grid, kBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, z, el,
+                                                               er, dm, out, m, d, nullptr, nullptr);
+        GNN_LAUNCH_CHECK();
+      }
+    }
+    return GNN_OK;
+  }
   static gnn_status_t run(const gnn_graph_t* g, const float* z, const float* el, const float* er,
                           GatDims dm, float* out, float* m, float* d, float* t, float* sg,
                           hipStream_t st) {
-    constexpr int GPB = (kWave / L) * (kBlock / kWave);
     ProfScope p("gat_fwd_fused", st);
-    const RowSplit sp = split_rows(g, 0, L >> dm.log2Hp, GPB);
-    // hub rows (one workgroup each) and the rest in one launch
-    const unsigned grid = sp.hub_grid + sp.rest_grid;
-    const RowLaunch rl{sp.hub.end, g->n};
-    if (grid != 0) {
-      if (t)
-        k_gat_fwd<L, NV, true><<<grid, kBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, z, el, er,
-                                                        dm, out, m, d, t, sg);
-      else
-        k_gat_fwd<L, NV, false><<<grid, kBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, z, el,
-                                                         er, dm, out, m, d, nullptr, nullptr);
-      GNN_LAUNCH_CHECK();
+    switch (pick_replicas<L, NV>(dm)) {
+      case 4: return launch<4>(g, z, el, er, dm, out, m, d, t, sg, st);
+      case 2: return launch<2>(g, z, el, er, dm, out, m, d, t, sg, st);
+      default: return launch<1>(g, z, el, er, dm, out, m, d, t, sg, st);
     }
-    return GNN_OK;
   }
 };
 
@@ -848,21 +917,34 @@ struct BwdDstLauncher {
 
 template <int L, int NV>
 struct BwdSrcLauncher {
+  template <int ES>
+  static gnn_status_t launch(const gnn_graph_t* g, const float* z, const float* el, const float4* vstate,
+                             const float* der, const float* gout, const float* a_l, const float* a_r,
+                             GatDims dm, float* dz, float* del, const float* alpha_t, hipStream_t st) {
+    if constexpr (L * ES <= kWave && (ES == 1 || NV == 1)) {
+      constexpr int GL = L * ES;
+      constexpr int GPB = (kWave / GL) * (kBlock / kWave);
+      const RowSplit sp = split_rows(g, 1, GL >> dm.log2Hp, GPB);
+      // hub rows (one workgroup each) and the rest in one launch
+      const unsigned grid = sp.hub_grid + sp.rest_grid;
+      const RowLaunch rl{sp.hub.end, g->n};
+      if (grid != 0) {
+        k_gat_bwd_src<L, NV, ES><<<grid, kBlock, 0, st>>>(rl, g->order[1], g->indptr_t, g->indices_t, z, el,
+                                                          vstate, der, gout, a_l, a_r, dm, dz, del, alpha_t);
+        GNN_LAUNCH_CHECK();
+      }
+    }
+    return GNN_OK;
+  }
   static gnn_status_t run(const gnn_graph_t* g, const float* z, const float* el, const float4* vstate,
                           const float* der, const float* gout, const float* a_l, const float* a_r,
                           GatDims dm, float* dz, float* del, const float* alpha_t, hipStream_t st) {
-    constexpr int GPB = (kWave / L) * (kBlock / kWave);
     ProfScope p("gat_bwd_src", st);
-    const RowSplit sp = split_rows(g, 1, L >> dm.log2Hp, GPB);
-    // hub rows (one workgroup each) and the rest in one launch
-    const unsigned grid = sp.hub_grid + sp.rest_grid;
-    const RowLaunch rl{sp.hub.end, g->n};
-    if (grid != 0) {
-      k_gat_bwd_src<L, NV><<<grid, kBlock, 0, st>>>(rl, g->order[1], g->indptr_t, g->indices_t, z, el,
-                                                    vstate, der, gout, a_l, a_r, dm, dz, del, alpha_t);
-      GNN_LAUNCH_CHECK();
+    switch (pick_replicas<L, NV>(dm)) {
+      case 4: return launch<4>(g, z, el, vstate, der, gout, a_l, a_r, dm, dz, del, alpha_t, st);
+      case 2: return launch<2>(g, z, el, vstate, der, gout, a_l, a_r, dm, dz, del, alpha_t, st);
+      default: return launch<1>(g, z, el, vstate, der, gout, a_l, a_r, dm, dz, del, alpha_t, st);
     }
-    return GNN_OK;
   }
 };
 

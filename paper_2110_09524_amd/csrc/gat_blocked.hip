@@ -365,7 +365,7 @@ static gnn_status_t head_major(const gnn_graph_t* g, int H, const float* a, floa
 
 // ---- host side -------------------------------------------------------------------------
 bool gat_blocked_applies(const gnn_graph_t* g, int heads, int f) {
-  if (g->nblk <= 1 || config_get(kCfgForceSimple)) return false;
+  if (!g->blocked_pays() || config_get(kCfgForceSimple)) return false;
   const int HF = heads * f;
   Slicing sl;
   return pick_slicing(heads, HF, sl);

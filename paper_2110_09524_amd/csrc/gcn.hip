@@ -318,7 +318,7 @@ static bool gcn_slicing(int F, int& SL, int& ns) {
 }
 
 static bool gcn_blocked_applies(const gnn_graph_t* g, int F) {
-  if (g->nblk <= 1 || config_get(kCfgForceSimple)) return false;
+  if (!g->blocked_pays() || config_get(kCfgForceSimple)) return false;
   int SL, ns;
   return gcn_slicing(F, SL, ns);
 }

@@ -194,11 +194,19 @@ struct RowSplit {
   RowRange hub, rest;
   unsigned hub_grid, rest_grid;
 };
+// The threshold drops from kCoopChunks to as few as kCoopMinChunks chunks while that adds no more
+// than kCoopCheapRows cooperative rows: on a small graph the longest ordinary row is the critical
+// path of the whole launch (a chunk is a chain of dependent loads), and a few hundred extra
+// workgroups cost nothing there.
+constexpr int kCoopMinChunks = 4;
+constexpr int kCoopCheapRows = 1024;
 inline RowSplit split_rows(const gnn_graph* g, int side, int chunk_edges, int gpb) {
-  const int thr = next_pow2(kCoopChunks * chunk_edges);  // degree threshold, a power of two
-  const int k = ilog2(thr);
   // degree >= 2^k  <=>  clz32(degree) <= 31 - k: a prefix of the degree order
-  int32_t n_hub = k >= 31 ? 0 : g->h_bucket_offsets[side][32 - k];
+  auto rows_at_least = [&](int k) { return k >= 31 ? 0 : g->h_bucket_offsets[side][32 - k]; };
+  int k = ilog2(next_pow2(kCoopChunks * chunk_edges));  // degree threshold 2^k
+  const int k_min = ilog2(next_pow2(kCoopMinChunks * chunk_edges));
+  while (k > k_min && rows_at_least(k - 1) <= kCoopCheapRows) --k;
+  const int32_t n_hub = rows_at_least(k);
   RowSplit s;
   s.hub = RowRange{0, n_hub, 1};
   s.rest = RowRange{n_hub, g->n, 0};

@@ -29,7 +29,10 @@ void clear_error() { g_err[0] = 0; }
 // gcn_mapping: thread mapping of the GCN aggregation, 0 vertex-balanced, 1 edge-balanced,
 // 2 (default) per graph what gnn_gcn_tune measured, vertex-balanced where it never ran
 // gmm_mapping: the same for the forward aggregation of the GMM layer (gnn_gmm_tune)
-static std::atomic<int64_t> g_config[kCfgCount] = {{24576}, {0}, {1}, {2}, {2}};
+// blocked_min_edges: mean edges per (row, column block) from which the column-blocked kernels are
+// used (below that the per-launch cost of visiting every row outweighs the cache residency;
+// break-even measured between 12 and 24 at 1 KB rows)
+static std::atomic<int64_t> g_config[kCfgCount] = {{24576}, {0}, {1}, {2}, {2}, {16}};
 int64_t config_get(ConfigKey k) { return g_config[k].load(std::memory_order_relaxed); }
 
 // ---- profiling ---------------------------------------------------------------
@@ -114,6 +117,12 @@ extern "C" gnn_status_t gnn_config_set(const char* key, int64_t value) {
   if (std::strcmp(key, "gcn_mapping") == 0) {
     GNN_REQUIRE(value >= 0 && value <= 2, GNN_ERR_INVALID_ARG, "gnn_config_set: gcn_mapping must be 0, 1 or 2");
     g_config[kCfgGcnMapping].store(value);
+    return GNN_OK;
+  }
+  if (std::strcmp(key, "blocked_min_edges") == 0) {
+    GNN_REQUIRE(value >= 0 && value <= (1 << 20), GNN_ERR_INVALID_ARG,
+                "gnn_config_set: blocked_min_edges out of range");
+    g_config[kCfgBlockedMinEdges].store(value);
     return GNN_OK;
   }
   if (std::strcmp(key, "gmm_mapping") == 0) {

@@ -372,3 +372,32 @@ def test_fusion_with_stashing_arm_on_a_column_blocked_graph_and_bad_arguments():
                                None)
     assert e.value.status == 1
     g.close()
+
+
+def test_sparse_graph_spanning_blocks_takes_the_single_launch_kernels():
+    """Default rule: column blocking is used from 16 edges per (row, block) on average."""
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev, run_gat
+    rng = np.random.default_rng(77)
+    n = 1500
+    indptr, indices = random_graph(rng, n, 30000, self_loops=False, duplicates=True)   # 20 edges per row
+    c = synth(rng, indptr, indices, 16, 4, 64)
+
+    def kernels_used(min_edges, block_cols):
+        pk.gnn_config_set("blocked_min_edges", min_edges)
+        pk.gnn_config_set("block_cols", block_cols)
+        try:
+            g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
+            pk.gnn_prof_reset()
+            pk.gnn_prof_enable(True)
+            run_gat(c, graph=g)
+            names = set(pk.gnn_prof_report())
+            pk.gnn_prof_enable(False)
+            g.close()
+        finally:
+            pk.gnn_config_set("block_cols", 24576)
+            pk.gnn_config_set("blocked_min_edges", 0)
+        return names
+    assert "gat_head_major" not in kernels_used(16, 256)      # 6 blocks: 3.3 edges per (row, block)
+    assert "gat_head_major" not in kernels_used(16, 1024)     # 2 blocks: 10 per (row, block)
+    assert "gat_head_major" in kernels_used(8, 1024)          # the same graph with the bar at 8
