@@ -148,3 +148,86 @@ def test_far_away_kernels_contribute_nothing_and_scale_is_one_over_k():
     f2 = om.gmm_forward(indptr, indices, X, np.hstack([W1, rng.standard_normal(W1.shape)]), c, mu2,
                         np.vstack([is1, [[1.0, 1.0]]]))
     np.testing.assert_allclose(f2["out"], 0.5 * f1["out"], rtol=1e-12, atol=1e-12)
+
+
+# ---- general pseudo-coordinates and their projection ---------------------------------------
+def _pcase(seed, n=30, m=110, fin=4, fout=3, K=2, r=3):
+    rng = np.random.default_rng(seed)
+    indptr, indices = random_graph(rng, n, m, self_loops=True, duplicates=True)
+    E = len(indices)
+    return dict(indptr=indptr, indices=indices, H=rng.standard_normal((n, fin)),
+                W=rng.standard_normal((fin, K * fout)) * 0.5, pseudo=rng.uniform(-1, 1, (E, r)),
+                mu=rng.standard_normal((K, r)) * 0.4, isg=0.5 + rng.random((K, r)),
+                gout=rng.standard_normal((n, fout)), K=K, r=r, fout=fout)
+
+
+def test_general_pseudo_reduces_to_the_degree_pair_layer():
+    from oracle.segments import edge_dst
+    rng = np.random.default_rng(21)
+    n = 25
+    indptr, indices = random_graph(rng, n, 90, self_loops=True, duplicates=True)
+    H, W = rng.standard_normal((n, 5)), rng.standard_normal((5, 3 * 4))
+    c = rng.uniform(0.2, 1.0, n)
+    mu, isg = rng.standard_normal((3, 2)) * 0.3, 0.5 + rng.random((3, 2))
+    gout = rng.standard_normal((n, 4))
+    pseudo = np.stack([c[indices], c[edge_dst(indptr)]], axis=1)
+    a = om.gmm_forward(indptr, indices, H, W, c, mu, isg)
+    b = om.gmm_pseudo_forward(indptr, indices, H, W, pseudo, mu, isg)
+    np.testing.assert_allclose(b["out"], a["out"], rtol=1e-13, atol=1e-13)
+    ga = om.gmm_backward(indptr, indices, H, W, c, mu, isg, gout, a)
+    gb = om.gmm_pseudo_backward(indptr, indices, H, W, pseudo, mu, isg, gout, b)
+    for k in ("gx", "gw_fc", "gmu", "ginv_sigma"):
+        np.testing.assert_allclose(gb[k], ga[k], rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("r", [1, 3, 4])
+def test_general_pseudo_against_loops_and_finite_differences(r):
+    t = _pcase(30 + r, r=r)
+    fwd = om.gmm_pseudo_forward(t["indptr"], t["indices"], t["H"], t["W"], t["pseudo"], t["mu"], t["isg"])
+    # brute force: the definition edge by edge with an explicit diagonal covariance
+    n, K, fout = len(t["indptr"]) - 1, t["K"], t["fout"]
+    Hk = (t["H"] @ t["W"]).reshape(n, K, fout)
+    ref = np.zeros((n, fout))
+    for v in range(n):
+        for e in range(t["indptr"][v], t["indptr"][v + 1]):
+            u = t["indices"][e]
+            for k in range(K):
+                d = t["pseudo"][e] - t["mu"][k]
+                cov_inv = np.diag(t["isg"][k] ** 2)
+                ref[v] += np.exp(-0.5 * d @ cov_inv @ d) * Hk[u, k] / K
+    np.testing.assert_allclose(fwd["out"], ref, rtol=1e-12, atol=1e-13)
+    g = om.gmm_pseudo_backward(t["indptr"], t["indices"], t["H"], t["W"], t["pseudo"], t["mu"], t["isg"],
+                               t["gout"], fwd)
+
+    def loss(**kw):
+        a = dict(H=t["H"], W=t["W"], pseudo=t["pseudo"], mu=t["mu"], isg=t["isg"])
+        a.update(kw)
+        o = om.gmm_pseudo_forward(t["indptr"], t["indices"], a["H"], a["W"], a["pseudo"], a["mu"], a["isg"])["out"]
+        return float((t["gout"] * o).sum())
+    rng = np.random.default_rng(0)
+    for name, key in (("H", "gx"), ("W", "gw_fc"), ("mu", "gmu"), ("isg", "ginv_sigma"), ("pseudo", "gpseudo")):
+        idx, fd = finite_difference(lambda x, name=name: loss(**{name: x}), t[name], h=1e-6, max_entries=10, rng=rng)
+        np.testing.assert_allclose(g[key].reshape(-1)[idx], fd, rtol=2e-5, atol=1e-8, err_msg=name)
+
+
+def test_pseudo_projection_values_and_gradients():
+    rng = np.random.default_rng(40)
+    n = 12
+    indptr, indices = random_graph(rng, n, 30, self_loops=True, duplicates=False)
+    c = rng.uniform(0.2, 1.0, n)
+    P, pb = rng.standard_normal((3, 2)), rng.standard_normal(3) * 0.2
+    m = om.pseudo_projection_forward(indptr, indices, c, P, pb)
+    # one edge by hand
+    v = int(np.flatnonzero(np.diff(indptr) > 0)[0])
+    e = indptr[v]
+    u = indices[e]
+    np.testing.assert_allclose(m[e], np.tanh(P @ np.array([c[u], c[v]]) + pb), rtol=1e-14)
+    # zero projection: every coordinate is tanh(bias)
+    np.testing.assert_allclose(om.pseudo_projection_forward(indptr, indices, c, np.zeros((3, 2)), pb),
+                               np.tanh(pb)[None, :].repeat(len(indices), 0), rtol=1e-14)
+    g = rng.standard_normal(m.shape)
+    gP, gpb = om.pseudo_projection_backward(indptr, indices, c, P, pb, g)
+    _, fd = finite_difference(lambda x: float((g * om.pseudo_projection_forward(indptr, indices, c, x, pb)).sum()), P)
+    np.testing.assert_allclose(gP.reshape(-1), fd, rtol=1e-6, atol=1e-9)
+    _, fd = finite_difference(lambda x: float((g * om.pseudo_projection_forward(indptr, indices, c, P, x)).sum()), pb)
+    np.testing.assert_allclose(gpb, fd, rtol=1e-6, atol=1e-9)
