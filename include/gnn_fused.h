@@ -276,6 +276,39 @@ gnn_status_t gnn_gmm_tune(gnn_graph_t* graph, int fout, int k, const float* hk /
                           void* stream, float* ms_out /*host [2], nullable*/);
 
 /* ------------------------------------------------------------------------- *
+ * MoNet / GMMConv layer with general pseudo-coordinates (App. A.2 "GMMConv"; Sec. 7.2 uses
+ * pseudo-coordinate dimensions r = 1, 2, 3 and 2 or 3 kernels):
+ *   w_j(e) = exp(-1/2 sum_d ((pseudo[e,d] - mu[j,d]) inv_sigma[j,d])^2),   d < r
+ *   out[v] = (1/k) sum over in-edges e = (u -> v) sum_j w_j(e) hk[u,j,:],   hk = x w_fc
+ * pseudo [nnz, r] is a per-edge INPUT in CSR order (position e of `indices`).  The backward
+ * call recomputes the weights and also returns gpseudo [nnz, r] (nullable), the gradient
+ * with respect to the pseudo-coordinates, for a caller that learns them.
+ * Limits: k <= 4, r <= 4, fout % 4 == 0, fout <= 256.  Errors as for gnn_gmm_*.
+ *
+ * gnn_pseudo_proj_fwd / _bwd: the projection that makes such coordinates from a per-vertex
+ * scalar c (1/sqrt(degree) in the paper's models): pseudo[e,d] = tanh(proj_w[d,0] c[u] +
+ * proj_w[d,1] c[v] + proj_b[d]); backward returns gproj_w [r,2], gproj_b [r] from gpseudo
+ * (workspace of gnn_pseudo_proj_workspace_bytes, sums in a fixed order).
+ * ------------------------------------------------------------------------- */
+size_t gnn_gmmp_workspace_bytes(const gnn_graph_t* graph, int fin, int fout, int k);
+gnn_status_t gnn_gmmp_fwd(const gnn_graph_t* graph, int fin, int fout, int k, int r, const float* x,
+                          const float* w_fc /*[fin,k*fout]*/, const float* pseudo /*[nnz,r]*/,
+                          const float* mu /*[k,r]*/, const float* inv_sigma /*[k,r]*/,
+                          float* hk /*[n,k*fout]*/, float* out /*[n,fout]*/, void* stream);
+gnn_status_t gnn_gmmp_bwd(const gnn_graph_t* graph, int fin, int fout, int k, int r, const float* x,
+                          const float* w_fc, const float* pseudo, const float* mu, const float* inv_sigma,
+                          const float* hk, const float* gout /*[n,fout]*/, float* gx /*nullable*/,
+                          float* gw_fc, float* gmu, float* ginv_sigma, float* gpseudo /*[nnz,r] nullable*/,
+                          void* ws, size_t ws_bytes, void* stream);
+size_t gnn_pseudo_proj_workspace_bytes(const gnn_graph_t* graph);
+gnn_status_t gnn_pseudo_proj_fwd(const gnn_graph_t* graph, int r, const float* c /*[n]*/,
+                                 const float* proj_w /*[r,2]*/, const float* proj_b /*[r]*/,
+                                 float* pseudo /*[nnz,r]*/, void* stream);
+gnn_status_t gnn_pseudo_proj_bwd(const gnn_graph_t* graph, int r, const float* c, const float* pseudo,
+                                 const float* gpseudo, float* gproj_w /*[r,2]*/, float* gproj_b /*[r]*/,
+                                 void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------- *
  * GCN layer with separable static edge weights (App. A.2 "GCN", no bias, identity
  * activation):
  *   out[v] = sum over in-edges (u -> v) of  c_src[u] c_dst[v] (x w)[u]

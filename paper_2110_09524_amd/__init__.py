@@ -7,6 +7,8 @@ from .binding import (  # noqa: F401
     gnn_gat_workspace_bytes, gnn_gat_fwd, gnn_gat_bwd, gnn_gat_stash_alpha, gnn_gat_bwd_stashed,
     gnn_edgeconv_workspace_bytes, gnn_edgeconv_fwd, gnn_edgeconv_bwd,
     gnn_gmm_workspace_bytes, gnn_gmm_fwd, gnn_gmm_bwd, gnn_gmm_tune,
+    gnn_gmmp_workspace_bytes, gnn_gmmp_fwd, gnn_gmmp_bwd,
+    gnn_pseudo_proj_workspace_bytes, gnn_pseudo_proj_fwd, gnn_pseudo_proj_bwd,
     gnn_gcn_workspace_bytes, gnn_gcn_fwd, gnn_gcn_bwd, gnn_gcn_tune,
     gnn_bias_act_fwd, gnn_bias_act_workspace_bytes, gnn_bias_act_bwd,
     gnn_softmax_xent_workspace_bytes, gnn_softmax_xent, gnn_sgd_update, gnn_knn_graph,

@@ -24,7 +24,8 @@ EXPORTS = [
     "gnn_graph_get_buckets", "gnn_graph_get_blocked", "gnn_config_set", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
     "gnn_gat_bwd", "gnn_gat_stash_alpha", "gnn_gat_bwd_stashed", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
     "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd", "gnn_gmm_tune",
-    "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_gcn_tune",
+    "gnn_gmmp_workspace_bytes", "gnn_gmmp_fwd", "gnn_gmmp_bwd", "gnn_pseudo_proj_workspace_bytes",
+    "gnn_pseudo_proj_fwd", "gnn_pseudo_proj_bwd", "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_gcn_tune",
     "gnn_bias_act_fwd", "gnn_bias_act_workspace_bytes", "gnn_bias_act_bwd", "gnn_softmax_xent_workspace_bytes",
     "gnn_softmax_xent", "gnn_sgd_update", "gnn_knn_graph", "gnn_prof_enable",
     "gnn_prof_collect", "gnn_prof_reset", "gnn_prof_count", "gnn_prof_get",
@@ -68,6 +69,14 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_gmm_fwd.argtypes = [vp, i32, i32, i32] + [vp] * 7 + [vp, sz, vp]
     lib.gnn_gmm_bwd.argtypes = [vp, i32, i32, i32] + [vp] * 11 + [vp, sz, vp]
     lib.gnn_gmm_tune.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, C.POINTER(C.c_float)]
+    lib.gnn_gmmp_workspace_bytes.restype = sz
+    lib.gnn_gmmp_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    lib.gnn_gmmp_fwd.argtypes = [vp, i32, i32, i32, i32] + [vp] * 7 + [vp]
+    lib.gnn_gmmp_bwd.argtypes = [vp, i32, i32, i32, i32] + [vp] * 12 + [vp, sz, vp]
+    lib.gnn_pseudo_proj_workspace_bytes.restype = sz
+    lib.gnn_pseudo_proj_workspace_bytes.argtypes = [vp]
+    lib.gnn_pseudo_proj_fwd.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+    lib.gnn_pseudo_proj_bwd.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.gnn_gcn_workspace_bytes.restype = sz
     lib.gnn_gcn_workspace_bytes.argtypes = [vp, i32, i32]
     lib.gnn_gcn_fwd.argtypes = [vp, i32, i32] + [vp] * 6 + [vp]
@@ -91,7 +100,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         fn = getattr(lib, name)
         if name not in ("gnn_last_error", "gnn_gat_workspace_bytes", "gnn_edgeconv_workspace_bytes",
                         "gnn_gmm_workspace_bytes", "gnn_gcn_workspace_bytes", "gnn_prof_count",
-                        "gnn_bias_act_workspace_bytes", "gnn_softmax_xent_workspace_bytes"):
+                        "gnn_bias_act_workspace_bytes", "gnn_softmax_xent_workspace_bytes",
+                        "gnn_gmmp_workspace_bytes", "gnn_pseudo_proj_workspace_bytes"):
             fn.restype = C.c_int
     return lib
 
@@ -287,6 +297,37 @@ def gnn_gmm_tune(g: Graph, fout, k, hk, c, mu, inv_sigma, out, stream=None):
     ms = (C.c_float * 2)()
     _check(lib().gnn_gmm_tune(g.handle, fout, k, _f(hk), _f(c), _f(mu), _f(inv_sigma), _f(out), _stream(stream), ms))
     return [float(v) for v in ms]
+
+
+def gnn_gmmp_workspace_bytes(g: Graph, fin, fout, k) -> int:
+    return int(lib().gnn_gmmp_workspace_bytes(g.handle, fin, fout, k))
+
+
+def gnn_gmmp_fwd(g: Graph, fin, fout, k, r, x, w_fc, pseudo, mu, inv_sigma, hk, out, stream=None):
+    _check(lib().gnn_gmmp_fwd(g.handle, fin, fout, k, r, _f(x), _f(w_fc), _f(pseudo), _f(mu), _f(inv_sigma),
+                              _f(hk), _f(out), _stream(stream)))
+
+
+def gnn_gmmp_bwd(g: Graph, fin, fout, k, r, x, w_fc, pseudo, mu, inv_sigma, hk, gout, gx, gw_fc, gmu, ginv_sigma,
+                 gpseudo, ws, stream=None):
+    wp, wb = _ws_args(ws)
+    _check(lib().gnn_gmmp_bwd(g.handle, fin, fout, k, r, _f(x), _f(w_fc), _f(pseudo), _f(mu), _f(inv_sigma),
+                              _f(hk), _f(gout), _f(gx), _f(gw_fc), _f(gmu), _f(ginv_sigma), _f(gpseudo), wp, wb,
+                              _stream(stream)))
+
+
+def gnn_pseudo_proj_workspace_bytes(g: Graph) -> int:
+    return int(lib().gnn_pseudo_proj_workspace_bytes(g.handle))
+
+
+def gnn_pseudo_proj_fwd(g: Graph, r, c, proj_w, proj_b, pseudo, stream=None):
+    _check(lib().gnn_pseudo_proj_fwd(g.handle, r, _f(c), _f(proj_w), _f(proj_b), _f(pseudo), _stream(stream)))
+
+
+def gnn_pseudo_proj_bwd(g: Graph, r, c, pseudo, gpseudo, gproj_w, gproj_b, ws, stream=None):
+    wp, wb = _ws_args(ws)
+    _check(lib().gnn_pseudo_proj_bwd(g.handle, r, _f(c), _f(pseudo), _f(gpseudo), _f(gproj_w), _f(gproj_b), wp, wb,
+                                     _stream(stream)))
 
 
 ACTS = {"identity": 0, "relu": 1, "elu": 2, "leaky": 3}

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgnnfused.so")
-SOURCES = ["runtime.hip", "plan.hip", "gemm.hip", "gat.hip", "gat_blocked.hip", "edgeconv.hip", "gmm.hip", "gcn.hip", "apply.hip", "knn.hip"]
+SOURCES = ["runtime.hip", "plan.hip", "gemm.hip", "gat.hip", "gat_blocked.hip", "edgeconv.hip", "gmm.hip", "gmm_pseudo.hip", "gcn.hip", "apply.hip", "knn.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=default",

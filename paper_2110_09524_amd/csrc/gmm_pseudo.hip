@@ -1,0 +1,535 @@
+// MoNet / GMMConv layer with general pseudo-coordinates (App. A.2 "GMMConv": w_k(m) for an
+// r-dimensional m_uv; Sec. 7.2 uses r = 1, 2, 3), and the learnable projection of the degree
+// pair that produces them.
+//
+//   w_k(e)  = exp(-1/2 sum_d ((m[e,d] - mu[k,d]) inv_sigma[k,d])^2)            (ApplyEdge)
+//   out[v]  = (1/K) sum_in-edges sum_k w_k(e) hk[u,k,:]                         (Aggregate)
+//
+// m is a per-edge input [E, r] in CSR order (an input like the graph itself, not an
+// intermediate: nothing else per-edge is stored).  Forward fuses the Gaussian weights with the
+// aggregation as in the degree-pair layer.  Backward recomputes the weights:
+//   destination side (CSR walk): dw_k(e) = <gout[v], hk[u,k,:]> / K needs one dot product per edge
+//     and kernel here (the pseudo-coordinates vary freely along a row, so the dot product cannot
+//     be postponed past the neighbourhood sum as in the degree-pair layer); from it
+//     gmu, ginv_sigma (summed over all edges in a fixed two-stage order) and gm[e,:];
+//   source side (CSC walk, no atomics): dhk[u,k,:] = (1/K) sum_out-edges w_k(e) gout[v,:],
+//     with m read through the plan's CSC position -> CSR edge id table.
+// At most 4 kernels and 4 pseudo-coordinate dimensions; fout <= 256.
+#include <type_traits>
+
+#include "common.h"
+#include "rowgroup.h"
+
+namespace gnn {
+
+constexpr int kPsBlock = 256;
+constexpr int kPsK = 4;   // kernels
+constexpr int kPsR = 4;   // pseudo-coordinate dimensions
+constexpr int kPsVals = 2 * kPsK * kPsR;  // gmu and ginv_sigma entries per partial slot
+
+struct PsParams {
+  int K, R, F;
+};
+
+// the K x R means and inverse widths, zero-padded, in registers (uniform)
+struct PsKernels {
+  float mu[kPsK][kPsR], is[kPsK][kPsR];
+};
+__device__ __forceinline__ PsKernels load_kernels(const float* __restrict__ mu, const float* __restrict__ is,
+                                                  int K, int R) {
+  PsKernels p;
+#pragma unroll
+  for (int k = 0; k < kPsK; ++k)
+#pragma unroll
+    for (int d = 0; d < kPsR; ++d) {
+      const bool ok = k < K && d < R;
+      p.mu[k][d] = ok ? mu[k * R + d] : 0.f;
+      p.is[k][d] = ok ? is[k * R + d] : 0.f;
+    }
+  return p;
+}
+__device__ __forceinline__ void load_pseudo(const float* __restrict__ m, int64_t e, int R, float (&out)[kPsR]) {
+#pragma unroll
+  for (int d = 0; d < kPsR; ++d) out[d] = d < R ? m[e * R + d] : 0.f;
+}
+__device__ __forceinline__ float gauss_k(const PsKernels& p, int k, const float (&m)[kPsR]) {
+  float q = 0.f;
+#pragma unroll
+  for (int d = 0; d < kPsR; ++d) {  // padded dimensions have inv_sigma 0
+    const float t = (m[d] - p.mu[k][d]) * p.is[k][d];
+    q = fmaf(t, t, q);
+  }
+  return __expf(-0.5f * q);
+}
+
+// ---- forward: one row group per destination (hub rows: one workgroup), one edge at a time ----
+template <int L>
+__global__ __launch_bounds__(kPsBlock) void k_gmmp_fwd(
+    RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    const int32_t* __restrict__ indices, const float* __restrict__ hk, const float* __restrict__ pseudo,
+    const float* __restrict__ mu, const float* __restrict__ inv_sigma, PsParams pm, float* __restrict__ out) {
+  constexpr int GPB = kPsBlock / L;
+  __shared__ float coop_buf[GPB * L * 4];
+  const int li = threadIdx.x & (L - 1);
+  const int grp = threadIdx.x / L;
+  int64_t r;
+  int gi, ngrp;
+  RowRange rr;
+  if (!pick_row<GPB>(rl, grp, rr, r, gi, ngrp)) return;
+  const int K = pm.K, R = pm.R, F = pm.F, KF = K * F;
+  const float inv_k = 1.f / (float)K;
+  const PsKernels pk = load_kernels(mu, inv_sigma, K, R);
+  const int32_t v = order[r];
+  const int32_t beg = indptr[v], end = indptr[v + 1];
+  const bool col_ok = 4 * li < F;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f), part = acc;
+  int folded = 0;
+  for (int32_t e = beg + gi; e < end; e += ngrp) {
+    const int32_t u = indices[e];
+    float m[kPsR];
+    load_pseudo(pseudo, e, R, m);
+    if (col_ok) {
+      float4 rowv[kPsK];
+#pragma unroll
+      for (int k = 0; k < kPsK; ++k)
+        if (k < K) rowv[k] = ld4(hk + (int64_t)u * KF + k * F + 4 * li);
+#pragma unroll
+      for (int k = 0; k < kPsK; ++k)
+        if (k < K) fma4(part, gauss_k(pk, k, m) * inv_k, rowv[k]);
+    }
+    if (++folded == 32) {  // two-level summation keeps long rows accurate
+      add4(acc, part);
+      part = make_float4(0.f, 0.f, 0.f, 0.f);
+      folded = 0;
+    }
+  }
+  add4(acc, part);
+  if (rr.coop) {
+    float vv[4];
+    pack4(vv, acc);
+    coop_sum<L, 4, GPB>(coop_buf, vv, grp, li);
+    if (grp != 0) return;
+    acc = unpack4(vv);
+  }
+  if (col_ok) st4(out + (int64_t)v * F + 4 * li, acc);
+}
+
+// ---- backward, destination side: gmu, ginv_sigma partials and gm[e,:] -------------------------
+// partial[block][kPsVals]: entries k*R+d of gmu, then of ginv_sigma, summed over the block's edges
+// in a fixed order (group slots, then groups in order).
+template <int L>
+__global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_dst(
+    RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    const int32_t* __restrict__ indices, const float* __restrict__ hk, const float* __restrict__ pseudo,
+    const float* __restrict__ mu, const float* __restrict__ inv_sigma, const float* __restrict__ gout,
+    PsParams pm, float* __restrict__ partial, float* __restrict__ gpseudo /* nullable */) {
+  constexpr int GPB = kPsBlock / L;
+  __shared__ float blk[GPB][kPsVals];
+  const int li = threadIdx.x & (L - 1);
+  const int grp = threadIdx.x / L;
+  int64_t r;
+  int gi, ngrp;
+  RowRange rr;
+  const bool active = pick_row<GPB>(rl, grp, rr, r, gi, ngrp);
+  const int K = pm.K, R = pm.R, F = pm.F, KF = K * F;
+  const float inv_k = 1.f / (float)K;
+  float gm_acc[kPsK][kPsR], gs_acc[kPsK][kPsR];  // every lane of the group keeps the same sums
+#pragma unroll
+  for (int k = 0; k < kPsK; ++k)
+#pragma unroll
+    for (int d = 0; d < kPsR; ++d) {
+      gm_acc[k][d] = 0.f;
+      gs_acc[k][d] = 0.f;
+    }
+  if (active) {
+    const PsKernels pk = load_kernels(mu, inv_sigma, K, R);
+    const int32_t v = order[r];
+    const int32_t beg = indptr[v], end = indptr[v + 1];
+    const bool col_ok = 4 * li < F;
+    const float4 g4 = col_ok ? ld4(gout + (int64_t)v * F + 4 * li) : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int32_t e = beg + gi; e < end; e += ngrp) {
+      const int32_t u = indices[e];
+      float m[kPsR];
+      load_pseudo(pseudo, e, R, m);
+      float dots[kPsK];
+#pragma unroll
+      for (int k = 0; k < kPsK; ++k) {
+        dots[k] = 0.f;
+        if (k < K && col_ok) dots[k] = dot4(g4, ld4(hk + (int64_t)u * KF + k * F + 4 * li));
+      }
+      float gm[kPsR];
+#pragma unroll
+      for (int d = 0; d < kPsR; ++d) gm[d] = 0.f;
+#pragma unroll
+      for (int k = 0; k < kPsK; ++k) {
+        if (k >= K) continue;
+        const float dw = group_sum_from<L>(dots[k], 1) * inv_k;  // <gout[v], hk[u,k,:]> / K, in every lane
+        const float dlog = dw * gauss_k(pk, k, m);
+#pragma unroll
+        for (int d = 0; d < kPsR; ++d) {
+          const float diff = m[d] - pk.mu[k][d];
+          const float is = pk.is[k][d];
+          const float t = dlog * diff * is;  // padded dimensions: is = 0
+          gm_acc[k][d] = fmaf(t, is, gm_acc[k][d]);
+          gs_acc[k][d] = fmaf(-t, diff, gs_acc[k][d]);
+          gm[d] = fmaf(-t, is, gm[d]);
+        }
+      }
+      if (gpseudo != nullptr && li == 0) {
+#pragma unroll
+        for (int d = 0; d < kPsR; ++d)
+          if (d < R) gpseudo[(int64_t)e * R + d] = gm[d];
+      }
+    }
+  }
+  // lane 0 of every group parks its sums; then one thread per entry adds the groups in order
+  if (li == 0) {
+#pragma unroll
+    for (int k = 0; k < kPsK; ++k)
+#pragma unroll
+      for (int d = 0; d < kPsR; ++d) {
+        blk[grp][k * kPsR + d] = gm_acc[k][d];
+        blk[grp][kPsK * kPsR + k * kPsR + d] = gs_acc[k][d];
+      }
+  }
+  __syncthreads();
+  if (threadIdx.x < kPsVals) {
+    float s = 0.f;
+    for (int g2 = 0; g2 < GPB; ++g2) s += blk[g2][threadIdx.x];
+    partial[(int64_t)blockIdx.x * kPsVals + threadIdx.x] = s;
+  }
+}
+
+// totals [kPsVals] (padded K x R layout) -> gmu, ginv_sigma [K, R]
+__global__ void k_gmmp_param_split(int K, int R, const float* __restrict__ totals, float* __restrict__ gmu,
+                                   float* __restrict__ gis) {
+  const int i = threadIdx.x;
+  if (i >= K * R) return;
+  const int k = i / R, d = i - k * R;
+  gmu[i] = totals[k * kPsR + d];
+  gis[i] = totals[kPsK * kPsR + k * kPsR + d];
+}
+
+// ---- backward, source side: dhk[u,k,:] = (1/K) sum over out-edges w_k(e) gout[v,:] ------------
+template <int L>
+__global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_src(
+    RowLaunch rl, const int32_t* __restrict__ order_t, const int32_t* __restrict__ indptr_t,
+    const int32_t* __restrict__ indices_t, const int32_t* __restrict__ eid_t,
+    const float* __restrict__ pseudo, const float* __restrict__ mu, const float* __restrict__ inv_sigma,
+    const float* __restrict__ gout, PsParams pm, float* __restrict__ dhk) {
+  constexpr int GPB = kPsBlock / L;
+  __shared__ float coop_buf[GPB * L * 4 * kPsK];
+  const int li = threadIdx.x & (L - 1);
+  const int grp = threadIdx.x / L;
+  int64_t r;
+  int gi, ngrp;
+  RowRange rr;
+  if (!pick_row<GPB>(rl, grp, rr, r, gi, ngrp)) return;
+  const int K = pm.K, R = pm.R, F = pm.F, KF = K * F;
+  const float inv_k = 1.f / (float)K;
+  const PsKernels pk = load_kernels(mu, inv_sigma, K, R);
+  const int32_t u = order_t[r];
+  const int32_t beg = indptr_t[u], end = indptr_t[u + 1];
+  const bool col_ok = 4 * li < F;
+  float4 acc[kPsK];
+#pragma unroll
+  for (int k = 0; k < kPsK; ++k) acc[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int32_t p = beg + gi; p < end; p += ngrp) {
+    const int32_t v = indices_t[p];
+    float m[kPsR];
+    load_pseudo(pseudo, eid_t[p], R, m);
+    if (col_ok) {
+      const float4 g4 = ld4(gout + (int64_t)v * F + 4 * li);
+#pragma unroll
+      for (int k = 0; k < kPsK; ++k)
+        if (k < K) fma4(acc[k], gauss_k(pk, k, m) * inv_k, g4);
+    }
+  }
+  if (rr.coop) {
+    float vv[4 * kPsK];
+#pragma unroll
+    for (int k = 0; k < kPsK; ++k) pack4(vv + 4 * k, acc[k]);
+    coop_sum<L, 4 * kPsK, GPB>(coop_buf, vv, grp, li);
+    if (grp != 0) return;
+#pragma unroll
+    for (int k = 0; k < kPsK; ++k) acc[k] = unpack4(vv + 4 * k);
+  }
+  if (col_ok) {
+#pragma unroll
+    for (int k = 0; k < kPsK; ++k)
+      if (k < K) st4(dhk + (int64_t)u * KF + k * F + 4 * li, acc[k]);
+  }
+}
+
+// ---- the projection that makes pseudo-coordinates from the degree pair ------------------------
+// m[e,d] = tanh(P[d,0] c[u] + P[d,1] c[v] + pb[d]); one thread per edge; dst_of[e] by walking rows
+__global__ void k_pseudo_proj_fwd(int32_t n, const int32_t* __restrict__ indptr,
+                                  const int32_t* __restrict__ indices, const float* __restrict__ c, int R,
+                                  const float* __restrict__ P, const float* __restrict__ pb,
+                                  float* __restrict__ pseudo) {
+  // one wavefront per destination row, lanes over its edges
+  const int lane = threadIdx.x & 63;
+  const int64_t v = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) >> 6;
+  if (v >= n) return;
+  const float cv = c[v];
+  for (int32_t e = indptr[v] + lane; e < indptr[v + 1]; e += 64) {
+    const float cu = c[indices[e]];
+    for (int d = 0; d < R; ++d) pseudo[(int64_t)e * R + d] = tanhf(fmaf(P[2 * d], cu, fmaf(P[2 * d + 1], cv, pb[d])));
+  }
+}
+
+// partial[block][3 * kPsR]: (gP[d,0], gP[d,1], gpb[d]) for d < kPsR, summed over the block's rows
+__global__ __launch_bounds__(kPsBlock) void k_pseudo_proj_bwd(
+    int32_t n, const int32_t* __restrict__ indptr, const int32_t* __restrict__ indices,
+    const float* __restrict__ c, int R, const float* __restrict__ pseudo, const float* __restrict__ gpseudo,
+    int32_t rows_per_block, float* __restrict__ partial) {
+  __shared__ float red[kPsBlock / 64][3 * kPsR];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  float s[3 * kPsR];
+#pragma unroll
+  for (int i = 0; i < 3 * kPsR; ++i) s[i] = 0.f;
+  const int64_t v0 = (int64_t)blockIdx.x * rows_per_block;
+  const int64_t v1 = v0 + rows_per_block < n ? v0 + rows_per_block : n;
+  for (int64_t v = v0 + w; v < v1; v += kPsBlock / 64) {
+    const float cv = c[v];
+    for (int32_t e = indptr[v] + lane; e < indptr[v + 1]; e += 64) {
+      const float cu = c[indices[e]];
+#pragma unroll
+      for (int d = 0; d < kPsR; ++d) {
+        if (d >= R) continue;
+        const float m = pseudo[(int64_t)e * R + d];
+        const float dpre = gpseudo[(int64_t)e * R + d] * (1.f - m * m);
+        s[3 * d] = fmaf(dpre, cu, s[3 * d]);
+        s[3 * d + 1] = fmaf(dpre, cv, s[3 * d + 1]);
+        s[3 * d + 2] += dpre;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 3 * kPsR; ++i) {
+    float t = s[i];
+    for (int off = 1; off < 64; off <<= 1) t += __shfl_xor(t, off, 64);
+    if (lane == 0) red[w][i] = t;
+  }
+  __syncthreads();
+  if (threadIdx.x < 3 * kPsR) {
+    float t = 0.f;
+    for (int q = 0; q < kPsBlock / 64; ++q) t += red[q][threadIdx.x];
+    partial[(int64_t)blockIdx.x * 3 * kPsR + threadIdx.x] = t;
+  }
+}
+
+__global__ void k_pseudo_proj_split(int R, const float* __restrict__ totals, float* __restrict__ gP,
+                                    float* __restrict__ gpb) {
+  const int d = threadIdx.x;
+  if (d >= R) return;
+  gP[2 * d] = totals[3 * d];
+  gP[2 * d + 1] = totals[3 * d + 1];
+  gpb[d] = totals[3 * d + 2];
+}
+
+// ---- host side --------------------------------------------------------------------------
+template <int L>
+static unsigned ps_grid(const gnn_graph_t* g, int side, RowLaunch& rl) {
+  constexpr int GPB = kPsBlock / L;
+  const RowSplit sp = split_rows(g, side, 4, GPB);  // edges are taken one at a time: count 4 as a chunk
+  rl = RowLaunch{sp.hub.end, g->n};
+  return sp.hub_grid + sp.rest_grid;
+}
+
+static int ps_lanes(int fout) { return pick_group(fout).L; }  // fout <= 256: one float4 slot per lane
+
+static int64_t ps_dst_blocks(const gnn_graph_t* g, int fout) {
+  RowLaunch rl;
+  switch (ps_lanes(fout)) {
+    case 4: return ps_grid<4>(g, 0, rl);
+    case 8: return ps_grid<8>(g, 0, rl);
+    case 16: return ps_grid<16>(g, 0, rl);
+    case 32: return ps_grid<32>(g, 0, rl);
+    default: return ps_grid<64>(g, 0, rl);
+  }
+}
+
+struct GmmpWs {
+  size_t total, dhk, partial, gemm;
+  int split_k;
+  int64_t nblk;
+};
+static GmmpWs gmmp_ws_layout(const gnn_graph_t* g, int fin, int fout, int K) {
+  GmmpWs w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += ws_granule(bytes); return o; };
+  w.nblk = ps_dst_blocks(g, fout);
+  w.dhk = take(sizeof(float) * (size_t)g->n * K * fout);
+  w.partial = take(sizeof(float) * (size_t)(w.nblk + 1 + sum_partials_scratch_rows((int)w.nblk)) * kPsVals);
+  w.split_k = gemm_pick_split_k(fin, K * fout, g->n);
+  w.gemm = take(w.split_k > 1 ? sizeof(float) * (size_t)w.split_k * fin * K * fout : 0);
+  w.total = off;
+  return w;
+}
+
+static gnn_status_t gmmp_check(const gnn_graph_t* g, int fin, int fout, int K, int R, const char* who) {
+  GNN_REQUIRE(g != nullptr, GNN_ERR_INVALID_ARG, "%s: graph is null", who);
+  GNN_REQUIRE(fin > 0 && fout > 0 && K > 0 && R > 0, GNN_ERR_INVALID_ARG, "%s: sizes must be positive", who);
+  GNN_REQUIRE(fout % 4 == 0 && fout <= 256, GNN_ERR_UNSUPPORTED,
+              "%s: fout = %d must be a multiple of 4, at most 256", who, fout);
+  GNN_REQUIRE(K <= kPsK && R <= kPsR, GNN_ERR_UNSUPPORTED, "%s: at most %d kernels and %d dimensions", who, kPsK,
+              kPsR);
+  return GNN_OK;
+}
+
+// calls fn with the lane count of a row group as a compile-time constant
+template <typename Fn>
+static gnn_status_t for_lanes(int lanes, Fn fn) {
+  switch (lanes) {
+    case 4: return fn(std::integral_constant<int, 4>{});
+    case 8: return fn(std::integral_constant<int, 8>{});
+    case 16: return fn(std::integral_constant<int, 16>{});
+    case 32: return fn(std::integral_constant<int, 32>{});
+    default: return fn(std::integral_constant<int, 64>{});
+  }
+}
+
+}  // namespace gnn
+
+using namespace gnn;
+
+extern "C" size_t gnn_gmmp_workspace_bytes(const gnn_graph_t* g, int fin, int fout, int k) {
+  if (!g || fin <= 0 || fout <= 0 || k <= 0 || fout % 4 != 0 || fout > 256) return 0;
+  return gmmp_ws_layout(g, fin, fout, k).total;
+}
+
+extern "C" gnn_status_t gnn_gmmp_fwd(const gnn_graph_t* g, int fin, int fout, int k, int r, const float* x,
+                                     const float* w_fc, const float* pseudo, const float* mu,
+                                     const float* inv_sigma, float* hk, float* out, void* stream) {
+  clear_error();
+  GNN_TRY(gmmp_check(g, fin, fout, k, r, "gnn_gmmp_fwd"));
+  if (g->n == 0) return GNN_OK;
+  GNN_REQUIRE(x && w_fc && mu && inv_sigma && hk && out && (pseudo || g->nnz == 0), GNN_ERR_INVALID_ARG,
+              "gnn_gmmp_fwd: null pointer");
+  GNN_REQUIRE(aligned16(hk) && aligned16(out), GNN_ERR_INVALID_ARG, "gnn_gmmp_fwd: hk, out must be 16-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  GNN_TRY(gemm_f32(g->n, k * fout, fin, x, fin, false, w_fc, k * fout, false, hk, k * fout, 1, nullptr, st));
+  const PsParams pm{k, r, fout};
+  ProfScope p("gmmp_fwd_fused", st);
+  return for_lanes(ps_lanes(fout), [&](auto lanes) -> gnn_status_t {
+    constexpr int L = decltype(lanes)::value;
+    RowLaunch rl;
+    const unsigned grid = ps_grid<L>(g, 0, rl);
+    if (grid != 0) {
+      k_gmmp_fwd<L><<<grid, kPsBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, hk, pseudo, mu, inv_sigma,
+                                              pm, out);
+      GNN_LAUNCH_CHECK();
+    }
+    return GNN_OK;
+  });
+}
+
+extern "C" gnn_status_t gnn_gmmp_bwd(const gnn_graph_t* g, int fin, int fout, int k, int r, const float* x,
+                                     const float* w_fc, const float* pseudo, const float* mu,
+                                     const float* inv_sigma, const float* hk, const float* gout, float* gx,
+                                     float* gw_fc, float* gmu, float* ginv_sigma, float* gpseudo, void* ws,
+                                     size_t ws_bytes, void* stream) {
+  clear_error();
+  GNN_TRY(gmmp_check(g, fin, fout, k, r, "gnn_gmmp_bwd"));
+  if (g->n == 0) return GNN_OK;
+  GNN_REQUIRE(x && w_fc && mu && inv_sigma && hk && gout && gw_fc && gmu && ginv_sigma && (pseudo || g->nnz == 0),
+              GNN_ERR_INVALID_ARG, "gnn_gmmp_bwd: null pointer");
+  GNN_REQUIRE(aligned16(hk) && aligned16(gout), GNN_ERR_INVALID_ARG,
+              "gnn_gmmp_bwd: hk, gout must be 16-byte aligned");
+  const GmmpWs W = gmmp_ws_layout(g, fin, fout, k);
+  GNN_REQUIRE(ws != nullptr && ws_bytes >= W.total, GNN_ERR_WORKSPACE,
+              "gnn_gmmp_bwd: workspace of %zu bytes given, %zu needed", ws_bytes, W.total);
+  GNN_REQUIRE(aligned16(ws), GNN_ERR_INVALID_ARG, "gnn_gmmp_bwd: workspace must be 16-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* base = static_cast<char*>(ws);
+  float* dhk = reinterpret_cast<float*>(base + W.dhk);
+  float* partial = reinterpret_cast<float*>(base + W.partial);
+  float* part = reinterpret_cast<float*>(base + W.gemm);
+  const PsParams pm{k, r, fout};
+  const int KF = k * fout;
+  {
+    ProfScope p("gmmp_bwd_dst", st);
+    unsigned grid = 0;
+    GNN_TRY(for_lanes(ps_lanes(fout), [&](auto lanes) -> gnn_status_t {
+      constexpr int L = decltype(lanes)::value;
+      RowLaunch rl;
+      grid = ps_grid<L>(g, 0, rl);
+      if (grid != 0) {
+        k_gmmp_bwd_dst<L><<<grid, kPsBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, hk, pseudo, mu,
+                                                    inv_sigma, gout, pm, partial, gpseudo);
+        GNN_LAUNCH_CHECK();
+      }
+      return GNN_OK;
+    }));
+    float* totals = partial + (int64_t)grid * kPsVals;
+    GNN_TRY(sum_partials_two_level(kPsVals, (int)grid, partial, totals + kPsVals, totals, st));
+    k_gmmp_param_split<<<1, 64, 0, st>>>(k, r, totals, gmu, ginv_sigma);
+    GNN_LAUNCH_CHECK();
+  }
+  {
+    ProfScope p("gmmp_bwd_src", st);
+    GNN_TRY(for_lanes(ps_lanes(fout), [&](auto lanes) -> gnn_status_t {
+      constexpr int L = decltype(lanes)::value;
+      RowLaunch rl;
+      const unsigned grid = ps_grid<L>(g, 1, rl);
+      if (grid != 0) {
+        k_gmmp_bwd_src<L><<<grid, kPsBlock, 0, st>>>(rl, g->order[1], g->indptr_t, g->indices_t, g->eid_t, pseudo,
+                                                    mu, inv_sigma, gout, pm, dhk);
+        GNN_LAUNCH_CHECK();
+      }
+      return GNN_OK;
+    }));
+  }
+  GNN_TRY(gemm_f32(fin, KF, g->n, x, fin, true, dhk, KF, false, gw_fc, KF, W.split_k, part, st));
+  if (gx) GNN_TRY(gemm_f32(g->n, fin, KF, dhk, KF, false, w_fc, KF, true, gx, fin, 1, nullptr, st));
+  return GNN_OK;
+}
+
+constexpr int kProjRowsPerBlock = 256;
+
+extern "C" size_t gnn_pseudo_proj_workspace_bytes(const gnn_graph_t* g) {
+  if (!g) return 0;
+  const int64_t blocks = cdiv(g->n > 0 ? g->n : 1, kProjRowsPerBlock);
+  return ws_granule(sizeof(float) * (size_t)(blocks + 1 + sum_partials_scratch_rows((int)blocks)) * 3 * kPsR);
+}
+
+extern "C" gnn_status_t gnn_pseudo_proj_fwd(const gnn_graph_t* g, int r, const float* c, const float* proj_w,
+                                            const float* proj_b, float* pseudo, void* stream) {
+  clear_error();
+  GNN_REQUIRE(g != nullptr, GNN_ERR_INVALID_ARG, "gnn_pseudo_proj_fwd: graph is null");
+  GNN_REQUIRE(r > 0 && r <= kPsR, GNN_ERR_UNSUPPORTED, "gnn_pseudo_proj_fwd: r = %d outside 1..%d", r, kPsR);
+  if (g->n == 0 || g->nnz == 0) return GNN_OK;
+  GNN_REQUIRE(c && proj_w && proj_b && pseudo, GNN_ERR_INVALID_ARG, "gnn_pseudo_proj_fwd: null pointer");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  ProfScope p("pseudo_proj_fwd", st);
+  k_pseudo_proj_fwd<<<(unsigned)cdiv((int64_t)g->n * 64, 256), 256, 0, st>>>(g->n, g->indptr, g->indices, c, r,
+                                                                            proj_w, proj_b, pseudo);
+  GNN_LAUNCH_CHECK();
+  return GNN_OK;
+}
+
+extern "C" gnn_status_t gnn_pseudo_proj_bwd(const gnn_graph_t* g, int r, const float* c, const float* pseudo,
+                                            const float* gpseudo, float* gproj_w, float* gproj_b, void* ws,
+                                            size_t ws_bytes, void* stream) {
+  clear_error();
+  GNN_REQUIRE(g != nullptr, GNN_ERR_INVALID_ARG, "gnn_pseudo_proj_bwd: graph is null");
+  GNN_REQUIRE(r > 0 && r <= kPsR, GNN_ERR_UNSUPPORTED, "gnn_pseudo_proj_bwd: r = %d outside 1..%d", r, kPsR);
+  GNN_REQUIRE(gproj_w && gproj_b, GNN_ERR_INVALID_ARG, "gnn_pseudo_proj_bwd: null pointer");
+  GNN_REQUIRE(ws != nullptr && ws_bytes >= gnn_pseudo_proj_workspace_bytes(g), GNN_ERR_WORKSPACE,
+              "gnn_pseudo_proj_bwd: workspace of %zu bytes given, %zu needed", ws_bytes,
+              gnn_pseudo_proj_workspace_bytes(g));
+  GNN_REQUIRE(g->nnz == 0 || (c && pseudo && gpseudo), GNN_ERR_INVALID_ARG, "gnn_pseudo_proj_bwd: null pointer");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  ProfScope p("pseudo_proj_bwd", st);
+  const int blocks = (int)cdiv(g->n > 0 ? g->n : 1, kProjRowsPerBlock);
+  float* partial = static_cast<float*>(ws);
+  k_pseudo_proj_bwd<<<blocks, kPsBlock, 0, st>>>(g->n, g->indptr, g->indices, c, r, pseudo, gpseudo,
+                                                 kProjRowsPerBlock, partial);
+  GNN_LAUNCH_CHECK();
+  float* totals = partial + (int64_t)blocks * 3 * kPsR;
+  GNN_TRY(sum_partials_two_level(3 * kPsR, blocks, partial, totals + 3 * kPsR, totals, st));
+  k_pseudo_proj_split<<<1, 64, 0, st>>>(r, totals, gproj_w, gproj_b);
+  GNN_LAUNCH_CHECK();
+  return GNN_OK;
+}
