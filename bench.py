@@ -217,6 +217,29 @@ def cpu_baseline_ec2(c, sample_clouds=2):
             "measured_s": dt}
 
 
+def cpu_baseline_monet(c, budget_rows):
+    """The oracle on the in-edges of sampled destination rows (projection, layer forward and backward)."""
+    import numpy as np
+    from oracle import gmm as om
+    from oracle.segments import restrict_rows
+    n, e = c["n"], c["nnz"]
+    rng = np.random.default_rng(12345)
+    rows = np.sort(rng.choice(n, size=min(budget_rows, n), replace=False))
+    ip, ix, _ = restrict_rows(c["indptr"], c["indices"], rows)
+    t0 = time.perf_counter()
+    ps = om.pseudo_projection_forward(ip, ix, c["c"], c["proj_w"], c["proj_b"])
+    fwd = om.gmm_pseudo_forward(ip, ix, c["x"], c["w_fc"], ps, c["mu"], c["inv_sigma"])
+    bwd = om.gmm_pseudo_backward(ip, ix, c["x"], c["w_fc"], ps, c["mu"], c["inv_sigma"], c["gout"], fwd)
+    om.pseudo_projection_backward(ip, ix, c["c"], c["proj_w"], c["proj_b"], bwd["gpseudo"])
+    dt = time.perf_counter() - t0
+    e_s = int(ix.shape[0])
+    return {"value": e_s / dt, "unit": "edges/s", "cores": int(oracle_threads()), "kind": "oracle",
+            "sample": (f"fp64 numpy oracle (projection + layer, fwd+bwd) on the in-edges of {len(rows)} seeded "
+                       f"destination rows ({e_s} of {e} edges) with all {n} vertices' dense products, {dt:.2f} s; "
+                       f"edges of the sample per second"),
+            "measured_s": dt}
+
+
 def cpu_baseline_full(c):
     """EdgeConv / GMM workloads are small enough for the oracle to run whole."""
     e = c["nnz"]
@@ -439,6 +462,35 @@ def main():
         if gmm_tune_ms:
             cfg["tune_ms"] = gmm_tune_ms
         gemm_flops = 2.0 * n * fin * K * F
+    elif kind == "monet":
+        F, K, R = c["fout"], c["k"], c["r"]
+        w_fc, cc, mu, inv_sigma = to(c["w_fc"]), to(c["c"]), to(c["mu"]), to(c["inv_sigma"])
+        proj_w, proj_b = to(c["proj_w"]), to(c["proj_b"])
+        pseudo, gpseudo = new(e, R), new(e, R)
+        hk, out = new(n, K * F), new(n, F)
+        gx, gw_fc, gmu, gis = new(n, fin), new(fin, K * F), new(K, R), new(K, R)
+        gproj_w, gproj_b = new(R, 2), new(R)
+        ws_bytes = max(pk.gnn_gmmp_workspace_bytes(g, fin, F, K), pk.gnn_pseudo_proj_workspace_bytes(g))
+        ws = new(max(ws_bytes, 16), dtype=torch.uint8)
+
+        def step():
+            pk.gnn_pseudo_proj_fwd(g, R, cc, proj_w, proj_b, pseudo)
+            pk.gnn_gmmp_fwd(g, fin, F, K, R, x, w_fc, pseudo, mu, inv_sigma, hk, out)
+            pk.gnn_gmmp_bwd(g, fin, F, K, R, x, w_fc, pseudo, mu, inv_sigma, hk, gout, gx, gw_fc, gmu, gis,
+                            gpseudo, ws)
+            pk.gnn_pseudo_proj_bwd(g, R, cc, pseudo, gpseudo, gproj_w, gproj_b, ws)
+        V, I = 4 * n * F, 4 * e + 8 * n
+        unique = {"gmmp_fwd_fused": I + 4 * e * R + K * V + V, "gmmp_bwd_dst": I + 8 * e * R + K * V + V,
+                  "gmmp_bwd_src": 2 * I + 4 * e * R + V + K * V}
+        gather = {"gmmp_fwd_fused": e * (4 + 4 * R + 4 * K * F), "gmmp_bwd_dst": e * (4 + 8 * R + 4 * K * F),
+                  "gmmp_bwd_src": e * (8 + 4 * R + 4 * F)}
+        flops = {"gmmp_fwd_fused": e * K * (2 * F + 4 * R + 8), "gmmp_bwd_dst": e * K * (2 * F + 10 * R + 10),
+                 "gmmp_bwd_src": e * K * (2 * F + 4 * R + 8)}
+        metric = "MoNet/GMM layer with projected pseudo-coordinates fwd+bwd edges/sec"
+        cfg = {"in_feat": fin, "out_feat": F, "kernels": K, "pseudo_dim": R,
+               "pseudo": "tanh(proj_w (1/sqrt(deg_u), 1/sqrt(deg_v)) + proj_b), [E, r] fp32",
+               "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded"}
+        gemm_flops = 2.0 * n * fin * K * F
     elif kind == "gcn":
         F = c["fout"]
         w, c_src, c_dst = to(c["w"]), to(c["c_src"]), to(c["c_dst"])
@@ -569,6 +621,8 @@ def main():
             result["cpu_baseline"] = cpu_baseline_gat2(c)
         elif kind == "ec2":
             result["cpu_baseline"] = cpu_baseline_ec2(c)
+        elif kind == "monet":
+            result["cpu_baseline"] = cpu_baseline_monet(c, args.cpu_rows)
         elif kind == "gcn":
             result["cpu_baseline"] = cpu_baseline_gcn(c, args.cpu_rows)
         else:

@@ -278,19 +278,20 @@ __global__ void k_pseudo_proj_fwd(int32_t n, const int32_t* __restrict__ indptr,
   }
 }
 
-// partial[block][3 * kPsR]: (gP[d,0], gP[d,1], gpb[d]) for d < kPsR, summed over the block's rows
+// partial[block][3 * kPsR]: (gP[d,0], gP[d,1], gpb[d]) for d < kPsR, summed over the block's rows.
+// A wavefront takes every (number of wavefronts)-th row, so that the long rows of a power-law
+// graph (they sit next to each other when vertices are numbered by weight) spread over the grid.
 __global__ __launch_bounds__(kPsBlock) void k_pseudo_proj_bwd(
     int32_t n, const int32_t* __restrict__ indptr, const int32_t* __restrict__ indices,
     const float* __restrict__ c, int R, const float* __restrict__ pseudo, const float* __restrict__ gpseudo,
-    int32_t rows_per_block, float* __restrict__ partial) {
+    float* __restrict__ partial) {
   __shared__ float red[kPsBlock / 64][3 * kPsR];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   float s[3 * kPsR];
 #pragma unroll
   for (int i = 0; i < 3 * kPsR; ++i) s[i] = 0.f;
-  const int64_t v0 = (int64_t)blockIdx.x * rows_per_block;
-  const int64_t v1 = v0 + rows_per_block < n ? v0 + rows_per_block : n;
-  for (int64_t v = v0 + w; v < v1; v += kPsBlock / 64) {
+  const int64_t waves = (int64_t)gridDim.x * (kPsBlock / 64);
+  for (int64_t v = (int64_t)blockIdx.x * (kPsBlock / 64) + w; v < n; v += waves) {
     const float cv = c[v];
     for (int32_t e = indptr[v] + lane; e < indptr[v + 1]; e += 64) {
       const float cu = c[indices[e]];
@@ -486,11 +487,15 @@ extern "C" gnn_status_t gnn_gmmp_bwd(const gnn_graph_t* g, int fin, int fout, in
   return GNN_OK;
 }
 
-constexpr int kProjRowsPerBlock = 256;
+// workgroups of the projection's backward pass (= partial slots): four rows per workgroup, at most 2048
+static int proj_blocks(int64_t n) {
+  int64_t b = cdiv(n > 0 ? n : 1, kPsBlock / 64);
+  return (int)(b > 2048 ? 2048 : b);
+}
 
 extern "C" size_t gnn_pseudo_proj_workspace_bytes(const gnn_graph_t* g) {
   if (!g) return 0;
-  const int64_t blocks = cdiv(g->n > 0 ? g->n : 1, kProjRowsPerBlock);
+  const int64_t blocks = proj_blocks(g->n);
   return ws_granule(sizeof(float) * (size_t)(blocks + 1 + sum_partials_scratch_rows((int)blocks)) * 3 * kPsR);
 }
 
@@ -522,10 +527,9 @@ extern "C" gnn_status_t gnn_pseudo_proj_bwd(const gnn_graph_t* g, int r, const f
   GNN_REQUIRE(g->nnz == 0 || (c && pseudo && gpseudo), GNN_ERR_INVALID_ARG, "gnn_pseudo_proj_bwd: null pointer");
   hipStream_t st = static_cast<hipStream_t>(stream);
   ProfScope p("pseudo_proj_bwd", st);
-  const int blocks = (int)cdiv(g->n > 0 ? g->n : 1, kProjRowsPerBlock);
+  const int blocks = proj_blocks(g->n);
   float* partial = static_cast<float*>(ws);
-  k_pseudo_proj_bwd<<<blocks, kPsBlock, 0, st>>>(g->n, g->indptr, g->indices, c, r, pseudo, gpseudo,
-                                                 kProjRowsPerBlock, partial);
+  k_pseudo_proj_bwd<<<blocks, kPsBlock, 0, st>>>(g->n, g->indptr, g->indices, c, r, pseudo, gpseudo, partial);
   GNN_LAUNCH_CHECK();
   float* totals = partial + (int64_t)blocks * 3 * kPsR;
   GNN_TRY(sum_partials_two_level(3 * kPsR, blocks, partial, totals + 3 * kPsR, totals, st));

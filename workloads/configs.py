@@ -212,6 +212,34 @@ def _make_ec2_c3(seed):
     )
 
 
+def _monet(name, n, graph, fin, fout, K, r, seed):
+    """MoNet layer with r-dimensional pseudo-coordinates projected from (1/sqrt(deg_u), 1/sqrt(deg_v))
+    (the paper's MoNet settings, Sec. 7.2 / 7.3)."""
+    indptr, indices = graph
+    rng = graphs.rng_for(seed ^ 0xA5A5)
+    deg = np.maximum(np.diff(indptr), 1)
+    return dict(
+        name=name, kind="monet", n=n, nnz=int(indices.shape[0]), fin=fin, fout=fout, k=K, r=r,
+        indptr=indptr, indices=indices, x=_normal(rng, (n, fin)),
+        w_fc=glorot(rng, fin, K * fout, (fin, K * fout)), c=(1.0 / np.sqrt(deg)).astype(np.float32),
+        proj_w=_normal(rng, (r, 2)), proj_b=(0.1 * _normal(rng, (r,))).astype(np.float32),
+        mu=(0.3 * _normal(rng, (K, r))).astype(np.float32), inv_sigma=np.ones((K, r), dtype=np.float32),
+        gout=_normal(rng, (n, fout)),
+    )
+
+
+def _make_monet_c4(seed):
+    # the ablation setting of Sec. 7.3: k = 2, r = 1, 16 features, Reddit-scale graph
+    n = 232_965
+    return _monet("monet_c4", n, graphs.chung_lu(n, 114_000_000, 2.1, SEED0 ^ 4), 602, 16, 2, 1, seed)
+
+
+def _make_monet_c5(seed):
+    # k = 3, r = 3 (the Pubmed / Citeseer setting) on the gmm_c5 graph
+    n = 100_000
+    return _monet("monet_c5", n, graphs.chung_lu(n, 2_000_000, 2.1, SEED0 ^ 5), 64, 16, 3, 3, seed)
+
+
 def _make_gcn_mid(seed):
     n = 6000
     return _gcn("gcn_mid", n, graphs.chung_lu(n, 300_000, 2.1, seed), 602, 256, seed)
@@ -252,6 +280,8 @@ _MAKERS = {
     "gat2_c2": (9, _make_gat2_c2),
     "gat2_c4": (10, _make_gat2_c4),
     "ec2_c3": (13, _make_ec2_c3),
+    "monet_c4": (14, _make_monet_c4),
+    "monet_c5": (15, _make_monet_c5),
 }
 NAMES = tuple(_MAKERS)
 
