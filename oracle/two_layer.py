@@ -44,6 +44,8 @@ def gat2_backward(indptr, indices, x, p, labels, slope, fwd=None):
 #   "edgeconv": params theta, phi
 #   "gmm":      params w_fc, mu, inv_sigma;  consts c (per-vertex pseudo-coordinate)
 #   "gcn":      params w;  consts c_src, c_dst
+#   "monet":    params w_fc, mu, inv_sigma, proj_w, proj_b;  consts c   (pseudo-coordinates projected
+#               from the pair (c[u], c[v]) to r = proj_w.shape[0] dimensions, each layer its own projection)
 def layer_forward(kind, indptr, indices, x, p, k):
     if kind == "gat":
         return og.gat_forward(indptr, indices, x, p["w"], p["al"], p["ar"], k["slope"])
@@ -56,6 +58,12 @@ def layer_forward(kind, indptr, indices, x, p, k):
     if kind == "gcn":
         from . import gcn as oc
         return oc.gcn_forward(indptr, indices, x, p["w"], k["c_src"], k["c_dst"])
+    if kind == "monet":
+        from . import gmm as om
+        ps = om.pseudo_projection_forward(indptr, indices, k["c"], p["proj_w"], p["proj_b"])
+        f = om.gmm_pseudo_forward(indptr, indices, x, p["w_fc"], ps, p["mu"], p["inv_sigma"])
+        f["pseudo"] = ps
+        return f
     raise ValueError(kind)
 
 
@@ -76,6 +84,11 @@ def layer_backward(kind, indptr, indices, x, p, k, gout, fwd):
         from . import gcn as oc
         b = oc.gcn_backward(indptr, indices, x, p["w"], k["c_src"], k["c_dst"], gout, fwd)
         return b["gx"], dict(w=b["gw"])
+    if kind == "monet":
+        from . import gmm as om
+        b = om.gmm_pseudo_backward(indptr, indices, x, p["w_fc"], fwd["pseudo"], p["mu"], p["inv_sigma"], gout, fwd)
+        gP, gpb = om.pseudo_projection_backward(indptr, indices, k["c"], p["proj_w"], p["proj_b"], b["gpseudo"])
+        return b["gx"], dict(w_fc=b["gw_fc"], mu=b["gmu"], inv_sigma=b["ginv_sigma"], proj_w=gP, proj_b=gpb)
     raise ValueError(kind)
 
 

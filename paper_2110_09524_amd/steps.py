@@ -90,6 +90,35 @@ class GmmLayer:
                       gout, gx, g["w_fc"], g["mu"], g["inv_sigma"], ws)
 
 
+class MonetLayer:
+    """GMM layer with pseudo-coordinates projected from the pair (c[u], c[v]) to r dimensions.
+    params: w_fc [fin, k*fout], mu, inv_sigma [k, r], proj_w [r, 2], proj_b [r]; c [n] constant."""
+
+    def __init__(self, graph, fin, fout, k, r, params, c):
+        self.g, self.fin, self.fout, self.k, self.r, self.p, self.c = graph, fin, fout, k, r, params, c
+        n, e, dev = graph.n, max(graph.nnz, 1), c.device
+        self.hk, self.out = _new(dev, n, k * fout), _new(dev, n, fout)
+        self.pseudo, self.gpseudo = _new(dev, e, r), _new(dev, e, r)
+        self.grads = {k_: torch.empty_like(v) for k_, v in params.items()}
+
+    def workspace_bytes(self):
+        return max(B.gnn_gmmp_workspace_bytes(self.g, self.fin, self.fout, self.k),
+                   B.gnn_pseudo_proj_workspace_bytes(self.g))
+
+    def forward(self, x, ws):
+        p = self.p
+        B.gnn_pseudo_proj_fwd(self.g, self.r, self.c, p["proj_w"], p["proj_b"], self.pseudo)
+        B.gnn_gmmp_fwd(self.g, self.fin, self.fout, self.k, self.r, x, p["w_fc"], self.pseudo, p["mu"],
+                       p["inv_sigma"], self.hk, self.out)
+        return self.out
+
+    def backward(self, x, gout, gx, ws):
+        p, g = self.p, self.grads
+        B.gnn_gmmp_bwd(self.g, self.fin, self.fout, self.k, self.r, x, p["w_fc"], self.pseudo, p["mu"],
+                       p["inv_sigma"], self.hk, gout, gx, g["w_fc"], g["mu"], g["inv_sigma"], self.gpseudo, ws)
+        B.gnn_pseudo_proj_bwd(self.g, self.r, self.c, self.pseudo, self.gpseudo, g["proj_w"], g["proj_b"], ws)
+
+
 class GcnLayer:
     """params: w [fin, fout]; c_src, c_dst [n]: the two factors of the static edge weight."""
 

@@ -161,8 +161,12 @@ def _two_layer_case(kind, seed):
         if kind == "gmm":
             return dict(w_fc=f32(rng.standard_normal((fi, 3 * fo)) * s), mu=f32(rng.standard_normal((3, 2)) * 0.3),
                         inv_sigma=f32(0.5 + rng.random((3, 2))))
+        if kind == "monet":
+            return dict(w_fc=f32(rng.standard_normal((fi, 3 * fo)) * s), mu=f32(rng.standard_normal((3, 3)) * 0.3),
+                        inv_sigma=f32(0.5 + rng.random((3, 3))), proj_w=f32(rng.standard_normal((3, 2))),
+                        proj_b=f32(0.2 * rng.standard_normal(3)))
         return dict(w=f32(rng.standard_normal((fi, fo)) * s))
-    if kind == "gmm":
+    if kind in ("gmm", "monet"):
         consts["c"] = f32(1.0 / np.sqrt(deg))
     if kind == "gcn":
         consts["c_src"] = f32(1.0 / np.sqrt(np.maximum(np.bincount(indices, minlength=n), 1)))
@@ -174,7 +178,7 @@ def _two_layer_case(kind, seed):
                 b2=f32(0.1 * rng.standard_normal(c)), labels=labels, **extra)
 
 
-@pytest.mark.parametrize("kind", ["edgeconv", "gmm", "gcn"])
+@pytest.mark.parametrize("kind", ["edgeconv", "gmm", "gcn", "monet"])
 def test_two_layer_step_of_every_layer_type(kind):
     """EdgeConv: the graph itself is built on the GPU from the coordinates (gnn_knn_graph)."""
     import torch
@@ -206,6 +210,9 @@ def test_two_layer_step_of_every_layer_type(kind):
     elif kind == "gmm":
         cc = dev(t["consts"]["c"])
         l1, l2 = steps.GmmLayer(g, fin, hid, 3, P1, cc), steps.GmmLayer(g, hid, c, 3, P2, cc)
+    elif kind == "monet":
+        cc = dev(t["consts"]["c"])
+        l1, l2 = steps.MonetLayer(g, fin, hid, 3, 3, P1, cc), steps.MonetLayer(g, hid, c, 3, 3, P2, cc)
     else:
         cs, cd = dev(t["consts"]["c_src"]), dev(t["consts"]["c_dst"])
         l1, l2 = steps.GcnLayer(g, fin, hid, P1, cs, cd), steps.GcnLayer(g, hid, c, P2, cs, cd)

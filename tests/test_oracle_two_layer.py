@@ -72,13 +72,17 @@ def _params(kind, rng, fin, fout, K=2):
     if kind == "gmm":
         return dict(w_fc=rng.standard_normal((fin, K * fout)) * s, mu=rng.standard_normal((K, 2)) * 0.3,
                     inv_sigma=0.5 + rng.random((K, 2)))
+    if kind == "monet":
+        return dict(w_fc=rng.standard_normal((fin, K * fout)) * s, mu=rng.standard_normal((K, 3)) * 0.3,
+                    inv_sigma=0.5 + rng.random((K, 3)), proj_w=rng.standard_normal((3, 2)),
+                    proj_b=rng.standard_normal(3) * 0.2)
     return dict(w=rng.standard_normal((fin, fout)) * s)
 
 
 import pytest
 
 
-@pytest.mark.parametrize("kind", ["gat", "edgeconv", "gmm", "gcn"])
+@pytest.mark.parametrize("kind", ["gat", "edgeconv", "gmm", "gcn", "monet"])
 def test_generic_chain_matches_finite_differences_for_every_layer_type(kind):
     rng = np.random.default_rng(11)
     n, fin, hid, c = 12, 4, 5, 3
