@@ -277,6 +277,9 @@ def main():
                     help="GAT workloads, the recomputation study: vertex_stash (default: forward stashes the "
                          "vertex-sized sums t, sg), recompute (nothing but m, d is kept; one more edge pass in "
                          "backward), edge_stash (per-edge softmax values stored after forward and read back)")
+    ap.add_argument("--gather-fp16", action="store_true",
+                    help="GAT workloads on the column-blocked path: gather neighbour rows from an fp16 copy "
+                         "(sums in fp32); outside the 1e-4 contract, reported as a variant only")
     ap.add_argument("--single-launch", action="store_true",
                     help="use the single-launch kernels also where the column-blocked ones apply")
     ap.add_argument("--compare-unfused", action="store_true",
@@ -315,6 +318,8 @@ def main():
 
     if args.single_launch:
         pk.gnn_config_set("force_simple_kernels", 1)
+    if args.gather_fp16:
+        pk.gnn_config_set("gather_precision", 1)
     t0 = time.perf_counter()
     g = pk.Graph(indptr, indices)
     torch.cuda.synchronize()
@@ -406,6 +411,7 @@ def main():
             + (4 * e * H if alpha_t is not None else 0)
         cfg = {"in_feat": fin, "heads": H, "hidden_per_head": F, "arm": args.arm,
                "single_launch_kernels": bool(args.single_launch), "saved_for_backward_bytes": saved,
+               "gather_storage": "fp16 copy (variant outside the 1e-4 contract)" if args.gather_fp16 else "fp32",
                "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded"}
         gemm_flops = 2.0 * n * fin * HF
     elif kind == "edgeconv":

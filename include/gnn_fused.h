@@ -116,6 +116,13 @@ gnn_status_t gnn_graph_get_blocked(const gnn_graph_t* graph, int side, int32_t* 
  *   "blocked_min_edges"     mean number of edges per (row, column block) from which the
  *                           column-blocked kernels are used (default 16; sparser graphs take
  *                           the single-launch kernels even when they span several blocks)
+ *   "gather_precision"      0 (default): fp32 throughout.  1: the column-blocked GAT kernels
+ *                           gather the neighbour rows (z in forward, gout in the source-side
+ *                           backward) from an fp16 copy, sums in fp32: about half the gather
+ *                           traffic; errors of about 1e-3 of a tensor's rms (several 1e-3 in
+ *                           the worst gradient entries) instead of the 1e-4 contract.  Set it before workspace sizes are
+ *                           queried; shapes it does not cover (heads*f % 64 != 0, a 64-column
+ *                           slice spanning heads) stay fp32.
  *   "force_simple_kernels"  1: always use the single-launch kernels
  *   "lds_scalar_table"      1 (default): the column-blocked destination-side GAT kernels
  *                           keep a block's per-vertex score table in LDS (one persistent

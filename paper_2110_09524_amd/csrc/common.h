@@ -84,7 +84,7 @@ inline size_t ws_granule(size_t bytes) { return align_up(bytes, 256); }
 
 // ---- tuning knobs (runtime.hip) -------------------------------------------------
 enum ConfigKey { kCfgBlockCols = 0, kCfgForceSimple = 1, kCfgLdsScalarTable = 2, kCfgGcnMapping = 3, kCfgGmmMapping = 4, kCfgBlockedMinEdges = 5,
-                 kCfgCount };
+                 kCfgGatherPrecision = 6, kCfgCount };
 int64_t config_get(ConfigKey k);
 
 // ---- dense products (gemm.hip) ------------------------------------------------

@@ -17,6 +17,8 @@
 // the destination-side kernel walks the CSR, the source-side kernel walks the
 // CSC transpose (no atomics), and alpha_e is recomputed from el, er, m, d.
 #include "common.h"
+#include <hip/hip_fp16.h>
+
 #include "gat_common.h"
 #include "rowgroup.h"
 
@@ -668,7 +670,7 @@ static int param_blocks(int64_t n) {
 
 struct GatWs {
   size_t total;
-  size_t dz, vstate, der, del, partial, gemm, blk_rows, blk_scal, blk_elt, blk_queue, fwd_gemm;
+  size_t dz, vstate, der, del, partial, gemm, blk_rows, blk_scal, blk_elt, blk_queue, fwd_gemm, blk_half;
   int split_k, nblk, fwd_split_k;
 };
 
@@ -694,6 +696,7 @@ static GatWs gat_ws_layout(const gnn_graph_t* g, int fin, int H, int F) {
   // a narrow projection of a mid-sized graph has too few output tiles to fill the chip: split K
   w.fwd_split_k = gemm_pick_split_k(n, HF, fin);
   w.fwd_gemm = take(w.fwd_split_k > 1 ? sizeof(float) * (size_t)w.fwd_split_k * n * HF : 0);
+  w.blk_half = take(gat_blocked_half(g, H, F) ? 2 * (size_t)n * HF : 0);  // fp16 copy of the gathered rows
   w.total = off;
   return w;
 }
@@ -783,10 +786,14 @@ template <int L, int NV>
 __global__ __launch_bounds__(kBlock) void k_gat_dst_finish(
     int32_t n_rows, const float* __restrict__ gout, const float* __restrict__ t_in,
     const float* __restrict__ out, const float* __restrict__ sg, const float* __restrict__ er,
-    const float* __restrict__ m_in, const float* __restrict__ d_in, GatDims dm, int head_major,
+    const float* __restrict__ m_in, const float* __restrict__ d_in, GatDims dm, int flags,
     float* __restrict__ der, float4* __restrict__ vstate) {
   constexpr int G = kWave / L;
   constexpr int GPB = G * (kBlock / kWave);
+  // flags: kDstHeadMajor - vstate is [H][n] instead of [n][H]; kDstHalfGout - gout is rounded to
+  // fp16 first, as the source-side kernel will see it when it gathers an fp16 copy (D and the
+  // per-edge dot products <gout[v], z[u]> then cancel exactly where they should)
+  const bool head_major = (flags & kDstHeadMajor) != 0, half_gout = (flags & kDstHalfGout) != 0;
   __shared__ float lds[GPB * 2 * L * NV];
   const int li = threadIdx.x & (L - 1);
   const int grp = threadIdx.x / L;
@@ -799,7 +806,10 @@ __global__ __launch_bounds__(kBlock) void k_gat_dst_finish(
     const int col = 4 * (li + j * L);
     float p1 = 0.f, pd = 0.f;
     if (col < HF) {
-      const float4 g4 = ld4(gout + v * HF + col);
+      float4 g4 = ld4(gout + v * HF + col);
+      if (half_gout)
+        g4 = make_float4(__half2float(__float2half_rn(g4.x)), __half2float(__float2half_rn(g4.y)),
+                         __half2float(__float2half_rn(g4.z)), __half2float(__float2half_rn(g4.w)));
       p1 = dot4(g4, ld4(t_in + v * HF + col));
       pd = dot4(g4, ld4(out + v * HF + col));
     }
@@ -1041,7 +1051,8 @@ extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, in
     return gat_blocked_fwd(g, make_dims(heads, f, slope), z, el, er, m, d, out, t, sg,
                            reinterpret_cast<float*>(base + L.blk_elt),
                            reinterpret_cast<int32_t*>(base + L.blk_queue),
-                           reinterpret_cast<float4*>(base + L.dz), st);
+                           reinterpret_cast<float4*>(base + L.dz),
+                           gat_blocked_half(g, heads, f) ? base + L.blk_half : nullptr, st);
   }
   return dispatch_group<FwdLauncher>(pick_group(HF), g, (const float*)z, (const float*)el,
                                      (const float*)er, make_dims(heads, f, slope), out, m, d, t, sg, st);
@@ -1126,10 +1137,11 @@ static gnn_status_t gat_bwd_impl(const char* who, const gnn_graph_t* g, int fin,
 
   // the per-edge stash is laid out for the single-launch source-side kernel
   const bool blocked = alpha_t == nullptr && gat_blocked_applies(g, heads, f);
+  const int dst_flags = (blocked ? kDstHeadMajor : 0) | (blocked && gat_blocked_half(g, heads, f) ? kDstHalfGout : 0);
   // a4: destination side.  With t and sg stashed by the forward call it is a vertex pass;
   // without them the sums are recomputed over the in-edges.
   if (t) {
-    GNN_TRY(gat_dst_finish(g, dm, gout, t, out, sg, er, m, d, blocked ? 1 : 0, der, vstate, st));
+    GNN_TRY(gat_dst_finish(g, dm, gout, t, out, sg, er, m, d, dst_flags, der, vstate, st));
   } else if (blocked) {
     float* rows_buf = reinterpret_cast<float*>(base + L.blk_rows);
     float* scal_buf = reinterpret_cast<float*>(base + L.blk_scal);
@@ -1144,7 +1156,7 @@ static gnn_status_t gat_bwd_impl(const char* who, const gnn_graph_t* g, int fin,
     float* rows_buf = reinterpret_cast<float*>(base + L.blk_rows);
     float* scal_buf = reinterpret_cast<float*>(base + L.blk_scal);
     GNN_TRY(gat_blocked_bwd_src(g, dm, z, el, vstate, der, gout, a_l, a_r, dz, del, rows_buf,
-                                scal_buf, st));
+                                scal_buf, gat_blocked_half(g, heads, f) ? base + L.blk_half : nullptr, st));
   } else {
     // a5: source side
     GNN_TRY(dispatch_group<BwdSrcLauncher>(gs, g, z, el, (const float4*)vstate, (const float*)der,

@@ -20,6 +20,8 @@
 // All per-edge values are still recomputed on the fly; nothing per-edge is stored.
 #include <atomic>
 
+#include <hip/hip_fp16.h>
+
 #include "common.h"
 #include "gat_common.h"
 #include "rowgroup.h"
@@ -67,12 +69,24 @@ static bool pick_slicing(int heads, int HF, Slicing& sl) {
 // chain of dependent loads at the start of a row is paid once per group, not once per row.
 constexpr int kRowsPerGroup = 4;
 
-template <int MODE>
+template <int NA>
 struct BlkRow {
   int32_t row, beg, end, c_first;
   float r_a, r_m, r_d, scal;
-  float4 acc, acc2;
+  float4 acc[NA], acc2[NA];
 };
+
+// HALF: the gathered matrix is an fp16 copy (the sums stay fp32).  A lane then owns 8 columns
+// (16 bytes of the copy) instead of 4, and a 128-byte slice covers 64 columns.
+__device__ __forceinline__ void fma8_half(float4 (&acc)[2], float w, const uint4& r) {
+  const __half2* h = reinterpret_cast<const __half2*>(&r);
+  const float2 a = __half22float2(h[0]), b = __half22float2(h[1]), c = __half22float2(h[2]),
+               d = __half22float2(h[3]);
+  acc[0].x = fmaf(w, a.x, acc[0].x); acc[0].y = fmaf(w, a.y, acc[0].y);
+  acc[0].z = fmaf(w, b.x, acc[0].z); acc[0].w = fmaf(w, b.y, acc[0].w);
+  acc[1].x = fmaf(w, c.x, acc[1].x); acc[1].y = fmaf(w, c.y, acc[1].y);
+  acc[1].z = fmaf(w, d.x, acc[1].z); acc[1].w = fmaf(w, d.y, acc[1].w);
+}
 
 // STAGE: the per-edge scalar el[u] of the slice's head is read from an LDS copy of the block's
 // part of the head-major table instead of being gathered from L2.  Such a scalar gather
@@ -83,7 +97,7 @@ struct BlkRow {
 // per-slice counter in device memory (zeroed before the launch).
 constexpr int kStageThreads = 1024;
 
-template <int SL, int MODE, bool STAGE>
+template <int SL, int MODE, bool STAGE, bool HALF>
 __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk(
     int32_t n_rows, const int32_t* __restrict__ order, const int2* __restrict__ bseg_b,
     const int32_t* __restrict__ bcol, const float* __restrict__ feat /* gathered rows: z or gout */,
@@ -102,6 +116,8 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
   constexpr int R = kRowsPerGroup;
   constexpr int U = SL < 8 ? 4 : 8;   // gathered rows in flight per lane
   constexpr bool DUAL = MODE == 2 || MODE == 3;  // two accumulators per lane
+  constexpr int CPL = HALF ? 8 : 4;              // columns per lane
+  constexpr int NA = CPL / 4;                    // float4 accumulators per lane and sum
   // The forward modes run the edge-softmax online across the block launches: every (row, slice)
   // carries its running maximum and sums from launch to launch, the running sums are rescaled
   // when the maximum grows, and the last block divides by the denominator.  No separate pass
@@ -140,7 +156,7 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
   int* l_beg = l_row + R;
   int* l_end = l_row + 2 * R;
 
-  const int col = slice * 4 * SL + 4 * li;
+  const int col = slice * CPL * SL + CPL * li;
   const bool leader = (slice % sph) == 0;  // one slice per head keeps the per-head scalars
 
   for (;;) {
@@ -170,14 +186,17 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
     wave_lds_fence();
 
     // issue every load a row needs before its edge loop
-    auto fetch = [&](int k, BlkRow<MODE>& s) {
+    auto fetch = [&](int k, BlkRow<NA>& s) {
       s.row = l_row[k];
       s.beg = l_beg[k];
       s.end = l_end[k];
       s.c_first = col_begin;
       s.r_a = 0.f; s.r_m = 0.f; s.r_d = 1.f; s.scal = 0.f;
-      s.acc = make_float4(0.f, 0.f, 0.f, 0.f);
-      s.acc2 = s.acc;
+#pragma unroll
+      for (int a = 0; a < NA; ++a) {
+        s.acc[a] = make_float4(0.f, 0.f, 0.f, 0.f);
+        s.acc2[a] = s.acc[a];
+      }
       if (s.row < 0) return;
       if (s.beg + li < s.end) s.c_first = bcol[s.beg + li];
       const int64_t rh = (int64_t)s.row * H + h;
@@ -197,8 +216,11 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
         s.r_d = d_in[rh];
       }
       if (!first) {
-        s.acc = ld4_stream(acc_buf + (int64_t)s.row * HF + col);
-        if (DUAL) s.acc2 = ld4_stream(acc2_buf + (int64_t)s.row * HF + col);
+#pragma unroll
+        for (int a = 0; a < NA; ++a) {
+          s.acc[a] = ld4_stream(acc_buf + (int64_t)s.row * HF + col + 4 * a);
+          if (DUAL) s.acc2[a] = ld4_stream(acc2_buf + (int64_t)s.row * HF + col + 4 * a);
+        }
         if (!ONLINE && MODE != 0 && leader && li == 0) s.scal = scal_buf[rh];
       }
     };
@@ -206,16 +228,22 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
     // Gathered rows are addressed with 32-bit byte offsets when the matrix is below 4 GB
     // (one 24-bit multiply-add per row instead of 64-bit arithmetic).
     const char* feat_bytes = reinterpret_cast<const char*>(feat);
-    const uint32_t row_bytes = (uint32_t)HF * 4u, col_bytes = (uint32_t)col * 4u;
+    constexpr uint32_t kElem = HALF ? 2u : 4u;  // bytes per stored element of the gathered matrix
+    const uint32_t row_bytes = (uint32_t)HF * kElem, col_bytes = (uint32_t)col * kElem;
 
-    BlkRow<MODE> cur, nxt;
+    BlkRow<NA> cur, nxt;
     fetch(0, cur);
     for (int k = 0; k < R; ++k) {
       if (k + 1 < R) fetch(k + 1, nxt);
       if (cur.row >= 0) {
         const int32_t end = cur.end;
         const float r_a = cur.r_a, r_m = cur.r_m, r_invd = ONLINE ? 0.f : 1.f / cur.r_d;
-        float4 acc = cur.acc, acc2 = cur.acc2;
+        float4 acc[NA], acc2[NA];
+#pragma unroll
+        for (int a = 0; a < NA; ++a) {
+          acc[a] = cur.acc[a];
+          acc2[a] = cur.acc2[a];
+        }
         float s_run = 0.f;
         // online state: the running maximum is uniform in the group, the sums are per lane
         // (lane 0 carries what earlier blocks left) and are added across lanes at the end
@@ -238,7 +266,12 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
             else e_a = STAGE ? l_el[c - col_begin] : (el_hm ? el[(int64_t)h * n_rows + c] : el[(int64_t)c * H + h]);
           }
           wave_lds_fence();
-          float4 part = make_float4(0.f, 0.f, 0.f, 0.f), part2 = part;
+          float4 part[NA], part2[NA];
+#pragma unroll
+          for (int a = 0; a < NA; ++a) {
+            part[a] = make_float4(0.f, 0.f, 0.f, 0.f);
+            part2[a] = part[a];
+          }
           float sc = 1.f;  // ONLINE: factor that brings the running sums to this chunk's maximum
 #pragma unroll
           for (int t0 = 0; t0 < SL; t0 += U) {
@@ -249,15 +282,16 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
               const int4 i4 = *reinterpret_cast<const int4*>(l_idx + t0 + 4 * q);
               idv[4 * q] = i4.x; idv[4 * q + 1] = i4.y; idv[4 * q + 2] = i4.z; idv[4 * q + 3] = i4.w;
             }
-            float4 rowv[U];
+            uint4 rowv[U];  // 16 bytes of the gathered row: 4 floats, or 8 halves
             if (narrow) {
 #pragma unroll
               for (int t = 0; t < U; ++t)
-                rowv[t] = *reinterpret_cast<const float4*>(
+                rowv[t] = *reinterpret_cast<const uint4*>(
                     feat_bytes + (__umul24((uint32_t)idv[t], row_bytes) + col_bytes));
             } else {
 #pragma unroll
-              for (int t = 0; t < U; ++t) rowv[t] = ld4(feat + (int64_t)idv[t] * HF + col);
+              for (int t = 0; t < U; ++t)
+                rowv[t] = *reinterpret_cast<const uint4*>(feat_bytes + ((int64_t)idv[t] * row_bytes + col_bytes));
             }
             if (t0 == 0) {
               float p = 0.f, p2 = 0.f;
@@ -301,16 +335,26 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
             }
 #pragma unroll
             for (int t = 0; t < U; ++t) {
-              fma4(part, pv[t], rowv[t]);
-              if (DUAL) fma4(part2, pv2[t], rowv[t]);
+              if constexpr (HALF) {
+                fma8_half(part, pv[t], rowv[t]);
+                if (DUAL) fma8_half(part2, pv2[t], rowv[t]);
+              } else {
+                const float4 rv = make_float4(__uint_as_float(rowv[t].x), __uint_as_float(rowv[t].y),
+                                              __uint_as_float(rowv[t].z), __uint_as_float(rowv[t].w));
+                fma4(part[0], pv[t], rv);
+                if (DUAL) fma4(part2[0], pv2[t], rv);
+              }
             }
           }
-          if (ONLINE) {
-            fold4(acc, sc, part);
-            if (DUAL) fold4(acc2, sc, part2);
-          } else {
-            add4(acc, part);
-            if (DUAL) add4(acc2, part2);
+#pragma unroll
+          for (int a = 0; a < NA; ++a) {
+            if (ONLINE) {
+              fold4(acc[a], sc, part[a]);
+              if (DUAL) fold4(acc2[a], sc, part2[a]);
+            } else {
+              add4(acc[a], part[a]);
+              if (DUAL) add4(acc2[a], part2[a]);
+            }
           }
           wave_lds_fence();
         }
@@ -320,8 +364,11 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
           if (last) {
             // the row is complete: normalise (a row without in-edges keeps out = 0, m = 0, d = 1)
             const float inv = d_tot > 0.f ? 1.f / d_tot : 0.f;
-            acc = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
-            if (DUAL) acc2 = make_float4(acc2.x * inv, acc2.y * inv, acc2.z * inv, acc2.w * inv);
+#pragma unroll
+            for (int a = 0; a < NA; ++a) {
+              scale4(acc[a], inv);
+              if (DUAL) scale4(acc2[a], inv);
+            }
             if (leader && li == 0) {
               const int64_t rh = (int64_t)cur.row * H + h;
               m_out[rh] = d_tot > 0.f ? m_run : 0.f;
@@ -332,8 +379,11 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
             state[(int64_t)cur.row * kSlices + slice] = make_float4(m_run, d_tot, s2_tot, 0.f);
           }
         }
-        st4_stream(acc_buf + (int64_t)cur.row * HF + col, acc);
-        if (DUAL) st4_stream(acc2_buf + (int64_t)cur.row * HF + col, acc2);
+#pragma unroll
+        for (int a = 0; a < NA; ++a) {
+          st4_stream(acc_buf + (int64_t)cur.row * HF + col + 4 * a, acc[a]);
+          if (DUAL) st4_stream(acc2_buf + (int64_t)cur.row * HF + col + 4 * a, acc2[a]);
+        }
         if (!ONLINE && MODE != 0 && leader) {
           const float tot = group_sum_from<SL>(s_run, 1);
           if (li == 0) scal_buf[(int64_t)cur.row * H + h] = cur.scal + tot;
@@ -364,6 +414,33 @@ static gnn_status_t head_major(const gnn_graph_t* g, int H, const float* a, floa
 }
 
 // ---- host side -------------------------------------------------------------------------
+// fp16 copy of the gathered matrix (configuration key "gather_precision" = 1): rows of 2*HF bytes
+// are cut into slices of 64 columns (one 128-byte line), each inside one head
+bool gat_blocked_half(const gnn_graph_t* g, int heads, int f) {
+  if (config_get(kCfgGatherPrecision) != 1 || !gat_blocked_applies(g, heads, f)) return false;
+  const int HF = heads * f;
+  if (HF % 64 != 0) return false;
+  const int q = HF / 64;
+  return (q == 1 || q == 2 || q == 4 || q == 8) && q % heads == 0;
+}
+
+__global__ void k_to_half(int64_t quads, const float* __restrict__ src, __half* __restrict__ dst) {
+  const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i >= quads) return;
+  const float4 v = ld4(src + 4 * i);
+  __half2* o = reinterpret_cast<__half2*>(dst + 4 * i);
+  o[0] = __floats2half2_rn(v.x, v.y);
+  o[1] = __floats2half2_rn(v.z, v.w);
+}
+
+static gnn_status_t to_half(const gnn_graph_t* g, int HF, const float* src, void* dst, hipStream_t st) {
+  ProfScope p("gat_to_half", st);
+  const int64_t quads = (int64_t)g->n * (HF / 4);
+  k_to_half<<<(unsigned)cdiv(quads, 256), 256, 0, st>>>(quads, src, static_cast<__half*>(dst));
+  GNN_LAUNCH_CHECK();
+  return GNN_OK;
+}
+
 bool gat_blocked_applies(const gnn_graph_t* g, int heads, int f) {
   if (!g->blocked_pays() || config_get(kCfgForceSimple)) return false;
   const int HF = heads * f;
@@ -403,13 +480,13 @@ static int device_cu_count() {
   return cus;
 }
 
-template <int SL, int MODE>
+template <int SL, int MODE, bool HALF = false>
 static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* name, GatDims dm,
                                   int el_hm, const float* feat,
                                   const float* el, const float* er, const float* m, const float* d,
                                   const float4* vstate, float* acc, float* acc2, float* scal,
                                   int32_t* queue, float4* state, float* m_out, float* d_out, hipStream_t st) {
-  const int ns = dm.HF / (4 * SL);
+  const int ns = dm.HF / ((HALF ? 8 : 4) * SL);
   const int sph = ns / dm.H;
   // 32-bit byte offsets (and 24-bit multiplies) reach every gathered row
   const int narrow = (int64_t)g->n * dm.HF * 4 < ((int64_t)1 << 32) && g->n < (1 << 24);
@@ -426,7 +503,7 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
       // idempotent, so a race between two first callers is harmless)
       static std::atomic<bool> attr_set{false};
       if (!attr_set.load(std::memory_order_acquire)) {
-        GNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gat_blk<SL, MODE, true>),
+        GNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gat_blk<SL, MODE, true, HALF>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStageLdsLimit));
         attr_set.store(true, std::memory_order_release);
       }
@@ -451,7 +528,7 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
         // one persistent workgroup per CU, a multiple of 8 so that every XCD serves one slice
         const unsigned pgrid = (unsigned)(device_cu_count() / kSlices * kSlices);
         ProfScope p(name, st);  // one timed bracket per launch
-        k_gat_blk<SL, MODE, true><<<pgrid, kStageThreads, staged_lds_bytes<SL>(g->block_cols), st>>>(
+        k_gat_blk<SL, MODE, true, HALF><<<pgrid, kStageThreads, staged_lds_bytes<SL>(g->block_cols), st>>>(
             g->n, g->order[side], bseg_b, g->bcol[side], feat, el, er, m, d, vstate, col_begin, dm, sph,
             b == 0, narrow, el_hm, acc, acc2, scal, queue + b * kSlices, cols_here, 1, ns, b == g->nblk - 1, state,
             m_out, d_out);
@@ -460,7 +537,7 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
     }
     if (!staged) {
       ProfScope p(name, st);  // one timed bracket per launch
-      k_gat_blk<SL, MODE, false><<<grid, kBlkThreads, lds, st>>>(
+      k_gat_blk<SL, MODE, false, HALF><<<grid, kBlkThreads, lds, st>>>(
           g->n, g->order[side], bseg_b, g->bcol[side], feat, el, er, m, d, vstate, col_begin, dm, sph,
           b == 0, narrow, el_hm, acc, acc2, scal, nullptr, 0, 1, ns, b == g->nblk - 1, state, m_out, d_out);
       GNN_LAUNCH_CHECK();
@@ -474,7 +551,12 @@ static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name,
                                int el_hm, const float* feat, const float* el, const float* er, const float* m,
                                const float* d, const float4* vstate, float* acc, float* acc2,
                                float* scal, int32_t* queue, float4* state, float* m_out, float* d_out,
-                               hipStream_t st) {
+                               hipStream_t st, bool half_feat = false) {
+  if (half_feat) {
+    if constexpr (MODE != 1)
+      return launch_blocks<8, MODE, true>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal,
+                                          queue, state, m_out, d_out, st);
+  }
   Slicing sl;
   if (!pick_slicing(dm.H, dm.HF, sl)) sl.SL = 0;
   switch (sl.SL) {
@@ -489,16 +571,22 @@ static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name,
 
 gnn_status_t gat_blocked_fwd(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                              const float* er, float* m, float* d, float* out, float* t, float* sg,
-                             float* el_t, int32_t* queue, float4* state, hipStream_t st) {
+                             float* el_t, int32_t* queue, float4* state, void* half_buf, hipStream_t st) {
   if (el_t) GNN_TRY(head_major(g, dm.H, el, el_t, st));
   if (!config_get(kCfgLdsScalarTable)) queue = nullptr;
   const float* el_use = el_t ? el_t : el;
   const int hm = el_t != nullptr;
+  const bool half = half_buf != nullptr && gat_blocked_half(g, dm.H, dm.F);
+  const float* feat = z;
+  if (half) {  // the rows the edges gather come from an fp16 copy; el, er were made from the fp32 rows
+    GNN_TRY(to_half(g, dm.HF, z, half_buf, st));
+    feat = static_cast<const float*>(half_buf);
+  }
   if (t)
-    return run_blocks<3>(g, 0, "gat_fwd_fused", dm, hm, z, el_use, er, nullptr, nullptr, nullptr, out, t, sg,
-                         queue, state, m, d, st);
-  return run_blocks<0>(g, 0, "gat_fwd_fused", dm, hm, z, el_use, er, nullptr, nullptr, nullptr, out, nullptr,
-                       nullptr, queue, state, m, d, st);
+    return run_blocks<3>(g, 0, "gat_fwd_fused", dm, hm, feat, el_use, er, nullptr, nullptr, nullptr, out, t, sg,
+                         queue, state, m, d, st, half);
+  return run_blocks<0>(g, 0, "gat_fwd_fused", dm, hm, feat, el_use, er, nullptr, nullptr, nullptr, out, nullptr,
+                       nullptr, queue, state, m, d, st, half);
 }
 
 gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
@@ -509,15 +597,22 @@ gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* 
   if (!config_get(kCfgLdsScalarTable)) queue = nullptr;
   GNN_TRY(run_blocks<1>(g, 0, "gat_bwd_dst", dm, el_t != nullptr, z, el_t ? el_t : el, er, m, d, nullptr,
                         t_buf, nullptr, sg_buf, queue, nullptr, nullptr, nullptr, st));
-  return gat_dst_finish(g, dm, gout, t_buf, out, sg_buf, er, m, d, 1, der, vstate, st);
+  return gat_dst_finish(g, dm, gout, t_buf, out, sg_buf, er, m, d,
+                        kDstHeadMajor | (gat_blocked_half(g, dm.H, dm.F) ? kDstHalfGout : 0), der, vstate, st);
 }
 
 gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                                  const float4* vstate, const float* der, const float* gout,
                                  const float* a_l, const float* a_r, float* dz, float* del,
-                                 float* a2_buf, float* sd_buf, hipStream_t st) {
-  GNN_TRY(run_blocks<2>(g, 1, "gat_bwd_src", dm, 0, gout, el, nullptr, nullptr, nullptr, vstate, dz,
-                        a2_buf, sd_buf, nullptr, nullptr, nullptr, nullptr, st));
+                                 float* a2_buf, float* sd_buf, void* half_buf, hipStream_t st) {
+  const bool half = half_buf != nullptr && gat_blocked_half(g, dm.H, dm.F);
+  const float* feat = gout;
+  if (half) {
+    GNN_TRY(to_half(g, dm.HF, gout, half_buf, st));
+    feat = static_cast<const float*>(half_buf);
+  }
+  GNN_TRY(run_blocks<2>(g, 1, "gat_bwd_src", dm, 0, feat, el, nullptr, nullptr, nullptr, vstate, dz,
+                        a2_buf, sd_buf, nullptr, nullptr, nullptr, nullptr, st, half));
   return gat_src_finish(g, dm, z, a2_buf, sd_buf, der, a_l, a_r, dz, del, st);
 }
 

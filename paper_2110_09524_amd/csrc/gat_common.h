@@ -36,11 +36,15 @@ gnn_status_t gat_blocked_fwd(const gnn_graph_t* g, GatDims dm, const float* z, c
                              const float* er, float* m, float* d, float* out, float* t, float* sg,
                              float* el_t /* [H][n] scratch or null */,
                              int32_t* queue /* nblk * 8 row counters or null */, float4* state,
+                             void* half_buf /* n * HF * 2 bytes or null: room for an fp16 copy of z */,
                              hipStream_t st);
-// vertex-side closing steps shared by both paths (gat.hip)
+// true when the blocked kernels would gather from an fp16 copy for this shape (configuration)
+bool gat_blocked_half(const gnn_graph_t* g, int heads, int f);
+// vertex-side closing steps shared by both paths (gat.hip); flags: see k_gat_dst_finish
+constexpr int kDstHeadMajor = 1, kDstHalfGout = 2;
 gnn_status_t gat_dst_finish(const gnn_graph_t* g, GatDims dm, const float* gout, const float* t,
                             const float* out, const float* sg, const float* er, const float* m,
-                            const float* d, int head_major, float* der, float4* vstate,
+                            const float* d, int flags, float* der, float4* vstate,
                             hipStream_t st);
 gnn_status_t gat_src_finish(const gnn_graph_t* g, GatDims dm, const float* z, const float* a2,
                             const float* sd, const float* der, const float* a_l, const float* a_r,
@@ -55,6 +59,7 @@ gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* 
 gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                                  const float4* vstate, const float* der, const float* gout,
                                  const float* a_l, const float* a_r, float* dz, float* del,
-                                 float* a2_buf, float* sd_buf, hipStream_t st);
+                                 float* a2_buf, float* sd_buf,
+                                 void* half_buf /* n * HF * 2 bytes or null */, hipStream_t st);
 
 }  // namespace gnn

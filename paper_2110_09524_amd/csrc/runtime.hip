@@ -32,7 +32,8 @@ void clear_error() { g_err[0] = 0; }
 // blocked_min_edges: mean edges per (row, column block) from which the column-blocked kernels are
 // used (below that the per-launch cost of visiting every row outweighs the cache residency;
 // break-even measured between 12 and 24 at 1 KB rows)
-static std::atomic<int64_t> g_config[kCfgCount] = {{24576}, {0}, {1}, {2}, {2}, {16}};
+// gather_precision: 0 the column-blocked GAT kernels gather fp32 rows, 1 they gather an fp16 copy
+static std::atomic<int64_t> g_config[kCfgCount] = {{24576}, {0}, {1}, {2}, {2}, {16}, {0}};
 int64_t config_get(ConfigKey k) { return g_config[k].load(std::memory_order_relaxed); }
 
 // ---- profiling ---------------------------------------------------------------
@@ -117,6 +118,11 @@ extern "C" gnn_status_t gnn_config_set(const char* key, int64_t value) {
   if (std::strcmp(key, "gcn_mapping") == 0) {
     GNN_REQUIRE(value >= 0 && value <= 2, GNN_ERR_INVALID_ARG, "gnn_config_set: gcn_mapping must be 0, 1 or 2");
     g_config[kCfgGcnMapping].store(value);
+    return GNN_OK;
+  }
+  if (std::strcmp(key, "gather_precision") == 0) {
+    GNN_REQUIRE(value == 0 || value == 1, GNN_ERR_INVALID_ARG, "gnn_config_set: gather_precision must be 0 or 1");
+    g_config[kCfgGatherPrecision].store(value);
     return GNN_OK;
   }
   if (std::strcmp(key, "blocked_min_edges") == 0) {
