@@ -109,6 +109,13 @@ gnn_status_t gnn_graph_get_blocked(const gnn_graph_t* graph, int side, int32_t* 
                                    int32_t* block_cols /*host*/, int32_t* bptr, int32_t* bcol,
                                    void* stream);
 
+/* Plan tables and the temporaries of gnn_graph_create come from a free list inside the library
+ * (blocks of up to 64 MB, at most 512 MB idle in total), so that graphs which are rebuilt all
+ * the time (a k-nearest-neighbour graph per training step) do not pay hipMalloc / hipFree each
+ * time.  gnn_graph_destroy waits for the device, then returns the graph's blocks to that list;
+ * this call hands every idle block back to the driver. */
+gnn_status_t gnn_release_cached_memory(void);
+
 /* Tuning knobs, read when a graph is created or a layer is called.  Keys:
  *   "block_cols"            gathered vertices per column block (default 24576:
  *                           24576 rows x one 128-byte slice per XCD = 3 MB of a

@@ -21,7 +21,7 @@ STATUS_NAMES = {0: "GNN_OK", 1: "GNN_ERR_INVALID_ARG", 2: "GNN_ERR_BAD_GRAPH",
 
 EXPORTS = [
     "gnn_last_error", "gnn_graph_create", "gnn_graph_destroy", "gnn_graph_get_csc",
-    "gnn_graph_get_buckets", "gnn_graph_get_blocked", "gnn_config_set", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
+    "gnn_graph_get_buckets", "gnn_graph_get_blocked", "gnn_release_cached_memory", "gnn_config_set", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
     "gnn_gat_bwd", "gnn_gat_stash_alpha", "gnn_gat_bwd_stashed", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
     "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd", "gnn_gmm_tune",
     "gnn_gmmp_workspace_bytes", "gnn_gmmp_fwd", "gnn_gmmp_bwd", "gnn_pseudo_proj_workspace_bytes",
@@ -53,6 +53,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_graph_get_buckets.argtypes = [vp, i32, vp, vp, vp, vp]
     lib.gnn_graph_get_blocked.argtypes = [vp, i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), vp, vp, vp]
     lib.gnn_config_set.argtypes = [C.c_char_p, i64]
+    lib.gnn_release_cached_memory.argtypes = []
     lib.gnn_linear_fwd.argtypes = [i64, i32, i32, vp, vp, vp, vp]
     lib.gnn_gat_workspace_bytes.restype = sz
     lib.gnn_gat_workspace_bytes.argtypes = [vp, i32, i32, i32]
@@ -328,6 +329,10 @@ def gnn_pseudo_proj_bwd(g: Graph, r, c, pseudo, gpseudo, gproj_w, gproj_b, ws, s
     wp, wb = _ws_args(ws)
     _check(lib().gnn_pseudo_proj_bwd(g.handle, r, _f(c), _f(pseudo), _f(gpseudo), _f(gproj_w), _f(gproj_b), wp, wb,
                                      _stream(stream)))
+
+
+def gnn_release_cached_memory():
+    _check(lib().gnn_release_cached_memory())
 
 
 ACTS = {"identity": 0, "relu": 1, "elu": 2, "leaky": 3}

@@ -178,6 +178,18 @@ static void pool_free(void* p) {
   (void)hipFree(p);
 }
 
+// returns every idle block to the driver
+static void pool_trim() {
+  std::unordered_multimap<size_t, void*> idle;
+  {
+    std::lock_guard<std::mutex> lk(g_pool_mu);
+    idle.swap(g_pool_free);
+    for (auto& kv : idle) g_pool_capacity.erase(kv.second);
+    g_pool_cached = 0;
+  }
+  for (auto& kv : idle) (void)hipFree(kv.second);
+}
+
 static void free_all(gnn_graph* g) {
   if (!g) return;
   (void)hipDeviceSynchronize();  // kernels that read the tables have finished (hipFree used to wait, too)
@@ -438,6 +450,12 @@ static gnn_status_t build(gnn_graph* g, hipStream_t st) {
 }  // namespace gnn
 
 using namespace gnn;
+
+extern "C" gnn_status_t gnn_release_cached_memory(void) {
+  clear_error();
+  pool_trim();
+  return GNN_OK;
+}
 
 extern "C" gnn_status_t gnn_graph_create(int32_t n, int64_t nnz, const int32_t* indptr,
                                          const int32_t* indices, void* stream, gnn_graph_t** graph) {

@@ -94,3 +94,33 @@ def test_blocked_edge_lists(block_cols):
     g = pk.Graph(dev(indptr), dev(indices))          # default block size: one block, no tables
     assert g.blocked(0)[0] == 1
     g.close()
+
+
+def test_plans_reuse_cached_memory_and_release_it():
+    """Rebuilding a plan of the same size takes its tables from the library's free list (no new device
+    memory), and gnn_release_cached_memory hands the idle blocks back to the driver."""
+    import torch
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev
+    from workloads import make
+    c = make("ec_c3_mid")
+    ip, ix = dev(c["indptr"]), dev(c["indices"])
+    g = pk.Graph(ip, ix)
+    csc = g.csc()                                   # also warms torch's own allocator
+    g.close()                                       # fills the library's free list
+    del csc
+    torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    for _ in range(5):
+        g = pk.Graph(ip, ix)
+        csc = g.csc()
+        g.close()
+    torch.cuda.synchronize()
+    assert torch.cuda.mem_get_info()[0] >= free0    # nothing new was taken from the driver
+    pk.gnn_release_cached_memory()
+    assert torch.cuda.mem_get_info()[0] > free0     # and the idle blocks went back
+    g = pk.Graph(ip, ix)                            # still works afterwards, same tables
+    again = g.csc()
+    for a, b in zip(csc, again):
+        assert torch.equal(a, b)
+    g.close()
