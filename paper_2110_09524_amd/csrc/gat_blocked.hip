@@ -32,10 +32,12 @@ constexpr int kBlkThreads = 256;
 constexpr int kSlices = 8;  // column slices of a wide row: one per XCD
 
 // How a row of HF floats is cut: `ns` slices of SL float4 each.  Wide rows (>= 1 KB) give every
-// XCD its own slice.  Narrower rows keep slices of a full 128-byte line (SL = 8) and have fewer
-// of them (ns = 4, 2, 1): workgroup id mod ns picks the slice, so XCD k and XCD k + ns work on the
-// same columns (for different rows) and each L2 still holds one slice of the column block.  A
-// gather of a half line would cost the L1 the same fill as a full one.
+// XCD its own slice.  512-byte rows keep slices of a full 128-byte line (SL = 8) and have four of
+// them: workgroup id mod 4 picks the slice, so XCD k and XCD k + 4 work on the same columns (for
+// different rows) and each L2 still holds one slice of the column block.  A gather of a half line
+// would cost the L1 the same fill as a full one.  Rows of 256 bytes and less are not blocked: at
+// Reddit scale the single-launch kernels were faster there (the whole matrix then fits the
+// Infinity Cache, and a launch per block costs more than it saves).
 struct Slicing {
   int SL, ns;
 };
@@ -46,7 +48,7 @@ static bool pick_slicing(int heads, int HF, Slicing& sl) {
     sl = Slicing{q, kSlices};
     return (q == 8 || q == 16 || q == 32) && kSlices % heads == 0;
   }
-  if ((q == 4 || q == 2 || q == 1) && q % heads == 0) {
+  if (q == 4 && q % heads == 0) {
     sl = Slicing{8, q};
     return true;
   }

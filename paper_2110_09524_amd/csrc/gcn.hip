@@ -302,8 +302,8 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
 }
 
 // A row of F floats is cut into `ns` slices of SL float4: one slice per XCD for rows of 1 KB and
-// more; narrower rows keep slices of a full 128-byte line and have fewer of them (workgroup id
-// mod ns picks the slice, so XCD k and XCD k + ns share columns and split the rows).
+// more; 512-byte rows keep slices of a full 128-byte line and have four of them (workgroup id
+// mod 4 picks the slice, so XCD k and XCD k + 4 share columns and split the rows).
 static bool gcn_slicing(int F, int& SL, int& ns) {
   if (F % 32 != 0) return false;
   const int q = F / 32;
@@ -314,7 +314,7 @@ static bool gcn_slicing(int F, int& SL, int& ns) {
   }
   SL = 8;
   ns = q;
-  return q == 4 || q == 2 || q == 1;
+  return q == 4;  // narrower rows stay with the single-launch kernel
 }
 
 static bool gcn_blocked_applies(const gnn_graph_t* g, int F) {
