@@ -1046,7 +1046,10 @@ extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, in
   // The column-blocked kernels need scratch (a head-major copy of el, row counters, and the
   // running softmax statistics, which borrow the dz area the backward call uses later: 128 of
   // its >= 512 bytes per vertex); without a workspace the single-launch kernels run.
-  if (gat_blocked_applies(g, heads, f) && have_ws) {
+  // Forward takes the column-blocked kernels from 1 KB rows on; at 512 bytes the single-launch
+  // forward kernel measured faster at Reddit scale (8.4 vs 9.1 ms) while the source-side backward
+  // kernel is faster blocked (9.6 vs 11.0 ms), so the two calls decide separately.
+  if (gat_blocked_applies(g, heads, f) && have_ws && HF >= 256) {
     char* base = static_cast<char*>(ws);
     return gat_blocked_fwd(g, make_dims(heads, f, slope), z, el, er, m, d, out, t, sg,
                            reinterpret_cast<float*>(base + L.blk_elt),
