@@ -63,6 +63,16 @@ def edgeconv_models(n, e, fin, F):
 def gmm_models(n, e, fin, F, K):
     V = 4 * n * F
     I = 4 * e + 8 * n
+    if fin % 4 == 0 and fin <= 256 and fin < K * F:
+        # the library aggregates the input rows per kernel and projects afterwards: the edge kernels
+        # of the forward pass and of the destination side of backward gather x (fin wide)
+        X = 4 * n * fin
+        unique = {"gmm_fwd_fused": I + X + 4 * n + K * X, "gmm_bwd_dst": I + X + 4 * n + K * X,
+                  "gmm_bwd_src": I + V + 4 * n + K * V}
+        gather = {"gmm_fwd_fused": e * (8 + 4 * fin), "gmm_bwd_dst": e * (8 + 4 * fin), "gmm_bwd_src": e * (8 + 4 * F)}
+        flops = {"gmm_fwd_fused": e * K * (2 * fin + 12), "gmm_bwd_dst": e * K * (6 * fin + 14),
+                 "gmm_bwd_src": e * K * (2 * F + 12)}
+        return unique, gather, flops
     unique = {"gmm_fwd_fused": I + K * V + 4 * n + V,
               "gmm_bwd_dst": I + K * V + 4 * n + V,
               "gmm_bwd_src": I + V + 4 * n + K * V}
@@ -453,7 +463,7 @@ def main():
         ws = new(max(ws_bytes, 16), dtype=torch.uint8)
 
         def step():
-            pk.gnn_gmm_fwd(g, fin, F, K, x, w_fc, cc, mu, inv_sigma, hk, out)
+            pk.gnn_gmm_fwd(g, fin, F, K, x, w_fc, cc, mu, inv_sigma, hk, out, ws)
             pk.gnn_gmm_bwd(g, fin, F, K, x, w_fc, cc, mu, inv_sigma, hk, gout, gx, gw_fc, gmu, gis, ws)
         unique, gather, flops = gmm_models(n, e, fin, F, K)
         pk.gnn_config_set("gmm_mapping", {"vertex": 0, "edge": 1, "tuned": 2}[args.gcn_mapping])
@@ -614,8 +624,9 @@ def main():
             lambda: pk.gnn_edgeconv_fwd(g, fin, F, x, theta, phi, pq, out, argmax, ws), out)
     if args.compare_unfused and kind == "gmm":
         from unfused_baseline.compare import compare_gmm
+        pk.gnn_linear_fwd(x, w_fc, hk)      # the comparator's input (the fused layer may skip hk)
         cmp = compare_gmm(c, indptr, indices, cc, mu, inv_sigma, hk,
-                          lambda: pk.gnn_gmm_fwd(g, fin, F, K, x, w_fc, cc, mu, inv_sigma, hk, out), out)
+                          lambda: pk.gnn_gmm_fwd(g, fin, F, K, x, w_fc, cc, mu, inv_sigma, hk, out, ws), out)
         cmp["fused_graph_fwd_ms"] = kern["gmm_fwd_fused"]["ms_per_step"]
         cmp["time_ratio_unfused_over_fused"] = cmp["unfused_graph_fwd_ms"] / cmp["fused_graph_fwd_ms"]
         result["unfused_comparison"] = cmp

@@ -259,6 +259,16 @@ gnn_status_t gnn_edgeconv_bwd(const gnn_graph_t* graph, int fin, int fout, const
  * per-vertex scalar supplied by the caller (no gradient).  The Gaussian
  * weights are never stored: backward recomputes them (Sec. 7.3).
  * Requirements: fout % 4 == 0, fout <= 256, 1 <= k <= 8.
+ *
+ * Order of projection and aggregation (the reorganization argument of Sec. 4: a linear
+ * operator commutes with the weighted sums, so it runs on whichever side is cheaper).
+ * When an input row is narrower than the k projected rows (fin < k*fout, fin % 4 == 0,
+ * fin <= 256) and the forward call is given the workspace, the layer aggregates first,
+ *   out = (1/k) [ sum_e w_j(m_e) x[u] ]_j  W',   W' = w_fc regrouped to [k*fin, fout],
+ * so an edge gathers fin floats once instead of k*fout, and hk is NOT written (the backward
+ * call then does not read it either: its destination side gathers x against gout W'^T).
+ * Otherwise (or without a workspace in the forward call) hk = x w_fc is written and the
+ * edges gather the projected rows; hk must then be passed unchanged to the backward call.
  * ------------------------------------------------------------------------- */
 size_t gnn_gmm_workspace_bytes(const gnn_graph_t* graph, int fin, int fout, int k);
 

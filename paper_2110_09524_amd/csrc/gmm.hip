@@ -284,6 +284,246 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd_eb(
   }
 }
 
+// ---- aggregate first, project afterwards (fin < K * fout) -----------------------------------
+// The projection is linear, so it commutes with the weighted sums (the observation behind Sec. 4,
+// applied in the other direction):
+//   out[v] = (1/K) sum_j ( sum_e w_j(e) x[u] ) W_j = (1/K) sum_j agg_j[v] W_j .
+// When the input row is narrower than the K projected rows, an edge then gathers fin floats once
+// instead of K * fout, and the projection becomes one dense product on vertices,
+// out = agg [n, K*fin] . W' [K*fin, fout].  The destination side of backward changes the same way:
+// <gout[v], hk[u,j,:]> = <G_j[v], x[u]> with G = gout W'^T, so it gathers x as well.
+template <int L>
+__global__ __launch_bounds__(kGmmBlock) void k_gmm_fwd_x(
+    RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    const int32_t* __restrict__ indices, const float* __restrict__ x, const float* __restrict__ c,
+    const float* __restrict__ mu, const float* __restrict__ inv_sigma, int K, int fin,
+    float* __restrict__ agg /* [n, K*fin] */) {
+  constexpr int GPB = kGmmBlock / L;
+  constexpr int KB = kGmmKB, U = 4;
+  constexpr int GS = (1 + KB) * L;
+  __shared__ __align__(16) float lds[GPB * GS];
+  __shared__ float coop_buf[GPB * L * 4 * KB];
+  const int lane = threadIdx.x & 63;
+  const int li = lane & (L - 1);
+  const int grp = threadIdx.x / L;
+  int64_t r;
+  int gi, ngrp;
+  RowRange rr;
+  if (!pick_row<GPB>(rl, grp, rr, r, gi, ngrp)) return;
+  int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
+  float* l_w = lds + grp * GS + L;
+  const float inv_k = 1.f / (float)K;
+  const int32_t v = order[r];
+  const int32_t beg = indptr[v], end = indptr[v + 1];
+  const float cv = c[v];
+  const bool col_ok = 4 * li < fin;
+  for (int k0 = 0; k0 < K; k0 += KB) {
+    float mu0[KB], mu1[KB], is0[KB], is1[KB];
+#pragma unroll
+    for (int q = 0; q < KB; ++q) {
+      const bool ok = k0 + q < K;
+      mu0[q] = ok ? mu[2 * (k0 + q)] : 0.f;
+      mu1[q] = ok ? mu[2 * (k0 + q) + 1] : 0.f;
+      is0[q] = ok ? inv_sigma[2 * (k0 + q)] : 0.f;
+      is1[q] = ok ? inv_sigma[2 * (k0 + q) + 1] : 0.f;
+    }
+    float4 acc[KB], part[KB];
+#pragma unroll
+    for (int q = 0; q < KB; ++q) {
+      acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      part[q] = acc[q];
+    }
+    constexpr int kFold = L >= 32 ? 1 : 32 / L;  // two-level summation, as in k_gmm_fwd
+    int chunk_no = 0;
+    for (int32_t c0 = beg + gi * L; c0 < end; c0 += ngrp * L) {
+      const bool e_ok = c0 + li < end;
+      const int32_t u = e_ok ? indices[c0 + li] : 0;
+      const float cu = c[u];
+      l_idx[li] = u;
+#pragma unroll
+      for (int q = 0; q < KB; ++q)
+        l_w[q * L + li] = (e_ok && k0 + q < K) ? gauss_w(cu, cv, mu0[q], mu1[q], is0[q], is1[q]) * inv_k : 0.f;
+      wave_lds_fence();
+      const int cnt = min(L, end - c0);
+      if (col_ok) {
+        for (int t0 = 0; t0 < cnt; t0 += U) {
+          float4 rowv[U];
+#pragma unroll
+          for (int t = 0; t < U; ++t) {
+            int uu = l_idx[min(t0 + t, L - 1)];  // past the chunk: a valid vertex with weight 0 or an unused slot
+            if (L == 64) uu = __builtin_amdgcn_readfirstlane(uu);
+            rowv[t] = ld4(x + (int64_t)uu * fin + 4 * li);
+          }
+#pragma unroll
+          for (int t = 0; t < U; ++t) {
+            if (t0 + t < L) {
+#pragma unroll
+              for (int q = 0; q < KB; ++q) fma4(part[q], l_w[q * L + t0 + t], rowv[t]);
+            }
+          }
+        }
+      }
+      if ((++chunk_no % kFold) == 0) {
+#pragma unroll
+        for (int q = 0; q < KB; ++q) {
+          add4(acc[q], part[q]);
+          part[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+      }
+      wave_lds_fence();
+    }
+#pragma unroll
+    for (int q = 0; q < KB; ++q) add4(acc[q], part[q]);
+    if (rr.coop) {  // every group of the workgroup shares the row and runs the same passes
+      float vv[4 * KB];
+#pragma unroll
+      for (int q = 0; q < KB; ++q) pack4(vv + 4 * q, acc[q]);
+      coop_sum<L, 4 * KB, GPB>(coop_buf, vv, grp, li);
+#pragma unroll
+      for (int q = 0; q < KB; ++q) acc[q] = unpack4(vv + 4 * q);
+    }
+    if (col_ok && (!rr.coop || grp == 0)) {
+#pragma unroll
+      for (int q = 0; q < KB; ++q)
+        if (k0 + q < K) st4(agg + ((int64_t)v * K + k0 + q) * fin + 4 * li, acc[q]);
+    }
+  }
+}
+
+// destination side of backward on gathered x rows; G [n, K*fin] = gout W'^T.  Partials as k_gmm_bwd_dst.
+template <int L>
+__global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_dst_x(
+    RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    const int32_t* __restrict__ indices, const float* __restrict__ x, const float* __restrict__ c,
+    const float* __restrict__ mu, const float* __restrict__ inv_sigma, const float* __restrict__ G, int K,
+    int fin, float* __restrict__ partial) {
+  constexpr int GPB = kGmmBlock / L;
+  constexpr int KB = kGmmKB, U = 4;
+  constexpr int GS = (1 + 3 * KB) * L;
+  __shared__ __align__(16) float lds[GPB * GS];
+  __shared__ float blk[GPB][kMaxK][4];
+  __shared__ float coop_buf[GPB * L * 3];
+  const int lane = threadIdx.x & 63;
+  const int li = lane & (L - 1);
+  const int grp = threadIdx.x / L;
+  int64_t r;
+  int gi, ngrp;
+  RowRange rr;
+  const bool active = pick_row<GPB>(rl, grp, rr, r, gi, ngrp);
+  int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
+  float* l_w = lds + grp * GS + L;
+  float* l_wr = l_w + KB * L;
+  float* l_ws = l_wr + KB * L;
+  const float inv_k = 1.f / (float)K;
+  for (int i = li; i < kMaxK * 4; i += L) blk[grp][i >> 2][i & 3] = 0.f;
+  if (active) {
+    const int32_t v = order[r];
+    const int32_t beg = indptr[v], end = indptr[v + 1];
+    const float cv = c[v];
+    const bool col_ok = 4 * li < fin;
+    for (int k0 = 0; k0 < K; k0 += KB) {
+      float mu0[KB], mu1[KB], is0[KB], is1[KB];
+#pragma unroll
+      for (int q = 0; q < KB; ++q) {
+        const bool ok = k0 + q < K;
+        mu0[q] = ok ? mu[2 * (k0 + q)] : 0.f;
+        mu1[q] = ok ? mu[2 * (k0 + q) + 1] : 0.f;
+        is0[q] = ok ? inv_sigma[2 * (k0 + q)] : 0.f;
+        is1[q] = ok ? inv_sigma[2 * (k0 + q) + 1] : 0.f;
+      }
+      float4 aA[KB], aR[KB], aS[KB];
+#pragma unroll
+      for (int q = 0; q < KB; ++q) {
+        aA[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        aR[q] = aA[q];
+        aS[q] = aA[q];
+      }
+      for (int32_t c0 = beg + gi * L; c0 < end; c0 += ngrp * L) {
+        const bool e_ok = c0 + li < end;
+        const int32_t u = e_ok ? indices[c0 + li] : 0;
+        const float cu = c[u];
+        l_idx[li] = u;
+#pragma unroll
+        for (int q = 0; q < KB; ++q) {
+          const float w = (e_ok && k0 + q < K) ? gauss_w(cu, cv, mu0[q], mu1[q], is0[q], is1[q]) : 0.f;
+          const float d0 = cu - mu0[q];
+          l_w[q * L + li] = w;
+          l_wr[q * L + li] = w * d0;
+          l_ws[q * L + li] = w * d0 * d0;
+        }
+        wave_lds_fence();
+        const int cnt = min(L, end - c0);
+        if (col_ok) {
+          for (int t0 = 0; t0 < cnt; t0 += U) {
+            float4 rowv[U];
+#pragma unroll
+            for (int t = 0; t < U; ++t) {
+              int uu = l_idx[min(t0 + t, L - 1)];
+              if (L == 64) uu = __builtin_amdgcn_readfirstlane(uu);
+              rowv[t] = ld4(x + (int64_t)uu * fin + 4 * li);
+            }
+#pragma unroll
+            for (int t = 0; t < U; ++t) {
+              if (t0 + t < L) {
+#pragma unroll
+                for (int q = 0; q < KB; ++q) {
+                  fma4(aA[q], l_w[q * L + t0 + t], rowv[t]);
+                  fma4(aR[q], l_wr[q * L + t0 + t], rowv[t]);
+                  fma4(aS[q], l_ws[q * L + t0 + t], rowv[t]);
+                }
+              }
+            }
+          }
+        }
+        wave_lds_fence();
+      }
+#pragma unroll
+      for (int q = 0; q < KB; ++q) {
+        if (k0 + q >= K) continue;
+        float tA = 0.f, tR = 0.f, tS = 0.f;
+        if (col_ok) {
+          const float4 g4 = ld4(G + ((int64_t)v * K + k0 + q) * fin + 4 * li);
+          tA = dot4(g4, aA[q]);
+          tR = dot4(g4, aR[q]);
+          tS = dot4(g4, aS[q]);
+        }
+        tA = group_sum_from<L>(tA, 1);
+        tR = group_sum_from<L>(tR, 1);
+        tS = group_sum_from<L>(tS, 1);
+        if (rr.coop) {
+          float vv[3] = {tA, tR, tS};
+          coop_sum<L, 3, GPB>(coop_buf, vv, grp, li);
+          tA = vv[0]; tR = vv[1]; tS = vv[2];
+        }
+        if (li == 0 && (!rr.coop || grp == 0)) {
+          const float d1 = cv - mu1[q];
+          blk[grp][k0 + q][0] = tR * is0[q] * is0[q] * inv_k;
+          blk[grp][k0 + q][1] = tA * d1 * is1[q] * is1[q] * inv_k;
+          blk[grp][k0 + q][2] = -tS * is0[q] * inv_k;
+          blk[grp][k0 + q][3] = -tA * d1 * d1 * is1[q] * inv_k;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < kMaxK * 4) {
+    const int k = threadIdx.x >> 2, q = threadIdx.x & 3;
+    float s = 0.f;
+    for (int g2 = 0; g2 < GPB; ++g2) s += blk[g2][k][q];  // fixed order
+    partial[((int64_t)blockIdx.x * kMaxK + k) * 4 + q] = s;
+  }
+}
+
+// W'[(k*fin + i), f] = w_fc[i, k*F + f]
+__global__ void k_gmm_wt(int fin, int K, int F, const float* __restrict__ w_fc, float* __restrict__ wt) {
+  const int64_t t = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (t >= (int64_t)fin * K * F) return;
+  const int f = (int)(t % F);
+  const int64_t ki = t / F;
+  const int i = (int)(ki % fin), k = (int)(ki / fin);
+  wt[t] = w_fc[(int64_t)i * K * F + (int64_t)k * F + f];
+}
+
 // ---- a10, destination side: gradients of mu and inv_sigma (CSR walk) ------------------
 // partial[block][j][4] = this block's share of (gmu_j0, gmu_j1, gis_j0, gis_j1)
 template <int L, int NV>
@@ -593,6 +833,46 @@ struct GmmFwdEbLauncher {
   }
 };
 
+template <int L, int NV>
+struct GmmFwdXLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, const float* x, const float* c, const float* mu,
+                          const float* is, int K, int fin, float* agg, hipStream_t st) {
+    constexpr int GPB = kGmmBlock / L;
+    ProfScope p("gmm_fwd_fused", st);
+    const RowSplit sp = split_rows(g, 0, L, GPB);
+    const unsigned grid = sp.hub_grid + sp.rest_grid;
+    const RowLaunch rl{sp.hub.end, g->n};
+    if (grid != 0) {
+      k_gmm_fwd_x<L><<<grid, kGmmBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, x, c, mu, is, K, fin, agg);
+      GNN_LAUNCH_CHECK();
+    }
+    return GNN_OK;
+  }
+};
+
+template <int L, int NV>
+struct GmmBwdDstXLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, const float* x, const float* c, const float* mu,
+                          const float* is, const float* G, int K, int fin, float* partial, float* gmu,
+                          float* gis, hipStream_t st) {
+    constexpr int GPB = kGmmBlock / L;
+    ProfScope p("gmm_bwd_dst", st);
+    const RowSplit sp = split_rows(g, 0, L, GPB);
+    const unsigned grid = sp.hub_grid + sp.rest_grid;
+    const RowLaunch rl{sp.hub.end, g->n};
+    if (grid != 0) {
+      k_gmm_bwd_dst_x<L><<<grid, kGmmBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, x, c, mu, is, G, K,
+                                                    fin, partial);
+      GNN_LAUNCH_CHECK();
+    }
+    float* totals = partial + (int64_t)grid * kMaxK * 4;
+    GNN_TRY(sum_partials_two_level(kMaxK * 4, (int)grid, partial, totals + kMaxK * 4, totals, st));
+    k_gmm_param_split<<<1, 64, 0, st>>>(K, totals, gmu, gis);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+  }
+};
+
 // number of workgroups (= partial slots) the destination-side kernel uses
 template <int L>
 static int64_t gmm_dst_blocks(const gnn_graph_t* g) {
@@ -674,30 +954,45 @@ static gnn_status_t gmm_aggregate(const gnn_graph_t* g, bool edge_balanced, cons
   return gmm_dispatch<GmmFwdLauncher>(pick_group(pm.F), g, hk, c, mu, is, pm, out, st);
 }
 
+// aggregate first when an input row is narrower than the K projected rows (and fits one float4 per lane)
+static bool gmm_aggregate_first(int fin, int fout, int K) {
+  return fin % 4 == 0 && fin <= 256 && fin < K * fout;
+}
+
 struct GmmWs {
-  size_t total, dhk, partial, gemm;
+  size_t total, dhk, partial, gemm, agg, wt;
   int split_k;
   int64_t nblk;
 };
+
+static int64_t gmm_dst_blocks_for(const gnn_graph_t* g, int width) {
+  switch (pick_group(width).L) {
+    case 4: return gmm_dst_blocks<4>(g);
+    case 8: return gmm_dst_blocks<8>(g);
+    case 16: return gmm_dst_blocks<16>(g);
+    case 32: return gmm_dst_blocks<32>(g);
+    default: return gmm_dst_blocks<64>(g);
+  }
+}
 
 static GmmWs gmm_ws_layout(const gnn_graph_t* g, int fin, int fout, int K) {
   const int64_t n = g->n;
   GmmWs w{};
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += ws_granule(bytes); return o; };
-  const GroupShape gs = pick_group(fout);
-  switch (gs.L) {
-    case 4: w.nblk = gmm_dst_blocks<4>(g); break;
-    case 8: w.nblk = gmm_dst_blocks<8>(g); break;
-    case 16: w.nblk = gmm_dst_blocks<16>(g); break;
-    case 32: w.nblk = gmm_dst_blocks<32>(g); break;
-    default: w.nblk = gmm_dst_blocks<64>(g); break;
+  const bool xg = gmm_aggregate_first(fin, fout, K);
+  w.nblk = gmm_dst_blocks_for(g, fout);
+  if (xg) {
+    const int64_t nb = gmm_dst_blocks_for(g, fin);
+    if (nb > w.nblk) w.nblk = nb;
   }
   w.dhk = take(sizeof(float) * (size_t)n * K * fout);
   // block slots + one slot for the totals + second-level scratch
   w.partial = take(sizeof(float) * (size_t)(w.nblk + 1 + sum_partials_scratch_rows((int)w.nblk)) * kMaxK * 4);
   w.split_k = gemm_pick_split_k(fin, K * fout, n);
   w.gemm = take(w.split_k > 1 ? sizeof(float) * (size_t)w.split_k * fin * K * fout : 0);
+  w.agg = take(xg ? sizeof(float) * (size_t)n * K * fin : 0);  // forward: aggregated inputs; backward: gout W'^T
+  w.wt = take(xg ? sizeof(float) * (size_t)K * fin * fout : 0);
   w.total = off;
   return w;
 }
@@ -725,8 +1020,6 @@ extern "C" gnn_status_t gnn_gmm_fwd(const gnn_graph_t* g, int fin, int fout, int
                                     const float* inv_sigma, float* hk, float* out, void* ws,
                                     size_t ws_bytes, void* stream) {
   clear_error();
-  (void)ws;
-  (void)ws_bytes;
   GNN_TRY(gmm_check(g, fin, fout, k, "gnn_gmm_fwd"));
   if (g->n == 0) return GNN_OK;
   GNN_REQUIRE(x && w_fc && c && mu && inv_sigma && hk && out, GNN_ERR_INVALID_ARG,
@@ -734,9 +1027,29 @@ extern "C" gnn_status_t gnn_gmm_fwd(const gnn_graph_t* g, int fin, int fout, int
   GNN_REQUIRE(aligned16(hk) && aligned16(out), GNN_ERR_INVALID_ARG,
               "gnn_gmm_fwd: hk, out must be 16-byte aligned");
   hipStream_t st = static_cast<hipStream_t>(stream);
-  GNN_TRY(gemm_f32(g->n, k * fout, fin, x, fin, false, w_fc, k * fout, false, hk, k * fout, 1, nullptr, st));
   GmmParams pm{k, fout};
-  return gmm_aggregate(g, gmm_use_edge_balanced(g, k), hk, c, mu, inv_sigma, pm, out, st);
+  const bool eb = gmm_use_edge_balanced(g, k);
+  if (!eb && gmm_aggregate_first(fin, fout, k) && ws != nullptr && aligned16(ws)) {
+    const GmmWs W = gmm_ws_layout(g, fin, fout, k);
+    if (ws_bytes >= W.total) {
+      // aggregate the input rows per kernel, then project: out = agg W'
+      char* base = static_cast<char*>(ws);
+      float* agg = reinterpret_cast<float*>(base + W.agg);
+      float* wt = reinterpret_cast<float*>(base + W.wt);
+      {
+        ProfScope p("gmm_weight_layout", st);
+        const int64_t cnt = (int64_t)fin * k * fout;
+        k_gmm_wt<<<(unsigned)cdiv(cnt, 256), 256, 0, st>>>(fin, k, fout, w_fc, wt);
+        GNN_LAUNCH_CHECK();
+      }
+      GNN_TRY((gmm_dispatch<GmmFwdXLauncher>(pick_group(fin), g, x, c, mu, inv_sigma, k, fin, agg, st)));
+      return gemm_f32(g->n, fout, (int64_t)k * fin, agg, (int64_t)k * fin, false, wt, fout, false, out, fout, 1,
+                      nullptr, st);
+    }
+  }
+  // project first: hk = x w_fc, then the fused weights + aggregate over the projected rows
+  GNN_TRY(gemm_f32(g->n, k * fout, fin, x, fin, false, w_fc, k * fout, false, hk, k * fout, 1, nullptr, st));
+  return gmm_aggregate(g, eb, hk, c, mu, inv_sigma, pm, out, st);
 }
 
 extern "C" gnn_status_t gnn_gmm_tune(gnn_graph_t* g, int fout, int k, const float* hk, const float* c,
@@ -811,7 +1124,22 @@ extern "C" gnn_status_t gnn_gmm_bwd(const gnn_graph_t* g, int fin, int fout, int
   const int KF = k * fout;
   GmmParams pm{k, fout};
   const GroupShape gs = pick_group(fout);
-  GNN_TRY(gmm_dispatch<GmmBwdDstLauncher>(gs, g, hk, c, mu, inv_sigma, gout, pm, partial, gmu, ginv_sigma, st));
+  if (gmm_aggregate_first(fin, fout, k)) {
+    // <gout[v], hk[u,j,:]> = <G_j[v], x[u]>, G = gout W'^T: the destination side gathers x rows
+    float* G = reinterpret_cast<float*>(base + L.agg);
+    float* wt = reinterpret_cast<float*>(base + L.wt);
+    {
+      ProfScope p("gmm_weight_layout", st);
+      const int64_t cnt = (int64_t)fin * k * fout;
+      k_gmm_wt<<<(unsigned)cdiv(cnt, 256), 256, 0, st>>>(fin, k, fout, w_fc, wt);
+      GNN_LAUNCH_CHECK();
+    }
+    GNN_TRY(gemm_f32(n, k * fin, fout, gout, fout, false, wt, fout, true, G, (int64_t)k * fin, 1, nullptr, st));
+    GNN_TRY((gmm_dispatch<GmmBwdDstXLauncher>(pick_group(fin), g, x, c, mu, inv_sigma, (const float*)G, k, fin,
+                                              partial, gmu, ginv_sigma, st)));
+  } else {
+    GNN_TRY(gmm_dispatch<GmmBwdDstLauncher>(gs, g, hk, c, mu, inv_sigma, gout, pm, partial, gmu, ginv_sigma, st));
+  }
   GNN_TRY(gmm_dispatch<GmmBwdSrcLauncher>(gs, g, c, mu, inv_sigma, gout, pm, dhk, st));
   GNN_TRY(gemm_f32(fin, KF, n, x, fin, true, dhk, KF, false, gw_fc, KF, L.split_k, part, st));
   if (gx) GNN_TRY(gemm_f32(n, fin, KF, dhk, KF, false, w_fc, KF, true, gx, fin, 1, nullptr, st));

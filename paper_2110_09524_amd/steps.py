@@ -81,7 +81,7 @@ class GmmLayer:
     def forward(self, x, ws):
         p = self.p
         B.gnn_gmm_fwd(self.g, self.fin, self.fout, self.k, x, p["w_fc"], self.c, p["mu"], p["inv_sigma"], self.hk,
-                      self.out)
+                      self.out, ws)
         return self.out
 
     def backward(self, x, gout, gx, ws):

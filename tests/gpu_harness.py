@@ -143,18 +143,21 @@ def run_edgeconv(c, backward=True, gout=None):
     return {k: v.cpu().numpy() for k, v in res.items()}
 
 
-def run_gmm(c, backward=True):
+def run_gmm(c, backward=True, fwd_workspace=True):
+    """fwd_workspace=False: the forward call gets no workspace and projects before it aggregates
+    whatever the widths are (with one it aggregates first when the input rows are narrower)."""
     n, fin, fout, K = c["n"], c["fin"], c["fout"], c["k"]
     indptr, indices = dev(c["indptr"]), dev(c["indices"])
     g = pk.Graph(indptr, indices)
     x, w_fc, cc = dev(c["x"]), dev(c["w_fc"]), dev(c["c"])
     mu, inv_sigma = dev(c["mu"]), dev(c["inv_sigma"])
     hk, out = empty((n, K * fout)), empty((n, fout))
-    pk.gnn_gmm_fwd(g, fin, fout, K, x, w_fc, cc, mu, inv_sigma, hk, out)
+    ws = workspace(pk.gnn_gmm_workspace_bytes(g, fin, fout, K))
+    pk.gnn_gmm_fwd(g, fin, fout, K, x, w_fc, cc, mu, inv_sigma, hk, out, ws if fwd_workspace else None)
     res = dict(hk=hk, out=out)
     if backward:
         gout = dev(c["gout"])
-        ws = workspace(pk.gnn_gmm_workspace_bytes(g, fin, fout, K))
+        ws.fill_(0xFF)      # nothing may survive in the workspace between the two calls
         gx, gw_fc = empty((n, fin)), empty((fin, K * fout))
         gmu, gis = empty((K, 2)), empty((K, 2))
         pk.gnn_gmm_bwd(g, fin, fout, K, x, w_fc, cc, mu, inv_sigma, hk, gout, gx, gw_fc, gmu, gis, ws)

@@ -9,14 +9,17 @@ from workloads import make
 pytestmark = pytest.mark.gpu
 
 
-def check(c):
+def check(c, **kw):
     from gpu_harness import assert_close, run_gmm
     args = (c["indptr"], c["indices"], c["x"], c["w_fc"], c["c"], c["mu"], c["inv_sigma"])
     fwd = om.gmm_forward(*args)
     bwd = om.gmm_backward(*args, c["gout"], fwd)
-    res = run_gmm(c)
+    res = run_gmm(c, **kw)
     n = c["n"]
-    assert_close("hk", res["hk"], fwd["Hk"].reshape(n, -1))
+    aggregate_first = kw.get("fwd_workspace", True) and c["fin"] % 4 == 0 and c["fin"] <= 256 and \
+        c["fin"] < c["k"] * c["fout"]
+    if not aggregate_first:      # hk is only written when the layer projects before it aggregates
+        assert_close("hk", res["hk"], fwd["Hk"].reshape(n, -1))
     assert_close("out", res["out"], fwd["out"])
     assert_close("gx", res["gx"], bwd["gx"], row_scale=True)
     assert_close("gw_fc", res["gw_fc"], bwd["gw_fc"], reduce_scale=True)
@@ -49,6 +52,21 @@ def test_shapes(fin, fout, K):
     rng = np.random.default_rng(fin + fout + K)
     indptr, indices = random_graph(rng, 263, 2600, self_loops=True, duplicates=True)
     check(synth(rng, indptr, indices, fin, fout, K))
+
+
+@pytest.mark.parametrize("fin,fout,K", [(64, 64, 3), (16, 16, 2), (8, 256, 4), (100, 64, 8), (4, 4, 2), (252, 100, 3)])
+def test_aggregate_first_and_project_first_agree_with_the_oracle(fin, fout, K):
+    """Input rows narrower than the K projected rows: the forward call aggregates x per kernel and
+    projects afterwards when it has a workspace, and projects first without one; the backward
+    call gathers x on the destination side.  Hub rows included (cooperative path)."""
+    print(f"gmm: aggregate first {fin}->{fout} K={K}", flush=True)
+    rng = np.random.default_rng(fin * 7 + fout + K)
+    n = 500
+    edges = [(u, 3) for u in range(n)] + [(int(rng.integers(0, n)), int(v)) for v in range(n) for _ in range(int(v) % 9)]
+    indptr, indices = tiny_graph(n, edges)
+    c = synth(rng, indptr, indices, fin, fout, K)
+    check(c)
+    check(c, fwd_workspace=False)
 
 
 def test_graph_without_edges():

@@ -107,7 +107,7 @@ def test_degree_pair_coordinates_agree_with_the_dedicated_layer():
     dst = np.repeat(np.arange(c["n"]), np.diff(c["indptr"]))
     c2 = dict(c, r=2, pseudo=np.stack([c["c"][c["indices"]], c["c"][dst]], axis=1).astype(np.float32))
     a, b = run_gmm(c), run(c2)
-    for k in ("out", "gmu", "ginv_sigma", "gw_fc"):
+    for k in ("out", "gmu", "ginv_sigma", "gw_fc"):      # (hk is not written by the dedicated layer here)
         assert_close(k, b[k], a[k].astype(np.float64), reduce_scale=k != "out")
 
 
