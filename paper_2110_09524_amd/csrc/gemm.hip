@@ -248,8 +248,15 @@ gnn_status_t sum_partials_two_level(int64_t count, int parts, const float* parti
   return sum_partials(count, rows, scratch, out, s);
 }
 
+// 128 output columns per tile unless the last such tile would be at least half empty
+static int gemm_tile_cols(int N) {
+  if (N <= 64) return 64;
+  const int waste = (N + 127) / 128 * 128 - N;
+  return waste >= 64 ? 64 : 128;
+}
+
 int gemm_pick_split_k(int64_t M, int N, int64_t K) {
-  const int bn = N > 64 ? 128 : 64;
+  const int bn = gemm_tile_cols(N);
   int64_t tiles = cdiv(M, BM) * cdiv(N, bn);
   if (tiles >= 512 || K < 256) return 1;
   int64_t want = cdiv(1536, tiles);
@@ -301,7 +308,7 @@ gnn_status_t gemm_f32(int64_t M, int N, int64_t K, const float* a, int64_t lda, 
               "gemm_f32: split-K without a partials buffer");
 #define GNN_GEMM_CASE(BN_, AK_, BK_)                                                          \
   return launch<BN_, AK_, BK_>(M, N, K, a, lda, b, ldb, c, ldc, split_k, partials, s)
-  if (N > 64) {
+  if (gemm_tile_cols(N) == 128) {
     if (a_kmajor) { if (b_kcontig) GNN_GEMM_CASE(128, true, true); else GNN_GEMM_CASE(128, true, false); }
     else          { if (b_kcontig) GNN_GEMM_CASE(128, false, true); else GNN_GEMM_CASE(128, false, false); }
   } else {
