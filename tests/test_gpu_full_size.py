@@ -174,3 +174,51 @@ def test_gcn_on_the_c4_graph_sampled_rows_and_consistency(c4):
     assert_close("gw (two kernel paths)", res["gw"], res2["gw"], reduce_scale=True)
     assert_close("gx (two kernel paths)", res["gx"], res2["gx"], row_scale=True)
     g.close()
+
+
+def test_monet_on_the_c4_graph_sampled_rows_and_consistency(c4):
+    """The general GMM layer with projected 1-D pseudo-coordinates (the ablation setting of Sec. 7.3:
+    k = 2, r = 1, 16 features) on the Reddit-scale graph: sampled rows, hub row included, against the
+    oracle, and the bilinearity identity <gx, x> = <gw_fc, w_fc> = <gout, out> over the whole graph."""
+    import torch
+    import paper_2110_09524_amd as pk
+    from gpu_harness import assert_close, dev, empty, workspace
+    from oracle import gmm as om
+    from oracle.segments import restrict_rows
+    n, fin, fout, K, R = c4["n"], c4["fin"], 16, 2, 1
+    ip, ix = c4["indptr"], c4["indices"]
+    E = len(ix)
+    rng = np.random.default_rng(11)
+    indeg = np.diff(ip)
+    cvec = (1.0 / np.sqrt(np.maximum(indeg, 1))).astype(np.float32)
+    w_fc = (rng.standard_normal((fin, K * fout)) * np.sqrt(2.0 / (fin + K * fout))).astype(np.float32)
+    P, pb = rng.standard_normal((R, 2)).astype(np.float32), (0.1 * rng.standard_normal(R)).astype(np.float32)
+    mu, isg = (0.3 * rng.standard_normal((K, R))).astype(np.float32), np.ones((K, R), dtype=np.float32)
+    gout = rng.standard_normal((n, fout)).astype(np.float32)
+    g = pk.Graph(dev(ip), dev(ix))
+    x, dw, dc, dmu, dis, dgo = dev(c4["x"]), dev(w_fc), dev(cvec), dev(mu), dev(isg), dev(gout)
+    pseudo, gps = empty((E, R)), empty((E, R))
+    hk, out = empty((n, K * fout)), empty((n, fout))
+    gx, gw, gmu, gis = empty((n, fin)), empty((fin, K * fout)), empty((K, R)), empty((K, R))
+    ws = workspace(max(pk.gnn_gmmp_workspace_bytes(g, fin, fout, K), pk.gnn_pseudo_proj_workspace_bytes(g)))
+    print("full size monet: GPU fwd+bwd", flush=True)
+    pk.gnn_pseudo_proj_fwd(g, R, dc, dev(P), dev(pb), pseudo)
+    pk.gnn_gmmp_fwd(g, fin, fout, K, R, x, dw, pseudo, dmu, dis, hk, out)
+    pk.gnn_gmmp_bwd(g, fin, fout, K, R, x, dw, pseudo, dmu, dis, hk, dgo, gx, gw, gmu, gis, gps, ws)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[int(np.argmax(indeg)), int(np.argmin(indeg))],
+                                     rng.choice(n, size=60, replace=False)]))
+    print(f"full size monet: oracle on the in-edges of {rows.size} rows", flush=True)
+    rip, rix, pos = restrict_rows(ip, ix, rows)
+    ps_ref = om.pseudo_projection_forward(rip, rix, cvec, P, pb)
+    assert_close("pseudo", pseudo.cpu().numpy()[pos], ps_ref)
+    fwd = om.gmm_pseudo_forward(rip, rix, c4["x"], w_fc, ps_ref, mu, isg)
+    assert_close("out", out.cpu().numpy()[rows], fwd["out"][rows])
+    bwd = om.gmm_pseudo_backward(rip, rix, c4["x"], w_fc, ps_ref, mu, isg, gout, fwd)
+    assert_close("gpseudo", gps.cpu().numpy()[pos], bwd["gpseudo"])
+    print("full size monet: bilinearity", flush=True)
+    a = float((gx.double() * x.double()).sum())
+    b = float((gw.double() * dw.double()).sum())
+    o = float((dgo.double() * out.double()).sum())
+    assert abs(a - o) <= 1e-4 * abs(o) + 1e-2 and abs(b - o) <= 1e-4 * abs(o) + 1e-2, (a, b, o)
+    g.close()
