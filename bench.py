@@ -292,6 +292,10 @@ def main():
                          "(sums in fp32); outside the 1e-4 contract, reported as a variant only")
     ap.add_argument("--single-launch", action="store_true",
                     help="use the single-launch kernels also where the column-blocked ones apply")
+    ap.add_argument("--block-cols", type=int, default=None,
+                    help="gathered vertices per column block of the blocked edge lists (library default 20480)")
+    ap.add_argument("--no-merge-blocks", action="store_true",
+                    help="one launch per column block instead of merged launches over sparse blocks")
     ap.add_argument("--compare-unfused", action="store_true",
                     help="also time the one-operator-per-kernel comparator (GAT with heads*f = 256: forward and "
                          "backward graph operators; EdgeConv and GMM: forward)")
@@ -330,6 +334,10 @@ def main():
         pk.gnn_config_set("force_simple_kernels", 1)
     if args.gather_fp16:
         pk.gnn_config_set("gather_precision", 1)
+    if args.block_cols is not None:
+        pk.gnn_config_set("block_cols", args.block_cols)
+    if args.no_merge_blocks:
+        pk.gnn_config_set("merge_blocks", 0)
     t0 = time.perf_counter()
     g = pk.Graph(indptr, indices)
     torch.cuda.synchronize()

@@ -109,6 +109,20 @@ gnn_status_t gnn_graph_get_blocked(const gnn_graph_t* graph, int side, int32_t* 
                                    int32_t* block_cols /*host*/, int32_t* bptr, int32_t* bcol,
                                    void* stream);
 
+/* Launch groups of the column-blocked kernels.  Such a kernel reads and writes a row's running
+ * sums once per launch, which costs as much as gathering some ten to twenty neighbour rows; blocks
+ * in which a row has fewer edges than that are therefore walked several per launch (a row's
+ * segments of up to 8 adjacent blocks one after the other), at the price of a wider set of
+ * gathered rows competing for the L2.  gnn_graph_create picks the partition of the block sequence
+ * with the least modelled cost from the edge counts of the blocks, once for kernels that keep one
+ * running sum per row (`sums` = 1: the GCN sum, the GAT forward pass without stash) and once for
+ * those that keep two (`sums` = 2: the GAT forward pass with stash, the source side of its
+ * backward pass).  Group j covers the blocks groups[j] .. groups[j + 1] - 1; *count = number of
+ * groups (0 when the graph has no blocked lists), groups (HOST, num_blocks + 1 ints, may be NULL)
+ * receives count + 1 boundaries. */
+gnn_status_t gnn_graph_get_launch_groups(const gnn_graph_t* graph, int side, int sums,
+                                         int32_t* groups /*host*/, int32_t* count /*host*/);
+
 /* Plan tables and the temporaries of gnn_graph_create come from a free list inside the library
  * (blocks of up to 64 MB, at most 512 MB idle in total), so that graphs which are rebuilt all
  * the time (a k-nearest-neighbour graph per training step) do not pay hipMalloc / hipFree each
@@ -117,9 +131,14 @@ gnn_status_t gnn_graph_get_blocked(const gnn_graph_t* graph, int side, int32_t* 
 gnn_status_t gnn_release_cached_memory(void);
 
 /* Tuning knobs, read when a graph is created or a layer is called.  Keys:
- *   "block_cols"            gathered vertices per column block (default 24576:
- *                           24576 rows x one 128-byte slice per XCD = 3 MB of a
+ *   "block_cols"            gathered vertices per column block (default 20480:
+ *                           20480 rows x one 128-byte slice per XCD = 2.5 MB of a
  *                           4 MB L2); 0 disables blocking
+ *   "merge_blocks"          1 (default): adjacent column blocks with few edges share one
+ *                           launch of a column-blocked kernel (up to 8 blocks; a row's running
+ *                           sums are then read and written once for all of them), chosen per
+ *                           graph from the edge counts of the blocks.  0: one launch per block.
+ *                           Read by gnn_graph_create.
  *   "blocked_min_edges"     mean number of edges per (row, column block) from which the
  *                           column-blocked kernels are used (default 16; sparser graphs take
  *                           the single-launch kernels even when they span several blocks)

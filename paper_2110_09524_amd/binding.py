@@ -21,7 +21,7 @@ STATUS_NAMES = {0: "GNN_OK", 1: "GNN_ERR_INVALID_ARG", 2: "GNN_ERR_BAD_GRAPH",
 
 EXPORTS = [
     "gnn_last_error", "gnn_graph_create", "gnn_graph_destroy", "gnn_graph_get_csc",
-    "gnn_graph_get_buckets", "gnn_graph_get_blocked", "gnn_release_cached_memory", "gnn_config_set", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
+    "gnn_graph_get_buckets", "gnn_graph_get_blocked", "gnn_graph_get_launch_groups", "gnn_release_cached_memory", "gnn_config_set", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
     "gnn_gat_bwd", "gnn_gat_stash_alpha", "gnn_gat_bwd_stashed", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
     "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd", "gnn_gmm_tune",
     "gnn_gmmp_workspace_bytes", "gnn_gmmp_fwd", "gnn_gmmp_bwd", "gnn_pseudo_proj_workspace_bytes",
@@ -52,6 +52,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_graph_get_csc.argtypes = [vp, vp, vp, vp, vp]
     lib.gnn_graph_get_buckets.argtypes = [vp, i32, vp, vp, vp, vp]
     lib.gnn_graph_get_blocked.argtypes = [vp, i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), vp, vp, vp]
+    lib.gnn_graph_get_launch_groups.argtypes = [vp, i32, i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.gnn_config_set.argtypes = [C.c_char_p, i64]
     lib.gnn_release_cached_memory.argtypes = []
     lib.gnn_linear_fwd.argtypes = [i64, i32, i32, vp, vp, vp, vp]
@@ -196,6 +197,17 @@ class Graph:
         _check(lib().gnn_graph_get_blocked(self._h, side, C.byref(nb), C.byref(bc), _i(bptr), _i(bcol),
                                            _stream(stream)))
         return nb.value, bc.value, bptr, bcol
+
+    def launch_groups(self, side: int, sums: int):
+        """Block boundaries of the launches of a column-blocked kernel that keeps `sums` running sums
+        per row: group j covers blocks result[j] .. result[j + 1] - 1 ([] without blocked lists)."""
+        cnt = C.c_int32()
+        _check(lib().gnn_graph_get_launch_groups(self._h, side, sums, None, C.byref(cnt)))
+        if cnt.value == 0:
+            return []
+        buf = (C.c_int32 * (cnt.value + 1))()
+        _check(lib().gnn_graph_get_launch_groups(self._h, side, sums, buf, C.byref(cnt)))
+        return list(buf)
 
     def buckets(self, side: int, stream=None):
         b = torch.empty(self.n, dtype=torch.int32, device=self.device)

@@ -82,9 +82,12 @@ struct Workspace {
 };
 inline size_t ws_granule(size_t bytes) { return align_up(bytes, 256); }
 
+// most column blocks one launch of a blocked kernel covers
+constexpr int kMaxMerge = 8;
+
 // ---- tuning knobs (runtime.hip) -------------------------------------------------
 enum ConfigKey { kCfgBlockCols = 0, kCfgForceSimple = 1, kCfgLdsScalarTable = 2, kCfgGcnMapping = 3, kCfgGmmMapping = 4, kCfgBlockedMinEdges = 5,
-                 kCfgGatherPrecision = 6, kCfgCount };
+                 kCfgGatherPrecision = 6, kCfgMergeBlocks = 7, kCfgCount };
 int64_t config_get(ConfigKey k);
 
 // ---- dense products (gemm.hip) ------------------------------------------------
@@ -133,6 +136,11 @@ struct gnn_graph {
   int32_t* bcol[2];
   int32_t* bseg[2];  // (begin, end) of row order[r] in block b at [b*n + r], two ints each
   std::vector<int32_t> h_block_begin[2];  // host: first edge of block b (nblk + 1 entries)
+  // Launch groups of the column-blocked kernels: group j covers the blocks h_group[side][a][j] ..
+  // h_group[side][a][j + 1] - 1 in one launch (adjacent sparse blocks are merged, so that a row's
+  // running sums are read and written once for all of them); a = 0 for kernels that keep one
+  // running sum per row, 1 for those that keep two.
+  std::vector<int32_t> h_group[2][2];
   // The column-blocked kernels visit every row once per block; that pays only when a row has
   // enough edges inside a block (configuration key "blocked_min_edges", mean over rows and blocks).
   bool blocked_pays() const {

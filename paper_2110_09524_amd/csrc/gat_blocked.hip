@@ -70,6 +70,12 @@ static bool pick_slicing(int heads, int HF, Slicing& sl) {
 // the per-row scalars and the running sums of the next row are already in flight, so the
 // chain of dependent loads at the start of a row is paid once per group, not once per row.
 constexpr int kRowsPerGroup = 4;
+// LDS floats of one group: SL gathered indices, 2 * SL edge weights, the rows of its run and
+// their (begin, end) in each of the launch's blocks; a multiple of 4 keeps the 16-byte reads aligned
+template <int SL>
+constexpr int kBlkGroupFloats = 3 * SL + kRowsPerGroup + 2 * kRowsPerGroup * kMaxMerge;
+static_assert(kBlkGroupFloats<4> % 4 == 0 && kBlkGroupFloats<8> % 4 == 0 && kBlkGroupFloats<16> % 4 == 0 &&
+              kBlkGroupFloats<32> % 4 == 0, "group scratch must stay 16-byte aligned");
 
 template <int NA>
 struct BlkRow {
@@ -111,7 +117,9 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
     int32_t quads_per_grab, int ns /* column slices: 8, 4, 2 or 1 */,
     int last /* forward modes: this is the last block */,
     float4* __restrict__ state /* forward modes: running (max, sum, sum2) per (row, slice) */,
-    float* __restrict__ m_out, float* __restrict__ d_out) {
+    float* __restrict__ m_out, float* __restrict__ d_out,
+    int nseg /* adjacent column blocks of this launch (1 .. kMaxMerge): segment j of the row at
+                position r of the degree order is bseg_b[j * n_rows + r] */) {
   constexpr int THREADS = STAGE ? kStageThreads : kBlkThreads;
   constexpr int G = kWave / SL;
   constexpr int GPB = THREADS / SL;
@@ -125,7 +133,7 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
   // when the maximum grows, and the last block divides by the denominator.  No separate pass
   // over the edges is needed for the softmax statistics.
   constexpr bool ONLINE = MODE == 0 || MODE == 3;
-  constexpr int GS = 3 * SL + 4 * R;  // LDS floats per group: idx | p | p2 | row, beg, end, pad
+  constexpr int GS = kBlkGroupFloats<SL>;  // LDS floats per group: idx | p | p2 | rows | (beg, end) per row and block
   static_assert(SL >= R, "one lane per pipelined row loads its metadata");
   static_assert(!STAGE || MODE != 2, "the source side needs 16 bytes per gathered vertex");
   extern __shared__ __align__(16) float lds[];  // GPB * GS floats, then (STAGE) the el table
@@ -155,8 +163,7 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
   float* l_p = lds + grp * GS + SL;
   float* l_p2 = lds + grp * GS + 2 * SL;
   int* l_row = reinterpret_cast<int*>(lds + grp * GS + 3 * SL);
-  int* l_beg = l_row + R;
-  int* l_end = l_row + 2 * R;
+  int2* l_seg = reinterpret_cast<int2*>(l_row + R);  // [R][kMaxMerge]
 
   const int col = slice * CPL * SL + CPL * li;
   const bool leader = (slice % sph) == 0;  // one slice per head keeps the per-head scalars
@@ -175,23 +182,25 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
     if (li < R) {
       const int64_t r = r0 + li;
       int32_t row = -1;
-      int2 seg = make_int2(0, 0);
-      if (r < n_rows) {
-        row = order[r];
-        seg = bseg_b[r];
-        if (!first && seg.x == seg.y && !(ONLINE && last)) row = -1;  // nothing to add to this row in this block
+      bool any = false;
+      if (r < n_rows) row = order[r];
+      for (int j = 0; j < nseg; ++j) {
+        int2 seg = make_int2(0, 0);
+        if (r < n_rows) seg = bseg_b[(int64_t)j * n_rows + r];
+        any = any || seg.x != seg.y;
+        l_seg[li * kMaxMerge + j] = seg;
       }
+      if (!first && !any && !(ONLINE && last)) row = -1;  // nothing to add to this row in these blocks
       l_row[li] = row;
-      l_beg[li] = seg.x;
-      l_end[li] = seg.y;
     }
     wave_lds_fence();
 
     // issue every load a row needs before its edge loop
     auto fetch = [&](int k, BlkRow<NA>& s) {
       s.row = l_row[k];
-      s.beg = l_beg[k];
-      s.end = l_end[k];
+      const int2 seg0 = l_seg[k * kMaxMerge];
+      s.beg = seg0.x;
+      s.end = seg0.y;
       s.c_first = col_begin;
       s.r_a = 0.f; s.r_m = 0.f; s.r_d = 1.f; s.scal = 0.f;
 #pragma unroll
@@ -238,7 +247,6 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
     for (int k = 0; k < R; ++k) {
       if (k + 1 < R) fetch(k + 1, nxt);
       if (cur.row >= 0) {
-        const int32_t end = cur.end;
         const float r_a = cur.r_a, r_m = cur.r_m, r_invd = ONLINE ? 0.f : 1.f / cur.r_d;
         float4 acc[NA], acc2[NA];
 #pragma unroll
@@ -251,8 +259,18 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
         // (lane 0 carries what earlier blocks left) and are added across lanes at the end
         float m_run = cur.r_m;
         float d_lane = li == 0 ? cur.r_d : 0.f, s2_lane = li == 0 ? cur.scal : 0.f;
-        int32_t c_next = cur.c_first;
-        for (int32_t c0 = cur.beg; c0 < end; c0 += SL) {
+        int32_t beg = cur.beg, end = cur.end, c_next = cur.c_first;
+        for (int sgi = 0; sgi < nseg; ++sgi) {
+        // the bounds and the first indices of the row's segment in the next block are in
+        // flight while this one is processed
+        int32_t beg_n = 0, end_n = 0, c_first_n = col_begin;
+        if (sgi + 1 < nseg) {
+          const int2 sn = l_seg[k * kMaxMerge + sgi + 1];
+          beg_n = sn.x;
+          end_n = sn.y;
+          if (beg_n + li < end_n) c_first_n = bcol[beg_n + li];
+        }
+        for (int32_t c0 = beg; c0 < end; c0 += SL) {
           const bool e_ok = c0 + li < end;
           // gathered vertex of edge c0 + li; lanes past the end point at the block's first
           // vertex (a valid, cache-resident row) and get weight 0, so the row phase below
@@ -360,6 +378,10 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
           }
           wave_lds_fence();
         }
+        beg = beg_n;
+        end = end_n;
+        c_next = c_first_n;
+        }
         if (ONLINE) {
           const float d_tot = group_sum_from<SL>(d_lane, 1);
           const float s2_tot = MODE == 3 ? group_sum_from<SL>(s2_lane, 1) : 0.f;
@@ -463,8 +485,8 @@ __global__ void k_zero_i32(int n, int32_t* __restrict__ p) {
 
 // LDS bytes of the staged kernel: per-group scratch plus the block's table
 template <int SL>
-static size_t staged_lds_bytes(int32_t block_cols) {
-  constexpr int GS = 3 * SL + 4 * kRowsPerGroup;
+static size_t staged_lds_bytes(int64_t block_cols) {
+  constexpr int GS = kBlkGroupFloats<SL>;
   return sizeof(float) * ((size_t)(kStageThreads / SL) * GS + (size_t)block_cols);
 }
 constexpr size_t kStageLdsLimit = 152 * 1024;  // of the 160 KB a CU has
@@ -492,14 +514,13 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
   const int sph = ns / dm.H;
   // 32-bit byte offsets (and 24-bit multiplies) reach every gathered row
   const int narrow = (int64_t)g->n * dm.HF * 4 < ((int64_t)1 << 32) && g->n < (1 << 24);
-  constexpr int GS = 3 * SL + 4 * kRowsPerGroup;
+  constexpr int GS = kBlkGroupFloats<SL>;
   const int rows_per_wg = (kBlkThreads / SL) * kRowsPerGroup;
   const unsigned grid = (unsigned)(cdiv(g->n, rows_per_wg) * ns);
   const size_t lds = sizeof(float) * (size_t)(kBlkThreads / SL) * GS;
   bool stage_ok = false;
   if constexpr (MODE != 2) {
-    stage_ok = queue != nullptr && el_hm && staged_lds_bytes<SL>(g->block_cols) <= kStageLdsLimit &&
-               (int)g->h_block_begin[side].size() == g->nblk + 1;
+    stage_ok = queue != nullptr && el_hm && (int)g->h_block_begin[side].size() == g->nblk + 1;
     if (stage_ok) {
       // more than 64 KB of dynamic LDS needs the attribute; once per instantiation (the call is
       // idempotent, so a race between two first callers is harmless)
@@ -514,7 +535,12 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
       GNN_LAUNCH_CHECK();
     }
   }
-  for (int b = 0; b < g->nblk; ++b) {
+  const std::vector<int32_t>& groups = g->h_group[side][(MODE == 2 || MODE == 3) ? 1 : 0];
+  GNN_REQUIRE(groups.size() >= 2 && groups.front() == 0 && groups.back() == g->nblk, GNN_ERR_UNSUPPORTED,
+              "gat blocked: the plan has no launch groups");
+  for (size_t gi = 0; gi + 1 < groups.size(); ++gi) {
+    const int b = groups[gi], b_end = groups[gi + 1], nseg = b_end - b;
+    GNN_REQUIRE(nseg >= 1 && nseg <= kMaxMerge, GNN_ERR_UNSUPPORTED, "gat blocked: bad launch group");
     const int2* bseg_b = reinterpret_cast<const int2*>(g->bseg[side]) + (int64_t)b * g->n;
     const int32_t col_begin = b * g->block_cols;
     bool staged = false;
@@ -523,17 +549,19 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
       // block with 237 edges per row); with short rows the persistent launch has too few rows in
       // flight per CU to hide the chain of loads at the start of a row (2.1 ms instead of 1.6 ms
       // at 68 edges per row).
-      const int64_t edges = (int64_t)g->h_block_begin[side][b + 1] - g->h_block_begin[side][b];
-      staged = stage_ok && edges >= (int64_t)kStageMinEdgesPerRow * g->n;
+      const int64_t edges = (int64_t)g->h_block_begin[side][b_end] - g->h_block_begin[side][b];
+      const int64_t cols_wide = (int64_t)nseg * g->block_cols;
+      const size_t stage_bytes = staged_lds_bytes<SL>(cols_wide);
+      staged = stage_ok && stage_bytes <= kStageLdsLimit && edges >= (int64_t)kStageMinEdgesPerRow * g->n;
       if (staged) {
-        const int32_t cols_here = g->n - col_begin < g->block_cols ? g->n - col_begin : g->block_cols;
+        const int32_t cols_here = (int32_t)(g->n - col_begin < cols_wide ? g->n - col_begin : cols_wide);
         // one persistent workgroup per CU, a multiple of 8 so that every XCD serves one slice
         const unsigned pgrid = (unsigned)(device_cu_count() / kSlices * kSlices);
         ProfScope p(name, st);  // one timed bracket per launch
-        k_gat_blk<SL, MODE, true, HALF><<<pgrid, kStageThreads, staged_lds_bytes<SL>(g->block_cols), st>>>(
+        k_gat_blk<SL, MODE, true, HALF><<<pgrid, kStageThreads, stage_bytes, st>>>(
             g->n, g->order[side], bseg_b, g->bcol[side], feat, el, er, m, d, vstate, col_begin, dm, sph,
-            b == 0, narrow, el_hm, acc, acc2, scal, queue + b * kSlices, cols_here, 1, ns, b == g->nblk - 1, state,
-            m_out, d_out);
+            b == 0, narrow, el_hm, acc, acc2, scal, queue + b * kSlices, cols_here, 1, ns, b_end == g->nblk, state,
+            m_out, d_out, nseg);
         GNN_LAUNCH_CHECK();
       }
     }
@@ -541,7 +569,7 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
       ProfScope p(name, st);  // one timed bracket per launch
       k_gat_blk<SL, MODE, false, HALF><<<grid, kBlkThreads, lds, st>>>(
           g->n, g->order[side], bseg_b, g->bcol[side], feat, el, er, m, d, vstate, col_begin, dm, sph,
-          b == 0, narrow, el_hm, acc, acc2, scal, nullptr, 0, 1, ns, b == g->nblk - 1, state, m_out, d_out);
+          b == 0, narrow, el_hm, acc, acc2, scal, nullptr, 0, 1, ns, b_end == g->nblk, state, m_out, d_out, nseg);
       GNN_LAUNCH_CHECK();
     }
   }

@@ -212,11 +212,14 @@ template <int SL>
 __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
     int32_t n_rows, const int32_t* __restrict__ order, const int2* __restrict__ bseg_b,
     const int32_t* __restrict__ bcol, const float* __restrict__ feat, int32_t col_begin, int F,
-    int first, int ns /* column slices: 8, 4, 2 or 1 */, float* __restrict__ acc_buf) {
+    int first, int ns /* column slices: 8, 4, 2 or 1 */, float* __restrict__ acc_buf,
+    int nseg /* adjacent column blocks of this launch (1 .. kMaxMerge): segment j of the row at
+                position r of the degree order is bseg_b[j * n_rows + r] */) {
   constexpr int GPB = kGcnBlock / SL;
   constexpr int R = kGcnRows;
   constexpr int U = SL < 8 ? 4 : 8;
-  constexpr int GS = SL + 4 * R;  // LDS ints per group: idx | row, beg, end, pad
+  constexpr int GS = SL + R + 2 * R * kMaxMerge;  // LDS ints per group: idx | rows | (beg, end) per row and block
+  static_assert(GS % 4 == 0, "group scratch must stay 16-byte aligned");
   static_assert(SL >= R, "one lane per pipelined row loads its metadata");
   __shared__ __align__(16) int lds[GPB * GS];
   const int lane = threadIdx.x & 63;
@@ -227,22 +230,22 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
   if (r0 >= n_rows) return;
   int* l_idx = lds + grp * GS;
   int* l_row = l_idx + SL;
-  int* l_beg = l_row + R;
-  int* l_end = l_row + 2 * R;
+  int2* l_seg = reinterpret_cast<int2*>(l_row + R);  // [R][kMaxMerge]
   const int col = slice * 4 * SL + 4 * li;
 
   if (li < R) {
     const int64_t r = r0 + li;
     int32_t row = -1;
-    int2 seg = make_int2(0, 0);
-    if (r < n_rows) {
-      row = order[r];
-      seg = bseg_b[r];
-      if (!first && seg.x == seg.y) row = -1;  // nothing to add to this row in this block
+    bool any = false;
+    if (r < n_rows) row = order[r];
+    for (int j = 0; j < nseg; ++j) {
+      int2 seg = make_int2(0, 0);
+      if (r < n_rows) seg = bseg_b[(int64_t)j * n_rows + r];
+      any = any || seg.x != seg.y;
+      l_seg[li * kMaxMerge + j] = seg;
     }
+    if (!first && !any) row = -1;  // nothing to add to this row in these blocks
     l_row[li] = row;
-    l_beg[li] = seg.x;
-    l_end[li] = seg.y;
   }
   wave_lds_fence();
 
@@ -252,8 +255,9 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
   };
   auto fetch = [&](int k, Row& s) {
     s.row = l_row[k];
-    s.beg = l_beg[k];
-    s.end = l_end[k];
+    const int2 seg0 = l_seg[k * kMaxMerge];
+    s.beg = seg0.x;
+    s.end = seg0.y;
     s.c_first = col_begin;
     s.acc = make_float4(0.f, 0.f, 0.f, 0.f);
     if (s.row < 0) return;
@@ -266,10 +270,19 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
   for (int k = 0; k < R; ++k) {
     if (k + 1 < R) fetch(k + 1, nxt);
     if (cur.row >= 0) {
-      const int32_t end = cur.end;
       float4 acc = cur.acc;
-      int32_t c_next = cur.c_first;
-      for (int32_t c0 = cur.beg; c0 < end; c0 += SL) {
+      int32_t beg = cur.beg, end = cur.end, c_next = cur.c_first;
+      for (int sgi = 0; sgi < nseg; ++sgi) {
+      // the bounds and the first indices of the row's segment in the next block are in flight
+      // while this one is processed
+      int32_t beg_n = 0, end_n = 0, c_first_n = col_begin;
+      if (sgi + 1 < nseg) {
+        const int2 sn = l_seg[k * kMaxMerge + sgi + 1];
+        beg_n = sn.x;
+        end_n = sn.y;
+        if (beg_n + li < end_n) c_first_n = bcol[beg_n + li];
+      }
+      for (int32_t c0 = beg; c0 < end; c0 += SL) {
         // lanes past the end point at the block's first vertex (valid, cache-resident) and
         // their rows are multiplied by 0
         const int32_t c = c0 + li < end ? c_next : col_begin;
@@ -294,6 +307,10 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
         }
         add4(acc, part);
         wave_lds_fence();
+      }
+      beg = beg_n;
+      end = end_n;
+      c_next = c_first_n;
       }
       st4_stream(acc_buf + (int64_t)cur.row * F + col, acc);
     }
@@ -329,11 +346,16 @@ static gnn_status_t launch_rowsum_blocks(const gnn_graph_t* g, int side, const c
   const int rows_per_wg = (kGcnBlock / SL) * kGcnRows;
   const int ns = F / (4 * SL);
   const unsigned grid = (unsigned)(cdiv(g->n, rows_per_wg) * ns);
-  for (int b = 0; b < g->nblk; ++b) {
+  const std::vector<int32_t>& groups = g->h_group[side][0];
+  GNN_REQUIRE(groups.size() >= 2 && groups.front() == 0 && groups.back() == g->nblk, GNN_ERR_UNSUPPORTED,
+              "gcn blocked: the plan has no launch groups");
+  for (size_t gi = 0; gi + 1 < groups.size(); ++gi) {
+    const int b = groups[gi], nseg = groups[gi + 1] - b;
+    GNN_REQUIRE(nseg >= 1 && nseg <= kMaxMerge, GNN_ERR_UNSUPPORTED, "gcn blocked: bad launch group");
     const int2* bseg_b = reinterpret_cast<const int2*>(g->bseg[side]) + (int64_t)b * g->n;
     ProfScope p(name, st);  // one timed bracket per launch
     k_rowsum_blk<SL><<<grid, kGcnBlock, 0, st>>>(g->n, g->order[side], bseg_b, g->bcol[side], feat,
-                                                b * g->block_cols, F, b == 0, ns, acc);
+                                                b * g->block_cols, F, b == 0, ns, acc, nseg);
     GNN_LAUNCH_CHECK();
   }
   return GNN_OK;

@@ -1,6 +1,8 @@
 // Graph plan: device-side validation of the CSR arrays, the CSC transpose
 // (stable radix sort by source), and the degree order / degree buckets of both
 // sides.  Integer work only; every table is a pure function of the input.
+#include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <mutex>
 #include <unordered_map>
@@ -312,6 +314,46 @@ static void finish_side(gnn_graph* g, int side, const PlanStage* stage) {
 // Column-blocked copy of one side's edge list: edges stable-sorted by
 // (column / block_cols, row); bptr[b*n + r] .. bptr[b*n + r + 1] is the range of
 // row r inside block b.  Only built when the vertex set spans several blocks.
+
+// Launch groups of the column-blocked kernels.  One launch over w adjacent blocks costs, in units
+// of one gathered edge per row: a fixed part (the row's running sums are read and written once,
+// its segment bounds and scalars fetched) plus d * (1 + spill * log2(columns / 24576)) for its d
+// edges per row, because a wider set of gathered row slices no longer sits in the L2.  Measured
+// with the Reddit-scale GAT layer (1 KB rows, two running sums per row): 0.3 ms fixed against
+// 0.076 ms per million edges at 24576 columns, 0.099 at twice, 0.128 at four times that; with one
+// running sum the fixed part is half.  The partition of the block sequence with the least total
+// cost comes from a dynamic programme; it merges the sparse tail blocks of a power-law graph and
+// leaves dense blocks alone.
+static std::vector<int32_t> launch_groups(const std::vector<int32_t>& begin, int32_t n, int32_t block_cols,
+                                          bool merge, double kFixed) {
+  constexpr double kSpill = 0.32, kFitCols = 24576.0;
+  const int nb = (int)begin.size() - 1;
+  std::vector<int32_t> groups;
+  if (nb < 1) return groups;
+  if (!merge || n <= 0) {
+    for (int b = 0; b <= nb; ++b) groups.push_back(b);
+    return groups;
+  }
+  std::vector<double> best((size_t)nb + 1, 0.0);
+  std::vector<int> width((size_t)nb + 1, 1);
+  for (int e = 1; e <= nb; ++e) {
+    best[e] = -1.0;
+    for (int w = 1; w <= kMaxMerge && w <= e; ++w) {
+      const double d = (double)((int64_t)begin[e] - begin[e - w]) / (double)n;
+      const double over = std::log2((double)w * (double)block_cols / kFitCols);
+      const double c = best[e - w] + kFixed + d * (1.0 + kSpill * (over > 0.0 ? over : 0.0));
+      if (best[e] < 0.0 || c < best[e]) {
+        best[e] = c;
+        width[e] = w;
+      }
+    }
+  }
+  for (int e = nb; e > 0; e -= width[e]) groups.push_back(e);
+  groups.push_back(0);
+  std::reverse(groups.begin(), groups.end());
+  return groups;
+}
+
 static gnn_status_t build_blocked(gnn_graph* g, int side, const int32_t* ptr, const int32_t* cols,
                                   hipStream_t st) {
   const int32_t n = g->n;
@@ -362,6 +404,9 @@ static gnn_status_t build_blocked(gnn_graph* g, int side, const int32_t* ptr, co
   GNN_HIP(hipMemcpyAsync(g->h_block_begin[side].data(), starts, sizeof(int32_t) * ((size_t)g->nblk + 1),
                          hipMemcpyDeviceToHost, st));
   GNN_HIP(hipStreamSynchronize(st));
+  const bool merge = config_get(kCfgMergeBlocks) != 0;
+  g->h_group[side][0] = launch_groups(g->h_block_begin[side], n, g->block_cols, merge, 8.0);
+  g->h_group[side][1] = launch_groups(g->h_block_begin[side], n, g->block_cols, merge, 16.0);
   return GNN_OK;
 }
 
@@ -542,5 +587,18 @@ extern "C" gnn_status_t gnn_graph_get_blocked(const gnn_graph_t* g, int side, in
       GNN_HIP(hipMemcpyAsync(bcol, g->bcol[side], sizeof(int32_t) * (size_t)g->nnz,
                              hipMemcpyDeviceToDevice, st));
   }
+  return GNN_OK;
+}
+
+extern "C" gnn_status_t gnn_graph_get_launch_groups(const gnn_graph_t* g, int side, int sums,
+                                                    int32_t* groups, int32_t* count) {
+  clear_error();
+  GNN_REQUIRE(g != nullptr && count != nullptr, GNN_ERR_INVALID_ARG, "gnn_graph_get_launch_groups: null argument");
+  GNN_REQUIRE(side == 0 || side == 1, GNN_ERR_INVALID_ARG, "gnn_graph_get_launch_groups: side must be 0 or 1");
+  GNN_REQUIRE(sums == 1 || sums == 2, GNN_ERR_INVALID_ARG, "gnn_graph_get_launch_groups: sums must be 1 or 2");
+  const std::vector<int32_t>& v = g->h_group[side][sums - 1];
+  *count = v.empty() ? 0 : (int32_t)v.size() - 1;
+  if (groups)
+    for (size_t i = 0; i < v.size(); ++i) groups[i] = v[i];
   return GNN_OK;
 }

@@ -22,8 +22,9 @@ void clear_error() { g_err[0] = 0; }
 // ---- tuning knobs -------------------------------------------------------------
 // block_cols: gathered vertices per column block of the blocked edge lists.  A block
 // of 128-byte row slices (one slice per XCD) should sit in one XCD's 4 MB L2:
-// 24576 * 128 B = 3 MB (the measured optimum at the Reddit-scale workload; fewer,
-// larger blocks save accumulator read-modify-writes, more would spill the L2).
+// 20480 * 128 B = 2.5 MB (the measured optimum at the Reddit-scale workload once sparse
+// blocks share launches; wider blocks spill the L2, narrower ones pay the accumulator
+// read-modify-writes more often).
 // 0 disables blocking.
 // lds_scalar_table: 1 lets the blocked destination-side kernels keep a block's el table in LDS
 // gcn_mapping: thread mapping of the GCN aggregation, 0 vertex-balanced, 1 edge-balanced,
@@ -33,7 +34,9 @@ void clear_error() { g_err[0] = 0; }
 // used (below that the per-launch cost of visiting every row outweighs the cache residency;
 // break-even measured between 12 and 24 at 1 KB rows)
 // gather_precision: 0 the column-blocked GAT kernels gather fp32 rows, 1 they gather an fp16 copy
-static std::atomic<int64_t> g_config[kCfgCount] = {{24576}, {0}, {1}, {2}, {2}, {16}, {0}};
+// merge_blocks: 1 (default) adjacent sparse column blocks share one launch of a blocked kernel
+// (read at gnn_graph_create), 0 every block has its own launch
+static std::atomic<int64_t> g_config[kCfgCount] = {{20480}, {0}, {1}, {2}, {2}, {16}, {0}, {1}};
 int64_t config_get(ConfigKey k) { return g_config[k].load(std::memory_order_relaxed); }
 
 // ---- profiling ---------------------------------------------------------------
@@ -123,6 +126,10 @@ extern "C" gnn_status_t gnn_config_set(const char* key, int64_t value) {
   if (std::strcmp(key, "gather_precision") == 0) {
     GNN_REQUIRE(value == 0 || value == 1, GNN_ERR_INVALID_ARG, "gnn_config_set: gather_precision must be 0 or 1");
     g_config[kCfgGatherPrecision].store(value);
+    return GNN_OK;
+  }
+  if (std::strcmp(key, "merge_blocks") == 0) {
+    g_config[kCfgMergeBlocks].store(value != 0);
     return GNN_OK;
   }
   if (std::strcmp(key, "blocked_min_edges") == 0) {

@@ -177,12 +177,14 @@ def test_bad_arguments_raise():
                                             # 512-byte rows: four slices of 128 bytes; narrower rows
                                             # take the single-launch kernels on such graphs, too
                                             (256, 1, 128), (300, 4, 32), (256, 2, 64), (500, 1, 64)])
-def test_column_blocked_path(block_cols, H, F):
+@pytest.mark.parametrize("merge", [0, 1])
+def test_column_blocked_path(block_cols, H, F, merge):
     """The multi-launch, column-blocked kernels (used when the gathered matrix exceeds
-    the L2 caches) on a graph small enough for the oracle, with small blocks forced."""
+    the L2 caches) on a graph small enough for the oracle, with small blocks forced: one launch
+    per block, and launches that walk several sparse blocks per row."""
     import paper_2110_09524_amd as pk
     from gpu_harness import dev, run_gat
-    print(f"gat: blocked path block_cols={block_cols} H={H} F={F}", flush=True)
+    print(f"gat: blocked path block_cols={block_cols} H={H} F={F} merge={merge}", flush=True)
     if (H, F) == (4, 64):
         c = make("gat_c4_mid")
     else:
@@ -191,12 +193,18 @@ def test_column_blocked_path(block_cols, H, F):
         c = synth(rng, indptr, indices, 24, H, F)
     fwd, bwd = oracle_all(c)
     pk.gnn_config_set("block_cols", block_cols)
+    pk.gnn_config_set("merge_blocks", merge)
     try:
         g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
-        assert g.blocked(0)[0] == -(-c["n"] // block_cols)
+        nb = g.blocked(0)[0]
+        assert nb == -(-c["n"] // block_cols)
+        launches = len(g.launch_groups(0, 2)) - 1
+        print(f"  {nb} blocks in {launches} launches", flush=True)
+        assert launches == nb if not merge else 1 <= launches <= nb
         res = run_gat(c, graph=g)
     finally:
-        pk.gnn_config_set("block_cols", 24576)
+        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("merge_blocks", 1)
     compare(c, res, fwd, bwd)
     # same inputs through the single-launch kernels: both paths must agree with the oracle
     pk.gnn_config_set("force_simple_kernels", 1)
@@ -251,7 +259,7 @@ def test_blocked_path_with_the_score_table_in_lds(H, F):
             pk.gnn_config_set("lds_scalar_table", 1)
         g.close()
     finally:
-        pk.gnn_config_set("block_cols", 24576)
+        pk.gnn_config_set("block_cols", 20480)
     compare(c, res, fwd, bwd)
     compare(c, res_nostash, fwd, bwd)
     for k in res:
@@ -277,11 +285,11 @@ def test_large_score_range_is_stable(blocked):
     fwd, bwd = oracle_all(c)
     spread = float(np.abs(fwd["M1"]).max())
     assert spread > 100.0                                       # the case is what it claims to be
-    pk.gnn_config_set("block_cols", 128 if blocked else 24576)
+    pk.gnn_config_set("block_cols", 128 if blocked else 20480)
     try:
         res = run_gat(c)
     finally:
-        pk.gnn_config_set("block_cols", 24576)
+        pk.gnn_config_set("block_cols", 20480)
     grads = {k: res.pop(k) for k in ("gx", "gw", "ga_l", "ga_r")}
     compare(c, res, fwd, None)
     assert np.isfinite(res["out"]).all() and (res["d"] >= 1.0 - 1e-6).all()
@@ -323,7 +331,7 @@ def test_many_vertices_few_edges_on_the_blocked_path():
     c = synth(rng, indptr, indices, 6, 4, 32)
     fwd, bwd = oracle_all(c)
     g = pk.Graph(dev(indptr), dev(indices))
-    assert g.blocked(0)[0] == 3
+    assert g.blocked(0)[0] == -(-n // 20480)
     res = run_gat(c, graph=g)
     compare(c, res, fwd, bwd)
     assert (res["out"][n // 2:] == 0).all()
@@ -363,7 +371,7 @@ def test_fusion_with_stashing_arm_on_a_column_blocked_graph_and_bad_arguments():
         g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
         res = run_gat(c, graph=g, alpha_stash=True)      # forward blocked, stashed backward single-launch
     finally:
-        pk.gnn_config_set("block_cols", 24576)
+        pk.gnn_config_set("block_cols", 20480)
     res.pop("alpha_t")
     compare(c, res, fwd, bwd)
     a = empty((4, 4))
@@ -395,7 +403,7 @@ def test_sparse_graph_spanning_blocks_takes_the_single_launch_kernels():
             pk.gnn_prof_enable(False)
             g.close()
         finally:
-            pk.gnn_config_set("block_cols", 24576)
+            pk.gnn_config_set("block_cols", 20480)
             pk.gnn_config_set("blocked_min_edges", 0)
         return names
     assert "gat_head_major" not in kernels_used(16, 256)      # 6 blocks: 3.3 edges per (row, block)
@@ -429,7 +437,7 @@ def test_fp16_gather_storage(H, F):
             pk.gnn_config_set("gather_precision", 0)
         g.close()
     finally:
-        pk.gnn_config_set("block_cols", 24576)
+        pk.gnn_config_set("block_cols", 20480)
     compare(c, ref32, fwd, bwd)                       # the default path keeps the contract
 
     def rel(a, b):
@@ -465,7 +473,7 @@ def test_fp16_gather_storage_leaves_uncovered_shapes_in_fp32():
             pk.gnn_config_set("gather_precision", 0)
         g.close()
     finally:
-        pk.gnn_config_set("block_cols", 24576)
+        pk.gnn_config_set("block_cols", 20480)
     for k in a:
         assert np.array_equal(a[k], b[k]), k
     with pytest.raises(pk.GnnError):

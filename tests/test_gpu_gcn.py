@@ -69,21 +69,28 @@ def test_graph_without_edges():
 
 
 @pytest.mark.parametrize("block_cols,fout", [(256, 256), (500, 128), (300, 512), (128, 1024), (256, 64)])
-def test_column_blocked_path(block_cols, fout):
+@pytest.mark.parametrize("merge", [0, 1])
+def test_column_blocked_path(block_cols, fout, merge):
     import paper_2110_09524_amd as pk
     from gpu_harness import dev
-    print(f"gcn: blocked path block_cols={block_cols} fout={fout}", flush=True)
+    print(f"gcn: blocked path block_cols={block_cols} fout={fout} merge={merge}", flush=True)
     rng = np.random.default_rng(block_cols + fout)
     indptr, indices = random_graph(rng, 1500, 30000, self_loops=False, duplicates=True)
     c = synth(rng, indptr, indices, 24, fout)
     pk.gnn_config_set("block_cols", block_cols)
+    pk.gnn_config_set("merge_blocks", merge)
     try:
         g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
-        assert g.blocked(0)[0] == -(-c["n"] // block_cols)
+        nb = g.blocked(0)[0]
+        assert nb == -(-c["n"] // block_cols)
+        launches = len(g.launch_groups(0, 1)) - 1
+        print(f"  {nb} blocks in {launches} launches", flush=True)
+        assert launches == nb if not merge else 1 <= launches <= nb
         check(c, graph=g)
         g.close()
     finally:
-        pk.gnn_config_set("block_cols", 24576)
+        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("merge_blocks", 1)
 
 
 def test_bad_arguments_raise():
@@ -119,7 +126,7 @@ def test_many_vertices_few_edges_on_the_blocked_path():
     indptr = np.cumsum(indptr).astype(np.int32)
     c = synth(rng, indptr, src.astype(np.int32), 6, 128)
     g = pk.Graph(dev(indptr), dev(c["indices"]))
-    assert g.blocked(0)[0] == 3
+    assert g.blocked(0)[0] == -(-n // 20480)
     res = check(c, graph=g)
     assert (res["out"][n // 2:] == 0).all()
     g.close()

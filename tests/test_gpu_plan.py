@@ -82,7 +82,7 @@ def test_blocked_edge_lists(block_cols):
     try:
         g = pk.Graph(dev(indptr), dev(indices))
     finally:
-        pk.gnn_config_set("block_cols", 24576)
+        pk.gnn_config_set("block_cols", 20480)
     ip_t, ix_t, _ = (t.cpu().numpy() for t in g.csc())
     for side, ptr, cols in ((0, indptr, indices), (1, ip_t, ix_t)):
         nb, bc, bptr, bcol = g.blocked(side)
@@ -93,6 +93,81 @@ def test_blocked_edge_lists(block_cols):
     g.close()
     g = pk.Graph(dev(indptr), dev(indices))          # default block size: one block, no tables
     assert g.blocked(0)[0] == 1
+    g.close()
+
+
+def _group_cost(begin, n, block_cols, groups, fixed):
+    """Modelled cost of a partition of the block sequence into launches (units: one gathered edge per
+    row): per launch a fixed part plus its edges per row, dearer by 32 % per doubling of the gathered
+    columns beyond 24576."""
+    cost = 0.0
+    for a, b in zip(groups[:-1], groups[1:]):
+        d = (begin[b] - begin[a]) / n
+        over = max(0.0, np.log2((b - a) * block_cols / 24576.0))
+        cost += fixed + d * (1.0 + 0.32 * over)
+    return cost
+
+
+def _all_partitions(nb, max_width):
+    def rec(start):
+        if start == nb:
+            yield [nb]
+            return
+        for w in range(1, min(max_width, nb - start) + 1):
+            for rest in rec(start + w):
+                yield [start] + rest
+    return rec(0)
+
+
+def test_launch_groups_merge_the_sparse_tail_and_keep_dense_blocks_alone():
+    """A graph whose first column block holds 150 edges per row and whose other two hold one each:
+    the launches of a column-blocked kernel are the dense block alone and the tail merged.  On a
+    small graph with ten narrow blocks the library's choice is the cheapest of all partitions under
+    the cost model it documents; without merging every block has its own launch."""
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev
+    print("plan: launch groups", flush=True)
+    rng = np.random.default_rng(12)
+    n, bc = 60000, 20480
+    cols = np.concatenate([rng.integers(0, bc, size=(n, 150)), rng.integers(bc, 2 * bc, size=(n, 1)),
+                           rng.integers(2 * bc, n, size=(n, 1))], axis=1)
+    indices = np.sort(cols, axis=1).astype(np.int32).ravel()
+    indptr = (np.arange(n + 1, dtype=np.int64) * cols.shape[1]).astype(np.int32)
+    g = pk.Graph(dev(indptr), dev(indices))
+    assert g.blocked(0)[:2] == (3, bc)
+    assert g.launch_groups(0, 1) == [0, 1, 3] == g.launch_groups(0, 2)
+    g.close()
+
+    n, bc = 3000, 300
+    cols = np.concatenate([rng.integers(0, bc, size=(n, 40))] +
+                          [rng.integers(b * bc, (b + 1) * bc, size=(n, int(k))) for b, k in
+                           zip(range(1, n // bc), rng.integers(0, 12, size=n // bc))], axis=1)
+    indices = np.sort(cols, axis=1).astype(np.int32).ravel()
+    indptr = (np.arange(n + 1, dtype=np.int64) * cols.shape[1]).astype(np.int32)
+    pk.gnn_config_set("block_cols", bc)
+    try:
+        g = pk.Graph(dev(indptr), dev(indices))
+        pk.gnn_config_set("merge_blocks", 0)
+        g_plain = pk.Graph(dev(indptr), dev(indices))
+    finally:
+        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("merge_blocks", 1)
+    nb = g.blocked(0)[0]
+    assert nb == 10
+    assert g_plain.launch_groups(0, 1) == list(range(nb + 1)) == g_plain.launch_groups(1, 2)
+    begin = np.zeros(nb + 1, dtype=np.int64)
+    np.add.at(begin, indices // bc + 1, 1)
+    begin = np.cumsum(begin)
+    for sums, fixed in ((1, 8.0), (2, 16.0)):
+        groups = g.launch_groups(0, sums)
+        assert groups[0] == 0 and groups[-1] == nb and all(0 < b - a <= 8 for a, b in zip(groups[:-1], groups[1:]))
+        assert len(groups) < nb + 1, groups
+        best = min(_group_cost(begin, n, bc, p, fixed) for p in _all_partitions(nb, 8))
+        assert abs(_group_cost(begin, n, bc, groups, fixed) - best) <= 1e-9 * best, groups
+    g.close()
+    g_plain.close()
+    g = pk.Graph(dev(indptr), dev(indices))          # one block: no groups
+    assert g.launch_groups(0, 1) == []
     g.close()
 
 
