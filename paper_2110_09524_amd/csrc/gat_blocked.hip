@@ -490,7 +490,7 @@ static size_t staged_lds_bytes(int64_t block_cols) {
   return sizeof(float) * ((size_t)(kStageThreads / SL) * GS + (size_t)block_cols);
 }
 constexpr size_t kStageLdsLimit = 152 * 1024;  // of the 160 KB a CU has
-constexpr int kStageMinEdgesPerRow = 128;       // mean edges per row of a block worth staging
+constexpr int kStageMinEdgesPerRow = 48;        // mean edges per row of a block worth staging
 
 static int query_cu_count() {
   int dev = 0, v = 0;
@@ -545,10 +545,9 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
     const int32_t col_begin = b * g->block_cols;
     bool staged = false;
     if constexpr (MODE != 2) {
-      // The LDS table pays on blocks whose rows are long (measured: 3.2 ms instead of 3.8 ms on a
-      // block with 237 edges per row); with short rows the persistent launch has too few rows in
-      // flight per CU to hide the chain of loads at the start of a row (2.1 ms instead of 1.6 ms
-      // at 68 edges per row).
+      // The LDS table pays on blocks whose rows are long (measured with 20480 columns: 2.7 ms
+      // instead of 3.5 ms at 220 edges per row, 1.28 instead of 1.43 ms at 67, no difference at
+      // 42); the persistent launch has a higher fixed cost, which sparser blocks do not repay.
       const int64_t edges = (int64_t)g->h_block_begin[side][b_end] - g->h_block_begin[side][b];
       const int64_t cols_wide = (int64_t)nseg * g->block_cols;
       const size_t stage_bytes = staged_lds_bytes<SL>(cols_wide);
