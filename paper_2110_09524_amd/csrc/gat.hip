@@ -1046,10 +1046,9 @@ extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, in
   // The column-blocked kernels need scratch (a head-major copy of el, row counters, and the
   // running softmax statistics, which borrow the dz area the backward call uses later: 128 of
   // its >= 512 bytes per vertex); without a workspace the single-launch kernels run.
-  // Forward takes the column-blocked kernels from 1 KB rows on; at 512 bytes the single-launch
-  // forward kernel measured faster at Reddit scale (8.4 vs 9.1 ms) while the source-side backward
-  // kernel is faster blocked (9.6 vs 11.0 ms), so the two calls decide separately.
-  if (gat_blocked_applies(g, heads, f) && have_ws && HF >= 256) {
+  // Rows of 512 bytes and more take them (two 256-byte slices at 512 bytes; measured at Reddit
+  // scale, 1 x 128: 7.9 ms against 8.5 ms for the single-launch forward kernel).
+  if (gat_blocked_applies(g, heads, f) && have_ws && HF >= 128) {
     char* base = static_cast<char*>(ws);
     return gat_blocked_fwd(g, make_dims(heads, f, slope), z, el, er, m, d, out, t, sg,
                            reinterpret_cast<float*>(base + L.blk_elt),

@@ -319,11 +319,12 @@ static void finish_side(gnn_graph* g, int side, const PlanStage* stage) {
 // of one gathered edge per row: a fixed part (the row's running sums are read and written once,
 // its segment bounds and scalars fetched) plus d * (1 + spill * log2(columns / 24576)) for its d
 // edges per row, because a wider set of gathered row slices no longer sits in the L2.  Measured
-// with the Reddit-scale GAT layer (1 KB rows, two running sums per row): 0.3 ms fixed against
-// 0.076 ms per million edges at 24576 columns, 0.099 at twice, 0.128 at four times that; with one
-// running sum the fixed part is half.  The partition of the block sequence with the least total
-// cost comes from a dynamic programme; it merges the sparse tail blocks of a power-law graph and
-// leaves dense blocks alone.
+// with the Reddit-scale GAT layer (1 KB rows): the per-edge part grows from 0.076 ms per million
+// edges at 24576 columns to 0.099 at twice and 0.128 at four times that; the fixed part that
+// gives the fastest partition is worth 8 to 12 gathered rows per row for kernels with two running
+// sums (of 4, 8, 12, 16, 24 tried), about half of that with one.  The partition of the block
+// sequence with the least total cost comes from a dynamic programme; it merges the sparse tail
+// blocks of a power-law graph and leaves dense blocks alone.
 static std::vector<int32_t> launch_groups(const std::vector<int32_t>& begin, int32_t n, int32_t block_cols,
                                           bool merge, double kFixed) {
   constexpr double kSpill = 0.32, kFitCols = 24576.0;
@@ -405,8 +406,8 @@ static gnn_status_t build_blocked(gnn_graph* g, int side, const int32_t* ptr, co
                          hipMemcpyDeviceToHost, st));
   GNN_HIP(hipStreamSynchronize(st));
   const bool merge = config_get(kCfgMergeBlocks) != 0;
-  g->h_group[side][0] = launch_groups(g->h_block_begin[side], n, g->block_cols, merge, 8.0);
-  g->h_group[side][1] = launch_groups(g->h_block_begin[side], n, g->block_cols, merge, 16.0);
+  g->h_group[side][0] = launch_groups(g->h_block_begin[side], n, g->block_cols, merge, 6.0);
+  g->h_group[side][1] = launch_groups(g->h_block_begin[side], n, g->block_cols, merge, 10.0);
   return GNN_OK;
 }
 

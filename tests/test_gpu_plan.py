@@ -158,7 +158,7 @@ def test_launch_groups_merge_the_sparse_tail_and_keep_dense_blocks_alone():
     begin = np.zeros(nb + 1, dtype=np.int64)
     np.add.at(begin, indices // bc + 1, 1)
     begin = np.cumsum(begin)
-    for sums, fixed in ((1, 8.0), (2, 16.0)):
+    for sums, fixed in ((1, 6.0), (2, 10.0)):
         groups = g.launch_groups(0, sums)
         assert groups[0] == 0 and groups[-1] == nb and all(0 < b - a <= 8 for a, b in zip(groups[:-1], groups[1:]))
         assert len(groups) < nb + 1, groups
