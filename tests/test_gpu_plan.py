@@ -168,6 +168,10 @@ def test_launch_groups_merge_the_sparse_tail_and_keep_dense_blocks_alone():
     g_plain.close()
     g = pk.Graph(dev(indptr), dev(indices))          # one block: no groups
     assert g.launch_groups(0, 1) == []
+    for side, sums in ((2, 1), (0, 3), (0, 0)):
+        with pytest.raises(pk.GnnError) as e:
+            g.launch_groups(side, sums)
+        assert e.value.status == 1
     g.close()
 
 
