@@ -283,7 +283,6 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
         }
         for (int32_t c0 = beg; c0 < end; c0 += SL) {
           const bool e_ok = c0 + li < end;
-          const int cnt = min(SL, end - c0);  // valid edges of this chunk (uniform in the group)
           // gathered vertex of edge c0 + li; lanes past the end point at the block's first
           // vertex (a valid, cache-resident row) and get weight 0, so the row phase below
           // needs no per-edge conditionals
@@ -314,25 +313,16 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
               const int4 i4 = *reinterpret_cast<const int4*>(l_idx + t0 + 4 * q);
               idv[4 * q] = i4.x; idv[4 * q + 1] = i4.y; idv[4 * q + 2] = i4.z; idv[4 * q + 3] = i4.w;
             }
-            // Quadruples of gathered rows that lie entirely past the end of the segment are
-            // skipped: a padded load costs the texture path as much as a real one, and the
-            // sparse blocks' segments are mostly shorter than a chunk.
             uint4 rowv[U];  // 16 bytes of the gathered row: 4 floats, or 8 halves
+            if (narrow) {
 #pragma unroll
-            for (int t4 = 0; t4 < U; t4 += 4) {
-              if (t0 + t4 < cnt) {
-                if (narrow) {
+              for (int t = 0; t < U; ++t)
+                rowv[t] = *reinterpret_cast<const uint4*>(
+                    feat_bytes + (__umul24((uint32_t)idv[t], row_bytes) + col_bytes));
+            } else {
 #pragma unroll
-                  for (int t = t4; t < t4 + 4; ++t)
-                    rowv[t] = *reinterpret_cast<const uint4*>(
-                        feat_bytes + (__umul24((uint32_t)idv[t], row_bytes) + col_bytes));
-                } else {
-#pragma unroll
-                  for (int t = t4; t < t4 + 4; ++t)
-                    rowv[t] = *reinterpret_cast<const uint4*>(feat_bytes +
-                                                              ((int64_t)idv[t] * row_bytes + col_bytes));
-                }
-              }
+              for (int t = 0; t < U; ++t)
+                rowv[t] = *reinterpret_cast<const uint4*>(feat_bytes + ((int64_t)idv[t] * row_bytes + col_bytes));
             }
             if (t0 == 0) {
               float p = 0.f, p2 = 0.f;
@@ -375,20 +365,15 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
               }
             }
 #pragma unroll
-            for (int t4 = 0; t4 < U; t4 += 4) {
-              if (t0 + t4 < cnt) {
-#pragma unroll
-                for (int t = t4; t < t4 + 4; ++t) {
-                  if constexpr (HALF) {
-                    fma8_half(part, pv[t], rowv[t]);
-                    if (DUAL) fma8_half(part2, pv2[t], rowv[t]);
-                  } else {
-                    const float4 rv = make_float4(__uint_as_float(rowv[t].x), __uint_as_float(rowv[t].y),
-                                                  __uint_as_float(rowv[t].z), __uint_as_float(rowv[t].w));
-                    fma4(part[0], pv[t], rv);
-                    if (DUAL) fma4(part2[0], pv2[t], rv);
-                  }
-                }
+            for (int t = 0; t < U; ++t) {
+              if constexpr (HALF) {
+                fma8_half(part, pv[t], rowv[t]);
+                if (DUAL) fma8_half(part2, pv2[t], rowv[t]);
+              } else {
+                const float4 rv = make_float4(__uint_as_float(rowv[t].x), __uint_as_float(rowv[t].y),
+                                              __uint_as_float(rowv[t].z), __uint_as_float(rowv[t].w));
+                fma4(part[0], pv[t], rv);
+                if (DUAL) fma4(part2[0], pv2[t], rv);
               }
             }
           }

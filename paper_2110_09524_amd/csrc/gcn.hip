@@ -284,9 +284,7 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
       }
       for (int32_t c0 = beg; c0 < end; c0 += SL) {
         // lanes past the end point at the block's first vertex (valid, cache-resident) and
-        // their rows are multiplied by 0; quadruples of gathered rows that lie entirely past
-        // the end are skipped (a load the texture path never sees costs nothing, a padded one
-        // costs as much as a real one)
+        // their rows are multiplied by 0
         const int32_t c = c0 + li < end ? c_next : col_begin;
         if (c0 + SL + li < end) c_next = bcol[c0 + SL + li];
         l_idx[li] = c;
@@ -303,17 +301,9 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
           }
           float4 rowv[U];
 #pragma unroll
-          for (int t4 = 0; t4 < U; t4 += 4)
-            if (t0 + t4 < cnt) {
+          for (int t = 0; t < U; ++t) rowv[t] = ld4(feat + (int64_t)idv[t] * F + col);
 #pragma unroll
-              for (int t = t4; t < t4 + 4; ++t) rowv[t] = ld4(feat + (int64_t)idv[t] * F + col);
-            }
-#pragma unroll
-          for (int t4 = 0; t4 < U; t4 += 4)
-            if (t0 + t4 < cnt) {
-#pragma unroll
-              for (int t = t4; t < t4 + 4; ++t) fma4(part, t0 + t < cnt ? 1.f : 0.f, rowv[t]);
-            }
+          for (int t = 0; t < U; ++t) fma4(part, t0 + t < cnt ? 1.f : 0.f, rowv[t]);
         }
         add4(acc, part);
         wave_lds_fence();
