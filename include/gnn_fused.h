@@ -149,6 +149,9 @@ gnn_status_t gnn_release_cached_memory(void);
  *                           the worst gradient entries) instead of the 1e-4 contract.  Set it before workspace sizes are
  *                           queried; shapes it does not cover (heads*f % 64 != 0, a 64-column
  *                           slice spanning heads) stay fp32.
+ *   "wide_offsets"          1: the column-blocked GAT kernels address the gathered rows with 64-bit
+ *                           offsets also where 32 bits reach every row (the code path of gathered
+ *                           matrices of 4 GB and more; meant for tests).  Default 0.
  *   "force_simple_kernels"  1: always use the single-launch kernels
  *   "lds_scalar_table"      1 (default): the column-blocked destination-side GAT kernels
  *                           keep a block's per-vertex score table in LDS (one persistent

@@ -87,7 +87,7 @@ constexpr int kMaxMerge = 8;
 
 // ---- tuning knobs (runtime.hip) -------------------------------------------------
 enum ConfigKey { kCfgBlockCols = 0, kCfgForceSimple = 1, kCfgLdsScalarTable = 2, kCfgGcnMapping = 3, kCfgGmmMapping = 4, kCfgBlockedMinEdges = 5,
-                 kCfgGatherPrecision = 6, kCfgMergeBlocks = 7, kCfgCount };
+                 kCfgGatherPrecision = 6, kCfgMergeBlocks = 7, kCfgWideOffsets = 8, kCfgCount };
 int64_t config_get(ConfigKey k);
 
 // ---- dense products (gemm.hip) ------------------------------------------------

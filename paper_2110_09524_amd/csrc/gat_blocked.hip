@@ -542,7 +542,8 @@ static gnn_status_t launch_blocks_impl(const gnn_graph_t* g, int side, const cha
   const int ns = dm.HF / ((HALF ? 8 : 4) * SL);
   const int sph = ns / dm.H;
   // 32-bit byte offsets (and 24-bit multiplies) reach every gathered row
-  const int narrow = (int64_t)g->n * dm.HF * 4 < ((int64_t)1 << 32) && g->n < (1 << 24);
+  const int narrow = (int64_t)g->n * dm.HF * 4 < ((int64_t)1 << 32) && g->n < (1 << 24) &&
+                     !config_get(kCfgWideOffsets);
   constexpr int GS = kBlkGroupFloats<SL>;
   const int rows_per_wg = (kBlkThreads / SL) * kRowsPerGroup;
   const unsigned grid = (unsigned)(cdiv(g->n, rows_per_wg) * ns);

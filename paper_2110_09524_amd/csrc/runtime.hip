@@ -36,7 +36,9 @@ void clear_error() { g_err[0] = 0; }
 // gather_precision: 0 the column-blocked GAT kernels gather fp32 rows, 1 they gather an fp16 copy
 // merge_blocks: 1 (default) adjacent sparse column blocks share one launch of a blocked kernel
 // (read at gnn_graph_create), 0 every block has its own launch
-static std::atomic<int64_t> g_config[kCfgCount] = {{20480}, {0}, {1}, {2}, {2}, {16}, {0}, {1}};
+// wide_offsets: 1 makes the column-blocked GAT kernels address gathered rows with 64-bit offsets
+// also where 32 bits reach every row (the path of matrices of 4 GB and more; a test hook)
+static std::atomic<int64_t> g_config[kCfgCount] = {{20480}, {0}, {1}, {2}, {2}, {16}, {0}, {1}, {0}};
 int64_t config_get(ConfigKey k) { return g_config[k].load(std::memory_order_relaxed); }
 
 // ---- profiling ---------------------------------------------------------------
@@ -126,6 +128,10 @@ extern "C" gnn_status_t gnn_config_set(const char* key, int64_t value) {
   if (std::strcmp(key, "gather_precision") == 0) {
     GNN_REQUIRE(value == 0 || value == 1, GNN_ERR_INVALID_ARG, "gnn_config_set: gather_precision must be 0 or 1");
     g_config[kCfgGatherPrecision].store(value);
+    return GNN_OK;
+  }
+  if (std::strcmp(key, "wide_offsets") == 0) {
+    g_config[kCfgWideOffsets].store(value != 0);
     return GNN_OK;
   }
   if (std::strcmp(key, "merge_blocks") == 0) {

@@ -478,3 +478,27 @@ def test_fp16_gather_storage_leaves_uncovered_shapes_in_fp32():
         assert np.array_equal(a[k], b[k]), k
     with pytest.raises(pk.GnnError):
         pk.gnn_config_set("gather_precision", 2)
+
+
+@pytest.mark.parametrize("H,F", [(4, 64), (1, 128)])
+def test_column_blocked_path_with_64_bit_row_offsets(H, F):
+    """Gathered matrices of 4 GB and more are addressed with 64-bit offsets; the configuration key
+    "wide_offsets" takes that path on a graph small enough for the oracle."""
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev, run_gat
+    print(f"gat: blocked path, 64-bit row offsets H={H} F={F}", flush=True)
+    rng = np.random.default_rng(77 + H)
+    indptr, indices = random_graph(rng, 1500, 30000, self_loops=False, duplicates=True)
+    c = synth(rng, indptr, indices, 24, H, F)
+    fwd, bwd = oracle_all(c)
+    pk.gnn_config_set("block_cols", 300)
+    pk.gnn_config_set("wide_offsets", 1)
+    try:
+        g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
+        res = run_gat(c, graph=g)
+        g.close()
+    finally:
+        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("wide_offsets", 0)
+    compare(c, res, fwd, bwd)
+
