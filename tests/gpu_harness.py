@@ -1,5 +1,7 @@
 """Runs the HIP library through its C ABI (via the ctypes binding) on workloads
 given as numpy arrays, and returns numpy arrays.  Used by the `gpu` tests only."""
+import os
+
 import numpy as np
 import torch
 
@@ -30,19 +32,38 @@ def workspace(nbytes):
     return torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
 
 
+# Every comparison leaves one record here: how many entries miss the literal bound
+# ATOL + RTOL * |oracle| (no scaling of the absolute term) and by what factor at worst.
+# tests/conftest.py writes the records to gpurun_out/tolerance_report.jsonl at the end of a run.
+LITERAL_LOG = []
+
+
+def _log_literal(name, err, ref, scaled, rtol, atol):
+    lit = ATOL + RTOL * np.abs(ref)
+    ratio = err / lit
+    miss = ratio > 1.0
+    LITERAL_LOG.append(dict(
+        test=os.environ.get("PYTEST_CURRENT_TEST", "").split(" ")[0], tensor=name, entries=int(err.size),
+        scaled_bound=bool(scaled), widened=bool(rtol != RTOL or atol != ATOL),
+        literal_misses=int(miss.sum()), worst_ratio=float(ratio.max()) if err.size else 0.0,
+        rms_ref=float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0))
+
+
 def assert_close(name, got, ref, rtol=RTOL, atol=ATOL, reduce_scale=False, row_scale=False):
-    """Element-wise |got - ref| <= atol_eff + rtol |ref|.
+    """Element-wise |got - ref| <= atol_eff + rtol |ref|; atol_eff = atol (the literal bound) unless:
 
-    row_scale=True is for the input gradient gx = dz w^T: every entry of row u is a dot
-    product with the same vector dz[u], whose fp32 rounding (inherited from the fp32
-    projection z and the scores built on it) is proportional to |dz[u]|, not to the
-    possibly cancelled entry, so the absolute term scales with the row's largest
-    entry: atol_eff[u] = atol * max(1, max_j |ref[u, j]|).
+    reduce_scale=True, for the gradients that are matrix products or sums over ALL vertices or
+    edges with terms of both signs (gw, gw_fc, gtheta, gphi, ga_l, ga_r): fp32 rounding there is
+    proportional to the partial sums, not to the (possibly cancelled) entry, so the absolute term
+    scales with the tensor's rms value: atol_eff = atol * max(1, rms(ref)).
 
-    reduce_scale=True is for gradients of shared parameters, each entry a sum over
-    all |V| vertices (or |E| edges): fp32 rounding there is proportional to the
-    magnitude of the partial sums, not to the (possibly cancelled) result, so the
-    absolute term scales with the tensor's rms value: atol_eff = atol * max(1, rms(ref)).
+    row_scale=True, for unnormalised sums over the ~10^4 in-edges of a hub row, and for the
+    gradients of the deliberately ill-conditioned large-score case: atol_eff[u] = atol *
+    max(1, max_j |ref[u, j]|).
+
+    tests/test_fp32_summation_bounds.py shows on the CPU that a plain fp32 evaluation in the
+    oracle's own order misses the literal bound in exactly these cases, by the same factors.
+    Every comparison is also logged against the literal bound (LITERAL_LOG).
     """
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
@@ -55,6 +76,7 @@ def assert_close(name, got, ref, rtol=RTOL, atol=ATOL, reduce_scale=False, row_s
         a = atol * np.maximum(1.0, np.abs(ref).max(axis=1, keepdims=True))
     err = np.abs(got - ref)
     tol = a + rtol * np.abs(ref)
+    _log_literal(name, err, ref, reduce_scale or row_scale, rtol, atol)
     bad = err > tol
     if bad.any():
         i = np.unravel_index(np.argmax(err - tol), err.shape)
@@ -72,6 +94,14 @@ def gat_kink_masks(indptr, fwd, tol=1e-5):
     Returns (amb_vh [n, heads] bool, amb_vertex [n] bool)."""
     amb_e = np.abs(fwd["M0"]) < tol
     n = indptr.shape[0] - 1
+    # The exclusion must stay an exception.  Scores of order 1 land within 1e-5 of zero at a rate
+    # of about 1e-5, so: at most one score in 10^4, and at most 1 % of the vertices masked; on
+    # small dense test graphs (a few hundred vertices, 10^5 .. 10^6 scores) up to 10 % of the rows.
+    n_amb = int(amb_e.sum())
+    assert n_amb <= max(4, amb_e.size // 10_000), f"{n_amb} of {amb_e.size} scores sit on the LeakyReLU kink"
+    rows_masked = 2 * int(amb_e.any(axis=1).sum())
+    assert rows_masked <= max(4, n // 100 if n >= 5000 else n // 10), \
+        f"{rows_masked} of {n} rows would be masked: the mask would hide the test"
     amb_vh = np.zeros((n, amb_e.shape[1]), dtype=bool)
     amb_vertex = np.zeros(n, dtype=bool)
     if amb_e.any():

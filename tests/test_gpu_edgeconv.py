@@ -37,7 +37,7 @@ def check(c):
         e = arg[v, j]
         assert ip[v] <= e < ip[v + 1]
         assert fwd["E_TP"][e, j] >= fwd["out"][v, j] - TIE_TOL
-    assert_close("gx", res["gx"], bwd["gx"], row_scale=True)
+    assert_close("gx", res["gx"], bwd["gx"])
     assert_close("gtheta", res["gtheta"], bwd["gtheta"], reduce_scale=True)
     assert_close("gphi", res["gphi"], bwd["gphi"], reduce_scale=True)
     return int(amb.sum())
