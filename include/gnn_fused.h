@@ -223,6 +223,23 @@ gnn_status_t gnn_gat_bwd(const gnn_graph_t* graph, int fin, int heads, int f, fl
                          float* gx /*nullable*/, float* gw, float* ga_l, float* ga_r,
                          void* ws, size_t ws_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): gnn_gat_bwd with its scratch in a
+ * device array built into the library, GNN_NOALLOC_SCRATCH_BYTES long (every GPU the library runs
+ * on holds its copy until the process ends).  Same arguments, kernels and results as gnn_gat_bwd
+ * minus (ws, ws_bytes); calls no hipMalloc/hipFree.  Fails with GNN_ERR_WORKSPACE and a message
+ * naming both sizes when gnn_gat_workspace_bytes(graph, fin, heads, f) exceeds the array.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams or threads) race and must be serialised by the caller.  Nothing the array holds is
+ * expected to survive from one call to the next. */
+#define GNN_NOALLOC_SCRATCH_BYTES (64u << 20)
+gnn_status_t gnn_gat_bwd_noalloc(const gnn_graph_t* graph, int fin, int heads, int f, float slope,
+                                 const float* x, const float* w, const float* a_l, const float* a_r,
+                                 const float* z, const float* el, const float* er, const float* m,
+                                 const float* d, const float* out, const float* t /*nullable*/,
+                                 const float* sg /*nullable*/, const float* gout /*[n,heads*f]*/,
+                                 float* gx /*nullable*/, float* gw, float* ga_l, float* ga_r, void* stream);
+
 /* The "fusion with stashing" arm of the recomputation study (Sec. 7.3): the fused kernels, but
  * the per-edge softmax values are stored after the forward pass and read back in the
  * backward pass instead of being recomputed.  Kept for that comparison; it needs O(|E|)

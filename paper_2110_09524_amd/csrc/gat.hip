@@ -19,6 +19,8 @@
 #include "common.h"
 #include <hip/hip_fp16.h>
 
+#include <mutex>
+
 #include "gat_common.h"
 #include "rowgroup.h"
 
@@ -1068,6 +1070,56 @@ extern "C" gnn_status_t gnn_gat_bwd(const gnn_graph_t* g, int fin, int heads, in
                                     void* ws, size_t ws_bytes, void* stream) {
   return gat_bwd_impl("gnn_gat_bwd", g, fin, heads, f, slope, x, w, a_l, a_r, z, el, er, m, d, out, t, sg,
                       nullptr, gout, gx, gw, ga_l, ga_r, ws, ws_bytes, stream);
+}
+
+// ---- backward call for callers that cannot allocate ---------------------------------
+// The scratch of gnn_gat_bwd (dz, the destination-side table, der, del, the partial sums of
+// the parameter gradients) lives in a device array of the library's code object instead of a
+// caller-provided workspace.  In host code the array's name is only a handle for the runtime:
+// its device address is looked up once per device and that pointer is what reaches the kernels.
+static __device__ __align__(256) unsigned char scratch[GNN_NOALLOC_SCRATCH_BYTES];
+
+namespace gnn {
+constexpr int kMaxScratchDevices = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxScratchDevices];  // per device, null until looked up
+
+static gnn_status_t noalloc_scratch(void** out) {
+  int dev = -1;
+  GNN_HIP(hipGetDevice(&dev));
+  GNN_REQUIRE(dev >= 0 && dev < kMaxScratchDevices, GNN_ERR_UNSUPPORTED,
+              "gnn_gat_bwd_noalloc: device index %d out of range", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    GNN_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));  // this device's copy of the array
+    GNN_REQUIRE(p != nullptr, GNN_ERR_HIP, "gnn_gat_bwd_noalloc: no device address for the scratch array");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return GNN_OK;
+}
+}  // namespace gnn
+
+extern "C" gnn_status_t gnn_gat_bwd_noalloc(const gnn_graph_t* g, int fin, int heads, int f, float slope,
+                                            const float* x, const float* w, const float* a_l,
+                                            const float* a_r, const float* z, const float* el,
+                                            const float* er, const float* m, const float* d, const float* out,
+                                            const float* t, const float* sg, const float* gout, float* gx,
+                                            float* gw, float* ga_l, float* ga_r, void* stream) {
+  clear_error();
+  GNN_TRY(check_gat_dims(g, fin, heads, f, "gnn_gat_bwd_noalloc"));
+  const size_t need = gat_ws_layout(g, fin, heads, f).total;
+  GNN_REQUIRE(need <= (size_t)GNN_NOALLOC_SCRATCH_BYTES, GNN_ERR_WORKSPACE,
+              "gnn_gat_bwd_noalloc: this graph and these widths need %zu bytes of scratch, the built-in "
+              "array holds %zu; use gnn_gat_bwd with a workspace", need, (size_t)GNN_NOALLOC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  GNN_TRY(noalloc_scratch(&ws));
+  // Every kernel of the backward pass writes its part of the scratch before reading it (the row
+  // counters of the column-blocked kernels are reset by a fill kernel), so what an earlier call
+  // left behind is never read.
+  return gat_bwd_impl("gnn_gat_bwd_noalloc", g, fin, heads, f, slope, x, w, a_l, a_r, z, el, er, m, d, out, t, sg,
+                      nullptr, gout, gx, gw, ga_l, ga_r, ws, (size_t)GNN_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 extern "C" gnn_status_t gnn_gat_stash_alpha(const gnn_graph_t* g, int heads, float slope, const float* el,
