@@ -692,7 +692,7 @@ static GatWs gat_ws_layout(const gnn_graph_t* g, int fin, int H, int F) {
   w.gemm = take(w.split_k > 1 ? sizeof(float) * (size_t)w.split_k * fin * HF : 0);
   const bool blocked = gat_blocked_applies(g, H, F);
   w.blk_rows = take(blocked ? sizeof(float) * n * HF : 0);  // T, then A2
-  w.blk_scal = take(blocked ? sizeof(float) * n * H : 0);   // sg, then sd
+  w.blk_scal = take(blocked ? sizeof(float) * n * 8 : 0);   // sg, then the slices' shares of del
   w.blk_elt = take(blocked ? sizeof(float) * n * H : 0);    // head-major el
   w.blk_queue = take(blocked ? sizeof(int32_t) * 8 * (size_t)g->nblk : 0);  // row counters of the staged kernels
   // a narrow projection of a mid-sized graph has too few output tiles to fill the chip: split K
@@ -1207,10 +1207,8 @@ static gnn_status_t gat_bwd_impl(const char* who, const gnn_graph_t* g, int fin,
     GNN_TRY(dispatch_group<BwdDstLauncher>(gs, g, z, el, er, m, d, out, gout, dm, der, vstate, st));
   }
   if (blocked) {
-    float* rows_buf = reinterpret_cast<float*>(base + L.blk_rows);
     float* scal_buf = reinterpret_cast<float*>(base + L.blk_scal);
-    GNN_TRY(gat_blocked_bwd_src(g, dm, z, el, vstate, der, gout, a_l, a_r, dz, del, rows_buf,
-                                scal_buf, gat_blocked_half(g, heads, f) ? base + L.blk_half : nullptr, st));
+    GNN_TRY(gat_blocked_bwd_src(g, dm, z, el, vstate, der, gout, a_l, a_r, dz, del, scal_buf, gat_blocked_half(g, heads, f) ? base + L.blk_half : nullptr, st));
   } else {
     // a5: source side
     GNN_TRY(dispatch_group<BwdSrcLauncher>(gs, g, z, el, (const float4*)vstate, (const float*)der,

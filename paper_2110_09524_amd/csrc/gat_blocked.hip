@@ -19,6 +19,10 @@
 // which also yields m and d (Sec. 6: exactly the O(|V|) state that is saved).
 // All per-edge values are still recomputed on the fly; nothing per-edge is stored.
 #include <atomic>
+#include <cstdlib>
+#include <map>
+#include <mutex>
+#include <string>
 
 #include <hip/hip_fp16.h>
 
@@ -71,7 +75,11 @@ static bool pick_slicing(int heads, int HF, Slicing& sl) {
 // MODE 0: forward        acc[v]  += sum_e alpha_e           z[u]      (acc = out)
 // MODE 1: bwd, dst side  acc[v]  += sum_e alpha_e g_e       z[u]      (acc = T), sg += sum alpha g
 // MODE 2: bwd, src side  acc[u]  += sum_e alpha_e           gout[v]   (acc = dz)
-//                        acc2[u] += sum_e alpha_e g_e       gout[v]   (acc2 = A2), sd += sum alpha g D[v]
+//                        scal[u, slice] += sum_e alpha_e g_e (<z[u], gout[v]>_slice - [leader] D[v])
+//                        The dot product is taken lane by lane: a lane multiplies its four columns
+//                        of the gathered row with its four columns of z[u] (kept in registers for
+//                        the whole row) and adds alpha g times that to a per-lane sum; the lanes are
+//                        added once per row.  The slices of a head add up to del[u, h].
 // MODE 3: forward that also stashes the destination-side sums of the backward pass:
 //                        acc = out as MODE 0, acc2[v] += sum_e alpha_e g_e z[u] (= t), sg += sum alpha g
 // A group of SL lanes owns (row, slice); lane li owns the float4 at column slice*4*SL + 4*li.
@@ -107,6 +115,13 @@ __device__ __forceinline__ void fma8_half(float4 (&acc)[2], float w, const uint4
   acc[1].z = fmaf(w, d.x, acc[1].z); acc[1].w = fmaf(w, d.y, acc[1].w);
 }
 
+__device__ __forceinline__ float dot8_half(const float4 (&zr)[2], const uint4& r) {
+  const __half2* h = reinterpret_cast<const __half2*>(&r);
+  const float2 a = __half22float2(h[0]), b = __half22float2(h[1]), c = __half22float2(h[2]),
+               d = __half22float2(h[3]);
+  return dot4(zr[0], make_float4(a.x, a.y, b.x, b.y)) + dot4(zr[1], make_float4(c.x, c.y, d.x, d.y));
+}
+
 // STAGE: the per-edge scalar el[u] of the slice's head is read from an LDS copy of the block's
 // part of the head-major table instead of being gathered from L2.  Such a scalar gather
 // costs a CU one 128-byte line fill per edge, as much as the 128-byte row slice itself; with
@@ -120,6 +135,7 @@ template <int SL, int MODE, bool STAGE, bool HALF, bool SKIP>
 __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk(
     int32_t n_rows, const int32_t* __restrict__ order, const int2* __restrict__ bseg_b,
     const int32_t* __restrict__ bcol, const float* __restrict__ feat /* gathered rows: z or gout */,
+    const float* __restrict__ rowfeat /* MODE 2: z, whose row u meets every gathered gout[v] */,
     const float* __restrict__ el, const float* __restrict__ er, const float* __restrict__ m_in,
     const float* __restrict__ d_in, const float4* __restrict__ vstate, int32_t col_begin,
     GatDims dm, int sph, int first, int narrow, int el_hm /* el is head-major [H][n] */,
@@ -136,7 +152,8 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
   constexpr int GPB = THREADS / SL;
   constexpr int R = kRowsPerGroup;
   constexpr int U = SL < 8 ? 4 : 8;   // gathered rows in flight per lane
-  constexpr bool DUAL = MODE == 2 || MODE == 3;  // two accumulators per lane
+  constexpr bool DUAL = MODE == 3;  // two vector accumulators per lane
+  constexpr bool SRC = MODE == 2;   // one vector accumulator, the row's own z in registers, a per-lane dot sum
   constexpr int CPL = HALF ? 8 : 4;              // columns per lane
   constexpr int NA = CPL / 4;                    // float4 accumulators per lane and sum
   // The forward modes run the edge-softmax online across the block launches: every (row, slice)
@@ -243,7 +260,12 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
           s.acc[a] = ld4_stream(acc_buf + (int64_t)s.row * HF + col + 4 * a);
           if (DUAL) s.acc2[a] = ld4_stream(acc2_buf + (int64_t)s.row * HF + col + 4 * a);
         }
-        if (!ONLINE && MODE != 0 && leader && li == 0) s.scal = scal_buf[rh];
+        if (MODE == 1 && leader && li == 0) s.scal = scal_buf[rh];
+        if (SRC && li == 0) s.scal = scal_buf[(int64_t)s.row * kSlices + slice];
+      }
+      if (SRC) {
+#pragma unroll
+        for (int a = 0; a < NA; ++a) s.acc2[a] = ld4_stream(rowfeat + (int64_t)s.row * HF + col + 4 * a);
       }
     };
 
@@ -265,7 +287,8 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
           acc[a] = cur.acc[a];
           acc2[a] = cur.acc2[a];
         }
-        float s_run = 0.f;
+        float s_run = 0.f;  // chunk-phase lanes: sum of alpha g (MODE 1), of alpha g D[v] (MODE 2)
+        float s_dot = 0.f;  // MODE 2, row-phase lanes: sum of alpha g <z[u], gout[v]> over the lane's columns
         // online state: the running maximum is uniform in the group, the sums are per lane
         // (lane 0 carries what earlier blocks left) and are added across lanes at the end
         float m_run = cur.r_m;
@@ -304,6 +327,7 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
             part[a] = make_float4(0.f, 0.f, 0.f, 0.f);
             part2[a] = part[a];
           }
+          float dpart = 0.f;
           float sc = 1.f;  // ONLINE: factor that brings the running sums to this chunk's maximum
 #pragma unroll
           for (int t0 = 0; t0 < SL; t0 += U) {
@@ -364,7 +388,7 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
                 m_run = m_new;
               }
               l_p[li] = p;
-              if (DUAL) l_p2[li] = p2;
+              if (DUAL || SRC) l_p2[li] = p2;
               wave_lds_fence();
             }
             float pv[U], pv2[U];
@@ -372,7 +396,7 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
             for (int q = 0; q < U / 4; ++q) {
               const float4 p4 = *reinterpret_cast<const float4*>(l_p + t0 + 4 * q);
               pv[4 * q] = p4.x; pv[4 * q + 1] = p4.y; pv[4 * q + 2] = p4.z; pv[4 * q + 3] = p4.w;
-              if (DUAL) {
+              if (DUAL || SRC) {
                 const float4 q4 = *reinterpret_cast<const float4*>(l_p2 + t0 + 4 * q);
                 pv2[4 * q] = q4.x; pv2[4 * q + 1] = q4.y; pv2[4 * q + 2] = q4.z; pv2[4 * q + 3] = q4.w;
               }
@@ -385,11 +409,13 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
                   if constexpr (HALF) {
                     fma8_half(part, pv[t], rowv[t]);
                     if (DUAL) fma8_half(part2, pv2[t], rowv[t]);
+                    if constexpr (SRC && NA == 2) dpart = fmaf(pv2[t], dot8_half(acc2, rowv[t]), dpart);
                   } else {
                     const float4 rv = make_float4(__uint_as_float(rowv[t].x), __uint_as_float(rowv[t].y),
                                                   __uint_as_float(rowv[t].z), __uint_as_float(rowv[t].w));
                     fma4(part[0], pv[t], rv);
                     if (DUAL) fma4(part2[0], pv2[t], rv);
+                    if (SRC) dpart = fmaf(pv2[t], dot4(acc2[0], rv), dpart);
                   }
                 }
               }
@@ -405,6 +431,7 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
               if (DUAL) add4(acc2[a], part2[a]);
             }
           }
+          if (SRC) s_dot += dpart;
           wave_lds_fence();
         }
         beg = beg_n;
@@ -437,9 +464,14 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
           st4_stream(acc_buf + (int64_t)cur.row * HF + col + 4 * a, acc[a]);
           if (DUAL) st4_stream(acc2_buf + (int64_t)cur.row * HF + col + 4 * a, acc2[a]);
         }
-        if (!ONLINE && MODE != 0 && leader) {
+        if (MODE == 1 && leader) {
           const float tot = group_sum_from<SL>(s_run, 1);
           if (li == 0) scal_buf[(int64_t)cur.row * H + h] = cur.scal + tot;
+        }
+        if (SRC) {
+          // this slice's share of del[u, h]; the D term is counted by one slice per head
+          const float tot = group_sum_from<SL>(s_dot - (leader ? s_run : 0.f), 1);
+          if (li == 0) scal_buf[(int64_t)cur.row * kSlices + slice] = cur.scal + tot;
         }
       }
       cur = nxt;
@@ -504,7 +536,8 @@ bool gat_blocked_applies(const gnn_graph_t* g, int heads, int f) {
 size_t gat_blocked_ws_bytes(const gnn_graph_t* g, int heads, int f) {
   if (!gat_blocked_applies(g, heads, f)) return 0;
   return ws_granule(sizeof(float) * (size_t)g->n * heads * f) +   // T, then A2
-         2 * ws_granule(sizeof(float) * (size_t)g->n * heads);    // sg, then sd; head-major el
+         ws_granule(sizeof(float) * (size_t)g->n * kSlices) +     // sg, then the slices' shares of del
+         ws_granule(sizeof(float) * (size_t)g->n * heads);        // head-major el
 }
 
 __global__ void k_zero_i32(int n, int32_t* __restrict__ p) {
@@ -533,9 +566,21 @@ static int device_cu_count() {
   return cus;
 }
 
+// Name of a launch's timed bracket: the kernel's name, or "name#i" for the i-th launch of a pass
+// when the environment variable GNN_PROF_PER_LAUNCH is set (for tuning the launch groups).
+static const char* bracket_name(const char* name, size_t launch) {
+  static const bool per_launch = std::getenv("GNN_PROF_PER_LAUNCH") != nullptr;
+  if (!per_launch) return name;
+  static std::mutex mu;
+  static std::map<std::string, std::string> names;  // node addresses are stable
+  std::lock_guard<std::mutex> lock(mu);
+  std::string key = std::string(name) + "#" + std::to_string(launch);
+  return names.emplace(key, key).first->second.c_str();
+}
+
 template <int SL, int MODE, bool HALF, bool SKIP>
 static gnn_status_t launch_blocks_impl(const gnn_graph_t* g, int side, const char* name, GatDims dm,
-                                  int el_hm, const float* feat,
+                                  int el_hm, const float* feat, const float* rowfeat,
                                   const float* el, const float* er, const float* m, const float* d,
                                   const float4* vstate, float* acc, float* acc2, float* scal,
                                   int32_t* queue, float4* state, float* m_out, float* d_out, hipStream_t st) {
@@ -586,18 +631,18 @@ static gnn_status_t launch_blocks_impl(const gnn_graph_t* g, int side, const cha
         const int32_t cols_here = (int32_t)(g->n - col_begin < cols_wide ? g->n - col_begin : cols_wide);
         // one persistent workgroup per CU, a multiple of 8 so that every XCD serves one slice
         const unsigned pgrid = (unsigned)(device_cu_count() / kSlices * kSlices);
-        ProfScope p(name, st);  // one timed bracket per launch
+        ProfScope p(bracket_name(name, gi), st);  // one timed bracket per launch
         k_gat_blk<SL, MODE, true, HALF, SKIP><<<pgrid, kStageThreads, stage_bytes, st>>>(
-            g->n, g->order[side], bseg_b, g->bcol[side], feat, el, er, m, d, vstate, col_begin, dm, sph,
+            g->n, g->order[side], bseg_b, g->bcol[side], feat, rowfeat, el, er, m, d, vstate, col_begin, dm, sph,
             b == 0, narrow, el_hm, acc, acc2, scal, queue + b * kSlices, cols_here, 1, ns, b_end == g->nblk, state,
             m_out, d_out, nseg);
         GNN_LAUNCH_CHECK();
       }
     }
     if (!staged) {
-      ProfScope p(name, st);  // one timed bracket per launch
+      ProfScope p(bracket_name(name, gi), st);  // one timed bracket per launch
       k_gat_blk<SL, MODE, false, HALF, SKIP><<<grid, kBlkThreads, lds, st>>>(
-          g->n, g->order[side], bseg_b, g->bcol[side], feat, el, er, m, d, vstate, col_begin, dm, sph,
+          g->n, g->order[side], bseg_b, g->bcol[side], feat, rowfeat, el, er, m, d, vstate, col_begin, dm, sph,
           b == 0, narrow, el_hm, acc, acc2, scal, nullptr, 0, 1, ns, b_end == g->nblk, state, m_out, d_out, nseg);
       GNN_LAUNCH_CHECK();
     }
@@ -607,37 +652,37 @@ static gnn_status_t launch_blocks_impl(const gnn_graph_t* g, int side, const cha
 
 template <int SL, int MODE, bool HALF = false>
 static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* name, GatDims dm,
-                                  int el_hm, const float* feat,
+                                  int el_hm, const float* feat, const float* rowfeat,
                                   const float* el, const float* er, const float* m, const float* d,
                                   const float4* vstate, float* acc, float* acc2, float* scal,
                                   int32_t* queue, float4* state, float* m_out, float* d_out, hipStream_t st) {
   const int ns = dm.HF / ((HALF ? 8 : 4) * SL);
   // the fp16 variant (one sub-iteration per chunk) measured 3 % slower with the skip
   if (ns >= 4 && !HALF)
-    return launch_blocks_impl<SL, MODE, HALF, true>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2,
+    return launch_blocks_impl<SL, MODE, HALF, true>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2,
                                                     scal, queue, state, m_out, d_out, st);
-  return launch_blocks_impl<SL, MODE, HALF, false>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2,
+  return launch_blocks_impl<SL, MODE, HALF, false>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2,
                                                    scal, queue, state, m_out, d_out, st);
 }
 
 template <int MODE>
 static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name, GatDims dm,
-                               int el_hm, const float* feat, const float* el, const float* er, const float* m,
+                               int el_hm, const float* feat, const float* rowfeat, const float* el, const float* er, const float* m,
                                const float* d, const float4* vstate, float* acc, float* acc2,
                                float* scal, int32_t* queue, float4* state, float* m_out, float* d_out,
                                hipStream_t st, bool half_feat = false) {
   if (half_feat) {
     if constexpr (MODE != 1)
-      return launch_blocks<8, MODE, true>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal,
+      return launch_blocks<8, MODE, true>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal,
                                           queue, state, m_out, d_out, st);
   }
   Slicing sl;
   if (!pick_slicing(dm.H, dm.HF, sl)) sl.SL = 0;
   switch (sl.SL) {
-    case 4: return launch_blocks<4, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
-    case 8: return launch_blocks<8, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
-    case 16: return launch_blocks<16, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
-    case 32: return launch_blocks<32, MODE>(g, side, name, dm, el_hm, feat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
+    case 4: return launch_blocks<4, MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
+    case 8: return launch_blocks<8, MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
+    case 16: return launch_blocks<16, MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
+    case 32: return launch_blocks<32, MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
   }
   set_error("gat blocked: unsupported slice width");
   return GNN_ERR_UNSUPPORTED;
@@ -657,9 +702,9 @@ gnn_status_t gat_blocked_fwd(const gnn_graph_t* g, GatDims dm, const float* z, c
     feat = static_cast<const float*>(half_buf);
   }
   if (t)
-    return run_blocks<3>(g, 0, "gat_fwd_fused", dm, hm, feat, el_use, er, nullptr, nullptr, nullptr, out, t, sg,
+    return run_blocks<3>(g, 0, "gat_fwd_fused", dm, hm, feat, nullptr, el_use, er, nullptr, nullptr, nullptr, out, t, sg,
                          queue, state, m, d, st, half);
-  return run_blocks<0>(g, 0, "gat_fwd_fused", dm, hm, feat, el_use, er, nullptr, nullptr, nullptr, out, nullptr,
+  return run_blocks<0>(g, 0, "gat_fwd_fused", dm, hm, feat, nullptr, el_use, er, nullptr, nullptr, nullptr, out, nullptr,
                        nullptr, queue, state, m, d, st, half);
 }
 
@@ -669,25 +714,55 @@ gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* 
                                  float* sg_buf, float* el_t, int32_t* queue, hipStream_t st) {
   if (el_t) GNN_TRY(head_major(g, dm.H, el, el_t, st));
   if (!config_get(kCfgLdsScalarTable)) queue = nullptr;
-  GNN_TRY(run_blocks<1>(g, 0, "gat_bwd_dst", dm, el_t != nullptr, z, el_t ? el_t : el, er, m, d, nullptr,
+  GNN_TRY(run_blocks<1>(g, 0, "gat_bwd_dst", dm, el_t != nullptr, z, nullptr, el_t ? el_t : el, er, m, d, nullptr,
                         t_buf, nullptr, sg_buf, queue, nullptr, nullptr, nullptr, st));
   return gat_dst_finish(g, dm, gout, t_buf, out, sg_buf, er, m, d,
                         kDstHeadMajor | (gat_blocked_half(g, dm.H, dm.F) ? kDstHalfGout : 0), der, vstate, st);
 }
 
+// dz[u,h,:] += a_l[h,:] del[u,h] + a_r[h,:] der[u,h], with del[u,h] = the sum of the shares its
+// slices left in sd ([n][8], slice-major inside a vertex); one thread per float4 of dz
+__global__ void k_gat_src_finish_blk(int64_t n, GatDims dm, int ns, const float* __restrict__ sd,
+                                     const float* __restrict__ der, const float* __restrict__ a_l,
+                                     const float* __restrict__ a_r, float* __restrict__ dz,
+                                     float* __restrict__ del) {
+  const int qpr = dm.HF / 4;  // float4 per row
+  const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i >= n * qpr) return;
+  const int64_t u = i / qpr;
+  const int col = 4 * (int)(i - u * qpr);
+  const int h = col / dm.F, sph = ns / dm.H;
+  float dl = 0.f;
+  for (int s = 0; s < sph; ++s) dl += sd[u * kSlices + h * sph + s];  // fixed order
+  if (col == h * dm.F) del[u * dm.H + h] = dl;
+  float4 o = ld4(dz + u * dm.HF + col);
+  fma4(o, dl, ld4(a_l + col));
+  fma4(o, der[u * dm.H + h], ld4(a_r + col));
+  st4(dz + u * dm.HF + col, o);
+}
+
 gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                                  const float4* vstate, const float* der, const float* gout,
                                  const float* a_l, const float* a_r, float* dz, float* del,
-                                 float* a2_buf, float* sd_buf, void* half_buf, hipStream_t st) {
+                                 float* sd_buf /* [n][8] scratch */, void* half_buf, hipStream_t st) {
   const bool half = half_buf != nullptr && gat_blocked_half(g, dm.H, dm.F);
   const float* feat = gout;
   if (half) {
     GNN_TRY(to_half(g, dm.HF, gout, half_buf, st));
     feat = static_cast<const float*>(half_buf);
   }
-  GNN_TRY(run_blocks<2>(g, 1, "gat_bwd_src", dm, 0, feat, el, nullptr, nullptr, nullptr, vstate, dz,
-                        a2_buf, sd_buf, nullptr, nullptr, nullptr, nullptr, st, half));
-  return gat_src_finish(g, dm, z, a2_buf, sd_buf, der, a_l, a_r, dz, del, st);
+  GNN_TRY(run_blocks<2>(g, 1, "gat_bwd_src", dm, 0, feat, z, el, nullptr, nullptr, nullptr, vstate, dz,
+                        nullptr, sd_buf, nullptr, nullptr, nullptr, nullptr, st, half));
+  Slicing sl;
+  int ns = 0;
+  if (half) ns = dm.HF / 64;
+  else if (pick_slicing(dm.H, dm.HF, sl)) ns = sl.ns;
+  GNN_REQUIRE(ns >= dm.H && ns % dm.H == 0 && ns <= kSlices, GNN_ERR_UNSUPPORTED, "gat blocked: bad slicing");
+  ProfScope p("gat_bwd_src_finish", st);
+  const int64_t quads = (int64_t)g->n * (dm.HF / 4);
+  k_gat_src_finish_blk<<<(unsigned)cdiv(quads, 256), 256, 0, st>>>(g->n, dm, ns, sd_buf, der, a_l, a_r, dz, del);
+  GNN_LAUNCH_CHECK();
+  return GNN_OK;
 }
 
 }  // namespace gnn

@@ -55,11 +55,11 @@ gnn_status_t gat_blocked_bwd_dst(const gnn_graph_t* g, GatDims dm, const float* 
                                  const float* gout, float* der, float4* vstate, float* t_buf,
                                  float* sg_buf, float* el_t /* [H][n] scratch or null */,
                                  int32_t* queue /* nblk * 8 row counters or null */, hipStream_t st);
-// writes dz, del; a2_buf is an [n, HF] scratch, sd_buf an [n, H] scratch
+// writes dz, del; sd_buf is an [n, 8] scratch (per-slice shares of del)
 gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                                  const float4* vstate, const float* der, const float* gout,
                                  const float* a_l, const float* a_r, float* dz, float* del,
-                                 float* a2_buf, float* sd_buf,
-                                 void* half_buf /* n * HF * 2 bytes or null */, hipStream_t st);
+                                 float* sd_buf, void* half_buf /* n * HF * 2 bytes or null */,
+                                 hipStream_t st);
 
 }  // namespace gnn
