@@ -99,6 +99,12 @@ gnn_status_t gemm_f32(int64_t M, int N, int64_t K, const float* a, int64_t lda, 
                       const float* b, int64_t ldb, bool b_kcontig, float* c, int64_t ldc,
                       int split_k, float* partials, hipStream_t s);
 int gemm_pick_split_k(int64_t M, int N, int64_t K);
+// z[M, heads*f] = x[M, K] w[K, heads*f] with the attention halves el = <a_l, z>, er = <a_r, z> ([M, heads])
+// taken from the accumulators; gemm_attn_epilogue_ok says for which head widths this exists
+bool gemm_attn_epilogue_ok(int heads, int f);
+gnn_status_t gemm_f32_attn(int64_t M, int heads, int f, int64_t K, const float* x, const float* w,
+                           const float* a_l, const float* a_r, float* z, float* el, float* er,
+                           hipStream_t s);
 // out[i] = sum over z < parts of partials[z*count + i], in a fixed order (reproducible)
 gnn_status_t sum_partials(int64_t count, int parts, const float* partials, float* out, hipStream_t s);
 constexpr int kSumChunk = 64;

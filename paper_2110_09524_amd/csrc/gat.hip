@@ -1032,14 +1032,19 @@ extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, in
   // a1: projection before propagation (split over K when the workspace offers room for the parts)
   const GatWs L = gat_ws_layout(g, fin, heads, f);
   const bool have_ws = ws != nullptr && ws_bytes >= L.total && aligned16(ws);
+  bool halves_done = false;
   if (have_ws && L.fwd_split_k > 1) {
     GNN_TRY(gemm_f32(n, HF, fin, x, fin, false, w, HF, false, z, HF, L.fwd_split_k,
                      reinterpret_cast<float*>(static_cast<char*>(ws) + L.fwd_gemm), st));
+  } else if (gemm_attn_epilogue_ok(heads, f) && fin < (1 << 24)) {
+    // a1 + a2: the attention halves come out of the projection's accumulators
+    GNN_TRY(gemm_f32_attn(n, heads, f, fin, x, w, a_l, a_r, z, el, er, st));
+    halves_done = true;
   } else {
     GNN_TRY(gemm_f32(n, HF, fin, x, fin, false, w, HF, false, z, HF, 1, nullptr, st));
   }
-  // a2: attention halves
-  {
+  // a2: attention halves (shapes the epilogue does not cover, and split-K projections)
+  if (!halves_done) {
     ProfScope p("gat_attn_halves", st);
     k_gat_attn_halves<<<(unsigned)cdiv(n * heads, 256), 256, 0, st>>>(n, heads, f, z, a_l, a_r, el, er);
     GNN_LAUNCH_CHECK();

@@ -20,11 +20,44 @@ constexpr int BK = 16;
 constexpr int GEMM_THREADS = 256;
 constexpr int LDS_PAD = 4;  // row stride = 4 (mod 32) banks: transposing stores spread over banks
 
-template <int BN, bool A_KMAJOR, bool B_KCONTIG>
-__global__ __launch_bounds__(GEMM_THREADS) void k_gemm_f32(
+// Attention halves in the epilogue of the projection (Sec. 4, text after Eq. 1: the score splits
+// into a source half <a_l, z[u]> and a destination half <a_r, z[v]>, both per-vertex): el[m, h] =
+// sum_f a_l[h, f] C[m, h*F + f], er likewise, taken from the accumulators before they are stored,
+// so z is not read again.  A lane holds one column of a 32-column MFMA tile, so the sum over a
+// head is a butterfly over the lanes of the tile that belong to that head (F = 4, 8, 16, 32), or,
+// for F = 64 with two tiles per wavefront, over both tiles and all 32 lanes.
+// v + (v of the lane the DPP control pairs this lane with), one VALU operation
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+  const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true);
+  return v + __int_as_float(t);
+}
+// Sum over aligned segments of `seg` lanes (a power of two, 1 .. 32); every lane of a segment ends
+// with the segment's total.  Pairings: lane ^ 1 and lane ^ 2 inside quads, then mirrored halves
+// of 8 and of 16 lanes (valid because all lanes of the smaller segment already agree), then the
+// other row of 16 through the crossbar.
+__device__ __forceinline__ float segment_sum(float v, int seg) {
+  if (seg > 1) v = dpp_add<0xB1>(v);    // quad_perm [1,0,3,2]
+  if (seg > 2) v = dpp_add<0x4E>(v);    // quad_perm [2,3,0,1]
+  if (seg > 4) v = dpp_add<0x141>(v);   // row_half_mirror
+  if (seg > 8) v = dpp_add<0x140>(v);   // row_mirror
+  if (seg > 16) v += __shfl_xor(v, 16, 64);
+  return v;
+}
+
+struct AttnEpilogue {
+  const float* a_l;
+  const float* a_r;
+  float* el;
+  float* er;
+  int H, F;
+};
+
+template <int BN, bool A_KMAJOR, bool B_KCONTIG, bool EPI = false>
+__global__ __launch_bounds__(GEMM_THREADS, 3) void k_gemm_f32(
     int64_t M, int N, int64_t K, const float* __restrict__ A, int64_t lda,
     const float* __restrict__ B, int64_t ldb, float* __restrict__ C, int64_t ldc,
-    int64_t k_per_split, int64_t split_stride) {
+    int64_t k_per_split, int64_t split_stride, AttnEpilogue epi) {
   constexpr int TN = BN / 64;          // MFMA tiles per wavefront along n
   constexpr int A_PER_T = BM * BK / GEMM_THREADS;  // 8
   constexpr int B_PER_T = BN * BK / GEMM_THREADS;  // 8 or 4
@@ -152,6 +185,48 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_f32(
         if (m < M && n < N) Cout[m * ldc + n] = acc[i][j][r];
       }
     }
+
+  if constexpr (EPI) {
+    const int F = epi.F, H = epi.H;
+    float wl[TN], wr[TN];
+    int hd[TN];           // head of the lane's column in tile j; -1: this lane stores nothing
+    const bool whole = F > 32;            // F == 32 * TN: the wavefront's columns are one head
+    const int seg = whole ? 32 : F;       // lanes of a tile that share a head
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = n0 + wn0 + j * 32 + lrow;
+      wl[j] = n < N ? epi.a_l[n] : 0.f;  // a_l, a_r are [H, F] = one value per column of C
+      wr[j] = n < N ? epi.a_r[n] : 0.f;
+      hd[j] = ((lrow & (seg - 1)) == 0 && n < N) ? n / F : -1;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t m = m0 + wm0 + i * 32 + (r >> 2) * 8 + lk * 4 + (r & 3);
+        float vl[TN], vr[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          vl[j] = wl[j] * acc[i][j][r];
+          vr[j] = wr[j] * acc[i][j][r];
+        }
+        if (whole) {
+#pragma unroll
+          for (int j = 1; j < TN; ++j) {
+            vl[0] += vl[j];
+            vr[0] += vr[j];
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < (whole ? 1 : TN); ++j) {
+          const float sl = segment_sum(vl[j], seg), sr = segment_sum(vr[j], seg);
+          if (hd[j] >= 0 && m < M) {
+            epi.el[m * H + hd[j]] = sl;
+            epi.er[m * H + hd[j]] = sr;
+          }
+        }
+      }
+  }
 }
 
 // c[i] = sum over z of partials[z][i], z ascending (fixed order => reproducible)
@@ -271,16 +346,17 @@ static gnn_status_t launch(int64_t M, int N, int64_t K, const float* a, int64_t 
                            int64_t ldb, float* c, int64_t ldc, int split_k, float* partials,
                            hipStream_t s) {
   dim3 grid((unsigned)cdiv(M, BM), (unsigned)cdiv(N, BN), (unsigned)split_k);
+  const AttnEpilogue none{nullptr, nullptr, nullptr, nullptr, 0, 0};
   if (split_k == 1) {
     ProfScope p("gemm_f32_mfma", s);
-    k_gemm_f32<BN, AK, BKC><<<grid, GEMM_THREADS, 0, s>>>(M, N, K, a, lda, b, ldb, c, ldc, K, 0);
+    k_gemm_f32<BN, AK, BKC><<<grid, GEMM_THREADS, 0, s>>>(M, N, K, a, lda, b, ldb, c, ldc, K, 0, none);
     GNN_LAUNCH_CHECK();
   } else {
     int64_t kps = cdiv(cdiv(K, split_k), BK) * BK;
     {
       ProfScope p("gemm_f32_mfma_splitk", s);
       k_gemm_f32<BN, AK, BKC><<<grid, GEMM_THREADS, 0, s>>>(M, N, K, a, lda, b, ldb, partials, N, kps,
-                                                            M * (int64_t)N);
+                                                            M * (int64_t)N, none);
       GNN_LAUNCH_CHECK();
     }
     ProfScope p("gemm_sum_partials", s);
@@ -316,6 +392,34 @@ gnn_status_t gemm_f32(int64_t M, int N, int64_t K, const float* a, int64_t lda, 
     else          { if (b_kcontig) GNN_GEMM_CASE(64, false, true); else GNN_GEMM_CASE(64, false, false); }
   }
 #undef GNN_GEMM_CASE
+}
+
+// z = x w with el, er from the epilogue; only for shapes gemm_attn_epilogue_ok() accepts
+bool gemm_attn_epilogue_ok(int heads, int f) {
+  const int N = heads * f;
+  if (f == 4 || f == 8 || f == 16 || f == 32) return true;
+  return f == 64 && gemm_tile_cols(N) == 128;
+}
+
+gnn_status_t gemm_f32_attn(int64_t M, int heads, int f, int64_t K, const float* x, const float* w,
+                           const float* a_l, const float* a_r, float* z, float* el, float* er,
+                           hipStream_t s) {
+  const int N = heads * f;
+  if (M <= 0) return GNN_OK;
+  GNN_REQUIRE(gemm_attn_epilogue_ok(heads, f), GNN_ERR_UNSUPPORTED, "gemm_f32_attn: unsupported head width");
+  GNN_REQUIRE(K > 0 && K < (1 << 24) && N < (1 << 24) && cdiv(M, BM) < (int64_t)INT32_MAX, GNN_ERR_UNSUPPORTED,
+              "gemm_f32_attn: sizes out of range");
+  const AttnEpilogue epi{a_l, a_r, el, er, heads, f};
+  ProfScope p("gemm_f32_mfma_attn", s);
+  if (gemm_tile_cols(N) == 128) {
+    dim3 grid((unsigned)cdiv(M, BM), (unsigned)cdiv(N, 128), 1);
+    k_gemm_f32<128, false, false, true><<<grid, GEMM_THREADS, 0, s>>>(M, N, K, x, K, w, N, z, N, K, 0, epi);
+  } else {
+    dim3 grid((unsigned)cdiv(M, BM), (unsigned)cdiv(N, 64), 1);
+    k_gemm_f32<64, false, false, true><<<grid, GEMM_THREADS, 0, s>>>(M, N, K, x, K, w, N, z, N, K, 0, epi);
+  }
+  GNN_LAUNCH_CHECK();
+  return GNN_OK;
 }
 
 }  // namespace gnn
