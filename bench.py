@@ -588,11 +588,29 @@ def main():
         # the projection and the input-gradient product take this name; same flop count each
         kern["gemm_f32_mfma"]["fp32_mfma_TFLOPs"] = gemm_flops / (kern["gemm_f32_mfma"]["avg_launch_ms"] * 1e-3) / 1e12
 
+    if "gemm_f32_mfma_attn" in kern:   # the projection with the attention halves in its epilogue
+        kern["gemm_f32_mfma_attn"]["fp32_mfma_TFLOPs"] = (
+            2.0 * n * fin * HF / (kern["gemm_f32_mfma_attn"]["avg_launch_ms"] * 1e-3) / 1e12)
+
+    # HBM-side counter readings are kept in a file; they are only reported when they were taken on
+    # the very kernel instantiation this run launched (the library names it)
     tv = read_traffic(args.workload)
-    traffic = float(tv["hbm_bytes_per_launch"]) if tv and tv.get("kernel") == dom else None
+    traffic, traffic_kernel = None, None
+    if tv and tv.get("kernel") == dom:
+        if kind == "gat":
+            mode = {"gat_bwd_src": 2, "gat_bwd_dst": 1, "gat_fwd_fused": 3 if t is not None else 0}.get(dom)
+            traffic_kernel = pk.gnn_gat_blocked_kernel_name(g, H, F, mode) if mode is not None else None
+            if traffic_kernel and traffic_kernel == tv.get("rocprof_kernel"):
+                traffic = float(tv["hbm_bytes_per_launch"])
+            else:
+                print(f"[bench] profiles/{args.workload}_hbm_traffic.txt was measured on "
+                      f"'{tv.get('rocprof_kernel')}', this run launches '{traffic_kernel}': traffic not reported",
+                      file=sys.stderr, flush=True)
+        else:
+            traffic = float(tv["hbm_bytes_per_launch"])
     roofline = {
         "kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-        "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+        "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_kernel": traffic_kernel,
         "algorithmic_bytes_per_launch": unique[dom] / lps, "avg_launch_ms": kern[dom]["avg_launch_ms"],
         "launches_per_step": lps,
         "bytes_model": "minimal unique bytes: every array the kernel touches counted once",

@@ -6,8 +6,12 @@
  * destination vertex that does Scatter, the lightweight ApplyEdge, the
  * ReduceScatter (edge-softmax) and the Aggregate under a single vertex-balanced
  * thread mapping (Sec. 5), and a backward pass that recomputes every per-edge
- * value from O(|V|) saved state (Sec. 6).  No function here reads or writes a
- * tensor with one row per edge.
+ * value from O(|V|) saved state (Sec. 6).  The layer calls of the scope table (GAT,
+ * EdgeConv, GMM with degree-pair coordinates, GCN) neither read nor write a tensor
+ * with one row per edge.  Two groups of calls do, and say so where they are declared:
+ * the general-pseudo-coordinate GMM layer (pseudo and gpseudo are [nnz, r] inputs /
+ * outputs of the layer's definition) and the "fusion with stashing" ablation arm
+ * (gnn_gat_stash_alpha, gnn_gat_bwd_stashed: [nnz, heads]).
  *
  * Conventions
  *   - A graph is the edge set {(u, e, v)} of App. A.1 stored as CSR by
@@ -25,7 +29,13 @@
  *     be NULL).
  *   - Every function returns a gnn_status_t.  On failure nothing useful has been
  *     written and gnn_last_error() returns a thread-local, library-owned string.
- *   - Outputs are bit-reproducible from run to run: no floating-point atomics.
+ *   - Outputs are bit-reproducible from run to run: sums are taken in a fixed order and
+ *     there are no floating-point atomics.  One exception, never taken silently: the
+ *     edge-balanced mapping of the GCN sum and of the GMM forward pass adds the pieces
+ *     of rows that span several runs with atomics; it runs only after gnn_gcn_tune /
+ *     gnn_gmm_tune has measured it faster on a graph, or when the configuration key
+ *     gcn_mapping / gmm_mapping is set to 1, and rows above 64 (32) edges may then
+ *     differ in the last bits from run to run.
  */
 #ifndef GNN_FUSED_H
 #define GNN_FUSED_H
@@ -83,7 +93,9 @@ typedef struct gnn_graph gnn_graph_t;
 gnn_status_t gnn_graph_create(int32_t n, int64_t nnz, const int32_t* indptr, const int32_t* indices,
                               void* stream, gnn_graph_t** graph);
 
-/* Frees the plan tables (not the borrowed CSR arrays).  NULL is accepted. */
+/* Frees the plan tables (not the borrowed CSR arrays).  NULL is accepted.  Waits for the
+ * device first (kernels still reading the tables must have finished, because the memory goes
+ * back to a free list that the next gnn_graph_create may draw from at once). */
 gnn_status_t gnn_graph_destroy(gnn_graph_t* graph);
 
 /* Introspection for bit-exact tests: copies plan tables into caller buffers
@@ -239,6 +251,14 @@ gnn_status_t gnn_gat_bwd_noalloc(const gnn_graph_t* graph, int fin, int heads, i
                                  const float* d, const float* out, const float* t /*nullable*/,
                                  const float* sg /*nullable*/, const float* gout /*[n,heads*f]*/,
                                  float* gx /*nullable*/, float* gw, float* ga_l, float* ga_r, void* stream);
+
+/* Introspection for measurement scripts: the instantiation of the column-blocked edge kernel that
+ * a pass over this graph launches for `heads` x `f` (mode 0 forward, 1 destination side recomputing,
+ * 2 source side, 3 forward with stash), spelled as a profiler prints it, e.g.
+ * "k_gat_blk<16, 2, false, false, true>"; the empty string when the single-launch kernels run.
+ * buf is a HOST buffer of len bytes. */
+gnn_status_t gnn_gat_blocked_kernel_name(const gnn_graph_t* graph, int heads, int f, int mode,
+                                         char* buf /*host*/, size_t len);
 
 /* The "fusion with stashing" arm of the recomputation study (Sec. 7.3): the fused kernels, but
  * the per-edge softmax values are stored after the forward pass and read back in the

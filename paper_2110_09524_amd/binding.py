@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "GNN_OK", 1: "GNN_ERR_INVALID_ARG", 2: "GNN_ERR_BAD_GRAPH",
 EXPORTS = [
     "gnn_last_error", "gnn_graph_create", "gnn_graph_destroy", "gnn_graph_get_csc",
     "gnn_graph_get_buckets", "gnn_graph_get_blocked", "gnn_graph_get_launch_groups", "gnn_release_cached_memory", "gnn_config_set", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
-    "gnn_gat_bwd", "gnn_gat_bwd_noalloc", "gnn_gat_stash_alpha", "gnn_gat_bwd_stashed", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
+    "gnn_gat_bwd", "gnn_gat_bwd_noalloc", "gnn_gat_blocked_kernel_name", "gnn_gat_stash_alpha", "gnn_gat_bwd_stashed", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
     "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd", "gnn_gmm_tune",
     "gnn_gmmp_workspace_bytes", "gnn_gmmp_fwd", "gnn_gmmp_bwd", "gnn_pseudo_proj_workspace_bytes",
     "gnn_pseudo_proj_fwd", "gnn_pseudo_proj_bwd", "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_gcn_tune",
@@ -61,6 +61,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_gat_fwd.argtypes = [vp, i32, i32, i32, f32] + [vp] * 12 + [vp, sz, vp]
     lib.gnn_gat_bwd.argtypes = [vp, i32, i32, i32, f32] + [vp] * 17 + [vp, sz, vp]
     lib.gnn_gat_bwd_noalloc.argtypes = [vp, i32, i32, i32, f32] + [vp] * 17 + [vp]
+    lib.gnn_gat_blocked_kernel_name.argtypes = [vp, i32, i32, i32, C.c_char_p, sz]
     lib.gnn_gat_stash_alpha.argtypes = [vp, i32, f32] + [vp] * 5 + [vp]
     lib.gnn_gat_bwd_stashed.argtypes = [vp, i32, i32, i32, f32] + [vp] * 18 + [vp, sz, vp]
     lib.gnn_edgeconv_workspace_bytes.restype = sz
@@ -251,6 +252,12 @@ def gnn_gat_bwd(g: Graph, fin, heads, f, slope, x, w, a_l, a_r, z, el, er, m, d,
     _check(lib().gnn_gat_bwd(g.handle, fin, heads, f, slope, _f(x), _f(w), _f(a_l), _f(a_r), _f(z),
                              _f(el), _f(er), _f(m), _f(d), _f(out), _f(t), _f(sg), _f(gout), _f(gx),
                              _f(gw), _f(ga_l), _f(ga_r), wp, wb, _stream(stream)))
+
+
+def gnn_gat_blocked_kernel_name(g: Graph, heads, f, mode) -> str:
+    buf = C.create_string_buffer(128)
+    _check(lib().gnn_gat_blocked_kernel_name(g.handle, heads, f, mode, buf, 128))
+    return buf.value.decode()
 
 
 NOALLOC_SCRATCH_BYTES = 64 << 20   # GNN_NOALLOC_SCRATCH_BYTES of the header

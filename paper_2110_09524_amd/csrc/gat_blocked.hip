@@ -766,3 +766,26 @@ gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* 
 }
 
 }  // namespace gnn
+
+// Which instantiation of the column-blocked kernel a pass launches for this graph and shape
+// (the plain, not LDS-staged variant), spelled as a profiler prints it; "" when the single-launch
+// kernels run instead.  Lets a measurement script check that stored counter readings belong to
+// the kernel it times.
+extern "C" gnn_status_t gnn_gat_blocked_kernel_name(const gnn_graph_t* g, int heads, int f, int mode,
+                                                    char* buf, size_t len) {
+  using namespace gnn;
+  clear_error();
+  GNN_REQUIRE(g != nullptr && buf != nullptr && len > 0, GNN_ERR_INVALID_ARG,
+              "gnn_gat_blocked_kernel_name: null argument");
+  GNN_REQUIRE(mode >= 0 && mode <= 3, GNN_ERR_INVALID_ARG, "gnn_gat_blocked_kernel_name: mode must be 0..3");
+  buf[0] = 0;
+  if (heads <= 0 || f <= 0 || !gat_blocked_applies(g, heads, f) || heads * f < 128) return GNN_OK;
+  const bool half = mode != 1 && gat_blocked_half(g, heads, f);
+  Slicing sl;
+  if (!pick_slicing(heads, heads * f, sl)) return GNN_OK;
+  const int SL = half ? 8 : sl.SL;
+  const int ns = heads * f / ((half ? 8 : 4) * SL);
+  std::snprintf(buf, len, "k_gat_blk<%d, %d, false, %s, %s>", SL, mode, half ? "true" : "false",
+                (ns >= 4 && !half) ? "true" : "false");
+  return GNN_OK;
+}

@@ -138,10 +138,20 @@ static std::unordered_multimap<size_t, void*> g_pool_free;  // capacity -> idle 
 static std::unordered_map<void*, size_t> g_pool_capacity;   // every pooled block, idle or in use
 static size_t g_pool_cached = 0;
 
+static void pool_trim();
+
 static hipError_t pool_alloc(void** out, size_t bytes) {
   *out = nullptr;
   if (bytes == 0) bytes = 1;
-  if (bytes > kPoolMaxBlock) return hipMalloc(out, bytes);
+  if (bytes > kPoolMaxBlock) {
+    hipError_t e = hipMalloc(out, bytes);
+    if (e == hipErrorOutOfMemory) {
+      (void)hipGetLastError();
+      pool_trim();
+      e = hipMalloc(out, bytes);
+    }
+    return e;
+  }
   size_t cap = 256;
   while (cap < bytes) cap <<= 1;
   {
@@ -155,6 +165,12 @@ static hipError_t pool_alloc(void** out, size_t bytes) {
     }
   }
   hipError_t e = hipMalloc(out, cap);
+  if (e == hipErrorOutOfMemory) {
+    // idle blocks of other sizes may be what fills the device: hand them back and try once more
+    (void)hipGetLastError();
+    pool_trim();
+    e = hipMalloc(out, cap);
+  }
   if (e == hipSuccess) {
     std::lock_guard<std::mutex> lk(g_pool_mu);
     g_pool_capacity[*out] = cap;
