@@ -81,3 +81,56 @@ def test_backward_is_the_transposed_product():
     np.testing.assert_allclose(bwd["dZ"], dZ, rtol=1e-12, atol=1e-12)
     np.testing.assert_allclose(bwd["gw"], H.T @ dZ, rtol=1e-12, atol=1e-12)
     np.testing.assert_allclose(bwd["gx"], dZ @ W.T, rtol=1e-12, atol=1e-12)
+
+
+# ---- general static edge weights ----------------------------------------------------------------
+def _weighted_adjacency(indptr, indices, ew, n):
+    # A[v, u] = sum of the weights of the edges u -> v (scipy adds duplicates when it multiplies)
+    return sp.csr_matrix((np.asarray(ew, dtype=np.float64), indices, indptr), shape=(n, n))
+
+
+def test_edge_weighted_forward_and_backward_are_sparse_products():
+    indptr, indices, H, W, _, _, gout = _case(11)
+    n = len(indptr) - 1
+    rng = np.random.default_rng(12)
+    ew = rng.standard_normal(len(indices))                 # both signs, duplicates weighted separately
+    A = _weighted_adjacency(indptr, indices, ew, n)
+    fwd = og.gcn_edge_forward(indptr, indices, H, W, ew)
+    np.testing.assert_allclose(fwd["out"], A @ (H @ W), rtol=1e-12, atol=1e-12)
+    bwd = og.gcn_edge_backward(indptr, indices, H, W, ew, gout, fwd)
+    dZ = A.T @ gout
+    np.testing.assert_allclose(bwd["gw"], H.T @ dZ, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(bwd["gx"], dZ @ W.T, rtol=1e-12, atol=1e-12)
+
+
+def test_edge_weighted_layer_reduces_to_the_separable_one():
+    indptr, indices, H, W, c_src, c_dst, gout = _case(13)
+    dst = np.repeat(np.arange(len(indptr) - 1), np.diff(indptr))
+    ew = c_src[indices] * c_dst[dst]
+    a = og.gcn_forward(indptr, indices, H, W, c_src, c_dst)["out"]
+    b = og.gcn_edge_forward(indptr, indices, H, W, ew)["out"]
+    np.testing.assert_allclose(b, a, rtol=1e-12, atol=1e-12)
+    ga = og.gcn_backward(indptr, indices, H, W, c_src, c_dst, gout)
+    gb = og.gcn_edge_backward(indptr, indices, H, W, ew, gout)
+    for k in ("gx", "gw"):
+        np.testing.assert_allclose(gb[k], ga[k], rtol=1e-12, atol=1e-12)
+
+
+def test_edge_weighted_closed_forms_and_finite_differences():
+    # two vertices, edges 0 -> 1 (weight 2), 1 -> 1 (weight -3), 1 -> 0 (weight 5); W = identity
+    indptr, indices = np.array([0, 1, 3], dtype=np.int32), np.array([1, 0, 1], dtype=np.int32)
+    H = np.array([[1.0, 10.0], [100.0, 1000.0]])
+    out = og.gcn_edge_forward(indptr, indices, H, np.eye(2), np.array([5.0, 2.0, -3.0]))["out"]
+    np.testing.assert_allclose(out, [[500.0, 5000.0], [2.0 - 300.0, 20.0 - 3000.0]])
+    # zero weights switch edges off; a weight on a missing gradient path leaves the others alone
+    indptr, indices, H, W, _, _, gout = _case(14)
+    rng = np.random.default_rng(15)
+    ew = rng.uniform(-1.0, 1.0, len(indices))
+    assert not og.gcn_edge_forward(indptr, indices, H, W, np.zeros_like(ew))["out"].any()
+    bwd = og.gcn_edge_backward(indptr, indices, H, W, ew, gout)
+    loss_H = lambda t: float((gout * og.gcn_edge_forward(indptr, indices, t, W, ew)["out"]).sum())
+    loss_W = lambda t: float((gout * og.gcn_edge_forward(indptr, indices, H, t, ew)["out"]).sum())
+    idx, g = finite_difference(loss_H, H, max_entries=60, rng=rng)
+    np.testing.assert_allclose(bwd["gx"].reshape(-1)[idx], g, rtol=1e-6, atol=1e-7)
+    idx, g = finite_difference(loss_W, W, max_entries=30, rng=rng)
+    np.testing.assert_allclose(bwd["gw"].reshape(-1)[idx], g, rtol=1e-6, atol=1e-7)
