@@ -159,11 +159,15 @@ def cpu_baseline_gcn(c, budget_rows):
     n, e = c["n"], c["nnz"]
     rng = np.random.default_rng(12345)
     rows = np.sort(rng.choice(n, size=min(budget_rows, n), replace=False))
-    ip, ix, _ = restrict_rows(c["indptr"], c["indices"], rows)
+    ip, ix, pos = restrict_rows(c["indptr"], c["indices"], rows)
     e_s = int(ix.shape[0])
     t0 = time.perf_counter()
-    fwd = og.gcn_forward(ip, ix, c["x"], c["w"], c["c_src"], c["c_dst"])
-    bwd = og.gcn_backward(ip, ix, c["x"], c["w"], c["c_src"], c["c_dst"], c["gout"], fwd)
+    if "ew" in c:
+        fwd = og.gcn_edge_forward(ip, ix, c["x"], c["w"], c["ew"][pos])
+        bwd = og.gcn_edge_backward(ip, ix, c["x"], c["w"], c["ew"][pos], c["gout"], fwd)
+    else:
+        fwd = og.gcn_forward(ip, ix, c["x"], c["w"], c["c_src"], c["c_dst"])
+        bwd = og.gcn_backward(ip, ix, c["x"], c["w"], c["c_src"], c["c_dst"], c["gout"], fwd)
     t_sample = time.perf_counter() - t0
     X64, W64 = c["x"].astype(np.float64), c["w"].astype(np.float64)
     t1 = time.perf_counter()
@@ -523,12 +527,22 @@ def main():
         ws_bytes = pk.gnn_gcn_workspace_bytes(g, fin, F)
         ws = new(max(ws_bytes, 16), dtype=torch.uint8)
 
+        ew = pk.EdgeWeights(g, to(c["ew"])) if "ew" in c else None   # general static weight per edge
+
         def step():
-            pk.gnn_gcn_fwd(g, fin, F, x, w, c_src, c_dst, zs, out)
-            pk.gnn_gcn_bwd(g, fin, F, x, w, c_src, c_dst, gout, gx, gw, ws)
+            if ew is not None:
+                pk.gnn_gcn_edge_fwd(g, ew, fin, F, x, w, zs, out)
+                pk.gnn_gcn_edge_bwd(g, ew, fin, F, x, w, gout, gx, gw, ws)
+            else:
+                pk.gnn_gcn_fwd(g, fin, F, x, w, c_src, c_dst, zs, out)
+                pk.gnn_gcn_bwd(g, fin, F, x, w, c_src, c_dst, gout, gx, gw, ws)
         unique, gather, flops = gcn_models(n, e, fin, F)
+        if ew is not None:    # one more 4-byte stream per edge and pass
+            unique = {k: v + 4 * e for k, v in unique.items()}
+            gather = {k: v + 4 * e for k, v in gather.items()}
         metric = "fused GCN layer fwd+bwd edges/sec"
-        cfg = {"in_feat": fin, "out_feat": F, "edge_weight": "1/sqrt(outdeg(u) indeg(v))",
+        cfg = {"in_feat": fin, "out_feat": F,
+               "edge_weight": "general static scalar per edge" if ew is not None else "1/sqrt(outdeg(u) indeg(v))",
                "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded", "mapping": args.gcn_mapping}
         pk.gnn_config_set("gcn_mapping", {"vertex": 0, "edge": 1, "tuned": 2}[args.gcn_mapping])
         if args.gcn_mapping == "tuned":

@@ -415,6 +415,29 @@ gnn_status_t gnn_gcn_bwd(const gnn_graph_t* graph, int fin, int fout, const floa
                          const float* c_src, const float* c_dst, const float* gout /*[n,fout]*/,
                          float* gx /*nullable*/, float* gw, void* ws, size_t ws_bytes, void* stream);
 
+/* The same layer with a GENERAL static weight per edge (App. A.2 "GCN": e_uv is any gradient-free
+ * scalar of the edge):  out[v] = sum over in-edges e = (u -> v) of edge_w[e] (x w)[u].
+ * The weights are static, so they are copied ONCE into every order the kernels walk (CSR, the CSC
+ * transpose and, on graphs that span several column blocks, both blocked edge lists: 4 * nnz bytes
+ * each); gnn_edge_weights_create does that (it allocates from the plan's free list and waits for
+ * the stream, like gnn_graph_create) and the layer calls then read one more coalesced stream
+ * next to the index list: no per-edge gather, no allocation.  edge_w is [nnz] in CSR order (the
+ * order of `indices`), duplicate edges carry their own weights; it is an input of the layer's
+ * definition, not a stash.  The handle belongs to the graph it was made for and must be
+ * destroyed before it.  z [n,fout] receives x w.  Vertex-balanced mapping only.
+ * Workspace of the backward call: gnn_gcn_workspace_bytes.  Errors as for gnn_gcn_fwd / bwd, plus
+ * INVALID_ARG for a handle made for another graph. */
+typedef struct gnn_edge_weights gnn_edge_weights_t;
+gnn_status_t gnn_edge_weights_create(const gnn_graph_t* graph, const float* edge_w /*[nnz]*/, void* stream,
+                                     gnn_edge_weights_t** weights);
+gnn_status_t gnn_edge_weights_destroy(gnn_edge_weights_t* weights);
+gnn_status_t gnn_gcn_edge_fwd(const gnn_graph_t* graph, const gnn_edge_weights_t* weights, int fin, int fout,
+                              const float* x /*[n,fin]*/, const float* w /*[fin,fout]*/,
+                              float* z /*[n,fout]*/, float* out /*[n,fout]*/, void* stream);
+gnn_status_t gnn_gcn_edge_bwd(const gnn_graph_t* graph, const gnn_edge_weights_t* weights, int fin, int fout,
+                              const float* x, const float* w, const float* gout /*[n,fout]*/,
+                              float* gx /*nullable*/, float* gw, void* ws, size_t ws_bytes, void* stream);
+
 /* Profile-driven choice of the thread mapping (Sec. 5: the fused Gather runs either
  * vertex-balanced, one thread group per row, or edge-balanced, one group per fixed run of
  * edges with atomic adds where a row spans several runs; the faster one is picked by

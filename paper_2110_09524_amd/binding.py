@@ -26,6 +26,7 @@ EXPORTS = [
     "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd", "gnn_gmm_tune",
     "gnn_gmmp_workspace_bytes", "gnn_gmmp_fwd", "gnn_gmmp_bwd", "gnn_pseudo_proj_workspace_bytes",
     "gnn_pseudo_proj_fwd", "gnn_pseudo_proj_bwd", "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_gcn_tune",
+    "gnn_edge_weights_create", "gnn_edge_weights_destroy", "gnn_gcn_edge_fwd", "gnn_gcn_edge_bwd",
     "gnn_bias_act_fwd", "gnn_bias_act_workspace_bytes", "gnn_bias_act_bwd", "gnn_softmax_xent_workspace_bytes",
     "gnn_softmax_xent", "gnn_sgd_update", "gnn_knn_graph", "gnn_prof_enable",
     "gnn_prof_collect", "gnn_prof_reset", "gnn_prof_count", "gnn_prof_get",
@@ -86,6 +87,10 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_gcn_fwd.argtypes = [vp, i32, i32] + [vp] * 6 + [vp]
     lib.gnn_gcn_bwd.argtypes = [vp, i32, i32] + [vp] * 7 + [vp, sz, vp]
     lib.gnn_gcn_tune.argtypes = [vp, i32, vp, sz, vp, C.POINTER(C.c_float)]
+    lib.gnn_edge_weights_create.argtypes = [vp, vp, vp, C.POINTER(vp)]
+    lib.gnn_edge_weights_destroy.argtypes = [vp]
+    lib.gnn_gcn_edge_fwd.argtypes = [vp, vp, i32, i32] + [vp] * 4 + [vp]
+    lib.gnn_gcn_edge_bwd.argtypes = [vp, vp, i32, i32] + [vp] * 5 + [vp, sz, vp]
     lib.gnn_bias_act_fwd.argtypes = [i64, i32, i32, f32, vp, vp, vp, vp]
     lib.gnn_bias_act_workspace_bytes.restype = sz
     lib.gnn_bias_act_workspace_bytes.argtypes = [i64, i32]
@@ -313,6 +318,42 @@ def gnn_gcn_bwd(g: Graph, fin, fout, x, w, c_src, c_dst, gout, gx, gw, ws, strea
     wp, wb = _ws_args(ws)
     _check(lib().gnn_gcn_bwd(g.handle, fin, fout, _f(x), _f(w), _f(c_src), _f(c_dst), _f(gout), _f(gx),
                              _f(gw), wp, wb, _stream(stream)))
+
+
+class EdgeWeights:
+    """Handle of gnn_edge_weights_create: a static scalar per edge ([nnz], CSR order) copied into
+    every order the kernels walk.  Keeps its graph alive; close it before the graph."""
+
+    def __init__(self, g: Graph, edge_w: torch.Tensor, stream=None):
+        self.graph = g
+        h = C.c_void_p()
+        _check(lib().gnn_edge_weights_create(g.handle, _f(edge_w) if g.nnz else None, _stream(stream), C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().gnn_edge_weights_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def handle(self):
+        return self._h
+
+
+def gnn_gcn_edge_fwd(g: Graph, ew: EdgeWeights, fin, fout, x, w, z, out, stream=None):
+    _check(lib().gnn_gcn_edge_fwd(g.handle, ew.handle, fin, fout, _f(x), _f(w), _f(z), _f(out), _stream(stream)))
+
+
+def gnn_gcn_edge_bwd(g: Graph, ew: EdgeWeights, fin, fout, x, w, gout, gx, gw, ws, stream=None):
+    wp, wb = _ws_args(ws)
+    _check(lib().gnn_gcn_edge_bwd(g.handle, ew.handle, fin, fout, _f(x), _f(w), _f(gout), _f(gx), _f(gw), wp, wb,
+                                  _stream(stream)))
 
 
 def gnn_gcn_tune(g: Graph, fout, ws, stream=None):

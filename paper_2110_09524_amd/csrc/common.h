@@ -121,6 +121,14 @@ gnn_status_t sum_partials_pair(int64_t count, int parts, const float* partials, 
 
 }  // namespace gnn
 
+// Static scalar per edge (App. A.2 "GCN": e_uv), copied once into every order the kernels walk.
+struct gnn_edge_weights {
+  const gnn_graph* graph;
+  int64_t nnz;
+  float* w_side[2];  // side 0: CSR order (as given); side 1: order of the CSC transpose
+  float* w_blk[2];   // order of the column-blocked edge list of each side; null without blocks
+};
+
 // The graph handle: borrowed CSR plus the plan tables it owns.
 struct gnn_graph {
   int32_t n;

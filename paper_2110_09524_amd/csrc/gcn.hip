@@ -38,16 +38,18 @@ __global__ void k_scale_rows(int64_t quads, int q_per_row, const float* __restri
 }
 
 // ---- single launch: out[row,:] = scale[row] * sum over the row's gathered vertices of feat ----
-template <int L, int NV>
+// W: every edge carries a static weight (wgt, in the order of cols); scale may then be null
+template <int L, int NV, bool W = false>
 __global__ __launch_bounds__(kGcnBlock) void k_rowsum(
     RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ ptr,
     const int32_t* __restrict__ cols, const float* __restrict__ feat, int F,
-    const float* __restrict__ scale, float* __restrict__ out) {
+    const float* __restrict__ scale, float* __restrict__ out, const float* __restrict__ wgt = nullptr) {
   constexpr int G = kWave / L;
   constexpr int GPB = G * (kGcnBlock / kWave);
   constexpr int NC = 4 * NV;
   constexpr int U = 4;
   __shared__ int lds[GPB * L];
+  __shared__ float lds_w[W ? GPB * L : 1];
   __shared__ float coop_buf[GPB * L * NC];
   const int lane = threadIdx.x & 63;
   const int li = lane & (L - 1);
@@ -57,6 +59,7 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum(
   RowRange rr;
   if (!pick_row<GPB>(rl, grp, rr, r, gi, ngrp)) return;
   int* l_idx = lds + grp * L;
+  float* l_w = lds_w + (W ? grp * L : 0);
   const int32_t v = order[r];
   const int32_t beg = ptr[v], end = ptr[v + 1];
 
@@ -69,6 +72,7 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum(
   }
   for (int32_t c0 = beg + gi * L; c0 < end; c0 += ngrp * L) {
     l_idx[li] = c0 + li < end ? cols[c0 + li] : 0;
+    if (W) l_w[li] = c0 + li < end ? wgt[c0 + li] : 0.f;
     wave_lds_fence();
     float4 part[NV];  // this chunk's share (two-level summation)
 #pragma unroll
@@ -76,10 +80,12 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum(
     const int cnt = min(L, end - c0);
     for (int t0 = 0; t0 < cnt; t0 += U) {
       int uu[U];
+      float ww[U];
 #pragma unroll
       for (int t = 0; t < U; ++t) {
         uu[t] = l_idx[t0 + t];
         if (L == 64) uu[t] = __builtin_amdgcn_readfirstlane(uu[t]);
+        ww[t] = W ? l_w[t0 + t] : (t0 + t < cnt ? 1.f : 0.f);  // padding adds 0 * row 0
       }
 #pragma unroll
       for (int j = 0; j < NV; ++j) {
@@ -88,7 +94,7 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum(
 #pragma unroll
         for (int t = 0; t < U; ++t) rowv[t] = ld4(feat + (int64_t)uu[t] * F + 4 * (li + j * L));
 #pragma unroll
-        for (int t = 0; t < U; ++t) fma4(part[j], t0 + t < cnt ? 1.f : 0.f, rowv[t]);  // padding adds 0 * row 0
+        for (int t = 0; t < U; ++t) fma4(part[j], ww[t], rowv[t]);
       }
     }
 #pragma unroll
@@ -104,7 +110,7 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum(
 #pragma unroll
     for (int j = 0; j < NV; ++j) acc[j] = unpack4(vv + 4 * j);
   }
-  const float s = scale[v];
+  const float s = scale ? scale[v] : 1.f;
 #pragma unroll
   for (int j = 0; j < NV; ++j)
     if (slot_ok[j])
@@ -208,17 +214,19 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_eb(
 }
 
 // ---- one column block of the same sum (running sums in acc_buf) -----------------------
-template <int SL, bool SKIP>
+// W: every edge carries a static weight, bw in the order of bcol (a second coalesced stream)
+template <int SL, bool SKIP, bool W = false>
 __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
     int32_t n_rows, const int32_t* __restrict__ order, const int2* __restrict__ bseg_b,
     const int32_t* __restrict__ bcol, const float* __restrict__ feat, int32_t col_begin, int F,
     int first, int ns /* column slices: 8, 4, 2 or 1 */, float* __restrict__ acc_buf,
     int nseg /* adjacent column blocks of this launch (1 .. kMaxMerge): segment j of the row at
-                position r of the degree order is bseg_b[j * n_rows + r] */) {
+                position r of the degree order is bseg_b[j * n_rows + r] */,
+    const float* __restrict__ bw = nullptr) {
   constexpr int GPB = kGcnBlock / SL;
   constexpr int R = kGcnRows;
   constexpr int U = SL < 8 ? 4 : 8;
-  constexpr int GS = SL + R + 2 * R * kMaxMerge;  // LDS ints per group: idx | rows | (beg, end) per row and block
+  constexpr int GS = SL + R + 2 * R * kMaxMerge + (W ? SL : 0);  // LDS ints per group: idx | rows | (beg, end) per row and block | weights
   static_assert(GS % 4 == 0, "group scratch must stay 16-byte aligned");
   static_assert(SL >= R, "one lane per pipelined row loads its metadata");
   __shared__ __align__(16) int lds[GPB * GS];
@@ -231,6 +239,7 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
   int* l_idx = lds + grp * GS;
   int* l_row = l_idx + SL;
   int2* l_seg = reinterpret_cast<int2*>(l_row + R);  // [R][kMaxMerge]
+  float* l_w = reinterpret_cast<float*>(l_idx + SL + R + 2 * R * kMaxMerge);
   const int col = slice * 4 * SL + 4 * li;
 
   if (li < R) {
@@ -251,6 +260,7 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
 
   struct Row {
     int32_t row, beg, end, c_first;
+    float w_first;
     float4 acc;
   };
   auto fetch = [&](int k, Row& s) {
@@ -259,9 +269,13 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
     s.beg = seg0.x;
     s.end = seg0.y;
     s.c_first = col_begin;
+    s.w_first = 0.f;
     s.acc = make_float4(0.f, 0.f, 0.f, 0.f);
     if (s.row < 0) return;
-    if (s.beg + li < s.end) s.c_first = bcol[s.beg + li];
+    if (s.beg + li < s.end) {
+      s.c_first = bcol[s.beg + li];
+      if (W) s.w_first = bw[s.beg + li];
+    }
     if (!first) s.acc = ld4_stream(acc_buf + (int64_t)s.row * F + col);
   };
 
@@ -272,15 +286,20 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
     if (cur.row >= 0) {
       float4 acc = cur.acc;
       int32_t beg = cur.beg, end = cur.end, c_next = cur.c_first;
+      float w_next = cur.w_first;
       for (int sgi = 0; sgi < nseg; ++sgi) {
       // the bounds and the first indices of the row's segment in the next block are in flight
       // while this one is processed
       int32_t beg_n = 0, end_n = 0, c_first_n = col_begin;
+      float w_first_n = 0.f;
       if (sgi + 1 < nseg) {
         const int2 sn = l_seg[k * kMaxMerge + sgi + 1];
         beg_n = sn.x;
         end_n = sn.y;
-        if (beg_n + li < end_n) c_first_n = bcol[beg_n + li];
+        if (beg_n + li < end_n) {
+          c_first_n = bcol[beg_n + li];
+          if (W) w_first_n = bw[beg_n + li];
+        }
       }
       for (int32_t c0 = beg; c0 < end; c0 += SL) {
         // lanes past the end point at the block's first vertex (valid, cache-resident) and
@@ -290,8 +309,13 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
         // half's sums: rows cut into four or more slices gain 2 % overall, rows cut into two lose
         // 24 % (measured), so SKIP is instantiated only for the former.
         const int32_t c = c0 + li < end ? c_next : col_begin;
-        if (c0 + SL + li < end) c_next = bcol[c0 + SL + li];
+        const float wv = c0 + li < end ? w_next : 0.f;
+        if (c0 + SL + li < end) {
+          c_next = bcol[c0 + SL + li];
+          if (W) w_next = bw[c0 + SL + li];
+        }
         l_idx[li] = c;
+        if (W) l_w[li] = wv;
         wave_lds_fence();
         const int cnt = min(SL, end - c0);
         float4 part = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -314,7 +338,7 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
           for (int t4 = 0; t4 < U; t4 += 4)
             if (!SKIP || t0 + t4 < cnt) {
 #pragma unroll
-              for (int t = t4; t < t4 + 4; ++t) fma4(part, t0 + t < cnt ? 1.f : 0.f, rowv[t]);
+              for (int t = t4; t < t4 + 4; ++t) fma4(part, W ? l_w[t0 + t] : (t0 + t < cnt ? 1.f : 0.f), rowv[t]);
             }
         }
         add4(acc, part);
@@ -323,6 +347,7 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
       beg = beg_n;
       end = end_n;
       c_next = c_first_n;
+      w_next = w_first_n;
       }
       st4_stream(acc_buf + (int64_t)cur.row * F + col, acc);
     }
@@ -358,7 +383,7 @@ static bool gcn_blocked_applies(const gnn_graph_t* g, int F) {
 
 template <int SL>
 static gnn_status_t launch_rowsum_blocks(const gnn_graph_t* g, int side, const char* name, const float* feat,
-                                         int F, float* acc, hipStream_t st) {
+                                         int F, float* acc, hipStream_t st, const float* bw = nullptr) {
   const int rows_per_wg = (kGcnBlock / SL) * kGcnRows;
   const int ns = F / (4 * SL);
   const unsigned grid = (unsigned)(cdiv(g->n, rows_per_wg) * ns);
@@ -370,7 +395,13 @@ static gnn_status_t launch_rowsum_blocks(const gnn_graph_t* g, int side, const c
     GNN_REQUIRE(nseg >= 1 && nseg <= kMaxMerge, GNN_ERR_UNSUPPORTED, "gcn blocked: bad launch group");
     const int2* bseg_b = reinterpret_cast<const int2*>(g->bseg[side]) + (int64_t)b * g->n;
     ProfScope p(name, st);  // one timed bracket per launch
-    if (ns >= 4)
+    if (bw != nullptr && ns >= 4)
+      k_rowsum_blk<SL, true, true><<<grid, kGcnBlock, 0, st>>>(g->n, g->order[side], bseg_b, g->bcol[side], feat,
+                                                              b * g->block_cols, F, b == 0, ns, acc, nseg, bw);
+    else if (bw != nullptr)
+      k_rowsum_blk<SL, false, true><<<grid, kGcnBlock, 0, st>>>(g->n, g->order[side], bseg_b, g->bcol[side], feat,
+                                                               b * g->block_cols, F, b == 0, ns, acc, nseg, bw);
+    else if (ns >= 4)
       k_rowsum_blk<SL, true><<<grid, kGcnBlock, 0, st>>>(g->n, g->order[side], bseg_b, g->bcol[side], feat,
                                                         b * g->block_cols, F, b == 0, ns, acc, nseg);
     else
@@ -395,6 +426,26 @@ struct RowsumLauncher {
     const RowLaunch rl{sp.hub.end, g->n};
     if (grid != 0) {
       k_rowsum<L, NV><<<grid, kGcnBlock, 0, st>>>(rl, g->order[side], ptr, cols, feat, F, scale, out);
+      GNN_LAUNCH_CHECK();
+    }
+    return GNN_OK;
+  }
+};
+
+// the same sum with a static weight per edge (wgt in the order of the side's edge array)
+template <int L, int NV>
+struct RowsumWeightedLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, int side, const char* name, const float* feat, int F,
+                          const float* wgt, float* out, hipStream_t st) {
+    constexpr int GPB = (kWave / L) * (kGcnBlock / kWave);
+    ProfScope p(name, st);
+    const RowSplit sp = split_rows(g, side, L, GPB);
+    const int32_t* ptr = side == 0 ? g->indptr : g->indptr_t;
+    const int32_t* cols = side == 0 ? g->indices : g->indices_t;
+    const unsigned grid = sp.hub_grid + sp.rest_grid;
+    const RowLaunch rl{sp.hub.end, g->n};
+    if (grid != 0) {
+      k_rowsum<L, NV, true><<<grid, kGcnBlock, 0, st>>>(rl, g->order[side], ptr, cols, feat, F, nullptr, out, wgt);
       GNN_LAUNCH_CHECK();
     }
     return GNN_OK;
@@ -477,6 +528,23 @@ static gnn_status_t gcn_aggregate(const gnn_graph_t* g, int side, const char* na
   return gcn_aggregate_vertex(g, side, name, feat, F, scale, out, st);
 }
 
+// out[row,:] = sum over the row's edges on `side` of weight * feat[neighbour,:]  (vertex-balanced:
+// column-blocked launches on large graphs, else one launch)
+static gnn_status_t gcn_aggregate_weighted(const gnn_graph_t* g, const gnn_edge_weights* ew, int side,
+                                           const char* name, const float* feat, int F, float* out,
+                                           hipStream_t st) {
+  if (gcn_blocked_applies(g, F) && ew->w_blk[side] != nullptr) {
+    int SL = 0, ns = 0;
+    gcn_slicing(F, SL, ns);
+    switch (SL) {
+      case 8: return launch_rowsum_blocks<8>(g, side, name, feat, F, out, st, ew->w_blk[side]);
+      case 16: return launch_rowsum_blocks<16>(g, side, name, feat, F, out, st, ew->w_blk[side]);
+      default: return launch_rowsum_blocks<32>(g, side, name, feat, F, out, st, ew->w_blk[side]);
+    }
+  }
+  return dispatch_rowsum<RowsumWeightedLauncher>(g, side, name, feat, F, ew->w_side[side], out, st);
+}
+
 struct GcnWs {
   size_t total, gs, dz, gemm;
   int split_k;
@@ -556,6 +624,51 @@ extern "C" gnn_status_t gnn_gcn_bwd(const gnn_graph_t* g, int fin, int fout, con
     GNN_LAUNCH_CHECK();
   }
   GNN_TRY(gcn_aggregate(g, 1, "gcn_bwd_src", gs, fout, c_src, dz, st));
+  GNN_TRY(gemm_f32(fin, fout, g->n, x, fin, true, dz, fout, false, gw, fout, L.split_k, part, st));
+  if (gx) GNN_TRY(gemm_f32(g->n, fin, fout, dz, fout, false, w, fout, true, gx, fin, 1, nullptr, st));
+  return GNN_OK;
+}
+
+static gnn_status_t gcn_edge_check(const gnn_graph_t* g, const gnn_edge_weights* ew, const char* who) {
+  GNN_REQUIRE(ew != nullptr, GNN_ERR_INVALID_ARG, "%s: edge weights are null", who);
+  GNN_REQUIRE(ew->graph == g && ew->nnz == g->nnz, GNN_ERR_INVALID_ARG,
+              "%s: the edge weights were made for another graph", who);
+  return GNN_OK;
+}
+
+extern "C" gnn_status_t gnn_gcn_edge_fwd(const gnn_graph_t* g, const gnn_edge_weights_t* ew, int fin, int fout,
+                                         const float* x, const float* w, float* z, float* out, void* stream) {
+  clear_error();
+  GNN_TRY(gcn_check(g, fin, fout, "gnn_gcn_edge_fwd"));
+  GNN_TRY(gcn_edge_check(g, ew, "gnn_gcn_edge_fwd"));
+  if (g->n == 0) return GNN_OK;
+  GNN_REQUIRE(x && w && z && out, GNN_ERR_INVALID_ARG, "gnn_gcn_edge_fwd: null pointer");
+  GNN_REQUIRE(aligned16(z) && aligned16(out), GNN_ERR_INVALID_ARG,
+              "gnn_gcn_edge_fwd: z, out must be 16-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  GNN_TRY(gemm_f32(g->n, fout, fin, x, fin, false, w, fout, false, z, fout, 1, nullptr, st));
+  return gcn_aggregate_weighted(g, ew, 0, "gcn_fwd_fused", z, fout, out, st);
+}
+
+extern "C" gnn_status_t gnn_gcn_edge_bwd(const gnn_graph_t* g, const gnn_edge_weights_t* ew, int fin, int fout,
+                                         const float* x, const float* w, const float* gout, float* gx,
+                                         float* gw, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  GNN_TRY(gcn_check(g, fin, fout, "gnn_gcn_edge_bwd"));
+  GNN_TRY(gcn_edge_check(g, ew, "gnn_gcn_edge_bwd"));
+  if (g->n == 0) return GNN_OK;
+  GNN_REQUIRE(x && w && gout && gw, GNN_ERR_INVALID_ARG, "gnn_gcn_edge_bwd: null pointer");
+  GNN_REQUIRE(aligned16(gout), GNN_ERR_INVALID_ARG, "gnn_gcn_edge_bwd: gout must be 16-byte aligned");
+  const GcnWs L = gcn_ws_layout(g->n, fin, fout);
+  GNN_REQUIRE(ws != nullptr && ws_bytes >= L.total, GNN_ERR_WORKSPACE,
+              "gnn_gcn_edge_bwd: workspace of %zu bytes given, %zu needed", ws_bytes, L.total);
+  GNN_REQUIRE(aligned16(ws), GNN_ERR_INVALID_ARG, "gnn_gcn_edge_bwd: workspace must be 16-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* base = static_cast<char*>(ws);
+  float* dz = reinterpret_cast<float*>(base + L.dz);
+  float* part = reinterpret_cast<float*>(base + L.gemm);
+  // dz[u] = sum over out-edges of e_uv gout[v]: the same weighted sum over the transpose
+  GNN_TRY(gcn_aggregate_weighted(g, ew, 1, "gcn_bwd_src", gout, fout, dz, st));
   GNN_TRY(gemm_f32(fin, fout, g->n, x, fin, true, dz, fout, false, gw, fout, L.split_k, part, st));
   if (gx) GNN_TRY(gemm_f32(g->n, fin, fout, dz, fout, false, w, fout, true, gx, fin, 1, nullptr, st));
   return GNN_OK;

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstring>
 #include <mutex>
+#include <new>
 #include <unordered_map>
 
 #include <rocprim/device/device_radix_sort.hpp>
@@ -549,6 +550,97 @@ extern "C" gnn_status_t gnn_graph_create(int32_t n, int64_t nnz, const int32_t* 
 extern "C" gnn_status_t gnn_graph_destroy(gnn_graph_t* graph) {
   clear_error();
   free_all(graph);
+  return GNN_OK;
+}
+
+// ---- static edge weights -----------------------------------------------------------------
+__global__ void k_block_keys_only(int32_t n, const int32_t* __restrict__ ptr, const int32_t* __restrict__ cols,
+                                  int32_t block_cols, uint64_t* __restrict__ keys) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) >> 6;
+  if (row >= n) return;
+  const int32_t beg = ptr[row], end = ptr[row + 1];
+  for (int32_t i = beg + lane; i < end; i += 64)
+    keys[i] = (uint64_t)(cols[i] / block_cols) * (uint64_t)n + (uint64_t)row;
+}
+
+__global__ void k_gather_f32(int64_t count, const int32_t* __restrict__ idx, const float* __restrict__ src,
+                             float* __restrict__ dst) {
+  const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i < count) dst[i] = src[idx[i]];
+}
+
+static void free_weights(gnn_edge_weights* w) {
+  if (!w) return;
+  (void)hipDeviceSynchronize();  // kernels that read the copies have finished
+  for (int s = 0; s < 2; ++s) {
+    pool_free(w->w_side[s]);
+    pool_free(w->w_blk[s]);
+  }
+  delete w;
+}
+
+static gnn_status_t build_weights(gnn_edge_weights* w, const float* edge_w, hipStream_t st) {
+  const gnn_graph* g = w->graph;
+  const int64_t nnz = g->nnz;
+  const int thr = 256;
+  if (nnz == 0) return GNN_OK;
+  for (int s = 0; s < 2; ++s) GNN_HIP(pool_alloc((void**)&w->w_side[s], sizeof(float) * (size_t)nnz));
+  GNN_HIP(hipMemcpyAsync(w->w_side[0], edge_w, sizeof(float) * (size_t)nnz, hipMemcpyDeviceToDevice, st));
+  k_gather_f32<<<(unsigned)cdiv(nnz, thr), thr, 0, st>>>(nnz, g->eid_t, edge_w, w->w_side[1]);
+  GNN_LAUNCH_CHECK();
+  if (g->nblk > 1) {
+    // The blocked lists are a stable sort of each side's edges by (column block, row); sorting the
+    // weights with the same keys and the same stable radix sort puts them in the same order.
+    TempBuffers tmp(st);
+    uint64_t *keys = nullptr, *keys_sorted = nullptr;
+    GNN_HIP(tmp.alloc(&keys, (size_t)nnz));
+    GNN_HIP(tmp.alloc(&keys_sorted, (size_t)nnz));
+    const int64_t slots = (int64_t)g->nblk * g->n;
+    int end_bit = 1;
+    while (end_bit < 64 && ((uint64_t)(slots - 1) >> end_bit) != 0) ++end_bit;
+    for (int s = 0; s < 2; ++s) {
+      GNN_HIP(pool_alloc((void**)&w->w_blk[s], sizeof(float) * (size_t)nnz));
+      const int32_t* ptr = s == 0 ? g->indptr : g->indptr_t;
+      const int32_t* cols = s == 0 ? g->indices : g->indices_t;
+      k_block_keys_only<<<(unsigned)cdiv((int64_t)g->n * 64, thr), thr, 0, st>>>(g->n, ptr, cols, g->block_cols, keys);
+      GNN_LAUNCH_CHECK();
+      size_t bytes = 0;
+      GNN_HIP(rocprim::radix_sort_pairs(nullptr, bytes, keys, keys_sorted, w->w_side[s], w->w_blk[s],
+                                        (size_t)nnz, 0, end_bit, st));
+      void* scratch = nullptr;
+      GNN_HIP(tmp.alloc((char**)&scratch, bytes));
+      GNN_HIP(rocprim::radix_sort_pairs(scratch, bytes, keys, keys_sorted, w->w_side[s], w->w_blk[s],
+                                        (size_t)nnz, 0, end_bit, st));
+    }
+  }
+  GNN_HIP(hipStreamSynchronize(st));
+  return GNN_OK;
+}
+
+extern "C" gnn_status_t gnn_edge_weights_create(const gnn_graph_t* g, const float* edge_w, void* stream,
+                                                gnn_edge_weights_t** out) {
+  clear_error();
+  GNN_REQUIRE(g != nullptr && out != nullptr, GNN_ERR_INVALID_ARG, "gnn_edge_weights_create: null argument");
+  GNN_REQUIRE(g->nnz == 0 || edge_w != nullptr, GNN_ERR_INVALID_ARG, "gnn_edge_weights_create: edge_w is null");
+  *out = nullptr;
+  gnn_edge_weights* w = new (std::nothrow) gnn_edge_weights();
+  GNN_REQUIRE(w != nullptr, GNN_ERR_HIP, "gnn_edge_weights_create: out of host memory");
+  w->graph = g;
+  w->nnz = g->nnz;
+  w->w_side[0] = w->w_side[1] = w->w_blk[0] = w->w_blk[1] = nullptr;
+  gnn_status_t s = build_weights(w, edge_w, static_cast<hipStream_t>(stream));
+  if (s != GNN_OK) {
+    free_weights(w);
+    return s;
+  }
+  *out = w;
+  return GNN_OK;
+}
+
+extern "C" gnn_status_t gnn_edge_weights_destroy(gnn_edge_weights_t* w) {
+  clear_error();
+  free_weights(w);
   return GNN_OK;
 }
 

@@ -203,6 +203,41 @@ def test_gcn_on_the_c4_graph_sampled_rows_and_consistency(c4, sample, capsys):
     assert_close("out", res["out"][rows], out_ref[rows])
     assert_close("gx", res["gx"], grads["gx"])
     assert_close("gw", res["gw"], grads["gw"], reduce_scale=True)
+    say("general static weight per edge, first two chunks of the sample")
+    import torch
+    from gpu_harness import empty, workspace
+    rng = np.random.default_rng(5)
+    ew = (rng.uniform(-1.0, 1.0, len(ix)) / np.repeat(np.sqrt(np.maximum(indeg, 1.0)), np.diff(ip))).astype(np.float32)
+    sub = np.concatenate(sample["chunks"][:2])
+    keep2 = np.zeros(n, dtype=bool)
+    keep2[sub] = True
+    gout2 = np.where(keep2[:, None], c["gout"], np.float32(0))
+    handle = pk.EdgeWeights(g, dev(ew))
+    dx, dw = dev(c["x"]), dev(c["w"])
+    z_w, out_w = empty((n, c["fout"])), empty((n, c["fout"]))
+    gx_w, gw_w_ = empty((n, fin)), empty((fin, c["fout"]))
+    ws = workspace(pk.gnn_gcn_workspace_bytes(g, fin, c["fout"]))
+    pk.gnn_gcn_edge_fwd(g, handle, fin, c["fout"], dx, dw, z_w, out_w)
+    pk.gnn_gcn_edge_bwd(g, handle, fin, c["fout"], dx, dw, dev(gout2), gx_w, gw_w_, ws)
+    torch.cuda.synchronize()
+    handle.close()
+    ref_out = np.zeros((n, c["fout"]))
+    ref = dict(gx=np.zeros((n, fin)), gw=np.zeros((fin, c["fout"])))
+    for ch in sample["chunks"][:2]:
+        rip, rix, pos = restrict_rows(ip, ix, ch)
+        fwd = og.gcn_edge_forward(rip, rix, c["x"], c["w"], ew[pos])
+        ref_out[ch] = fwd["out"][ch]
+        go = np.zeros_like(gout2)
+        go[ch] = gout2[ch]
+        bwd = og.gcn_edge_backward(rip, rix, c["x"], c["w"], ew[pos], go, fwd)
+        for k in ref:
+            ref[k] += bwd[k]
+        del fwd, bwd
+    assert_close("out (edge weights)", out_w.cpu().numpy()[sub], ref_out[sub])
+    assert_close("gx (edge weights)", gx_w.cpu().numpy(), ref["gx"])
+    assert_close("gw (edge weights)", gw_w_.cpu().numpy(), ref["gw"], reduce_scale=True)
+    del z_w, out_w, gx_w, gw_w_, ws
+
     say("properties")
     res = run_gcn(c, graph=g)
     gw_w = float((res["gw"].astype(np.float64) * c["w"]).sum())

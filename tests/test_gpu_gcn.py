@@ -195,3 +195,110 @@ def test_tune_records_a_choice_and_results_stay_right():
     with pytest.raises(pk.GnnError):
         pk.gnn_config_set("gcn_mapping", 3)
     g.close()
+
+
+# ---- general static weight per edge --------------------------------------------------------------
+def run_gcn_edge(c, want_gx=True):
+    import torch
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev, empty, workspace
+    n, fin, fout = c["n"], c["fin"], c["fout"]
+    g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
+    ew = pk.EdgeWeights(g, dev(c["ew"]))
+    x, w = dev(c["x"]), dev(c["w"])
+    z, out = empty((n, fout)), empty((n, fout))
+    pk.gnn_gcn_edge_fwd(g, ew, fin, fout, x, w, z, out)
+    ws = workspace(pk.gnn_gcn_workspace_bytes(g, fin, fout))
+    ws.fill_(0xFF)
+    gx = empty((n, fin)) if want_gx else None
+    gw = empty((fin, fout))
+    pk.gnn_gcn_edge_bwd(g, ew, fin, fout, x, w, dev(c["gout"]), gx, gw, ws)
+    torch.cuda.synchronize()
+    res = dict(z=z.cpu().numpy(), out=out.cpu().numpy(), gw=gw.cpu().numpy())
+    if want_gx:
+        res["gx"] = gx.cpu().numpy()
+    nblk = g.blocked(0)[0]
+    ew.close()
+    g.close()
+    return res, nblk
+
+
+def check_edge(c, **kw):
+    from gpu_harness import assert_close
+    fwd = og.gcn_edge_forward(c["indptr"], c["indices"], c["x"], c["w"], c["ew"])
+    bwd = og.gcn_edge_backward(c["indptr"], c["indices"], c["x"], c["w"], c["ew"], c["gout"], fwd)
+    res, nblk = run_gcn_edge(c, **kw)
+    assert_close("z", res["z"], fwd["Z"])
+    assert_close("out", res["out"], fwd["out"])
+    assert_close("gw", res["gw"], bwd["gw"], reduce_scale=True)
+    if "gx" in res:
+        assert_close("gx", res["gx"], bwd["gx"])
+    return res, nblk
+
+
+@pytest.mark.parametrize("fin,fout", [(3, 4), (9, 20), (64, 64), (17, 128), (8, 512), (5, 1024)])
+def test_edge_weighted_shapes(fin, fout):
+    """A general static scalar per edge (both signs, duplicates weighted separately, empty rows,
+    a hub): single-launch kernels, CSR side and CSC side."""
+    print(f"gcn: per-edge weights fin={fin} fout={fout}", flush=True)
+    rng = np.random.default_rng(fin * 100 + fout + 1)
+    n = 400
+    src = rng.integers(0, n, size=4000)
+    dst = rng.integers(0, n, size=4000)
+    edges = [(int(s), int(d)) for s, d in zip(src, dst) if d % 7 != 3]        # every 7th row empty
+    edges += [(u, 0) for u in range(n)] + [(0, v) for v in range(1, n, 2) if v % 7 != 3]
+    indptr, indices = tiny_graph(n, edges)
+    c = synth(rng, indptr, indices, fin, fout)
+    c["ew"] = rng.standard_normal(len(indices)).astype(np.float32)
+    res, _ = check_edge(c)
+    assert (res["out"][np.diff(indptr) == 0] == 0).all()
+    check_edge(c, want_gx=False)
+
+
+@pytest.mark.parametrize("block_cols,fout", [(256, 256), (1000, 128), (300, 512), (128, 1024)])
+def test_edge_weighted_column_blocked_path(block_cols, fout):
+    """The same on the column-blocked kernels: the weights travel in the order of the blocked edge
+    lists (sorted once with the plan's keys), both sides, merged launches included."""
+    import paper_2110_09524_amd as pk
+    print(f"gcn: per-edge weights, blocked, block_cols={block_cols} fout={fout}", flush=True)
+    rng = np.random.default_rng(block_cols + fout)
+    indptr, indices = random_graph(rng, 1500, 30000, self_loops=False, duplicates=True)
+    c = synth(rng, indptr, indices, 24, fout)
+    c["ew"] = rng.uniform(-2.0, 2.0, len(indices)).astype(np.float32)
+    pk.gnn_config_set("block_cols", block_cols)
+    try:
+        _, nblk = check_edge(c)
+    finally:
+        pk.gnn_config_set("block_cols", 20480)
+    assert nblk == -(-1500 // block_cols)
+
+
+def test_edge_weighted_mid_workload_and_separable_case():
+    """On the Reddit-shaped mid-size workload; with e_uv = c_src[u] c_dst[v] the general layer
+    reproduces the separable one."""
+    from gpu_harness import assert_close, run_gcn
+    print("gcn: per-edge weights, gcn_mid", flush=True)
+    c = dict(make("gcn_mid"))
+    dst = np.repeat(np.arange(c["n"]), np.diff(c["indptr"]))
+    c["ew"] = (c["c_src"][c["indices"]] * c["c_dst"][dst]).astype(np.float32)
+    res, _ = check_edge(c)
+    sep = run_gcn(c)
+    assert_close("out vs separable", res["out"], sep["out"].astype(np.float64))
+    assert_close("gx vs separable", res["gx"], sep["gx"].astype(np.float64))
+
+
+def test_edge_weights_belong_to_their_graph():
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev, empty
+    rng = np.random.default_rng(3)
+    ip1, ix1 = random_graph(rng, 50, 200, self_loops=True)
+    ip2, ix2 = random_graph(rng, 50, 210, self_loops=True)
+    g1, g2 = pk.Graph(dev(ip1), dev(ix1)), pk.Graph(dev(ip2), dev(ix2))
+    ew = pk.EdgeWeights(g1, dev(rng.standard_normal(len(ix1)).astype(np.float32)))
+    a = empty((50, 8))
+    with pytest.raises(pk.GnnError) as e:
+        pk.gnn_gcn_edge_fwd(g2, ew, 8, 8, a, a, a, a)
+    assert e.value.status == 1
+    ew.close()
+    g1.close()
+    g2.close()

@@ -170,6 +170,16 @@ def _make_gcn_c4(seed):
     return _gcn("gcn_c4", n, graphs.chung_lu(n, 114_000_000, 2.1, SEED0 ^ 4), 602, 256, seed)
 
 
+def _make_gcnw_c4(seed):
+    # gcn_c4 with a general static weight per edge (App. A.2 "GCN": e_uv), here uniform in (0, 2/indeg(v))
+    c = _make_gcn_c4(seed)
+    rng = graphs.rng_for(seed ^ 0x5A5A)
+    indeg = np.diff(c["indptr"]).astype(np.float32)
+    dst_deg = np.repeat(indeg, np.diff(c["indptr"]))
+    c.update(name="gcnw_c4", ew=(rng.random(c["nnz"], dtype=np.float32) * 2.0 / np.maximum(dst_deg, 1.0)).astype(np.float32))
+    return c
+
+
 def _make_gcn_c5(seed):
     # GCN on the gmm_c5 graph (100 000 vertices, average degree 21): several rows per run of edges
     n = 100_000
@@ -274,6 +284,7 @@ _MAKERS = {
     "ec_l3": (11, _make_ec_l3),
     "ec_l4": (12, _make_ec_l4),
     "gcn_c4": (6, _make_gcn_c4),
+    "gcnw_c4": (16, _make_gcnw_c4),
     "gcn_mid": (106, _make_gcn_mid),
     "gcn_c5": (8, _make_gcn_c5),
     "gat2_mid": (109, _make_gat2_mid),
