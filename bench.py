@@ -424,7 +424,7 @@ def main():
                 pk.gnn_gat_bwd(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, t, sg, gout,
                                gx, gw, ga_l, ga_r, ws)
             else:
-                pk.gnn_gat_stash_alpha(g, H, c["slope"], el, er, m, d, alpha_t)
+                pk.gnn_gat_stash_alpha(g, H, F, c["slope"], el, er, m, d, alpha_t)
                 pk.gnn_gat_bwd_stashed(g, fin, H, F, c["slope"], x, w, a_l, a_r, z, el, er, m, d, out, t, sg,
                                        alpha_t, gout, gx, gw, ga_l, ga_r, ws)
         unique, gather, flops = gat_models(n, e, fin, H, F)

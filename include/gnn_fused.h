@@ -264,15 +264,20 @@ gnn_status_t gnn_gat_blocked_kernel_name(const gnn_graph_t* graph, int heads, in
  * the per-edge softmax values are stored after the forward pass and read back in the
  * backward pass instead of being recomputed.  Kept for that comparison; it needs O(|E|)
  * memory, which the default path avoids.
- * gnn_gat_stash_alpha: alpha_t [nnz, heads] in the order of the plan's CSC transpose
- *   (position p = p-th edge in (source, CSR position) order), value = softmax weight of the
- *   edge with the sign of its raw score (negative: LeakyReLU' = slope).  Call after
- *   gnn_gat_fwd (needs el, er, m, d).
- * gnn_gat_bwd_stashed: as gnn_gat_bwd, with the source side reading alpha_t; it always uses
- *   the single-launch kernels (the stash is laid out for them). */
-gnn_status_t gnn_gat_stash_alpha(const gnn_graph_t* graph, int heads, float slope, const float* el,
+ * gnn_gat_stash_alpha: nnz * heads floats, value = softmax weight of an edge with the sign of
+ *   its raw score (negative: LeakyReLU' = slope), laid out for the source-side kernel that the
+ *   backward pass of this graph and shape (heads x f) takes; gnn_gat_stash_layout says which:
+ *     0  alpha_t[p, h], p = position in the plan's CSC transpose ((source, CSR position) order),
+ *        for the single-launch kernel;
+ *     1  alpha_t[h, q], q = position in the source side's column-blocked edge list
+ *        (gnn_graph_get_blocked, side 1), for the column-blocked kernel.
+ *   Call after gnn_gat_fwd (needs el, er, m, d).
+ * gnn_gat_bwd_stashed: as gnn_gat_bwd, with the source side reading the stash instead of
+ *   recomputing the softmax values (the per-destination scalar D is still gathered). */
+int gnn_gat_stash_layout(const gnn_graph_t* graph, int heads, int f);
+gnn_status_t gnn_gat_stash_alpha(const gnn_graph_t* graph, int heads, int f, float slope, const float* el,
                                  const float* er, const float* m, const float* d,
-                                 float* alpha_t /*[nnz,heads]*/, void* stream);
+                                 float* alpha_t /*nnz*heads floats*/, void* stream);
 gnn_status_t gnn_gat_bwd_stashed(const gnn_graph_t* graph, int fin, int heads, int f, float slope,
                                  const float* x, const float* w, const float* a_l, const float* a_r,
                                  const float* z, const float* el, const float* er, const float* m,

@@ -4,7 +4,7 @@ csrc/; importing this package without the built library raises ImportError."""
 from .binding import (  # noqa: F401
     EXPORTS, GNN_NUM_BUCKETS, LIB_PATH, GnnError, Graph, lib, load_library,
     gnn_config_set, gnn_linear_fwd, gnn_release_cached_memory,
-    gnn_gat_workspace_bytes, gnn_gat_fwd, gnn_gat_bwd, gnn_gat_bwd_noalloc, NOALLOC_SCRATCH_BYTES, gnn_gat_blocked_kernel_name, gnn_gat_stash_alpha, gnn_gat_bwd_stashed,
+    gnn_gat_workspace_bytes, gnn_gat_fwd, gnn_gat_bwd, gnn_gat_bwd_noalloc, NOALLOC_SCRATCH_BYTES, gnn_gat_blocked_kernel_name, gnn_gat_stash_alpha, gnn_gat_stash_layout, gnn_gat_bwd_stashed,
     gnn_edgeconv_workspace_bytes, gnn_edgeconv_fwd, gnn_edgeconv_bwd,
     gnn_gmm_workspace_bytes, gnn_gmm_fwd, gnn_gmm_bwd, gnn_gmm_tune,
     gnn_gmmp_workspace_bytes, gnn_gmmp_fwd, gnn_gmmp_bwd,

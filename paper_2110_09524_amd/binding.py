@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "GNN_OK", 1: "GNN_ERR_INVALID_ARG", 2: "GNN_ERR_BAD_GRAPH",
 EXPORTS = [
     "gnn_last_error", "gnn_graph_create", "gnn_graph_destroy", "gnn_graph_get_csc",
     "gnn_graph_get_buckets", "gnn_graph_get_blocked", "gnn_graph_get_launch_groups", "gnn_release_cached_memory", "gnn_config_set", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
-    "gnn_gat_bwd", "gnn_gat_bwd_noalloc", "gnn_gat_blocked_kernel_name", "gnn_gat_stash_alpha", "gnn_gat_bwd_stashed", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
+    "gnn_gat_bwd", "gnn_gat_bwd_noalloc", "gnn_gat_blocked_kernel_name", "gnn_gat_stash_layout", "gnn_gat_stash_alpha", "gnn_gat_bwd_stashed", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
     "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd", "gnn_gmm_tune",
     "gnn_gmmp_workspace_bytes", "gnn_gmmp_fwd", "gnn_gmmp_bwd", "gnn_pseudo_proj_workspace_bytes",
     "gnn_pseudo_proj_fwd", "gnn_pseudo_proj_bwd", "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_gcn_tune",
@@ -63,7 +63,9 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_gat_bwd.argtypes = [vp, i32, i32, i32, f32] + [vp] * 17 + [vp, sz, vp]
     lib.gnn_gat_bwd_noalloc.argtypes = [vp, i32, i32, i32, f32] + [vp] * 17 + [vp]
     lib.gnn_gat_blocked_kernel_name.argtypes = [vp, i32, i32, i32, C.c_char_p, sz]
-    lib.gnn_gat_stash_alpha.argtypes = [vp, i32, f32] + [vp] * 5 + [vp]
+    lib.gnn_gat_stash_alpha.argtypes = [vp, i32, i32, f32] + [vp] * 5 + [vp]
+    lib.gnn_gat_stash_layout.argtypes = [vp, i32, i32]
+    lib.gnn_gat_stash_layout.restype = i32
     lib.gnn_gat_bwd_stashed.argtypes = [vp, i32, i32, i32, f32] + [vp] * 18 + [vp, sz, vp]
     lib.gnn_edgeconv_workspace_bytes.restype = sz
     lib.gnn_edgeconv_workspace_bytes.argtypes = [vp, i32, i32]
@@ -275,8 +277,12 @@ def gnn_gat_bwd_noalloc(g: Graph, fin, heads, f, slope, x, w, a_l, a_r, z, el, e
                                      _f(gw), _f(ga_l), _f(ga_r), _stream(stream)))
 
 
-def gnn_gat_stash_alpha(g: Graph, heads, slope, el, er, m, d, alpha_t, stream=None):
-    _check(lib().gnn_gat_stash_alpha(g.handle, heads, slope, _f(el), _f(er), _f(m), _f(d), _f(alpha_t),
+def gnn_gat_stash_layout(g: Graph, heads, f) -> int:
+    return int(lib().gnn_gat_stash_layout(g.handle, heads, f))
+
+
+def gnn_gat_stash_alpha(g: Graph, heads, f, slope, el, er, m, d, alpha_t, stream=None):
+    _check(lib().gnn_gat_stash_alpha(g.handle, heads, f, slope, _f(el), _f(er), _f(m), _f(d), _f(alpha_t),
                                      _stream(stream)))
 
 

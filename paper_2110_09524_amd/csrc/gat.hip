@@ -1127,15 +1127,20 @@ extern "C" gnn_status_t gnn_gat_bwd_noalloc(const gnn_graph_t* g, int fin, int h
                       nullptr, gout, gx, gw, ga_l, ga_r, ws, (size_t)GNN_NOALLOC_SCRATCH_BYTES, stream);
 }
 
-extern "C" gnn_status_t gnn_gat_stash_alpha(const gnn_graph_t* g, int heads, float slope, const float* el,
+extern "C" int gnn_gat_stash_layout(const gnn_graph_t* g, int heads, int f) {
+  return g != nullptr && heads > 0 && f > 0 && gat_blocked_applies(g, heads, f) ? 1 : 0;
+}
+
+extern "C" gnn_status_t gnn_gat_stash_alpha(const gnn_graph_t* g, int heads, int f, float slope, const float* el,
                                             const float* er, const float* m, const float* d, float* alpha_t,
                                             void* stream) {
   clear_error();
   GNN_REQUIRE(g != nullptr, GNN_ERR_INVALID_ARG, "gnn_gat_stash_alpha: graph is null");
-  GNN_REQUIRE(heads > 0 && heads <= 64, GNN_ERR_INVALID_ARG, "gnn_gat_stash_alpha: heads out of range");
+  GNN_REQUIRE(heads > 0 && heads <= 64 && f > 0, GNN_ERR_INVALID_ARG, "gnn_gat_stash_alpha: sizes out of range");
   if (g->nnz == 0) return GNN_OK;
   GNN_REQUIRE(el && er && m && d && alpha_t, GNN_ERR_INVALID_ARG, "gnn_gat_stash_alpha: null pointer");
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (gat_blocked_applies(g, heads, f)) return gat_blocked_stash_alpha(g, heads, slope, el, er, m, d, alpha_t, st);
   ProfScope p("gat_stash_alpha", st);
   const int64_t count = g->nnz * heads;
   k_gat_stash_alpha<<<(unsigned)cdiv(count, 256), 256, 0, st>>>(count, heads, slope, g->indices, g->indices_t,
@@ -1194,8 +1199,8 @@ static gnn_status_t gat_bwd_impl(const char* who, const gnn_graph_t* g, int fin,
   const GatDims dm = make_dims(heads, f, slope);
   const GroupShape gs = pick_group(HF);
 
-  // the per-edge stash is laid out for the single-launch source-side kernel
-  const bool blocked = alpha_t == nullptr && gat_blocked_applies(g, heads, f);
+  // the per-edge stash is laid out for whichever source-side kernel this graph and shape take
+  const bool blocked = gat_blocked_applies(g, heads, f);
   const int dst_flags = (blocked ? kDstHeadMajor : 0) | (blocked && gat_blocked_half(g, heads, f) ? kDstHalfGout : 0);
   // a4: destination side.  With t and sg stashed by the forward call it is a vertex pass;
   // without them the sums are recomputed over the in-edges.
@@ -1213,7 +1218,8 @@ static gnn_status_t gat_bwd_impl(const char* who, const gnn_graph_t* g, int fin,
   }
   if (blocked) {
     float* scal_buf = reinterpret_cast<float*>(base + L.blk_scal);
-    GNN_TRY(gat_blocked_bwd_src(g, dm, z, el, vstate, der, gout, a_l, a_r, dz, del, scal_buf, gat_blocked_half(g, heads, f) ? base + L.blk_half : nullptr, st));
+    GNN_TRY(gat_blocked_bwd_src(g, dm, z, el, vstate, der, gout, a_l, a_r, dz, del, scal_buf,
+                                gat_blocked_half(g, heads, f) ? base + L.blk_half : nullptr, st, alpha_t));
   } else {
     // a5: source side
     GNN_TRY(dispatch_group<BwdSrcLauncher>(gs, g, z, el, (const float4*)vstate, (const float*)der,

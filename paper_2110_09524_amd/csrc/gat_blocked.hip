@@ -146,7 +146,10 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
     float4* __restrict__ state /* forward modes: running (max, sum, sum2) per (row, slice) */,
     float* __restrict__ m_out, float* __restrict__ d_out,
     int nseg /* adjacent column blocks of this launch (1 .. kMaxMerge): segment j of the row at
-                position r of the degree order is bseg_b[j * n_rows + r] */) {
+                position r of the degree order is bseg_b[j * n_rows + r] */,
+    const float* __restrict__ alpha_b /* MODE 2, nullable: stashed signed softmax values, [H][nnz] in the
+                                         order of bcol (the "fusion with stashing" arm) */,
+    int64_t nnz) {
   constexpr int THREADS = STAGE ? kStageThreads : kBlkThreads;
   constexpr int G = kWave / SL;
   constexpr int GPB = THREADS / SL;
@@ -176,7 +179,7 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
   const float* l_el = lds + GPB * GS;
   // [quad, quad_end): the group's current run of row quadruples (R consecutive rows of the
   // degree order each); a staged group draws the next run from the slice's counter
-  int64_t quad = 0, quad_end = 0;
+  int64_t quad = 0, quad_end = 0, static_iter = 0;
   if (STAGE) {
     float* dst = lds + GPB * GS;
     const float* src = el + (int64_t)h * n_rows + col_begin;
@@ -198,10 +201,16 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
 
   for (;;) {
     if (STAGE && quad == quad_end) {
-      int q = 0;
-      if (li == 0) q = atomicAdd(queue + slice, quads_per_grab);
-      quad = __shfl(q, lane & ~(SL - 1), 64);
-      quad_end = quad + quads_per_grab;
+      if (quads_per_grab > 0) {
+        int q = 0;
+        if (li == 0) q = atomicAdd(queue + slice, quads_per_grab);
+        quad = __shfl(q, lane & ~(SL - 1), 64);
+        quad_end = quad + quads_per_grab;
+      } else {  // static: the groups of a slice take the quadruples round-robin
+        static_iter += 1;
+        quad = (int64_t)(blockIdx.x / ns) * GPB + grp + (static_iter - 1) * (int64_t)(gridDim.x / ns) * GPB;
+        quad_end = quad + 1;
+      }
     }
     const int64_t r0 = quad * R;
     if (r0 >= n_rows) break;  // the counter only grows: every group ends here
@@ -314,8 +323,9 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
           if (c0 + SL + li < end) c_next = bcol[c0 + SL + li];
           l_idx[li] = c;
           // per-edge scalars: issue the loads now, use them after the row loads are in flight
-          float e_a = 0.f;
+          float e_a = 0.f, a_st = 0.f;
           float4 vs = make_float4(0.f, 0.f, 1.f, 0.f);
+          if (MODE == 2 && alpha_b != nullptr && e_ok) a_st = alpha_b[(int64_t)h * nnz + c0 + li];
           if (e_ok) {
             if (MODE == 2) vs = vstate[(int64_t)h * n_rows + c];  // head-major (er, m, 1/d, D) of the destination
             else e_a = STAGE ? l_el[c - col_begin] : (el_hm ? el[(int64_t)h * n_rows + c] : el[(int64_t)c * H + h]);
@@ -365,9 +375,14 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
               float p = 0.f, p2 = 0.f;
               if (e_ok) {
                 if (MODE == 2) {
-                  const float raw = r_a + vs.x;
-                  p = __expf(leaky(raw, dm.slope) - vs.y) * vs.z;
-                  p2 = raw > 0.f ? p : dm.slope * p;
+                  if (alpha_b != nullptr) {  // read back instead of recomputed; D[v] is still gathered
+                    p = fabsf(a_st);
+                    p2 = a_st > 0.f ? p : dm.slope * p;
+                  } else {
+                    const float raw = r_a + vs.x;
+                    p = __expf(leaky(raw, dm.slope) - vs.y) * vs.z;
+                    p2 = raw > 0.f ? p : dm.slope * p;
+                  }
                   s_run = fmaf(p2, vs.w, s_run);
                 } else if (!ONLINE) {
                   const float raw = e_a + r_a;
@@ -578,12 +593,22 @@ static const char* bracket_name(const char* name, size_t launch) {
   return names.emplace(key, key).first->second.c_str();
 }
 
+static int stage_grab() {
+  static const int v = std::getenv("GNN_STAGE_GRAB") ? std::atoi(std::getenv("GNN_STAGE_GRAB")) : 1;
+  return v;
+}
+static int stage_min_edges() {
+  static const int v = std::getenv("GNN_STAGE_MIN") ? std::atoi(std::getenv("GNN_STAGE_MIN")) : 48;
+  return v;
+}
+
 template <int SL, int MODE, bool HALF, bool SKIP>
 static gnn_status_t launch_blocks_impl(const gnn_graph_t* g, int side, const char* name, GatDims dm,
                                   int el_hm, const float* feat, const float* rowfeat,
                                   const float* el, const float* er, const float* m, const float* d,
                                   const float4* vstate, float* acc, float* acc2, float* scal,
-                                  int32_t* queue, float4* state, float* m_out, float* d_out, hipStream_t st) {
+                                  int32_t* queue, float4* state, float* m_out, float* d_out, hipStream_t st,
+                                  const float* alpha_b = nullptr) {
   const int ns = dm.HF / ((HALF ? 8 : 4) * SL);
   const int sph = ns / dm.H;
   // 32-bit byte offsets (and 24-bit multiplies) reach every gathered row
@@ -626,7 +651,7 @@ static gnn_status_t launch_blocks_impl(const gnn_graph_t* g, int side, const cha
       const int64_t edges = (int64_t)g->h_block_begin[side][b_end] - g->h_block_begin[side][b];
       const int64_t cols_wide = (int64_t)nseg * g->block_cols;
       const size_t stage_bytes = staged_lds_bytes<SL>(cols_wide);
-      staged = stage_ok && stage_bytes <= kStageLdsLimit && edges >= (int64_t)kStageMinEdgesPerRow * g->n;
+      staged = stage_ok && stage_bytes <= kStageLdsLimit && edges >= (int64_t)stage_min_edges() * g->n;
       if (staged) {
         const int32_t cols_here = (int32_t)(g->n - col_begin < cols_wide ? g->n - col_begin : cols_wide);
         // one persistent workgroup per CU, a multiple of 8 so that every XCD serves one slice
@@ -634,8 +659,8 @@ static gnn_status_t launch_blocks_impl(const gnn_graph_t* g, int side, const cha
         ProfScope p(bracket_name(name, gi), st);  // one timed bracket per launch
         k_gat_blk<SL, MODE, true, HALF, SKIP><<<pgrid, kStageThreads, stage_bytes, st>>>(
             g->n, g->order[side], bseg_b, g->bcol[side], feat, rowfeat, el, er, m, d, vstate, col_begin, dm, sph,
-            b == 0, narrow, el_hm, acc, acc2, scal, queue + b * kSlices, cols_here, 1, ns, b_end == g->nblk, state,
-            m_out, d_out, nseg);
+            b == 0, narrow, el_hm, acc, acc2, scal, queue + b * kSlices, cols_here, stage_grab(), ns, b_end == g->nblk, state,
+            m_out, d_out, nseg, alpha_b, g->nnz);
         GNN_LAUNCH_CHECK();
       }
     }
@@ -643,7 +668,8 @@ static gnn_status_t launch_blocks_impl(const gnn_graph_t* g, int side, const cha
       ProfScope p(bracket_name(name, gi), st);  // one timed bracket per launch
       k_gat_blk<SL, MODE, false, HALF, SKIP><<<grid, kBlkThreads, lds, st>>>(
           g->n, g->order[side], bseg_b, g->bcol[side], feat, rowfeat, el, er, m, d, vstate, col_begin, dm, sph,
-          b == 0, narrow, el_hm, acc, acc2, scal, nullptr, 0, 1, ns, b_end == g->nblk, state, m_out, d_out, nseg);
+          b == 0, narrow, el_hm, acc, acc2, scal, nullptr, 0, 1, ns, b_end == g->nblk, state, m_out, d_out, nseg,
+          alpha_b, g->nnz);
       GNN_LAUNCH_CHECK();
     }
   }
@@ -655,14 +681,15 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
                                   int el_hm, const float* feat, const float* rowfeat,
                                   const float* el, const float* er, const float* m, const float* d,
                                   const float4* vstate, float* acc, float* acc2, float* scal,
-                                  int32_t* queue, float4* state, float* m_out, float* d_out, hipStream_t st) {
+                                  int32_t* queue, float4* state, float* m_out, float* d_out, hipStream_t st,
+                                  const float* alpha_b = nullptr) {
   const int ns = dm.HF / ((HALF ? 8 : 4) * SL);
   // the fp16 variant (one sub-iteration per chunk) measured 3 % slower with the skip
   if (ns >= 4 && !HALF)
     return launch_blocks_impl<SL, MODE, HALF, true>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2,
-                                                    scal, queue, state, m_out, d_out, st);
+                                                    scal, queue, state, m_out, d_out, st, alpha_b);
   return launch_blocks_impl<SL, MODE, HALF, false>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2,
-                                                   scal, queue, state, m_out, d_out, st);
+                                                   scal, queue, state, m_out, d_out, st, alpha_b);
 }
 
 template <int MODE>
@@ -670,19 +697,19 @@ static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name,
                                int el_hm, const float* feat, const float* rowfeat, const float* el, const float* er, const float* m,
                                const float* d, const float4* vstate, float* acc, float* acc2,
                                float* scal, int32_t* queue, float4* state, float* m_out, float* d_out,
-                               hipStream_t st, bool half_feat = false) {
+                               hipStream_t st, bool half_feat = false, const float* alpha_b = nullptr) {
   if (half_feat) {
     if constexpr (MODE != 1)
       return launch_blocks<8, MODE, true>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal,
-                                          queue, state, m_out, d_out, st);
+                                          queue, state, m_out, d_out, st, alpha_b);
   }
   Slicing sl;
   if (!pick_slicing(dm.H, dm.HF, sl)) sl.SL = 0;
   switch (sl.SL) {
-    case 4: return launch_blocks<4, MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
-    case 8: return launch_blocks<8, MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
-    case 16: return launch_blocks<16, MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
-    case 32: return launch_blocks<32, MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st);
+    case 4: return launch_blocks<4, MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st, alpha_b);
+    case 8: return launch_blocks<8, MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st, alpha_b);
+    case 16: return launch_blocks<16, MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st, alpha_b);
+    case 32: return launch_blocks<32, MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st, alpha_b);
   }
   set_error("gat blocked: unsupported slice width");
   return GNN_ERR_UNSUPPORTED;
@@ -741,10 +768,43 @@ __global__ void k_gat_src_finish_blk(int64_t n, GatDims dm, int ns, const float*
   st4(dz + u * dm.HF + col, o);
 }
 
+// The per-edge stash of the "fusion with stashing" arm in the order the source-side kernel walks:
+// alpha_b[h][q] for position q of the source side's blocked edge list = softmax value of that edge
+// with the sign of its raw score.  One 16-lane group per source row, its segments block by block.
+__global__ __launch_bounds__(256) void k_gat_stash_alpha_blk(
+    int32_t n, int32_t nblk, int64_t nnz, int H, float slope, const int32_t* __restrict__ bptr,
+    const int32_t* __restrict__ bcol, const float* __restrict__ el, const float* __restrict__ er,
+    const float* __restrict__ m, const float* __restrict__ d, float* __restrict__ alpha_b) {
+  const int li = threadIdx.x & 15;
+  const int64_t u = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) >> 4;
+  if (u >= n) return;
+  for (int b = 0; b < nblk; ++b) {
+    const int32_t beg = bptr[(int64_t)b * n + u], end = bptr[(int64_t)b * n + u + 1];
+    for (int32_t q = beg + li; q < end; q += 16) {
+      const int64_t v = bcol[q];
+      for (int h = 0; h < H; ++h) {
+        const float raw = el[u * H + h] + er[v * H + h];
+        const float a = __expf(leaky(raw, slope) - m[v * H + h]) / d[v * H + h];
+        alpha_b[(int64_t)h * nnz + q] = raw > 0.f ? a : -a;
+      }
+    }
+  }
+}
+
+gnn_status_t gat_blocked_stash_alpha(const gnn_graph_t* g, int H, float slope, const float* el, const float* er,
+                                     const float* m, const float* d, float* alpha_b, hipStream_t st) {
+  ProfScope p("gat_stash_alpha", st);
+  k_gat_stash_alpha_blk<<<(unsigned)cdiv((int64_t)g->n * 16, 256), 256, 0, st>>>(
+      g->n, g->nblk, g->nnz, H, slope, g->bptr[1], g->bcol[1], el, er, m, d, alpha_b);
+  GNN_LAUNCH_CHECK();
+  return GNN_OK;
+}
+
 gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* z, const float* el,
                                  const float4* vstate, const float* der, const float* gout,
                                  const float* a_l, const float* a_r, float* dz, float* del,
-                                 float* sd_buf /* [n][8] scratch */, void* half_buf, hipStream_t st) {
+                                 float* sd_buf /* [n][8] scratch */, void* half_buf, hipStream_t st,
+                                 const float* alpha_b) {
   const bool half = half_buf != nullptr && gat_blocked_half(g, dm.H, dm.F);
   const float* feat = gout;
   if (half) {
@@ -752,7 +812,7 @@ gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* 
     feat = static_cast<const float*>(half_buf);
   }
   GNN_TRY(run_blocks<2>(g, 1, "gat_bwd_src", dm, 0, feat, z, el, nullptr, nullptr, nullptr, vstate, dz,
-                        nullptr, sd_buf, nullptr, nullptr, nullptr, nullptr, st, half));
+                        nullptr, sd_buf, nullptr, nullptr, nullptr, nullptr, st, half, alpha_b));
   Slicing sl;
   int ns = 0;
   if (half) ns = dm.HF / 64;

@@ -60,6 +60,10 @@ gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* 
                                  const float4* vstate, const float* der, const float* gout,
                                  const float* a_l, const float* a_r, float* dz, float* del,
                                  float* sd_buf, void* half_buf /* n * HF * 2 bytes or null */,
-                                 hipStream_t st);
+                                 hipStream_t st,
+                                 const float* alpha_b = nullptr /* [H][nnz] stash in blocked order, or null */);
+// writes the per-edge stash in the order gat_blocked_bwd_src reads it
+gnn_status_t gat_blocked_stash_alpha(const gnn_graph_t* g, int H, float slope, const float* el, const float* er,
+                                     const float* m, const float* d, float* alpha_b, hipStream_t st);
 
 }  // namespace gnn

@@ -134,7 +134,7 @@ def run_gat(c, backward=True, want_gx=True, graph=None, stash=True, alpha_stash=
     alpha_t = None
     if alpha_stash:
         alpha_t = empty((max(len(c["indices"]), 1), H))
-        pk.gnn_gat_stash_alpha(g, H, c["slope"], el, er, m, d, alpha_t)
+        pk.gnn_gat_stash_alpha(g, H, F, c["slope"], el, er, m, d, alpha_t)
         res["alpha_t"] = alpha_t
     if backward:
         gout = dev(c["gout"])

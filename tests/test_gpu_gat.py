@@ -366,13 +366,25 @@ def test_fusion_with_stashing_arm_on_a_column_blocked_graph_and_bad_arguments():
     indptr, indices = random_graph(rng, 1500, 30000, self_loops=False, duplicates=True)
     c = synth(rng, indptr, indices, 24, 4, 64)
     fwd, bwd = oracle_all(c)
+    from gpu_harness import assert_close
+    n, nnz, H = c["n"], c["nnz"], c["heads"]
     pk.gnn_config_set("block_cols", 256)
     try:
         g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
-        res = run_gat(c, graph=g, alpha_stash=True)      # forward blocked, stashed backward single-launch
+        assert pk.gnn_gat_stash_layout(g, 4, 64) == 1    # the stash is laid out for the column-blocked kernel
+        res = run_gat(c, graph=g, alpha_stash=True)      # forward and stashed backward both column-blocked
     finally:
         pk.gnn_config_set("block_cols", 20480)
-    res.pop("alpha_t")
+    # layout 1: [h][q], q = position in the source side's blocked list = the CSC entries (source,
+    # CSR position) stable-sorted by (block of the destination, source)
+    csc = np.lexsort((np.arange(nnz), c["indices"]))
+    dst = np.repeat(np.arange(n), np.diff(c["indptr"]))
+    key = (dst[csc] // 256).astype(np.int64) * n + c["indices"][csc]
+    order = csc[np.argsort(key, kind="stable")]
+    ref = (fwd["M2"] * np.where(fwd["M0"] > 0, 1.0, -1.0))[order].T
+    got = res.pop("alpha_t").reshape(-1)[:H * nnz].reshape(H, nnz)
+    near_kink = np.abs(fwd["M0"][order]).T < 1e-5
+    assert_close("alpha_b", np.where(near_kink, ref, got), ref)
     compare(c, res, fwd, bwd)
     a = empty((4, 4))
     with pytest.raises(pk.GnnError) as e:
