@@ -179,7 +179,7 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
   const float* l_el = lds + GPB * GS;
   // [quad, quad_end): the group's current run of row quadruples (R consecutive rows of the
   // degree order each); a staged group draws the next run from the slice's counter
-  int64_t quad = 0, quad_end = 0, static_iter = 0;
+  int64_t quad = 0, quad_end = 0;
   if (STAGE) {
     float* dst = lds + GPB * GS;
     const float* src = el + (int64_t)h * n_rows + col_begin;
@@ -201,16 +201,14 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
 
   for (;;) {
     if (STAGE && quad == quad_end) {
-      if (quads_per_grab > 0) {
-        int q = 0;
-        if (li == 0) q = atomicAdd(queue + slice, quads_per_grab);
-        quad = __shfl(q, lane & ~(SL - 1), 64);
-        quad_end = quad + quads_per_grab;
-      } else {  // static: the groups of a slice take the quadruples round-robin
-        static_iter += 1;
-        quad = (int64_t)(blockIdx.x / ns) * GPB + grp + (static_iter - 1) * (int64_t)(gridDim.x / ns) * GPB;
-        quad_end = quad + 1;
-      }
+      // One quadruple per draw: the rows come in degree order, so consecutive quadruples of the hub
+      // rows are all heavy, and a group that took several at once would be the last to finish
+      // (measured on the hub block of a Reddit-scale graph: 2.7 ms with one per draw, 6.9 ms with
+      // four, 4.8 ms with a static round-robin assignment).
+      int q = 0;
+      if (li == 0) q = atomicAdd(queue + slice, quads_per_grab);
+      quad = __shfl(q, lane & ~(SL - 1), 64);
+      quad_end = quad + quads_per_grab;
     }
     const int64_t r0 = quad * R;
     if (r0 >= n_rows) break;  // the counter only grows: every group ends here
@@ -593,15 +591,6 @@ static const char* bracket_name(const char* name, size_t launch) {
   return names.emplace(key, key).first->second.c_str();
 }
 
-static int stage_grab() {
-  static const int v = std::getenv("GNN_STAGE_GRAB") ? std::atoi(std::getenv("GNN_STAGE_GRAB")) : 1;
-  return v;
-}
-static int stage_min_edges() {
-  static const int v = std::getenv("GNN_STAGE_MIN") ? std::atoi(std::getenv("GNN_STAGE_MIN")) : 48;
-  return v;
-}
-
 template <int SL, int MODE, bool HALF, bool SKIP>
 static gnn_status_t launch_blocks_impl(const gnn_graph_t* g, int side, const char* name, GatDims dm,
                                   int el_hm, const float* feat, const float* rowfeat,
@@ -651,7 +640,7 @@ static gnn_status_t launch_blocks_impl(const gnn_graph_t* g, int side, const cha
       const int64_t edges = (int64_t)g->h_block_begin[side][b_end] - g->h_block_begin[side][b];
       const int64_t cols_wide = (int64_t)nseg * g->block_cols;
       const size_t stage_bytes = staged_lds_bytes<SL>(cols_wide);
-      staged = stage_ok && stage_bytes <= kStageLdsLimit && edges >= (int64_t)stage_min_edges() * g->n;
+      staged = stage_ok && stage_bytes <= kStageLdsLimit && edges >= (int64_t)kStageMinEdgesPerRow * g->n;
       if (staged) {
         const int32_t cols_here = (int32_t)(g->n - col_begin < cols_wide ? g->n - col_begin : cols_wide);
         // one persistent workgroup per CU, a multiple of 8 so that every XCD serves one slice
@@ -659,7 +648,7 @@ static gnn_status_t launch_blocks_impl(const gnn_graph_t* g, int side, const cha
         ProfScope p(bracket_name(name, gi), st);  // one timed bracket per launch
         k_gat_blk<SL, MODE, true, HALF, SKIP><<<pgrid, kStageThreads, stage_bytes, st>>>(
             g->n, g->order[side], bseg_b, g->bcol[side], feat, rowfeat, el, er, m, d, vstate, col_begin, dm, sph,
-            b == 0, narrow, el_hm, acc, acc2, scal, queue + b * kSlices, cols_here, stage_grab(), ns, b_end == g->nblk, state,
+            b == 0, narrow, el_hm, acc, acc2, scal, queue + b * kSlices, cols_here, 1, ns, b_end == g->nblk, state,
             m_out, d_out, nseg, alpha_b, g->nnz);
         GNN_LAUNCH_CHECK();
       }
