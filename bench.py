@@ -610,7 +610,7 @@ def main():
     # the very kernel instantiation this run launched (the library names it)
     tv = read_traffic(args.workload)
     traffic, traffic_kernel = None, None
-    if tv and tv.get("kernel") == dom:
+    if tv and dom in [k.strip() for k in tv.get("kernel", "").split(",")]:   # one kernel may serve several passes
         if kind == "gat":
             mode = {"gat_bwd_src": 2, "gat_bwd_dst": 1, "gat_fwd_fused": 3 if t is not None else 0}.get(dom)
             traffic_kernel = pk.gnn_gat_blocked_kernel_name(g, H, F, mode) if mode is not None else None
