@@ -298,6 +298,9 @@ def main():
                     help="use the single-launch kernels also where the column-blocked ones apply")
     ap.add_argument("--block-cols", type=int, default=None,
                     help="gathered vertices per column block of the blocked edge lists (library default 20480)")
+    ap.add_argument("--no-pseudo-t", action="store_true",
+                    help="MoNet workloads: the backward pass reads the pseudo-coordinates through the plan's "
+                         "position -> edge table instead of a second copy in the transposed list's order")
     ap.add_argument("--no-merge-blocks", action="store_true",
                     help="one launch per column block instead of merged launches over sparse blocks")
     ap.add_argument("--compare-unfused", action="store_true",
@@ -495,6 +498,7 @@ def main():
         w_fc, cc, mu, inv_sigma = to(c["w_fc"]), to(c["c"]), to(c["mu"]), to(c["inv_sigma"])
         proj_w, proj_b = to(c["proj_w"]), to(c["proj_b"])
         pseudo, gpseudo = new(e, R), new(e, R)
+        pseudo_t = None if args.no_pseudo_t else new(e, R)   # the coordinates in the transposed list's order
         hk, out = new(n, K * F), new(n, F)
         gx, gw_fc, gmu, gis = new(n, fin), new(fin, K * F), new(K, R), new(K, R)
         gproj_w, gproj_b = new(R, 2), new(R)
@@ -502,16 +506,16 @@ def main():
         ws = new(max(ws_bytes, 16), dtype=torch.uint8)
 
         def step():
-            pk.gnn_pseudo_proj_fwd(g, R, cc, proj_w, proj_b, pseudo)
+            pk.gnn_pseudo_proj_fwd(g, R, cc, proj_w, proj_b, pseudo, pseudo_t=pseudo_t)
             pk.gnn_gmmp_fwd(g, fin, F, K, R, x, w_fc, pseudo, mu, inv_sigma, hk, out)
             pk.gnn_gmmp_bwd(g, fin, F, K, R, x, w_fc, pseudo, mu, inv_sigma, hk, gout, gx, gw_fc, gmu, gis,
-                            gpseudo, ws)
+                            gpseudo, ws, pseudo_t=pseudo_t)
             pk.gnn_pseudo_proj_bwd(g, R, cc, pseudo, gpseudo, gproj_w, gproj_b, ws)
         V, I = 4 * n * F, 4 * e + 8 * n
         unique = {"gmmp_fwd_fused": I + 4 * e * R + K * V + V, "gmmp_bwd_dst": I + 8 * e * R + K * V + V,
-                  "gmmp_bwd_src": 2 * I + 4 * e * R + V + K * V}
+                  "gmmp_bwd_src": (1 if pseudo_t is not None else 2) * I + 4 * e * R + V + K * V}
         gather = {"gmmp_fwd_fused": e * (4 + 4 * R + 4 * K * F), "gmmp_bwd_dst": e * (4 + 8 * R + 4 * K * F),
-                  "gmmp_bwd_src": e * (8 + 4 * R + 4 * F)}
+                  "gmmp_bwd_src": e * ((4 if pseudo_t is not None else 8) + 4 * R + 4 * F)}
         flops = {"gmmp_fwd_fused": e * K * (2 * F + 4 * R + 8), "gmmp_bwd_dst": e * K * (2 * F + 10 * R + 10),
                  "gmmp_bwd_src": e * K * (2 * F + 4 * R + 8)}
         metric = "MoNet/GMM layer with projected pseudo-coordinates fwd+bwd edges/sec"

@@ -370,12 +370,19 @@ gnn_status_t gnn_gmm_tune(gnn_graph_t* graph, int fout, int k, const float* hk /
  *   out[v] = (1/k) sum over in-edges e = (u -> v) sum_j w_j(e) hk[u,j,:],   hk = x w_fc
  * pseudo [nnz, r] is a per-edge INPUT in CSR order (position e of `indices`).  The backward
  * call recomputes the weights and also returns gpseudo [nnz, r] (nullable), the gradient
- * with respect to the pseudo-coordinates, for a caller that learns them.
+ * with respect to the pseudo-coordinates, for a caller that learns them.  pseudo_t (nullable)
+ * holds the same coordinates in the order of the transposed edge list (position p of
+ * gnn_graph_get_csc's indices_t): the source side of backward walks that list, and without
+ * pseudo_t it reads pseudo through the plan's position -> edge table, one scattered 4r-byte read
+ * per edge (3.2 against 1.4 ms at Reddit scale).  Rows of up to 64 projected floats (k fout <= 64,
+ * the paper's 16 hidden features) take kernels that walk an edge set in chunks with 8 gathers
+ * in flight per lane.
  * Limits: k <= 4, r <= 4, fout % 4 == 0, fout <= 256.  Errors as for gnn_gmm_*.
  *
  * gnn_pseudo_proj_fwd / _bwd: the projection that makes such coordinates from a per-vertex
  * scalar c (1/sqrt(degree) in the paper's models): pseudo[e,d] = tanh(proj_w[d,0] c[u] +
- * proj_w[d,1] c[v] + proj_b[d]); backward returns gproj_w [r,2], gproj_b [r] from gpseudo
+ * proj_w[d,1] c[v] + proj_b[d]), written in CSR order to pseudo and, if pseudo_t is not null, in the
+ * transposed list's order to pseudo_t (computed from c a second time, not permuted); backward returns gproj_w [r,2], gproj_b [r] from gpseudo
  * (workspace of gnn_pseudo_proj_workspace_bytes, sums in a fixed order).
  * ------------------------------------------------------------------------- */
 size_t gnn_gmmp_workspace_bytes(const gnn_graph_t* graph, int fin, int fout, int k);
@@ -387,11 +394,11 @@ gnn_status_t gnn_gmmp_bwd(const gnn_graph_t* graph, int fin, int fout, int k, in
                           const float* w_fc, const float* pseudo, const float* mu, const float* inv_sigma,
                           const float* hk, const float* gout /*[n,fout]*/, float* gx /*nullable*/,
                           float* gw_fc, float* gmu, float* ginv_sigma, float* gpseudo /*[nnz,r] nullable*/,
-                          void* ws, size_t ws_bytes, void* stream);
+                          const float* pseudo_t /*[nnz,r] nullable*/, void* ws, size_t ws_bytes, void* stream);
 size_t gnn_pseudo_proj_workspace_bytes(const gnn_graph_t* graph);
 gnn_status_t gnn_pseudo_proj_fwd(const gnn_graph_t* graph, int r, const float* c /*[n]*/,
                                  const float* proj_w /*[r,2]*/, const float* proj_b /*[r]*/,
-                                 float* pseudo /*[nnz,r]*/, void* stream);
+                                 float* pseudo /*[nnz,r]*/, float* pseudo_t /*[nnz,r] nullable*/, void* stream);
 gnn_status_t gnn_pseudo_proj_bwd(const gnn_graph_t* graph, int r, const float* c, const float* pseudo,
                                  const float* gpseudo, float* gproj_w /*[r,2]*/, float* gproj_b /*[r]*/,
                                  void* ws, size_t ws_bytes, void* stream);

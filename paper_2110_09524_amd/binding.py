@@ -79,10 +79,10 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_gmmp_workspace_bytes.restype = sz
     lib.gnn_gmmp_workspace_bytes.argtypes = [vp, i32, i32, i32]
     lib.gnn_gmmp_fwd.argtypes = [vp, i32, i32, i32, i32] + [vp] * 7 + [vp]
-    lib.gnn_gmmp_bwd.argtypes = [vp, i32, i32, i32, i32] + [vp] * 12 + [vp, sz, vp]
+    lib.gnn_gmmp_bwd.argtypes = [vp, i32, i32, i32, i32] + [vp] * 13 + [vp, sz, vp]
     lib.gnn_pseudo_proj_workspace_bytes.restype = sz
     lib.gnn_pseudo_proj_workspace_bytes.argtypes = [vp]
-    lib.gnn_pseudo_proj_fwd.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+    lib.gnn_pseudo_proj_fwd.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.gnn_pseudo_proj_bwd.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.gnn_gcn_workspace_bytes.restype = sz
     lib.gnn_gcn_workspace_bytes.argtypes = [vp, i32, i32]
@@ -387,19 +387,20 @@ def gnn_gmmp_fwd(g: Graph, fin, fout, k, r, x, w_fc, pseudo, mu, inv_sigma, hk, 
 
 
 def gnn_gmmp_bwd(g: Graph, fin, fout, k, r, x, w_fc, pseudo, mu, inv_sigma, hk, gout, gx, gw_fc, gmu, ginv_sigma,
-                 gpseudo, ws, stream=None):
+                 gpseudo, ws, stream=None, pseudo_t=None):
     wp, wb = _ws_args(ws)
     _check(lib().gnn_gmmp_bwd(g.handle, fin, fout, k, r, _f(x), _f(w_fc), _f(pseudo), _f(mu), _f(inv_sigma),
-                              _f(hk), _f(gout), _f(gx), _f(gw_fc), _f(gmu), _f(ginv_sigma), _f(gpseudo), wp, wb,
-                              _stream(stream)))
+                              _f(hk), _f(gout), _f(gx), _f(gw_fc), _f(gmu), _f(ginv_sigma), _f(gpseudo),
+                              _f(pseudo_t), wp, wb, _stream(stream)))
 
 
 def gnn_pseudo_proj_workspace_bytes(g: Graph) -> int:
     return int(lib().gnn_pseudo_proj_workspace_bytes(g.handle))
 
 
-def gnn_pseudo_proj_fwd(g: Graph, r, c, proj_w, proj_b, pseudo, stream=None):
-    _check(lib().gnn_pseudo_proj_fwd(g.handle, r, _f(c), _f(proj_w), _f(proj_b), _f(pseudo), _stream(stream)))
+def gnn_pseudo_proj_fwd(g: Graph, r, c, proj_w, proj_b, pseudo, stream=None, pseudo_t=None):
+    _check(lib().gnn_pseudo_proj_fwd(g.handle, r, _f(c), _f(proj_w), _f(proj_b), _f(pseudo), _f(pseudo_t),
+                                     _stream(stream)))
 
 
 def gnn_pseudo_proj_bwd(g: Graph, r, c, pseudo, gpseudo, gproj_w, gproj_b, ws, stream=None):

@@ -15,6 +15,7 @@
 //   source side (CSC walk, no atomics): dhk[u,k,:] = (1/K) sum_out-edges w_k(e) gout[v,:],
 //     with m read through the plan's CSC position -> CSR edge id table.
 // At most 4 kernels and 4 pseudo-coordinate dimensions; fout <= 256.
+#include <algorithm>
 #include <type_traits>
 
 #include "common.h"
@@ -215,7 +216,8 @@ template <int L>
 __global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_src(
     RowLaunch rl, const int32_t* __restrict__ order_t, const int32_t* __restrict__ indptr_t,
     const int32_t* __restrict__ indices_t, const int32_t* __restrict__ eid_t,
-    const float* __restrict__ pseudo, const float* __restrict__ mu, const float* __restrict__ inv_sigma,
+    const float* __restrict__ pseudo, const float* __restrict__ pseudo_t /* nullable: pseudo in this walk's order */,
+    const float* __restrict__ mu, const float* __restrict__ inv_sigma,
     const float* __restrict__ gout, PsParams pm, float* __restrict__ dhk) {
   constexpr int GPB = kPsBlock / L;
   __shared__ float coop_buf[GPB * L * 4 * kPsK];
@@ -237,7 +239,8 @@ __global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_src(
   for (int32_t p = beg + gi; p < end; p += ngrp) {
     const int32_t v = indices_t[p];
     float m[kPsR];
-    load_pseudo(pseudo, eid_t[p], R, m);
+    if (pseudo_t != nullptr) load_pseudo(pseudo_t, p, R, m);
+    else load_pseudo(pseudo, eid_t[p], R, m);
     if (col_ok) {
       const float4 g4 = ld4(gout + (int64_t)v * F + 4 * li);
 #pragma unroll
@@ -261,20 +264,354 @@ __global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_src(
   }
 }
 
+// ---- narrow rows (K * fout <= 64 floats): chunks of edges, gathered rows in flight ------------
+// With 16 hidden features (the paper's MoNet settings) a projected row hk[u] is 128-192 bytes.  The
+// kernels above then spend their time on the per-edge chain index -> row -> arithmetic, taken one
+// edge at a time (measured at Reddit scale with every gather served by the L2: forward 1.4 of 1.6 ms,
+// so the fabric behind the L2s is not what bounds them).  Here a group of G lanes owns the row and
+// one float4 of hk[u, :, :] per lane (lane li: kernel li / (F/4), columns 4 (li % (F/4))), and an edge
+// set is walked in chunks of G edges in two phases, as in the attention kernels:
+//   chunk phase: lane li takes edge li of the chunk: index, pseudo-coordinates, the K Gaussian
+//                weights; index and weights are parked in LDS;
+//   row phase:   every lane reads them back (broadcast reads) and has 8 row loads in flight.
+// LDS traffic of a group stays inside its wavefront.
+constexpr int kNrU = 8;  // gathered rows in flight per lane
+
+// LDS floats of a group: G indices, then kPsK x G weights (forward, source side) or G x G partial
+// dot products (destination side)
+template <int G>
+constexpr int kNrGroupFloats = G + (kPsK > G ? kPsK : G) * G;
+
+__device__ __forceinline__ void read8i(const int* p, int (&v)[kNrU]) {
+  const int4 a = *reinterpret_cast<const int4*>(p), b = *reinterpret_cast<const int4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void read8f(const float* p, float (&v)[kNrU]) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
+// forward: out[v, f] = (1/K) sum_e sum_k w_k(e) hk[u, k, f]; the sum over k is taken last, across lanes
+template <int G>
+__global__ __launch_bounds__(kPsBlock) void k_gmmp_fwd_nr(
+    RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    const int32_t* __restrict__ indices, const float* __restrict__ hk, const float* __restrict__ pseudo,
+    const float* __restrict__ mu, const float* __restrict__ inv_sigma, PsParams pm, float* __restrict__ out) {
+  constexpr int GPB = kPsBlock / G;
+  constexpr int GS = kNrGroupFloats<G>;
+  __shared__ __align__(16) float lds[GPB * GS];
+  __shared__ float coop_buf[GPB * G * 4];
+  const int lane = threadIdx.x & 63;
+  const int li = threadIdx.x & (G - 1);
+  const int grp = threadIdx.x / G;
+  int64_t r;
+  int gi, ngrp;
+  RowRange rr;
+  if (!pick_row<GPB>(rl, grp, rr, r, gi, ngrp)) return;
+  const int K = pm.K, R = pm.R, F = pm.F, KF = K * F, F4 = F / 4;
+  const float inv_k = 1.f / (float)K;
+  const PsKernels pk = load_kernels(mu, inv_sigma, K, R);
+  const int32_t v = order[r];
+  const int32_t beg = indptr[v], end = indptr[v + 1];
+  const bool col_ok = li < K * F4;
+  const int myk = col_ok ? li / F4 : 0;
+  int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
+  float* l_w = lds + grp * GS + G;  // [kPsK][G]
+  const float* my_row = hk + 4 * li;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f), part = acc;
+  int folded = 0;
+  for (int32_t e0 = beg + gi * G; e0 < end; e0 += ngrp * G) {
+    const bool e_ok = e0 + li < end;
+    const int cnt = min(G, end - e0);
+    int32_t u = 0;
+    float m[kPsR];
+#pragma unroll
+    for (int d = 0; d < kPsR; ++d) m[d] = 0.f;
+    if (e_ok) {
+      u = indices[e0 + li];
+      load_pseudo(pseudo, e0 + li, R, m);
+    }
+    wave_lds_fence();  // the previous chunk's reads are done
+    l_idx[li] = u;
+#pragma unroll
+    for (int k = 0; k < kPsK; ++k)
+      if (k < K) l_w[k * G + li] = e_ok ? gauss_k(pk, k, m) * inv_k : 0.f;
+    wave_lds_fence();
+#pragma unroll
+    for (int t0 = 0; t0 < G; t0 += kNrU) {
+      if (t0 < cnt) {
+        int idv[kNrU];
+        float wv[kNrU];
+        read8i(l_idx + t0, idv);
+        float4 rowv[kNrU];
+#pragma unroll
+        for (int t = 0; t < kNrU; ++t)
+          if (col_ok && t0 + t < cnt) rowv[t] = ld4(my_row + (int64_t)idv[t] * KF);
+        read8f(l_w + myk * G + t0, wv);
+#pragma unroll
+        for (int t = 0; t < kNrU; ++t)
+          if (col_ok && t0 + t < cnt) fma4(part, wv[t], rowv[t]);
+      }
+    }
+    folded += G;
+    if (folded >= 32) {  // two-level summation keeps long rows accurate
+      add4(acc, part);
+      part = make_float4(0.f, 0.f, 0.f, 0.f);
+      folded = 0;
+    }
+  }
+  add4(acc, part);
+  // kernels 1 .. K-1 sit F/4 lanes further on: add them in order
+  float4 tot = acc;
+  const int base = lane & ~(G - 1);
+  for (int k = 1; k < K; ++k) {
+    const int srcl = base + ((li + k * F4) & (G - 1));
+    tot.x += __shfl(acc.x, srcl, 64);
+    tot.y += __shfl(acc.y, srcl, 64);
+    tot.z += __shfl(acc.z, srcl, 64);
+    tot.w += __shfl(acc.w, srcl, 64);
+  }
+  if (rr.coop) {
+    float vv[4];
+    pack4(vv, tot);
+    coop_sum<G, 4, GPB>(coop_buf, vv, grp, li);
+    if (grp != 0) return;
+    tot = unpack4(vv);
+  }
+  if (li < F4) st4(out + (int64_t)v * F + 4 * li, tot);
+}
+
+// destination side of backward: the row phase leaves every lane's part of <gout[v], hk[u, k, :]> in
+// LDS, and the lane that owns the edge adds the F/4 parts of each kernel in lane order
+template <int G>
+__global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_dst_nr(
+    RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
+    const int32_t* __restrict__ indices, const float* __restrict__ hk, const float* __restrict__ pseudo,
+    const float* __restrict__ mu, const float* __restrict__ inv_sigma, const float* __restrict__ gout,
+    PsParams pm, float* __restrict__ partial, float* __restrict__ gpseudo /* nullable */) {
+  constexpr int GPB = kPsBlock / G;
+  constexpr int GS = kNrGroupFloats<G>;
+  __shared__ __align__(16) float lds[GPB * GS];
+  __shared__ float blk[GPB][kPsVals];
+  const int li = threadIdx.x & (G - 1);
+  const int grp = threadIdx.x / G;
+  int64_t r;
+  int gi, ngrp;
+  RowRange rr;
+  const bool active = pick_row<GPB>(rl, grp, rr, r, gi, ngrp);
+  const int K = pm.K, R = pm.R, F = pm.F, KF = K * F, F4 = F / 4;
+  const float inv_k = 1.f / (float)K;
+  float gm_acc[kPsK][kPsR], gs_acc[kPsK][kPsR];  // sums over the edges this lane owned
+#pragma unroll
+  for (int k = 0; k < kPsK; ++k)
+#pragma unroll
+    for (int d = 0; d < kPsR; ++d) {
+      gm_acc[k][d] = 0.f;
+      gs_acc[k][d] = 0.f;
+    }
+  if (active) {
+    const PsKernels pk = load_kernels(mu, inv_sigma, K, R);
+    const int32_t v = order[r];
+    const int32_t beg = indptr[v], end = indptr[v + 1];
+    const bool col_ok = li < K * F4;
+    const int f4 = col_ok ? li % F4 : 0;
+    const float4 g4 = col_ok ? ld4(gout + (int64_t)v * F + 4 * f4) : make_float4(0.f, 0.f, 0.f, 0.f);
+    int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
+    float* l_d = lds + grp * GS + G;  // [column lane][edge of the chunk]
+    const float* my_row = hk + 4 * li;
+    for (int32_t e0 = beg + gi * G; e0 < end; e0 += ngrp * G) {
+      const bool e_ok = e0 + li < end;
+      const int cnt = min(G, end - e0);
+      int32_t u = 0;
+      float m[kPsR];
+#pragma unroll
+      for (int d = 0; d < kPsR; ++d) m[d] = 0.f;
+      if (e_ok) {
+        u = indices[e0 + li];
+        load_pseudo(pseudo, e0 + li, R, m);
+      }
+      wave_lds_fence();
+      l_idx[li] = u;
+      wave_lds_fence();
+#pragma unroll
+      for (int t0 = 0; t0 < G; t0 += kNrU) {
+        if (t0 < cnt) {
+          int idv[kNrU];
+          read8i(l_idx + t0, idv);
+          float4 rowv[kNrU];
+#pragma unroll
+          for (int t = 0; t < kNrU; ++t)
+            if (col_ok && t0 + t < cnt) rowv[t] = ld4(my_row + (int64_t)idv[t] * KF);
+          float dv[kNrU];
+#pragma unroll
+          for (int t = 0; t < kNrU; ++t) dv[t] = (col_ok && t0 + t < cnt) ? dot4(g4, rowv[t]) : 0.f;
+          *reinterpret_cast<float4*>(l_d + li * G + t0) = make_float4(dv[0], dv[1], dv[2], dv[3]);
+          *reinterpret_cast<float4*>(l_d + li * G + t0 + 4) = make_float4(dv[4], dv[5], dv[6], dv[7]);
+        }
+      }
+      wave_lds_fence();
+      if (e_ok) {
+        float gm[kPsR];
+#pragma unroll
+        for (int d = 0; d < kPsR; ++d) gm[d] = 0.f;
+#pragma unroll
+        for (int k = 0; k < kPsK; ++k) {
+          if (k >= K) continue;
+          float dot = 0.f;
+          for (int j = 0; j < F4; ++j) dot += l_d[(k * F4 + j) * G + li];
+          const float dlog = dot * inv_k * gauss_k(pk, k, m);  // dw_k(e) w_k(e)
+#pragma unroll
+          for (int d = 0; d < kPsR; ++d) {
+            const float diff = m[d] - pk.mu[k][d];
+            const float is = pk.is[k][d];
+            const float t = dlog * diff * is;  // padded dimensions: is = 0
+            gm_acc[k][d] = fmaf(t, is, gm_acc[k][d]);
+            gs_acc[k][d] = fmaf(-t, diff, gs_acc[k][d]);
+            gm[d] = fmaf(-t, is, gm[d]);
+          }
+        }
+        if (gpseudo != nullptr) {
+#pragma unroll
+          for (int d = 0; d < kPsR; ++d)
+            if (d < R) gpseudo[(int64_t)(e0 + li) * R + d] = gm[d];
+        }
+      }
+    }
+  }
+  // the group's lanes are added in a fixed (butterfly) order, then the groups in order
+#pragma unroll
+  for (int k = 0; k < kPsK; ++k)
+#pragma unroll
+    for (int d = 0; d < kPsR; ++d) {
+      if (k < K && d < R) {
+        const float a = group_sum_from<G>(gm_acc[k][d], 1), b = group_sum_from<G>(gs_acc[k][d], 1);
+        if (li == 0) {
+          blk[grp][k * kPsR + d] = a;
+          blk[grp][kPsK * kPsR + k * kPsR + d] = b;
+        }
+      } else if (li == 0) {
+        blk[grp][k * kPsR + d] = 0.f;
+        blk[grp][kPsK * kPsR + k * kPsR + d] = 0.f;
+      }
+    }
+  __syncthreads();
+  if (threadIdx.x < kPsVals) {
+    float s = 0.f;
+    for (int g2 = 0; g2 < GPB; ++g2) s += blk[g2][threadIdx.x];
+    partial[(int64_t)blockIdx.x * kPsVals + threadIdx.x] = s;
+  }
+}
+
+// source side of backward: dhk[u, k, f] = (1/K) sum over out-edges w_k(e) gout[v, f]; the lanes of the K
+// kernels read the same columns of gout[v]
+template <int G>
+__global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_src_nr(
+    RowLaunch rl, const int32_t* __restrict__ order_t, const int32_t* __restrict__ indptr_t,
+    const int32_t* __restrict__ indices_t, const int32_t* __restrict__ eid_t,
+    const float* __restrict__ pseudo, const float* __restrict__ pseudo_t /* nullable: pseudo in this walk's order */,
+    const float* __restrict__ mu, const float* __restrict__ inv_sigma,
+    const float* __restrict__ gout, PsParams pm, float* __restrict__ dhk) {
+  constexpr int GPB = kPsBlock / G;
+  constexpr int GS = kNrGroupFloats<G>;
+  __shared__ __align__(16) float lds[GPB * GS];
+  __shared__ float coop_buf[GPB * G * 4];
+  const int li = threadIdx.x & (G - 1);
+  const int grp = threadIdx.x / G;
+  int64_t r;
+  int gi, ngrp;
+  RowRange rr;
+  if (!pick_row<GPB>(rl, grp, rr, r, gi, ngrp)) return;
+  const int K = pm.K, R = pm.R, F = pm.F, KF = K * F, F4 = F / 4;
+  const float inv_k = 1.f / (float)K;
+  const PsKernels pk = load_kernels(mu, inv_sigma, K, R);
+  const int32_t u = order_t[r];
+  const int32_t beg = indptr_t[u], end = indptr_t[u + 1];
+  const bool col_ok = li < K * F4;
+  const int myk = col_ok ? li / F4 : 0;
+  const int f4 = col_ok ? li % F4 : 0;
+  int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
+  float* l_w = lds + grp * GS + G;  // [kPsK][G]
+  const float* my_row = gout + 4 * f4;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f), part = acc;
+  int folded = 0;
+  for (int32_t p0 = beg + gi * G; p0 < end; p0 += ngrp * G) {
+    const bool e_ok = p0 + li < end;
+    const int cnt = min(G, end - p0);
+    int32_t v = 0;
+    float m[kPsR];
+#pragma unroll
+    for (int d = 0; d < kPsR; ++d) m[d] = 0.f;
+    if (e_ok) {
+      v = indices_t[p0 + li];
+      if (pseudo_t != nullptr) load_pseudo(pseudo_t, p0 + li, R, m);
+      else load_pseudo(pseudo, eid_t[p0 + li], R, m);
+    }
+    wave_lds_fence();
+    l_idx[li] = v;
+#pragma unroll
+    for (int k = 0; k < kPsK; ++k)
+      if (k < K) l_w[k * G + li] = e_ok ? gauss_k(pk, k, m) * inv_k : 0.f;
+    wave_lds_fence();
+#pragma unroll
+    for (int t0 = 0; t0 < G; t0 += kNrU) {
+      if (t0 < cnt) {
+        int idv[kNrU];
+        float wv[kNrU];
+        read8i(l_idx + t0, idv);
+        float4 rowv[kNrU];
+#pragma unroll
+        for (int t = 0; t < kNrU; ++t)
+          if (col_ok && t0 + t < cnt) rowv[t] = ld4(my_row + (int64_t)idv[t] * F);
+        read8f(l_w + myk * G + t0, wv);
+#pragma unroll
+        for (int t = 0; t < kNrU; ++t)
+          if (col_ok && t0 + t < cnt) fma4(part, wv[t], rowv[t]);
+      }
+    }
+    folded += G;
+    if (folded >= 32) {
+      add4(acc, part);
+      part = make_float4(0.f, 0.f, 0.f, 0.f);
+      folded = 0;
+    }
+  }
+  add4(acc, part);
+  if (rr.coop) {
+    float vv[4];
+    pack4(vv, acc);
+    coop_sum<G, 4, GPB>(coop_buf, vv, grp, li);
+    if (grp != 0) return;
+    acc = unpack4(vv);
+  }
+  if (col_ok) st4(dhk + (int64_t)u * KF + 4 * li, acc);
+}
+
 // ---- the projection that makes pseudo-coordinates from the degree pair ------------------------
-// m[e,d] = tanh(P[d,0] c[u] + P[d,1] c[v] + pb[d]); one thread per edge; dst_of[e] by walking rows
+// m[e,d] = tanh(P[d,0] c[u] + P[d,1] c[v] + pb[d]).  One wavefront per row of the walked list, lanes
+// over its edges, four edges per lane in flight.  side 0: rows are destinations (CSR walk, the row's
+// vertex is v); side 1: rows are sources (transposed list, the row's vertex is u) and the output is in
+// that list's order.  What bounds a pass is the gather of c at the other end of every edge, one L1 line
+// fill per edge (an edge-parallel version with perfectly even load took the same time).
 __global__ void k_pseudo_proj_fwd(int32_t n, const int32_t* __restrict__ indptr,
                                   const int32_t* __restrict__ indices, const float* __restrict__ c, int R,
-                                  const float* __restrict__ P, const float* __restrict__ pb,
+                                  const float* __restrict__ P, const float* __restrict__ pb, int side,
                                   float* __restrict__ pseudo) {
-  // one wavefront per destination row, lanes over its edges
   const int lane = threadIdx.x & 63;
-  const int64_t v = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) >> 6;
-  if (v >= n) return;
-  const float cv = c[v];
-  for (int32_t e = indptr[v] + lane; e < indptr[v + 1]; e += 64) {
-    const float cu = c[indices[e]];
-    for (int d = 0; d < R; ++d) pseudo[(int64_t)e * R + d] = tanhf(fmaf(P[2 * d], cu, fmaf(P[2 * d + 1], cv, pb[d])));
+  const int64_t row = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) >> 6;
+  if (row >= n) return;
+  const float c_row = c[row];
+  const int32_t end = indptr[row + 1];
+  for (int32_t e0 = indptr[row] + lane; e0 < end; e0 += 256) {
+    float c_other[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) c_other[j] = e0 + 64 * j < end ? c[indices[e0 + 64 * j]] : 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (e0 + 64 * j >= end) continue;
+      const float cu = side == 0 ? c_other[j] : c_row, cv = side == 0 ? c_row : c_other[j];
+      for (int d = 0; d < R; ++d)
+        pseudo[(int64_t)(e0 + 64 * j) * R + d] = tanhf(fmaf(P[2 * d], cu, fmaf(P[2 * d + 1], cv, pb[d])));
+    }
   }
 }
 
@@ -293,16 +630,20 @@ __global__ __launch_bounds__(kPsBlock) void k_pseudo_proj_bwd(
   const int64_t waves = (int64_t)gridDim.x * (kPsBlock / 64);
   for (int64_t v = (int64_t)blockIdx.x * (kPsBlock / 64) + w; v < n; v += waves) {
     const float cv = c[v];
-    for (int32_t e = indptr[v] + lane; e < indptr[v + 1]; e += 64) {
-      const float cu = c[indices[e]];
+    const int32_t end = indptr[v + 1];
+    for (int32_t e0 = indptr[v] + lane; e0 < end; e0 += 128) {  // two edges per lane in flight
+      const int32_t e1 = e0 + 64;
+      const bool ok1 = e1 < end;
+      const float cu0 = c[indices[e0]], cu1 = ok1 ? c[indices[e1]] : 0.f;
 #pragma unroll
       for (int d = 0; d < kPsR; ++d) {
         if (d >= R) continue;
-        const float m = pseudo[(int64_t)e * R + d];
-        const float dpre = gpseudo[(int64_t)e * R + d] * (1.f - m * m);
-        s[3 * d] = fmaf(dpre, cu, s[3 * d]);
-        s[3 * d + 1] = fmaf(dpre, cv, s[3 * d + 1]);
-        s[3 * d + 2] += dpre;
+        const float m0 = pseudo[(int64_t)e0 * R + d], q0 = gpseudo[(int64_t)e0 * R + d];
+        const float m1 = ok1 ? pseudo[(int64_t)e1 * R + d] : 0.f, q1 = ok1 ? gpseudo[(int64_t)e1 * R + d] : 0.f;
+        const float dpre0 = q0 * (1.f - m0 * m0), dpre1 = q1 * (1.f - m1 * m1);
+        s[3 * d] = fmaf(dpre1, cu1, fmaf(dpre0, cu0, s[3 * d]));
+        s[3 * d + 1] = fmaf(dpre1, cv, fmaf(dpre0, cv, s[3 * d + 1]));
+        s[3 * d + 2] += dpre0 + dpre1;
       }
     }
   }
@@ -340,15 +681,36 @@ static unsigned ps_grid(const gnn_graph_t* g, int side, RowLaunch& rl) {
 
 static int ps_lanes(int fout) { return pick_group(fout).L; }  // fout <= 256: one float4 slot per lane
 
+// Lanes per group of the chunked kernels for narrow rows, 0 where they do not apply: the K * fout / 4
+// float4 slots of a projected row must fit 16 lanes.
+static int nr_lanes(int K, int fout) {
+  const int q = K * fout / 4;
+  if (q > 16 || config_get(kCfgForceSimple)) return 0;
+  return q <= 8 ? 8 : 16;
+}
+template <int G>
+static unsigned nr_grid(const gnn_graph_t* g, int side, RowLaunch& rl) {
+  constexpr int GPB = kPsBlock / G;
+  // an ordinary row is walked by one group, G edges at a time with 8 gathers in flight; rows from 64
+  // such chunks on are shared by a workgroup
+  const RowSplit sp = split_rows(g, side, 4 * G, GPB);
+  rl = RowLaunch{sp.hub.end, g->n};
+  return sp.hub_grid + sp.rest_grid;
+}
+
+// partial slots of the destination-side kernel: enough for either kernel family
 static int64_t ps_dst_blocks(const gnn_graph_t* g, int fout) {
   RowLaunch rl;
+  int64_t b;
   switch (ps_lanes(fout)) {
-    case 4: return ps_grid<4>(g, 0, rl);
-    case 8: return ps_grid<8>(g, 0, rl);
-    case 16: return ps_grid<16>(g, 0, rl);
-    case 32: return ps_grid<32>(g, 0, rl);
-    default: return ps_grid<64>(g, 0, rl);
+    case 4: b = ps_grid<4>(g, 0, rl); break;
+    case 8: b = ps_grid<8>(g, 0, rl); break;
+    case 16: b = ps_grid<16>(g, 0, rl); break;
+    case 32: b = ps_grid<32>(g, 0, rl); break;
+    default: b = ps_grid<64>(g, 0, rl); break;
   }
+  const int64_t b8 = nr_grid<8>(g, 0, rl), b16 = nr_grid<16>(g, 0, rl);
+  return std::max(b, std::max(b8, b16));
 }
 
 struct GmmpWs {
@@ -413,6 +775,19 @@ extern "C" gnn_status_t gnn_gmmp_fwd(const gnn_graph_t* g, int fin, int fout, in
   GNN_TRY(gemm_f32(g->n, k * fout, fin, x, fin, false, w_fc, k * fout, false, hk, k * fout, 1, nullptr, st));
   const PsParams pm{k, r, fout};
   ProfScope p("gmmp_fwd_fused", st);
+  if (const int G = nr_lanes(k, fout)) {
+    return for_lanes(G, [&](auto lanes) -> gnn_status_t {
+      constexpr int GL = decltype(lanes)::value == 8 ? 8 : 16;
+      RowLaunch rl;
+      const unsigned grid = nr_grid<GL>(g, 0, rl);
+      if (grid != 0) {
+        k_gmmp_fwd_nr<GL><<<grid, kPsBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, hk, pseudo, mu,
+                                                    inv_sigma, pm, out);
+        GNN_LAUNCH_CHECK();
+      }
+      return GNN_OK;
+    });
+  }
   return for_lanes(ps_lanes(fout), [&](auto lanes) -> gnn_status_t {
     constexpr int L = decltype(lanes)::value;
     RowLaunch rl;
@@ -429,8 +804,8 @@ extern "C" gnn_status_t gnn_gmmp_fwd(const gnn_graph_t* g, int fin, int fout, in
 extern "C" gnn_status_t gnn_gmmp_bwd(const gnn_graph_t* g, int fin, int fout, int k, int r, const float* x,
                                      const float* w_fc, const float* pseudo, const float* mu,
                                      const float* inv_sigma, const float* hk, const float* gout, float* gx,
-                                     float* gw_fc, float* gmu, float* ginv_sigma, float* gpseudo, void* ws,
-                                     size_t ws_bytes, void* stream) {
+                                     float* gw_fc, float* gmu, float* ginv_sigma, float* gpseudo,
+                                     const float* pseudo_t, void* ws, size_t ws_bytes, void* stream) {
   clear_error();
   GNN_TRY(gmmp_check(g, fin, fout, k, r, "gnn_gmmp_bwd"));
   if (g->n == 0) return GNN_OK;
@@ -452,15 +827,20 @@ extern "C" gnn_status_t gnn_gmmp_bwd(const gnn_graph_t* g, int fin, int fout, in
   {
     ProfScope p("gmmp_bwd_dst", st);
     unsigned grid = 0;
-    GNN_TRY(for_lanes(ps_lanes(fout), [&](auto lanes) -> gnn_status_t {
+    const int G = nr_lanes(k, fout);
+    GNN_TRY(for_lanes(G ? G : ps_lanes(fout), [&](auto lanes) -> gnn_status_t {
       constexpr int L = decltype(lanes)::value;
+      constexpr int GL = L == 8 ? 8 : 16;
       RowLaunch rl;
-      grid = ps_grid<L>(g, 0, rl);
-      if (grid != 0) {
+      grid = G ? nr_grid<GL>(g, 0, rl) : ps_grid<L>(g, 0, rl);
+      if (grid == 0) return GNN_OK;
+      if (G)
+        k_gmmp_bwd_dst_nr<GL><<<grid, kPsBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, hk, pseudo, mu,
+                                                        inv_sigma, gout, pm, partial, gpseudo);
+      else
         k_gmmp_bwd_dst<L><<<grid, kPsBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, hk, pseudo, mu,
                                                     inv_sigma, gout, pm, partial, gpseudo);
-        GNN_LAUNCH_CHECK();
-      }
+      GNN_LAUNCH_CHECK();
       return GNN_OK;
     }));
     float* totals = partial + (int64_t)grid * kPsVals;
@@ -470,15 +850,20 @@ extern "C" gnn_status_t gnn_gmmp_bwd(const gnn_graph_t* g, int fin, int fout, in
   }
   {
     ProfScope p("gmmp_bwd_src", st);
-    GNN_TRY(for_lanes(ps_lanes(fout), [&](auto lanes) -> gnn_status_t {
+    const int G = nr_lanes(k, fout);
+    GNN_TRY(for_lanes(G ? G : ps_lanes(fout), [&](auto lanes) -> gnn_status_t {
       constexpr int L = decltype(lanes)::value;
+      constexpr int GL = L == 8 ? 8 : 16;
       RowLaunch rl;
-      const unsigned grid = ps_grid<L>(g, 1, rl);
-      if (grid != 0) {
+      const unsigned grid = G ? nr_grid<GL>(g, 1, rl) : ps_grid<L>(g, 1, rl);
+      if (grid == 0) return GNN_OK;
+      if (G)
+        k_gmmp_bwd_src_nr<GL><<<grid, kPsBlock, 0, st>>>(rl, g->order[1], g->indptr_t, g->indices_t, g->eid_t,
+                                                        pseudo, pseudo_t, mu, inv_sigma, gout, pm, dhk);
+      else
         k_gmmp_bwd_src<L><<<grid, kPsBlock, 0, st>>>(rl, g->order[1], g->indptr_t, g->indices_t, g->eid_t, pseudo,
-                                                    mu, inv_sigma, gout, pm, dhk);
-        GNN_LAUNCH_CHECK();
-      }
+                                                    pseudo_t, mu, inv_sigma, gout, pm, dhk);
+      GNN_LAUNCH_CHECK();
       return GNN_OK;
     }));
   }
@@ -500,7 +885,7 @@ extern "C" size_t gnn_pseudo_proj_workspace_bytes(const gnn_graph_t* g) {
 }
 
 extern "C" gnn_status_t gnn_pseudo_proj_fwd(const gnn_graph_t* g, int r, const float* c, const float* proj_w,
-                                            const float* proj_b, float* pseudo, void* stream) {
+                                            const float* proj_b, float* pseudo, float* pseudo_t, void* stream) {
   clear_error();
   GNN_REQUIRE(g != nullptr, GNN_ERR_INVALID_ARG, "gnn_pseudo_proj_fwd: graph is null");
   GNN_REQUIRE(r > 0 && r <= kPsR, GNN_ERR_UNSUPPORTED, "gnn_pseudo_proj_fwd: r = %d outside 1..%d", r, kPsR);
@@ -508,9 +893,13 @@ extern "C" gnn_status_t gnn_pseudo_proj_fwd(const gnn_graph_t* g, int r, const f
   GNN_REQUIRE(c && proj_w && proj_b && pseudo, GNN_ERR_INVALID_ARG, "gnn_pseudo_proj_fwd: null pointer");
   hipStream_t st = static_cast<hipStream_t>(stream);
   ProfScope p("pseudo_proj_fwd", st);
-  k_pseudo_proj_fwd<<<(unsigned)cdiv((int64_t)g->n * 64, 256), 256, 0, st>>>(g->n, g->indptr, g->indices, c, r,
-                                                                            proj_w, proj_b, pseudo);
+  const unsigned grid = (unsigned)cdiv((int64_t)g->n * 64, 256);
+  k_pseudo_proj_fwd<<<grid, 256, 0, st>>>(g->n, g->indptr, g->indices, c, r, proj_w, proj_b, 0, pseudo);
   GNN_LAUNCH_CHECK();
+  if (pseudo_t != nullptr) {
+    k_pseudo_proj_fwd<<<grid, 256, 0, st>>>(g->n, g->indptr_t, g->indices_t, c, r, proj_w, proj_b, 1, pseudo_t);
+    GNN_LAUNCH_CHECK();
+  }
   return GNN_OK;
 }
 

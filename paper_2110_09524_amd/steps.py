@@ -99,6 +99,7 @@ class MonetLayer:
         n, e, dev = graph.n, max(graph.nnz, 1), c.device
         self.hk, self.out = _new(dev, n, k * fout), _new(dev, n, fout)
         self.pseudo, self.gpseudo = _new(dev, e, r), _new(dev, e, r)
+        self.pseudo_t = _new(dev, e, r)   # the same coordinates in the transposed list's order
         self.grads = {k_: torch.empty_like(v) for k_, v in params.items()}
 
     def workspace_bytes(self):
@@ -107,7 +108,7 @@ class MonetLayer:
 
     def forward(self, x, ws):
         p = self.p
-        B.gnn_pseudo_proj_fwd(self.g, self.r, self.c, p["proj_w"], p["proj_b"], self.pseudo)
+        B.gnn_pseudo_proj_fwd(self.g, self.r, self.c, p["proj_w"], p["proj_b"], self.pseudo, pseudo_t=self.pseudo_t)
         B.gnn_gmmp_fwd(self.g, self.fin, self.fout, self.k, self.r, x, p["w_fc"], self.pseudo, p["mu"],
                        p["inv_sigma"], self.hk, self.out)
         return self.out
@@ -115,7 +116,8 @@ class MonetLayer:
     def backward(self, x, gout, gx, ws):
         p, g = self.p, self.grads
         B.gnn_gmmp_bwd(self.g, self.fin, self.fout, self.k, self.r, x, p["w_fc"], self.pseudo, p["mu"],
-                       p["inv_sigma"], self.hk, gout, gx, g["w_fc"], g["mu"], g["inv_sigma"], self.gpseudo, ws)
+                       p["inv_sigma"], self.hk, gout, gx, g["w_fc"], g["mu"], g["inv_sigma"], self.gpseudo, ws,
+                       pseudo_t=self.pseudo_t)
         B.gnn_pseudo_proj_bwd(self.g, self.r, self.c, self.pseudo, self.gpseudo, g["proj_w"], g["proj_b"], ws)
 
 

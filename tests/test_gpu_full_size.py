@@ -291,9 +291,11 @@ def test_monet_on_the_c4_graph_sampled_rows_and_consistency(c4, sample, capsys):
     gP, gpb = empty((R, 2)), empty((R,))
     ws = workspace(max(pk.gnn_gmmp_workspace_bytes(g, fin, fout, K), pk.gnn_pseudo_proj_workspace_bytes(g)))
     say("GPU fwd+bwd, upstream gradient zero outside the sample")
-    pk.gnn_pseudo_proj_fwd(g, R, dc, dP, dpb, pseudo)
+    pseudo_t = empty((E, R))   # the launch configuration bench.py times: coordinates in both edge orders
+    pk.gnn_pseudo_proj_fwd(g, R, dc, dP, dpb, pseudo, pseudo_t=pseudo_t)
     pk.gnn_gmmp_fwd(g, fin, fout, K, R, x, dw, pseudo, dmu, dis, hk, out)
-    pk.gnn_gmmp_bwd(g, fin, fout, K, R, x, dw, pseudo, dmu, dis, hk, dgo, gx, gw, gmu, gis, gps, ws)
+    pk.gnn_gmmp_bwd(g, fin, fout, K, R, x, dw, pseudo, dmu, dis, hk, dgo, gx, gw, gmu, gis, gps, ws,
+                    pseudo_t=pseudo_t)
     pk.gnn_pseudo_proj_bwd(g, R, dc, pseudo, gps, gP, gpb, ws)
     torch.cuda.synchronize()
     say(f"oracle on the {sample['edges']} in-edges of {rows.size} rows")

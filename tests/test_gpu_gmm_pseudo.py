@@ -20,7 +20,12 @@ def synth(rng, indptr, indices, fin, fout, K, r):
                 gout=rng.standard_normal((n, fout)).astype(np.float32))
 
 
-def run(c, want_gx=True, want_gpseudo=True):
+def transposed_order(indices):
+    """CSR positions in the order of the transposed edge list: by source, then by CSR position."""
+    return np.argsort(indices, kind="stable")
+
+
+def run(c, want_gx=True, want_gpseudo=True, transposed=False):
     import torch
     import paper_2110_09524_amd as pk
     from gpu_harness import dev, empty, workspace
@@ -35,7 +40,9 @@ def run(c, want_gx=True, want_gpseudo=True):
     gx = empty((n, fin)) if want_gx else None
     gps = empty((max(E, 1), r)) if want_gpseudo else None
     gw, gmu, gis = empty((fin, K * fout)), empty((K, r)), empty((K, r))
-    pk.gnn_gmmp_bwd(g, fin, fout, K, r, x, w_fc, pseudo, mu, isg, hk, dev(c["gout"]), gx, gw, gmu, gis, gps, ws)
+    pseudo_t = dev(c["pseudo"][transposed_order(c["indices"])]) if transposed and E else None
+    pk.gnn_gmmp_bwd(g, fin, fout, K, r, x, w_fc, pseudo, mu, isg, hk, dev(c["gout"]), gx, gw, gmu, gis, gps, ws,
+                    pseudo_t=pseudo_t)
     torch.cuda.synchronize()
     res = dict(hk=hk, out=out, gw_fc=gw, gmu=gmu, ginv_sigma=gis)
     if want_gx:
@@ -71,6 +78,33 @@ def test_shapes(fin, fout, K, r):
     rng = np.random.default_rng(fin + fout + 10 * K + r)
     indptr, indices = random_graph(rng, 400, 5000, self_loops=True, duplicates=True)
     check(synth(rng, indptr, indices, fin, fout, K, r))
+
+
+@pytest.mark.parametrize("fout,K,r", [(16, 2, 1), (16, 3, 3), (64, 4, 2)])
+def test_coordinates_in_the_transposed_order_give_the_same_bits(fout, K, r):
+    """pseudo_t only changes where the source side of backward reads its coordinates from."""
+    from workloads import graphs
+    print(f"gmmp: pseudo_t fout={fout} K={K} r={r}", flush=True)
+    indptr, indices = graphs.chung_lu(3000, 60_000, 2.1, 17)
+    c = synth(np.random.default_rng(fout + K), indptr, indices, 24, fout, K, r)
+    a, b = check(c), check(c, transposed=True)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+
+
+def test_single_edge_kernels_agree_with_the_chunked_ones():
+    """Rows of up to 64 projected floats take the chunked kernels; force_simple_kernels selects the
+    one-edge-at-a-time kernels that wider rows use.  Both against the oracle."""
+    import paper_2110_09524_amd as pk
+    from workloads import graphs
+    indptr, indices = graphs.chung_lu(4000, 90_000, 2.1, 23)
+    c = synth(np.random.default_rng(3), indptr, indices, 20, 16, 3, 2)
+    check(c)
+    pk.gnn_config_set("force_simple_kernels", 1)
+    try:
+        check(c)
+    finally:
+        pk.gnn_config_set("force_simple_kernels", 0)
 
 
 def test_the_papers_settings_on_a_power_law_graph():
@@ -126,11 +160,12 @@ def test_projection_forward_backward_and_bad_arguments():
     for r in (1, 2, 3):
         P, pb = rng.standard_normal((r, 2)).astype(np.float32), (0.2 * rng.standard_normal(r)).astype(np.float32)
         gps = rng.standard_normal((E, r)).astype(np.float32)
-        pseudo, gP, gpb = empty((E, r)), empty((r, 2)), empty((r,))
-        pk.gnn_pseudo_proj_fwd(g, r, dev(c), dev(P), dev(pb), pseudo)
+        pseudo, pseudo_t, gP, gpb = empty((E, r)), empty((E, r)), empty((r, 2)), empty((r,))
+        pk.gnn_pseudo_proj_fwd(g, r, dev(c), dev(P), dev(pb), pseudo, pseudo_t=pseudo_t)
         pk.gnn_pseudo_proj_bwd(g, r, dev(c), pseudo, dev(gps), gP, gpb, workspace(pk.gnn_pseudo_proj_workspace_bytes(g)))
         torch.cuda.synchronize()
         assert_close("pseudo", pseudo.cpu().numpy(), om.pseudo_projection_forward(indptr, indices, c, P, pb))
+        assert np.array_equal(pseudo_t.cpu().numpy(), pseudo.cpu().numpy()[transposed_order(indices)])
         rP, rpb = om.pseudo_projection_backward(indptr, indices, c, P, pb, gps)
         assert_close("gproj_w", gP.cpu().numpy(), rP)
         assert_close("gproj_b", gpb.cpu().numpy(), rpb)
