@@ -298,6 +298,9 @@ def main():
                     help="use the single-launch kernels also where the column-blocked ones apply")
     ap.add_argument("--block-cols", type=int, default=None,
                     help="gathered vertices per column block of the blocked edge lists (library default 20480)")
+    ap.add_argument("--monet-two-call", action="store_true",
+                    help="MoNet workloads: projection and layer as separate calls with [E, r] coordinate arrays "
+                         "between them (gnn_pseudo_proj_* + gnn_gmmp_*) instead of gnn_monet_*")
     ap.add_argument("--no-pseudo-t", action="store_true",
                     help="MoNet workloads: the backward pass reads the pseudo-coordinates through the plan's "
                          "position -> edge table instead of a second copy in the transposed list's order")
@@ -497,30 +500,46 @@ def main():
         F, K, R = c["fout"], c["k"], c["r"]
         w_fc, cc, mu, inv_sigma = to(c["w_fc"]), to(c["c"]), to(c["mu"]), to(c["inv_sigma"])
         proj_w, proj_b = to(c["proj_w"]), to(c["proj_b"])
-        pseudo, gpseudo = new(e, R), new(e, R)
-        pseudo_t = None if args.no_pseudo_t else new(e, R)   # the coordinates in the transposed list's order
+        fused = not args.monet_two_call and K * F <= 64   # projection evaluated inside the layer's kernels
         hk, out = new(n, K * F), new(n, F)
         gx, gw_fc, gmu, gis = new(n, fin), new(fin, K * F), new(K, R), new(K, R)
         gproj_w, gproj_b = new(R, 2), new(R)
         ws_bytes = max(pk.gnn_gmmp_workspace_bytes(g, fin, F, K), pk.gnn_pseudo_proj_workspace_bytes(g))
         ws = new(max(ws_bytes, 16), dtype=torch.uint8)
-
-        def step():
-            pk.gnn_pseudo_proj_fwd(g, R, cc, proj_w, proj_b, pseudo, pseudo_t=pseudo_t)
-            pk.gnn_gmmp_fwd(g, fin, F, K, R, x, w_fc, pseudo, mu, inv_sigma, hk, out)
-            pk.gnn_gmmp_bwd(g, fin, F, K, R, x, w_fc, pseudo, mu, inv_sigma, hk, gout, gx, gw_fc, gmu, gis,
-                            gpseudo, ws, pseudo_t=pseudo_t)
-            pk.gnn_pseudo_proj_bwd(g, R, cc, pseudo, gpseudo, gproj_w, gproj_b, ws)
         V, I = 4 * n * F, 4 * e + 8 * n
-        unique = {"gmmp_fwd_fused": I + 4 * e * R + K * V + V, "gmmp_bwd_dst": I + 8 * e * R + K * V + V,
-                  "gmmp_bwd_src": (1 if pseudo_t is not None else 2) * I + 4 * e * R + V + K * V}
-        gather = {"gmmp_fwd_fused": e * (4 + 4 * R + 4 * K * F), "gmmp_bwd_dst": e * (4 + 8 * R + 4 * K * F),
-                  "gmmp_bwd_src": e * ((4 if pseudo_t is not None else 8) + 4 * R + 4 * F)}
-        flops = {"gmmp_fwd_fused": e * K * (2 * F + 4 * R + 8), "gmmp_bwd_dst": e * K * (2 * F + 10 * R + 10),
-                 "gmmp_bwd_src": e * K * (2 * F + 4 * R + 8)}
+        if fused:
+            def step():
+                pk.gnn_monet_fwd(g, fin, F, K, R, x, w_fc, cc, proj_w, proj_b, mu, inv_sigma, hk, out)
+                pk.gnn_monet_bwd(g, fin, F, K, R, x, w_fc, cc, proj_w, proj_b, mu, inv_sigma, hk, gout, gx, gw_fc,
+                                 gmu, gis, gproj_w, gproj_b, ws)
+            # no per-edge array: the index list, the vertex scalar c (4 n bytes) and the rows
+            unique = {"monet_fwd_fused": I + 4 * n + K * V + V, "monet_bwd_dst": I + 4 * n + K * V + V,
+                      "monet_bwd_src": I + 4 * n + V + K * V}
+            gather = {"monet_fwd_fused": e * (4 + 4 + 4 * K * F), "monet_bwd_dst": e * (4 + 4 + 4 * K * F),
+                      "monet_bwd_src": e * (4 + 4 + 4 * F)}
+            flops = {"monet_fwd_fused": e * (K * (2 * F + 4 * R + 8) + 12 * R),
+                     "monet_bwd_dst": e * (K * (2 * F + 10 * R + 10) + 20 * R),
+                     "monet_bwd_src": e * (K * (2 * F + 4 * R + 8) + 12 * R)}
+        else:
+            pseudo, gpseudo = new(e, R), new(e, R)
+            pseudo_t = None if args.no_pseudo_t else new(e, R)   # the coordinates in the transposed list's order
+
+            def step():
+                pk.gnn_pseudo_proj_fwd(g, R, cc, proj_w, proj_b, pseudo, pseudo_t=pseudo_t)
+                pk.gnn_gmmp_fwd(g, fin, F, K, R, x, w_fc, pseudo, mu, inv_sigma, hk, out)
+                pk.gnn_gmmp_bwd(g, fin, F, K, R, x, w_fc, pseudo, mu, inv_sigma, hk, gout, gx, gw_fc, gmu, gis,
+                                gpseudo, ws, pseudo_t=pseudo_t)
+                pk.gnn_pseudo_proj_bwd(g, R, cc, pseudo, gpseudo, gproj_w, gproj_b, ws)
+            unique = {"gmmp_fwd_fused": I + 4 * e * R + K * V + V, "gmmp_bwd_dst": I + 8 * e * R + K * V + V,
+                      "gmmp_bwd_src": (1 if pseudo_t is not None else 2) * I + 4 * e * R + V + K * V}
+            gather = {"gmmp_fwd_fused": e * (4 + 4 * R + 4 * K * F), "gmmp_bwd_dst": e * (4 + 8 * R + 4 * K * F),
+                      "gmmp_bwd_src": e * ((4 if pseudo_t is not None else 8) + 4 * R + 4 * F)}
+            flops = {"gmmp_fwd_fused": e * K * (2 * F + 4 * R + 8), "gmmp_bwd_dst": e * K * (2 * F + 10 * R + 10),
+                     "gmmp_bwd_src": e * K * (2 * F + 4 * R + 8)}
         metric = "MoNet/GMM layer with projected pseudo-coordinates fwd+bwd edges/sec"
         cfg = {"in_feat": fin, "out_feat": F, "kernels": K, "pseudo_dim": R,
-               "pseudo": "tanh(proj_w (1/sqrt(deg_u), 1/sqrt(deg_v)) + proj_b), [E, r] fp32",
+               "pseudo": "tanh(proj_w (1/sqrt(deg_u), 1/sqrt(deg_v)) + proj_b), " +
+                         ("evaluated inside the layer's kernels, no per-edge array" if fused else "[E, r] fp32 arrays"),
                "graph": "Chung-Lu power law (gamma 2.1) + self-loops, seeded"}
         gemm_flops = 2.0 * n * fin * K * F
     elif kind == "gcn":

@@ -404,6 +404,32 @@ gnn_status_t gnn_pseudo_proj_bwd(const gnn_graph_t* graph, int r, const float* c
                                  void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------- *
+ * MoNet layer with the projection fused in (the paper's MoNet models, Sec. 7.2 / 7.3: pseudo-
+ * coordinates are a learnable projection of the degree pair, then App. A.2 "GMMConv"):
+ *   m[e,d] = tanh(proj_w[d,0] c[u] + proj_w[d,1] c[v] + proj_b[d]),   w_j(e), out as above.
+ * Every edge function of the chain (projection, tanh, Gaussian weight, weighting) is evaluated
+ * inside the gather kernels from the per-vertex scalar c at the two ends of the edge, forward and
+ * again in both halves of backward; no per-edge tensor is read, written or kept (Sec. 4, Sec. 6).
+ * Same results as gnn_pseudo_proj_fwd + gnn_gmmp_fwd and gnn_gmmp_bwd + gnn_pseudo_proj_bwd.
+ * c [n], proj_w [r,2], proj_b [r]; backward returns gproj_w [r,2], gproj_b [r] besides the
+ * gradients of gnn_gmmp_bwd (gx nullable).  Limits: those of gnn_gmmp_* and k * fout <= 64 (the
+ * paper's 16 hidden features; wider layers take the two-call form), else GNN_ERR_UNSUPPORTED.
+ * Workspace: gnn_monet_workspace_bytes; parameter gradients are summed in a fixed order.
+ * ------------------------------------------------------------------------- */
+size_t gnn_monet_workspace_bytes(const gnn_graph_t* graph, int fin, int fout, int k);
+gnn_status_t gnn_monet_fwd(const gnn_graph_t* graph, int fin, int fout, int k, int r, const float* x,
+                           const float* w_fc /*[fin,k*fout]*/, const float* c /*[n]*/,
+                           const float* proj_w /*[r,2]*/, const float* proj_b /*[r]*/, const float* mu /*[k,r]*/,
+                           const float* inv_sigma /*[k,r]*/, float* hk /*[n,k*fout]*/, float* out /*[n,fout]*/,
+                           void* stream);
+gnn_status_t gnn_monet_bwd(const gnn_graph_t* graph, int fin, int fout, int k, int r, const float* x,
+                           const float* w_fc, const float* c, const float* proj_w, const float* proj_b,
+                           const float* mu, const float* inv_sigma, const float* hk,
+                           const float* gout /*[n,fout]*/, float* gx /*nullable*/, float* gw_fc, float* gmu,
+                           float* ginv_sigma, float* gproj_w, float* gproj_b, void* ws, size_t ws_bytes,
+                           void* stream);
+
+/* ------------------------------------------------------------------------- *
  * GCN layer with separable static edge weights (App. A.2 "GCN", no bias, identity
  * activation):
  *   out[v] = sum over in-edges (u -> v) of  c_src[u] c_dst[v] (x w)[u]

@@ -25,7 +25,8 @@ EXPORTS = [
     "gnn_gat_bwd", "gnn_gat_bwd_noalloc", "gnn_gat_blocked_kernel_name", "gnn_gat_stash_layout", "gnn_gat_stash_alpha", "gnn_gat_bwd_stashed", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
     "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd", "gnn_gmm_tune",
     "gnn_gmmp_workspace_bytes", "gnn_gmmp_fwd", "gnn_gmmp_bwd", "gnn_pseudo_proj_workspace_bytes",
-    "gnn_pseudo_proj_fwd", "gnn_pseudo_proj_bwd", "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_gcn_tune",
+    "gnn_pseudo_proj_fwd", "gnn_pseudo_proj_bwd", "gnn_monet_workspace_bytes", "gnn_monet_fwd", "gnn_monet_bwd",
+    "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_gcn_tune",
     "gnn_edge_weights_create", "gnn_edge_weights_destroy", "gnn_gcn_edge_fwd", "gnn_gcn_edge_bwd",
     "gnn_bias_act_fwd", "gnn_bias_act_workspace_bytes", "gnn_bias_act_bwd", "gnn_softmax_xent_workspace_bytes",
     "gnn_softmax_xent", "gnn_sgd_update", "gnn_knn_graph", "gnn_prof_enable",
@@ -82,6 +83,10 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_gmmp_bwd.argtypes = [vp, i32, i32, i32, i32] + [vp] * 13 + [vp, sz, vp]
     lib.gnn_pseudo_proj_workspace_bytes.restype = sz
     lib.gnn_pseudo_proj_workspace_bytes.argtypes = [vp]
+    lib.gnn_monet_workspace_bytes.restype = sz
+    lib.gnn_monet_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    lib.gnn_monet_fwd.argtypes = [vp, i32, i32, i32, i32] + [vp] * 9 + [vp]
+    lib.gnn_monet_bwd.argtypes = [vp, i32, i32, i32, i32] + [vp] * 15 + [vp, sz, vp]
     lib.gnn_pseudo_proj_fwd.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.gnn_pseudo_proj_bwd.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.gnn_gcn_workspace_bytes.restype = sz
@@ -112,7 +117,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         if name not in ("gnn_last_error", "gnn_gat_workspace_bytes", "gnn_edgeconv_workspace_bytes",
                         "gnn_gmm_workspace_bytes", "gnn_gcn_workspace_bytes", "gnn_prof_count",
                         "gnn_bias_act_workspace_bytes", "gnn_softmax_xent_workspace_bytes",
-                        "gnn_gmmp_workspace_bytes", "gnn_pseudo_proj_workspace_bytes"):
+                        "gnn_gmmp_workspace_bytes", "gnn_pseudo_proj_workspace_bytes", "gnn_monet_workspace_bytes"):
             fn.restype = C.c_int
     return lib
 
@@ -407,6 +412,23 @@ def gnn_pseudo_proj_bwd(g: Graph, r, c, pseudo, gpseudo, gproj_w, gproj_b, ws, s
     wp, wb = _ws_args(ws)
     _check(lib().gnn_pseudo_proj_bwd(g.handle, r, _f(c), _f(pseudo), _f(gpseudo), _f(gproj_w), _f(gproj_b), wp, wb,
                                      _stream(stream)))
+
+
+def gnn_monet_workspace_bytes(g: Graph, fin, fout, k) -> int:
+    return int(lib().gnn_monet_workspace_bytes(g.handle, fin, fout, k))
+
+
+def gnn_monet_fwd(g: Graph, fin, fout, k, r, x, w_fc, c, proj_w, proj_b, mu, inv_sigma, hk, out, stream=None):
+    _check(lib().gnn_monet_fwd(g.handle, fin, fout, k, r, _f(x), _f(w_fc), _f(c), _f(proj_w), _f(proj_b), _f(mu),
+                               _f(inv_sigma), _f(hk), _f(out), _stream(stream)))
+
+
+def gnn_monet_bwd(g: Graph, fin, fout, k, r, x, w_fc, c, proj_w, proj_b, mu, inv_sigma, hk, gout, gx, gw_fc, gmu,
+                  ginv_sigma, gproj_w, gproj_b, ws, stream=None):
+    wp, wb = _ws_args(ws)
+    _check(lib().gnn_monet_bwd(g.handle, fin, fout, k, r, _f(x), _f(w_fc), _f(c), _f(proj_w), _f(proj_b), _f(mu),
+                               _f(inv_sigma), _f(hk), _f(gout), _f(gx), _f(gw_fc), _f(gmu), _f(ginv_sigma),
+                               _f(gproj_w), _f(gproj_b), wp, wb, _stream(stream)))
 
 
 def gnn_release_cached_memory():

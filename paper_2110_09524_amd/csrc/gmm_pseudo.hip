@@ -277,6 +277,35 @@ __global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_src(
 // LDS traffic of a group stays inside its wavefront.
 constexpr int kNrU = 8;  // gathered rows in flight per lane
 
+// PROJ variants: the pseudo-coordinates are not read from an [E, r] array but made on the spot from the
+// per-vertex scalar at the two ends of the edge, m[d] = tanh(P[d,0] c[u] + P[d,1] c[v] + pb[d]) (the
+// paper's MoNet models project the degree pair this way): one more scalar gather per edge, no
+// per-edge tensor at all.
+struct ProjArgs {
+  const float* c;   // [n]
+  const float* P;   // [r, 2]
+  const float* pb;  // [r]
+};
+struct ProjRegs {
+  float p0[kPsR], p1[kPsR], b[kPsR];
+};
+__device__ __forceinline__ ProjRegs load_proj(const ProjArgs& a, int R) {
+  ProjRegs q;
+#pragma unroll
+  for (int d = 0; d < kPsR; ++d) {
+    const bool ok = d < R;
+    q.p0[d] = ok ? a.P[2 * d] : 0.f;
+    q.p1[d] = ok ? a.P[2 * d + 1] : 0.f;
+    q.b[d] = ok ? a.pb[d] : 0.f;
+  }
+  return q;
+}
+__device__ __forceinline__ void project(const ProjRegs& q, int R, float cu, float cv, float (&m)[kPsR]) {
+#pragma unroll
+  for (int d = 0; d < kPsR; ++d) m[d] = d < R ? tanhf(fmaf(q.p0[d], cu, fmaf(q.p1[d], cv, q.b[d]))) : 0.f;
+}
+constexpr int kPsValsProj = kPsVals + 3 * kPsR;  // + (gP[d,0], gP[d,1], gpb[d]) per dimension
+
 // LDS floats of a group: G indices, then kPsK x G weights (forward, source side) or G x G partial
 // dot products (destination side)
 template <int G>
@@ -292,11 +321,12 @@ __device__ __forceinline__ void read8f(const float* p, float (&v)[kNrU]) {
 }
 
 // forward: out[v, f] = (1/K) sum_e sum_k w_k(e) hk[u, k, f]; the sum over k is taken last, across lanes
-template <int G>
+template <int G, bool PROJ>
 __global__ __launch_bounds__(kPsBlock) void k_gmmp_fwd_nr(
     RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
     const int32_t* __restrict__ indices, const float* __restrict__ hk, const float* __restrict__ pseudo,
-    const float* __restrict__ mu, const float* __restrict__ inv_sigma, PsParams pm, float* __restrict__ out) {
+    ProjArgs pa, const float* __restrict__ mu, const float* __restrict__ inv_sigma, PsParams pm,
+    float* __restrict__ out) {
   constexpr int GPB = kPsBlock / G;
   constexpr int GS = kNrGroupFloats<G>;
   __shared__ __align__(16) float lds[GPB * GS];
@@ -313,6 +343,12 @@ __global__ __launch_bounds__(kPsBlock) void k_gmmp_fwd_nr(
   const PsKernels pk = load_kernels(mu, inv_sigma, K, R);
   const int32_t v = order[r];
   const int32_t beg = indptr[v], end = indptr[v + 1];
+  ProjRegs pq;
+  float cv = 0.f;
+  if (PROJ) {
+    pq = load_proj(pa, R);
+    cv = pa.c[v];
+  }
   const bool col_ok = li < K * F4;
   const int myk = col_ok ? li / F4 : 0;
   int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
@@ -329,7 +365,8 @@ __global__ __launch_bounds__(kPsBlock) void k_gmmp_fwd_nr(
     for (int d = 0; d < kPsR; ++d) m[d] = 0.f;
     if (e_ok) {
       u = indices[e0 + li];
-      load_pseudo(pseudo, e0 + li, R, m);
+      if (PROJ) project(pq, R, pa.c[u], cv, m);
+      else load_pseudo(pseudo, e0 + li, R, m);
     }
     wave_lds_fence();  // the previous chunk's reads are done
     l_idx[li] = u;
@@ -383,16 +420,20 @@ __global__ __launch_bounds__(kPsBlock) void k_gmmp_fwd_nr(
 
 // destination side of backward: the row phase leaves every lane's part of <gout[v], hk[u, k, :]> in
 // LDS, and the lane that owns the edge adds the F/4 parts of each kernel in lane order
-template <int G>
+// PROJ: the gradient of the projection's parameters is summed here as well (slots kPsVals ... of a
+// partial row), so gpseudo is never written
+template <int G, bool PROJ>
 __global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_dst_nr(
     RowLaunch rl, const int32_t* __restrict__ order, const int32_t* __restrict__ indptr,
     const int32_t* __restrict__ indices, const float* __restrict__ hk, const float* __restrict__ pseudo,
-    const float* __restrict__ mu, const float* __restrict__ inv_sigma, const float* __restrict__ gout,
-    PsParams pm, float* __restrict__ partial, float* __restrict__ gpseudo /* nullable */) {
+    ProjArgs pa, const float* __restrict__ mu, const float* __restrict__ inv_sigma,
+    const float* __restrict__ gout, PsParams pm, float* __restrict__ partial,
+    float* __restrict__ gpseudo /* nullable */) {
   constexpr int GPB = kPsBlock / G;
   constexpr int GS = kNrGroupFloats<G>;
+  constexpr int NVALS = PROJ ? kPsValsProj : kPsVals;
   __shared__ __align__(16) float lds[GPB * GS];
-  __shared__ float blk[GPB][kPsVals];
+  __shared__ float blk[GPB][NVALS];
   const int li = threadIdx.x & (G - 1);
   const int grp = threadIdx.x / G;
   int64_t r;
@@ -409,10 +450,19 @@ __global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_dst_nr(
       gm_acc[k][d] = 0.f;
       gs_acc[k][d] = 0.f;
     }
+  float gp_acc[3 * kPsR];  // PROJ: (gP[d,0], gP[d,1], gpb[d])
+#pragma unroll
+  for (int i = 0; i < 3 * kPsR; ++i) gp_acc[i] = 0.f;
   if (active) {
     const PsKernels pk = load_kernels(mu, inv_sigma, K, R);
     const int32_t v = order[r];
     const int32_t beg = indptr[v], end = indptr[v + 1];
+    ProjRegs pq;
+    float cv = 0.f;
+    if (PROJ) {
+      pq = load_proj(pa, R);
+      cv = pa.c[v];
+    }
     const bool col_ok = li < K * F4;
     const int f4 = col_ok ? li % F4 : 0;
     const float4 g4 = col_ok ? ld4(gout + (int64_t)v * F + 4 * f4) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -424,11 +474,17 @@ __global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_dst_nr(
       const int cnt = min(G, end - e0);
       int32_t u = 0;
       float m[kPsR];
+      float cu = 0.f;
 #pragma unroll
       for (int d = 0; d < kPsR; ++d) m[d] = 0.f;
       if (e_ok) {
         u = indices[e0 + li];
-        load_pseudo(pseudo, e0 + li, R, m);
+        if (PROJ) {
+          cu = pa.c[u];
+          project(pq, R, cu, cv, m);
+        } else {
+          load_pseudo(pseudo, e0 + li, R, m);
+        }
       }
       wave_lds_fence();
       l_idx[li] = u;
@@ -470,7 +526,15 @@ __global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_dst_nr(
             gm[d] = fmaf(-t, is, gm[d]);
           }
         }
-        if (gpseudo != nullptr) {
+        if (PROJ) {
+#pragma unroll
+          for (int d = 0; d < kPsR; ++d) {
+            const float dpre = gm[d] * (1.f - m[d] * m[d]);  // through the tanh; padded dimensions: gm = 0
+            gp_acc[3 * d] = fmaf(dpre, cu, gp_acc[3 * d]);
+            gp_acc[3 * d + 1] = fmaf(dpre, cv, gp_acc[3 * d + 1]);
+            gp_acc[3 * d + 2] += dpre;
+          }
+        } else if (gpseudo != nullptr) {
 #pragma unroll
           for (int d = 0; d < kPsR; ++d)
             if (d < R) gpseudo[(int64_t)(e0 + li) * R + d] = gm[d];
@@ -494,22 +558,30 @@ __global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_dst_nr(
         blk[grp][kPsK * kPsR + k * kPsR + d] = 0.f;
       }
     }
+  if (PROJ) {
+#pragma unroll
+    for (int i = 0; i < 3 * kPsR; ++i) {
+      float a = 0.f;
+      if (i / 3 < R) a = group_sum_from<G>(gp_acc[i], 1);
+      if (li == 0) blk[grp][kPsVals + i] = a;
+    }
+  }
   __syncthreads();
-  if (threadIdx.x < kPsVals) {
+  if (threadIdx.x < NVALS) {
     float s = 0.f;
     for (int g2 = 0; g2 < GPB; ++g2) s += blk[g2][threadIdx.x];
-    partial[(int64_t)blockIdx.x * kPsVals + threadIdx.x] = s;
+    partial[(int64_t)blockIdx.x * NVALS + threadIdx.x] = s;
   }
 }
 
 // source side of backward: dhk[u, k, f] = (1/K) sum over out-edges w_k(e) gout[v, f]; the lanes of the K
 // kernels read the same columns of gout[v]
-template <int G>
+template <int G, bool PROJ>
 __global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_src_nr(
     RowLaunch rl, const int32_t* __restrict__ order_t, const int32_t* __restrict__ indptr_t,
     const int32_t* __restrict__ indices_t, const int32_t* __restrict__ eid_t,
     const float* __restrict__ pseudo, const float* __restrict__ pseudo_t /* nullable: pseudo in this walk's order */,
-    const float* __restrict__ mu, const float* __restrict__ inv_sigma,
+    ProjArgs pa, const float* __restrict__ mu, const float* __restrict__ inv_sigma,
     const float* __restrict__ gout, PsParams pm, float* __restrict__ dhk) {
   constexpr int GPB = kPsBlock / G;
   constexpr int GS = kNrGroupFloats<G>;
@@ -526,6 +598,12 @@ __global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_src_nr(
   const PsKernels pk = load_kernels(mu, inv_sigma, K, R);
   const int32_t u = order_t[r];
   const int32_t beg = indptr_t[u], end = indptr_t[u + 1];
+  ProjRegs pq;
+  float cu = 0.f;
+  if (PROJ) {
+    pq = load_proj(pa, R);
+    cu = pa.c[u];
+  }
   const bool col_ok = li < K * F4;
   const int myk = col_ok ? li / F4 : 0;
   const int f4 = col_ok ? li % F4 : 0;
@@ -543,7 +621,8 @@ __global__ __launch_bounds__(kPsBlock) void k_gmmp_bwd_src_nr(
     for (int d = 0; d < kPsR; ++d) m[d] = 0.f;
     if (e_ok) {
       v = indices_t[p0 + li];
-      if (pseudo_t != nullptr) load_pseudo(pseudo_t, p0 + li, R, m);
+      if (PROJ) project(pq, R, cu, pa.c[v], m);
+      else if (pseudo_t != nullptr) load_pseudo(pseudo_t, p0 + li, R, m);
       else load_pseudo(pseudo, eid_t[p0 + li], R, m);
     }
     wave_lds_fence();
@@ -724,7 +803,7 @@ static GmmpWs gmmp_ws_layout(const gnn_graph_t* g, int fin, int fout, int K) {
   auto take = [&](size_t bytes) { size_t o = off; off += ws_granule(bytes); return o; };
   w.nblk = ps_dst_blocks(g, fout);
   w.dhk = take(sizeof(float) * (size_t)g->n * K * fout);
-  w.partial = take(sizeof(float) * (size_t)(w.nblk + 1 + sum_partials_scratch_rows((int)w.nblk)) * kPsVals);
+  w.partial = take(sizeof(float) * (size_t)(w.nblk + 1 + sum_partials_scratch_rows((int)w.nblk)) * kPsValsProj);
   w.split_k = gemm_pick_split_k(fin, K * fout, g->n);
   w.gemm = take(w.split_k > 1 ? sizeof(float) * (size_t)w.split_k * fin * K * fout : 0);
   w.total = off;
@@ -781,8 +860,8 @@ extern "C" gnn_status_t gnn_gmmp_fwd(const gnn_graph_t* g, int fin, int fout, in
       RowLaunch rl;
       const unsigned grid = nr_grid<GL>(g, 0, rl);
       if (grid != 0) {
-        k_gmmp_fwd_nr<GL><<<grid, kPsBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, hk, pseudo, mu,
-                                                    inv_sigma, pm, out);
+        k_gmmp_fwd_nr<GL, false><<<grid, kPsBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, hk, pseudo,
+                                                           ProjArgs{}, mu, inv_sigma, pm, out);
         GNN_LAUNCH_CHECK();
       }
       return GNN_OK;
@@ -835,8 +914,9 @@ extern "C" gnn_status_t gnn_gmmp_bwd(const gnn_graph_t* g, int fin, int fout, in
       grid = G ? nr_grid<GL>(g, 0, rl) : ps_grid<L>(g, 0, rl);
       if (grid == 0) return GNN_OK;
       if (G)
-        k_gmmp_bwd_dst_nr<GL><<<grid, kPsBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, hk, pseudo, mu,
-                                                        inv_sigma, gout, pm, partial, gpseudo);
+        k_gmmp_bwd_dst_nr<GL, false><<<grid, kPsBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, hk, pseudo,
+                                                               ProjArgs{}, mu, inv_sigma, gout, pm, partial,
+                                                               gpseudo);
       else
         k_gmmp_bwd_dst<L><<<grid, kPsBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, hk, pseudo, mu,
                                                     inv_sigma, gout, pm, partial, gpseudo);
@@ -858,8 +938,9 @@ extern "C" gnn_status_t gnn_gmmp_bwd(const gnn_graph_t* g, int fin, int fout, in
       const unsigned grid = G ? nr_grid<GL>(g, 1, rl) : ps_grid<L>(g, 1, rl);
       if (grid == 0) return GNN_OK;
       if (G)
-        k_gmmp_bwd_src_nr<GL><<<grid, kPsBlock, 0, st>>>(rl, g->order[1], g->indptr_t, g->indices_t, g->eid_t,
-                                                        pseudo, pseudo_t, mu, inv_sigma, gout, pm, dhk);
+        k_gmmp_bwd_src_nr<GL, false><<<grid, kPsBlock, 0, st>>>(rl, g->order[1], g->indptr_t, g->indices_t,
+                                                               g->eid_t, pseudo, pseudo_t, ProjArgs{}, mu,
+                                                               inv_sigma, gout, pm, dhk);
       else
         k_gmmp_bwd_src<L><<<grid, kPsBlock, 0, st>>>(rl, g->order[1], g->indptr_t, g->indices_t, g->eid_t, pseudo,
                                                     pseudo_t, mu, inv_sigma, gout, pm, dhk);
@@ -924,5 +1005,110 @@ extern "C" gnn_status_t gnn_pseudo_proj_bwd(const gnn_graph_t* g, int r, const f
   GNN_TRY(sum_partials_two_level(3 * kPsR, blocks, partial, totals + 3 * kPsR, totals, st));
   k_pseudo_proj_split<<<1, 64, 0, st>>>(r, totals, gproj_w, gproj_b);
   GNN_LAUNCH_CHECK();
+  return GNN_OK;
+}
+
+// ---- MoNet layer with the projection of the degree pair fused in ------------------------------
+static gnn_status_t monet_check(const gnn_graph_t* g, int fin, int fout, int K, int R, const char* who) {
+  GNN_TRY(gmmp_check(g, fin, fout, K, R, who));
+  GNN_REQUIRE(K * fout <= 64, GNN_ERR_UNSUPPORTED,
+              "%s: k * fout = %d above 64 (wider layers: gnn_pseudo_proj_fwd + gnn_gmmp_fwd)", who, K * fout);
+  return GNN_OK;
+}
+
+extern "C" size_t gnn_monet_workspace_bytes(const gnn_graph_t* g, int fin, int fout, int k) {
+  return gnn_gmmp_workspace_bytes(g, fin, fout, k);
+}
+
+extern "C" gnn_status_t gnn_monet_fwd(const gnn_graph_t* g, int fin, int fout, int k, int r, const float* x,
+                                      const float* w_fc, const float* c, const float* proj_w,
+                                      const float* proj_b, const float* mu, const float* inv_sigma, float* hk,
+                                      float* out, void* stream) {
+  clear_error();
+  GNN_TRY(monet_check(g, fin, fout, k, r, "gnn_monet_fwd"));
+  if (g->n == 0) return GNN_OK;
+  GNN_REQUIRE(x && w_fc && c && proj_w && proj_b && mu && inv_sigma && hk && out, GNN_ERR_INVALID_ARG,
+              "gnn_monet_fwd: null pointer");
+  GNN_REQUIRE(aligned16(hk) && aligned16(out), GNN_ERR_INVALID_ARG, "gnn_monet_fwd: hk, out must be 16-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  GNN_TRY(gemm_f32(g->n, k * fout, fin, x, fin, false, w_fc, k * fout, false, hk, k * fout, 1, nullptr, st));
+  const PsParams pm{k, r, fout};
+  const ProjArgs pa{c, proj_w, proj_b};
+  ProfScope p("monet_fwd_fused", st);
+  return for_lanes(k * fout <= 32 ? 8 : 16, [&](auto lanes) -> gnn_status_t {
+    constexpr int GL = decltype(lanes)::value == 8 ? 8 : 16;
+    RowLaunch rl;
+    const unsigned grid = nr_grid<GL>(g, 0, rl);
+    if (grid != 0) {
+      k_gmmp_fwd_nr<GL, true><<<grid, kPsBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, hk, nullptr, pa, mu,
+                                                        inv_sigma, pm, out);
+      GNN_LAUNCH_CHECK();
+    }
+    return GNN_OK;
+  });
+}
+
+extern "C" gnn_status_t gnn_monet_bwd(const gnn_graph_t* g, int fin, int fout, int k, int r, const float* x,
+                                      const float* w_fc, const float* c, const float* proj_w,
+                                      const float* proj_b, const float* mu, const float* inv_sigma,
+                                      const float* hk, const float* gout, float* gx, float* gw_fc, float* gmu,
+                                      float* ginv_sigma, float* gproj_w, float* gproj_b, void* ws,
+                                      size_t ws_bytes, void* stream) {
+  clear_error();
+  GNN_TRY(monet_check(g, fin, fout, k, r, "gnn_monet_bwd"));
+  if (g->n == 0) return GNN_OK;
+  GNN_REQUIRE(x && w_fc && c && proj_w && proj_b && mu && inv_sigma && hk && gout && gw_fc && gmu && ginv_sigma &&
+                  gproj_w && gproj_b,
+              GNN_ERR_INVALID_ARG, "gnn_monet_bwd: null pointer");
+  GNN_REQUIRE(aligned16(hk) && aligned16(gout), GNN_ERR_INVALID_ARG,
+              "gnn_monet_bwd: hk, gout must be 16-byte aligned");
+  const GmmpWs W = gmmp_ws_layout(g, fin, fout, k);
+  GNN_REQUIRE(ws != nullptr && ws_bytes >= W.total, GNN_ERR_WORKSPACE,
+              "gnn_monet_bwd: workspace of %zu bytes given, %zu needed", ws_bytes, W.total);
+  GNN_REQUIRE(aligned16(ws), GNN_ERR_INVALID_ARG, "gnn_monet_bwd: workspace must be 16-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* base = static_cast<char*>(ws);
+  float* dhk = reinterpret_cast<float*>(base + W.dhk);
+  float* partial = reinterpret_cast<float*>(base + W.partial);
+  float* part = reinterpret_cast<float*>(base + W.gemm);
+  const PsParams pm{k, r, fout};
+  const ProjArgs pa{c, proj_w, proj_b};
+  const int KF = k * fout;
+  const int G = KF <= 32 ? 8 : 16;
+  {
+    ProfScope p("monet_bwd_dst", st);
+    unsigned grid = 0;
+    GNN_TRY(for_lanes(G, [&](auto lanes) -> gnn_status_t {
+      constexpr int GL = decltype(lanes)::value == 8 ? 8 : 16;
+      RowLaunch rl;
+      grid = nr_grid<GL>(g, 0, rl);
+      if (grid == 0) return GNN_OK;
+      k_gmmp_bwd_dst_nr<GL, true><<<grid, kPsBlock, 0, st>>>(rl, g->order[0], g->indptr, g->indices, hk, nullptr, pa,
+                                                            mu, inv_sigma, gout, pm, partial, nullptr);
+      GNN_LAUNCH_CHECK();
+      return GNN_OK;
+    }));
+    float* totals = partial + (int64_t)grid * kPsValsProj;
+    GNN_TRY(sum_partials_two_level(kPsValsProj, (int)grid, partial, totals + kPsValsProj, totals, st));
+    k_gmmp_param_split<<<1, 64, 0, st>>>(k, r, totals, gmu, ginv_sigma);
+    GNN_LAUNCH_CHECK();
+    k_pseudo_proj_split<<<1, 64, 0, st>>>(r, totals + kPsVals, gproj_w, gproj_b);
+    GNN_LAUNCH_CHECK();
+  }
+  {
+    ProfScope p("monet_bwd_src", st);
+    GNN_TRY(for_lanes(G, [&](auto lanes) -> gnn_status_t {
+      constexpr int GL = decltype(lanes)::value == 8 ? 8 : 16;
+      RowLaunch rl;
+      const unsigned grid = nr_grid<GL>(g, 1, rl);
+      if (grid == 0) return GNN_OK;
+      k_gmmp_bwd_src_nr<GL, true><<<grid, kPsBlock, 0, st>>>(rl, g->order[1], g->indptr_t, g->indices_t, g->eid_t,
+                                                            nullptr, nullptr, pa, mu, inv_sigma, gout, pm, dhk);
+      GNN_LAUNCH_CHECK();
+      return GNN_OK;
+    }));
+  }
+  GNN_TRY(gemm_f32(fin, KF, g->n, x, fin, true, dhk, KF, false, gw_fc, KF, W.split_k, part, st));
+  if (gx) GNN_TRY(gemm_f32(g->n, fin, KF, dhk, KF, false, w_fc, KF, true, gx, fin, 1, nullptr, st));
   return GNN_OK;
 }

@@ -98,8 +98,11 @@ class MonetLayer:
         self.g, self.fin, self.fout, self.k, self.r, self.p, self.c = graph, fin, fout, k, r, params, c
         n, e, dev = graph.n, max(graph.nnz, 1), c.device
         self.hk, self.out = _new(dev, n, k * fout), _new(dev, n, fout)
-        self.pseudo, self.gpseudo = _new(dev, e, r), _new(dev, e, r)
-        self.pseudo_t = _new(dev, e, r)   # the same coordinates in the transposed list's order
+        # up to 64 projected floats per row the projection is fused into the layer's kernels and no
+        # per-edge tensor exists; wider layers keep the coordinates, in both edge orders
+        self.fused = k * fout <= 64
+        if not self.fused:
+            self.pseudo, self.gpseudo, self.pseudo_t = _new(dev, e, r), _new(dev, e, r), _new(dev, e, r)
         self.grads = {k_: torch.empty_like(v) for k_, v in params.items()}
 
     def workspace_bytes(self):
@@ -108,6 +111,10 @@ class MonetLayer:
 
     def forward(self, x, ws):
         p = self.p
+        if self.fused:
+            B.gnn_monet_fwd(self.g, self.fin, self.fout, self.k, self.r, x, p["w_fc"], self.c, p["proj_w"],
+                            p["proj_b"], p["mu"], p["inv_sigma"], self.hk, self.out)
+            return self.out
         B.gnn_pseudo_proj_fwd(self.g, self.r, self.c, p["proj_w"], p["proj_b"], self.pseudo, pseudo_t=self.pseudo_t)
         B.gnn_gmmp_fwd(self.g, self.fin, self.fout, self.k, self.r, x, p["w_fc"], self.pseudo, p["mu"],
                        p["inv_sigma"], self.hk, self.out)
@@ -115,6 +122,11 @@ class MonetLayer:
 
     def backward(self, x, gout, gx, ws):
         p, g = self.p, self.grads
+        if self.fused:
+            B.gnn_monet_bwd(self.g, self.fin, self.fout, self.k, self.r, x, p["w_fc"], self.c, p["proj_w"],
+                            p["proj_b"], p["mu"], p["inv_sigma"], self.hk, gout, gx, g["w_fc"], g["mu"],
+                            g["inv_sigma"], g["proj_w"], g["proj_b"], ws)
+            return
         B.gnn_gmmp_bwd(self.g, self.fin, self.fout, self.k, self.r, x, p["w_fc"], self.pseudo, p["mu"],
                        p["inv_sigma"], self.hk, gout, gx, g["w_fc"], g["mu"], g["inv_sigma"], self.gpseudo, ws,
                        pseudo_t=self.pseudo_t)

@@ -319,6 +319,19 @@ def test_monet_on_the_c4_graph_sampled_rows_and_consistency(c4, sample, capsys):
     rP, rpb = om.pseudo_projection_backward(rip, rix, cvec, P, pb, bwd["gpseudo"])
     assert_close("gproj_w", gP.cpu().numpy(), rP)
     assert_close("gproj_b", gpb.cpu().numpy(), rpb)
+    say("the fused calls (what bench.py times): no per-edge array")
+    hk2, out2 = empty((n, K * fout)), empty((n, fout))
+    gx2, gw2, gmu2, gis2 = empty((n, fin)), empty((fin, K * fout)), empty((K, R)), empty((K, R))
+    gP2, gpb2 = empty((R, 2)), empty((R,))
+    pk.gnn_monet_fwd(g, fin, fout, K, R, x, dw, dc, dP, dpb, dmu, dis, hk2, out2)
+    pk.gnn_monet_bwd(g, fin, fout, K, R, x, dw, dc, dP, dpb, dmu, dis, hk2, dgo, gx2, gw2, gmu2, gis2, gP2, gpb2, ws)
+    torch.cuda.synchronize()
+    # same expressions in the same order as the two-call form above, which was checked against the oracle
+    for k, t2, t in (("hk", hk2, hk), ("out", out2, out), ("gx", gx2, gx), ("gw_fc", gw2, gw), ("gmu", gmu2, gmu),
+                     ("ginv_sigma", gis2, gis)):
+        assert torch.equal(t2, t), k
+    assert_close("gproj_w", gP2.cpu().numpy(), rP)      # summed in another order than gnn_pseudo_proj_bwd
+    assert_close("gproj_b", gpb2.cpu().numpy(), rpb)
     say("bilinearity")
     a = float((gx.double() * x.double()).sum())
     b = float((gw.double() * dw.double()).sum())
