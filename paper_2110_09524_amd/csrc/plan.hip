@@ -100,10 +100,24 @@ __global__ void k_block_keys(int32_t n, int64_t nnz, const int32_t* __restrict__
   const int64_t row = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) >> 6;
   if (row >= n) return;
   const int32_t beg = ptr[row], end = ptr[row + 1];
-  for (int32_t i = beg + lane; i < end; i += 64) {
-    const uint64_t key = (uint64_t)(cols[i] / block_cols) * (uint64_t)n + (uint64_t)row;
-    keys[i] = key;
-    atomicAdd(&counts[key], 1);  // integer count
+  // The lanes of a wavefront share the row, and within a row equal blocks usually sit next to each
+  // other (sorted columns): only the first lane of a run of equal blocks adds the run's length
+  // (one atomic per run instead of one per edge; integer counts, so the order does not matter).
+  for (int32_t i0 = beg; i0 < end; i0 += 64) {
+    const int32_t i = i0 + lane;
+    const bool valid = i < end;
+    const int32_t b = valid ? cols[i] / block_cols : -1;
+    const uint64_t key = (uint64_t)(uint32_t)b * (uint64_t)n + (uint64_t)row;
+    if (valid) keys[i] = key;
+    const int32_t b_prev = __shfl_up(b, 1, 64);
+    const bool head = valid && (lane == 0 || b != b_prev);
+    const uint64_t heads = __ballot(head);
+    const int nvalid = min(64, end - i0);  // the valid lanes are a prefix
+    if (head) {
+      const uint64_t later = lane == 63 ? 0ull : heads >> (lane + 1);
+      const int next = later != 0 ? lane + 1 + __builtin_ctzll(later) : nvalid;
+      atomicAdd(&counts[key], next - lane);
+    }
   }
 }
 
