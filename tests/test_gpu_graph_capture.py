@@ -60,3 +60,53 @@ def test_captured_gat_step_replays_exactly(name):
         for k in eager:
             assert torch.equal(eager[k], captured[k]), f"replay {replay}: {k} differs from the eager result"
     g.close()
+
+
+def test_captured_monet_step_replays_exactly():
+    """The same for the MoNet layer with the projection fused in (a two-stage fixed-order reduction of the
+    parameter gradients sits inside the captured backward call)."""
+    import torch
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev, empty, workspace
+    from workloads import make
+    print("graph capture: monet_c5", flush=True)
+    c = make("monet_c5")
+    n, fin, F, K, R = c["n"], c["fin"], c["fout"], c["k"], c["r"]
+    g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
+    x, w_fc, cc, P, pb, mu, isg, gout = (dev(c[k]) for k in ("x", "w_fc", "c", "proj_w", "proj_b", "mu", "inv_sigma",
+                                                              "gout"))
+    bufs = lambda: dict(hk=empty((n, K * F)), out=empty((n, F)), gx=empty((n, fin)), gw_fc=empty((fin, K * F)),
+                        gmu=empty((K, R)), gis=empty((K, R)), gP=empty((R, 2)), gpb=empty((R,)))
+    ws = workspace(pk.gnn_monet_workspace_bytes(g, fin, F, K))
+
+    def step(b):
+        pk.gnn_monet_fwd(g, fin, F, K, R, x, w_fc, cc, P, pb, mu, isg, b["hk"], b["out"])
+        pk.gnn_monet_bwd(g, fin, F, K, R, x, w_fc, cc, P, pb, mu, isg, b["hk"], gout, b["gx"], b["gw_fc"], b["gmu"],
+                         b["gis"], b["gP"], b["gpb"], ws)
+
+    captured = bufs()
+    side = torch.cuda.Stream()          # default priority
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(captured)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(captured)
+    rng = np.random.default_rng(23)
+    for replay in range(3):
+        x.copy_(dev(rng.standard_normal(c["x"].shape).astype(np.float32)))
+        P.mul_(-0.7)
+        torch.cuda.synchronize()
+        eager = bufs()
+        step(eager)
+        torch.cuda.synchronize()
+        for t in captured.values():
+            t.fill_(float("nan"))
+        ws.fill_(0xFF)
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in eager:
+            assert torch.equal(eager[k], captured[k]), f"replay {replay}: {k} differs from the eager result"
+    g.close()
