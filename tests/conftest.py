@@ -31,7 +31,8 @@ def _column_blocked_kernels_on_small_graphs():
 @pytest.fixture(autouse=True, scope="session")
 def _tolerance_report():
     """Writes what gpu_harness.assert_close logged about the literal tolerance (entries beyond
-    1e-5 + 1e-4 |oracle| and the worst ratio, per tensor and test) to gpurun_out/."""
+    1e-5 + 1e-4 |oracle| and the worst ratio, per tensor and test) as tolerance_report.jsonl into the
+    directory named by GNN_TEST_REPORT_DIR (default: test_reports/ at the repository root)."""
     yield
     try:
         import gpu_harness
@@ -40,7 +41,7 @@ def _tolerance_report():
     if not gpu_harness.LITERAL_LOG:
         return
     import json
-    out = os.path.join(ROOT, "gpurun_out")
+    out = os.environ.get("GNN_TEST_REPORT_DIR") or os.path.join(ROOT, "test_reports")
     os.makedirs(out, exist_ok=True)
     with open(os.path.join(out, "tolerance_report.jsonl"), "w") as f:
         for rec in gpu_harness.LITERAL_LOG:

@@ -34,7 +34,7 @@ def workspace(nbytes):
 
 # Every comparison leaves one record here: how many entries miss the literal bound
 # ATOL + RTOL * |oracle| (no scaling of the absolute term) and by what factor at worst.
-# tests/conftest.py writes the records to gpurun_out/tolerance_report.jsonl at the end of a run.
+# tests/conftest.py writes the records to tolerance_report.jsonl at the end of a run.
 LITERAL_LOG = []
 
 
