@@ -306,6 +306,9 @@ def main():
                          "position -> edge table instead of a second copy in the transposed list's order")
     ap.add_argument("--no-merge-blocks", action="store_true",
                     help="one launch per column block instead of merged launches over sparse blocks")
+    ap.add_argument("--resident-sums", type=int, default=None, choices=(0, 1),
+                    help="1: the column-blocked kernels run all blocks in one persistent launch with the "
+                         "running sums kept on the chip; 0: one launch per block group")
     ap.add_argument("--compare-unfused", action="store_true",
                     help="also time the one-operator-per-kernel comparator (GAT with heads*f = 256: forward and "
                          "backward graph operators; EdgeConv and GMM: forward)")
@@ -348,6 +351,10 @@ def main():
         pk.gnn_config_set("block_cols", args.block_cols)
     if args.no_merge_blocks:
         pk.gnn_config_set("merge_blocks", 0)
+    if args.resident_sums is not None:
+        pk.gnn_config_set("resident_sums", args.resident_sums)
+    for kv in filter(None, os.environ.get("GNN_CONFIG", "").split(",")):  # experiments: key=value,key=value
+        pk.gnn_config_set(kv.split("=")[0], int(kv.split("=")[1]))
     t0 = time.perf_counter()
     g = pk.Graph(indptr, indices)
     torch.cuda.synchronize()

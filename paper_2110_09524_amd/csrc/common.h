@@ -84,11 +84,15 @@ inline size_t ws_granule(size_t bytes) { return align_up(bytes, 256); }
 
 // most column blocks one launch of a blocked kernel covers
 constexpr int kMaxMerge = 8;
+// step counters of the persistent kernels: kClockStride ints apart, one per XCD
+constexpr int kXcds = 8;
+constexpr int kClockStride = 32;
 
 // ---- tuning knobs (runtime.hip) -------------------------------------------------
 enum ConfigKey { kCfgBlockCols = 0, kCfgForceSimple = 1, kCfgLdsScalarTable = 2, kCfgGcnMapping = 3, kCfgGmmMapping = 4, kCfgBlockedMinEdges = 5,
-                 kCfgGatherPrecision = 6, kCfgMergeBlocks = 7, kCfgWideOffsets = 8, kCfgCount };
+                 kCfgGatherPrecision = 6, kCfgMergeBlocks = 7, kCfgWideOffsets = 8, kCfgResidentSums = 9, kCfgResidentSpin = 10, kCfgCount };
 int64_t config_get(ConfigKey k);
+int device_cu_count();  // compute units of the current device (256 when the query fails)
 
 // ---- dense products (gemm.hip) ------------------------------------------------
 // c[M,N] = op(a) op(b), fp32 MFMA.  a_kmajor: a is stored [K,M] (m contiguous)
@@ -149,6 +153,10 @@ struct gnn_graph {
   int32_t* bptr[2];
   int32_t* bcol[2];
   int32_t* bseg[2];  // (begin, end) of row order[r] in block b at [b*n + r], two ints each
+  // Step counters of the persistent ("resident sums") kernels, one per XCD on a 128-byte line of
+  // its own; a launch zeroes them first.  Calls on one graph that overlap in time share them:
+  // their results stay right (the counters only pace the workgroups), their cache hit rates suffer.
+  int32_t* phase_clock;
   std::vector<int32_t> h_block_begin[2];  // host: first edge of block b (nblk + 1 entries)
   // Launch groups of the column-blocked kernels: group j covers the blocks h_group[side][a][j] ..
   // h_group[side][a][j + 1] - 1 in one launch (adjacent sparse blocks are merged, so that a row's

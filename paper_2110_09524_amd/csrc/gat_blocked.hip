@@ -567,18 +567,6 @@ static size_t staged_lds_bytes(int64_t block_cols) {
 constexpr size_t kStageLdsLimit = 152 * 1024;  // of the 160 KB a CU has
 constexpr int kStageMinEdgesPerRow = 48;        // mean edges per row of a block worth staging
 
-static int query_cu_count() {
-  int dev = 0, v = 0;
-  if (hipGetDevice(&dev) == hipSuccess &&
-      hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-    return v;
-  return 256;
-}
-static int device_cu_count() {
-  static const int cus = query_cu_count();  // one GPU type per process; initialised once, thread-safe
-  return cus;
-}
-
 // Name of a launch's timed bracket: the kernel's name, or "name#i" for the i-th launch of a pass
 // when the environment variable GNN_PROF_PER_LAUNCH is set (for tuning the launch groups).
 static const char* bracket_name(const char* name, size_t launch) {

@@ -18,6 +18,8 @@
 // a group a fixed run of consecutive edges and joins the pieces of a row that spans several
 // runs with atomic adds.  gnn_gcn_tune times both on a graph and the layer calls then use the
 // faster one per side (the profile-driven choice of the mapping).
+#include <atomic>
+
 #include "common.h"
 #include "rowgroup.h"
 
@@ -355,6 +357,174 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
   }
 }
 
+// ---- all column blocks in one persistent launch: the running sums stay in LDS ------------
+// The launches above pay for cache residency with one read-add-write of the [n, F] running sums
+// per block.  Here one workgroup per CU runs for the whole pass and keeps the sums of up to
+// kResSlots (row, slice) pairs in LDS.  It takes all of them through column block 0, then all of
+// them through block 1, and so on ("phases"); after the last block it writes the rows out once
+// and takes its next rows ("generation").  Every workgroup owns the same number of rows per
+// generation, picked from the degree order with a stride of the number of groups on the chip,
+// so all workgroups carry nearly the same load in every phase; the workgroups of an XCD start
+// a phase together (phase_sync), so an L2 serves gathers from one block at a time.  Inside a
+// workgroup the groups draw rows from an LDS counter, longest rows first, which levels the
+// segments' lengths.  A row's sums run in block order and its edges in list order, so the
+// result is bit-identical to the launch-per-block path whoever draws what.
+constexpr int kResThreads = 1024;
+constexpr int kResRows = 8;  // rows per group and generation (on average: the groups draw them)
+
+template <int SL>
+constexpr int kResSlots = (kResThreads / SL) * kResRows;
+// LDS ints of a workgroup: sums | (beg, end) of two phases | row ids | per group idx (and weights) | two counters
+template <int SL, bool W>
+constexpr int kResLdsInts = 4 * SL * kResSlots<SL> + 2 * 2 * kResSlots<SL> + kResSlots<SL> +
+                            (kResThreads / SL) * (W ? 2 : 1) * SL + 4;
+
+template <int SL, bool W>
+__global__ __launch_bounds__(kResThreads) void k_rowsum_res(
+    int32_t n_rows, const int32_t* __restrict__ order, const int2* __restrict__ bseg /* [nblk][n_rows] */,
+    const int32_t* __restrict__ bcol, const float* __restrict__ feat, int32_t block_cols, int nblk, int F,
+    int ns, const float* __restrict__ scale /* nullable: factor per row */, float* __restrict__ out,
+    const float* __restrict__ bw, int32_t* __restrict__ clock /* nullable: step counters, zeroed */,
+    int spin_limit) {
+  constexpr int GPB = kResThreads / SL;
+  constexpr int R = kResRows;
+  constexpr int NSLOT = kResSlots<SL>;
+  constexpr int U = SL < 8 ? 4 : 8;
+  static_assert(NSLOT <= kResThreads, "one thread per slot loads its segment bounds");
+  extern __shared__ __align__(16) int lds_res[];
+  const int lane = threadIdx.x & 63;
+  const int li = threadIdx.x & (SL - 1);
+  const int grp = threadIdx.x / SL;
+  const int slice = blockIdx.x % ns;
+  const int64_t nwg = gridDim.x / ns;         // workgroups that serve this slice
+  const int64_t wg = blockIdx.x / ns;
+  const int64_t ngroups = nwg * GPB;
+  float4* l_acc = reinterpret_cast<float4*>(lds_res);            // [NSLOT][SL]
+  int2* l_seg = reinterpret_cast<int2*>(lds_res + 4 * SL * NSLOT);  // [2][NSLOT]
+  int* l_row = lds_res + 4 * SL * NSLOT + 4 * NSLOT;             // [NSLOT]
+  int* l_idx = l_row + NSLOT + grp * (W ? 2 : 1) * SL;
+  float* l_w = reinterpret_cast<float*>(l_idx + SL);
+  int* l_cnt = l_row + NSLOT + GPB * (W ? 2 : 1) * SL;           // [2]
+  const int col = slice * 4 * SL + 4 * li;
+
+  const int64_t rows_per_group = (n_rows + ngroups - 1) / ngroups;
+  const int ngen = (int)((rows_per_group + R - 1) / R);
+  // workgroups go to the XCDs round-robin: those with the same id mod 8 share an L2
+  PhaseClock pc{clock ? clock + (blockIdx.x % kXcds) * kClockStride : nullptr, (int)(gridDim.x / kXcds), spin_limit,
+                false};
+
+  struct Item {
+    int32_t beg, end, c_first;
+    float w_first;
+  };
+
+  for (int gen = 0; gen < ngen; ++gen) {
+    const int64_t j0 = gen * rows_per_group / ngen, j1 = (gen + 1) * rows_per_group / ngen;
+    const int nslots = (int)(j1 - j0) * GPB;  // slot q = k * GPB + g: row at position (j0 + k) * ngroups + wg * GPB + g
+    __syncthreads();                          // the previous generation's rows are written out
+    int64_t pos = -1;                         // thread q < nslots: position of slot q's row in the degree order
+    if ((int)threadIdx.x < nslots) {
+      const int64_t r = (j0 + threadIdx.x / GPB) * ngroups + wg * GPB + threadIdx.x % GPB;
+      if (r < n_rows) pos = r;
+      l_row[threadIdx.x] = pos >= 0 ? order[pos] : -1;
+      l_seg[threadIdx.x] = pos >= 0 ? bseg[pos] : make_int2(0, 0);
+    }
+    for (int i = threadIdx.x; i < nslots * SL; i += kResThreads) l_acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (threadIdx.x == 0) l_cnt[0] = 0;
+
+    for (int p = 0; p < nblk; ++p) {
+      const int32_t col_begin = p * block_cols;
+      phase_sync(pc, gen * nblk + p);
+      const int2* seg_p = l_seg + (p & 1) * NSLOT;
+      int* cnt_p = l_cnt + (p & 1);
+      // the next phase's bounds travel while this one is worked on
+      int2 seg_next = make_int2(0, 0);
+      if (p + 1 < nblk && pos >= 0) seg_next = bseg[(int64_t)(p + 1) * n_rows + pos];
+      if (threadIdx.x == 0) l_cnt[(p + 1) & 1] = 0;
+
+      auto grab = [&]() {
+        int q = 0;
+        if (li == 0) q = atomicAdd(cnt_p, 1);
+        return __shfl(q, lane & ~(SL - 1), 64);
+      };
+      auto fetch = [&](int q) {
+        Item it{0, 0, col_begin, 0.f};
+        if (q >= nslots) return it;
+        const int2 sg = seg_p[q];
+        it.beg = sg.x;
+        it.end = sg.y;
+        if (it.beg + li < it.end) {
+          it.c_first = bcol[it.beg + li];
+          if (W) it.w_first = bw[it.beg + li];
+        }
+        return it;
+      };
+
+      int q = grab();
+      Item cur = fetch(q);
+      while (q < nslots) {
+        const int qn = grab();
+        const Item nxt = fetch(qn);
+        const int32_t beg = cur.beg, end = cur.end;
+        if (beg < end) {
+          float4 acc = l_acc[q * SL + li];
+          int32_t c_next = cur.c_first;
+          float w_next = cur.w_first;
+          for (int32_t c0 = beg; c0 < end; c0 += SL) {
+            const int32_t c = c0 + li < end ? c_next : col_begin;
+            const float wv = c0 + li < end ? w_next : 0.f;
+            if (c0 + SL + li < end) {
+              c_next = bcol[c0 + SL + li];
+              if (W) w_next = bw[c0 + SL + li];
+            }
+            l_idx[li] = c;
+            if (W) l_w[li] = wv;
+            wave_lds_fence();
+            const int cn = min(SL, end - c0);
+            float4 part = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int t0 = 0; t0 < SL; t0 += U) {
+              int idv[U];
+#pragma unroll
+              for (int qq = 0; qq < U / 4; ++qq) {
+                const int4 i4 = *reinterpret_cast<const int4*>(l_idx + t0 + 4 * qq);
+                idv[4 * qq] = i4.x; idv[4 * qq + 1] = i4.y; idv[4 * qq + 2] = i4.z; idv[4 * qq + 3] = i4.w;
+              }
+              float4 rowv[U];
+#pragma unroll
+              for (int t4 = 0; t4 < U; t4 += 4)
+                if (t0 + t4 < cn) {
+#pragma unroll
+                  for (int t = t4; t < t4 + 4; ++t) rowv[t] = ld4(feat + (int64_t)idv[t] * F + col);
+                }
+#pragma unroll
+              for (int t4 = 0; t4 < U; t4 += 4)
+                if (t0 + t4 < cn) {
+#pragma unroll
+                  for (int t = t4; t < t4 + 4; ++t) fma4(part, W ? l_w[t0 + t] : (t0 + t < cn ? 1.f : 0.f), rowv[t]);
+                }
+            }
+            add4(acc, part);
+            wave_lds_fence();
+          }
+          l_acc[q * SL + li] = acc;
+        }
+        q = qn;
+        cur = nxt;
+      }
+      if ((int)threadIdx.x < nslots) l_seg[((p + 1) & 1) * NSLOT + threadIdx.x] = seg_next;
+    }
+    __syncthreads();
+    for (int q = grp; q < nslots; q += GPB) {
+      const int32_t row = l_row[q];
+      if (row < 0) continue;
+      float4 acc = l_acc[q * SL + li];
+      if (scale != nullptr) scale4(acc, scale[row]);
+      st4_stream(out + (int64_t)row * F + col, acc);
+    }
+  }
+}
+
 // A row of F floats is cut into `ns` slices of SL float4.  Slices of 256 bytes where the row has
 // 2, 4 or 8 of them (measured at 1 KB rows: 17.8 -> 17.2 ms per layer against 8 slices of 128
 // bytes, 22.9 ms with two of 512); wider rows have 8 slices, one per XCD.  With fewer than 8,
@@ -409,6 +579,38 @@ static gnn_status_t launch_rowsum_blocks(const gnn_graph_t* g, int side, const c
                                                          b * g->block_cols, F, b == 0, ns, acc, nseg);
     GNN_LAUNCH_CHECK();
   }
+  return GNN_OK;
+}
+
+__global__ void k_zero_clock(int32_t* __restrict__ clock) { clock[threadIdx.x] = 0; }
+
+// LDS of the persistent kernel; more than 64 KB of dynamic LDS needs the attribute once per instantiation
+constexpr size_t kResLdsLimit = 152 * 1024;
+template <int SL, bool W>
+static gnn_status_t launch_rowsum_resident(const gnn_graph_t* g, int side, const char* name, const float* feat,
+                                           int F, const float* scale, float* out, hipStream_t st,
+                                           const float* bw) {
+  const int ns = F / (4 * SL);
+  const size_t lds = sizeof(int) * (size_t)kResLdsInts<SL, W>;
+  GNN_REQUIRE(lds <= kResLdsLimit, GNN_ERR_UNSUPPORTED, "gcn resident: %zu bytes of LDS", lds);
+  static std::atomic<bool> attr_set{false};
+  if (!attr_set.load(std::memory_order_acquire)) {
+    GNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_rowsum_res<SL, W>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kResLdsLimit));
+    attr_set.store(true, std::memory_order_release);
+  }
+  // one workgroup per CU, a multiple of the slice count so that every XCD serves one slice
+  const unsigned grid = (unsigned)(device_cu_count() / kXcds * kXcds);
+  ProfScope p(name, st);
+  int32_t* clock = g->phase_clock;
+  if (clock != nullptr) {
+    k_zero_clock<<<1, kXcds * kClockStride, 0, st>>>(clock);
+    GNN_LAUNCH_CHECK();
+  }
+  k_rowsum_res<SL, W><<<grid, kResThreads, lds, st>>>(g->n, g->order[side], reinterpret_cast<const int2*>(g->bseg[side]),
+                                                     g->bcol[side], feat, g->block_cols, g->nblk, F, ns, scale, out, bw,
+                                                     clock, (int)config_get(kCfgResidentSpin));
+  GNN_LAUNCH_CHECK();
   return GNN_OK;
 }
 
@@ -507,6 +709,8 @@ static gnn_status_t gcn_aggregate_vertex(const gnn_graph_t* g, int side, const c
   if (gcn_blocked_applies(g, F)) {
     int SL = 0, ns = 0;
     gcn_slicing(F, SL, ns);
+    if (config_get(kCfgResidentSums) && SL == 16)
+      return launch_rowsum_resident<16, false>(g, side, name, feat, F, scale, out, st, nullptr);
     switch (SL) {
       case 8: GNN_TRY(launch_rowsum_blocks<8>(g, side, name, feat, F, out, st)); break;
       case 16: GNN_TRY(launch_rowsum_blocks<16>(g, side, name, feat, F, out, st)); break;
@@ -536,6 +740,8 @@ static gnn_status_t gcn_aggregate_weighted(const gnn_graph_t* g, const gnn_edge_
   if (gcn_blocked_applies(g, F) && ew->w_blk[side] != nullptr) {
     int SL = 0, ns = 0;
     gcn_slicing(F, SL, ns);
+    if (config_get(kCfgResidentSums) && SL == 16)
+      return launch_rowsum_resident<16, true>(g, side, name, feat, F, nullptr, out, st, ew->w_blk[side]);
     switch (SL) {
       case 8: return launch_rowsum_blocks<8>(g, side, name, feat, F, out, st, ew->w_blk[side]);
       case 16: return launch_rowsum_blocks<16>(g, side, name, feat, F, out, st, ew->w_blk[side]);

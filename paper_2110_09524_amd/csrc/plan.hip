@@ -237,6 +237,7 @@ static void free_all(gnn_graph* g) {
     pool_free(g->bcol[s]);
     pool_free(g->bseg[s]);
   }
+  pool_free(g->phase_clock);
   delete g;
 }
 
@@ -517,6 +518,7 @@ static gnn_status_t build(gnn_graph* g, hipStream_t st) {
     g->nblk = (int32_t)cdiv(n, g->block_cols);
     GNN_TRY(build_blocked(g, 0, g->indptr, g->indices, st));
     GNN_TRY(build_blocked(g, 1, g->indptr_t, g->indices_t, st));
+    GNN_HIP(pool_alloc((void**)&g->phase_clock, sizeof(int32_t) * kXcds * kClockStride));
   }
   GNN_HIP(hipStreamSynchronize(st));
   finish_side(g, 0, stage);

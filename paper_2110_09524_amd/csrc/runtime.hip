@@ -38,8 +38,24 @@ void clear_error() { g_err[0] = 0; }
 // (read at gnn_graph_create), 0 every block has its own launch
 // wide_offsets: 1 makes the column-blocked GAT kernels address gathered rows with 64-bit offsets
 // also where 32 bits reach every row (the path of matrices of 4 GB and more; a test hook)
-static std::atomic<int64_t> g_config[kCfgCount] = {{20480}, {0}, {1}, {2}, {2}, {16}, {0}, {1}, {0}};
+// resident_sums: 1 lets the column-blocked aggregations run all blocks in one persistent launch
+// that keeps the rows' running sums on the chip (LDS) instead of reading and writing them per block
+static std::atomic<int64_t> g_config[kCfgCount] = {{20480}, {0}, {1}, {2}, {2}, {16}, {0}, {1}, {0}, {0}, {4096}};
+// resident_spin: polls after which a workgroup of that launch stops waiting for the others of its XCD
+// at a block boundary (the wait only paces the workgroups; 0 = never wait)
 int64_t config_get(ConfigKey k) { return g_config[k].load(std::memory_order_relaxed); }
+
+static int query_cu_count() {
+  int dev = 0, v = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+    return v;
+  return 256;
+}
+int device_cu_count() {
+  static const int cus = query_cu_count();  // one GPU type per process; initialised once, thread-safe
+  return cus;
+}
 
 // ---- profiling ---------------------------------------------------------------
 struct Pending {
@@ -132,6 +148,15 @@ extern "C" gnn_status_t gnn_config_set(const char* key, int64_t value) {
   }
   if (std::strcmp(key, "wide_offsets") == 0) {
     g_config[kCfgWideOffsets].store(value != 0);
+    return GNN_OK;
+  }
+  if (std::strcmp(key, "resident_sums") == 0) {
+    g_config[kCfgResidentSums].store(value != 0);
+    return GNN_OK;
+  }
+  if (std::strcmp(key, "resident_spin") == 0) {
+    GNN_REQUIRE(value >= 0 && value <= (1 << 24), GNN_ERR_INVALID_ARG, "gnn_config_set: resident_spin out of range");
+    g_config[kCfgResidentSpin].store(value);
     return GNN_OK;
   }
   if (std::strcmp(key, "merge_blocks") == 0) {

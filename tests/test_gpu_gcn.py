@@ -69,8 +69,11 @@ def test_graph_without_edges():
 
 
 @pytest.mark.parametrize("block_cols,fout", [(256, 256), (500, 128), (300, 512), (128, 1024), (256, 64)])
-@pytest.mark.parametrize("merge", [0, 1])
+@pytest.mark.parametrize("merge", [0, 1, 2, 3])
 def test_column_blocked_path(block_cols, fout, merge):
+    """merge 0 / 1: one launch per block / merged launches; 2: all blocks in one persistent launch
+    (running sums in LDS); 3: the same with the workgroups' bounded wait for each other cut to zero
+    polls, which must not change any result."""
     import paper_2110_09524_amd as pk
     from gpu_harness import dev
     print(f"gcn: blocked path block_cols={block_cols} fout={fout} merge={merge}", flush=True)
@@ -78,19 +81,23 @@ def test_column_blocked_path(block_cols, fout, merge):
     indptr, indices = random_graph(rng, 1500, 30000, self_loops=False, duplicates=True)
     c = synth(rng, indptr, indices, 24, fout)
     pk.gnn_config_set("block_cols", block_cols)
-    pk.gnn_config_set("merge_blocks", merge)
+    pk.gnn_config_set("merge_blocks", int(merge == 1))
+    pk.gnn_config_set("resident_sums", int(merge >= 2))
+    pk.gnn_config_set("resident_spin", 0 if merge == 3 else 4096)
     try:
         g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
         nb = g.blocked(0)[0]
         assert nb == -(-c["n"] // block_cols)
         launches = len(g.launch_groups(0, 1)) - 1
         print(f"  {nb} blocks in {launches} launches", flush=True)
-        assert launches == nb if not merge else 1 <= launches <= nb
+        assert launches == nb if merge != 1 else 1 <= launches <= nb
         check(c, graph=g)
         g.close()
     finally:
         pk.gnn_config_set("block_cols", 20480)
         pk.gnn_config_set("merge_blocks", 1)
+        pk.gnn_config_set("resident_sums", 0)
+        pk.gnn_config_set("resident_spin", 4096)
 
 
 def test_bad_arguments_raise():
@@ -256,20 +263,24 @@ def test_edge_weighted_shapes(fin, fout):
 
 
 @pytest.mark.parametrize("block_cols,fout", [(256, 256), (1000, 128), (300, 512), (128, 1024)])
-def test_edge_weighted_column_blocked_path(block_cols, fout):
+@pytest.mark.parametrize("resident", [0, 1])
+def test_edge_weighted_column_blocked_path(block_cols, fout, resident):
     """The same on the column-blocked kernels: the weights travel in the order of the blocked edge
-    lists (sorted once with the plan's keys), both sides, merged launches included."""
+    lists (sorted once with the plan's keys), both sides, merged launches included; resident = 1:
+    all blocks in one persistent launch."""
     import paper_2110_09524_amd as pk
-    print(f"gcn: per-edge weights, blocked, block_cols={block_cols} fout={fout}", flush=True)
+    print(f"gcn: per-edge weights, blocked, block_cols={block_cols} fout={fout} resident={resident}", flush=True)
     rng = np.random.default_rng(block_cols + fout)
     indptr, indices = random_graph(rng, 1500, 30000, self_loops=False, duplicates=True)
     c = synth(rng, indptr, indices, 24, fout)
     c["ew"] = rng.uniform(-2.0, 2.0, len(indices)).astype(np.float32)
     pk.gnn_config_set("block_cols", block_cols)
+    pk.gnn_config_set("resident_sums", resident)
     try:
         _, nblk = check_edge(c)
     finally:
         pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("resident_sums", 0)
     assert nblk == -(-1500 // block_cols)
 
 
