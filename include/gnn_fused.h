@@ -31,9 +31,10 @@
  *     written and gnn_last_error() returns a thread-local, library-owned string.
  *   - Outputs are bit-reproducible from run to run: sums are taken in a fixed order and
  *     there are no floating-point atomics.  One exception, never taken silently: the
- *     edge-balanced mapping of the GCN sum and of the GMM forward pass adds the pieces
- *     of rows that span several runs with atomics; it runs only after gnn_gcn_tune /
- *     gnn_gmm_tune has measured it faster on a graph, or when the configuration key
+ *     edge-balanced mapping of the GCN sums, of the GMM forward pass and of the source side
+ *     of the GMM backward pass adds the pieces of rows that span several runs with atomics;
+ *     it runs only after gnn_gcn_tune / gnn_gmm_tune / gnn_gmm_tune_bwd has measured it
+ *     faster on a graph, or when the configuration key
  *     gcn_mapping / gmm_mapping is set to 1, and rows above 64 (32) edges may then
  *     differ in the last bits from run to run.
  */
@@ -172,8 +173,9 @@ gnn_status_t gnn_release_cached_memory(void);
  *   "gcn_mapping"           thread mapping of the GCN aggregation: 0 vertex-balanced,
  *                           1 edge-balanced, 2 (default) what gnn_gcn_tune measured as
  *                           faster on the graph (vertex-balanced if it never ran)
- *   "gmm_mapping"           the same for the forward aggregation of the GMM layer
- *                           (gnn_gmm_tune; the edge-balanced mapping takes at most 4 kernels)
+ *   "gmm_mapping"           the same for the forward aggregation of the GMM layer and the two
+ *                           halves of its backward pass (gnn_gmm_tune, gnn_gmm_tune_bwd; the
+ *                           edge-balanced mapping takes at most 4 kernels)
  * Errors: INVALID_ARG for an unknown key or a value out of range. */
 gnn_status_t gnn_config_set(const char* key, int64_t value);
 
@@ -362,6 +364,21 @@ gnn_status_t gnn_gmm_bwd(const gnn_graph_t* graph, int fin, int fout, int k, con
 gnn_status_t gnn_gmm_tune(gnn_graph_t* graph, int fout, int k, const float* hk /*[n,k*fout]*/,
                           const float* c, const float* mu, const float* inv_sigma, float* out /*[n,fout]*/,
                           void* stream, float* ms_out /*host [2], nullable*/);
+
+/* The same choice for the two halves of gnn_gmm_bwd (Sec. 5): the destination side (gradients of
+ * mu and inv_sigma; its edge-balanced form needs no atomics, a row's pieces are complete on their
+ * own because the gradients are linear in the per-edge terms) and the source side (dhk; pieces of
+ * rows that span several runs of 32 edges are added atomically).  Runs each half in both mappings
+ * on the tensors of a backward call and records the faster mapping per half in the graph handle;
+ * gnn_gmm_bwd follows it while "gmm_mapping" is 2 (the destination side only where the layer
+ * projects first, which is what the timing compares with).  ws as for gnn_gmm_bwd; its contents
+ * are scratch afterwards.  ms_out (host, nullable): 4 floats, milliseconds per pass {destination
+ * vertex-balanced, edge-balanced, source vertex-balanced, edge-balanced} (zeros when k > 4 or the
+ * graph has no edges).  Waits for the stream.  Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
+gnn_status_t gnn_gmm_tune_bwd(gnn_graph_t* graph, int fin, int fout, int k, const float* hk /*[n,k*fout]*/,
+                              const float* c, const float* mu, const float* inv_sigma,
+                              const float* gout /*[n,fout]*/, void* ws, size_t ws_bytes, void* stream,
+                              float* ms_out /*host [4], nullable*/);
 
 /* ------------------------------------------------------------------------- *
  * MoNet / GMMConv layer with general pseudo-coordinates (App. A.2 "GMMConv"; Sec. 7.2 uses

@@ -6,7 +6,7 @@ from .binding import (  # noqa: F401
     gnn_config_set, gnn_linear_fwd, gnn_release_cached_memory,
     gnn_gat_workspace_bytes, gnn_gat_fwd, gnn_gat_bwd, gnn_gat_bwd_noalloc, NOALLOC_SCRATCH_BYTES, gnn_gat_blocked_kernel_name, gnn_gat_stash_alpha, gnn_gat_stash_layout, gnn_gat_bwd_stashed,
     gnn_edgeconv_workspace_bytes, gnn_edgeconv_fwd, gnn_edgeconv_bwd,
-    gnn_gmm_workspace_bytes, gnn_gmm_fwd, gnn_gmm_bwd, gnn_gmm_tune,
+    gnn_gmm_workspace_bytes, gnn_gmm_fwd, gnn_gmm_bwd, gnn_gmm_tune, gnn_gmm_tune_bwd,
     gnn_gmmp_workspace_bytes, gnn_gmmp_fwd, gnn_gmmp_bwd,
     gnn_pseudo_proj_workspace_bytes, gnn_pseudo_proj_fwd, gnn_pseudo_proj_bwd,
     gnn_monet_workspace_bytes, gnn_monet_fwd, gnn_monet_bwd,

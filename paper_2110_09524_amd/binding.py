@@ -23,7 +23,7 @@ EXPORTS = [
     "gnn_last_error", "gnn_graph_create", "gnn_graph_destroy", "gnn_graph_get_csc",
     "gnn_graph_get_buckets", "gnn_graph_get_blocked", "gnn_graph_get_launch_groups", "gnn_release_cached_memory", "gnn_config_set", "gnn_linear_fwd", "gnn_gat_workspace_bytes", "gnn_gat_fwd",
     "gnn_gat_bwd", "gnn_gat_bwd_noalloc", "gnn_gat_blocked_kernel_name", "gnn_gat_stash_layout", "gnn_gat_stash_alpha", "gnn_gat_bwd_stashed", "gnn_edgeconv_workspace_bytes", "gnn_edgeconv_fwd", "gnn_edgeconv_bwd",
-    "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd", "gnn_gmm_tune",
+    "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd", "gnn_gmm_tune", "gnn_gmm_tune_bwd",
     "gnn_gmmp_workspace_bytes", "gnn_gmmp_fwd", "gnn_gmmp_bwd", "gnn_pseudo_proj_workspace_bytes",
     "gnn_pseudo_proj_fwd", "gnn_pseudo_proj_bwd", "gnn_monet_workspace_bytes", "gnn_monet_fwd", "gnn_monet_bwd",
     "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_gcn_tune",
@@ -77,6 +77,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_gmm_fwd.argtypes = [vp, i32, i32, i32] + [vp] * 7 + [vp, sz, vp]
     lib.gnn_gmm_bwd.argtypes = [vp, i32, i32, i32] + [vp] * 11 + [vp, sz, vp]
     lib.gnn_gmm_tune.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, C.POINTER(C.c_float)]
+    lib.gnn_gmm_tune_bwd.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, C.c_size_t, vp, C.POINTER(C.c_float)]
     lib.gnn_gmmp_workspace_bytes.restype = sz
     lib.gnn_gmmp_workspace_bytes.argtypes = [vp, i32, i32, i32]
     lib.gnn_gmmp_fwd.argtypes = [vp, i32, i32, i32, i32] + [vp] * 7 + [vp]
@@ -379,6 +380,15 @@ def gnn_gmm_tune(g: Graph, fout, k, hk, c, mu, inv_sigma, out, stream=None):
     """Returns the two measured times (ms): vertex-balanced, edge-balanced forward aggregation."""
     ms = (C.c_float * 2)()
     _check(lib().gnn_gmm_tune(g.handle, fout, k, _f(hk), _f(c), _f(mu), _f(inv_sigma), _f(out), _stream(stream), ms))
+    return [float(v) for v in ms]
+
+
+def gnn_gmm_tune_bwd(g: Graph, fin, fout, k, hk, c, mu, inv_sigma, gout, ws, stream=None):
+    """Returns the four measured times (ms): destination side vertex-/edge-balanced, source side likewise."""
+    wp, wb = _ws_args(ws)
+    ms = (C.c_float * 4)()
+    _check(lib().gnn_gmm_tune_bwd(g.handle, fin, fout, k, _f(hk), _f(c), _f(mu), _f(inv_sigma), _f(gout), wp, wb,
+                                  _stream(stream), ms))
     return [float(v) for v in ms]
 
 

@@ -170,4 +170,5 @@ struct gnn_graph {
   }
   int8_t gcn_edge_balanced[2];  // per side: -1 not tuned, 0 / 1 what gnn_gcn_tune found faster
   int8_t gmm_edge_balanced;     // forward aggregation: -1 not tuned, 0 / 1 what gnn_gmm_tune found faster
+  int8_t gmm_bwd_edge_balanced[2];  // backward, destination / source side: the same from gnn_gmm_tune_bwd
 };

@@ -134,13 +134,15 @@ __global__ void k_zero_f4(int64_t quads, float* __restrict__ p) {
   if (i < quads) st4(p + 4 * i, make_float4(0.f, 0.f, 0.f, 0.f));
 }
 
-template <int L, int NV>
+// W: every edge carries a static weight (wgt, in the order of cols); scale may then be null
+template <int L, int NV, bool W = false>
 __global__ __launch_bounds__(kGcnBlock) void k_rowsum_eb(
     int32_t n, int32_t nnz, const int32_t* __restrict__ ptr, const int32_t* __restrict__ cols,
-    const float* __restrict__ feat, int F, const float* __restrict__ scale, float* __restrict__ out) {
+    const float* __restrict__ feat, int F, const float* __restrict__ scale, float* __restrict__ out,
+    const float* __restrict__ wgt = nullptr) {
   constexpr int GPB = kGcnBlock / L;
   constexpr int U = 4;
-  constexpr int GS = kEbEdges + U;  // the run's gathered vertices, then U entries of padding
+  constexpr int GS = (W ? 2 : 1) * (kEbEdges + U);  // the run's gathered vertices (and weights), each with U entries of padding
   __shared__ int lds[GPB * GS];
   const int lane = threadIdx.x & 63;
   const int li = lane & (L - 1);
@@ -150,7 +152,11 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_eb(
   const int32_t e0 = (int32_t)(run * kEbEdges);
   const int32_t e1 = min(e0 + kEbEdges, nnz);
   int* l_idx = lds + grp * GS;
-  for (int i = li; i < GS; i += L) l_idx[i] = e0 + i < e1 ? cols[e0 + i] : 0;  // padding gathers row 0, weight 0
+  float* l_wt = reinterpret_cast<float*>(l_idx + kEbEdges + U);
+  for (int i = li; i < kEbEdges + U; i += L) {
+    l_idx[i] = e0 + i < e1 ? cols[e0 + i] : 0;  // padding gathers row 0, weight 0
+    if (W) l_wt[i] = e0 + i < e1 ? wgt[e0 + i] : 0.f;
+  }
 
   // row of the first edge: ptr[lo] <= e0 < ptr[hi] throughout (ptr[0] = 0, ptr[n] = nnz)
   int32_t lo = 0, hi = n;
@@ -185,10 +191,11 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_eb(
 #pragma unroll
         for (int t = 0; t < U; ++t) rowv[t] = ld4(feat + (int64_t)uu[t] * F + 4 * (li + j * L));
 #pragma unroll
-        for (int t = 0; t < U; ++t) fma4(acc[j], t0 + t < seg_end ? 1.f : 0.f, rowv[t]);
+        for (int t = 0; t < U; ++t)
+          fma4(acc[j], t0 + t < seg_end ? (W ? l_wt[t0 - e0 + t] : 1.f) : 0.f, rowv[t]);
       }
     }
-    const float s = scale[v];
+    const float s = scale != nullptr ? scale[v] : 1.f;
     const bool whole = row_beg >= e0 && row_end <= e1;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
@@ -674,6 +681,26 @@ struct RowsumEbLauncher {
   }
 };
 
+template <int L, int NV>
+struct RowsumWeightedEbLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, int side, const char* name, const float* feat, int F,
+                          const float* wgt, float* out, hipStream_t st) {
+    constexpr int GPB = kGcnBlock / L;
+    ProfScope p(name, st);
+    const int64_t quads = (int64_t)g->n * (F / 4);
+    k_zero_f4<<<(unsigned)cdiv(quads, 256), 256, 0, st>>>(quads, out);
+    GNN_LAUNCH_CHECK();
+    const int64_t runs = cdiv(g->nnz, kEbEdges);
+    if (runs != 0) {
+      k_rowsum_eb<L, NV, true><<<(unsigned)cdiv(runs, GPB), kGcnBlock, 0, st>>>(
+          g->n, (int32_t)g->nnz, side == 0 ? g->indptr : g->indptr_t, side == 0 ? g->indices : g->indices_t,
+          feat, F, nullptr, out, wgt);
+      GNN_LAUNCH_CHECK();
+    }
+    return GNN_OK;
+  }
+};
+
 template <template <int, int> class Launcher>
 static gnn_status_t dispatch_rowsum(const gnn_graph_t* g, int side, const char* name, const float* feat, int F,
                                     const float* scale, float* out, hipStream_t st) {
@@ -737,6 +764,9 @@ static gnn_status_t gcn_aggregate(const gnn_graph_t* g, int side, const char* na
 static gnn_status_t gcn_aggregate_weighted(const gnn_graph_t* g, const gnn_edge_weights* ew, int side,
                                            const char* name, const float* feat, int F, float* out,
                                            hipStream_t st) {
+  // edge-balanced only on request (gcn_mapping = 1): gnn_gcn_tune times the unweighted sums
+  if (config_get(kCfgGcnMapping) == 1)
+    return dispatch_rowsum<RowsumWeightedEbLauncher>(g, side, name, feat, F, ew->w_side[side], out, st);
   if (gcn_blocked_applies(g, F) && ew->w_blk[side] != nullptr) {
     int SL = 0, ns = 0;
     gcn_slicing(F, SL, ns);

@@ -795,6 +795,293 @@ __global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_src(
   }
 }
 
+// ---- a10, edge-balanced mapping of both halves of the backward pass (Sec. 5) --------------
+// As k_gmm_fwd_eb: a group owns kGmmEbEdges consecutive positions of an edge array and walks the
+// row pieces inside its run.  At most kGmmKB kernels.
+//
+// Source side (edge array of the CSC transpose): dhk[u,j,:] = (1/K) sum over out-edges
+// w_j(e) gout[v,:]; an edge gathers gout[v] once for all kernels.  Pieces of rows that span
+// several runs are added atomically onto a dhk zeroed before.
+template <int L, int NV>
+__global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_src_eb(
+    int32_t n, int32_t nnz, const int32_t* __restrict__ indptr_t, const int32_t* __restrict__ indices_t,
+    const float* __restrict__ c, const float* __restrict__ mu, const float* __restrict__ inv_sigma,
+    const float* __restrict__ gout, GmmParams pm, float* __restrict__ dhk) {
+  constexpr int GPB = kGmmBlock / L;
+  constexpr int KB = kGmmKB, U = 4, RUN = kGmmEbEdges;
+  constexpr int GS = (1 + KB) * (RUN + U);  // idx | w[KB], each with U entries of padding
+  __shared__ __align__(16) float lds[GPB * GS];
+  const int lane = threadIdx.x & 63;
+  const int li = lane & (L - 1);
+  const int grp = threadIdx.x / L;
+  const int64_t run = (int64_t)blockIdx.x * GPB + grp;
+  if (run * RUN >= nnz) return;
+  const int32_t e0 = (int32_t)(run * RUN);
+  const int32_t e1 = min(e0 + RUN, nnz);
+  int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
+  float* l_w = lds + grp * GS + (RUN + U);
+  const int K = pm.K, F = pm.F, KF = K * F;
+  const float inv_k = 1.f / (float)K;
+
+  for (int i = li; i < RUN + U; i += L) {
+    l_idx[i] = e0 + i < e1 ? indices_t[e0 + i] : 0;  // padding gathers row 0 with weight 0
+#pragma unroll
+    for (int q = 0; q < KB; ++q) l_w[q * (RUN + U) + i] = 0.f;
+  }
+  float mu0[KB], mu1[KB], is0[KB], is1[KB];
+#pragma unroll
+  for (int q = 0; q < KB; ++q) {
+    const bool ok = q < K;
+    mu0[q] = ok ? mu[2 * q] : 0.f;
+    mu1[q] = ok ? mu[2 * q + 1] : 0.f;
+    is0[q] = ok ? inv_sigma[2 * q] : 0.f;
+    is1[q] = ok ? inv_sigma[2 * q + 1] : 0.f;
+  }
+  int32_t lo = 0, hi = n;  // row of the first edge: indptr_t[lo] <= e0 < indptr_t[hi] throughout
+  while (hi - lo > 1) {
+    const int32_t mid = (lo + hi) >> 1;
+    if (indptr_t[mid] <= e0) lo = mid; else hi = mid;
+  }
+  int32_t u = lo, row_beg = indptr_t[u], row_end = indptr_t[u + 1];
+  wave_lds_fence();
+
+  bool slot_ok[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) slot_ok[j] = 4 * (li + j * L) < F;
+
+  int32_t e = e0;
+  while (e < e1) {
+    const int32_t seg_end = min(row_end, e1);
+    const float cu = c[u];
+    for (int32_t t = e + li; t < seg_end; t += L) {
+      const float cv = c[l_idx[t - e0]];
+#pragma unroll
+      for (int q = 0; q < KB; ++q)
+        if (q < K) l_w[q * (RUN + U) + (t - e0)] = gauss_w(cu, cv, mu0[q], mu1[q], is0[q], is1[q]) * inv_k;
+    }
+    wave_lds_fence();
+    float4 acc[KB][NV];
+#pragma unroll
+    for (int q = 0; q < KB; ++q)
+#pragma unroll
+      for (int j = 0; j < NV; ++j) acc[q][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int32_t t0 = e; t0 < seg_end; t0 += U) {
+      int vv[U];
+      float ok[U];
+#pragma unroll
+      for (int t = 0; t < U; ++t) {
+        vv[t] = l_idx[t0 - e0 + t];
+        if (L == 64) vv[t] = __builtin_amdgcn_readfirstlane(vv[t]);
+        ok[t] = t0 + t < seg_end ? 1.f : 0.f;  // entries past the piece belong to the next row
+      }
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        if (!slot_ok[j]) continue;
+        float4 rowv[U];
+#pragma unroll
+        for (int t = 0; t < U; ++t) rowv[t] = ld4(gout + (int64_t)vv[t] * F + 4 * (li + j * L));
+#pragma unroll
+        for (int t = 0; t < U; ++t)
+#pragma unroll
+          for (int q = 0; q < KB; ++q)
+            if (q < K) fma4(acc[q][j], ok[t] * l_w[q * (RUN + U) + (t0 - e0 + t)], rowv[t]);
+      }
+    }
+    const bool whole = row_beg >= e0 && row_end <= e1;
+#pragma unroll
+    for (int q = 0; q < KB; ++q) {
+      if (q >= K) continue;
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        if (!slot_ok[j]) continue;
+        float* o = dhk + (int64_t)u * KF + q * F + 4 * (li + j * L);
+        if (whole) {
+          st4(o, acc[q][j]);
+        } else {
+          unsafeAtomicAdd(o, acc[q][j].x);
+          unsafeAtomicAdd(o + 1, acc[q][j].y);
+          unsafeAtomicAdd(o + 2, acc[q][j].z);
+          unsafeAtomicAdd(o + 3, acc[q][j].w);
+        }
+      }
+    }
+    e = seg_end;
+    if (e < e1) {  // the next row that has edges starts at e
+      do {
+        ++u;
+        row_beg = row_end;
+        row_end = indptr_t[u + 1];
+      } while (row_end == row_beg);
+    }
+  }
+}
+
+// Destination side (CSR edge array): the sums A_j, R_j, S_j of a row piece are dotted with gout[v]
+// right away (everything is linear in the per-edge terms, so a row's pieces need not meet) and
+// the piece's share of (gmu_j0, gmu_j1, gis_j0, gis_j1) is added to the group's totals, pieces in
+// edge order; groups, then workgroups are summed in a fixed order as in the vertex-balanced
+// kernel: no atomics, bit-reproducible.  partial[block][j][4] as k_gmm_bwd_dst.
+template <int L, int NV>
+__global__ __launch_bounds__(kGmmBlock) void k_gmm_bwd_dst_eb(
+    int32_t n, int32_t nnz, const int32_t* __restrict__ indptr, const int32_t* __restrict__ indices,
+    const float* __restrict__ hk, const float* __restrict__ c, const float* __restrict__ mu,
+    const float* __restrict__ inv_sigma, const float* __restrict__ gout, GmmParams pm,
+    float* __restrict__ partial) {
+  constexpr int GPB = kGmmBlock / L;
+  constexpr int KB = kGmmKB, U = kGmmU, RUN = kGmmEbEdges;
+  constexpr int GS = (1 + 3 * KB) * (RUN + U);  // idx | w[KB] | w d0 [KB] | w d0^2 [KB], each padded by U
+  __shared__ __align__(16) float lds[GPB * GS];
+  __shared__ float blk[GPB][kMaxK][4];
+  const int lane = threadIdx.x & 63;
+  const int li = lane & (L - 1);
+  const int grp = threadIdx.x / L;
+  const int64_t run = (int64_t)blockIdx.x * GPB + grp;
+  const int K = pm.K, F = pm.F, KF = K * F;
+  const float inv_k = 1.f / (float)K;
+  for (int i = li; i < kMaxK * 4; i += L) blk[grp][i >> 2][i & 3] = 0.f;
+  if (run * RUN < nnz) {
+    const int32_t e0 = (int32_t)(run * RUN);
+    const int32_t e1 = min(e0 + RUN, nnz);
+    int* l_idx = reinterpret_cast<int*>(lds + grp * GS);
+    float* l_w = lds + grp * GS + (RUN + U);
+    float* l_wr = l_w + KB * (RUN + U);
+    float* l_ws = l_wr + KB * (RUN + U);
+    for (int i = li; i < RUN + U; i += L) {
+      l_idx[i] = e0 + i < e1 ? indices[e0 + i] : 0;
+#pragma unroll
+      for (int q = 0; q < KB; ++q) {
+        l_w[q * (RUN + U) + i] = 0.f;
+        l_wr[q * (RUN + U) + i] = 0.f;
+        l_ws[q * (RUN + U) + i] = 0.f;
+      }
+    }
+    float mu0[KB], mu1[KB], is0[KB], is1[KB];
+#pragma unroll
+    for (int q = 0; q < KB; ++q) {
+      const bool ok = q < K;
+      mu0[q] = ok ? mu[2 * q] : 0.f;
+      mu1[q] = ok ? mu[2 * q + 1] : 0.f;
+      is0[q] = ok ? inv_sigma[2 * q] : 0.f;
+      is1[q] = ok ? inv_sigma[2 * q + 1] : 0.f;
+    }
+    int32_t lo = 0, hi = n;
+    while (hi - lo > 1) {
+      const int32_t mid = (lo + hi) >> 1;
+      if (indptr[mid] <= e0) lo = mid; else hi = mid;
+    }
+    int32_t v = lo, row_end = indptr[v + 1];
+    wave_lds_fence();
+    bool slot_ok[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) slot_ok[j] = 4 * (li + j * L) < F;
+    float tot[KB][4];  // the group's totals (all lanes carry them; lane 0 stores)
+#pragma unroll
+    for (int q = 0; q < KB; ++q) tot[q][0] = tot[q][1] = tot[q][2] = tot[q][3] = 0.f;
+
+    int32_t e = e0;
+    while (e < e1) {
+      const int32_t seg_end = min(row_end, e1);
+      const float cv = c[v];
+      float4 g4[NV];
+#pragma unroll
+      for (int j = 0; j < NV; ++j)
+        g4[j] = slot_ok[j] ? ld4(gout + (int64_t)v * F + 4 * (li + j * L)) : make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int32_t t = e + li; t < seg_end; t += L) {
+        const float cu = c[l_idx[t - e0]];
+#pragma unroll
+        for (int q = 0; q < KB; ++q)
+          if (q < K) {
+            const float w = gauss_w(cu, cv, mu0[q], mu1[q], is0[q], is1[q]);
+            const float d0 = cu - mu0[q];
+            l_w[q * (RUN + U) + (t - e0)] = w;
+            l_wr[q * (RUN + U) + (t - e0)] = w * d0;
+            l_ws[q * (RUN + U) + (t - e0)] = w * d0 * d0;
+          }
+      }
+      wave_lds_fence();
+      float4 aA[KB][NV], aR[KB][NV], aS[KB][NV];
+#pragma unroll
+      for (int q = 0; q < KB; ++q)
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+          aA[q][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+          aR[q][j] = aA[q][j];
+          aS[q][j] = aA[q][j];
+        }
+      for (int32_t t0 = e; t0 < seg_end; t0 += U) {
+        int uu[U];
+        float ok[U];
+#pragma unroll
+        for (int t = 0; t < U; ++t) {
+          uu[t] = l_idx[t0 - e0 + t];
+          if (L == 64) uu[t] = __builtin_amdgcn_readfirstlane(uu[t]);
+          ok[t] = t0 + t < seg_end ? 1.f : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+          if (!slot_ok[j]) continue;
+          float4 rowv[U][KB];
+#pragma unroll
+          for (int t = 0; t < U; ++t)
+#pragma unroll
+            for (int q = 0; q < KB; ++q)
+              if (q < K) rowv[t][q] = ld4(hk + (int64_t)uu[t] * KF + q * F + 4 * (li + j * L));
+#pragma unroll
+          for (int t = 0; t < U; ++t)
+#pragma unroll
+            for (int q = 0; q < KB; ++q)
+              if (q < K) {
+                const int at = q * (RUN + U) + (t0 - e0 + t);
+                fma4(aA[q][j], ok[t] * l_w[at], rowv[t][q]);
+                fma4(aR[q][j], ok[t] * l_wr[at], rowv[t][q]);
+                fma4(aS[q][j], ok[t] * l_ws[at], rowv[t][q]);
+              }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < KB; ++q) {
+        if (q >= K) continue;
+        float tA = 0.f, tR = 0.f, tS = 0.f;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+          tA += dot4(g4[j], aA[q][j]);
+          tR += dot4(g4[j], aR[q][j]);
+          tS += dot4(g4[j], aS[q][j]);
+        }
+        tA = group_sum_from<L>(tA, 1);
+        tR = group_sum_from<L>(tR, 1);
+        tS = group_sum_from<L>(tS, 1);
+        const float d1 = cv - mu1[q];
+        tot[q][0] += tR * is0[q] * is0[q] * inv_k;
+        tot[q][1] += tA * d1 * is1[q] * is1[q] * inv_k;
+        tot[q][2] += -tS * is0[q] * inv_k;
+        tot[q][3] += -tA * d1 * d1 * is1[q] * inv_k;
+      }
+      e = seg_end;
+      if (e < e1) {
+        do {
+          ++v;
+          row_end = indptr[v + 1];
+        } while (row_end == e);
+      }
+    }
+    if (li == 0) {
+#pragma unroll
+      for (int q = 0; q < KB; ++q) {
+        blk[grp][q][0] = tot[q][0]; blk[grp][q][1] = tot[q][1];
+        blk[grp][q][2] = tot[q][2]; blk[grp][q][3] = tot[q][3];
+      }
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < kMaxK * 4) {
+    const int k = threadIdx.x >> 2, q = threadIdx.x & 3;
+    float s = 0.f;
+    for (int gi = 0; gi < GPB; ++gi) s += blk[gi][k][q];  // fixed order
+    partial[((int64_t)blockIdx.x * kMaxK + k) * 4 + q] = s;
+  }
+}
+
 template <int L, int NV>
 struct GmmFwdLauncher {
   static gnn_status_t run(const gnn_graph_t* g, const float* hk, const float* c, const float* mu,
@@ -925,6 +1212,46 @@ struct GmmBwdSrcLauncher {
   }
 };
 
+template <int L, int NV>
+struct GmmBwdDstEbLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, const float* hk, const float* c, const float* mu,
+                          const float* is, const float* gout, GmmParams pm, float* partial,
+                          float* gmu, float* gis, hipStream_t st) {
+    constexpr int GPB = kGmmBlock / L;
+    ProfScope p("gmm_bwd_dst", st);
+    const unsigned grid = (unsigned)cdiv(cdiv(g->nnz, kGmmEbEdges), GPB);
+    if (grid != 0) {
+      k_gmm_bwd_dst_eb<L, NV><<<grid, kGmmBlock, 0, st>>>(g->n, (int32_t)g->nnz, g->indptr, g->indices, hk, c, mu,
+                                                          is, gout, pm, partial);
+      GNN_LAUNCH_CHECK();
+    }
+    float* totals = partial + (int64_t)grid * kMaxK * 4;
+    GNN_TRY(sum_partials_two_level(kMaxK * 4, (int)grid, partial, totals + kMaxK * 4, totals, st));
+    k_gmm_param_split<<<1, 64, 0, st>>>(pm.K, totals, gmu, gis);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+  }
+};
+
+template <int L, int NV>
+struct GmmBwdSrcEbLauncher {
+  static gnn_status_t run(const gnn_graph_t* g, const float* c, const float* mu, const float* is,
+                          const float* gout, GmmParams pm, float* dhk, hipStream_t st) {
+    constexpr int GPB = kGmmBlock / L;
+    ProfScope p("gmm_bwd_src", st);
+    const int64_t quads = (int64_t)g->n * (pm.K * pm.F / 4);
+    k_gmm_zero_f4<<<(unsigned)cdiv(quads, 256), 256, 0, st>>>(quads, dhk);
+    GNN_LAUNCH_CHECK();
+    const int64_t runs = cdiv(g->nnz, kGmmEbEdges);
+    if (runs != 0) {
+      k_gmm_bwd_src_eb<L, NV><<<(unsigned)cdiv(runs, GPB), kGmmBlock, 0, st>>>(
+          g->n, (int32_t)g->nnz, g->indptr_t, g->indices_t, c, mu, is, gout, pm, dhk);
+      GNN_LAUNCH_CHECK();
+    }
+    return GNN_OK;
+  }
+};
+
 // fout <= 256 keeps NV == 1
 template <template <int, int> class Launcher, typename... Args>
 static gnn_status_t gmm_dispatch(GroupShape gs, Args... args) {
@@ -946,6 +1273,15 @@ static bool gmm_use_edge_balanced(const gnn_graph_t* g, int K) {
   const int64_t mode = config_get(kCfgGmmMapping);
   if (mode == 1) return true;
   return mode == 2 && g->gmm_edge_balanced == 1;
+}
+
+// the same for the two halves of the backward pass (side 0: destination, 1: source); gnn_gmm_tune_bwd
+// records what it measured
+static bool gmm_bwd_use_edge_balanced(const gnn_graph_t* g, int K, int side) {
+  if (K > kGmmKB) return false;
+  const int64_t mode = config_get(kCfgGmmMapping);
+  if (mode == 1) return true;
+  return mode == 2 && g->gmm_bwd_edge_balanced[side] == 1;
 }
 
 static gnn_status_t gmm_aggregate(const gnn_graph_t* g, bool edge_balanced, const float* hk, const float* c,
@@ -984,6 +1320,10 @@ static GmmWs gmm_ws_layout(const gnn_graph_t* g, int fin, int fout, int K) {
   w.nblk = gmm_dst_blocks_for(g, fout);
   if (xg) {
     const int64_t nb = gmm_dst_blocks_for(g, fin);
+    if (nb > w.nblk) w.nblk = nb;
+  }
+  if (K <= kGmmKB) {  // the edge-balanced destination side: one slot per workgroup of runs
+    const int64_t nb = cdiv(cdiv(g->nnz, kGmmEbEdges), kGmmBlock / pick_group(fout).L);
     if (nb > w.nblk) w.nblk = nb;
   }
   w.dhk = take(sizeof(float) * (size_t)n * K * fout);
@@ -1099,6 +1439,66 @@ extern "C" gnn_status_t gnn_gmm_tune(gnn_graph_t* g, int fout, int k, const floa
   return GNN_OK;
 }
 
+// times `reps` runs of fn after one warm-up; status and milliseconds per run
+template <typename Fn>
+static gnn_status_t time_passes(hipStream_t st, int reps, Fn fn, float* ms) {
+  hipEvent_t a = nullptr, b = nullptr;
+  GNN_HIP(hipEventCreate(&a));
+  if (hipEventCreate(&b) != hipSuccess) {
+    (void)hipEventDestroy(a);
+    set_error("hipEventCreate failed");
+    return GNN_ERR_HIP;
+  }
+  gnn_status_t status = fn();  // warm-up
+  if (status == GNN_OK && hipEventRecord(a, st) != hipSuccess) status = GNN_ERR_HIP;
+  for (int r = 0; r < reps && status == GNN_OK; ++r) status = fn();
+  if (status == GNN_OK && (hipEventRecord(b, st) != hipSuccess || hipEventSynchronize(b) != hipSuccess))
+    status = GNN_ERR_HIP;
+  float t = 0.f;
+  if (status == GNN_OK && hipEventElapsedTime(&t, a, b) != hipSuccess) status = GNN_ERR_HIP;
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
+  if (status == GNN_ERR_HIP && gnn_last_error()[0] == 0) set_error("a HIP event call failed");
+  *ms = t / (float)reps;
+  return status;
+}
+
+extern "C" gnn_status_t gnn_gmm_tune_bwd(gnn_graph_t* g, int fin, int fout, int k, const float* hk,
+                                         const float* c, const float* mu, const float* inv_sigma,
+                                         const float* gout, void* ws, size_t ws_bytes, void* stream,
+                                         float* ms_out) {
+  clear_error();
+  GNN_TRY(gmm_check(g, fin, fout, k, "gnn_gmm_tune_bwd"));
+  float ms[4] = {0.f, 0.f, 0.f, 0.f};
+  if (g->n != 0 && g->nnz != 0 && k <= kGmmKB) {
+    GNN_REQUIRE(hk && c && mu && inv_sigma && gout, GNN_ERR_INVALID_ARG, "gnn_gmm_tune_bwd: null pointer");
+    GNN_REQUIRE(aligned16(hk) && aligned16(gout), GNN_ERR_INVALID_ARG,
+                "gnn_gmm_tune_bwd: hk, gout must be 16-byte aligned");
+    const GmmWs L = gmm_ws_layout(g, fin, fout, k);
+    GNN_REQUIRE(ws != nullptr && ws_bytes >= L.total, GNN_ERR_WORKSPACE,
+                "gnn_gmm_tune_bwd: workspace of %zu bytes given, %zu needed", ws_bytes, L.total);
+    GNN_REQUIRE(aligned16(ws), GNN_ERR_INVALID_ARG, "gnn_gmm_tune_bwd: workspace must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(ws);
+    float* dhk = reinterpret_cast<float*>(base + L.dhk);
+    float* partial = reinterpret_cast<float*>(base + L.partial);
+    float* gmu = dhk;  // the destination side's results are not kept: they land in the dhk area (4 k floats)
+    float* gis = dhk + 2 * k;
+    GmmParams pm{k, fout};
+    const GroupShape gs = pick_group(fout);
+    constexpr int kReps = 3;
+    GNN_TRY(time_passes(st, kReps, [&] { return gmm_dispatch<GmmBwdDstLauncher>(gs, g, hk, c, mu, inv_sigma, gout, pm, partial, gmu, gis, st); }, &ms[0]));
+    GNN_TRY(time_passes(st, kReps, [&] { return gmm_dispatch<GmmBwdDstEbLauncher>(gs, g, hk, c, mu, inv_sigma, gout, pm, partial, gmu, gis, st); }, &ms[1]));
+    GNN_TRY(time_passes(st, kReps, [&] { return gmm_dispatch<GmmBwdSrcLauncher>(gs, g, c, mu, inv_sigma, gout, pm, dhk, st); }, &ms[2]));
+    GNN_TRY(time_passes(st, kReps, [&] { return gmm_dispatch<GmmBwdSrcEbLauncher>(gs, g, c, mu, inv_sigma, gout, pm, dhk, st); }, &ms[3]));
+    g->gmm_bwd_edge_balanced[0] = ms[1] < ms[0] ? 1 : 0;
+    g->gmm_bwd_edge_balanced[1] = ms[3] < ms[2] ? 1 : 0;
+  }
+  if (ms_out)
+    for (int i = 0; i < 4; ++i) ms_out[i] = ms[i];
+  return GNN_OK;
+}
+
 extern "C" gnn_status_t gnn_gmm_bwd(const gnn_graph_t* g, int fin, int fout, int k, const float* x,
                                     const float* w_fc, const float* c, const float* mu,
                                     const float* inv_sigma, const float* hk, const float* gout,
@@ -1124,7 +1524,21 @@ extern "C" gnn_status_t gnn_gmm_bwd(const gnn_graph_t* g, int fin, int fout, int
   const int KF = k * fout;
   GmmParams pm{k, fout};
   const GroupShape gs = pick_group(fout);
-  if (gmm_aggregate_first(fin, fout, k)) {
+  // the tuner compares the destination side with the project-first kernel: where the layer would
+  // gather the narrower input rows instead, only an explicit gmm_mapping = 1 switches
+  const bool eb_dst = gmm_bwd_use_edge_balanced(g, k, 0) &&
+                      (config_get(kCfgGmmMapping) == 1 || !gmm_aggregate_first(fin, fout, k));
+  const bool eb_src = gmm_bwd_use_edge_balanced(g, k, 1);
+  if (eb_dst) {
+    const float* hk_use = hk;
+    if (gmm_aggregate_first(fin, fout, k)) {
+      // the forward call may have aggregated first and left hk unwritten: project again, into the
+      // dhk area, which the source side fills only afterwards
+      GNN_TRY(gemm_f32(n, KF, fin, x, fin, false, w_fc, KF, false, dhk, KF, 1, nullptr, st));
+      hk_use = dhk;
+    }
+    GNN_TRY(gmm_dispatch<GmmBwdDstEbLauncher>(gs, g, hk_use, c, mu, inv_sigma, gout, pm, partial, gmu, ginv_sigma, st));
+  } else if (gmm_aggregate_first(fin, fout, k)) {
     // <gout[v], hk[u,j,:]> = <G_j[v], x[u]>, G = gout W'^T: the destination side gathers x rows
     float* G = reinterpret_cast<float*>(base + L.agg);
     float* wt = reinterpret_cast<float*>(base + L.wt);
@@ -1140,7 +1554,8 @@ extern "C" gnn_status_t gnn_gmm_bwd(const gnn_graph_t* g, int fin, int fout, int
   } else {
     GNN_TRY(gmm_dispatch<GmmBwdDstLauncher>(gs, g, hk, c, mu, inv_sigma, gout, pm, partial, gmu, ginv_sigma, st));
   }
-  GNN_TRY(gmm_dispatch<GmmBwdSrcLauncher>(gs, g, c, mu, inv_sigma, gout, pm, dhk, st));
+  if (eb_src) GNN_TRY(gmm_dispatch<GmmBwdSrcEbLauncher>(gs, g, c, mu, inv_sigma, gout, pm, dhk, st));
+  else GNN_TRY(gmm_dispatch<GmmBwdSrcLauncher>(gs, g, c, mu, inv_sigma, gout, pm, dhk, st));
   GNN_TRY(gemm_f32(fin, KF, n, x, fin, true, dhk, KF, false, gw_fc, KF, L.split_k, part, st));
   if (gx) GNN_TRY(gemm_f32(n, fin, KF, dhk, KF, false, w_fc, KF, true, gx, fin, 1, nullptr, st));
   return GNN_OK;

@@ -554,6 +554,7 @@ extern "C" gnn_status_t gnn_graph_create(int32_t n, int64_t nnz, const int32_t* 
   g->indices = indices;
   g->gcn_edge_balanced[0] = g->gcn_edge_balanced[1] = -1;
   g->gmm_edge_balanced = -1;
+  g->gmm_bwd_edge_balanced[0] = g->gmm_bwd_edge_balanced[1] = -1;
   gnn_status_t s = build(g, static_cast<hipStream_t>(stream));
   if (s != GNN_OK) {
     free_all(g);

@@ -313,3 +313,19 @@ def test_edge_weights_belong_to_their_graph():
     ew.close()
     g1.close()
     g2.close()
+
+
+@pytest.mark.parametrize("fin,fout", [(9, 20), (64, 64), (8, 512)])
+def test_edge_weighted_edge_balanced_mapping(edge_balanced, fin, fout):
+    """The general edge-weight layer in the edge-balanced mapping (runs of 64 edge positions, the
+    weights read next to the indices): rows spanning several runs, empty rows, a ragged tail."""
+    print(f"gcn: per-edge weights, edge-balanced fin={fin} fout={fout}", flush=True)
+    rng = np.random.default_rng(fin * 31 + fout)
+    n = 600
+    edges = [(u, 0) for u in range(n)] + [(0, v) for v in range(12, n, 3)]
+    edges += [(int(rng.integers(0, n)), int(v)) for v in range(20, n) for _ in range(int(v) % 5)]
+    indptr, indices = tiny_graph(n, edges)
+    c = synth(rng, indptr, indices, fin, fout)
+    c["ew"] = rng.uniform(-2.0, 2.0, len(indices)).astype(np.float32)
+    res, _ = check_edge(c)
+    assert (res["out"][np.diff(indptr) == 0] == 0).all()

@@ -86,7 +86,7 @@ def test_empty_rows_and_hub():
     check(synth(rng, indptr, indices, 10, 32, 3))
 
 
-# ---- edge-balanced forward mapping (Sec. 5) and the profile-driven choice ------------------
+# ---- edge-balanced mapping of forward and both backward halves (Sec. 5), profile-driven choice ----
 @pytest.fixture
 def edge_balanced():
     import paper_2110_09524_amd as pk
@@ -143,4 +143,68 @@ def test_tune_records_a_choice_and_results_stay_right():
     np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-4, atol=1e-5)
     with pytest.raises(pk.GnnError):
         pk.gnn_config_set("gmm_mapping", 5)
+    g.close()
+
+
+def test_backward_tune_records_a_choice_and_results_stay_right():
+    """gnn_gmm_tune_bwd times both halves of backward in both mappings; whatever it records, a
+    following backward call matches the oracle."""
+    import torch
+    import paper_2110_09524_amd as pk
+    from gpu_harness import assert_close, dev, empty, workspace
+    print("gmm: tune backward", flush=True)
+    c = make("gmm_c5_mid")
+    n, fin, fout, K = c["n"], c["fin"], c["fout"], c["k"]
+    g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
+    x, w_fc, cc, mu, isg = dev(c["x"]), dev(c["w_fc"]), dev(c["c"]), dev(c["mu"]), dev(c["inv_sigma"])
+    gout = dev(c["gout"])
+    hk, out = empty((n, K * fout)), empty((n, fout))
+    ws = workspace(pk.gnn_gmm_workspace_bytes(g, fin, fout, K))
+    pk.gnn_gmm_fwd(g, fin, fout, K, x, w_fc, cc, mu, isg, hk, out)      # no workspace: projects first, writes hk
+    ms = pk.gnn_gmm_tune_bwd(g, fin, fout, K, hk, cc, mu, isg, gout, ws)
+    print("  ms: dst vertex/edge", ms[:2], "src vertex/edge", ms[2:], flush=True)
+    assert len(ms) == 4 and all(t > 0 for t in ms)
+    args = (c["indptr"], c["indices"], c["x"], c["w_fc"], c["c"], c["mu"], c["inv_sigma"])
+    fwd = om.gmm_forward(*args)
+    bwd = om.gmm_backward(*args, c["gout"], fwd)
+    for mapping in (2, 1, 0):       # the recorded choice, edge-balanced forced, vertex-balanced forced
+        pk.gnn_config_set("gmm_mapping", mapping)
+        try:
+            gx, gw_fc, gmu, gis = empty((n, fin)), empty((fin, K * fout)), empty((K, 2)), empty((K, 2))
+            ws.fill_(0xFF)
+            pk.gnn_gmm_bwd(g, fin, fout, K, x, w_fc, cc, mu, isg, hk, gout, gx, gw_fc, gmu, gis, ws)
+            torch.cuda.synchronize()
+        finally:
+            pk.gnn_config_set("gmm_mapping", 2)
+        assert_close(f"gx mapping={mapping}", gx.cpu().numpy(), bwd["gx"])
+        assert_close(f"gw_fc mapping={mapping}", gw_fc.cpu().numpy(), bwd["gw_fc"], reduce_scale=True)
+        assert_close(f"gmu mapping={mapping}", gmu.cpu().numpy(), bwd["gmu"])
+        assert_close(f"ginv_sigma mapping={mapping}", gis.cpu().numpy(), bwd["ginv_sigma"])
+    with pytest.raises(pk.GnnError) as e:
+        pk.gnn_gmm_tune_bwd(g, fin, fout, K, hk, cc, mu, isg, gout, workspace(256))
+    assert e.value.status == 3
+    g.close()
+
+
+def test_edge_balanced_destination_side_is_bit_reproducible(edge_balanced):
+    """The edge-balanced destination side of backward adds a row's pieces in a fixed order (no
+    atomics): gmu and ginv_sigma repeat bit for bit."""
+    import torch
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev, empty, workspace
+    print("gmm: edge-balanced dst side twice", flush=True)
+    c = make("gmm_c5_mid")
+    n, fin, fout, K = c["n"], c["fin"], c["fout"], c["k"]
+    g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
+    x, w_fc, cc, mu, isg = dev(c["x"]), dev(c["w_fc"]), dev(c["c"]), dev(c["mu"]), dev(c["inv_sigma"])
+    hk, out = empty((n, K * fout)), empty((n, fout))
+    ws = workspace(pk.gnn_gmm_workspace_bytes(g, fin, fout, K))
+    pk.gnn_gmm_fwd(g, fin, fout, K, x, w_fc, cc, mu, isg, hk, out, ws)
+    runs = []
+    for _ in range(2):
+        gw_fc, gmu, gis = empty((fin, K * fout)), empty((K, 2)), empty((K, 2))
+        pk.gnn_gmm_bwd(g, fin, fout, K, x, w_fc, cc, mu, isg, hk, dev(c["gout"]), None, gw_fc, gmu, gis, ws)
+        torch.cuda.synchronize()
+        runs.append((gmu.cpu().numpy().copy(), gis.cpu().numpy().copy()))
+    assert np.array_equal(runs[0][0], runs[1][0]) and np.array_equal(runs[0][1], runs[1][1])
     g.close()
