@@ -494,6 +494,315 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
   }
 }
 
+// ---- all column blocks in one persistent launch: the running sums stay in LDS -------------------
+// The launches of k_gat_blk pay for cache residency with a read-add-write of the rows' running
+// sums (and softmax statistics) per block.  Here one 1024-thread workgroup per CU runs for the
+// whole pass and keeps the state of kGatResSlots (row, slice) pairs in LDS: the running sums, the
+// softmax statistics, the row's own scalars.  It takes all of them through column block 0, then
+// all of them through block 1, ... ("phases"), writes each row out in the last phase and then
+// takes its next rows ("generation").  Every workgroup of the chip owns the same number of rows
+// per generation, picked from the degree order with a stride of the number of groups, so the
+// workgroups carry nearly equal loads in every phase; the workgroups of an XCD enter a phase
+// together (phase_step_done: a bounded wait that only serves cache residency), so an L2 serves one
+// block at a time.  Inside a workgroup the groups draw (row, slice) slots from an LDS counter,
+// longest rows first.  A row's chunks are summed in the order of the launch-per-block kernels
+// (blocks ascending, edges in list order), so the results do not depend on who draws what.
+// MODE as k_gat_blk; one segment per phase, fp32 rows, per-edge scalars gathered from L2.
+constexpr int kGatResThreads = 1024;
+template <int SL, int MODE>
+constexpr int kGatResSlots = (kGatResThreads / SL) * (MODE == 3 ? 4 : 8);
+// LDS ints of a workgroup: sums (two for MODE 3) | state float4 | (beg, end) of two phases | rows |
+// per group idx, p, p2 | two counters
+template <int SL, int MODE>
+constexpr int kGatResLdsInts = (MODE == 3 ? 2 : 1) * 4 * SL * kGatResSlots<SL, MODE> + 4 * kGatResSlots<SL, MODE> +
+                               4 * kGatResSlots<SL, MODE> + kGatResSlots<SL, MODE> +
+                               (kGatResThreads / SL) * 3 * SL + 4;
+
+template <int SL, int MODE, bool SKIP>
+__global__ __launch_bounds__(kGatResThreads) void k_gat_res(
+    int32_t n_rows, const int32_t* __restrict__ order, const int2* __restrict__ bseg /* [nblk][n_rows] */,
+    const int32_t* __restrict__ bcol, const float* __restrict__ feat /* gathered rows: z or gout */,
+    const float* __restrict__ rowfeat /* MODE 2: z */, const float* __restrict__ el,
+    const float* __restrict__ er, const float* __restrict__ m_in, const float* __restrict__ d_in,
+    const float4* __restrict__ vstate, GatDims dm, int sph, int narrow, int el_hm, int32_t block_cols,
+    int nblk, int ns, float* __restrict__ acc_buf, float* __restrict__ acc2_buf, float* __restrict__ scal_buf,
+    float* __restrict__ m_out, float* __restrict__ d_out, int32_t* __restrict__ clock, int spin_limit) {
+  constexpr int GPB = kGatResThreads / SL;
+  constexpr int NSLOT = kGatResSlots<SL, MODE>;
+  constexpr int R = NSLOT / GPB;
+  constexpr int U = SL < 8 ? 4 : 8;
+  constexpr bool DUAL = MODE == 3;
+  constexpr bool SRC = MODE == 2;
+  constexpr bool ONLINE = MODE == 0 || MODE == 3;
+  static_assert(NSLOT <= kGatResThreads, "one thread per slot loads its metadata");
+  extern __shared__ __align__(16) int lds_gr[];
+  const int lane = threadIdx.x & 63;
+  const int li = threadIdx.x & (SL - 1);
+  const int grp = threadIdx.x / SL;
+  const int slice = blockIdx.x % ns;
+  const int64_t nwg = gridDim.x / ns, wg = blockIdx.x / ns;  // workgroups that serve this slice
+  const int64_t ngroups = nwg * GPB;
+  const int H = dm.H, HF = dm.HF;
+  const int h = slice / sph;
+  const bool leader = (slice % sph) == 0;  // one slice per head keeps the per-head scalars
+  const int col = slice * 4 * SL + 4 * li;
+
+  float4* l_acc = reinterpret_cast<float4*>(lds_gr);                                   // [NSLOT][SL]
+  float4* l_acc2 = l_acc + (DUAL ? SL * NSLOT : 0);                                    // [NSLOT][SL] (MODE 3)
+  float4* l_state = l_acc2 + SL * NSLOT;                                               // [NSLOT]
+  int2* l_seg = reinterpret_cast<int2*>(l_state + NSLOT);                              // [2][NSLOT]
+  int* l_row = reinterpret_cast<int*>(l_seg + 2 * NSLOT);                              // [NSLOT]
+  int* l_idx = l_row + NSLOT + grp * 3 * SL;
+  float* l_p = reinterpret_cast<float*>(l_idx + SL);
+  float* l_p2 = l_p + SL;
+  int* l_cnt = l_row + NSLOT + GPB * 3 * SL;                                           // [2]
+
+  const int64_t rows_per_group = (n_rows + ngroups - 1) / ngroups;
+  const int ngen = (int)((rows_per_group + R - 1) / R);
+  // workgroups go to the XCDs round-robin: those with the same id mod 8 share an L2
+  PhaseClock pc{clock ? clock + (blockIdx.x % kXcds) * kClockStride : nullptr, (int)(gridDim.x / kXcds), spin_limit,
+                false};
+
+  const char* feat_bytes = reinterpret_cast<const char*>(feat);
+  const uint32_t row_bytes = (uint32_t)HF * 4u, col_bytes = (uint32_t)col * 4u;
+
+  struct Item {
+    int32_t beg, end, c_first;
+    float4 zr;  // MODE 2: the row's own z slice
+  };
+
+  for (int gen = 0; gen < ngen; ++gen) {
+    const int64_t j0 = gen * rows_per_group / ngen, j1 = (gen + 1) * rows_per_group / ngen;
+    const int nslots = (int)(j1 - j0) * GPB;  // slot q: row at position (j0 * GPB + q) * nwg + wg (or + nwg - 1 - wg)
+    // (the previous generation ended with a workgroup barrier: its tables are free)
+    int64_t pos = -1;                         // thread q < nslots: position of slot q's row in the degree order
+    if ((int)threadIdx.x < nslots) {
+      // consecutive positions of the degree order go to consecutive workgroups, in alternating
+      // direction from one round to the next, so every workgroup gets the same mix of degrees
+      const int64_t r = (j0 * GPB + threadIdx.x) * nwg + ((threadIdx.x & 1) ? nwg - 1 - wg : wg);
+      if (r < n_rows) pos = r;
+      const int32_t row = pos >= 0 ? order[pos] : -1;
+      l_row[threadIdx.x] = row;
+      l_seg[threadIdx.x] = pos >= 0 ? bseg[pos] : make_int2(0, 0);
+      // state: forward (m_run, d, s2, er[row]); MODE 1 (sum alpha g, er, m, 1/d); MODE 2 (del share, el[row])
+      float4 stt = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (row >= 0) {
+        const int64_t rh = (int64_t)row * H + h;
+        if (ONLINE) stt = make_float4(-INFINITY, 0.f, 0.f, er[rh]);
+        else if (MODE == 1) stt = make_float4(0.f, er[rh], m_in[rh], 1.f / d_in[rh]);
+        else stt = make_float4(0.f, el[rh], 0.f, 0.f);
+      }
+      l_state[threadIdx.x] = stt;
+    }
+    for (int i = threadIdx.x; i < nslots * SL; i += kGatResThreads) {
+      l_acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (DUAL) l_acc2[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    if (threadIdx.x == 0) l_cnt[0] = 0;
+    __syncthreads();  // the tables are in place
+
+    // a group's next slot of phase p, from that phase's counter
+    auto grab = [&](int p) {
+      int q = 0;
+      if (li == 0) q = atomicAdd(l_cnt + (p & 1), 1);
+      return __shfl(q, lane & ~(SL - 1), 64);
+    };
+    // what a slot needs before its edge loop in phase p: bounds, first indices, (MODE 2) the row's own z
+    auto fetch = [&](int p, int q) {
+      Item it{0, 0, p * block_cols, make_float4(0.f, 0.f, 0.f, 0.f)};
+      if (q >= nslots) return it;
+      const int2 sg = l_seg[(p & 1) * NSLOT + q];
+      it.beg = sg.x;
+      it.end = sg.y;
+      if (it.beg + li < it.end) it.c_first = bcol[it.beg + li];
+      if (SRC) {
+        const int32_t row = l_row[q];
+        if (row >= 0 && it.beg < it.end) it.zr = ld4_stream(rowfeat + (int64_t)row * HF + col);
+      }
+      return it;
+    };
+    int q = grab(0);
+    Item cur = fetch(0, q);
+
+    for (int p = 0; p < nblk; ++p) {
+      const int32_t col_begin = p * block_cols;
+      const bool last = p + 1 == nblk;
+      // the next phase's bounds travel while this one is worked on
+      int2 seg_next = make_int2(0, 0);
+      if (!last && pos >= 0) seg_next = bseg[(int64_t)(p + 1) * n_rows + pos];
+      if (threadIdx.x == 0) l_cnt[(p + 1) & 1] = 0;
+
+      while (q < nslots) {
+        const int qn = grab(p);
+        const Item nxt = fetch(p, qn);
+        const int32_t row = l_row[q];
+        const int32_t beg = cur.beg, end = cur.end;
+        if (row >= 0 && (beg < end || last)) {
+          const float4 stt = l_state[q];
+          float4 acc = l_acc[q * SL + li], acc2 = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (DUAL) acc2 = l_acc2[q * SL + li];
+          if (SRC) acc2 = cur.zr;
+          const float r_a = ONLINE ? stt.w : stt.y;
+          const float r_m = stt.z, r_invd = stt.w;  // MODE 1
+          float s_run = 0.f;  // chunk-phase lanes: sum of alpha g (MODE 1), of alpha g D[v] (MODE 2)
+          float s_dot = 0.f;  // MODE 2, row-phase lanes: sum of alpha g <z[u], gout[v]> over the lane's columns
+          float m_run = stt.x;  // ONLINE
+          float d_lane = li == 0 ? stt.y : 0.f, s2_lane = li == 0 ? stt.z : 0.f;
+          int32_t c_next = cur.c_first;
+          for (int32_t c0 = beg; c0 < end; c0 += SL) {
+            const bool e_ok = c0 + li < end;
+            const int cnt = min(SL, end - c0);
+            const int32_t c = e_ok ? c_next : col_begin;
+            if (c0 + SL + li < end) c_next = bcol[c0 + SL + li];
+            l_idx[li] = c;
+            float e_a = 0.f;
+            float4 vs = make_float4(0.f, 0.f, 1.f, 0.f);
+            if (e_ok) {
+              if (SRC) vs = vstate[(int64_t)h * n_rows + c];  // head-major (er, m, 1/d, D) of the destination
+              else e_a = el_hm ? el[(int64_t)h * n_rows + c] : el[(int64_t)c * H + h];
+            }
+            wave_lds_fence();
+            float4 part = make_float4(0.f, 0.f, 0.f, 0.f), part2 = part;
+            float dpart = 0.f;
+            float sc = 1.f;  // ONLINE: factor that brings the running sums to this chunk's maximum
+#pragma unroll
+            for (int t0 = 0; t0 < SL; t0 += U) {
+              int idv[U];
+#pragma unroll
+              for (int qq = 0; qq < U / 4; ++qq) {
+                const int4 i4 = *reinterpret_cast<const int4*>(l_idx + t0 + 4 * qq);
+                idv[4 * qq] = i4.x; idv[4 * qq + 1] = i4.y; idv[4 * qq + 2] = i4.z; idv[4 * qq + 3] = i4.w;
+              }
+              float4 rowv[U];
+#pragma unroll
+              for (int t4 = 0; t4 < U; t4 += 4) {
+                if (!SKIP || t0 + t4 < cnt) {
+                  if (narrow) {
+#pragma unroll
+                    for (int t = t4; t < t4 + 4; ++t)
+                      rowv[t] = *reinterpret_cast<const float4*>(
+                          feat_bytes + (__umul24((uint32_t)idv[t], row_bytes) + col_bytes));
+                  } else {
+#pragma unroll
+                    for (int t = t4; t < t4 + 4; ++t)
+                      rowv[t] = *reinterpret_cast<const float4*>(feat_bytes + ((int64_t)idv[t] * row_bytes + col_bytes));
+                  }
+                }
+              }
+              if (t0 == 0) {
+                float pe = 0.f, pe2 = 0.f;
+                if (e_ok) {
+                  if (SRC) {
+                    const float raw = r_a + vs.x;
+                    pe = __expf(leaky(raw, dm.slope) - vs.y) * vs.z;
+                    pe2 = raw > 0.f ? pe : dm.slope * pe;
+                    s_run = fmaf(pe2, vs.w, s_run);
+                  } else if (!ONLINE) {
+                    const float raw = e_a + r_a;
+                    pe = __expf(leaky(raw, dm.slope) - r_m) * r_invd;
+                    pe = raw > 0.f ? pe : dm.slope * pe;  // MODE 1
+                    s_run += pe;
+                  }
+                }
+                if (ONLINE) {
+                  const float raw = e_a + r_a;
+                  const float sc_e = e_ok ? leaky(raw, dm.slope) : -INFINITY;
+                  const float m_new = fmaxf(m_run, group_max_from<SL>(sc_e, 1));  // finite: lane 0 of a chunk is valid
+                  sc = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
+                  pe = e_ok ? __expf(sc_e - m_new) : 0.f;
+                  pe2 = raw > 0.f ? pe : dm.slope * pe;
+                  d_lane = fmaf(d_lane, sc, pe);
+                  s2_lane = fmaf(s2_lane, sc, pe2);
+                  m_run = m_new;
+                }
+                l_p[li] = pe;
+                if (DUAL || SRC) l_p2[li] = pe2;
+                wave_lds_fence();
+              }
+              float pv[U], pv2[U];
+#pragma unroll
+              for (int qq = 0; qq < U / 4; ++qq) {
+                const float4 p4 = *reinterpret_cast<const float4*>(l_p + t0 + 4 * qq);
+                pv[4 * qq] = p4.x; pv[4 * qq + 1] = p4.y; pv[4 * qq + 2] = p4.z; pv[4 * qq + 3] = p4.w;
+                if (DUAL || SRC) {
+                  const float4 q4 = *reinterpret_cast<const float4*>(l_p2 + t0 + 4 * qq);
+                  pv2[4 * qq] = q4.x; pv2[4 * qq + 1] = q4.y; pv2[4 * qq + 2] = q4.z; pv2[4 * qq + 3] = q4.w;
+                }
+              }
+#pragma unroll
+              for (int t4 = 0; t4 < U; t4 += 4) {
+                if (!SKIP || t0 + t4 < cnt) {
+#pragma unroll
+                  for (int t = t4; t < t4 + 4; ++t) {
+                    fma4(part, pv[t], rowv[t]);
+                    if (DUAL) fma4(part2, pv2[t], rowv[t]);
+                    if (SRC) dpart = fmaf(pv2[t], dot4(acc2, rowv[t]), dpart);
+                  }
+                }
+              }
+            }
+            if (ONLINE) {
+              fold4(acc, sc, part);
+              if (DUAL) fold4(acc2, sc, part2);
+            } else {
+              add4(acc, part);
+            }
+            if (SRC) s_dot += dpart;
+            wave_lds_fence();
+          }
+          // close the item: statistics back to the slot, or (last phase) the finished row to memory
+          float4 st_new = stt;
+          if (ONLINE) {
+            const float d_tot = group_sum_from<SL>(d_lane, 1);
+            const float s2_tot = MODE == 3 ? group_sum_from<SL>(s2_lane, 1) : 0.f;
+            st_new = make_float4(m_run, d_tot, s2_tot, stt.w);
+            if (last) {
+              // the row is complete: normalise (a row without in-edges keeps out = 0, m = 0, d = 1)
+              const float inv = d_tot > 0.f ? 1.f / d_tot : 0.f;
+              scale4(acc, inv);
+              if (DUAL) scale4(acc2, inv);
+              if (leader && li == 0) {
+                const int64_t rh = (int64_t)row * H + h;
+                m_out[rh] = d_tot > 0.f ? m_run : 0.f;
+                d_out[rh] = d_tot > 0.f ? d_tot : 1.f;
+                if (MODE == 3) scal_buf[rh] = s2_tot * inv;
+              }
+            }
+          } else if (MODE == 1) {
+            if (leader) st_new.x = stt.x + group_sum_from<SL>(s_run, 1);
+            if (last && leader && li == 0) scal_buf[(int64_t)row * H + h] = st_new.x;
+          } else {
+            // this slice's share of del[u, h]; the D term is counted by one slice per head
+            st_new.x = stt.x + group_sum_from<SL>(s_dot - (leader ? s_run : 0.f), 1);
+            if (last && li == 0) scal_buf[(int64_t)row * kSlices + slice] = st_new.x;
+          }
+          if (last) {
+            st4_stream(acc_buf + (int64_t)row * HF + col, acc);
+            if (DUAL) st4_stream(acc2_buf + (int64_t)row * HF + col, acc2);
+          } else {
+            l_acc[q * SL + li] = acc;
+            if (DUAL) l_acc2[q * SL + li] = acc2;
+            if (li == 0) l_state[q] = st_new;
+          }
+        }
+        q = qn;
+        cur = nxt;
+      }
+      if ((int)threadIdx.x < nslots) l_seg[((p + 1) & 1) * NSLOT + threadIdx.x] = seg_next;
+      __syncthreads();  // the workgroup is done with this block; the next phase's bounds are in LDS
+      if (!last) {      // first slot of the next phase: its loads travel during the wait below
+        q = grab(p + 1);
+        cur = fetch(p + 1, q);
+      }
+      phase_step_done(pc, gen * nblk + p);
+      __syncthreads();  // every workgroup of the XCD is done with this block (or the wait ran out)
+
+    }
+  }
+}
+
+__global__ void k_gat_zero_clock(int32_t* __restrict__ clock) { clock[threadIdx.x] = 0; }
+
 // elT[h][v] = el[v][h]: a column block of gathered vertices then spans 4 B per vertex in
 // the head a slice needs instead of 4*H (fewer L2 lines for the per-edge scalar gathers)
 __global__ void k_gat_head_major(int64_t n, int H, const float* __restrict__ a, float* __restrict__ aT) {
@@ -669,12 +978,65 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
                                                    scal, queue, state, m_out, d_out, st, alpha_b);
 }
 
+// The persistent kernel applies to fp32 rows in 256-byte slices, without a per-edge stash
+static bool gat_resident_applies(const gnn_graph_t* g, GatDims dm, bool half_feat, const float* alpha_b) {
+  if (!config_get(kCfgResidentSums) || half_feat || alpha_b != nullptr || g->phase_clock == nullptr) return false;
+  Slicing sl;
+  return pick_slicing(dm.H, dm.HF, sl) && sl.SL == 16;
+}
+
+template <int MODE, bool SKIP>
+static gnn_status_t launch_resident_impl(const gnn_graph_t* g, int side, const char* name, GatDims dm, int el_hm,
+                                         const float* feat, const float* rowfeat, const float* el, const float* er,
+                                         const float* m, const float* d, const float4* vstate, float* acc,
+                                         float* acc2, float* scal, float* m_out, float* d_out, hipStream_t st) {
+  constexpr int SL = 16;
+  const int ns = dm.HF / (4 * SL);
+  const int sph = ns / dm.H;
+  const int narrow = (int64_t)g->n * dm.HF * 4 < ((int64_t)1 << 32) && g->n < (1 << 24) &&
+                     !config_get(kCfgWideOffsets);
+  const size_t lds = sizeof(int) * (size_t)kGatResLdsInts<SL, MODE>;
+  static_assert(sizeof(int) * (size_t)kGatResLdsInts<SL, MODE> <= 160 * 1024, "the slots must fit the LDS of a CU");
+  static std::atomic<bool> attr_set{false};
+  if (!attr_set.load(std::memory_order_acquire)) {
+    GNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gat_res<SL, MODE, SKIP>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set.store(true, std::memory_order_release);
+  }
+  // one workgroup per CU, a multiple of 8 so that every XCD serves one slice
+  const unsigned grid = (unsigned)(device_cu_count() / kXcds * kXcds);
+  ProfScope p(name, st);
+  k_gat_zero_clock<<<1, kXcds * kClockStride, 0, st>>>(g->phase_clock);
+  GNN_LAUNCH_CHECK();
+  k_gat_res<SL, MODE, SKIP><<<grid, kGatResThreads, lds, st>>>(
+      g->n, g->order[side], reinterpret_cast<const int2*>(g->bseg[side]), g->bcol[side], feat, rowfeat, el, er, m, d,
+      vstate, dm, sph, narrow, el_hm, g->block_cols, g->nblk, ns, acc, acc2, scal, m_out, d_out, g->phase_clock,
+      (int)config_get(kCfgResidentSpin));
+  GNN_LAUNCH_CHECK();
+  return GNN_OK;
+}
+
+template <int MODE>
+static gnn_status_t launch_resident(const gnn_graph_t* g, int side, const char* name, GatDims dm, int el_hm,
+                                    const float* feat, const float* rowfeat, const float* el, const float* er,
+                                    const float* m, const float* d, const float4* vstate, float* acc, float* acc2,
+                                    float* scal, float* m_out, float* d_out, hipStream_t st) {
+  if (dm.HF / 64 >= 4)
+    return launch_resident_impl<MODE, true>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2,
+                                            scal, m_out, d_out, st);
+  return launch_resident_impl<MODE, false>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2,
+                                           scal, m_out, d_out, st);
+}
+
 template <int MODE>
 static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name, GatDims dm,
                                int el_hm, const float* feat, const float* rowfeat, const float* el, const float* er, const float* m,
                                const float* d, const float4* vstate, float* acc, float* acc2,
                                float* scal, int32_t* queue, float4* state, float* m_out, float* d_out,
                                hipStream_t st, bool half_feat = false, const float* alpha_b = nullptr) {
+  if (gat_resident_applies(g, dm, half_feat, alpha_b))
+    return launch_resident<MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal,
+                                 m_out, d_out, st);
   if (half_feat) {
     if constexpr (MODE != 1)
       return launch_blocks<8, MODE, true>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal,

@@ -372,7 +372,7 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
 // and takes its next rows ("generation").  Every workgroup owns the same number of rows per
 // generation, picked from the degree order with a stride of the number of groups on the chip,
 // so all workgroups carry nearly the same load in every phase; the workgroups of an XCD start
-// a phase together (phase_sync), so an L2 serves gathers from one block at a time.  Inside a
+// a phase together (phase_step_done), so an L2 serves gathers from one block at a time.  Inside a
 // workgroup the groups draw rows from an LDS counter, longest rows first, which levels the
 // segments' lengths.  A row's sums run in block order and its edges in list order, so the
 // result is bit-identical to the launch-per-block path whoever draws what.
@@ -427,51 +427,53 @@ __global__ __launch_bounds__(kResThreads) void k_rowsum_res(
 
   for (int gen = 0; gen < ngen; ++gen) {
     const int64_t j0 = gen * rows_per_group / ngen, j1 = (gen + 1) * rows_per_group / ngen;
-    const int nslots = (int)(j1 - j0) * GPB;  // slot q = k * GPB + g: row at position (j0 + k) * ngroups + wg * GPB + g
+    const int nslots = (int)(j1 - j0) * GPB;  // slot q: row at position (j0 * GPB + q) * nwg + wg (or + nwg - 1 - wg)
     __syncthreads();                          // the previous generation's rows are written out
     int64_t pos = -1;                         // thread q < nslots: position of slot q's row in the degree order
     if ((int)threadIdx.x < nslots) {
-      const int64_t r = (j0 + threadIdx.x / GPB) * ngroups + wg * GPB + threadIdx.x % GPB;
+      // consecutive positions of the degree order go to consecutive workgroups, in alternating
+      // direction from one round to the next, so every workgroup gets the same mix of degrees
+      const int64_t r = (j0 * GPB + threadIdx.x) * nwg + ((threadIdx.x & 1) ? nwg - 1 - wg : wg);
       if (r < n_rows) pos = r;
       l_row[threadIdx.x] = pos >= 0 ? order[pos] : -1;
       l_seg[threadIdx.x] = pos >= 0 ? bseg[pos] : make_int2(0, 0);
     }
     for (int i = threadIdx.x; i < nslots * SL; i += kResThreads) l_acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (threadIdx.x == 0) l_cnt[0] = 0;
+    __syncthreads();  // the tables are in place
+
+    // a group's next slot of phase p, from that phase's counter
+    auto grab = [&](int p) {
+      int q = 0;
+      if (li == 0) q = atomicAdd(l_cnt + (p & 1), 1);
+      return __shfl(q, lane & ~(SL - 1), 64);
+    };
+    // what a slot needs before its edge loop in phase p: bounds and first indices
+    auto fetch = [&](int p, int q) {
+      Item it{0, 0, p * block_cols, 0.f};
+      if (q >= nslots) return it;
+      const int2 sg = l_seg[(p & 1) * NSLOT + q];
+      it.beg = sg.x;
+      it.end = sg.y;
+      if (it.beg + li < it.end) {
+        it.c_first = bcol[it.beg + li];
+        if (W) it.w_first = bw[it.beg + li];
+      }
+      return it;
+    };
+    int q = grab(0);
+    Item cur = fetch(0, q);
 
     for (int p = 0; p < nblk; ++p) {
       const int32_t col_begin = p * block_cols;
-      phase_sync(pc, gen * nblk + p);
-      const int2* seg_p = l_seg + (p & 1) * NSLOT;
-      int* cnt_p = l_cnt + (p & 1);
       // the next phase's bounds travel while this one is worked on
       int2 seg_next = make_int2(0, 0);
       if (p + 1 < nblk && pos >= 0) seg_next = bseg[(int64_t)(p + 1) * n_rows + pos];
       if (threadIdx.x == 0) l_cnt[(p + 1) & 1] = 0;
 
-      auto grab = [&]() {
-        int q = 0;
-        if (li == 0) q = atomicAdd(cnt_p, 1);
-        return __shfl(q, lane & ~(SL - 1), 64);
-      };
-      auto fetch = [&](int q) {
-        Item it{0, 0, col_begin, 0.f};
-        if (q >= nslots) return it;
-        const int2 sg = seg_p[q];
-        it.beg = sg.x;
-        it.end = sg.y;
-        if (it.beg + li < it.end) {
-          it.c_first = bcol[it.beg + li];
-          if (W) it.w_first = bw[it.beg + li];
-        }
-        return it;
-      };
-
-      int q = grab();
-      Item cur = fetch(q);
       while (q < nslots) {
-        const int qn = grab();
-        const Item nxt = fetch(qn);
+        const int qn = grab(p);
+        const Item nxt = fetch(p, qn);
         const int32_t beg = cur.beg, end = cur.end;
         if (beg < end) {
           float4 acc = l_acc[q * SL + li];
@@ -520,8 +522,14 @@ __global__ __launch_bounds__(kResThreads) void k_rowsum_res(
         cur = nxt;
       }
       if ((int)threadIdx.x < nslots) l_seg[((p + 1) & 1) * NSLOT + threadIdx.x] = seg_next;
+      __syncthreads();  // the workgroup is done with this block; the next phase's bounds are in LDS
+      if (p + 1 < nblk) {  // first slot of the next phase: its loads travel during the wait below
+        q = grab(p + 1);
+        cur = fetch(p + 1, q);
+      }
+      phase_step_done(pc, gen * nblk + p);
+      __syncthreads();  // every workgroup of the XCD is done with this block (or the wait ran out)
     }
-    __syncthreads();
     for (int q = grp; q < nslots; q += GPB) {
       const int32_t row = l_row[q];
       if (row < 0) continue;

@@ -40,30 +40,27 @@ __device__ __forceinline__ float group_sum_from(float v, int lo_stride) {
 }
 
 // Pace of the persistent kernels.  Workgroups that share an L2 (one XCD) walk the column blocks
-// step by step; before step `step` every workgroup reports the previous step done on its XCD's
-// counter and waits until all `nwg` workgroups of the XCD have done so.  The wait only keeps the
-// gathered block cache-resident: results never depend on it, so it is bounded (`spin_limit`
-// polls) and a workgroup that once ran into the bound stops waiting for the rest of the launch
-// (with a limit of 0 nothing is ever waited for).  Every thread of the workgroup must call it; it
-// is a workgroup barrier in any case.
+// step by step: a workgroup that has finished step `step` reports it on its XCD's counter and
+// waits until all `nwg` workgroups of the XCD have done so.  The wait only keeps the gathered
+// block cache-resident: results never depend on it, so it is bounded (`spin_limit` polls) and a
+// workgroup that once ran into the bound stops waiting for the rest of the launch (with a limit
+// of 0 nothing is ever waited for).  One thread does the reporting and waiting; the caller puts
+// workgroup barriers around it, and whatever the other threads can prepare for the next step
+// (the next row's bounds and indices) between the two.
 struct PhaseClock {
   int32_t* counter;  // this XCD's counter, zero at launch; null: no pacing between workgroups
   int nwg, spin_limit;
   bool gave_up;
 };
-__device__ __forceinline__ void phase_sync(PhaseClock& pc, int step) {
-  __syncthreads();  // the workgroup's own step boundary (its LDS sums and tables change hands)
-  if (pc.counter == nullptr) return;
-  if (threadIdx.x == 0) {
-    if (step > 0) __hip_atomic_fetch_add(pc.counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const int target = pc.nwg * step;
-    int polls = 0;
-    while (!pc.gave_up && __hip_atomic_load(pc.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-      if (++polls > pc.spin_limit) pc.gave_up = true;
-      else __builtin_amdgcn_s_sleep(4);
-    }
+__device__ __forceinline__ void phase_step_done(PhaseClock& pc, int step) {
+  if (pc.counter == nullptr || threadIdx.x != 0) return;
+  __hip_atomic_fetch_add(pc.counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const int target = pc.nwg * (step + 1);
+  int polls = 0;
+  while (!pc.gave_up && __hip_atomic_load(pc.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+    if (++polls > pc.spin_limit) pc.gave_up = true;
+    else __builtin_amdgcn_s_sleep(2);
   }
-  __syncthreads();
 }
 
 __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }

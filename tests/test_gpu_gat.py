@@ -177,11 +177,13 @@ def test_bad_arguments_raise():
                                             # 512-byte rows: four slices of 128 bytes; narrower rows
                                             # take the single-launch kernels on such graphs, too
                                             (256, 1, 128), (300, 4, 32), (256, 2, 64), (500, 1, 64)])
-@pytest.mark.parametrize("merge", [0, 1])
+@pytest.mark.parametrize("merge", [0, 1, 2])
 def test_column_blocked_path(block_cols, H, F, merge):
     """The multi-launch, column-blocked kernels (used when the gathered matrix exceeds
     the L2 caches) on a graph small enough for the oracle, with small blocks forced: one launch
-    per block, and launches that walk several sparse blocks per row."""
+    per block (0), launches that walk several sparse blocks per row (1), and all blocks in one
+    persistent launch that keeps the running sums in LDS (2; rows cut into 256-byte slices, the
+    other shapes fall back to the launches)."""
     import paper_2110_09524_amd as pk
     from gpu_harness import dev, run_gat
     print(f"gat: blocked path block_cols={block_cols} H={H} F={F} merge={merge}", flush=True)
@@ -193,19 +195,23 @@ def test_column_blocked_path(block_cols, H, F, merge):
         c = synth(rng, indptr, indices, 24, H, F)
     fwd, bwd = oracle_all(c)
     pk.gnn_config_set("block_cols", block_cols)
-    pk.gnn_config_set("merge_blocks", merge)
+    pk.gnn_config_set("merge_blocks", int(merge == 1))
+    pk.gnn_config_set("resident_sums", int(merge == 2))
     try:
         g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
         nb = g.blocked(0)[0]
         assert nb == -(-c["n"] // block_cols)
         launches = len(g.launch_groups(0, 2)) - 1
         print(f"  {nb} blocks in {launches} launches", flush=True)
-        assert launches == nb if not merge else 1 <= launches <= nb
+        assert launches == nb if merge != 1 else 1 <= launches <= nb
         res = run_gat(c, graph=g)
+        res_recompute = run_gat(c, graph=g, stash=False)   # blocked recompute of the dst side
     finally:
         pk.gnn_config_set("block_cols", 20480)
         pk.gnn_config_set("merge_blocks", 1)
+        pk.gnn_config_set("resident_sums", 0)
     compare(c, res, fwd, bwd)
+    compare(c, res_recompute, fwd, bwd)
     # same inputs through the single-launch kernels: both paths must agree with the oracle
     pk.gnn_config_set("force_simple_kernels", 1)
     try:
@@ -214,7 +220,40 @@ def test_column_blocked_path(block_cols, H, F, merge):
         pk.gnn_config_set("force_simple_kernels", 0)
     compare(c, res2, fwd, bwd)
     assert np.array_equal(res["m"], res2["m"])      # the row maximum is exact on both paths
-    compare(c, run_gat(c, graph=g, stash=False), fwd, bwd)   # blocked recompute of the dst side
+
+
+@pytest.mark.parametrize("H,F,block_cols", [(4, 64, 256), (1, 256, 500), (2, 256, 200), (1, 128, 256), (2, 64, 300)])
+def test_resident_sums_repeat_the_launch_per_block_results_bit_for_bit(H, F, block_cols):
+    """The persistent kernel adds a row's chunks in the order of the launch-per-block kernels, whoever
+    draws the row and however the workgroups pace each other (also with the bounded wait cut to zero
+    polls): every output equals the unmerged launches' bit for bit."""
+    import paper_2110_09524_amd as pk
+    from gpu_harness import dev, run_gat
+    print(f"gat: resident sums H={H} F={F} block_cols={block_cols}", flush=True)
+    rng = np.random.default_rng(7 * block_cols + H + F)
+    n = 1800
+    indptr, indices = random_graph(rng, n, 40000, self_loops=False, duplicates=True)
+    c = synth(rng, indptr, indices, 16, H, F)
+    pk.gnn_config_set("block_cols", block_cols)
+    pk.gnn_config_set("merge_blocks", 0)
+    try:
+        g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
+        runs = {}
+        for key, resident, spin in (("launches", 0, 4096), ("resident", 1, 4096), ("unpaced", 1, 0)):
+            pk.gnn_config_set("resident_sums", resident)
+            pk.gnn_config_set("resident_spin", spin)
+            runs[key] = (run_gat(c, graph=g), run_gat(c, graph=g, stash=False))
+    finally:
+        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("merge_blocks", 1)
+        pk.gnn_config_set("resident_sums", 0)
+        pk.gnn_config_set("resident_spin", 4096)
+    g.close()
+    for key in ("resident", "unpaced"):
+        for a, b in zip(runs["launches"], runs[key]):
+            for name in a:
+                if isinstance(a[name], np.ndarray):
+                    assert np.array_equal(a[name], b[name]), f"{key}: {name} differs from the launch-per-block result"
 
 
 @pytest.mark.parametrize("H,F", [(4, 64), (8, 32), (1, 512), (2, 128), (1, 256)])
