@@ -27,14 +27,38 @@ __device__ __forceinline__ void wave_lds_fence() {
 }
 
 // butterfly reductions over lane-index bits [lo_stride, L): lanes that differ only
-// in those bits end up with the same value
+// in those bits end up with the same value.  Over whole groups (lo_stride == 1) the
+// steps inside a row of 16 lanes are DPP operations on the vector ALU (pairings: lane ^ 1
+// and lane ^ 2 inside quads, then the mirrored halves of 8 and of 16 lanes, which pair the
+// right quads because all lanes of a quad already agree); the results are the same bits as
+// the xor butterfly's, without four dependent trips through the LDS crossbar.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
 template <int L>
 __device__ __forceinline__ float group_max_from(float v, int lo_stride) {
+  if (lo_stride == 1) {
+    if (L > 1) v = fmaxf(v, dpp_move<0xB1>(v));   // quad_perm [1,0,3,2]
+    if (L > 2) v = fmaxf(v, dpp_move<0x4E>(v));   // quad_perm [2,3,0,1]
+    if (L > 4) v = fmaxf(v, dpp_move<0x141>(v));  // row_half_mirror
+    if (L > 8) v = fmaxf(v, dpp_move<0x140>(v));  // row_mirror
+    for (int off = 16; off < L; off <<= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+  }
   for (int off = lo_stride; off < L; off <<= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
   return v;
 }
 template <int L>
 __device__ __forceinline__ float group_sum_from(float v, int lo_stride) {
+  if (lo_stride == 1) {
+    if (L > 1) v += dpp_move<0xB1>(v);
+    if (L > 2) v += dpp_move<0x4E>(v);
+    if (L > 4) v += dpp_move<0x141>(v);
+    if (L > 8) v += dpp_move<0x140>(v);
+    for (int off = 16; off < L; off <<= 1) v += __shfl_xor(v, off, 64);
+    return v;
+  }
   for (int off = lo_stride; off < L; off <<= 1) v += __shfl_xor(v, off, 64);
   return v;
 }
