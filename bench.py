@@ -297,7 +297,7 @@ def main():
     ap.add_argument("--single-launch", action="store_true",
                     help="use the single-launch kernels also where the column-blocked ones apply")
     ap.add_argument("--block-cols", type=int, default=None,
-                    help="gathered vertices per column block of the blocked edge lists (library default 20480)")
+                    help="gathered vertices per column block of the blocked edge lists (library default 12288)")
     ap.add_argument("--monet-two-call", action="store_true",
                     help="MoNet workloads: projection and layer as separate calls with [E, r] coordinate arrays "
                          "between them (gnn_pseudo_proj_* + gnn_gmmp_*) instead of gnn_monet_*")

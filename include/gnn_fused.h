@@ -144,9 +144,24 @@ gnn_status_t gnn_graph_get_launch_groups(const gnn_graph_t* graph, int side, int
 gnn_status_t gnn_release_cached_memory(void);
 
 /* Tuning knobs, read when a graph is created or a layer is called.  Keys:
- *   "block_cols"            gathered vertices per column block (default 20480:
- *                           20480 rows x one 128-byte slice per XCD = 2.5 MB of a
- *                           4 MB L2); 0 disables blocking
+ *   "block_cols"            gathered vertices per column block (default 12288:
+ *                           12288 rows x one 256-byte slice = 3 MB of an XCD's 4 MB L2);
+ *                           0 disables blocking.  Read by gnn_graph_create.
+ *   "resident_sums"         1 (default): where rows are cut into 256-byte slices the column-blocked
+ *                           GAT and GCN kernels run all blocks of a pass in ONE persistent launch
+ *                           (one 1024-thread workgroup per CU) that keeps the rows' running sums
+ *                           and softmax statistics in LDS, a few thousand rows per workgroup at a
+ *                           time, instead of reading and writing them once per block.  The
+ *                           workgroups of an XCD meet at the end of every such batch of rows
+ *                           through counters the graph handle owns (a bounded wait that only
+ *                           serves cache residency); layer calls on ONE graph that overlap in
+ *                           time share those counters: their results stay right, their cache
+ *                           hit rates suffer.  0: one launch per block or group of blocks.
+ *                           Both give the same bits as one launch per block.
+ *   "resident_spin"         polls after which a workgroup of that launch stops waiting for the
+ *                           others of its XCD (default 4096; 0 = never wait; meant for tests)
+ *   "resident_sync_every"   the workgroups of an XCD meet after every k-th column block instead
+ *                           of once per batch of rows (default 0 = once per batch)
  *   "merge_blocks"          1 (default): adjacent column blocks with few edges share one
  *                           launch of a column-blocked kernel (up to 8 blocks; a row's running
  *                           sums are then read and written once for all of them), chosen per

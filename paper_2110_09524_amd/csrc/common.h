@@ -90,7 +90,7 @@ constexpr int kClockStride = 32;
 
 // ---- tuning knobs (runtime.hip) -------------------------------------------------
 enum ConfigKey { kCfgBlockCols = 0, kCfgForceSimple = 1, kCfgLdsScalarTable = 2, kCfgGcnMapping = 3, kCfgGmmMapping = 4, kCfgBlockedMinEdges = 5,
-                 kCfgGatherPrecision = 6, kCfgMergeBlocks = 7, kCfgWideOffsets = 8, kCfgResidentSums = 9, kCfgResidentSpin = 10, kCfgCount };
+                 kCfgGatherPrecision = 6, kCfgMergeBlocks = 7, kCfgWideOffsets = 8, kCfgResidentSums = 9, kCfgResidentSpin = 10, kCfgResidentSyncEvery = 11, kCfgCount };
 int64_t config_get(ConfigKey k);
 int device_cu_count();  // compute units of the current device (256 when the query fails)
 

@@ -526,7 +526,7 @@ __global__ __launch_bounds__(kGatResThreads) void k_gat_res(
     const float* __restrict__ er, const float* __restrict__ m_in, const float* __restrict__ d_in,
     const float4* __restrict__ vstate, GatDims dm, int sph, int narrow, int el_hm, int32_t block_cols,
     int nblk, int ns, float* __restrict__ acc_buf, float* __restrict__ acc2_buf, float* __restrict__ scal_buf,
-    float* __restrict__ m_out, float* __restrict__ d_out, int32_t* __restrict__ clock, int spin_limit) {
+    float* __restrict__ m_out, float* __restrict__ d_out, int32_t* __restrict__ clock, int spin_limit, int sync_every) {
   constexpr int GPB = kGatResThreads / SL;
   constexpr int NSLOT = kGatResSlots<SL, MODE>;
   constexpr int R = NSLOT / GPB;
@@ -561,7 +561,7 @@ __global__ __launch_bounds__(kGatResThreads) void k_gat_res(
   const int ngen = (int)((rows_per_group + R - 1) / R);
   // workgroups go to the XCDs round-robin: those with the same id mod 8 share an L2
   PhaseClock pc{clock ? clock + (blockIdx.x % kXcds) * kClockStride : nullptr, (int)(gridDim.x / kXcds), spin_limit,
-                false};
+                false, sync_every > 0 ? sync_every : nblk};
 
   const char* feat_bytes = reinterpret_cast<const char*>(feat);
   const uint32_t row_bytes = (uint32_t)HF * 4u, col_bytes = (uint32_t)col * 4u;
@@ -1011,7 +1011,7 @@ static gnn_status_t launch_resident_impl(const gnn_graph_t* g, int side, const c
   k_gat_res<SL, MODE, SKIP><<<grid, kGatResThreads, lds, st>>>(
       g->n, g->order[side], reinterpret_cast<const int2*>(g->bseg[side]), g->bcol[side], feat, rowfeat, el, er, m, d,
       vstate, dm, sph, narrow, el_hm, g->block_cols, g->nblk, ns, acc, acc2, scal, m_out, d_out, g->phase_clock,
-      (int)config_get(kCfgResidentSpin));
+      (int)config_get(kCfgResidentSpin), (int)config_get(kCfgResidentSyncEvery));
   GNN_LAUNCH_CHECK();
   return GNN_OK;
 }
@@ -1167,8 +1167,8 @@ gnn_status_t gat_blocked_bwd_src(const gnn_graph_t* g, GatDims dm, const float* 
 }  // namespace gnn
 
 // Which instantiation of the column-blocked kernel a pass launches for this graph and shape
-// (the plain, not LDS-staged variant), spelled as a profiler prints it; "" when the single-launch
-// kernels run instead.  Lets a measurement script check that stored counter readings belong to
+// (the persistent kernel, or the plain, not LDS-staged variant of the launch-per-block kernel),
+// spelled as a profiler prints it; "" when the single-launch kernels run instead.  Lets a measurement script check that stored counter readings belong to
 // the kernel it times.
 extern "C" gnn_status_t gnn_gat_blocked_kernel_name(const gnn_graph_t* g, int heads, int f, int mode,
                                                     char* buf, size_t len) {
@@ -1182,6 +1182,10 @@ extern "C" gnn_status_t gnn_gat_blocked_kernel_name(const gnn_graph_t* g, int he
   const bool half = mode != 1 && gat_blocked_half(g, heads, f);
   Slicing sl;
   if (!pick_slicing(heads, heads * f, sl)) return GNN_OK;
+  if (gat_resident_applies(g, make_dims(heads, f, 0.2f), half, nullptr)) {
+    std::snprintf(buf, len, "k_gat_res<16, %d, %s>", mode, heads * f / 64 >= 4 ? "true" : "false");
+    return GNN_OK;
+  }
   const int SL = half ? 8 : sl.SL;
   const int ns = heads * f / ((half ? 8 : 4) * SL);
   std::snprintf(buf, len, "k_gat_blk<%d, %d, false, %s, %s>", SL, mode, half ? "true" : "false",

@@ -392,7 +392,7 @@ __global__ __launch_bounds__(kResThreads) void k_rowsum_res(
     const int32_t* __restrict__ bcol, const float* __restrict__ feat, int32_t block_cols, int nblk, int F,
     int ns, const float* __restrict__ scale /* nullable: factor per row */, float* __restrict__ out,
     const float* __restrict__ bw, int32_t* __restrict__ clock /* nullable: step counters, zeroed */,
-    int spin_limit) {
+    int spin_limit, int sync_every) {
   constexpr int GPB = kResThreads / SL;
   constexpr int R = kResRows;
   constexpr int NSLOT = kResSlots<SL>;
@@ -418,7 +418,7 @@ __global__ __launch_bounds__(kResThreads) void k_rowsum_res(
   const int ngen = (int)((rows_per_group + R - 1) / R);
   // workgroups go to the XCDs round-robin: those with the same id mod 8 share an L2
   PhaseClock pc{clock ? clock + (blockIdx.x % kXcds) * kClockStride : nullptr, (int)(gridDim.x / kXcds), spin_limit,
-                false};
+                false, sync_every > 0 ? sync_every : nblk};
 
   struct Item {
     int32_t beg, end, c_first;
@@ -624,7 +624,7 @@ static gnn_status_t launch_rowsum_resident(const gnn_graph_t* g, int side, const
   }
   k_rowsum_res<SL, W><<<grid, kResThreads, lds, st>>>(g->n, g->order[side], reinterpret_cast<const int2*>(g->bseg[side]),
                                                      g->bcol[side], feat, g->block_cols, g->nblk, F, ns, scale, out, bw,
-                                                     clock, (int)config_get(kCfgResidentSpin));
+                                                     clock, (int)config_get(kCfgResidentSpin), (int)config_get(kCfgResidentSyncEvery));
   GNN_LAUNCH_CHECK();
   return GNN_OK;
 }

@@ -75,11 +75,12 @@ struct PhaseClock {
   int32_t* counter;  // this XCD's counter, zero at launch; null: no pacing between workgroups
   int nwg, spin_limit;
   bool gave_up;
+  int every;  // the workgroups meet after every `every`-th step only
 };
 __device__ __forceinline__ void phase_step_done(PhaseClock& pc, int step) {
-  if (pc.counter == nullptr || threadIdx.x != 0) return;
+  if (pc.counter == nullptr || threadIdx.x != 0 || (step + 1) % pc.every != 0) return;
   __hip_atomic_fetch_add(pc.counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  const int target = pc.nwg * (step + 1);
+  const int target = pc.nwg * ((step + 1) / pc.every);
   int polls = 0;
   while (!pc.gave_up && __hip_atomic_load(pc.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
     if (++polls > pc.spin_limit) pc.gave_up = true;

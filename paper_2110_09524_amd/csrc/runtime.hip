@@ -38,9 +38,12 @@ void clear_error() { g_err[0] = 0; }
 // (read at gnn_graph_create), 0 every block has its own launch
 // wide_offsets: 1 makes the column-blocked GAT kernels address gathered rows with 64-bit offsets
 // also where 32 bits reach every row (the path of matrices of 4 GB and more; a test hook)
-// resident_sums: 1 lets the column-blocked aggregations run all blocks in one persistent launch
-// that keeps the rows' running sums on the chip (LDS) instead of reading and writing them per block
-static std::atomic<int64_t> g_config[kCfgCount] = {{20480}, {0}, {1}, {2}, {2}, {16}, {0}, {1}, {0}, {0}, {4096}};
+// resident_sums: 1 (default) lets the column-blocked aggregations run all blocks in one persistent
+// launch that keeps the rows' running sums on the chip (LDS); 0: one launch per block or group of
+// blocks, the sums read and written in between
+static std::atomic<int64_t> g_config[kCfgCount] = {{12288}, {0}, {1}, {2}, {2}, {16}, {0}, {1}, {0}, {1}, {4096}, {0}};
+// resident_sync_every: the workgroups of an XCD meet after every k-th column block (0, default: once
+// per generation of rows, after the last block)
 // resident_spin: polls after which a workgroup of that launch stops waiting for the others of its XCD
 // at a block boundary (the wait only paces the workgroups; 0 = never wait)
 int64_t config_get(ConfigKey k) { return g_config[k].load(std::memory_order_relaxed); }
@@ -152,6 +155,11 @@ extern "C" gnn_status_t gnn_config_set(const char* key, int64_t value) {
   }
   if (std::strcmp(key, "resident_sums") == 0) {
     g_config[kCfgResidentSums].store(value != 0);
+    return GNN_OK;
+  }
+  if (std::strcmp(key, "resident_sync_every") == 0) {
+    GNN_REQUIRE(value >= 0 && value <= 64, GNN_ERR_INVALID_ARG, "gnn_config_set: resident_sync_every must be 0 .. 64");
+    g_config[kCfgResidentSyncEvery].store(value);
     return GNN_OK;
   }
   if (std::strcmp(key, "resident_spin") == 0) {

@@ -143,14 +143,20 @@ def test_gat_c4_sampled_rows_and_consistency(c4, sample, capsys):
         assert_close(k + " (two kernel paths)", res[k], res2[k],
                      reduce_scale=k in ("gw", "ga_l", "ga_r"))
     assert_close("gx (two kernel paths)", res["gx"], res2["gx"])
-    # the hub block's LDS-table variant adds the same terms in the same order as the plain one
-    pk.gnn_config_set("lds_scalar_table", 0)
+    # the launch-per-block kernels (one launch per column block, the dense blocks with the score table
+    # in LDS) add the same terms in the same order as the persistent kernel: every output bit for bit
+    say("launch-per-block kernels against the persistent launch")
+    pk.gnn_config_set("resident_sums", 0)
+    pk.gnn_config_set("merge_blocks", 0)
     try:
-        res3 = run_gat(c, graph=g, backward=False)
+        g2 = pk.Graph(dev(ip), dev(ix))
+        res3 = run_gat(c, graph=g2)
+        g2.close()
     finally:
-        pk.gnn_config_set("lds_scalar_table", 1)
-    for k in ("out", "t", "sg", "m", "d"):
-        assert np.array_equal(res[k], res3[k]), f"{k}: LDS-table and plain variants differ at full size"
+        pk.gnn_config_set("resident_sums", 1)
+        pk.gnn_config_set("merge_blocks", 1)
+    for k in ("out", "t", "sg", "m", "d", "gx", "gw", "ga_l", "ga_r"):
+        assert np.array_equal(res[k], res3[k]), f"{k}: persistent and launch-per-block kernels differ at full size"
     g.close()
 
 

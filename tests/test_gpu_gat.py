@@ -207,9 +207,9 @@ def test_column_blocked_path(block_cols, H, F, merge):
         res = run_gat(c, graph=g)
         res_recompute = run_gat(c, graph=g, stash=False)   # blocked recompute of the dst side
     finally:
-        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("block_cols", 12288)
         pk.gnn_config_set("merge_blocks", 1)
-        pk.gnn_config_set("resident_sums", 0)
+        pk.gnn_config_set("resident_sums", 1)
     compare(c, res, fwd, bwd)
     compare(c, res_recompute, fwd, bwd)
     # same inputs through the single-launch kernels: both paths must agree with the oracle
@@ -244,9 +244,9 @@ def test_resident_sums_repeat_the_launch_per_block_results_bit_for_bit(H, F, blo
             pk.gnn_config_set("resident_spin", spin)
             runs[key] = (run_gat(c, graph=g), run_gat(c, graph=g, stash=False))
     finally:
-        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("block_cols", 12288)
         pk.gnn_config_set("merge_blocks", 1)
-        pk.gnn_config_set("resident_sums", 0)
+        pk.gnn_config_set("resident_sums", 1)
         pk.gnn_config_set("resident_spin", 4096)
     g.close()
     for key in ("resident", "unpaced"):
@@ -282,6 +282,7 @@ def test_blocked_path_with_the_score_table_in_lds(H, F):
     assert in_block0 >= 128 * n and len(indices) - in_block0 < 128 * n   # one block of each kind
     fwd, bwd = oracle_all(c)
     pk.gnn_config_set("block_cols", block_cols)
+    pk.gnn_config_set("resident_sums", 0)       # the launch-per-block kernels are the ones with the table
     try:
         g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
         assert g.blocked(0)[0] == 2
@@ -298,14 +299,15 @@ def test_blocked_path_with_the_score_table_in_lds(H, F):
             pk.gnn_config_set("lds_scalar_table", 1)
         g.close()
     finally:
-        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("block_cols", 12288)
+        pk.gnn_config_set("resident_sums", 1)
     compare(c, res, fwd, bwd)
     compare(c, res_nostash, fwd, bwd)
     for k in res:
         assert np.array_equal(res[k], ref[k]), f"{k}: LDS-table and plain variants differ"
 
 
-@pytest.mark.parametrize("blocked", [False, True])
+@pytest.mark.parametrize("blocked", [False, True, "launch per block"])
 def test_large_score_range_is_stable(blocked):
     """Scores spanning hundreds of units: without the max subtraction exp() would overflow,
     with it most weights underflow to exactly 0 and the rest must still match (Sec. 7.2, the
@@ -324,11 +326,13 @@ def test_large_score_range_is_stable(blocked):
     fwd, bwd = oracle_all(c)
     spread = float(np.abs(fwd["M1"]).max())
     assert spread > 100.0                                       # the case is what it claims to be
-    pk.gnn_config_set("block_cols", 128 if blocked else 20480)
+    pk.gnn_config_set("block_cols", 128 if blocked else 12288)
+    pk.gnn_config_set("resident_sums", int(blocked != "launch per block"))
     try:
         res = run_gat(c)
     finally:
-        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("block_cols", 12288)
+        pk.gnn_config_set("resident_sums", 1)
     grads = {k: res.pop(k) for k in ("gx", "gw", "ga_l", "ga_r")}
     compare(c, res, fwd, None)
     assert np.isfinite(res["out"]).all() and (res["d"] >= 1.0 - 1e-6).all()
@@ -370,7 +374,7 @@ def test_many_vertices_few_edges_on_the_blocked_path():
     c = synth(rng, indptr, indices, 6, 4, 32)
     fwd, bwd = oracle_all(c)
     g = pk.Graph(dev(indptr), dev(indices))
-    assert g.blocked(0)[0] == -(-n // 20480)
+    assert g.blocked(0)[0] == -(-n // 12288)
     res = run_gat(c, graph=g)
     compare(c, res, fwd, bwd)
     assert (res["out"][n // 2:] == 0).all()
@@ -413,7 +417,7 @@ def test_fusion_with_stashing_arm_on_a_column_blocked_graph_and_bad_arguments():
         assert pk.gnn_gat_stash_layout(g, 4, 64) == 1    # the stash is laid out for the column-blocked kernel
         res = run_gat(c, graph=g, alpha_stash=True)      # forward and stashed backward both column-blocked
     finally:
-        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("block_cols", 12288)
     # layout 1: [h][q], q = position in the source side's blocked list = the CSC entries (source,
     # CSR position) stable-sorted by (block of the destination, source)
     csc = np.lexsort((np.arange(nnz), c["indices"]))
@@ -454,7 +458,7 @@ def test_sparse_graph_spanning_blocks_takes_the_single_launch_kernels():
             pk.gnn_prof_enable(False)
             g.close()
         finally:
-            pk.gnn_config_set("block_cols", 20480)
+            pk.gnn_config_set("block_cols", 12288)
             pk.gnn_config_set("blocked_min_edges", 0)
         return names
     assert "gat_head_major" not in kernels_used(16, 256)      # 6 blocks: 3.3 edges per (row, block)
@@ -488,7 +492,7 @@ def test_fp16_gather_storage(H, F):
             pk.gnn_config_set("gather_precision", 0)
         g.close()
     finally:
-        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("block_cols", 12288)
     compare(c, ref32, fwd, bwd)                       # the default path keeps the contract
 
     def rel(a, b):
@@ -524,15 +528,16 @@ def test_fp16_gather_storage_leaves_uncovered_shapes_in_fp32():
             pk.gnn_config_set("gather_precision", 0)
         g.close()
     finally:
-        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("block_cols", 12288)
     for k in a:
         assert np.array_equal(a[k], b[k]), k
     with pytest.raises(pk.GnnError):
         pk.gnn_config_set("gather_precision", 2)
 
 
+@pytest.mark.parametrize("resident", [1, 0])
 @pytest.mark.parametrize("H,F", [(4, 64), (1, 128)])
-def test_column_blocked_path_with_64_bit_row_offsets(H, F):
+def test_column_blocked_path_with_64_bit_row_offsets(H, F, resident):
     """Gathered matrices of 4 GB and more are addressed with 64-bit offsets; the configuration key
     "wide_offsets" takes that path on a graph small enough for the oracle."""
     import paper_2110_09524_amd as pk
@@ -544,12 +549,14 @@ def test_column_blocked_path_with_64_bit_row_offsets(H, F):
     fwd, bwd = oracle_all(c)
     pk.gnn_config_set("block_cols", 300)
     pk.gnn_config_set("wide_offsets", 1)
+    pk.gnn_config_set("resident_sums", resident)
     try:
         g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
         res = run_gat(c, graph=g)
         g.close()
     finally:
-        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("block_cols", 12288)
         pk.gnn_config_set("wide_offsets", 0)
+        pk.gnn_config_set("resident_sums", 1)
     compare(c, res, fwd, bwd)
 

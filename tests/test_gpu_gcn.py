@@ -94,9 +94,9 @@ def test_column_blocked_path(block_cols, fout, merge):
         check(c, graph=g)
         g.close()
     finally:
-        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("block_cols", 12288)
         pk.gnn_config_set("merge_blocks", 1)
-        pk.gnn_config_set("resident_sums", 0)
+        pk.gnn_config_set("resident_sums", 1)
         pk.gnn_config_set("resident_spin", 4096)
 
 
@@ -133,7 +133,7 @@ def test_many_vertices_few_edges_on_the_blocked_path():
     indptr = np.cumsum(indptr).astype(np.int32)
     c = synth(rng, indptr, src.astype(np.int32), 6, 128)
     g = pk.Graph(dev(indptr), dev(c["indices"]))
-    assert g.blocked(0)[0] == -(-n // 20480)
+    assert g.blocked(0)[0] == -(-n // 12288)
     res = check(c, graph=g)
     assert (res["out"][n // 2:] == 0).all()
     g.close()
@@ -279,8 +279,8 @@ def test_edge_weighted_column_blocked_path(block_cols, fout, resident):
     try:
         _, nblk = check_edge(c)
     finally:
-        pk.gnn_config_set("block_cols", 20480)
-        pk.gnn_config_set("resident_sums", 0)
+        pk.gnn_config_set("block_cols", 12288)
+        pk.gnn_config_set("resident_sums", 1)
     assert nblk == -(-1500 // block_cols)
 
 

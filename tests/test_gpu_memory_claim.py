@@ -45,6 +45,6 @@ def test_blocked_path_workspace_is_still_vertex_sized():
             sizes.append(pk.gnn_gat_workspace_bytes(g, 64, 4, 64))
             g.close()
     finally:
-        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("block_cols", 12288)
     assert sizes[0] == sizes[1]
     assert sizes[0] < 6 * 4 * n * 256

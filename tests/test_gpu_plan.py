@@ -82,7 +82,7 @@ def test_blocked_edge_lists(block_cols):
     try:
         g = pk.Graph(dev(indptr), dev(indices))
     finally:
-        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("block_cols", 12288)
     ip_t, ix_t, _ = (t.cpu().numpy() for t in g.csc())
     for side, ptr, cols in ((0, indptr, indices), (1, ip_t, ix_t)):
         nb, bc, bptr, bcol = g.blocked(side)
@@ -133,7 +133,11 @@ def test_launch_groups_merge_the_sparse_tail_and_keep_dense_blocks_alone():
                            rng.integers(2 * bc, n, size=(n, 1))], axis=1)
     indices = np.sort(cols, axis=1).astype(np.int32).ravel()
     indptr = (np.arange(n + 1, dtype=np.int64) * cols.shape[1]).astype(np.int32)
-    g = pk.Graph(dev(indptr), dev(indices))
+    pk.gnn_config_set("block_cols", bc)
+    try:
+        g = pk.Graph(dev(indptr), dev(indices))
+    finally:
+        pk.gnn_config_set("block_cols", 12288)
     assert g.blocked(0)[:2] == (3, bc)
     assert g.launch_groups(0, 1) == [0, 1, 3] == g.launch_groups(0, 2)
     g.close()
@@ -150,7 +154,7 @@ def test_launch_groups_merge_the_sparse_tail_and_keep_dense_blocks_alone():
         pk.gnn_config_set("merge_blocks", 0)
         g_plain = pk.Graph(dev(indptr), dev(indices))
     finally:
-        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("block_cols", 12288)
         pk.gnn_config_set("merge_blocks", 1)
     nb = g.blocked(0)[0]
     assert nb == 10

@@ -1,6 +1,6 @@
 """Seeded random sweep over all four layers: graph sizes from 1 to 1800 vertices, empty graphs, hub
 vertices that hear from / speak to most of the graph, rows without in-edges, duplicate edges, odd
-and maximal widths, forced column blocking with merged and unmerged launches, both thread
+and maximal widths, forced column blocking in one persistent launch or with merged and unmerged launches, both thread
 mappings, every backward arm — each case against the fp64 oracle element by element."""
 import numpy as np
 import pytest
@@ -43,14 +43,16 @@ def one_trial(rng, pk):
     bc = int(rng.choice([24576, 16, 64, 128, 300, 512])) if n >= 60 else 24576
     mg = int(rng.integers(0, 2))
     kind = str(rng.choice(["gat", "gat", "gmm", "ec", "gcn", "gcnw"]))
-    pk.gnn_config_set("block_cols", bc)
+    rs = int((int(indices.sum()) + len(indices) + n) % 2)   # persistent launch or launches per block (a function
+    pk.gnn_config_set("block_cols", bc)                      # of the graph, so the random stream stays as it was)
     pk.gnn_config_set("merge_blocks", mg)
+    pk.gnn_config_set("resident_sums", rs)
     gpu_harness.ROW_SCALED_IN_SWEEP.update({"gx", "out"} if kind == "gmm" else {"gx"})
     if kind == "gat":
         H, F = GAT_SHAPES[int(rng.integers(0, len(GAT_SHAPES)))]
         fin = int(rng.choice([2, 5, 24, 70]))
         stash, astash = bool(rng.random() < 0.7), bool(rng.random() < 0.25)
-        desc = f"gat n={n} nnz={len(indices)} fin={fin} H={H} F={F} bc={bc} merge={mg} stash={stash} alpha_stash={astash}"
+        desc = f"gat n={n} nnz={len(indices)} fin={fin} H={H} F={F} bc={bc} merge={mg} resident={rs} stash={stash} alpha_stash={astash}"
         c = TG.synth(rng, indptr, indices, fin, H, F)
         fwd, bwd = TG.oracle_all(c)
         try:
@@ -76,7 +78,7 @@ def one_trial(rng, pk):
     else:
         fin, fout = int(rng.choice([3, 16, 40])), int(rng.choice([4, 32, 64, 128, 256, 512, 1024, 36]))
         mp = int(rng.integers(0, 2))
-        desc = f"{kind} n={n} nnz={len(indices)} fin={fin} fout={fout} bc={bc} merge={mg} mapping={mp}"
+        desc = f"{kind} n={n} nnz={len(indices)} fin={fin} fout={fout} bc={bc} merge={mg} resident={rs} mapping={mp}"
         c = TC.synth(rng, indptr, indices, fin, fout)
         if kind == "gcn":
             pk.gnn_config_set("gcn_mapping", mp)
@@ -103,8 +105,9 @@ def test_random_cases_match_the_oracle(seed):
                 failures.append(f"seed {seed} trial {trial}: {str(ex)[:300]}")
             finally:
                 gpu_harness.ROW_SCALED_IN_SWEEP.clear()
-                pk.gnn_config_set("block_cols", 20480)
+                pk.gnn_config_set("block_cols", 12288)
                 pk.gnn_config_set("merge_blocks", 1)
+                pk.gnn_config_set("resident_sums", 1)
                 pk.gnn_config_set("gmm_mapping", 2)
                 pk.gnn_config_set("gcn_mapping", 2)
     finally:

@@ -59,7 +59,7 @@ def test_noalloc_backward_on_the_column_blocked_kernels():
     try:
         ref, got = _both(c, True)
     finally:
-        pk.gnn_config_set("block_cols", 20480)
+        pk.gnn_config_set("block_cols", 12288)
     for k in ("gx", "gw", "ga_l", "ga_r"):
         assert np.array_equal(got[k], ref[k]), k
 
