@@ -9,17 +9,25 @@ import pytest
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name", ["gat_c2", "gat_c4_mid"])
-def test_captured_gat_step_replays_exactly(name):
+@pytest.mark.parametrize("name,block_cols", [("gat_c2", None), ("gat_c4_mid", None), ("gat_c4_mid", 1024)])
+def test_captured_gat_step_replays_exactly(name, block_cols):
+    """block_cols = 1024 puts the 6000-vertex graph on the column-blocked path: the persistent
+    kernels (and the small kernel that zeroes their step counters) are what the graph records."""
     import torch
     import paper_2110_09524_amd as pk
     from gpu_harness import dev, empty, workspace
     from workloads import make
-    print(f"graph capture: {name}", flush=True)
+    print(f"graph capture: {name} block_cols={block_cols}", flush=True)
     c = make(name)
     n, fin, H, F = c["n"], c["fin"], c["heads"], c["f"]
     HF = H * F
-    g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
+    if block_cols:
+        pk.gnn_config_set("block_cols", block_cols)
+    try:
+        g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
+    finally:
+        pk.gnn_config_set("block_cols", 12288)
+    assert not block_cols or g.blocked(0)[0] > 1
     x, w, a_l, a_r, gout = (dev(c[k]) for k in ("x", "w", "a_l", "a_r", "gout"))
     bufs = lambda: dict(z=empty((n, HF)), out=empty((n, HF)), t=empty((n, HF)), el=empty((n, H)),
                         er=empty((n, H)), m=empty((n, H)), d=empty((n, H)), sg=empty((n, H)),
