@@ -526,7 +526,10 @@ __global__ __launch_bounds__(kGatResThreads) void k_gat_res(
     const float* __restrict__ er, const float* __restrict__ m_in, const float* __restrict__ d_in,
     const float4* __restrict__ vstate, GatDims dm, int sph, int narrow, int el_hm, int32_t block_cols,
     int nblk, int ns, float* __restrict__ acc_buf, float* __restrict__ acc2_buf, float* __restrict__ scal_buf,
-    float* __restrict__ m_out, float* __restrict__ d_out, int32_t* __restrict__ clock, int spin_limit, int sync_every) {
+    float* __restrict__ m_out, float* __restrict__ d_out, int32_t* __restrict__ clock, int spin_limit, int sync_every,
+    const float* __restrict__ alpha_b /* MODE 2, nullable: stashed signed softmax values, [H][nnz] in the order of
+                                         bcol (the "fusion with stashing" arm) */,
+    int64_t nnz) {
   constexpr int GPB = kGatResThreads / SL;
   constexpr int NSLOT = kGatResSlots<SL, MODE>;
   constexpr int R = NSLOT / GPB;
@@ -655,8 +658,9 @@ __global__ __launch_bounds__(kGatResThreads) void k_gat_res(
             const int32_t c = e_ok ? c_next : col_begin;
             if (c0 + SL + li < end) c_next = bcol[c0 + SL + li];
             l_idx[li] = c;
-            float e_a = 0.f;
+            float e_a = 0.f, a_st = 0.f;
             float4 vs = make_float4(0.f, 0.f, 1.f, 0.f);
+            if (SRC && alpha_b != nullptr && e_ok) a_st = alpha_b[(int64_t)h * nnz + c0 + li];
             if (e_ok) {
               if (SRC) vs = vstate[(int64_t)h * n_rows + c];  // head-major (er, m, 1/d, D) of the destination
               else e_a = el_hm ? el[(int64_t)h * n_rows + c] : el[(int64_t)c * H + h];
@@ -693,9 +697,14 @@ __global__ __launch_bounds__(kGatResThreads) void k_gat_res(
                 float pe = 0.f, pe2 = 0.f;
                 if (e_ok) {
                   if (SRC) {
-                    const float raw = r_a + vs.x;
-                    pe = __expf(leaky(raw, dm.slope) - vs.y) * vs.z;
-                    pe2 = raw > 0.f ? pe : dm.slope * pe;
+                    if (alpha_b != nullptr) {  // read back instead of recomputed; D[v] is still gathered
+                      pe = fabsf(a_st);
+                      pe2 = a_st > 0.f ? pe : dm.slope * pe;
+                    } else {
+                      const float raw = r_a + vs.x;
+                      pe = __expf(leaky(raw, dm.slope) - vs.y) * vs.z;
+                      pe2 = raw > 0.f ? pe : dm.slope * pe;
+                    }
                     s_run = fmaf(pe2, vs.w, s_run);
                   } else if (!ONLINE) {
                     const float raw = e_a + r_a;
@@ -978,9 +987,9 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
                                                    scal, queue, state, m_out, d_out, st, alpha_b);
 }
 
-// The persistent kernel applies to fp32 rows in 256-byte slices, without a per-edge stash
-static bool gat_resident_applies(const gnn_graph_t* g, GatDims dm, bool half_feat, const float* alpha_b) {
-  if (!config_get(kCfgResidentSums) || half_feat || alpha_b != nullptr || g->phase_clock == nullptr) return false;
+// The persistent kernel applies to fp32 rows in 256-byte slices
+static bool gat_resident_applies(const gnn_graph_t* g, GatDims dm, bool half_feat) {
+  if (!config_get(kCfgResidentSums) || half_feat || g->phase_clock == nullptr) return false;
   Slicing sl;
   return pick_slicing(dm.H, dm.HF, sl) && sl.SL == 16;
 }
@@ -989,7 +998,8 @@ template <int MODE, bool SKIP>
 static gnn_status_t launch_resident_impl(const gnn_graph_t* g, int side, const char* name, GatDims dm, int el_hm,
                                          const float* feat, const float* rowfeat, const float* el, const float* er,
                                          const float* m, const float* d, const float4* vstate, float* acc,
-                                         float* acc2, float* scal, float* m_out, float* d_out, hipStream_t st) {
+                                         float* acc2, float* scal, float* m_out, float* d_out, hipStream_t st,
+                                         const float* alpha_b) {
   constexpr int SL = 16;
   const int ns = dm.HF / (4 * SL);
   const int sph = ns / dm.H;
@@ -1011,7 +1021,7 @@ static gnn_status_t launch_resident_impl(const gnn_graph_t* g, int side, const c
   k_gat_res<SL, MODE, SKIP><<<grid, kGatResThreads, lds, st>>>(
       g->n, g->order[side], reinterpret_cast<const int2*>(g->bseg[side]), g->bcol[side], feat, rowfeat, el, er, m, d,
       vstate, dm, sph, narrow, el_hm, g->block_cols, g->nblk, ns, acc, acc2, scal, m_out, d_out, g->phase_clock,
-      (int)config_get(kCfgResidentSpin), (int)config_get(kCfgResidentSyncEvery));
+      (int)config_get(kCfgResidentSpin), (int)config_get(kCfgResidentSyncEvery), alpha_b, g->nnz);
   GNN_LAUNCH_CHECK();
   return GNN_OK;
 }
@@ -1020,12 +1030,12 @@ template <int MODE>
 static gnn_status_t launch_resident(const gnn_graph_t* g, int side, const char* name, GatDims dm, int el_hm,
                                     const float* feat, const float* rowfeat, const float* el, const float* er,
                                     const float* m, const float* d, const float4* vstate, float* acc, float* acc2,
-                                    float* scal, float* m_out, float* d_out, hipStream_t st) {
+                                    float* scal, float* m_out, float* d_out, hipStream_t st, const float* alpha_b) {
   if (dm.HF / 64 >= 4)
     return launch_resident_impl<MODE, true>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2,
-                                            scal, m_out, d_out, st);
+                                            scal, m_out, d_out, st, alpha_b);
   return launch_resident_impl<MODE, false>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2,
-                                           scal, m_out, d_out, st);
+                                           scal, m_out, d_out, st, alpha_b);
 }
 
 template <int MODE>
@@ -1034,9 +1044,9 @@ static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name,
                                const float* d, const float4* vstate, float* acc, float* acc2,
                                float* scal, int32_t* queue, float4* state, float* m_out, float* d_out,
                                hipStream_t st, bool half_feat = false, const float* alpha_b = nullptr) {
-  if (gat_resident_applies(g, dm, half_feat, alpha_b))
+  if (gat_resident_applies(g, dm, half_feat))
     return launch_resident<MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal,
-                                 m_out, d_out, st);
+                                 m_out, d_out, st, alpha_b);
   if (half_feat) {
     if constexpr (MODE != 1)
       return launch_blocks<8, MODE, true>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal,
@@ -1182,7 +1192,7 @@ extern "C" gnn_status_t gnn_gat_blocked_kernel_name(const gnn_graph_t* g, int he
   const bool half = mode != 1 && gat_blocked_half(g, heads, f);
   Slicing sl;
   if (!pick_slicing(heads, heads * f, sl)) return GNN_OK;
-  if (gat_resident_applies(g, make_dims(heads, f, 0.2f), half, nullptr)) {
+  if (gat_resident_applies(g, make_dims(heads, f, 0.2f), half)) {
     std::snprintf(buf, len, "k_gat_res<16, %d, %s>", mode, heads * f / 64 >= 4 ? "true" : "false");
     return GNN_OK;
   }
