@@ -650,6 +650,14 @@ def main():
                 print(f"[bench] profiles/{args.workload}_hbm_traffic.txt was measured on "
                       f"'{tv.get('rocprof_kernel')}', this run launches '{traffic_kernel}': traffic not reported",
                       file=sys.stderr, flush=True)
+        elif kind == "gcn":
+            traffic_kernel = pk.gnn_gcn_blocked_kernel_name(g, F, ew is not None)
+            if traffic_kernel and traffic_kernel == tv.get("rocprof_kernel"):
+                traffic = float(tv["hbm_bytes_per_launch"])
+            else:
+                print(f"[bench] profiles/{args.workload}_hbm_traffic.txt was measured on "
+                      f"'{tv.get('rocprof_kernel')}', this run launches '{traffic_kernel}': traffic not reported",
+                      file=sys.stderr, flush=True)
         else:
             traffic = float(tv["hbm_bytes_per_launch"])
     roofline = {

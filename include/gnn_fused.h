@@ -271,9 +271,10 @@ gnn_status_t gnn_gat_bwd_noalloc(const gnn_graph_t* graph, int fin, int heads, i
 
 /* Introspection for measurement scripts: the instantiation of the column-blocked edge kernel that
  * a pass over this graph launches for `heads` x `f` (mode 0 forward, 1 destination side recomputing,
- * 2 source side, 3 forward with stash), spelled as a profiler prints it, e.g.
- * "k_gat_blk<16, 2, false, false, true>"; the empty string when the single-launch kernels run.
- * buf is a HOST buffer of len bytes. */
+ * 2 source side, 3 forward with stash) under the current configuration, spelled as a profiler
+ * prints it, e.g. "k_gat_res<16, 2, true>" (the persistent launch) or
+ * "k_gat_blk<16, 2, false, false, true>" (one launch per block); the empty string when the
+ * single-launch kernels run.  buf is a HOST buffer of len bytes. */
 gnn_status_t gnn_gat_blocked_kernel_name(const gnn_graph_t* graph, int heads, int f, int mode,
                                          char* buf /*host*/, size_t len);
 
@@ -524,6 +525,12 @@ gnn_status_t gnn_gcn_edge_bwd(const gnn_graph_t* graph, const gnn_edge_weights_t
  * gnn_graph_create).  Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
 gnn_status_t gnn_gcn_tune(gnn_graph_t* graph, int fout, void* ws, size_t ws_bytes, void* stream,
                           float* ms_out /*host [4], nullable*/);
+
+/* The same for the GCN sums over rows of `fout` floats (weighted = 1: the layer with a general weight
+ * per edge), e.g. "k_rowsum_res<16, false>" or "k_rowsum_blk<16, true, false>"; the empty string
+ * when the single-launch or edge-balanced kernels run. */
+gnn_status_t gnn_gcn_blocked_kernel_name(const gnn_graph_t* graph, int fout, int weighted,
+                                         char* buf /*host*/, size_t len);
 
 /* ------------------------------------------------------------------------- *
  * Lightweight vertex operators and the loss of a node-classification step (Sec. 3:

@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     gnn_gmmp_workspace_bytes, gnn_gmmp_fwd, gnn_gmmp_bwd,
     gnn_pseudo_proj_workspace_bytes, gnn_pseudo_proj_fwd, gnn_pseudo_proj_bwd,
     gnn_monet_workspace_bytes, gnn_monet_fwd, gnn_monet_bwd,
-    gnn_gcn_workspace_bytes, gnn_gcn_fwd, gnn_gcn_bwd, gnn_gcn_tune,
+    gnn_gcn_workspace_bytes, gnn_gcn_fwd, gnn_gcn_bwd, gnn_gcn_tune, gnn_gcn_blocked_kernel_name,
     EdgeWeights, gnn_gcn_edge_fwd, gnn_gcn_edge_bwd,
     gnn_bias_act_fwd, gnn_bias_act_workspace_bytes, gnn_bias_act_bwd,
     gnn_softmax_xent_workspace_bytes, gnn_softmax_xent, gnn_sgd_update, gnn_knn_graph,

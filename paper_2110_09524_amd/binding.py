@@ -26,7 +26,7 @@ EXPORTS = [
     "gnn_gmm_workspace_bytes", "gnn_gmm_fwd", "gnn_gmm_bwd", "gnn_gmm_tune", "gnn_gmm_tune_bwd",
     "gnn_gmmp_workspace_bytes", "gnn_gmmp_fwd", "gnn_gmmp_bwd", "gnn_pseudo_proj_workspace_bytes",
     "gnn_pseudo_proj_fwd", "gnn_pseudo_proj_bwd", "gnn_monet_workspace_bytes", "gnn_monet_fwd", "gnn_monet_bwd",
-    "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_gcn_tune",
+    "gnn_gcn_workspace_bytes", "gnn_gcn_fwd", "gnn_gcn_bwd", "gnn_gcn_tune", "gnn_gcn_blocked_kernel_name",
     "gnn_edge_weights_create", "gnn_edge_weights_destroy", "gnn_gcn_edge_fwd", "gnn_gcn_edge_bwd",
     "gnn_bias_act_fwd", "gnn_bias_act_workspace_bytes", "gnn_bias_act_bwd", "gnn_softmax_xent_workspace_bytes",
     "gnn_softmax_xent", "gnn_sgd_update", "gnn_knn_graph", "gnn_prof_enable",
@@ -64,6 +64,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.gnn_gat_bwd.argtypes = [vp, i32, i32, i32, f32] + [vp] * 17 + [vp, sz, vp]
     lib.gnn_gat_bwd_noalloc.argtypes = [vp, i32, i32, i32, f32] + [vp] * 17 + [vp]
     lib.gnn_gat_blocked_kernel_name.argtypes = [vp, i32, i32, i32, C.c_char_p, sz]
+    lib.gnn_gcn_blocked_kernel_name.argtypes = [vp, i32, i32, C.c_char_p, sz]
     lib.gnn_gat_stash_alpha.argtypes = [vp, i32, i32, f32] + [vp] * 5 + [vp]
     lib.gnn_gat_stash_layout.argtypes = [vp, i32, i32]
     lib.gnn_gat_stash_layout.restype = i32
@@ -270,6 +271,12 @@ def gnn_gat_bwd(g: Graph, fin, heads, f, slope, x, w, a_l, a_r, z, el, er, m, d,
 def gnn_gat_blocked_kernel_name(g: Graph, heads, f, mode) -> str:
     buf = C.create_string_buffer(128)
     _check(lib().gnn_gat_blocked_kernel_name(g.handle, heads, f, mode, buf, 128))
+    return buf.value.decode()
+
+
+def gnn_gcn_blocked_kernel_name(g: Graph, fout, weighted=False) -> str:
+    buf = C.create_string_buffer(128)
+    _check(lib().gnn_gcn_blocked_kernel_name(g.handle, fout, int(bool(weighted)), buf, 128))
     return buf.value.decode()
 
 

@@ -19,6 +19,7 @@
 // runs with atomic adds.  gnn_gcn_tune times both on a graph and the layer calls then use the
 // faster one per side (the profile-driven choice of the mapping).
 #include <atomic>
+#include <cstdio>
 
 #include "common.h"
 #include "rowgroup.h"
@@ -975,5 +976,23 @@ extern "C" gnn_status_t gnn_gcn_tune(gnn_graph_t* g, int fout, void* ws, size_t 
   }
   if (ms_out)
     for (int i = 0; i < 4; ++i) ms_out[i] = ms[i];
+  return GNN_OK;
+}
+
+// Which instantiation of the column-blocked sum a pass launches for this graph and width under the
+// current configuration, spelled as a profiler prints it; "" when other kernels run.
+extern "C" gnn_status_t gnn_gcn_blocked_kernel_name(const gnn_graph_t* g, int fout, int weighted, char* buf,
+                                                    size_t len) {
+  clear_error();
+  GNN_REQUIRE(g != nullptr && buf != nullptr && len > 0, GNN_ERR_INVALID_ARG,
+              "gnn_gcn_blocked_kernel_name: null argument");
+  buf[0] = 0;
+  if (fout <= 0 || !gcn_blocked_applies(g, fout) || config_get(kCfgGcnMapping) == 1) return GNN_OK;
+  int SL = 0, ns = 0;
+  gcn_slicing(fout, SL, ns);
+  if (config_get(kCfgResidentSums) && SL == 16 && g->phase_clock != nullptr)
+    std::snprintf(buf, len, "k_rowsum_res<16, %s>", weighted ? "true" : "false");
+  else
+    std::snprintf(buf, len, "k_rowsum_blk<%d, %s, %s>", SL, ns >= 4 ? "true" : "false", weighted ? "true" : "false");
   return GNN_OK;
 }
