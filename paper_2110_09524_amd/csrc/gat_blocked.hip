@@ -501,11 +501,11 @@ __global__ __launch_bounds__(STAGE ? kStageThreads : kBlkThreads) void k_gat_blk
 // softmax statistics, the row's own scalars.  It takes all of them through column block 0, then
 // all of them through block 1, ... ("phases"), writes each row out in the last phase and then
 // takes its next rows ("generation").  Every workgroup of the chip owns the same number of rows
-// per generation, picked from the degree order with a stride of the number of groups, so the
-// workgroups carry nearly equal loads in every phase; the workgroups of an XCD enter a phase
-// together (phase_step_done: a bounded wait that only serves cache residency), so an L2 serves one
-// block at a time.  Inside a workgroup the groups draw (row, slice) slots from an LDS counter,
-// longest rows first.  A row's chunks are summed in the order of the launch-per-block kernels
+// per generation, dealt from the degree order one position at a time in alternating direction,
+// so the workgroups carry nearly equal loads in every phase and walk the blocks in step by
+// themselves; the workgroups of an XCD meet once per generation (phase_step_done: a bounded wait
+// that only serves cache residency), so an L2 serves one block at a time.  Inside a workgroup the
+// groups draw (row, slice) slots from an LDS counter, longest rows first.  A row's chunks are summed in the order of the launch-per-block kernels
 // (blocks ascending, edges in list order), so the results do not depend on who draws what.
 // MODE as k_gat_blk; one segment per phase, fp32 rows, per-edge scalars gathered from L2.
 constexpr int kGatResThreads = 1024;

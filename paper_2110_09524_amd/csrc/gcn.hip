@@ -371,12 +371,13 @@ __global__ __launch_bounds__(kGcnBlock) void k_rowsum_blk(
 // kResSlots (row, slice) pairs in LDS.  It takes all of them through column block 0, then all of
 // them through block 1, and so on ("phases"); after the last block it writes the rows out once
 // and takes its next rows ("generation").  Every workgroup owns the same number of rows per
-// generation, picked from the degree order with a stride of the number of groups on the chip,
-// so all workgroups carry nearly the same load in every phase; the workgroups of an XCD start
-// a phase together (phase_step_done), so an L2 serves gathers from one block at a time.  Inside a
-// workgroup the groups draw rows from an LDS counter, longest rows first, which levels the
-// segments' lengths.  A row's sums run in block order and its edges in list order, so the
-// result is bit-identical to the launch-per-block path whoever draws what.
+// generation, dealt from the degree order one position at a time in alternating direction, so
+// all workgroups carry nearly the same load in every phase and walk the blocks in step by
+// themselves; the workgroups of an XCD meet once per generation (phase_step_done, a bounded
+// wait), so an L2 serves gathers from one block at a time.  Inside a workgroup the groups draw
+// rows from an LDS counter, longest rows first, which levels the segments' lengths.  A row's
+// sums run in block order and its edges in list order, so the result is bit-identical to the
+// launch-per-block path whoever draws what.
 constexpr int kResThreads = 1024;
 constexpr int kResRows = 8;  // rows per group and generation (on average: the groups draw them)
 
