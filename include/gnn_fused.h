@@ -147,7 +147,8 @@ gnn_status_t gnn_release_cached_memory(void);
  *   "block_cols"            gathered vertices per column block (default 12288:
  *                           12288 rows x one 256-byte slice = 3 MB of an XCD's 4 MB L2);
  *                           0 disables blocking.  Read by gnn_graph_create.
- *   "resident_sums"         1 (default): where rows are cut into 256-byte slices the column-blocked
+ *   "resident_sums"         1 (default): where rows are cut into 256-byte slices (and for single-head
+ *                           or GCN rows of at most 64 floats, one slice) the column-blocked
  *                           GAT and GCN kernels run all blocks of a pass in ONE persistent launch
  *                           (one 1024-thread workgroup per CU) that keeps the rows' running sums
  *                           and softmax statistics in LDS, a few thousand rows per workgroup at a

@@ -1054,8 +1054,9 @@ extern "C" gnn_status_t gnn_gat_fwd(const gnn_graph_t* g, int fin, int heads, in
   // running softmax statistics, which borrow the dz area the backward call uses later: 128 of
   // its >= 512 bytes per vertex); without a workspace the single-launch kernels run.
   // Rows of 512 bytes and more take them (two 256-byte slices at 512 bytes; measured at Reddit
-  // scale, 1 x 128: 7.9 ms against 8.5 ms for the single-launch forward kernel).
-  if (gat_blocked_applies(g, heads, f) && have_ws && HF >= 128) {
+  // scale, 1 x 128: 7.9 ms against 8.5 ms for the single-launch forward kernel), and single-head
+  // rows of up to 256 bytes as one slice of the persistent kernels.
+  if (gat_blocked_applies(g, heads, f) && have_ws) {
     char* base = static_cast<char*>(ws);
     return gat_blocked_fwd(g, make_dims(heads, f, slope), z, el, er, m, d, out, t, sg,
                            reinterpret_cast<float*>(base + L.blk_elt),

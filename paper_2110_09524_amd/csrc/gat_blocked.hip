@@ -46,6 +46,15 @@ struct Slicing {
   int SL, ns;
 };
 static bool pick_slicing(int heads, int HF, Slicing& sl) {
+  // One head of at most 64 columns: the row is a single slice of up to 256 bytes, every XCD holds the
+  // whole column block (12288 x 256 bytes = 3 MB).  Only the persistent kernels take it: a launch per
+  // block measured slower than the single-launch kernels here (4.04 against 3.69 ms for the source
+  // side of a 1 x 64 layer at Reddit scale), its read-add-write of the sums being as large as the
+  // gathered block.
+  if (heads == 1 && HF <= 64 && HF % 4 == 0 && config_get(kCfgResidentSums)) {
+    sl = Slicing{16, 1};
+    return true;
+  }
   if (HF % 32 != 0) return false;
   const int q = HF / 32;  // 128-byte lines per row
   // Slices of 256 bytes (two lines, 16 lanes) where the row has 2, 4 or 8 of them and a slice
@@ -548,7 +557,10 @@ __global__ __launch_bounds__(kGatResThreads) void k_gat_res(
   const int H = dm.H, HF = dm.HF;
   const int h = slice / sph;
   const bool leader = (slice % sph) == 0;  // one slice per head keeps the per-head scalars
-  const int col = slice * 4 * SL + 4 * li;
+  // a row narrower than its slice (a single slice of fewer than 64 columns): the lanes past its end
+  // gather the row's first columns again (same cache line) and keep zeros where it matters
+  const bool col_ok = slice * 4 * SL + 4 * li < HF;
+  const int col = col_ok ? slice * 4 * SL + 4 * li : 0;
 
   float4* l_acc = reinterpret_cast<float4*>(lds_gr);                                   // [NSLOT][SL]
   float4* l_acc2 = l_acc + (DUAL ? SL * NSLOT : 0);                                    // [NSLOT][SL] (MODE 3)
@@ -620,7 +632,7 @@ __global__ __launch_bounds__(kGatResThreads) void k_gat_res(
       if (it.beg + li < it.end) it.c_first = bcol[it.beg + li];
       if (SRC) {
         const int32_t row = l_row[q];
-        if (row >= 0 && it.beg < it.end) it.zr = ld4_stream(rowfeat + (int64_t)row * HF + col);
+        if (row >= 0 && it.beg < it.end && col_ok) it.zr = ld4_stream(rowfeat + (int64_t)row * HF + col);
       }
       return it;
     };
@@ -786,8 +798,10 @@ __global__ __launch_bounds__(kGatResThreads) void k_gat_res(
             if (last && li == 0) scal_buf[(int64_t)row * kSlices + slice] = st_new.x;
           }
           if (last) {
-            st4_stream(acc_buf + (int64_t)row * HF + col, acc);
-            if (DUAL) st4_stream(acc2_buf + (int64_t)row * HF + col, acc2);
+            if (col_ok) {
+              st4_stream(acc_buf + (int64_t)row * HF + col, acc);
+              if (DUAL) st4_stream(acc2_buf + (int64_t)row * HF + col, acc2);
+            }
           } else {
             l_acc[q * SL + li] = acc;
             if (DUAL) l_acc2[q * SL + li] = acc2;
@@ -835,7 +849,7 @@ static gnn_status_t head_major(const gnn_graph_t* g, int H, const float* a, floa
 bool gat_blocked_half(const gnn_graph_t* g, int heads, int f) {
   if (config_get(kCfgGatherPrecision) != 1 || !gat_blocked_applies(g, heads, f)) return false;
   const int HF = heads * f;
-  if (HF % 64 != 0) return false;
+  if (HF % 64 != 0 || HF < 128) return false;
   const int q = HF / 64;
   return (q == 1 || q == 2 || q == 4 || q == 8) && q % heads == 0;
 }
@@ -1001,7 +1015,7 @@ static gnn_status_t launch_resident_impl(const gnn_graph_t* g, int side, const c
                                          float* acc2, float* scal, float* m_out, float* d_out, hipStream_t st,
                                          const float* alpha_b) {
   constexpr int SL = 16;
-  const int ns = dm.HF / (4 * SL);
+  const int ns = dm.HF <= 4 * SL ? 1 : dm.HF / (4 * SL);
   const int sph = ns / dm.H;
   const int narrow = (int64_t)g->n * dm.HF * 4 < ((int64_t)1 << 32) && g->n < (1 << 24) &&
                      !config_get(kCfgWideOffsets);
@@ -1054,6 +1068,8 @@ static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name,
   }
   Slicing sl;
   if (!pick_slicing(dm.H, dm.HF, sl)) sl.SL = 0;
+  GNN_REQUIRE(sl.SL == 0 || dm.HF >= 128, GNN_ERR_UNSUPPORTED,
+              "gat blocked: rows of one slice are served by the persistent kernels only");
   switch (sl.SL) {
     case 4: return launch_blocks<4, MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st, alpha_b);
     case 8: return launch_blocks<8, MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal, queue, state, m_out, d_out, st, alpha_b);
@@ -1188,7 +1204,7 @@ extern "C" gnn_status_t gnn_gat_blocked_kernel_name(const gnn_graph_t* g, int he
               "gnn_gat_blocked_kernel_name: null argument");
   GNN_REQUIRE(mode >= 0 && mode <= 3, GNN_ERR_INVALID_ARG, "gnn_gat_blocked_kernel_name: mode must be 0..3");
   buf[0] = 0;
-  if (heads <= 0 || f <= 0 || !gat_blocked_applies(g, heads, f) || heads * f < 128) return GNN_OK;
+  if (heads <= 0 || f <= 0 || !gat_blocked_applies(g, heads, f)) return GNN_OK;
   const bool half = mode != 1 && gat_blocked_half(g, heads, f);
   Slicing sl;
   if (!pick_slicing(heads, heads * f, sl)) return GNN_OK;

@@ -414,7 +414,10 @@ __global__ __launch_bounds__(kResThreads) void k_rowsum_res(
   int* l_idx = l_row + NSLOT + grp * (W ? 2 : 1) * SL;
   float* l_w = reinterpret_cast<float*>(l_idx + SL);
   int* l_cnt = l_row + NSLOT + GPB * (W ? 2 : 1) * SL;           // [2]
-  const int col = slice * 4 * SL + 4 * li;
+  // a row narrower than its slice: the lanes past its end gather its first columns again (same
+  // cache line) and store nothing
+  const bool col_ok = slice * 4 * SL + 4 * li < F;
+  const int col = col_ok ? slice * 4 * SL + 4 * li : 0;
 
   const int64_t rows_per_group = (n_rows + ngroups - 1) / ngroups;
   const int ngen = (int)((rows_per_group + R - 1) / R);
@@ -534,7 +537,7 @@ __global__ __launch_bounds__(kResThreads) void k_rowsum_res(
     }
     for (int q = grp; q < nslots; q += GPB) {
       const int32_t row = l_row[q];
-      if (row < 0) continue;
+      if (row < 0 || !col_ok) continue;
       float4 acc = l_acc[q * SL + li];
       if (scale != nullptr) scale4(acc, scale[row]);
       st4_stream(out + (int64_t)row * F + col, acc);
@@ -547,6 +550,13 @@ __global__ __launch_bounds__(kResThreads) void k_rowsum_res(
 // bytes, 22.9 ms with two of 512); wider rows have 8 slices, one per XCD.  With fewer than 8,
 // workgroup id mod `ns` picks the slice, so XCD k and XCD k + ns share columns and split the rows.
 static bool gcn_slicing(int F, int& SL, int& ns) {
+  // rows of at most 64 floats: one slice, persistent kernel only (a launch per block would move
+  // as many bytes of running sums as of gathered rows)
+  if (F <= 64 && F % 4 == 0 && config_get(kCfgResidentSums)) {
+    SL = 16;
+    ns = 1;
+    return true;
+  }
   if (F % 32 != 0) return false;
   const int q = F / 32;
   if (q == 4 || q == 8 || q == 16) {
@@ -607,7 +617,7 @@ template <int SL, bool W>
 static gnn_status_t launch_rowsum_resident(const gnn_graph_t* g, int side, const char* name, const float* feat,
                                            int F, const float* scale, float* out, hipStream_t st,
                                            const float* bw) {
-  const int ns = F / (4 * SL);
+  const int ns = F <= 4 * SL ? 1 : F / (4 * SL);
   const size_t lds = sizeof(int) * (size_t)kResLdsInts<SL, W>;
   GNN_REQUIRE(lds <= kResLdsLimit, GNN_ERR_UNSUPPORTED, "gcn resident: %zu bytes of LDS", lds);
   static std::atomic<bool> attr_set{false};

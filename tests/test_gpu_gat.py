@@ -176,7 +176,10 @@ def test_bad_arguments_raise():
                                             (200, 2, 256), (128, 8, 128),
                                             # 512-byte rows: four slices of 128 bytes; narrower rows
                                             # take the single-launch kernels on such graphs, too
-                                            (256, 1, 128), (300, 4, 32), (256, 2, 64), (500, 1, 64)])
+                                            (256, 1, 128), (300, 4, 32), (256, 2, 64), (500, 1, 64),
+                                            # one head of at most 64 columns: a single slice of the
+                                            # persistent kernels (merge = 2), rows shorter than the slice
+                                            (300, 1, 44), (256, 1, 4), (200, 1, 60)])
 @pytest.mark.parametrize("merge", [0, 1, 2])
 def test_column_blocked_path(block_cols, H, F, merge):
     """The multi-launch, column-blocked kernels (used when the gathered matrix exceeds

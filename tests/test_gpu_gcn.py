@@ -68,7 +68,7 @@ def test_graph_without_edges():
     assert (res["out"] == 0).all() and (res["gw"] == 0).all() and (res["gx"] == 0).all()
 
 
-@pytest.mark.parametrize("block_cols,fout", [(256, 256), (500, 128), (300, 512), (128, 1024), (256, 64)])
+@pytest.mark.parametrize("block_cols,fout", [(256, 256), (500, 128), (300, 512), (128, 1024), (256, 64), (300, 36), (200, 4)])
 @pytest.mark.parametrize("merge", [0, 1, 2, 3])
 def test_column_blocked_path(block_cols, fout, merge):
     """merge 0 / 1: one launch per block / merged launches; 2: all blocks in one persistent launch
@@ -262,7 +262,7 @@ def test_edge_weighted_shapes(fin, fout):
     check_edge(c, want_gx=False)
 
 
-@pytest.mark.parametrize("block_cols,fout", [(256, 256), (1000, 128), (300, 512), (128, 1024)])
+@pytest.mark.parametrize("block_cols,fout", [(256, 256), (1000, 128), (300, 512), (128, 1024), (256, 44)])
 @pytest.mark.parametrize("resident", [0, 1])
 def test_edge_weighted_column_blocked_path(block_cols, fout, resident):
     """The same on the column-blocked kernels: the weights travel in the order of the blocked edge
