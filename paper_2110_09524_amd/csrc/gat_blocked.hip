@@ -527,7 +527,7 @@ constexpr int kGatResLdsInts = (MODE == 3 ? 2 : 1) * 4 * SL * kGatResSlots<SL, M
                                4 * kGatResSlots<SL, MODE> + kGatResSlots<SL, MODE> +
                                (kGatResThreads / SL) * 3 * SL + 4;
 
-template <int SL, int MODE, bool SKIP>
+template <int SL, int MODE, bool SKIP, bool HALF>
 __global__ __launch_bounds__(kGatResThreads) void k_gat_res(
     int32_t n_rows, const int32_t* __restrict__ order, const int2* __restrict__ bseg /* [nblk][n_rows] */,
     const int32_t* __restrict__ bcol, const float* __restrict__ feat /* gathered rows: z or gout */,
@@ -579,7 +579,18 @@ __global__ __launch_bounds__(kGatResThreads) void k_gat_res(
                 false, sync_every > 0 ? sync_every : nblk};
 
   const char* feat_bytes = reinterpret_cast<const char*>(feat);
-  const uint32_t row_bytes = (uint32_t)HF * 4u, col_bytes = (uint32_t)col * 4u;
+  constexpr uint32_t kElem = HALF ? 2u : 4u;  // bytes per stored element of the gathered matrix
+  const uint32_t row_bytes = (uint32_t)HF * kElem, col_bytes = (uint32_t)col * kElem;
+  using RowRaw = std::conditional_t<HALF, uint2, float4>;  // a lane's four columns of a gathered row
+  auto widen = [](const RowRaw& r) {
+    if constexpr (HALF) {
+      const __half2* hh = reinterpret_cast<const __half2*>(&r);
+      const float2 lo = __half22float2(hh[0]), hi = __half22float2(hh[1]);
+      return make_float4(lo.x, lo.y, hi.x, hi.y);
+    } else {
+      return r;
+    }
+  };
 
   struct Item {
     int32_t beg, end, c_first;
@@ -689,19 +700,19 @@ __global__ __launch_bounds__(kGatResThreads) void k_gat_res(
                 const int4 i4 = *reinterpret_cast<const int4*>(l_idx + t0 + 4 * qq);
                 idv[4 * qq] = i4.x; idv[4 * qq + 1] = i4.y; idv[4 * qq + 2] = i4.z; idv[4 * qq + 3] = i4.w;
               }
-              float4 rowv[U];
+              RowRaw rowv[U];
 #pragma unroll
               for (int t4 = 0; t4 < U; t4 += 4) {
                 if (!SKIP || t0 + t4 < cnt) {
                   if (narrow) {
 #pragma unroll
                     for (int t = t4; t < t4 + 4; ++t)
-                      rowv[t] = *reinterpret_cast<const float4*>(
+                      rowv[t] = *reinterpret_cast<const RowRaw*>(
                           feat_bytes + (__umul24((uint32_t)idv[t], row_bytes) + col_bytes));
                   } else {
 #pragma unroll
                     for (int t = t4; t < t4 + 4; ++t)
-                      rowv[t] = *reinterpret_cast<const float4*>(feat_bytes + ((int64_t)idv[t] * row_bytes + col_bytes));
+                      rowv[t] = *reinterpret_cast<const RowRaw*>(feat_bytes + ((int64_t)idv[t] * row_bytes + col_bytes));
                   }
                 }
               }
@@ -755,9 +766,10 @@ __global__ __launch_bounds__(kGatResThreads) void k_gat_res(
                 if (!SKIP || t0 + t4 < cnt) {
 #pragma unroll
                   for (int t = t4; t < t4 + 4; ++t) {
-                    fma4(part, pv[t], rowv[t]);
-                    if (DUAL) fma4(part2, pv2[t], rowv[t]);
-                    if (SRC) dpart = fmaf(pv2[t], dot4(acc2, rowv[t]), dpart);
+                    const float4 rv = widen(rowv[t]);
+                    fma4(part, pv[t], rv);
+                    if (DUAL) fma4(part2, pv2[t], rv);
+                    if (SRC) dpart = fmaf(pv2[t], dot4(acc2, rv), dpart);
                   }
                 }
               }
@@ -1001,14 +1013,15 @@ static gnn_status_t launch_blocks(const gnn_graph_t* g, int side, const char* na
                                                    scal, queue, state, m_out, d_out, st, alpha_b);
 }
 
-// The persistent kernel applies to fp32 rows in 256-byte slices
-static bool gat_resident_applies(const gnn_graph_t* g, GatDims dm, bool half_feat) {
-  if (!config_get(kCfgResidentSums) || half_feat || g->phase_clock == nullptr) return false;
+// The persistent kernel applies to rows cut into slices of 64 columns (256 bytes of fp32, or one
+// 128-byte line of an fp16 copy)
+static bool gat_resident_applies(const gnn_graph_t* g, GatDims dm) {
+  if (!config_get(kCfgResidentSums) || g->phase_clock == nullptr) return false;
   Slicing sl;
   return pick_slicing(dm.H, dm.HF, sl) && sl.SL == 16;
 }
 
-template <int MODE, bool SKIP>
+template <int MODE, bool SKIP, bool HALF>
 static gnn_status_t launch_resident_impl(const gnn_graph_t* g, int side, const char* name, GatDims dm, int el_hm,
                                          const float* feat, const float* rowfeat, const float* el, const float* er,
                                          const float* m, const float* d, const float4* vstate, float* acc,
@@ -1023,7 +1036,7 @@ static gnn_status_t launch_resident_impl(const gnn_graph_t* g, int side, const c
   static_assert(sizeof(int) * (size_t)kGatResLdsInts<SL, MODE> <= 160 * 1024, "the slots must fit the LDS of a CU");
   static std::atomic<bool> attr_set{false};
   if (!attr_set.load(std::memory_order_acquire)) {
-    GNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gat_res<SL, MODE, SKIP>),
+    GNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gat_res<SL, MODE, SKIP, HALF>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set.store(true, std::memory_order_release);
   }
@@ -1032,7 +1045,7 @@ static gnn_status_t launch_resident_impl(const gnn_graph_t* g, int side, const c
   ProfScope p(name, st);
   k_gat_zero_clock<<<1, kXcds * kClockStride, 0, st>>>(g->phase_clock);
   GNN_LAUNCH_CHECK();
-  k_gat_res<SL, MODE, SKIP><<<grid, kGatResThreads, lds, st>>>(
+  k_gat_res<SL, MODE, SKIP, HALF><<<grid, kGatResThreads, lds, st>>>(
       g->n, g->order[side], reinterpret_cast<const int2*>(g->bseg[side]), g->bcol[side], feat, rowfeat, el, er, m, d,
       vstate, dm, sph, narrow, el_hm, g->block_cols, g->nblk, ns, acc, acc2, scal, m_out, d_out, g->phase_clock,
       (int)config_get(kCfgResidentSpin), (int)config_get(kCfgResidentSyncEvery), alpha_b, g->nnz);
@@ -1044,14 +1057,20 @@ template <int MODE>
 static gnn_status_t launch_resident(const gnn_graph_t* g, int side, const char* name, GatDims dm, int el_hm,
                                     const float* feat, const float* rowfeat, const float* el, const float* er,
                                     const float* m, const float* d, const float4* vstate, float* acc, float* acc2,
-                                    float* scal, float* m_out, float* d_out, hipStream_t st, const float* alpha_b) {
+                                    float* scal, float* m_out, float* d_out, hipStream_t st, const float* alpha_b,
+                                    bool half_feat) {
+  if (half_feat) {
+    if constexpr (MODE != 1)
+      return launch_resident_impl<MODE, true, true>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc,
+                                                    acc2, scal, m_out, d_out, st, alpha_b);
+  }
   // gathers past a segment's end are skipped on rows of four and more slices; on narrower rows the
   // source side gains from it as well (6.48 -> 6.14 ms for the two layers of a 128 / 44-wide model at
   // Reddit scale), the forward modes lose a little (5.87 -> 5.96 ms)
   if (dm.HF / 64 >= 4 || MODE == 2)
-    return launch_resident_impl<MODE, true>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2,
+    return launch_resident_impl<MODE, true, false>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2,
                                             scal, m_out, d_out, st, alpha_b);
-  return launch_resident_impl<MODE, false>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2,
+  return launch_resident_impl<MODE, false, false>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2,
                                            scal, m_out, d_out, st, alpha_b);
 }
 
@@ -1061,9 +1080,9 @@ static gnn_status_t run_blocks(const gnn_graph_t* g, int side, const char* name,
                                const float* d, const float4* vstate, float* acc, float* acc2,
                                float* scal, int32_t* queue, float4* state, float* m_out, float* d_out,
                                hipStream_t st, bool half_feat = false, const float* alpha_b = nullptr) {
-  if (gat_resident_applies(g, dm, half_feat))
+  if (gat_resident_applies(g, dm))
     return launch_resident<MODE>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal,
-                                 m_out, d_out, st, alpha_b);
+                                 m_out, d_out, st, alpha_b, half_feat);
   if (half_feat) {
     if constexpr (MODE != 1)
       return launch_blocks<8, MODE, true>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate, acc, acc2, scal,
@@ -1211,8 +1230,9 @@ extern "C" gnn_status_t gnn_gat_blocked_kernel_name(const gnn_graph_t* g, int he
   const bool half = mode != 1 && gat_blocked_half(g, heads, f);
   Slicing sl;
   if (!pick_slicing(heads, heads * f, sl)) return GNN_OK;
-  if (gat_resident_applies(g, make_dims(heads, f, 0.2f), half)) {
-    std::snprintf(buf, len, "k_gat_res<16, %d, %s>", mode, (heads * f / 64 >= 4 || mode == 2) ? "true" : "false");
+  if (gat_resident_applies(g, make_dims(heads, f, 0.2f))) {
+    std::snprintf(buf, len, "k_gat_res<16, %d, %s, %s>", mode,
+                  (half || heads * f / 64 >= 4 || mode == 2) ? "true" : "false", half ? "true" : "false");
     return GNN_OK;
   }
   const int SL = half ? 8 : sl.SL;

@@ -469,22 +469,24 @@ def test_sparse_graph_spanning_blocks_takes_the_single_launch_kernels():
     assert "gat_head_major" in kernels_used(8, 1024)          # the same graph with the bar at 8
 
 
+@pytest.mark.parametrize("resident", [1, 0])
 @pytest.mark.parametrize("H,F", [(4, 64), (2, 64), (2, 128), (1, 512), (8, 64), (1, 128)])
-def test_fp16_gather_storage(H, F):
-    """gather_precision = 1: the column-blocked kernels gather from an fp16 copy of z / gout and sum in
-    fp32.  Every gathered element carries a relative rounding error of up to 2^-11; in the backward
+def test_fp16_gather_storage(H, F, resident):
+    """gather_precision = 1: the column-blocked kernels (the persistent launch, or a launch per block with
+    resident = 0) gather from an fp16 copy of z / gout and sum in fp32.  Every gathered element carries a relative rounding error of up to 2^-11; in the backward
     pass these errors enter dot products over f columns, so the worst entry of a gradient may be off by
     several 1e-3 of the tensor's rms.  The results are compared with the oracle at 1.5e-2 of the rms
     (worst entry) and 2e-3 (rms of the error), not at the 1e-4 contract; the fp32 path on the same
     inputs must be at least as close."""
     import paper_2110_09524_amd as pk
     from gpu_harness import dev, run_gat
-    print(f"gat: fp16 gather storage H={H} F={F}", flush=True)
+    print(f"gat: fp16 gather storage H={H} F={F} resident={resident}", flush=True)
     rng = np.random.default_rng(4000 + H * F)
     indptr, indices = random_graph(rng, 1200, 30000, self_loops=True, duplicates=True)
     c = synth(rng, indptr, indices, 20, H, F)
     fwd, bwd = oracle_all(c)
     pk.gnn_config_set("block_cols", 256)
+    pk.gnn_config_set("resident_sums", resident)
     try:
         g = pk.Graph(dev(c["indptr"]), dev(c["indices"]))
         ref32 = run_gat(c, graph=g)
@@ -496,6 +498,7 @@ def test_fp16_gather_storage(H, F):
         g.close()
     finally:
         pk.gnn_config_set("block_cols", 12288)
+        pk.gnn_config_set("resident_sums", 1)
     compare(c, ref32, fwd, bwd)                       # the default path keeps the contract
 
     def rel(a, b):
