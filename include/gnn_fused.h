@@ -170,7 +170,10 @@ gnn_status_t gnn_release_cached_memory(void);
  *                           Read by gnn_graph_create.
  *   "blocked_min_edges"     mean number of edges per (row, column block) from which the
  *                           column-blocked kernels are used (default 16; sparser graphs take
- *                           the single-launch kernels even when they span several blocks)
+ *                           the single-launch kernels even when they span several blocks).
+ *                           Read by the layer calls and by gnn_graph_create, which builds no
+ *                           blocked lists for a graph below it (lowering the key afterwards
+ *                           does not bring them back for that graph).
  *   "gather_precision"      0 (default): fp32 throughout.  1: the column-blocked GAT kernels
  *                           gather the neighbour rows (z in forward, gout in the source-side
  *                           backward) from an fp16 copy, sums in fp32: about half the gather

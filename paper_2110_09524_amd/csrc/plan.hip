@@ -15,15 +15,35 @@
 
 namespace gnn {
 
+// largest value over the wavefront (all 64 lanes take part), then one atomic per wavefront
+__device__ __forceinline__ void wave_atomic_max(int* __restrict__ dst, int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, 64));
+  if ((threadIdx.x & 63) == 0 && v > 0) atomicMax(dst, v);
+}
+
+// bad[0]: error flags; bad[1]: the largest in-degree (it sets the width of the degree sort's keys)
 __global__ void k_validate_indptr(int32_t n, int64_t nnz, const int32_t* __restrict__ indptr,
                                   int* __restrict__ bad) {
   int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (i > n) return;
-  int32_t a = indptr[i];
-  if (i == 0 && a != 0) atomicOr(bad, 1);
-  if (i == n && (int64_t)a != nnz) atomicOr(bad, 2);
-  if (i < n && indptr[i + 1] < a) atomicOr(bad, 4);
-  if (a < 0 || (int64_t)a > nnz) atomicOr(bad, 4);
+  int deg = 0;
+  if (i <= n) {
+    int32_t a = indptr[i];
+    if (i == 0 && a != 0) atomicOr(bad, 1);
+    if (i == n && (int64_t)a != nnz) atomicOr(bad, 2);
+    if (i < n) {
+      deg = indptr[i + 1] - a;
+      if (deg < 0) atomicOr(bad, 4);
+    }
+    if (a < 0 || (int64_t)a > nnz) atomicOr(bad, 4);
+  }
+  wave_atomic_max(bad + 1, deg);
+}
+
+// *out = max(*out, largest of v[0..count))
+__global__ void k_max_i32(int64_t count, const int32_t* __restrict__ v, int* __restrict__ out) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  wave_atomic_max(out, i < count ? v[i] : 0);
 }
 
 __global__ void k_validate_indices_and_count(int32_t n, int64_t nnz,
@@ -273,8 +293,7 @@ static int bits_for(uint32_t max_value) {
 // serves all of them.  One staging block per host thread, allocated on first use and kept.
 struct PlanStage {
   int32_t hist[2][GNN_NUM_BUCKETS];
-  uint32_t max_degree[2];
-  int bad;
+  int head[3];  // error flags, largest in-degree, largest out-degree
 };
 static PlanStage* plan_stage() {
   static thread_local PlanStage* stage = nullptr;
@@ -300,6 +319,8 @@ __global__ void k_bucket_offsets(const int32_t* __restrict__ hist, int32_t* __re
 // enqueues the degree order and buckets of one side; finish_side completes it after the wait
 static gnn_status_t build_side(gnn_graph* g, int side, const int32_t* ptr, TempBuffers& tmp,
                                PlanStage* stage, hipStream_t st) {
+  // the sort's keys are as wide as the largest degree (one 8-bit pass for a kNN graph instead of four)
+  const int key_bits = bits_for((uint32_t)g->max_degree[side]);
   const int32_t n = g->n;
   const int thr = 256;
   uint32_t *deg = nullptr, *deg_sorted = nullptr;
@@ -324,20 +345,18 @@ static gnn_status_t build_side(gnn_graph* g, int side, const int32_t* ptr, TempB
     // stable descending sort by degree: ties keep ascending vertex id
     size_t bytes = 0;
     GNN_HIP(rocprim::radix_sort_pairs_desc(nullptr, bytes, deg, deg_sorted, ids, g->order[side],
-                                           (size_t)n, 0, 32, st));
+                                           (size_t)n, 0, key_bits, st));
     void* scratch = nullptr;
     GNN_HIP(tmp.alloc((char**)&scratch, bytes));
     GNN_HIP(rocprim::radix_sort_pairs_desc(scratch, bytes, deg, deg_sorted, ids, g->order[side],
-                                           (size_t)n, 0, 32, st));
+                                           (size_t)n, 0, key_bits, st));
     GNN_HIP(hipMemcpyAsync(stage->hist[side], hist, sizeof(stage->hist[side]), hipMemcpyDeviceToHost, st));
-    GNN_HIP(hipMemcpyAsync(&stage->max_degree[side], deg_sorted, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
   }
   return GNN_OK;
 }
 
 // after the stream has been waited for: the host copies of the bucket table
 static void finish_side(gnn_graph* g, int side, const PlanStage* stage) {
-  g->max_degree[side] = (int32_t)stage->max_degree[side];
   g->h_bucket_offsets[side][0] = 0;
   for (int b = 0; b < GNN_NUM_BUCKETS; ++b)
     g->h_bucket_offsets[side][b + 1] = g->h_bucket_offsets[side][b] + stage->hist[side][b];
@@ -452,8 +471,8 @@ static gnn_status_t build(gnn_graph* g, hipStream_t st) {
   GNN_REQUIRE(stage != nullptr, GNN_ERR_HIP, "gnn_graph_create: no pinned staging memory");
   std::memset(stage, 0, sizeof(PlanStage));
   int* bad = nullptr;
-  GNN_HIP(tmp.alloc(&bad, 1));
-  GNN_HIP(hipMemsetAsync(bad, 0, sizeof(int), st));
+  GNN_HIP(tmp.alloc(&bad, 3));  // error flags, largest in-degree, largest out-degree
+  GNN_HIP(hipMemsetAsync(bad, 0, 3 * sizeof(int), st));
 
   GNN_HIP(pool_alloc((void**)&g->indptr_t, sizeof(int32_t) * (size_t)(n + 1)));
   GNN_HIP(pool_alloc((void**)&g->indices_t, sizeof(int32_t) * (size_t)(nnz ? nnz : 1)));
@@ -468,11 +487,15 @@ static gnn_status_t build(gnn_graph* g, hipStream_t st) {
   if (nnz > 0) {
     k_validate_indices_and_count<<<cdiv(nnz, thr), thr, 0, st>>>(n, nnz, g->indices, outdeg, bad);
     GNN_LAUNCH_CHECK();
+    k_max_i32<<<cdiv((int64_t)n, thr), thr, 0, st>>>(n, outdeg, bad + 2);
+    GNN_LAUNCH_CHECK();
   }
   // the kernels below index with the source ids, so this one has to be waited for
-  GNN_HIP(hipMemcpyAsync(&stage->bad, bad, sizeof(int), hipMemcpyDeviceToHost, st));
+  GNN_HIP(hipMemcpyAsync(stage->head, bad, sizeof(stage->head), hipMemcpyDeviceToHost, st));
   GNN_HIP(hipStreamSynchronize(st));
-  const int h_bad = stage->bad;
+  const int h_bad = stage->head[0];
+  g->max_degree[0] = stage->head[1];
+  g->max_degree[1] = stage->head[2];
   GNN_REQUIRE(h_bad == 0, GNN_ERR_BAD_GRAPH,
               "gnn_graph_create: malformed CSR (%s%s%s%s)", (h_bad & 1) ? "indptr[0] != 0; " : "",
               (h_bad & 2) ? "indptr[n] != nnz; " : "", (h_bad & 4) ? "indptr not monotone; " : "",
@@ -512,9 +535,12 @@ static gnn_status_t build(gnn_graph* g, hipStream_t st) {
   GNN_TRY(build_side(g, 1, g->indptr_t, tmp, stage, st));
   g->block_cols = (int32_t)config_get(kCfgBlockCols);
   g->nblk = 1;
-  // the (block, row) pointer table has nblk * n entries: keep it below 2^28
+  // the (block, row) pointer table has nblk * n entries: keep it below 2^28.  A graph too sparse
+  // for the column-blocked kernels to pay (fewer than "blocked_min_edges" edges per row and block:
+  // a kNN graph rebuilt every step, say) gets no lists, which are most of a small plan's launches.
   if (g->block_cols > 0 && n > g->block_cols && nnz > 0 &&
-      cdiv(n, g->block_cols) * (int64_t)n < ((int64_t)1 << 28)) {
+      cdiv(n, g->block_cols) * (int64_t)n < ((int64_t)1 << 28) &&
+      nnz >= config_get(kCfgBlockedMinEdges) * (int64_t)n * cdiv(n, g->block_cols)) {
     g->nblk = (int32_t)cdiv(n, g->block_cols);
     GNN_TRY(build_blocked(g, 0, g->indptr, g->indices, st));
     GNN_TRY(build_blocked(g, 1, g->indptr_t, g->indices_t, st));

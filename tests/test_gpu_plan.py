@@ -96,6 +96,39 @@ def test_blocked_edge_lists(block_cols):
     g.close()
 
 
+def test_no_blocked_lists_for_graphs_too_sparse_to_use_them():
+    """With fewer than "blocked_min_edges" edges per (row, block) the column-blocked kernels are never
+    chosen, so gnn_graph_create does not build their lists (most of the launches of a small plan);
+    the rest of the plan is the same and the layers run on the single-launch kernels."""
+    import paper_2110_09524_amd as pk
+    import test_gpu_gat as TG
+    from gpu_harness import dev, run_gat
+    rng = np.random.default_rng(41)
+    indptr, indices = random_graph(rng, 400, 4000, self_loops=True, duplicates=False)   # 11 edges per row
+    pk.gnn_config_set("block_cols", 100)                                                # 4 blocks: 2.7 per (row, block)
+    try:
+        dense_enough = pk.Graph(dev(indptr), dev(indices))      # the suite runs with blocked_min_edges = 0
+        pk.gnn_config_set("blocked_min_edges", 16)
+        try:
+            sparse = pk.Graph(dev(indptr), dev(indices))
+        finally:
+            pk.gnn_config_set("blocked_min_edges", 0)
+    finally:
+        pk.gnn_config_set("block_cols", 12288)
+    assert dense_enough.blocked(0)[0] == 4 and dense_enough.blocked(1)[0] == 4
+    assert sparse.blocked(0)[0] == 1 and sparse.blocked(1)[0] == 1
+    for a, b in zip(dense_enough.csc(), sparse.csc()):
+        assert bool((a == b).all())
+    for side in (0, 1):
+        for a, b in zip(dense_enough.buckets(side), sparse.buckets(side)):
+            assert bool((a == b).all())
+    c = TG.synth(rng, indptr, indices, 12, 2, 16)
+    fwd, bwd = TG.oracle_all(c)
+    TG.compare(c, run_gat(c, graph=sparse), fwd, bwd)
+    dense_enough.close()
+    sparse.close()
+
+
 def _group_cost(begin, n, block_cols, groups, fixed):
     """Modelled cost of a partition of the block sequence into launches (units: one gathered edge per
     row): per launch a fixed part plus its edges per row, dearer by 32 % per doubling of the gathered
