@@ -83,36 +83,46 @@ __global__ __launch_bounds__(kApplyThreads) void k_bias_act_bwd(
 }
 
 // ---- softmax cross-entropy ---------------------------------------------------------------
-// one thread per vertex (the class count is small); per-workgroup loss sums to partial[]
+// A workgroup takes kXentVerts consecutive vertices, 16 lanes per vertex (lane j owns classes
+// j, j + 16, ...: the 16 groups of a pass read 16 consecutive rows, one contiguous run), 4 passes;
+// per-workgroup loss sums to partial[], in a fixed order.
+constexpr int kXentVerts = 64;
 __global__ __launch_bounds__(kApplyThreads) void k_softmax_xent(
     int64_t n, int c, float inv_count, const float* __restrict__ logits, const int32_t* __restrict__ labels,
     float* __restrict__ glogits, float* __restrict__ partial) {
-  __shared__ float red[kApplyThreads];
-  const int64_t v = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  float loss = 0.f;
-  if (v < n) {
+  constexpr int L = 16, G = kApplyThreads / L;
+  __shared__ float red[G];
+  const int li = threadIdx.x & (L - 1), grp = threadIdx.x / L;
+  float loss = 0.f;  // lane 0 of a group: the sum over the group's vertices, in pass order
+  for (int pass = 0; pass < kXentVerts / G; ++pass) {
+    const int64_t v = blockIdx.x * (int64_t)kXentVerts + pass * G + grp;
+    if (v >= n) break;  // uniform over the group
     const float* z = logits + v * c;
     float* g = glogits + v * c;
     const int32_t lab = labels[v];
     if (lab < 0 || lab >= c) {  // unlabelled
-      for (int j = 0; j < c; ++j) g[j] = 0.f;
-    } else {
-      float mx = z[0];
-      for (int j = 1; j < c; ++j) mx = fmaxf(mx, z[j]);
-      float se = 0.f;
-      for (int j = 0; j < c; ++j) se += expf(z[j] - mx);
-      const float inv = 1.f / se;
-      for (int j = 0; j < c; ++j) g[j] = (expf(z[j] - mx) * inv - (j == lab ? 1.f : 0.f)) * inv_count;
-      loss = (mx + logf(se)) - z[lab];
+      for (int j = li; j < c; j += L) g[j] = 0.f;
+      continue;
     }
+    float mx = -INFINITY;
+    for (int j = li; j < c; j += L) mx = fmaxf(mx, z[j]);
+#pragma unroll
+    for (int o = L / 2; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, L));
+    float se = 0.f;
+    for (int j = li; j < c; j += L) se += expf(z[j] - mx);
+#pragma unroll
+    for (int o = L / 2; o > 0; o >>= 1) se += __shfl_xor(se, o, L);
+    const float inv = 1.f / se;
+    for (int j = li; j < c; j += L) g[j] = (expf(z[j] - mx) * inv - (j == lab ? 1.f : 0.f)) * inv_count;
+    loss += (mx + logf(se)) - z[lab];
   }
-  red[threadIdx.x] = loss;
+  if (li == 0) red[grp] = loss;
   __syncthreads();
-  for (int off = kApplyThreads / 2; off > 0; off >>= 1) {
-    if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
-    __syncthreads();
+  if (threadIdx.x == 0) {
+    float s = 0.f;
+    for (int i = 0; i < G; ++i) s += red[i];  // fixed order
+    partial[blockIdx.x] = s;
   }
-  if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
 }
 
 // loss = inv_count * sum of the partials, in a fixed tree order (one workgroup)
@@ -214,7 +224,7 @@ extern "C" gnn_status_t gnn_bias_act_bwd(int64_t n, int f, int act, float slope,
 
 extern "C" size_t gnn_softmax_xent_workspace_bytes(int64_t n) {
   if (n <= 0) return 0;
-  return ws_granule(sizeof(float) * (size_t)cdiv(n, kApplyThreads));
+  return ws_granule(sizeof(float) * (size_t)cdiv(n, kXentVerts));
 }
 
 extern "C" gnn_status_t gnn_softmax_xent(int64_t n, int c, int64_t n_labelled, const float* logits,
@@ -225,7 +235,7 @@ extern "C" gnn_status_t gnn_softmax_xent(int64_t n, int c, int64_t n_labelled, c
   GNN_REQUIRE(c <= 4096, GNN_ERR_UNSUPPORTED, "gnn_softmax_xent: %d classes exceed 4096", c);
   GNN_REQUIRE(loss != nullptr, GNN_ERR_INVALID_ARG, "gnn_softmax_xent: loss is null");
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int64_t parts = cdiv(n, kApplyThreads);
+  const int64_t parts = cdiv(n, kXentVerts);
   GNN_REQUIRE(parts < (int64_t)INT32_MAX, GNN_ERR_UNSUPPORTED, "gnn_softmax_xent: too many vertices");
   if (n != 0) {
     GNN_REQUIRE(logits && labels && glogits, GNN_ERR_INVALID_ARG, "gnn_softmax_xent: null pointer");

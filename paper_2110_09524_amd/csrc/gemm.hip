@@ -314,8 +314,8 @@ __global__ void k_sum_partials(int64_t count, int splits, int64_t stride,
 }
 
 // Same sum for short outputs and many parts: 8 threads share one output element, each
-// adds every 8th part of its range in ascending order, then the 8 subtotals are added in
-// order through LDS.  blockIdx.y selects a range of `chunk` consecutive parts and writes
+// adds every 8th part of its range (in four interleaved running sums), then the 8 subtotals are
+// added in order through LDS.  blockIdx.y selects a range of `chunk` consecutive parts and writes
 // its subtotal to row blockIdx.y of the output (a second call then adds the rows).
 // The grouping is fixed, so the result is reproducible.
 __global__ __launch_bounds__(256) void k_sum_partials_wide(int64_t count, int parts, int64_t stride,
@@ -328,8 +328,18 @@ __global__ __launch_bounds__(256) void k_sum_partials_wide(int64_t count, int pa
   const int z0 = blockIdx.y * chunk;
   const int z1 = z0 + chunk < parts ? z0 + chunk : parts;
   float s = 0.f;
-  if (i < count)
-    for (int z = z0 + lane8; z < z1; z += 8) s += partials[(int64_t)z * stride + i];
+  if (i < count) {
+    // four interleaved running sums keep four loads in flight; their order is fixed
+    float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int z = z0 + lane8;
+    for (; z + 24 < z1; z += 32) {
+      const float* p = partials + (int64_t)z * stride + i;
+      const float v0 = p[0], v1 = p[8 * stride], v2 = p[16 * stride], v3 = p[24 * stride];
+      s += v0; s1 += v1; s2 += v2; s3 += v3;
+    }
+    for (; z < z1; z += 8) s += partials[(int64_t)z * stride + i];
+    s = (s + s1) + (s2 + s3);
+  }
   sub[lane8][col] = s;
   __syncthreads();
   if (lane8 == 0 && i < count) {
