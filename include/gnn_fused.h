@@ -276,7 +276,7 @@ gnn_status_t gnn_gat_bwd_noalloc(const gnn_graph_t* graph, int fin, int heads, i
 /* Introspection for measurement scripts: the instantiation of the column-blocked edge kernel that
  * a pass over this graph launches for `heads` x `f` (mode 0 forward, 1 destination side recomputing,
  * 2 source side, 3 forward with stash) under the current configuration, spelled as a profiler
- * prints it, e.g. "k_gat_res<16, 2, true, false>" (the persistent launch) or
+ * prints it, e.g. "k_gat_res<16, 2, true, false, true>" (the persistent launch) or
  * "k_gat_blk<16, 2, false, false, true>" (one launch per block); the empty string when the
  * single-launch kernels run.  buf is a HOST buffer of len bytes. */
 gnn_status_t gnn_gat_blocked_kernel_name(const gnn_graph_t* graph, int heads, int f, int mode,

@@ -527,13 +527,13 @@ constexpr int kGatResLdsInts = (MODE == 3 ? 2 : 1) * 4 * SL * kGatResSlots<SL, M
                                4 * kGatResSlots<SL, MODE> + kGatResSlots<SL, MODE> +
                                (kGatResThreads / SL) * 3 * SL + 4;
 
-template <int SL, int MODE, bool SKIP, bool HALF>
+template <int SL, int MODE, bool SKIP, bool HALF, bool NARROW>
 __global__ __launch_bounds__(kGatResThreads) void k_gat_res(
     int32_t n_rows, const int32_t* __restrict__ order, const int2* __restrict__ bseg /* [nblk][n_rows] */,
     const int32_t* __restrict__ bcol, const float* __restrict__ feat /* gathered rows: z or gout */,
     const float* __restrict__ rowfeat /* MODE 2: z */, const float* __restrict__ el,
     const float* __restrict__ er, const float* __restrict__ m_in, const float* __restrict__ d_in,
-    const float4* __restrict__ vstate, GatDims dm, int sph, int narrow, int el_hm, int32_t block_cols,
+    const float4* __restrict__ vstate, GatDims dm, int sph, int el_hm, int32_t block_cols,
     int nblk, int ns, float* __restrict__ acc_buf, float* __restrict__ acc2_buf, float* __restrict__ scal_buf,
     float* __restrict__ m_out, float* __restrict__ d_out, int32_t* __restrict__ clock, int spin_limit, int sync_every,
     const float* __restrict__ alpha_b /* MODE 2, nullable: stashed signed softmax values, [H][nnz] in the order of
@@ -704,7 +704,7 @@ __global__ __launch_bounds__(kGatResThreads) void k_gat_res(
 #pragma unroll
               for (int t4 = 0; t4 < U; t4 += 4) {
                 if (!SKIP || t0 + t4 < cnt) {
-                  if (narrow) {
+                  if constexpr (NARROW) {  // 32-bit byte offsets from a scalar base reach every row
 #pragma unroll
                     for (int t = t4; t < t4 + 4; ++t)
                       rowv[t] = *reinterpret_cast<const RowRaw*>(
@@ -1021,8 +1021,8 @@ static bool gat_resident_applies(const gnn_graph_t* g, GatDims dm) {
   return pick_slicing(dm.H, dm.HF, sl) && sl.SL == 16;
 }
 
-template <int MODE, bool SKIP, bool HALF>
-static gnn_status_t launch_resident_impl(const gnn_graph_t* g, int side, const char* name, GatDims dm, int el_hm,
+template <int MODE, bool SKIP, bool HALF, bool NARROW>
+static gnn_status_t launch_resident_addr(const gnn_graph_t* g, int side, const char* name, GatDims dm, int el_hm,
                                          const float* feat, const float* rowfeat, const float* el, const float* er,
                                          const float* m, const float* d, const float4* vstate, float* acc,
                                          float* acc2, float* scal, float* m_out, float* d_out, hipStream_t st,
@@ -1030,13 +1030,11 @@ static gnn_status_t launch_resident_impl(const gnn_graph_t* g, int side, const c
   constexpr int SL = 16;
   const int ns = dm.HF <= 4 * SL ? 1 : dm.HF / (4 * SL);
   const int sph = ns / dm.H;
-  const int narrow = (int64_t)g->n * dm.HF * 4 < ((int64_t)1 << 32) && g->n < (1 << 24) &&
-                     !config_get(kCfgWideOffsets);
   const size_t lds = sizeof(int) * (size_t)kGatResLdsInts<SL, MODE>;
   static_assert(sizeof(int) * (size_t)kGatResLdsInts<SL, MODE> <= 160 * 1024, "the slots must fit the LDS of a CU");
   static std::atomic<bool> attr_set{false};
   if (!attr_set.load(std::memory_order_acquire)) {
-    GNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gat_res<SL, MODE, SKIP, HALF>),
+    GNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gat_res<SL, MODE, SKIP, HALF, NARROW>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set.store(true, std::memory_order_release);
   }
@@ -1045,12 +1043,30 @@ static gnn_status_t launch_resident_impl(const gnn_graph_t* g, int side, const c
   ProfScope p(name, st);
   k_gat_zero_clock<<<1, kXcds * kClockStride, 0, st>>>(g->phase_clock);
   GNN_LAUNCH_CHECK();
-  k_gat_res<SL, MODE, SKIP, HALF><<<grid, kGatResThreads, lds, st>>>(
+  k_gat_res<SL, MODE, SKIP, HALF, NARROW><<<grid, kGatResThreads, lds, st>>>(
       g->n, g->order[side], reinterpret_cast<const int2*>(g->bseg[side]), g->bcol[side], feat, rowfeat, el, er, m, d,
-      vstate, dm, sph, narrow, el_hm, g->block_cols, g->nblk, ns, acc, acc2, scal, m_out, d_out, g->phase_clock,
+      vstate, dm, sph, el_hm, g->block_cols, g->nblk, ns, acc, acc2, scal, m_out, d_out, g->phase_clock,
       (int)config_get(kCfgResidentSpin), (int)config_get(kCfgResidentSyncEvery), alpha_b, g->nnz);
   GNN_LAUNCH_CHECK();
   return GNN_OK;
+}
+
+// 32-bit byte offsets (and 24-bit multiplies) reach every gathered row
+static bool gat_resident_narrow(const gnn_graph_t* g, GatDims dm) {
+  return (int64_t)g->n * dm.HF * 4 < ((int64_t)1 << 32) && g->n < (1 << 24) && !config_get(kCfgWideOffsets);
+}
+
+template <int MODE, bool SKIP, bool HALF>
+static gnn_status_t launch_resident_impl(const gnn_graph_t* g, int side, const char* name, GatDims dm, int el_hm,
+                                         const float* feat, const float* rowfeat, const float* el, const float* er,
+                                         const float* m, const float* d, const float4* vstate, float* acc,
+                                         float* acc2, float* scal, float* m_out, float* d_out, hipStream_t st,
+                                         const float* alpha_b) {
+  if (gat_resident_narrow(g, dm))
+    return launch_resident_addr<MODE, SKIP, HALF, true>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate,
+                                                        acc, acc2, scal, m_out, d_out, st, alpha_b);
+  return launch_resident_addr<MODE, SKIP, HALF, false>(g, side, name, dm, el_hm, feat, rowfeat, el, er, m, d, vstate,
+                                                       acc, acc2, scal, m_out, d_out, st, alpha_b);
 }
 
 template <int MODE>
@@ -1231,8 +1247,9 @@ extern "C" gnn_status_t gnn_gat_blocked_kernel_name(const gnn_graph_t* g, int he
   Slicing sl;
   if (!pick_slicing(heads, heads * f, sl)) return GNN_OK;
   if (gat_resident_applies(g, make_dims(heads, f, 0.2f))) {
-    std::snprintf(buf, len, "k_gat_res<16, %d, %s, %s>", mode,
-                  (half || heads * f / 64 >= 4 || mode == 2) ? "true" : "false", half ? "true" : "false");
+    std::snprintf(buf, len, "k_gat_res<16, %d, %s, %s, %s>", mode,
+                  (half || heads * f / 64 >= 4 || mode == 2) ? "true" : "false", half ? "true" : "false",
+                  gat_resident_narrow(g, make_dims(heads, f, 0.2f)) ? "true" : "false");
     return GNN_OK;
   }
   const int SL = half ? 8 : sl.SL;
