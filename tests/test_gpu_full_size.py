@@ -157,6 +157,24 @@ def test_gat_c4_sampled_rows_and_consistency(c4, sample, capsys):
         pk.gnn_config_set("merge_blocks", 1)
     for k in ("out", "t", "sg", "m", "d", "gx", "gw", "ga_l", "ga_r"):
         assert np.array_equal(res[k], res3[k]), f"{k}: persistent and launch-per-block kernels differ at full size"
+    # the optional fp16 copy of the gathered rows (outside the 1e-4 contract) on the persistent kernels,
+    # all batches of rows: within the rounding of an fp16 operand of the fp32 results above
+    say("fp16 gather storage on the persistent launch")
+    pk.gnn_config_set("gather_precision", 1)
+    try:
+        res16 = run_gat(c, graph=g)
+    finally:
+        pk.gnn_config_set("gather_precision", 0)
+    for k in ("out", "gx", "gw", "ga_l", "ga_r"):
+        a, b = res16[k].astype(np.float64), res[k].astype(np.float64)
+        scale = max(float(np.sqrt(np.mean(b * b))), 1e-30)
+        # an entry is held to the larger of the tensor's rms and its own row's largest entry (hub rows of gx
+        # are sums over ~10^4 edges, far above the rms)
+        row = np.maximum(np.abs(b).max(axis=1, keepdims=True), scale)
+        worst, rms = float((np.abs(a - b) / row).max()), float(np.sqrt(np.mean((a - b) ** 2)) / scale)
+        say(f"  {k}: fp16 gather against fp32, worst {worst:.1e} of its row's scale, rms {rms:.1e} of the tensor's rms")
+        assert worst < 1.5e-2 and rms < 2e-3, f"{k}: fp16 gather error worst {worst:.2e} rms {rms:.2e}"
+    assert np.array_equal(res16["m"], res["m"]) and not np.array_equal(res16["out"], res["out"])
     g.close()
 
 
