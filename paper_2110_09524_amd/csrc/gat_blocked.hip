@@ -694,6 +694,7 @@ __global__ __launch_bounds__(kGatResThreads) void k_gat_res(
             float sc = 1.f;  // ONLINE: factor that brings the running sums to this chunk's maximum
 #pragma unroll
             for (int t0 = 0; t0 < SL; t0 += U) {
+              if (SKIP && t0 >= cnt) break;  // nothing of this chunk is left: no index or weight reads either
               int idv[U];
 #pragma unroll
               for (int qq = 0; qq < U / 4; ++qq) {
